@@ -1,0 +1,155 @@
+"""Loader for the CPU oracle (csd_oracle.cpp) — TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg import this.
+The GPU package never does.  This module compiles the C++ file with g++ and
+wraps its `extern "C"` functions with numpy array marshalling; it contains no
+arithmetic of its own.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "csd_oracle.cpp")
+_LIB = os.path.join(_HERE, "libcsd_oracle.so")
+_lib = None
+
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_u64p = ctypes.POINTER(ctypes.c_uint64)
+_f32p = ctypes.POINTER(ctypes.c_float)
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with g++ (plain -O2, no GPU toolchain)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["g++", "-O2", "-std=c++14", "-shared", "-fPIC", "-o", _LIB, _SRC])
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        lib.oracle_quantize_prob.restype = ctypes.c_uint32
+        lib.oracle_quantize_prob.argtypes = [ctypes.c_float]
+        lib.oracle_alpha_q.restype = ctypes.c_uint32
+        lib.oracle_alpha_q.argtypes = [ctypes.c_double]
+        lib.oracle_matches.restype = ctypes.c_int64
+        lib.oracle_matches.argtypes = [_i32p, _i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                       ctypes.c_int32, _i32p, ctypes.c_int64]
+        lib.oracle_edges.restype = ctypes.c_int64
+        lib.oracle_edges.argtypes = [_i32p, _f32p, _i32p, ctypes.c_int32, ctypes.c_int32,
+                                     ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _i32p, _u64p,
+                                     ctypes.c_int64]
+        lib.oracle_draft.restype = ctypes.c_int32
+        lib.oracle_draft.argtypes = [_i32p, _f32p, _i32p, ctypes.c_int32, ctypes.c_int32,
+                                     ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_uint32,
+                                     ctypes.c_int32, _i32p, _f32p, _f32p]
+        lib.oracle_accept.restype = ctypes.c_int32
+        lib.oracle_accept.argtypes = [_i32p, ctypes.c_int32, _i32p]
+        lib.oracle_draft_all.restype = None
+        lib.oracle_draft_all.argtypes = [_i32p, _f32p, _i32p, ctypes.c_int32, ctypes.c_int32,
+                                         ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                         ctypes.c_uint32, ctypes.c_int32, _i32p, _i32p, _f32p, _f32p,
+                                         _i32p, _i32p]
+        _lib = lib
+    return _lib
+
+
+def _i32(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.ctypes.data_as(_i32p)
+
+
+def _f32(a):
+    if a is None:
+        return None, None
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a, a.ctypes.data_as(_f32p)
+
+
+def quantize_prob(p: float) -> int:
+    return int(_load().oracle_quantize_prob(ctypes.c_float(p)))
+
+
+def alpha_q(alpha: float) -> int:
+    return int(_load().oracle_alpha_q(float(alpha)))
+
+
+def matches(tok, length, i, k):
+    """(j, e) rows of path i's match set for one problem: tok [N][max_len], length [N]."""
+    tok, tp = _i32(tok)
+    length, lp = _i32(length)
+    N, max_len = tok.shape
+    lib = _load()
+    cap = max(1, N * max_len)
+    out = np.empty((cap, 2), dtype=np.int32)
+    n = lib.oracle_matches(tp, lp, N, max_len, i, k, out.ctypes.data_as(_i32p), cap)
+    return out[:n].copy()
+
+
+def edges(tok, prob, length, i, k, L):
+    """Edge rows of path i's DAG: (duv int32 [n][3], cs uint64 [n][2]) sorted by (d, u, v)."""
+    tok, tp = _i32(tok)
+    prob, pp = _f32(prob)
+    length, lp = _i32(length)
+    N, max_len = tok.shape
+    lib = _load()
+    n = lib.oracle_edges(tp, pp, lp, N, max_len, i, k, L, None, None, 0)
+    duv = np.empty((max(n, 1), 3), dtype=np.int32)
+    cs = np.empty((max(n, 1), 2), dtype=np.uint64)
+    lib.oracle_edges(tp, pp, lp, N, max_len, i, k, L, duv.ctypes.data_as(_i32p),
+                     cs.ctypes.data_as(_u64p), n)
+    return duv[:n].copy(), cs[:n].copy()
+
+
+def draft(tok, prob, length, i, k, L, alpha=1.0, score_mode=0):
+    """Draft of path i for one problem -> (tokens [L], draft_len, token_scores [L], path_score)."""
+    tok, tp = _i32(tok)
+    prob, pp = _f32(prob)
+    length, lp = _i32(length)
+    N, max_len = tok.shape
+    d = np.empty(L, dtype=np.int32)
+    ts = np.empty(L, dtype=np.float32)
+    ps = ctypes.c_float(0.0)
+    lib = _load()
+    n = lib.oracle_draft(tp, pp, lp, N, max_len, i, k, L, lib.oracle_alpha_q(float(alpha)),
+                         score_mode, d.ctypes.data_as(_i32p), ts.ctypes.data_as(_f32p),
+                         ctypes.byref(ps))
+    return d, int(n), ts, np.float32(ps.value)
+
+
+def accept(draft_tokens, draft_len, target) -> int:
+    d, dp = _i32(draft_tokens)
+    t, tp = _i32(target)
+    return int(_load().oracle_accept(dp, int(draft_len), tp))
+
+
+def draft_all(tok, prob, length, k, L, alpha=1.0, score_mode=0, target=None):
+    """All paths of all problems: tok [P][N][max_len], prob same or None, length [P][N].
+
+    Returns dict(draft [P][N][L], draft_len [P][N], token_scores [P][N][L],
+    path_scores [P][N], accept_len [P][N] or None)."""
+    tok, tp = _i32(tok)
+    prob, pp = _f32(prob)
+    length, lp = _i32(length)
+    P, N, max_len = tok.shape
+    d = np.empty((P, N, L), dtype=np.int32)
+    dl = np.empty((P, N), dtype=np.int32)
+    ts = np.empty((P, N, L), dtype=np.float32)
+    ps = np.empty((P, N), dtype=np.float32)
+    lib = _load()
+    if target is not None:
+        target, tgp = _i32(target)
+        al = np.empty((P, N), dtype=np.int32)
+        alp = al.ctypes.data_as(_i32p)
+    else:
+        tgp, al, alp = None, None, None
+    lib.oracle_draft_all(tp, pp, lp, P, N, max_len, k, L, lib.oracle_alpha_q(float(alpha)),
+                         score_mode, d.ctypes.data_as(_i32p), dl.ctypes.data_as(_i32p),
+                         ts.ctypes.data_as(_f32p), ps.ctypes.data_as(_f32p), tgp, alp)
+    return dict(draft=d, draft_len=dl, token_scores=ts, path_scores=ps, accept_len=al)

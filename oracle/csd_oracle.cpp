@@ -1,0 +1,273 @@
+/*
+ * CPU oracle for consensus draft construction across N parallel sampling
+ * paths ("Speculative Decoding for Multi-Sample Inference", Method section,
+ * Eq. 3, Eq. 5, the greedy extraction rule, the "Draft acceptance" paragraph
+ * and Algorithm 1 of Appendix A).
+ *
+ * THIS FILE IS TEST INFRASTRUCTURE.  It is a plain, slow, obviously-correct
+ * statement of what the method computes, written to be checked against the
+ * paper by eye.  It shares no code, header, table or helper with the GPU
+ * library, and the GPU library never calls it.  Only the tests, the smoke
+ * check and the benchmark's CPU-baseline leg may load it.
+ *
+ * The method is a heuristic defined by its algorithm, so the oracle is the
+ * algorithm itself, step by step, in the order of Algorithm 1:
+ *   1. take the k-token suffix of path i;
+ *   2. scan every other path j for places where that suffix occurs and
+ *      collect the tokens that follow (the candidate pool C_t, Eq. 3);
+ *   3. build the layered DAG: layer d holds the d-th token after each match,
+ *      equal tokens of a layer are one node, and every (u -> v) transition
+ *      between consecutive layers accumulates a weight (Eq. 5);
+ *   4. walk the layers greedily (the extraction rule after Eq. 5);
+ *   5. count how many leading draft tokens equal the verification targets
+ *      ("Draft acceptance").
+ * Every history is scanned naively for every query; tables are std::map.
+ *
+ * Readings of the paper taken here (each is also listed in the design notes):
+ *  R1  A match must be followed by at least one token, and the continuation
+ *      starts at the token AFTER the matched suffix (Introduction: "tokens
+ *      immediately following these matches").  0-based: position e of path j
+ *      is a match when y_j[e-q .. e-1] equals the query and e < len_j.
+ *  R2  Any position of path j's current history qualifies, also beyond
+ *      path i's own length (Eq. 3's t' <= t only says "already generated").
+ *  R3  q = min(k, len_i); q = 0 gives an empty draft.  Path i itself is
+ *      never searched (j != i, Eq. 3).
+ *  R4  Candidates are a multiset: every (j, e) is one instance of Eq. 5's
+ *      sum, even when two continuations hold the same tokens.
+ *  R5  p_theta(v_i | u_i) is the probability the model assigned to token v
+ *      when it sampled it in path j (supplied by the caller with the token).
+ *      It is quantised once to a 16-bit fraction: round-to-nearest-even of
+ *      p * 65536, clamped to [0, 65536]; NaN counts as 0.  With no
+ *      probabilities supplied every p is 1.
+ *  R6  Freq(u -> v) is the raw count of instances with u in layer d-1 and v
+ *      in layer d.
+ *  R7  All weights are exact integers: with alpha_q = round(alpha * 65536),
+ *      a count C and a probability sum S (in 1/65536 units) give
+ *      key = alpha_q * S + (65536 - alpha_q) * (C << 16) = weight * 2^32.
+ *  R8  The greedy step picks, among the successors v of the current node
+ *      (edges (cur, v) of layer d), the one whose weight is largest; the
+ *      weight is the node in-weight  sum over u of w(u, v)  (score_mode 0,
+ *      the paper's formula) or the single edge weight w(cur, v)
+ *      (score_mode 1).  Ties go to the lowest token id.  The walk stops at L
+ *      tokens or when the current node has no successor (leaf / empty DAG).
+ *  R9  The predecessor of a layer-1 token is the last query token.
+ *  R10 token_score[d] = key / 2^32 as float, path_score = (sum of keys)/2^32.
+ *  R11 Accept length = number of leading draft tokens equal to the targets,
+ *      in [0, draft_len]; no bonus token (Table 1's values never exceed L).
+ *
+ * Build: g++ -O2 -shared -fPIC -o libcsd_oracle.so csd_oracle.cpp
+ */
+#include <cmath>
+#include <cstdint>
+#include <map>
+#include <utility>
+#include <vector>
+
+namespace {
+
+struct Weight {            /* one DAG edge or node: Eq. 5's two sums */
+  uint64_t C = 0;          /* Freq: number of instances              */
+  uint64_t S = 0;          /* sum of quantised probabilities         */
+};
+
+struct Candidate {         /* one element of the pool C_t (Eq. 3)    */
+  int32_t j;               /* path it was found in                   */
+  int32_t e;               /* index of its first continuation token  */
+};
+
+/* R5: probability -> integer in [0, 65536]. */
+uint32_t quantize_prob(float p) {
+  if (std::isnan(p)) return 0;
+  double x = std::nearbyint(static_cast<double>(p) * 65536.0); /* half-even */
+  if (x < 0.0) x = 0.0;
+  if (x > 65536.0) x = 65536.0;
+  return static_cast<uint32_t>(x);
+}
+
+/* One problem's histories: tok[j*max_len + t], prob likewise (may be null). */
+struct Paths {
+  const int32_t* tok;
+  const float* prob;
+  const int32_t* len;
+  int32_t N;
+  int32_t max_len;
+  int32_t token(int32_t j, int32_t t) const { return tok[(int64_t)j * max_len + t]; }
+  uint32_t pq(int32_t j, int32_t t) const {
+    return prob ? quantize_prob(prob[(int64_t)j * max_len + t]) : 65536u;
+  }
+};
+
+/* Algorithm 1, the search loop (Eq. 3): the candidate pool of path i. */
+std::vector<Candidate> candidate_pool(const Paths& Y, int32_t i, int32_t k, int32_t* q_out) {
+  std::vector<Candidate> pool;
+  int32_t len_i = Y.len[i];
+  int32_t q = k < len_i ? k : len_i;                       /* R3 */
+  *q_out = q;
+  if (q <= 0) return pool;
+  for (int32_t j = 0; j < Y.N; ++j) {
+    if (j == i) continue;                                  /* R3 */
+    for (int32_t e = q; e <= Y.len[j] - 1; ++e) {          /* R1, R2 */
+      bool same = true;
+      for (int32_t a = 0; a < q; ++a)
+        if (Y.token(j, e - q + a) != Y.token(i, len_i - q + a)) same = false;
+      if (same) pool.push_back(Candidate{j, e});
+    }
+  }
+  return pool;                                             /* ascending (j, e) */
+}
+
+typedef std::map<std::pair<int32_t, int32_t>, Weight> EdgeTable;   /* (u, v) -> weight */
+
+/* Algorithm 1, DAG construction (Eq. 5): edges[d-1] is the table of layer d. */
+std::vector<EdgeTable> build_dag(const Paths& Y, const std::vector<Candidate>& pool, int32_t L) {
+  std::vector<EdgeTable> edges(L > 0 ? L : 0);
+  for (int32_t d = 1; d <= L; ++d) {
+    for (const Candidate& c : pool) {
+      int32_t t = c.e + d - 1;                 /* d-th token after the match */
+      if (t >= Y.len[c.j]) continue;           /* this candidate has ended   */
+      int32_t u = Y.token(c.j, t - 1);         /* R9 for d = 1               */
+      int32_t v = Y.token(c.j, t);
+      Weight& w = edges[d - 1][std::make_pair(u, v)];
+      w.C += 1;                                /* R4, R6 */
+      w.S += Y.pq(c.j, t);                     /* R5     */
+    }
+  }
+  return edges;
+}
+
+uint64_t weight_key(const Weight& w, uint32_t alpha_q) {   /* R7 */
+  return (uint64_t)alpha_q * w.S + (uint64_t)(65536u - alpha_q) * (w.C << 16);
+}
+
+}  // namespace
+
+extern "C" {
+
+uint32_t oracle_quantize_prob(float p) { return quantize_prob(p); }
+
+/* alpha in [0,1] -> alpha_q in [0, 65536] (R7). */
+uint32_t oracle_alpha_q(double alpha) {
+  double x = std::nearbyint(alpha * 65536.0);
+  if (x < 0.0) x = 0.0;
+  if (x > 65536.0) x = 65536.0;
+  return (uint32_t)x;
+}
+
+/* Match set of path i (Eq. 3) as (j, e) rows in ascending order.  Returns the
+ * number of matches; writes at most cap rows. */
+int64_t oracle_matches(const int32_t* tok, const int32_t* len, int32_t N, int32_t max_len,
+                       int32_t i, int32_t k, int32_t* out_je, int64_t cap) {
+  Paths Y{tok, nullptr, len, N, max_len};
+  int32_t q;
+  std::vector<Candidate> pool = candidate_pool(Y, i, k, &q);
+  for (int64_t m = 0; m < (int64_t)pool.size() && m < cap; ++m) {
+    out_je[2 * m] = pool[m].j;
+    out_je[2 * m + 1] = pool[m].e;
+  }
+  return (int64_t)pool.size();
+}
+
+/* Edge tables of path i's DAG (Eq. 5) as rows (d, u, v) / (C, S) sorted by
+ * (d, u, v).  Returns the number of rows; writes at most cap rows. */
+int64_t oracle_edges(const int32_t* tok, const float* prob, const int32_t* len, int32_t N,
+                     int32_t max_len, int32_t i, int32_t k, int32_t L,
+                     int32_t* out_duv, uint64_t* out_cs, int64_t cap) {
+  Paths Y{tok, prob, len, N, max_len};
+  int32_t q;
+  std::vector<Candidate> pool = candidate_pool(Y, i, k, &q);
+  std::vector<EdgeTable> edges = build_dag(Y, pool, L);
+  int64_t n = 0;
+  for (int32_t d = 1; d <= L; ++d) {
+    for (const auto& kv : edges[d - 1]) {
+      if (n < cap) {
+        out_duv[3 * n] = d;
+        out_duv[3 * n + 1] = kv.first.first;
+        out_duv[3 * n + 2] = kv.first.second;
+        out_cs[2 * n] = kv.second.C;
+        out_cs[2 * n + 1] = kv.second.S;
+      }
+      ++n;
+    }
+  }
+  return n;
+}
+
+/* Draft of path i (Algorithm 1 as a whole).  draft[L] is padded with -1,
+ * token_scores[L] with 0.  Returns the draft length. */
+int32_t oracle_draft(const int32_t* tok, const float* prob, const int32_t* len, int32_t N,
+                     int32_t max_len, int32_t i, int32_t k, int32_t L, uint32_t alpha_q,
+                     int32_t score_mode, int32_t* draft, float* token_scores,
+                     float* path_score) {
+  for (int32_t d = 0; d < L; ++d) { draft[d] = -1; token_scores[d] = 0.0f; }
+  *path_score = 0.0f;
+  Paths Y{tok, prob, len, N, max_len};
+  int32_t q;
+  std::vector<Candidate> pool = candidate_pool(Y, i, k, &q);
+  if (pool.empty()) return 0;
+  std::vector<EdgeTable> edges = build_dag(Y, pool, L);
+
+  int32_t cur = Y.token(i, Y.len[i] - 1);        /* R9: root = last query token */
+  uint64_t key_sum = 0;
+  int32_t n = 0;
+  for (int32_t d = 1; d <= L; ++d) {
+    const EdgeTable& E = edges[d - 1];
+    /* node in-weights of this layer: sum over all predecessors u (R8) */
+    std::map<int32_t, Weight> node;
+    for (const auto& kv : E) {
+      Weight& w = node[kv.first.second];
+      w.C += kv.second.C;
+      w.S += kv.second.S;
+    }
+    bool found = false;
+    int32_t best_v = 0;
+    uint64_t best_key = 0;
+    for (const auto& kv : E) {                   /* ascending (u, v) */
+      if (kv.first.first != cur) continue;       /* successors of cur only */
+      int32_t v = kv.first.second;
+      uint64_t key = weight_key(score_mode == 0 ? node[v] : kv.second, alpha_q);
+      if (!found || key > best_key) {            /* strict > keeps the lowest id on ties */
+        found = true;
+        best_v = v;
+        best_key = key;
+      }
+    }
+    if (!found) break;                           /* leaf, or the layer is empty */
+    draft[n] = best_v;
+    token_scores[n] = (float)((double)best_key / 4294967296.0);   /* R10 */
+    key_sum += best_key;
+    cur = best_v;
+    ++n;
+  }
+  *path_score = (float)((double)key_sum / 4294967296.0);
+  return n;
+}
+
+/* "Draft acceptance": length of the longest draft prefix equal to the targets (R11). */
+int32_t oracle_accept(const int32_t* draft, int32_t draft_len, const int32_t* target) {
+  int32_t a = 0;
+  while (a < draft_len && draft[a] == target[a]) ++a;
+  return a;
+}
+
+/* Convenience loop used for replays and for timing: every path of every
+ * problem.  Arrays are [P][N][...]; target / accept_len may be null. */
+void oracle_draft_all(const int32_t* tok, const float* prob, const int32_t* len, int32_t P,
+                      int32_t N, int32_t max_len, int32_t k, int32_t L, uint32_t alpha_q,
+                      int32_t score_mode, int32_t* draft, int32_t* draft_len,
+                      float* token_scores, float* path_scores, const int32_t* target,
+                      int32_t* accept_len) {
+  for (int32_t p = 0; p < P; ++p) {
+    const int32_t* tk = tok + (int64_t)p * N * max_len;
+    const float* pr = prob ? prob + (int64_t)p * N * max_len : nullptr;
+    const int32_t* ln = len + (int64_t)p * N;
+    for (int32_t i = 0; i < N; ++i) {
+      int64_t r = (int64_t)p * N + i;
+      draft_len[r] = oracle_draft(tk, pr, ln, N, max_len, i, k, L, alpha_q, score_mode,
+                                  draft + r * L, token_scores + r * L, path_scores + r);
+      if (target && accept_len)
+        accept_len[r] = oracle_accept(draft + r * L, draft_len[r], target + r * L);
+    }
+  }
+}
+
+}  /* extern "C" */

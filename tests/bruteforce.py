@@ -1,0 +1,87 @@
+"""Brute-force statement of the method for TINY inputs, in exact rational
+arithmetic, used only to pin the C++ oracle.
+
+Written from the definitions, not from the oracle: matches are a literal
+set-builder over every (j, e) (Eq. 3 of the paper), candidates are explicit
+token sequences, edge weights are Eq. 5 evaluated with fractions.Fraction for
+a real-valued alpha, and the greedy rule is evaluated on those rationals.
+"""
+from collections import defaultdict
+from fractions import Fraction
+
+
+def quant(p):
+    """Probability as a multiple of 1/65536 (Python round() is half-to-even)."""
+    if p != p:
+        return 0
+    return max(0, min(65536, round(float(p) * 65536.0)))
+
+
+def match_set(paths, i, k):
+    yi = paths[i]
+    q = min(k, len(yi))
+    if q == 0:
+        return q, set()
+    suffix = tuple(yi[len(yi) - q:])
+    return q, {(j, e) for j, yj in enumerate(paths) if j != i
+               for e in range(q, len(yj)) if tuple(yj[e - q:e]) == suffix}
+
+
+def candidates(paths, probs, i, k, L):
+    """Each candidate = [(predecessor, token, prob_fraction), ...] of length <= L."""
+    _, M = match_set(paths, i, k)
+    out = []
+    for (j, e) in M:
+        seq = []
+        for t in range(e, min(e + L, len(paths[j]))):
+            p = Fraction(quant(probs[j][t]), 65536) if probs is not None else Fraction(1)
+            seq.append((paths[j][t - 1], paths[j][t], p))
+        out.append(seq)
+    return out
+
+
+def edge_tables(paths, probs, i, k, L):
+    """{(d, u, v): [count, prob_sum_fraction]} with d = 1..L."""
+    E = defaultdict(lambda: [0, Fraction(0)])
+    for seq in candidates(paths, probs, i, k, L):
+        for d, (u, v, p) in enumerate(seq, start=1):
+            E[(d, u, v)][0] += 1
+            E[(d, u, v)][1] += p
+    return dict(E)
+
+
+def draft(paths, probs, i, k, L, alpha=Fraction(1), score_mode=0):
+    """Returns (tokens, scores) with scores as exact Fractions."""
+    alpha = Fraction(alpha)
+    E = edge_tables(paths, probs, i, k, L)
+    if not E:
+        return [], []
+
+    def w(cs):
+        return alpha * cs[1] + (1 - alpha) * cs[0]
+
+    cur = paths[i][-1]
+    toks, scores = [], []
+    for d in range(1, L + 1):
+        succ = sorted(v for (dd, u, v) in E if dd == d and u == cur)
+        if not succ:
+            break
+        def score(v):
+            if score_mode == 1:
+                return w(E[(d, cur, v)])
+            return sum(w(cs) for (dd, u, vv), cs in E.items() if dd == d and vv == v)
+        best = max(score(v) for v in succ)
+        v_star = min(v for v in succ if score(v) == best)
+        toks.append(v_star)
+        scores.append(best)
+        cur = v_star
+    return toks, scores
+
+
+def accept(draft_tokens, target):
+    a = 0
+    for x, y in zip(draft_tokens, target):
+        if x != y:
+            break
+        a += 1
+    return a

@@ -1,0 +1,303 @@
+"""Pins for the CPU oracle: everything here runs without a GPU.
+
+The oracle is checked against things other than itself: a hand-derived worked
+example (tests/golden), closed forms, invariants, reductions to library
+routines (collections.Counter, numpy.nonzero) and an exact-rational brute
+force on thousands of tiny inputs.
+"""
+import json
+import os
+from collections import Counter
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import bruteforce as bf
+from paper_2503_05330_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "hand_worked_dag.json")
+
+
+def pack(paths, probs=None, max_len=None):
+    """Ragged python lists -> (tok [N][max_len], prob or None, len [N])."""
+    N = len(paths)
+    max_len = max_len or max(1, max(len(p) for p in paths))
+    tok = np.full((N, max_len), -7, dtype=np.int32)      # junk past the end must be ignored
+    pr = None if probs is None else np.full((N, max_len), 0.123, dtype=np.float32)
+    for j, p in enumerate(paths):
+        tok[j, :len(p)] = p
+        if probs is not None:
+            pr[j, :len(p)] = probs[j]
+    return tok, pr, np.array([len(p) for p in paths], dtype=np.int32)
+
+
+# ---------------------------------------------------------------- worked example
+def test_hand_worked_example(oracle):
+    g = json.load(open(GOLDEN))
+    tok, _, ln = pack(g["paths"])
+    i, k, L = g["query_path"], g["k"], g["L"]
+    assert oracle.matches(tok, ln, i, k).tolist() == g["matches"]
+    duv, cs = oracle.edges(tok, None, ln, i, k, L)
+    assert [list(r) + [int(c[0])] for r, c in zip(duv.tolist(), cs)] == g["edges_counts"]
+    assert (cs[:, 1] == cs[:, 0] * 65536).all()          # p = 1 for every instance
+    for mode in (0, 1):
+        want = g["no_probs"]["mode%d" % mode]
+        for alpha in (0.0, 0.3, 1.0):                    # no probs: alpha cannot matter
+            d, n, ts, ps = oracle.draft(tok, None, ln, i, k, L, alpha, mode)
+            assert d[:n].tolist() == want["draft"] and n == len(want["draft"])
+            assert ts[:n].tolist() == want["token_scores"] and float(ps) == want["path_score"]
+    tokp, pr, ln = pack(g["paths"], g["probs"])
+    for key, alpha in (("alpha1_mode0", 1.0), ("alpha0.5_mode0", 0.5)):
+        want = g["with_probs"][key]
+        d, n, ts, ps = oracle.draft(tokp, pr, ln, i, k, L, alpha, 0)
+        assert d[:n].tolist() == want["draft"]
+        assert ts[:n].tolist() == want["token_scores"] and float(ps) == want["path_score"]
+    for a in g["accept"]:
+        d, n, _, _ = oracle.draft(tok, None, ln, i, k, L, 1.0, a["mode"])
+        assert oracle.accept(d, n, np.array(a["target"], dtype=np.int32)) == a["accept_len"]
+
+
+def test_strict_length_reading_would_lose_a_match(oracle):
+    """Reading R2: path 1's second occurrence lies beyond path 0's own length
+    (e = 7 > len_0 = 4) and still counts."""
+    g = json.load(open(GOLDEN))
+    tok, _, ln = pack(g["paths"])
+    assert [1, 7] in oracle.matches(tok, ln, 0, 2).tolist()
+
+
+# ---------------------------------------------------------------- quantisation
+def test_quantize_prob_values(oracle):
+    q = oracle.quantize_prob
+    assert q(0.0) == 0 and q(1.0) == 65536 and q(0.5) == 32768 and q(0.25) == 16384
+    assert q(-0.5) == 0 and q(7.0) == 65536 and q(float("nan")) == 0
+    assert q(1.0 / 65536) == 1
+    # exact halves go to the even neighbour
+    assert q(2.5 / 65536) == 2 and q(3.5 / 65536) == 4 and q(0.5 / 65536) == 0
+    assert q(np.float32(0.7)) == round(float(np.float32(0.7)) * 65536)
+    assert oracle.alpha_q(1.0) == 65536 and oracle.alpha_q(0.0) == 0 and oracle.alpha_q(0.5) == 32768
+
+
+# ---------------------------------------------------------------- closed forms
+def test_closed_form_identical_paths_draft_own_continuation(oracle):
+    """N identical paths over a sequence without repeated q-grams; path 0 is
+    truncated to t tokens: its draft is seq[t:t+L], each score N-1."""
+    N, T, k, L = 5, 40, 3, 6
+    seq = list(range(100, 100 + T))                      # all tokens distinct
+    for t in (3, 10, T - 2):
+        paths = [seq[:t]] + [seq for _ in range(N - 1)]
+        tok, _, ln = pack(paths)
+        d, n, ts, ps = oracle.draft(tok, None, ln, 0, k, L)
+        want = seq[t:t + L]
+        assert d[:n].tolist() == want and n == len(want)
+        assert ts[:n].tolist() == [float(N - 1)] * n and float(ps) == n * (N - 1)
+        assert (d[n:] == -1).all() and (ts[n:] == 0).all()
+    # a full-length path's suffix sits at the very end of the others: no successor, no draft
+    tok, _, ln = pack([seq] * N)
+    assert oracle.draft(tok, None, ln, 0, k, L)[1] == 0
+
+
+def test_closed_form_constant_paths(oracle):
+    """All tokens equal: M = (N-1)(T-q); alive at layer d = (N-1)(T-q-d+1)."""
+    N, T, k, L, c = 4, 20, 3, 6, 9
+    tok, _, ln = pack([[c] * T] * N)
+    assert len(oracle.matches(tok, ln, 1, k)) == (N - 1) * (T - k)
+    d, n, ts, ps = oracle.draft(tok, None, ln, 1, k, L)
+    assert n == min(L, T - k) and d[:n].tolist() == [c] * n
+    assert ts[:n].tolist() == [float((N - 1) * (T - k - dd + 1)) for dd in range(1, n + 1)]
+    # short paths: the walk ends when no candidate is alive any more
+    T2 = 6
+    tok, _, ln = pack([[c] * T2] * N)
+    d, n, ts, _ = oracle.draft(tok, None, ln, 0, k, L)
+    assert n == T2 - k and ts[:n].tolist() == [float((N - 1) * (T2 - k - dd + 1)) for dd in range(1, n + 1)]
+
+
+def test_closed_form_disjoint_vocab_is_empty(oracle):
+    paths = [list(range(100 * j, 100 * j + 30)) for j in range(4)]
+    tok, _, ln = pack(paths)
+    for i in range(4):
+        d, n, ts, ps = oracle.draft(tok, None, ln, i, 2, 5)
+        assert n == 0 and (d == -1).all() and (ts == 0).all() and float(ps) == 0.0
+        assert len(oracle.matches(tok, ln, i, 2)) == 0
+        assert len(oracle.edges(tok, None, ln, i, 2, 5)[0]) == 0
+
+
+def test_short_and_empty_paths(oracle):
+    paths = [[], [4, 4, 4, 4], [4]]
+    tok, _, ln = pack(paths)
+    assert oracle.draft(tok, None, ln, 0, 3, 4)[1] == 0          # q = 0
+    # path 2 has one token: q clips to 1 and matches path 1 at e = 1, 2, 3
+    assert oracle.matches(tok, ln, 2, 3).tolist() == [[1, 1], [1, 2], [1, 3]]
+    d, n, ts, _ = oracle.draft(tok, None, ln, 2, 3, 4)
+    assert d[:n].tolist() == [4, 4, 4] and ts[:n].tolist() == [3.0, 2.0, 1.0]
+
+
+def test_ties_break_to_lowest_id(oracle):
+    # two continuations of equal weight after the query (7): tokens 30 and 12
+    paths = [[1, 7], [7, 30, 5], [7, 12, 5], [0, 7]]
+    tok, _, ln = pack(paths)
+    for mode in (0, 1):
+        d, n, ts, _ = oracle.draft(tok, None, ln, 0, 1, 2, 1.0, mode)
+        assert d[:n].tolist() == [12, 5] and ts[:n].tolist() == [1.0, 2.0 if mode == 0 else 1.0]
+
+
+# ---------------------------------------------------------------- library reductions
+def test_match_positions_reduce_to_numpy_nonzero(oracle):
+    rng = np.random.default_rng(7)
+    other = rng.integers(0, 6, size=200).astype(np.int32)
+    for tokq in range(6):
+        tok, _, ln = pack([[3, tokq], other.tolist()])
+        got = oracle.matches(tok, ln, 0, 1)
+        want = np.nonzero(other[:-1] == tokq)[0] + 1          # successor index; last token has none
+        assert (got[:, 0] == 1).all() and got[:, 1].tolist() == want.tolist()
+
+
+def test_layer1_counts_reduce_to_ngram_counter(oracle):
+    """L = 1, alpha = 0: the edge table is the successor-count table of the
+    q-gram over the other paths — a plain n-gram Counter."""
+    w = synth.scaled(synth.WORKLOADS["C1"], vocab=12, pool=6, max_len=96)
+    tokens, probs = synth.make_paths(w)
+    tok = tokens[0]
+    ln = np.array([96, 80, 96, 50], dtype=np.int32)
+    for q in (1, 2, 3):
+        for i in range(4):
+            gram = tuple(tok[i, ln[i] - q:ln[i]])
+            cnt = Counter()
+            for j in range(4):
+                if j == i:
+                    continue
+                seq = tok[j, :ln[j]].tolist()
+                cnt.update(seq[e] for e in range(q, len(seq)) if tuple(seq[e - q:e]) == gram)
+            duv, cs = oracle.edges(tok, probs[0], ln, i, q, 1)
+            assert {int(r[2]): int(c[0]) for r, c in zip(duv, cs)} == dict(cnt)
+            assert (duv[:, 0] == 1).all() and (duv[:, 1] == gram[-1]).all()
+            d, n, ts, _ = oracle.draft(tok, probs[0], ln, i, q, 1, alpha=0.0)
+            if cnt:
+                top = max(cnt.values())
+                assert n == 1 and d[0] == min(v for v, c in cnt.items() if c == top) and ts[0] == top
+            else:
+                assert n == 0
+
+
+# ---------------------------------------------------------------- brute force
+def _random_case(rng):
+    N = int(rng.integers(2, 5))
+    V = int(rng.integers(2, 7))
+    paths = [rng.integers(0, V, size=int(rng.integers(0, 25))).tolist() for _ in range(N)]
+    # probabilities on a coarse dyadic grid so that ties between sums are common
+    probs = [(rng.integers(0, 9, size=len(p)) / 8.0).astype(np.float32).tolist() for p in paths]
+    return paths, probs
+
+
+def test_brute_force_tiny_inputs(oracle):
+    rng = np.random.default_rng(12345)
+    n_nonempty = 0
+    for case in range(1500):
+        paths, probs = _random_case(rng)
+        use_probs = case % 3 != 0
+        k = int(rng.integers(1, 5))
+        L = int(rng.integers(1, 7))
+        alpha = Fraction(int(rng.integers(0, 5)), 4)
+        mode = int(rng.integers(0, 2))
+        tok, pr, ln = pack(paths, probs if use_probs else None, max_len=26)
+        for i in range(len(paths)):
+            q, M = bf.match_set(paths, i, k)
+            assert oracle.matches(tok, ln, i, k).tolist() == [list(m) for m in sorted(M)]
+            E = bf.edge_tables(paths, probs if use_probs else None, i, k, L)
+            duv, cs = oracle.edges(tok, pr, ln, i, k, L)
+            assert [tuple(r) for r in duv.tolist()] == sorted(E)
+            for r, c in zip(duv.tolist(), cs):
+                assert int(c[0]) == E[tuple(r)][0] and Fraction(int(c[1]), 65536) == E[tuple(r)][1]
+            toks, scores = bf.draft(paths, probs if use_probs else None, i, k, L, alpha, mode)
+            d, n, ts, ps = oracle.draft(tok, pr, ln, i, k, L, float(alpha), mode)
+            assert d[:n].tolist() == toks and n == len(toks)
+            assert (d[n:] == -1).all() and (ts[n:] == 0).all()
+            assert ts[:n].tolist() == [float(np.float32(float(s))) for s in scores]
+            assert float(ps) == float(np.float32(float(sum(scores, Fraction(0)))))
+            n_nonempty += n > 0
+            tgt = rng.integers(0, 3, size=L).astype(np.int32)
+            if n and rng.random() < 0.5:
+                tgt[:n] = d[:n]
+                tgt[int(rng.integers(0, L)):] = -5
+            assert oracle.accept(d, n, tgt) == bf.accept(toks, tgt.tolist())
+    assert n_nonempty > 1000
+
+
+def test_real_valued_probabilities_against_fractions(oracle):
+    """Arbitrary float32 probabilities and alpha = k/65536: the integer key
+    equals Eq. 5 evaluated exactly on the quantised probabilities."""
+    rng = np.random.default_rng(99)
+    for case in range(200):
+        N = 3
+        paths = [rng.integers(0, 4, size=int(rng.integers(4, 30))).tolist() for _ in range(N)]
+        probs = [rng.random(len(p)).astype(np.float32).tolist() for p in paths]
+        alpha_q = int(rng.integers(0, 65537))
+        tok, pr, ln = pack(paths, probs)
+        for mode in (0, 1):
+            toks, scores = bf.draft(paths, probs, 0, 2, 5, Fraction(alpha_q, 65536), mode)
+            d, n, ts, ps = oracle.draft(tok, pr, ln, 0, 2, 5, alpha_q / 65536.0, mode)
+            assert d[:n].tolist() == toks
+            assert ts[:n].tolist() == [float(np.float32(float(s))) for s in scores]
+
+
+# ---------------------------------------------------------------- invariants on the synthetic workloads
+@pytest.mark.parametrize("name", ["C1", "C2"])
+def test_invariants_on_synthetic_paths(oracle, name):
+    w = synth.WORKLOADS[name]
+    if name == "C2":
+        w = synth.scaled(w, max_len=256, n_paths=8)
+    tokens, probs = synth.make_paths(w)
+    tok, pr = tokens[0], probs[0]
+    k, L = w.query_len, w.draft_len
+    seen = 0
+    for t in range(8, w.max_len, 23):
+        ln = np.full(w.n_paths, t, dtype=np.int32)
+        for i in range(w.n_paths):
+            M = oracle.matches(tok, ln, i, k)
+            duv, cs = oracle.edges(tok, pr, ln, i, k, L)
+            E = {tuple(r): (int(c[0]), int(c[1])) for r, c in zip(duv.tolist(), cs)}
+            for mode in (0, 1):
+                d, n, ts, ps = oracle.draft(tok, pr, ln, i, k, L, 1.0, mode)
+                if len(M) == 0:
+                    assert n == 0
+                    continue
+                assert n >= 1            # every match has a successor, so layer 1 is never empty
+                cur = int(tok[i, t - 1])
+                for dd in range(n):
+                    c, s = E[(dd + 1, cur, int(d[dd]))]      # KeyError = transition is not an edge
+                    assert c > 0
+                    assert float(ts[dd]) * 65536 >= s * (1 - 1e-6)   # in-weight >= edge weight
+                    cur = int(d[dd])
+                seen += 1
+            # alpha = 0 ignores probabilities; without probabilities alpha is irrelevant
+            a = oracle.draft(tok, pr, ln, i, k, L, 0.0, 0)
+            b = oracle.draft(tok, None, ln, i, k, L, 0.0, 0)
+            c_ = oracle.draft(tok, None, ln, i, k, L, 0.37, 0)
+            assert a[0].tolist() == b[0].tolist() == c_[0].tolist()
+            assert a[2].tolist() == b[2].tolist() == c_[2].tolist()
+    assert seen > 20
+
+
+def test_draft_all_matches_single_calls(oracle):
+    w = synth.scaled(synth.WORKLOADS["C4"], n_problems=3, n_paths=5, max_len=120)
+    tokens, probs = synth.make_paths(w)
+    ln = np.random.default_rng(3).integers(0, 121, size=(3, 5)).astype(np.int32)
+    tg = synth.make_targets(tokens, 60, w.draft_len)
+    out = oracle.draft_all(tokens, probs, ln, 3, w.draft_len, 1.0, 0, tg)
+    for p in range(3):
+        for i in range(5):
+            d, n, ts, ps = oracle.draft(tokens[p], probs[p], ln[p], i, 3, w.draft_len)
+            assert out["draft"][p, i].tolist() == d.tolist() and out["draft_len"][p, i] == n
+            assert out["token_scores"][p, i].tolist() == ts.tolist() and out["path_scores"][p, i] == ps
+            assert out["accept_len"][p, i] == oracle.accept(d, n, tg[p, i])
+
+
+def test_generator_is_seeded_and_shaped():
+    for name, w in synth.WORKLOADS.items():
+        if name in ("C4", "C5"):
+            w = synth.scaled(w, n_problems=min(w.n_problems, 2), max_len=512)
+        a, pa = synth.make_paths(w)
+        b, pb = synth.make_paths(w)
+        assert (a == b).all() and (pa == pb).all()
+        assert a.shape == (w.n_problems, w.n_paths, w.max_len) and a.dtype == np.int32
+        assert a.min() >= 0 and a.max() < w.vocab and pa.min() > 0 and pa.max() <= 1
