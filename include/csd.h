@@ -1,0 +1,166 @@
+/*
+ * csd — consensus speculative drafting across N parallel sampling paths.
+ *
+ * C-ABI boundary of the MI355X (gfx950) library.  The operations follow the
+ * problem statement of "Speculative Decoding for Multi-Sample Inference"
+ * (Method section and Algorithm 1 of Appendix A): keep the token histories of
+ * N parallel sampling paths (the "dynamic draft pool"), and at every decoding
+ * step produce, for every path, a draft of up to L tokens by
+ *   (1) matching the path's last k tokens against every OTHER path's history
+ *       (Eq. 3),
+ *   (2) merging the tokens that follow the matches into a layered token DAG
+ *       whose edges carry  w(u,v) = alpha * sum_i p(v_i|u_i)
+ *                                   + (1 - alpha) * Freq(u -> v)      (Eq. 5),
+ *   (3) walking the layers greedily by largest weight (rule after Eq. 5),
+ * and then measuring how many leading draft tokens equal the tokens the
+ * target model sampled ("Draft acceptance" paragraph).
+ *
+ * Conventions
+ *  - P problems are independent; each has N paths of at most max_len tokens.
+ *  - Every pointer named d_* is DEVICE memory owned by the caller.  Arrays are
+ *    dense row-major with the shape given in brackets.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Every call except csd_status / csd_dump_* only enqueues work on `stream`
+ *    and returns; nothing is allocated, freed or synchronised by them.
+ *  - The library owns only the small host-side handle.  All device state lives
+ *    in the caller's workspace, which must stay allocated, and untouched by
+ *    the caller, until csd_destroy.
+ *  - All functions return CSD_OK (0) or a negative csd_error.  On an error
+ *    nothing has been enqueued.  A handle is not thread-safe.
+ *  - Token ids must lie in [0, vocab).  Ids outside are a caller error: the
+ *    append kernel raises CSD_STATUS_TOKEN_RANGE (see csd_status); drafts that
+ *    involve such ids are memory-safe but unspecified.
+ *
+ * Exactness.  Probabilities are quantised once at append to multiples of
+ * 1/65536 (round to nearest even, clamped to [0,1], NaN -> 0); alpha likewise.
+ * All sums are exact 64-bit integers, so every output is independent of the
+ * order in which the GPU accumulates: draft tokens, lengths and accept lengths
+ * are exact, and scores are the exact rational weight rounded once to float.
+ */
+#ifndef CSD_H_
+#define CSD_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct csd_index csd_index; /* opaque, host-side, library-owned */
+
+typedef enum {
+  CSD_OK = 0,
+  CSD_ERR_INVALID_ARG = -1,   /* NULL pointer, dimension or argument out of range     */
+  CSD_ERR_CAPACITY = -2,      /* append would exceed max_len / dump buffer too small  */
+  CSD_ERR_WORKSPACE = -3,     /* workspace too small or misaligned (needs 256 B)      */
+  CSD_ERR_HIP = -4,           /* a HIP runtime call failed                            */
+  CSD_ERR_UNIMPLEMENTED = -5  /* reserved flag bits set                               */
+} csd_error;
+
+/* Limits of this build (csd_create rejects configurations beyond them). */
+#define CSD_MAX_QUERY_LEN 8
+#define CSD_MAX_DRAFT_LEN 32
+#define CSD_MAX_VOCAB ((1 << 29) - 1)
+#define CSD_MAX_POSITIONS (1 << 24) /* n_paths * max_len per problem */
+
+/* csd_config.flags: how matches are found (Eq. 3).  Both give identical results. */
+#define CSD_MATCH_AUTO 0   /* library picks                                         */
+#define CSD_MATCH_SCAN 1   /* compare the query against every history position      */
+#define CSD_MATCH_INDEX 2  /* look the query up in the incremental n-gram hash index */
+
+/* Sticky device-side status bits, read with csd_status. */
+#define CSD_STATUS_CAPACITY 1u     /* an append was clipped at max_len               */
+#define CSD_STATUS_TOKEN_RANGE 2u  /* a token id outside [0, vocab) was appended     */
+#define CSD_STATUS_TABLE_FULL 4u   /* a draft was cut short: DAG tables exhausted    */
+
+typedef struct {
+  int32_t n_problems;     /* P > 0                                                    */
+  int32_t n_paths;        /* N > 0                                                    */
+  int32_t max_len;        /* tokens per path, > 0; N * max_len <= CSD_MAX_POSITIONS   */
+  int32_t vocab;          /* V in [1, CSD_MAX_VOCAB]                                  */
+  int32_t max_query_len;  /* upper bound of csd_draft's query_len, 1..CSD_MAX_QUERY_LEN */
+  int32_t max_draft_len;  /* upper bound of csd_draft's draft_len, 1..CSD_MAX_DRAFT_LEN */
+  float alpha;            /* Eq. 5's alpha in [0,1]; the paper's experiments use 1    */
+  int32_t score_mode;     /* 0: greedy step ranks successors by node in-weight
+                             sum_u w(u,v) (the rule after Eq. 5); 1: by w(cur,v)      */
+  int32_t flags;          /* CSD_MATCH_*; all other bits must be 0                    */
+} csd_config;
+
+/* Size in bytes of the device workspace csd_create needs for this config. */
+int csd_workspace_bytes(const csd_config* cfg, size_t* out_bytes);
+
+/* Creates an index (the draft pool of the Method section, "Dynamic Draft Pool
+ * Construction") over P x N empty paths inside d_workspace (256-byte aligned,
+ * at least csd_workspace_bytes) and enqueues its initialisation on `stream`. */
+int csd_create(const csd_config* cfg, void* d_workspace, size_t workspace_bytes, void* stream,
+               csd_index** out_index);
+
+/* Frees the host handle.  Does not touch the workspace. */
+int csd_destroy(csd_index* index);
+
+/* Empties every path (same state as after csd_create). */
+int csd_reset(csd_index* index, void* stream);
+
+/* Appends up to n tokens to every path: the pool "iteratively" grows with the
+ * generation (Method, "Dynamic Draft Pool Construction").
+ *   d_tokens [P][N][n] int32  tokens sampled this step, oldest first.
+ *   d_probs  [P][N][n] float  probability the model gave each of them when it
+ *                             sampled it (Eq. 5's p_theta); NULL = all 1.
+ *   d_counts [P][N]    int32  how many of the n tokens path (p,i) really takes
+ *                             (clamped to [0,n]); NULL = n for every path.
+ * CSD_ERR_CAPACITY if the host can tell that a path would exceed max_len
+ * (always the case with d_counts == NULL); with d_counts the kernel clips the
+ * append at max_len and raises CSD_STATUS_CAPACITY. */
+int csd_append(csd_index* index, const int32_t* d_tokens, const float* d_probs,
+               const int32_t* d_counts, int32_t n, void* stream);
+
+/* Builds the draft of every path (Algorithm 1): suffix match of the last
+ * q = min(query_len, len_i) tokens against all other paths (Eq. 3), DAG edge
+ * weights (Eq. 5), greedy walk of at most draft_len layers.
+ *   d_draft_tokens [P][N][draft_len] int32  draft, padded with -1.
+ *   d_draft_len    [P][N]            int32  number of draft tokens (0 = no match).
+ *   d_token_scores [P][N][draft_len] float  weight of each chosen token, padded
+ *                                           with 0; may be NULL.
+ *   d_path_scores  [P][N]            float  sum of those weights; may be NULL.
+ * query_len in [1, max_query_len], draft_len in [1, max_draft_len]. */
+int csd_draft(csd_index* index, int32_t query_len, int32_t draft_len, int32_t* d_draft_tokens,
+              int32_t* d_draft_len, float* d_token_scores, float* d_path_scores, void* stream);
+
+/* Greedy accept length ("Draft acceptance"): for every path the number of
+ * leading draft tokens equal to the target tokens, in [0, draft_len[p][i]].
+ *   d_targets    [P][N][draft_len] int32  tokens the target model sampled.
+ *   d_accept_len [P][N]            int32  output. */
+int csd_accept(csd_index* index, const int32_t* d_draft_tokens, const int32_t* d_draft_len,
+               const int32_t* d_targets, int32_t draft_len, int32_t* d_accept_len, void* stream);
+
+/* Waits for `stream` and copies the sticky CSD_STATUS_* bits to *host_flags. */
+int csd_status(csd_index* index, uint32_t* host_flags, void* stream);
+
+/* ---- debug / parity only: canonical dumps of intermediate results ---------
+ * These allocate temporary device memory, synchronise `stream`, and are not
+ * meant for the decoding loop.  They run the same matching and aggregation
+ * device code as csd_draft. */
+
+/* Match sets of Eq. 3.  Row r = p*N + i owns d_match_je[d_match_off[r] ..
+ * d_match_off[r+1]) as (j, e) pairs in ascending order: path j, index e of the
+ * first token after the match.  d_match_je [cap][2], d_match_off [P*N+1].
+ * CSD_ERR_CAPACITY if there are more than cap matches (offsets still valid). */
+int csd_dump_matches(csd_index* index, int32_t query_len, int32_t* d_match_je,
+                     int32_t* d_match_off, int64_t cap, void* stream);
+
+/* Edge tables of Eq. 5.  Row r owns rows d_edge_off[r] .. d_edge_off[r+1] of
+ * d_edge_duv [cap][3] = (layer d in 1..draft_len, u, v) sorted ascending and
+ * d_edge_cs [cap][2] = (count C, probability sum S in 1/65536 units).
+ * CSD_ERR_CAPACITY if cap is too small or a path's tables exceed the
+ * on-chip tier (such a path is still drafted correctly by csd_draft). */
+int csd_dump_edges(csd_index* index, int32_t query_len, int32_t draft_len, int32_t* d_edge_duv,
+                   uint64_t* d_edge_cs, int32_t* d_edge_off, int64_t cap, void* stream);
+
+/* Text for a csd_error (and, for CSD_ERR_HIP, the last HIP error string). */
+const char* csd_strerror(int err);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CSD_H_ */

@@ -1,0 +1,78 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every symbol the header declares, sizes its workspace, and rejects bad
+arguments before anything is enqueued."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2503_05330_amd import binding
+    return binding.load()
+
+
+def test_exports_every_declared_symbol(lib):
+    from paper_2503_05330_amd import binding
+    header = open(os.path.join(ROOT, "include", "csd.h")).read()
+    declared = sorted(set(re.findall(r"^(?:int|const char\*)\s+(csd_[a-z_]+)\s*\(", header, re.M)))
+    assert declared, "no declarations found"
+    for name in declared:
+        assert hasattr(lib, name), "libcsd.so does not export " + name
+    assert sorted(binding.EXPORTS) == declared
+
+
+def test_workspace_size_and_validation(lib):
+    from paper_2503_05330_amd import binding as b
+    good = dict(n_problems=1, n_paths=16, max_len=1024, vocab=32000, max_query_len=3,
+                max_draft_len=8, alpha=1.0, score_mode=0, flags=0)
+    n = b.workspace_bytes(b.Config(**good))
+    assert n >= 2 * 16 * 1024 * 4 and n % 256 == 0
+    out = ctypes.c_size_t(0)
+    bad_cases = [dict(n_problems=0), dict(n_paths=-1), dict(max_len=0), dict(vocab=0),
+                 dict(vocab=1 << 29), dict(max_query_len=0), dict(max_query_len=9),
+                 dict(max_draft_len=0), dict(max_draft_len=33), dict(alpha=1.5),
+                 dict(alpha=float("nan")), dict(score_mode=2), dict(n_paths=4097, max_len=4096)]
+    for bad in bad_cases:
+        cfg = b.Config(**{**good, **bad})
+        assert lib.csd_workspace_bytes(ctypes.byref(cfg), ctypes.byref(out)) == b.ERR_INVALID_ARG, bad
+    cfg = b.Config(**{**good, "flags": 8})
+    assert lib.csd_workspace_bytes(ctypes.byref(cfg), ctypes.byref(out)) == b.ERR_UNIMPLEMENTED
+    assert lib.csd_workspace_bytes(None, ctypes.byref(out)) == b.ERR_INVALID_ARG
+    assert lib.csd_workspace_bytes(ctypes.byref(b.Config(**good)), None) == b.ERR_INVALID_ARG
+
+
+def test_null_and_misaligned_arguments_are_rejected(lib):
+    from paper_2503_05330_amd import binding as b
+    cfg = b.Config(1, 4, 64, 100, 3, 5, 1.0, 0, 0)
+    h = ctypes.c_void_p()
+    assert lib.csd_create(ctypes.byref(cfg), None, 1 << 20, None, ctypes.byref(h)) == b.ERR_INVALID_ARG
+    assert lib.csd_create(ctypes.byref(cfg), 256, 16, None, ctypes.byref(h)) == b.ERR_WORKSPACE
+    assert lib.csd_create(ctypes.byref(cfg), 257, 1 << 20, None, ctypes.byref(h)) == b.ERR_WORKSPACE
+    assert lib.csd_create(ctypes.byref(cfg), 256, 1 << 20, None, None) == b.ERR_INVALID_ARG
+    assert h.value is None
+    for fn, args in ((lib.csd_destroy, (None,)), (lib.csd_reset, (None, None)),
+                     (lib.csd_append, (None, None, None, None, 1, None)),
+                     (lib.csd_draft, (None, 1, 1, None, None, None, None, None)),
+                     (lib.csd_accept, (None, None, None, None, 1, None, None)),
+                     (lib.csd_status, (None, None, None)),
+                     (lib.csd_dump_matches, (None, 1, None, None, 0, None)),
+                     (lib.csd_dump_edges, (None, 1, 1, None, None, None, 0, None))):
+        assert fn(*args) == b.ERR_INVALID_ARG
+    for code in (0, -1, -2, -3, -4, -5, -99):
+        assert isinstance(b.strerror(code), str) and b.strerror(code)
+
+
+def test_binding_has_no_cpu_fallback():
+    """The product path must not import the oracle."""
+    pkg = os.path.join(ROOT, "paper_2503_05330_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"import\s+oracle|from\s+oracle|csd_oracle|oracle[/.]", text), \
+                    f + " reaches for the oracle"

@@ -1,0 +1,242 @@
+"""GPU parity: the HIP library, called through its C-ABI, against the CPU
+oracle on the same seeded inputs.  Bit-exact on match positions, edge tables,
+draft tokens, draft lengths and accept lengths; scores within 1e-6 relative
+(they are in fact the same exact integers rounded once to float)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2503_05330_amd import binding, synth
+from replay import assert_step_equal, gpu_replay
+
+pytestmark = pytest.mark.gpu
+
+
+def oracle_step(oracle, tokens, probs, lens_t, k, L, alpha, mode, target=None):
+    return oracle.draft_all(tokens, probs, lens_t, k, L, alpha, mode, target)
+
+
+def check_dumps(oracle, ix, tokens, probs, lens_t, k, L):
+    """Match sets and edge tables of every row at the index's current state."""
+    P, N, _ = tokens.shape
+    je, moff = ix.dump_matches(k)
+    duv, cs, eoff = ix.dump_edges(k, L)
+    for p in range(P):
+        for i in range(N):
+            r = p * N + i
+            want = oracle.matches(tokens[p], lens_t[p], i, k)
+            assert np.array_equal(je[moff[r]:moff[r + 1]], want), "matches row %d" % r
+            wduv, wcs = oracle.edges(tokens[p], None if probs is None else probs[p], lens_t[p], i, k, L)
+            assert np.array_equal(duv[eoff[r]:eoff[r + 1]], wduv), "edge keys row %d" % r
+            assert np.array_equal(cs[eoff[r]:eoff[r + 1]], wcs), "edge weights row %d" % r
+
+
+def run_config(oracle, w, use_probs, alpha, mode, check_every=1, dump_at=(), flags=0, accept=False):
+    tokens, probs = synth.make_paths(w)
+    if not use_probs:
+        probs = None
+    T = w.max_len
+    targets = None
+    if accept:
+        targets = np.stack([synth.make_noisy_targets(w, tokens, t + 1, w.draft_len) for t in range(T)])
+    print("replay", w.name, "P,N,T", tokens.shape, "probs", use_probs, "alpha", alpha, "mode", mode,
+          "flags", flags, flush=True)
+    got = gpu_replay(tokens, probs, w.query_len, w.draft_len, alpha, mode, flags, targets=targets)
+    assert got["status"] == 0
+    n_nonempty = 0
+    for t in list(range(0, T, check_every)) + [T - 1]:
+        want = oracle_step(oracle, tokens, probs, got["lens"][t], w.query_len, w.draft_len, alpha, mode,
+                           targets[t] if accept else None)
+        assert_step_equal(got, want, t, w.name)
+        n_nonempty += int((want["draft_len"] > 0).sum())
+    assert n_nonempty > 0
+    # intermediate results at chosen history lengths (fresh index, appended in one call)
+    for t in dump_at:
+        dev = torch.device("cuda:0")
+        ix = binding.Index(w.n_problems, w.n_paths, T, w.vocab, w.query_len, w.draft_len, alpha, mode,
+                           flags, device=dev)
+        ix.append(torch.from_numpy(np.ascontiguousarray(tokens[:, :, :t])).to(dev),
+                  None if probs is None else torch.from_numpy(np.ascontiguousarray(probs[:, :, :t])).to(dev),
+                  None, t)
+        lens_t = np.full(tokens.shape[:2], t, dtype=np.int32)
+        check_dumps(oracle, ix, tokens, probs, lens_t, w.query_len, w.draft_len)
+        for q in range(1, w.query_len):      # shorter queries at full history: many more matches
+            je, moff = ix.dump_matches(q)
+            for p in range(min(w.n_problems, 2)):
+                for i in range(w.n_paths):
+                    r = p * w.n_paths + i
+                    assert np.array_equal(je[moff[r]:moff[r + 1]], oracle.matches(tokens[p], lens_t[p], i, q))
+    return got
+
+
+def test_c1_every_step_all_modes(oracle):
+    w = synth.WORKLOADS["C1"]
+    run_config(oracle, w, True, 1.0, 0, dump_at=(5, 100, 256))
+    run_config(oracle, w, True, 0.5, 1)
+    run_config(oracle, w, False, 1.0, 0, dump_at=(256,))
+    run_config(oracle, w, True, 0.0, 0)
+
+
+def test_c2_every_step(oracle):
+    w = synth.WORKLOADS["C2"]
+    run_config(oracle, w, True, 1.0, 0, dump_at=(511, 1024))
+    run_config(oracle, w, False, 1.0, 1)
+
+
+def test_c3_every_step(oracle):
+    w = synth.WORKLOADS["C3"]
+    run_config(oracle, w, True, 1.0, 0, check_every=1, dump_at=(2048,))
+
+
+def test_c4_batched_problems(oracle):
+    w = synth.WORKLOADS["C4"]
+    run_config(oracle, w, True, 1.0, 0, check_every=4, dump_at=(1024,))
+
+
+def test_c5_sparse_matches_with_accept(oracle):
+    w = synth.WORKLOADS["C5"]
+    got = run_config(oracle, w, True, 1.0, 0, check_every=16, dump_at=(4096,), accept=True)
+    assert got["accept_len"].max() > 0
+
+
+def test_ragged_appends(oracle):
+    for name in ("C1", "C2"):
+        w = synth.WORKLOADS[name]
+        tokens, probs = synth.make_paths(w)
+        steps = w.max_len // 2
+        counts = synth.make_ragged_counts(w, 4, steps)
+        got = gpu_replay(tokens, probs, w.query_len, w.draft_len, steps=steps, counts=counts, n_per_step=4)
+        assert got["status"] in (0, binding.STATUS_CAPACITY)
+        assert got["lens"].max() > got["lens"].min()
+        for t in range(steps):
+            want = oracle_step(oracle, tokens, probs, got["lens"][t], w.query_len, w.draft_len, 1.0, 0)
+            assert_step_equal(got, want, t, "ragged " + name)
+
+
+def test_query_len_longer_and_shorter_than_history(oracle):
+    """q = min(k, len_i): the first steps of a replay use 1- and 2-token queries; also
+    draft() with every query_len up to the maximum on a full history."""
+    w = synth.scaled(synth.WORKLOADS["C2"], max_len=300, query_len=8, draft_len=32)
+    tokens, probs = synth.make_paths(w)
+    dev = torch.device("cuda:0")
+    ix = binding.Index(1, w.n_paths, 300, w.vocab, 8, 32, 0.25, 0, 0, device=dev)
+    ix.append(torch.from_numpy(tokens).to(dev), torch.from_numpy(probs).to(dev), None, 300)
+    lens = np.full((1, w.n_paths), 300, dtype=np.int32)
+    for k in range(1, 9):
+        for L in (1, 7, 32):
+            out = ix.draft(k, L)
+            want = oracle.draft_all(tokens, probs, lens, k, L, 0.25, 0)
+            got = dict(draft=out["tokens"].cpu().numpy()[None], draft_len=out["length"].cpu().numpy()[None],
+                       token_scores=out["token_scores"].cpu().numpy()[None],
+                       path_scores=out["path_scores"].cpu().numpy()[None])
+            assert_step_equal(got, want, 0, "k=%d L=%d" % (k, L))
+
+
+def _one_shot(oracle, paths, probs, k, L, alpha=1.0, mode=0, flags=0):
+    """Appends whole (possibly ragged) paths in one call and compares one draft."""
+    N = len(paths)
+    T = max(len(p) for p in paths)
+    tok = np.zeros((1, N, T), dtype=np.int32)
+    pr = np.ones((1, N, T), dtype=np.float32) if probs is not None else None
+    cnt = np.zeros((1, N), dtype=np.int32)
+    for j, p in enumerate(paths):
+        tok[0, j, :len(p)] = p
+        cnt[0, j] = len(p)
+        if probs is not None:
+            pr[0, j, :len(p)] = probs[j]
+    dev = torch.device("cuda:0")
+    ix = binding.Index(1, N, T, int(tok.max()) + 1, max(k, 1), L, alpha, mode, flags, device=dev)
+    ix.append(torch.from_numpy(tok).to(dev), None if pr is None else torch.from_numpy(pr).to(dev),
+              torch.from_numpy(cnt).to(dev), T)
+    out = ix.draft(k, L)
+    want = oracle.draft_all(tok, pr, cnt, k, L, alpha, mode)
+    got = dict(draft=out["tokens"].cpu().numpy()[None], draft_len=out["length"].cpu().numpy()[None],
+               token_scores=out["token_scores"].cpu().numpy()[None],
+               path_scores=out["path_scores"].cpu().numpy()[None])
+    assert_step_equal(got, want, 0)
+    assert ix.status() == 0
+    return ix, tok, pr, cnt, want
+
+
+def test_degenerate_constant_paths_streaming_tier(oracle):
+    """All tokens equal: (N-1)(T-q) matches, far more than the on-chip match list holds."""
+    for N, T in ((4, 700), (16, 1024)):
+        ix, tok, pr, cnt, want = _one_shot(oracle, [[5] * T] * N, None, 3, 8)
+        assert (want["draft_len"] == 8).all()
+        assert want["token_scores"][0, 0, 0] == (N - 1) * (T - 3)
+        je, off = ix.dump_matches(3, cap=N * N * T)
+        assert off[-1] == N * (N - 1) * (T - 3)
+        assert np.array_equal(je[off[1]:off[2]], oracle.matches(tok[0], cnt[0], 1, 3))
+
+
+def test_many_distinct_edges_overflow_the_lds_table(oracle):
+    """A frequent query token followed by random continuations: thousands of distinct
+    DAG edges force the layer-by-layer tier, and (second case) its token classes."""
+    rng = np.random.default_rng(5)
+    for reps, n_paths in ((120, 5), (700, 5)):
+        paths, probs = [], []
+        for j in range(n_paths):
+            body = rng.integers(10, 4000, size=(reps, 6))
+            body[:, 0] = 7                                  # the query token recurs every 6 tokens
+            paths.append(body.reshape(-1).tolist())
+            probs.append((rng.integers(1, 9, size=reps * 6) / 8.0).tolist())
+        paths[0] = paths[0][:-5]                            # path 0 ends with the query token 7
+        probs[0] = probs[0][:-5]
+        for mode in (0, 1):
+            _one_shot(oracle, paths, probs, 1, 6, 0.5, mode)
+
+
+def test_empty_and_tiny_paths(oracle):
+    _one_shot(oracle, [[1, 2, 3], [], [3], [2, 3, 9, 2, 3]], None, 2, 4)
+    _one_shot(oracle, [[4], [4, 4], [9]], [[0.5], [0.25, 1.0], [1.0]], 3, 3)
+    # nothing appended at all: every draft is empty
+    dev = torch.device("cuda:0")
+    ix = binding.Index(2, 3, 16, 10, 2, 4, device=dev)
+    out = ix.draft(2, 4)
+    assert (out["length"].cpu().numpy() == 0).all() and (out["tokens"].cpu().numpy() == -1).all()
+    assert (out["token_scores"].cpu().numpy() == 0).all() and (out["path_scores"].cpu().numpy() == 0).all()
+
+
+def test_hand_worked_example_on_gpu(oracle):
+    import json, os
+    g = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "hand_worked_dag.json")))
+    for mode in (0, 1):
+        ix, tok, pr, cnt, want = _one_shot(oracle, g["paths"], None, g["k"], g["L"], 1.0, mode)
+        assert want["draft"][0, 0].tolist() == g["no_probs"]["mode%d" % mode]["draft"]
+    je, off = ix.dump_matches(g["k"])
+    assert je[off[0]:off[1]].tolist() == g["matches"]
+    duv, cs, eoff = ix.dump_edges(g["k"], g["L"])
+    assert [r + [int(c[0])] for r, c in zip(duv[eoff[0]:eoff[1]].tolist(), cs[eoff[0]:eoff[1]])] == g["edges_counts"]
+
+
+def test_status_bits_and_reset(oracle):
+    dev = torch.device("cuda:0")
+    ix = binding.Index(1, 2, 8, 100, 2, 4, device=dev)
+    t = torch.tensor([[[1, 2, 3, 4, 5, 6], [1, 2, 3, 4, 5, 6]]], dtype=torch.int32, device=dev)
+    ix.append(t, None, None, 6)
+    assert ix.status() == 0
+    with pytest.raises(binding.CsdError) as e:           # 6 + 6 > 8 and the host knows it
+        ix.append(t, None, None, 6)
+    assert e.value.code == binding.ERR_CAPACITY
+    cnt = torch.tensor([[1, 6]], dtype=torch.int32, device=dev)
+    ix.append(t, None, cnt, 6)                            # path 1 is clipped by the kernel
+    assert ix.status() == binding.STATUS_CAPACITY
+    ix.reset()
+    assert ix.status() == 0
+    bad = torch.tensor([[[100], [-1]]], dtype=torch.int32, device=dev)
+    ix.append(bad, None, None, 1)
+    assert ix.status() == binding.STATUS_TOKEN_RANGE
+    ix.reset()
+    # after reset the index behaves like a new one
+    ix.append(torch.tensor([[[7, 8, 9, 7], [7, 8, 9, 7]]], dtype=torch.int32, device=dev)[:, :, :4].contiguous(), None, None, 4)
+    out = ix.draft(1, 3)
+    assert out["tokens"].cpu().numpy()[0, 0].tolist() == [8, 9, 7]
+
+
+def test_determinism_two_runs_identical(oracle):
+    w = synth.WORKLOADS["C2"]
+    tokens, probs = synth.make_paths(w)
+    a = gpu_replay(tokens, probs, 3, 8, steps=400)
+    b = gpu_replay(tokens, probs, 3, 8, steps=400)
+    for key in ("draft", "draft_len", "token_scores", "path_scores"):
+        assert np.array_equal(a[key], b[key])
