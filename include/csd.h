@@ -63,6 +63,7 @@ typedef enum {
 #define CSD_MAX_DRAFT_LEN 32
 #define CSD_MAX_VOCAB ((1 << 29) - 1)
 #define CSD_MAX_POSITIONS (1 << 24) /* n_paths * max_len per problem */
+#define CSD_MAX_STEP_TOKENS 32767   /* csd_step: tokens per path per call */
 
 /* csd_config.flags: how matches are found (Eq. 3).  Both give identical results. */
 #define CSD_MATCH_AUTO 0   /* library picks                                         */
@@ -133,6 +134,33 @@ int csd_draft(csd_index* index, int32_t query_len, int32_t draft_len, int32_t* d
  *   d_accept_len [P][N]            int32  output. */
 int csd_accept(csd_index* index, const int32_t* d_draft_tokens, const int32_t* d_draft_len,
                const int32_t* d_targets, int32_t draft_len, int32_t* d_accept_len, void* stream);
+
+/* One decoding step in ONE launch: csd_append(d_tokens, d_probs, d_counts, n),
+ * then csd_draft(query_len, draft_len, ...) on the grown paths, then, if
+ * d_targets is given, csd_accept of the fresh drafts (Algorithm 1 run at step t
+ * of the generation, followed by the check of "Draft acceptance").  Results are
+ * identical to the three separate calls.  Arguments as in those calls;
+ * d_targets and d_accept_len are both NULL or both non-NULL; n in
+ * [1, CSD_MAX_STEP_TOKENS].  Consecutive calls on one index must be enqueued
+ * on the same stream (or be ordered by the caller). */
+int csd_step(csd_index* index, const int32_t* d_tokens, const float* d_probs,
+             const int32_t* d_counts, int32_t n, int32_t query_len, int32_t draft_len,
+             int32_t* d_draft_tokens, int32_t* d_draft_len, float* d_token_scores,
+             float* d_path_scores, const int32_t* d_targets, int32_t* d_accept_len, void* stream);
+
+/* n_steps consecutive decoding steps with one token per path and step, issued
+ * from a host loop inside the library (no device-side loop): step t appends
+ * d_tokens[t] (with d_probs[t], may be NULL), drafts into slice t of the
+ * outputs and, if d_targets is given, checks slice t of it.
+ *   d_tokens [n_steps][P][N], d_probs same; d_draft_tokens [n_steps][P][N][draft_len],
+ *   d_draft_len [n_steps][P][N], d_token_scores / d_path_scores likewise or NULL,
+ *   d_targets [n_steps][P][N][draft_len] and d_accept_len [n_steps][P][N] or both NULL.
+ * fused != 0: one csd_step launch per step; fused == 0: csd_append, csd_draft
+ * and csd_accept launches per step.  Both give identical results. */
+int csd_replay(csd_index* index, int32_t n_steps, const int32_t* d_tokens, const float* d_probs,
+               int32_t query_len, int32_t draft_len, int32_t* d_draft_tokens,
+               int32_t* d_draft_len, float* d_token_scores, float* d_path_scores,
+               const int32_t* d_targets, int32_t* d_accept_len, int32_t fused, void* stream);
 
 /* Waits for `stream` and copies the sticky CSD_STATUS_* bits to *host_flags. */
 int csd_status(csd_index* index, uint32_t* host_flags, void* stream);

@@ -19,8 +19,8 @@ STATUS_CAPACITY, STATUS_TOKEN_RANGE, STATUS_TABLE_FULL = 1, 2, 4
 OK, ERR_INVALID_ARG, ERR_CAPACITY, ERR_WORKSPACE, ERR_HIP, ERR_UNIMPLEMENTED = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ["csd_workspace_bytes", "csd_create", "csd_destroy", "csd_reset", "csd_append",
-           "csd_draft", "csd_accept", "csd_status", "csd_dump_matches", "csd_dump_edges",
-           "csd_strerror"]
+           "csd_draft", "csd_accept", "csd_step", "csd_replay", "csd_status", "csd_dump_matches",
+           "csd_dump_edges", "csd_strerror"]
 
 
 class Config(ctypes.Structure):
@@ -57,6 +57,8 @@ def load() -> ctypes.CDLL:
         lib.csd_append.argtypes = [_vp, _vp, _vp, _vp, i32, _vp]
         lib.csd_draft.argtypes = [_vp, i32, i32, _vp, _vp, _vp, _vp, _vp]
         lib.csd_accept.argtypes = [_vp, _vp, _vp, _vp, i32, _vp, _vp]
+        lib.csd_step.argtypes = [_vp, _vp, _vp, _vp, i32, i32, i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+        lib.csd_replay.argtypes = [_vp, i32, _vp, _vp, i32, i32, _vp, _vp, _vp, _vp, _vp, _vp, i32, _vp]
         lib.csd_status.argtypes = [_vp, ctypes.POINTER(ctypes.c_uint32), _vp]
         lib.csd_dump_matches.argtypes = [_vp, i32, _vp, _vp, i64, _vp]
         lib.csd_dump_edges.argtypes = [_vp, i32, i32, _vp, _vp, _vp, i64, _vp]
@@ -164,6 +166,54 @@ class Index:
                                       _ptr(draft_len_t, torch.int32, self.rows),
                                       _ptr(targets, torch.int32, self.rows * draft_len), draft_len,
                                       _ptr(out, torch.int32, self.rows), _stream()), "csd_accept")
+        return out
+
+    def _outputs(self, L, scores, lead=()):
+        P, N = self.P, self.N
+        mk = lambda shape, dt: torch.empty(tuple(lead) + shape, dtype=dt, device=self.device)
+        return dict(tokens=mk((P, N, L), torch.int32), length=mk((P, N), torch.int32),
+                    token_scores=mk((P, N, L), torch.float32) if scores else None,
+                    path_scores=mk((P, N), torch.float32) if scores else None)
+
+    def step(self, tokens, probs, counts, n, query_len, draft_len, out=None, targets=None,
+             accept_out=None, scores=True):
+        """One fused decode step (append + draft [+ accept]) in one launch."""
+        L = draft_len
+        if out is None:
+            out = self._outputs(L, scores)
+        if targets is not None and accept_out is None:
+            accept_out = torch.empty((self.P, self.N), dtype=torch.int32, device=self.device)
+        self._check(load().csd_step(self._h, _ptr(tokens, torch.int32, self.rows * n),
+                                    _ptr(probs, torch.float32, self.rows * n),
+                                    _ptr(counts, torch.int32, self.rows), n, query_len, L,
+                                    _ptr(out["tokens"], torch.int32, self.rows * L),
+                                    _ptr(out["length"], torch.int32, self.rows),
+                                    _ptr(out.get("token_scores"), torch.float32, self.rows * L),
+                                    _ptr(out.get("path_scores"), torch.float32, self.rows),
+                                    _ptr(targets, torch.int32, self.rows * L),
+                                    _ptr(accept_out, torch.int32, self.rows), _stream()), "csd_step")
+        out["accept"] = accept_out
+        return out
+
+    def replay(self, n_steps, tokens, probs, query_len, draft_len, out=None, targets=None,
+               accept_out=None, fused=True, scores=True):
+        """n_steps decode steps from a host loop inside the library.
+        tokens / probs [n_steps][P][N]; outputs get a leading n_steps axis."""
+        L, S = draft_len, n_steps
+        if out is None:
+            out = self._outputs(L, scores, lead=(S,))
+        if targets is not None and accept_out is None:
+            accept_out = torch.empty((S, self.P, self.N), dtype=torch.int32, device=self.device)
+        self._check(load().csd_replay(self._h, S, _ptr(tokens, torch.int32, S * self.rows),
+                                      _ptr(probs, torch.float32, S * self.rows), query_len, L,
+                                      _ptr(out["tokens"], torch.int32, S * self.rows * L),
+                                      _ptr(out["length"], torch.int32, S * self.rows),
+                                      _ptr(out.get("token_scores"), torch.float32, S * self.rows * L),
+                                      _ptr(out.get("path_scores"), torch.float32, S * self.rows),
+                                      _ptr(targets, torch.int32, S * self.rows * L),
+                                      _ptr(accept_out, torch.int32, S * self.rows),
+                                      1 if fused else 0, _stream()), "csd_replay")
+        out["accept"] = accept_out
         return out
 
     def status(self) -> int:

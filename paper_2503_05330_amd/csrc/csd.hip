@@ -7,11 +7,17 @@
 // acceptance check ("Draft acceptance").
 //
 // Nothing here is a dense contraction, so there is no MFMA: the work is
-// integer compares, LDS hash-histogram atomics and wavefront reductions.
+// integer compares, hash lookups, LDS hash-histogram atomics and wavefront
+// reductions.  The step is latency-bound (a chain of a few dependent memory
+// round trips per path), so the design minimises round trips and barriers:
+//   * one launch per decode step (append + draft + accept fused),
+//   * one wave64 per (problem, path): no workgroup barriers on the hot path,
+//   * matches come from an incrementally updated n-gram hash index,
+//   * DAG tables live in LDS, argmax reductions use DPP lane moves.
 //
 // Exactness: every weight is an integer (probabilities are quantised to
-// 1/65536 at append), so LDS atomics may accumulate in any order and the
-// result is still unique.
+// 1/65536 at append), so atomics may accumulate in any order and the result is
+// still unique.
 #include <hip/hip_runtime.h>
 
 #include <climits>
@@ -26,14 +32,16 @@ namespace {
 
 typedef unsigned long long u64;
 
-constexpr int kBlock = 256;                 // threads per (problem, path) workgroup
-constexpr int kWaves = kBlock / 64;         // wave64
+constexpr int kWave = 64;
+constexpr int kScanBlock = 256;             // threads per row when matches come from a scan
 constexpr int kMatchCap = 1024;             // matches kept in LDS; beyond -> streaming tier
 constexpr int kTableCap = 2048;             // LDS hash slots for DAG edges + nodes
 constexpr uint32_t kTokMask = (1u << 29) - 1;
 constexpr uint32_t kAnyTok = kTokMask;      // "any predecessor": marks node (in-weight) entries
 constexpr u64 kEmpty = ~0ull;
 constexpr int kMaxClassBits = 20;           // streaming tier: at most 2^20 token classes
+constexpr int kBucketWords = 16;            // one 64-byte line: [count, 15 postings]
+constexpr int kBucketSlots = kBucketWords - 1;
 
 // ---------------------------------------------------------------- small helpers
 
@@ -70,6 +78,8 @@ __device__ __forceinline__ uint32_t quantize_prob(float p) {
   return (uint32_t)x;
 }
 
+// ---------------------------------------------------------------- argmax reductions
+
 struct Cand {      // a successor proposed for the greedy step
   u64 key;         // its weight * 2^32
   int32_t v;       // its token id; INT_MAX = none
@@ -80,120 +90,383 @@ __device__ __forceinline__ Cand cand_best(Cand a, Cand b) {
   bool take_b = (b.key > a.key) || (b.key == a.key && b.v < a.v);
   return take_b ? b : a;
 }
-__device__ __forceinline__ Cand wave_argmax(Cand c) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    Cand x;
-    x.key = __shfl_xor(c.key, o);
-    x.v = __shfl_xor(c.v, o);
-    c = cand_best(c, x);
-  }
-  return c;
+
+// One DPP step: every lane combines its candidate with the one the lane-move
+// pattern CTRL delivers; lanes the pattern does not reach combine with "none".
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ Cand dpp_step(Cand c) {
+  const Cand none = cand_none();
+  Cand x;
+  uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp((int)(uint32_t)none.key, (int)(uint32_t)c.key,
+                                                      CTRL, ROW_MASK, 0xF, false);
+  uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp((int)(uint32_t)(none.key >> 32),
+                                                      (int)(uint32_t)(c.key >> 32), CTRL, ROW_MASK,
+                                                      0xF, false);
+  x.key = ((u64)hi << 32) | lo;
+  x.v = __builtin_amdgcn_update_dpp(none.v, c.v, CTRL, ROW_MASK, 0xF, false);
+  return cand_best(c, x);
 }
 
-// ---------------------------------------------------------------- per-workgroup state
+// Argmax over the 64 lanes of a wave; every lane gets the result.  Four
+// row_shr steps scan each row of 16 lanes, row_bcast:15 and row_bcast:31 carry
+// the row results up, lane 63 ends with the total.
+__device__ __forceinline__ Cand wave_argmax(Cand c) {
+  c = dpp_step<0x111, 0xF>(c);   // row_shr:1
+  c = dpp_step<0x112, 0xF>(c);   // row_shr:2
+  c = dpp_step<0x114, 0xF>(c);   // row_shr:4
+  c = dpp_step<0x118, 0xF>(c);   // row_shr:8
+  c = dpp_step<0x142, 0xA>(c);   // row_bcast:15 into rows 1 and 3
+  c = dpp_step<0x143, 0xC>(c);   // row_bcast:31 into rows 2 and 3
+  Cand r;
+  uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)c.key, 63);
+  uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(c.key >> 32), 63);
+  r.key = ((u64)hi << 32) | lo;
+  r.v = __builtin_amdgcn_readlane(c.v, 63);
+  return r;
+}
 
-struct Lds {
-  u64 keys[kTableCap];
-  u64 vals[kTableCap];
-  int32_t match[kMatchCap];   // matches as offsets j*max_len + e into the problem's history
-  Cand red[2][kWaves];
-  int n_match;                // total matches found (may exceed kMatchCap)
-  int n_keys;                 // distinct keys in the table
-  int overflow;               // table ran out of room
+// ---------------------------------------------------------------- device state
+
+struct IndexView {              // device state inside the caller's workspace
+  int32_t* tok;                 // [P][N][max_len] token histories
+  uint32_t* pq;                 // [P][N][max_len] quantised generation probabilities
+  const int32_t* len_old;       // [P][N] lengths before this launch
+  int32_t* len_new;             // [P][N] lengths after it (== len_old when nothing is appended)
+  uint32_t* status;             // sticky CSD_STATUS_* bits
+  int32_t* gram;                // n-gram index [P][kmax][n_buckets][16], or null (scan mode)
+  uint32_t bucket_mask;         // n_buckets - 1 (power of two)
+  int32_t P, N, max_len, vocab, kmax;
 };
 
-struct Ctx {                  // one (problem, query path)
-  const int32_t* tok;         // [N][max_len] of this problem
-  const uint32_t* pq;         // same shape, quantised probabilities
-  const int32_t* len;         // [N]
-  int32_t N, max_len;
-  int32_t i;                  // query path
-  int32_t q;                  // effective query length min(k, len_i)
-  int32_t Q[CSD_MAX_QUERY_LEN];   // Q[a] = a-th token from the end of path i
+struct StepIn {                 // tokens a step appends; n == 0: none
+  const int32_t* tok;           // [P][N][n]
+  const float* prob;            // [P][N][n] or null
+  const int32_t* counts;        // [P][N] or null
+  int32_t n;
+};
+
+// One problem's paths as they are AFTER this step's append, readable while the
+// append is still in flight: positions below the old length come from the
+// history, newer ones straight from the step's input.  No workgroup ever reads
+// history cells that another workgroup of the same launch writes.
+struct Paths {
+  const int32_t* tok;
+  const uint32_t* pq;
+  const int32_t* len_old;
+  const int32_t* st;
+  const float* sp;
+  const int32_t* sc;
+  int32_t n, N, max_len;
+
+  __device__ __forceinline__ int32_t old_len(int32_t j) const { return len_old[j]; }
+  __device__ __forceinline__ int32_t new_len(int32_t j, int32_t old_j) const {
+    if (n == 0) return old_j;
+    int32_t c = sc ? sc[j] : n;
+    c = c < 0 ? 0 : (c > n ? n : c);
+    int32_t room = max_len - old_j;
+    return old_j + (c < room ? c : room);
+  }
+  __device__ __forceinline__ int32_t token(int32_t j, int32_t t, int32_t old_j) const {
+    return t < old_j ? tok[(int64_t)j * max_len + t] : st[(int64_t)j * n + (t - old_j)];
+  }
+  __device__ __forceinline__ uint32_t prob(int32_t j, int32_t t, int32_t old_j) const {
+    if (t < old_j) return pq[(int64_t)j * max_len + t];
+    return sp ? quantize_prob(sp[(int64_t)j * n + (t - old_j)]) : 65536u;
+  }
+};
+
+struct Match {                  // one element of the candidate pool (Eq. 3)
+  int32_t off;                  // j * max_len + e: first continuation token
+  int16_t rem_new;              // new_len_j - e: continuation tokens that exist, clipped to 63
+  int16_t rel_old;              // old_len_j - e, clipped to [-32767, 63]; < 0: e itself is new
+};
+
+struct Slot {
+  u64 key;
+  u64 val;
+};
+
+struct Lds {
+  Slot table[kTableCap];
+  Match match[kMatchCap];
+  Cand red[2][kScanBlock / kWave];
+  int n_match;                  // total matches found (may exceed kMatchCap)
+  int n_keys;                   // distinct keys in the table
+  int overflow;                 // table ran out of room
+};
+
+struct Ctx {                    // one (problem, query path)
+  Paths y;
+  const int32_t* gram;          // this problem's index tables, or null
+  uint32_t bucket_mask;
+  int32_t kmax;
+  int32_t i;                    // query path
+  int32_t len_i;                // its length after the append
+  int32_t q;                    // effective query length min(k, len_i)
+  int32_t Q[CSD_MAX_QUERY_LEN]; // Q[a] = a-th token from the end of path i
   int tid;
 };
 
-__device__ __forceinline__ void load_query(Ctx& c, int32_t k) {
-  int32_t len_i = c.len[c.i];
-  c.q = k < len_i ? k : len_i;
-  const int32_t* row = c.tok + (int64_t)c.i * c.max_len;
-#pragma unroll
-  for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) c.Q[a] = (a < c.q) ? row[len_i - 1 - a] : 0;
+// ---------------------------------------------------------------- n-gram hash index
+//
+// For every gram length g = 1..kmax one table of 64-byte buckets.  A posting
+// (j, e) — "the g tokens before index e of path j" — is stored under the hash of
+// those g tokens when token e is appended, so a query finds its matches (Eq. 3)
+// without touching the histories.  Bucket r of a gram's probe sequence is
+// (h + r * step) mod n_buckets with an odd step; an insert goes into the first
+// bucket of the sequence that is not full, so a lookup may stop at the first
+// bucket that is not full.  Hash collisions are harmless: every posting is
+// verified against the history before it counts.
+
+struct GramHash {
+  uint32_t h, step;
+};
+__device__ __forceinline__ GramHash gram_hash_begin(int g) { return GramHash{0x9E3779B9u * (uint32_t)g, 0u}; }
+__device__ __forceinline__ void gram_hash_add(u64& acc, int32_t token) {
+  acc = (acc ^ (u64)(uint32_t)token) * 0xD6E8FEB86659FD93ull;
+  acc ^= acc >> 32;
+}
+__device__ __forceinline__ GramHash gram_hash_end(u64 acc) {
+  uint32_t a = mix_u64(acc);
+  uint32_t b = mix_u64(acc ^ 0xA5A5A5A5A5A5A5A5ull);
+  return GramHash{a, (b << 1) | 1u};
+}
+__device__ __forceinline__ const int32_t* gram_table(const int32_t* gram, int g, uint32_t mask) {
+  return gram + (int64_t)(g - 1) * ((int64_t)mask + 1) * kBucketWords;
 }
 
-// Does the q-gram that ends just before index e of `row` equal the query?
-__device__ __forceinline__ bool gram_equals_query(const Ctx& c, const int32_t* row, int32_t e) {
-  bool hit = row[e - 1] == c.Q[0];
+// Inserts posting `off` under hash gh of gram length g.  Bounded: at most
+// n_buckets attempts, and the tables hold more slots than there are positions.
+__device__ __forceinline__ void gram_insert(int32_t* gram, uint32_t mask, int g, GramHash gh,
+                                            int32_t off) {
+  int32_t* tbl = const_cast<int32_t*>(gram_table(gram, g, mask));
+  for (uint32_t r = 0; r <= mask; ++r) {
+    int32_t* b = tbl + (int64_t)((gh.h + r * gh.step) & mask) * kBucketWords;
+    int32_t c = atomicAdd(b, 1);
+    if (c < kBucketSlots) {
+      b[1 + c] = off;
+      return;
+    }
+  }
+}
+
+// Stores this row's share of the step (tokens, quantised probabilities, index
+// postings, new length).  Called by all threads of the row's workgroup.
+template <int BLOCK>
+__device__ __forceinline__ void append_row(const IndexView& ix, const Paths& y, int32_t p,
+                                           int32_t i, int32_t old_i, int32_t new_i, int tid) {
+  int64_t row = (int64_t)p * ix.N + i;
+  int32_t cnt = new_i - old_i;
+  uint32_t flags = 0;
+  if (tid == 0) {
+    ix.len_new[row] = new_i;
+    int32_t want = y.sc ? y.sc[i] : y.n;
+    want = want < 0 ? 0 : (want > y.n ? y.n : want);
+    if (want > cnt) flags |= CSD_STATUS_CAPACITY;
+  }
+  for (int32_t t = tid; t < cnt; t += BLOCK) {
+    int32_t v = y.st[(int64_t)i * y.n + t];
+    if (v < 0 || v >= ix.vocab) flags |= CSD_STATUS_TOKEN_RANGE;
+    ix.tok[row * ix.max_len + old_i + t] = v;
+    ix.pq[row * ix.max_len + old_i + t] = y.sp ? quantize_prob(y.sp[(int64_t)i * y.n + t]) : 65536u;
+  }
+  if (ix.gram) {
+    int32_t* gram = ix.gram + (int64_t)p * ix.kmax * ((int64_t)ix.bucket_mask + 1) * kBucketWords;
+    for (int32_t it = tid; it < cnt * ix.kmax; it += BLOCK) {
+      int32_t t = it / ix.kmax;
+      int32_t g = it - t * ix.kmax + 1;
+      int32_t e = old_i + t;                        // the new token is the successor
+      if (e < g) continue;                          // fewer than g tokens before it
+      u64 acc = gram_hash_begin(g).h;
+      for (int32_t a = g; a >= 1; --a) gram_hash_add(acc, y.token(i, e - a, old_i));
+      gram_insert(gram, ix.bucket_mask, g, gram_hash_end(acc), i * ix.max_len + e);
+    }
+  }
+  if (flags) atomicOr(ix.status, flags);
+}
+
+// ---------------------------------------------------------------- matching (Eq. 3)
+
+__device__ __forceinline__ void load_query(Ctx& c, int32_t k, int32_t old_i) {
+  c.q = k < c.len_i ? k : c.len_i;
 #pragma unroll
-  for (int a = 1; a < CSD_MAX_QUERY_LEN; ++a)
-    if (a < c.q && hit) hit = row[e - 1 - a] == c.Q[a];
+  for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a)
+    c.Q[a] = (a < c.q) ? c.y.token(c.i, c.len_i - 1 - a, old_i) : 0;
+}
+
+// Does the q-gram that ends just before index e of path j equal the query?
+// All q tokens are fetched at once (one memory round trip, not q).
+__device__ __forceinline__ bool gram_equals_query(const Ctx& c, int32_t j, int32_t e,
+                                                  int32_t old_j) {
+  int32_t t[CSD_MAX_QUERY_LEN];
+#pragma unroll
+  for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) t[a] = (a < c.q) ? c.y.token(j, e - 1 - a, old_j) : 0;
+  bool hit = true;
+#pragma unroll
+  for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) hit = hit && (a >= c.q || t[a] == c.Q[a]);
   return hit;
 }
 
-// ---------------------------------------------------------------- match sinks
+__device__ __forceinline__ Match make_match(const Ctx& c, int32_t j, int32_t e, int32_t old_j,
+                                            int32_t new_j) {
+  int32_t rn = new_j - e, ro = old_j - e;
+  Match m;
+  m.off = j * c.y.max_len + e;
+  m.rem_new = (int16_t)(rn > 63 ? 63 : rn);
+  m.rel_old = (int16_t)(ro < -32767 ? -32767 : (ro > 63 ? 63 : ro));
+  return m;
+}
 
 // Compacts hits into the LDS match list with one LDS atomic per wave.
 // push() must be reached by all 64 lanes of a wave together.
 struct ListSink {
   Lds* s;
-  __device__ __forceinline__ void push(bool hit, int32_t off) {
+  __device__ __forceinline__ void push(bool hit, Match m) {
     u64 mask = __ballot(hit);
     if (mask == 0) return;
     int lane = __lane_id();
     int base = 0;
     if (lane == 0) base = atomicAdd(&s->n_match, (int)__popcll(mask));
-    base = __shfl(base, 0);
+    base = __builtin_amdgcn_readfirstlane(base);
     int slot = base + (int)__popcll(mask & ((1ull << lane) - 1ull));
-    if (hit && slot < kMatchCap) s->match[slot] = off;
+    if (hit && slot < kMatchCap) s->match[slot] = m;
   }
 };
 
 // Marks hits in a bitmap over all positions of the problem (debug dump).
 struct BitmapSink {
   uint32_t* bits;
-  __device__ __forceinline__ void push(bool hit, int32_t off) {
-    if (hit) atomicOr(&bits[off >> 5], 1u << (off & 31));
+  __device__ __forceinline__ void push(bool hit, Match m) {
+    if (hit) atomicOr(&bits[m.off >> 5], 1u << (m.off & 31));
+  }
+};
+
+// Hands every hit to a callable (streaming tier).
+template <class F>
+struct FnSink {
+  F f;
+  __device__ __forceinline__ void push(bool hit, Match m) {
+    if (hit) f(m);
   }
 };
 
 // Eq. 3 by exhaustive comparison: every position e of every other path j with
-// q <= e <= len_j - 1 is tested.  Loop bounds are uniform over the workgroup.
-template <class Sink>
+// q <= e <= len_j - 1 is tested.  Trip counts are uniform over the workgroup;
+// four tiles are in flight at a time.
+template <int BLOCK, class Sink>
 __device__ __forceinline__ void match_scan(const Ctx& c, Sink& sink) {
-  for (int32_t j = 0; j < c.N; ++j) {
-    if (j == c.i) continue;
-    int32_t len_j = c.len[j];
-    const int32_t* row = c.tok + (int64_t)j * c.max_len;
-    for (int32_t e0 = c.q; e0 < len_j; e0 += kBlock) {
-      int32_t e = e0 + c.tid;
-      bool hit = (e < len_j) && gram_equals_query(c, row, e);
-      sink.push(hit, j * c.max_len + e);
+  constexpr int kUnroll = 4;
+  int32_t tiles_per_path = (c.y.max_len + BLOCK - 1) / BLOCK;
+  int32_t tiles = c.y.N * tiles_per_path;
+  for (int32_t g0 = 0; g0 < tiles; g0 += kUnroll) {
+    bool hit[kUnroll];
+    Match m[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      int32_t g = g0 + u;
+      int32_t j = g / tiles_per_path;
+      int32_t e = c.q + (g - j * tiles_per_path) * BLOCK + c.tid;
+      hit[u] = false;
+      m[u] = Match{0, 0, 0};
+      if (g < tiles && j != c.i) {
+        int32_t old_j = c.y.old_len(j);
+        int32_t new_j = c.y.new_len(j, old_j);
+        if (e < new_j) {
+          hit[u] = gram_equals_query(c, j, e, old_j);
+          m[u] = make_match(c, j, e, old_j, new_j);
+        }
+      }
     }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) sink.push(hit[u], m[u]);
+  }
+}
+
+// Eq. 3 through the hash index, by ONE wave.  Postings of earlier steps come
+// from the gram's bucket sequence; positions this very launch appends are not
+// looked up (their inserts may be in flight) but tested directly.
+template <class Sink>
+__device__ __forceinline__ void match_index(const Ctx& c, Sink& sink) {
+  const int lane = c.tid & 63;
+  // (a) positions appended by this launch: e in [max(old_j, q), new_j)
+  if (c.y.n > 0) {
+    for (int32_t j0 = 0; j0 < c.y.N; j0 += kWave) {
+      int32_t j = j0 + lane;
+      bool live = j < c.y.N && j != c.i;
+      int32_t old_j = live ? c.y.old_len(j) : 0;
+      int32_t new_j = live ? c.y.new_len(j, old_j) : 0;
+      for (int32_t t = 0; t < c.y.n; ++t) {
+        int32_t e = old_j + t;
+        bool hit = live && e < new_j && e >= c.q && gram_equals_query(c, j, e, old_j);
+        sink.push(hit, make_match(c, j, e, old_j, new_j));
+      }
+    }
+  }
+  // (b) postings of earlier launches
+  u64 acc = gram_hash_begin(c.q).h;
+#pragma unroll
+  for (int a = CSD_MAX_QUERY_LEN - 1; a >= 0; --a)
+    if (a < c.q) gram_hash_add(acc, c.Q[a]);
+  GramHash gh = gram_hash_end(acc);
+  const int32_t* tbl = gram_table(c.gram, c.q, c.bucket_mask);
+  const int sub = lane & 15;          // word of the bucket this lane reads
+  const int grp = lane >> 4;          // which of the 4 buckets of a batch
+  uint32_t n_buckets = c.bucket_mask + 1;
+  int per_round = 1;                  // batches of 4 buckets in flight per round trip
+  for (uint32_t r0 = 0; r0 < n_buckets; r0 += 4u * per_round, per_round = 4) {
+    bool seq_ends = false;
+    for (int u = 0; u < per_round; ++u) {   // independent loads: one round trip
+      uint32_t r = r0 + 4u * u + grp;
+      int32_t word = -1;
+      if (r < n_buckets)
+        word = tbl[(int64_t)((gh.h + r * gh.step) & c.bucket_mask) * kBucketWords + sub];
+      int32_t count = __shfl(word, lane & ~15);
+      bool full = count >= kBucketSlots;
+      bool cand = sub >= 1 && word >= 0 && (sub - 1) < (full ? kBucketSlots : count);
+      int32_t j = 0, e = 0, old_j = 0, new_j = 0;
+      bool hit = false;
+      if (cand) {
+        j = word / c.y.max_len;
+        e = word - j * c.y.max_len;
+        if (j != c.i && j < c.y.N) {
+          old_j = c.y.old_len(j);
+          if (e < old_j) {               // postings at or beyond old_j belong to case (a)
+            new_j = c.y.new_len(j, old_j);
+            hit = gram_equals_query(c, j, e, old_j);
+          }
+        }
+      }
+      sink.push(hit, make_match(c, j, e, old_j, new_j));
+      if (__ballot(!full || r >= n_buckets) != 0) seq_ends = true;
+    }
+    if (seq_ends) break;
   }
 }
 
 // ---------------------------------------------------------------- LDS hash table
 
+template <int BLOCK>
+__device__ __forceinline__ void block_sync() {
+  __syncthreads();   // a one-wave workgroup needs no hardware barrier: the compiler drops it
+}
+
+template <int BLOCK>
 __device__ __forceinline__ void table_clear(Lds& s, uint32_t mask, int tid) {
-  for (uint32_t h = tid; h <= mask; h += kBlock) {
-    s.keys[h] = kEmpty;
-    s.vals[h] = 0ull;
-  }
+  for (uint32_t h = tid; h <= mask; h += BLOCK) s.table[h] = Slot{kEmpty, 0ull};
   if (tid == 0) {
     s.n_keys = 0;
     s.overflow = 0;
   }
 }
 
-// vals[key] += delta, inserting the key if new.  Sets s.overflow when the
+// table[key] += delta, inserting the key if new.  Sets s.overflow when the
 // table is more than 3/4 full (the caller then falls back) — never spins.
 __device__ __forceinline__ void table_add(Lds& s, uint32_t mask, u64 key, u64 delta) {
   uint32_t h = mix_u64(key) & mask;
   for (uint32_t probe = 0; probe <= mask; ++probe) {
-    u64 cur = s.keys[h];
+    u64 cur = s.table[h].key;
     if (cur == kEmpty) {
-      cur = atomicCAS(&s.keys[h], kEmpty, key);
+      cur = atomicCAS(&s.table[h].key, kEmpty, key);
       if (cur == kEmpty) {
         int n = atomicAdd(&s.n_keys, 1) + 1;
         if ((uint32_t)n > (mask + 1) - ((mask + 1) >> 2)) s.overflow = 1;
@@ -201,7 +474,7 @@ __device__ __forceinline__ void table_add(Lds& s, uint32_t mask, u64 key, u64 de
       }
     }
     if (cur == key) {
-      atomicAdd(&s.vals[h], delta);
+      atomicAdd(&s.table[h].val, delta);
       return;
     }
     h = (h + 1) & mask;
@@ -212,35 +485,38 @@ __device__ __forceinline__ void table_add(Lds& s, uint32_t mask, u64 key, u64 de
 __device__ __forceinline__ u64 table_get(const Lds& s, uint32_t mask, u64 key) {
   uint32_t h = mix_u64(key) & mask;
   for (uint32_t probe = 0; probe <= mask; ++probe) {
-    u64 cur = s.keys[h];
-    if (cur == key) return s.vals[h];
-    if (cur == kEmpty) return 0ull;
+    Slot x = s.table[h];
+    if (x.key == key) return x.val;
+    if (x.key == kEmpty) return 0ull;
     h = (h + 1) & mask;
   }
   return 0ull;
 }
 
 // Workgroup-wide argmax of the per-thread candidates; every thread gets the result.
+template <int BLOCK>
 __device__ __forceinline__ Cand block_argmax(Lds& s, Cand c, int tid, int parity) {
   c = wave_argmax(c);
+  if (BLOCK == kWave) return c;
   if ((tid & 63) == 0) s.red[parity][tid >> 6] = c;
   __syncthreads();
   Cand r = s.red[parity][0];
 #pragma unroll
-  for (int w = 1; w < kWaves; ++w) r = cand_best(r, s.red[parity][w]);
+  for (int w = 1; w < BLOCK / kWave; ++w) r = cand_best(r, s.red[parity][w]);
   return r;
 }
 
 // Successors of `cur` in layer d as held by the table, best one per thread.
+template <int BLOCK>
 __device__ __forceinline__ Cand scan_successors(const Lds& s, uint32_t mask, int d, int32_t cur,
                                                 uint32_t alpha_q, int score_mode, int tid,
                                                 Cand best) {
   u64 want = dag_key(d, (uint32_t)cur, 0) >> 29;
-  for (uint32_t h = tid; h <= mask; h += kBlock) {
-    u64 key = s.keys[h];
-    if ((key >> 29) != want) continue;
-    uint32_t v = (uint32_t)(key & kTokMask);
-    u64 w = score_mode ? s.vals[h] : table_get(s, mask, dag_key(d, kAnyTok, v));
+  for (uint32_t h = tid; h <= mask; h += BLOCK) {
+    Slot x = s.table[h];
+    if ((x.key >> 29) != want) continue;
+    uint32_t v = (uint32_t)(x.key & kTokMask);
+    u64 w = score_mode ? x.val : table_get(s, mask, dag_key(d, kAnyTok, v));
     best = cand_best(best, Cand{weight_key(w, alpha_q), (int32_t)v});
   }
   return best;
@@ -253,42 +529,56 @@ struct DraftOut {               // what one thread contributes to the outputs
   int32_t n = 0;
 };
 
+// The (u, v, p) instance that match m contributes to layer d, if it reaches it.
+__device__ __forceinline__ bool layer_instance(const Ctx& c, Match m, int32_t d, uint32_t& u,
+                                               uint32_t& v, u64& w) {
+  if (d > (int32_t)m.rem_new) return false;        // the candidate has ended
+  int32_t j = m.off / c.y.max_len;
+  int32_t e = m.off - j * c.y.max_len;
+  // rel_old is exact unless clipped at 63 (a step appends at most 32767 tokens), and
+  // d <= 32 < 63: every index read below is then on the history side either way
+  int32_t old_j = e + (int32_t)m.rel_old;
+  u = (uint32_t)c.y.token(j, e + d - 2, old_j);
+  v = (uint32_t)c.y.token(j, e + d - 1, old_j);
+  w = pack_cs(1u, c.y.prob(j, e + d - 1, old_j));
+  return true;
+}
+
 // ---------------------------------------------------------------- tier 1: everything in LDS
 
 // Eq. 5: every (match, layer) instance adds (1, p) to its edge (d,u,v) and to
 // its node (d,*,v).  Returns the table mask used.
+template <int BLOCK>
 __device__ __forceinline__ uint32_t build_dag(Lds& s, const Ctx& c, int32_t M, int32_t L) {
   uint32_t want = 4u * (uint32_t)M * (uint32_t)L;     // <= 50 % load without any merging
   uint32_t size = 64;
   while (size < want && size < (uint32_t)kTableCap) size <<= 1;
   uint32_t mask = size - 1;
-  table_clear(s, mask, c.tid);
-  __syncthreads();
+  table_clear<BLOCK>(s, mask, c.tid);
+  block_sync<BLOCK>();
   int32_t items = M * L;
-  for (int32_t idx = c.tid; idx < items; idx += kBlock) {
+  for (int32_t idx = c.tid; idx < items; idx += BLOCK) {
     int32_t d = idx / M + 1;
-    int32_t off = s.match[idx - (d - 1) * M];
-    int32_t j = off / c.max_len;
-    int32_t t = off - j * c.max_len + d - 1;         // index of the layer-d token in path j
-    if (t < c.len[j] && !s.overflow) {
-      uint32_t u = (uint32_t)c.tok[off + d - 2];
-      uint32_t v = (uint32_t)c.tok[off + d - 1];
-      u64 w = pack_cs(1u, c.pq[off + d - 1]);
+    Match m = s.match[idx - (d - 1) * M];
+    uint32_t u, v;
+    u64 w;
+    if (layer_instance(c, m, d, u, v, w) && !s.overflow) {
       table_add(s, mask, dag_key(d, u, v), w);
       table_add(s, mask, dag_key(d, kAnyTok, v), w);
     }
   }
-  __syncthreads();
+  block_sync<BLOCK>();
   return mask;
 }
 
 // Greedy walk over the finished tables (rule after Eq. 5).
+template <int BLOCK>
 __device__ __forceinline__ void walk_dag(Lds& s, const Ctx& c, uint32_t mask, int32_t L,
                                          uint32_t alpha_q, int score_mode, DraftOut& o) {
   int32_t cur = c.Q[0];
   for (int32_t d = 1; d <= L; ++d) {
-    Cand best = scan_successors(s, mask, d, cur, alpha_q, score_mode, c.tid, cand_none());
-    best = block_argmax(s, best, c.tid, d & 1);
+    Cand best = scan_successors<BLOCK>(s, mask, d, cur, alpha_q, score_mode, c.tid, cand_none());
+    best = block_argmax<BLOCK>(s, best, c.tid, d & 1);
     if (best.v == INT_MAX) break;                     // leaf: no edge leaves cur
     if (c.tid == d - 1) { o.tok = best.v; o.key = best.key; }
     o.key_sum += best.key;
@@ -299,30 +589,28 @@ __device__ __forceinline__ void walk_dag(Lds& s, const Ctx& c, uint32_t mask, in
 
 // ---------------------------------------------------------------- tier 2: streaming, layer by layer
 
-// Calls f(off, j, e) for every match.  Uses the LDS list when it holds all of
-// them, else compares every position again.
-template <class F>
+template <int BLOCK, bool INDEXED, class Sink>
+__device__ __forceinline__ void find_matches(const Ctx& c, Sink& sink) {
+  if (INDEXED) match_index(c, sink);
+  else match_scan<BLOCK>(c, sink);
+}
+
+// Calls f(match) for every match.  Uses the LDS list when it holds all of
+// them, else runs the matcher again.
+template <int BLOCK, bool INDEXED, class F>
 __device__ __forceinline__ void for_each_match(const Lds& s, const Ctx& c, int32_t M, F f) {
   if (M <= kMatchCap) {
-    for (int32_t m = c.tid; m < M; m += kBlock) {
-      int32_t off = s.match[m];
-      int32_t j = off / c.max_len;
-      f(off, j, off - j * c.max_len);
-    }
+    for (int32_t m = c.tid; m < M; m += BLOCK) f(s.match[m]);
   } else {
-    for (int32_t j = 0; j < c.N; ++j) {
-      if (j == c.i) continue;
-      int32_t len_j = c.len[j];
-      const int32_t* row = c.tok + (int64_t)j * c.max_len;
-      for (int32_t e = c.q + c.tid; e < len_j; e += kBlock)
-        if (gram_equals_query(c, row, e)) f(j * c.max_len + e, j, e);
-    }
+    FnSink<F> sink{f};
+    find_matches<BLOCK, INDEXED>(c, sink);
   }
 }
 
 // Same result as build_dag + walk_dag with bounded memory for any input: one
 // layer at a time, and within a layer one class of tokens (by hash residue)
 // at a time, doubling the number of classes whenever a class overflows LDS.
+template <int BLOCK, bool INDEXED>
 __device__ __forceinline__ void walk_streaming(Lds& s, const Ctx& c, int32_t M, int32_t L,
                                                uint32_t alpha_q, int score_mode,
                                                uint32_t* status, DraftOut& o) {
@@ -338,31 +626,29 @@ __device__ __forceinline__ void walk_streaming(Lds& s, const Ctx& c, int32_t M, 
       best = cand_none();
       uint32_t n_class = 1u << class_bits;
       for (uint32_t r = 0; r < n_class && !failed; ++r) {
-        __syncthreads();                               // previous readers are done
-        table_clear(s, mask, c.tid);
-        __syncthreads();
-        for_each_match(s, c, M, [&](int32_t off, int32_t j, int32_t e) {
-          int32_t t = e + d - 1;
-          if (t >= c.len[j] || s.overflow) return;
-          uint32_t v = (uint32_t)c.tok[off + d - 1];
+        block_sync<BLOCK>();                           // previous readers are done
+        table_clear<BLOCK>(s, mask, c.tid);
+        block_sync<BLOCK>();
+        for_each_match<BLOCK, INDEXED>(s, c, M, [&](Match m) {
+          uint32_t u, v;
+          u64 w;
+          if (s.overflow || !layer_instance(c, m, d, u, v, w)) return;
           if ((mix_u64(v) & (n_class - 1)) != r) return;
-          uint32_t u = (uint32_t)c.tok[off + d - 2];
-          u64 w = pack_cs(1u, c.pq[off + d - 1]);
           table_add(s, mask, dag_key(d, kAnyTok, v), w);
           if (u == (uint32_t)cur) table_add(s, mask, dag_key(d, u, v), w);
         });
-        __syncthreads();
+        block_sync<BLOCK>();
         if (s.overflow) failed = true;                 // uniform: read after the barrier
-        else best = scan_successors(s, mask, d, cur, alpha_q, score_mode, c.tid, best);
+        else best = scan_successors<BLOCK>(s, mask, d, cur, alpha_q, score_mode, c.tid, best);
       }
       if (failed) ++class_bits;
     } while (failed && class_bits <= kMaxClassBits);
-    if (failed) {                                      // cannot happen for vocab < 2^29 in practice
+    if (failed) {                                      // 2^20 classes did not suffice
       if (c.tid == 0) atomicOr(status, CSD_STATUS_TABLE_FULL);
       break;
     }
     parity ^= 1;
-    best = block_argmax(s, best, c.tid, parity);
+    best = block_argmax<BLOCK>(s, best, c.tid, parity);
     if (best.v == INT_MAX) break;
     if (c.tid == d - 1) { o.tok = best.v; o.key = best.key; }
     o.key_sum += best.key;
@@ -372,14 +658,6 @@ __device__ __forceinline__ void walk_streaming(Lds& s, const Ctx& c, int32_t M, 
 }
 
 // ---------------------------------------------------------------- kernels
-
-struct IndexView {              // device state inside the caller's workspace
-  int32_t* tok;                 // [P][N][max_len]
-  uint32_t* pq;                 // [P][N][max_len]
-  int32_t* len;                 // [P][N]
-  uint32_t* status;             // sticky CSD_STATUS_* bits
-  int32_t P, N, max_len, vocab;
-};
 
 // Workgroups are dealt round-robin to the 8 XCDs; this maps them back so that
 // each XCD works on a contiguous range of (problem, path) rows and the paths of
@@ -391,98 +669,120 @@ __device__ __forceinline__ int32_t xcd_row(int32_t rows) {
 }
 inline uint32_t xcd_grid(int64_t rows) { return (uint32_t)((rows + 7) / 8 * 8); }
 
-__device__ __forceinline__ Ctx make_ctx(const IndexView& ix, int32_t row) {
+__device__ __forceinline__ Ctx make_ctx(const IndexView& ix, const StepIn& in, int32_t row,
+                                        int32_t& p_out) {
   Ctx c;
   int32_t p = row / ix.N;
+  p_out = p;
+  int64_t cells = (int64_t)p * ix.N * ix.max_len;
   c.i = row - p * ix.N;
-  c.tok = ix.tok + (int64_t)p * ix.N * ix.max_len;
-  c.pq = ix.pq + (int64_t)p * ix.N * ix.max_len;
-  c.len = ix.len + (int64_t)p * ix.N;
-  c.N = ix.N;
-  c.max_len = ix.max_len;
+  c.y.tok = ix.tok + cells;
+  c.y.pq = ix.pq + cells;
+  c.y.len_old = ix.len_old + (int64_t)p * ix.N;
+  c.y.n = in.n;
+  c.y.st = in.n ? in.tok + (int64_t)p * ix.N * in.n : nullptr;
+  c.y.sp = (in.n && in.prob) ? in.prob + (int64_t)p * ix.N * in.n : nullptr;
+  c.y.sc = (in.n && in.counts) ? in.counts + (int64_t)p * ix.N : nullptr;
+  c.y.N = ix.N;
+  c.y.max_len = ix.max_len;
+  c.gram = ix.gram ? ix.gram + (int64_t)p * ix.kmax * ((int64_t)ix.bucket_mask + 1) * kBucketWords
+                   : nullptr;
+  c.bucket_mask = ix.bucket_mask;
+  c.kmax = ix.kmax;
   c.tid = threadIdx.x;
   return c;
 }
 
-__global__ __launch_bounds__(kBlock) void reset_kernel(IndexView ix) {
-  int64_t t = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (t < (int64_t)ix.P * ix.N) ix.len[t] = 0;
+__global__ __launch_bounds__(256) void reset_kernel(IndexView ix, int64_t gram_words) {
+  int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  int64_t stride = (int64_t)gridDim.x * 256;
+  int64_t rows = (int64_t)ix.P * ix.N;
+  for (int64_t r = t; r < rows; r += stride) ix.len_new[r] = 0;
+  for (int64_t w = t; w < gram_words; w += stride) ix.gram[w] = (w & (kBucketWords - 1)) ? -1 : 0;
   if (t == 0) *ix.status = 0u;
 }
 
-// One thread per path: stores the step's tokens and quantised probabilities
-// behind the path's current end.
-__global__ __launch_bounds__(kBlock) void append_kernel(IndexView ix, const int32_t* tokens,
-                                                        const float* probs, const int32_t* counts,
-                                                        int32_t n) {
-  int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (r >= (int64_t)ix.P * ix.N) return;
-  int32_t cnt = counts ? counts[r] : n;
-  cnt = cnt < 0 ? 0 : (cnt > n ? n : cnt);
-  int32_t len = ix.len[r];
-  uint32_t flags = 0;
-  if (len + cnt > ix.max_len) {
-    cnt = ix.max_len - len;
-    flags |= CSD_STATUS_CAPACITY;
-  }
-  int32_t* trow = ix.tok + r * ix.max_len;
-  uint32_t* prow = ix.pq + r * ix.max_len;
-  for (int32_t t = 0; t < cnt; ++t) {
-    int32_t v = tokens[r * n + t];
-    if (v < 0 || v >= ix.vocab) flags |= CSD_STATUS_TOKEN_RANGE;
-    trow[len + t] = v;
-    prow[len + t] = probs ? quantize_prob(probs[r * n + t]) : 65536u;
-  }
-  ix.len[r] = len + cnt;
-  if (flags) atomicOr(ix.status, flags);
+// Append only: one workgroup per (problem, path).
+__global__ __launch_bounds__(256) void append_kernel(IndexView ix, StepIn in) {
+  int32_t row = blockIdx.x;
+  int32_t p;
+  Ctx c = make_ctx(ix, in, row, p);
+  int32_t old_i = c.y.old_len(c.i);
+  int32_t new_i = c.y.new_len(c.i, old_i);
+  // every thread has read the old length before thread 0 overwrites it (len_new may alias len_old)
+  __syncthreads();
+  append_row<256>(ix, c.y, p, c.i, old_i, new_i, c.tid);
 }
 
-// One workgroup per (problem, path): match (Eq. 3) -> DAG (Eq. 5) -> greedy walk.
-__global__ __launch_bounds__(kBlock) void draft_kernel(IndexView ix, int32_t k, int32_t L,
-                                                       uint32_t alpha_q, int32_t score_mode,
-                                                       int32_t* draft_tokens, int32_t* draft_len,
-                                                       float* token_scores, float* path_scores) {
+struct DraftArgs {
+  int32_t k, L;
+  uint32_t alpha_q;
+  int32_t score_mode;
+  int32_t* draft_tokens;        // [P][N][L]
+  int32_t* draft_len;           // [P][N]
+  float* token_scores;          // [P][N][L] or null
+  float* path_scores;           // [P][N] or null
+  const int32_t* targets;       // [P][N][L] or null
+  int32_t* accept_len;          // [P][N] or null
+};
+
+// One workgroup per (problem, path): [append] -> match (Eq. 3) -> DAG (Eq. 5)
+// -> greedy walk -> [accept].  With in.n > 0 the launch also performs the
+// step's append; every workgroup then reads the other paths through `Paths`,
+// which never touches cells written by this launch.
+template <int BLOCK, bool INDEXED>
+__global__ __launch_bounds__(BLOCK) void draft_kernel(IndexView ix, StepIn in, DraftArgs a) {
   __shared__ Lds s;
   int32_t row = xcd_row(ix.P * ix.N);
   if (row < 0) return;
-  Ctx c = make_ctx(ix, row);
-  load_query(c, k);
+  int32_t p;
+  Ctx c = make_ctx(ix, in, row, p);
+  int32_t old_i = c.y.old_len(c.i);
+  c.len_i = c.y.new_len(c.i, old_i);
+  if (in.n > 0) append_row<BLOCK>(ix, c.y, p, c.i, old_i, c.len_i, c.tid);
+  load_query(c, a.k, old_i);
   if (c.tid == 0) s.n_match = 0;
-  __syncthreads();
+  block_sync<BLOCK>();
 
   DraftOut o;
+  const int32_t L = a.L;
   if (c.q > 0) {
     ListSink sink{&s};
-    match_scan(c, sink);
-    __syncthreads();
+    find_matches<BLOCK, INDEXED>(c, sink);
+    block_sync<BLOCK>();
     int32_t M = s.n_match;
     if (M > 0) {
       bool streaming = M > kMatchCap;
       if (!streaming) {
-        uint32_t mask = build_dag(s, c, M, L);
+        uint32_t mask = build_dag<BLOCK>(s, c, M, L);
         streaming = s.overflow != 0;
-        if (!streaming) walk_dag(s, c, mask, L, alpha_q, score_mode, o);
+        if (!streaming) walk_dag<BLOCK>(s, c, mask, L, a.alpha_q, a.score_mode, o);
       }
-      if (streaming) walk_streaming(s, c, M, L, alpha_q, score_mode, ix.status, o);
+      if (streaming)
+        walk_streaming<BLOCK, INDEXED>(s, c, M, L, a.alpha_q, a.score_mode, ix.status, o);
     }
   }
+  bool live = c.tid < o.n;
   if (c.tid < L) {
-    bool live = c.tid < o.n;
-    draft_tokens[(int64_t)row * L + c.tid] = live ? o.tok : -1;
-    if (token_scores) token_scores[(int64_t)row * L + c.tid] = live ? key_to_score(o.key) : 0.0f;
+    a.draft_tokens[(int64_t)row * L + c.tid] = live ? o.tok : -1;
+    if (a.token_scores) a.token_scores[(int64_t)row * L + c.tid] = live ? key_to_score(o.key) : 0.0f;
   }
   if (c.tid == 0) {
-    draft_len[row] = o.n;
-    if (path_scores) path_scores[row] = key_to_score(o.key_sum);
+    a.draft_len[row] = o.n;
+    if (a.path_scores) a.path_scores[row] = key_to_score(o.key_sum);
+  }
+  if (a.targets && c.tid < kWave) {     // "Draft acceptance": first lane whose token differs
+    bool same = live && c.tid < L && a.targets[(int64_t)row * L + c.tid] == o.tok;
+    u64 differs = __ballot(!same);
+    if (c.tid == 0) a.accept_len[row] = differs ? (int32_t)__ffsll((long long)differs) - 1 : kWave;
   }
 }
 
-__global__ __launch_bounds__(kBlock) void accept_kernel(int64_t rows, int32_t L,
-                                                        const int32_t* draft_tokens,
-                                                        const int32_t* draft_len,
-                                                        const int32_t* targets,
-                                                        int32_t* accept_len) {
-  int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+__global__ __launch_bounds__(256) void accept_kernel(int64_t rows, int32_t L,
+                                                     const int32_t* draft_tokens,
+                                                     const int32_t* draft_len,
+                                                     const int32_t* targets, int32_t* accept_len) {
+  int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (r >= rows) return;
   int32_t n = draft_len[r];
   n = n < 0 ? 0 : (n > L ? L : n);
@@ -493,26 +793,30 @@ __global__ __launch_bounds__(kBlock) void accept_kernel(int64_t rows, int32_t L,
 
 // ---- debug dumps ------------------------------------------------------------
 
-__global__ __launch_bounds__(kBlock) void dump_match_bits_kernel(IndexView ix, int32_t k,
-                                                                 uint32_t* bits, int32_t words) {
+template <int BLOCK, bool INDEXED>
+__global__ __launch_bounds__(BLOCK) void dump_match_bits_kernel(IndexView ix, StepIn in, int32_t k,
+                                                                uint32_t* bits, int32_t words) {
   int32_t row = xcd_row(ix.P * ix.N);
   if (row < 0) return;
-  Ctx c = make_ctx(ix, row);
-  load_query(c, k);
+  int32_t p;
+  Ctx c = make_ctx(ix, in, row, p);   // in.n == 0: nothing is being appended
+  int32_t old_i = c.y.old_len(c.i);
+  c.len_i = old_i;
+  load_query(c, k, old_i);
   if (c.q <= 0) return;
   BitmapSink sink{bits + (int64_t)row * words};
-  match_scan(c, sink);
+  find_matches<BLOCK, INDEXED>(c, sink);
 }
 
 // counts[row] = number of set bits of the row (one workgroup per row)
-__global__ __launch_bounds__(kBlock) void count_bits_kernel(const uint32_t* bits, int32_t words,
-                                                            int32_t* counts) {
+__global__ __launch_bounds__(256) void count_bits_kernel(const uint32_t* bits, int32_t words,
+                                                         int32_t* counts) {
   __shared__ int total;
   if (threadIdx.x == 0) total = 0;
   __syncthreads();
   const uint32_t* b = bits + (int64_t)blockIdx.x * words;
   int n = 0;
-  for (int32_t w = threadIdx.x; w < words; w += kBlock) n += __popc(b[w]);
+  for (int32_t w = threadIdx.x; w < words; w += 256) n += __popc(b[w]);
   atomicAdd(&total, n);
   __syncthreads();
   if (threadIdx.x == 0) counts[blockIdx.x] = total;
@@ -567,52 +871,56 @@ __global__ __launch_bounds__(64) void expand_bits_kernel(const uint32_t* bits, i
 // Builds the tier-1 DAG tables of a row exactly as draft_kernel does and writes
 // the edge entries, sorted by key, to tmp rows of kTableCap entries.
 // counts[row] = number of edges, or -1 if the row needs the streaming tier.
-__global__ __launch_bounds__(kBlock) void dump_edge_rows_kernel(IndexView ix, int32_t k, int32_t L,
-                                                                u64* tmp_keys, u64* tmp_vals,
-                                                                int32_t* counts) {
+template <int BLOCK, bool INDEXED>
+__global__ __launch_bounds__(BLOCK) void dump_edge_rows_kernel(IndexView ix, StepIn in, int32_t k,
+                                                               int32_t L, u64* tmp_keys,
+                                                               u64* tmp_vals, int32_t* counts) {
   __shared__ Lds s;
   __shared__ int n_edges;
   int32_t row = xcd_row(ix.P * ix.N);
   if (row < 0) return;
-  Ctx c = make_ctx(ix, row);
-  load_query(c, k);
+  int32_t p;
+  Ctx c = make_ctx(ix, in, row, p);   // in.n == 0: nothing is being appended
+  int32_t old_i = c.y.old_len(c.i);
+  c.len_i = old_i;
+  load_query(c, k, old_i);
   if (c.tid == 0) { s.n_match = 0; n_edges = 0; }
-  __syncthreads();
+  block_sync<BLOCK>();
   if (c.q <= 0) { if (c.tid == 0) counts[row] = 0; return; }
   ListSink sink{&s};
-  match_scan(c, sink);
-  __syncthreads();
+  find_matches<BLOCK, INDEXED>(c, sink);
+  block_sync<BLOCK>();
   int32_t M = s.n_match;
   if (M == 0) { if (c.tid == 0) counts[row] = 0; return; }
   if (M > kMatchCap) { if (c.tid == 0) counts[row] = -1; return; }
-  uint32_t mask = build_dag(s, c, M, L);
+  uint32_t mask = build_dag<BLOCK>(s, c, M, L);
   if (s.overflow) { if (c.tid == 0) counts[row] = -1; return; }
   u64* ok = tmp_keys + (int64_t)row * kTableCap;
   u64* ov = tmp_vals + (int64_t)row * kTableCap;
-  for (uint32_t h = c.tid; h <= mask; h += kBlock) {
-    u64 key = s.keys[h];
+  for (uint32_t h = c.tid; h <= mask; h += BLOCK) {
+    u64 key = s.table[h].key;
     if (key == kEmpty || ((key >> 29) & kTokMask) == kAnyTok) continue;
     int rank = 0;                                     // keys are distinct: rank = sorted position
     for (uint32_t g = 0; g <= mask; ++g) {
-      u64 other = s.keys[g];
+      u64 other = s.table[g].key;
       if (other != kEmpty && ((other >> 29) & kTokMask) != kAnyTok && other < key) ++rank;
     }
     ok[rank] = key;
-    ov[rank] = s.vals[h];
+    ov[rank] = s.table[h].val;
     atomicAdd(&n_edges, 1);
   }
-  __syncthreads();
+  block_sync<BLOCK>();
   if (c.tid == 0) counts[row] = n_edges;
 }
 
-__global__ __launch_bounds__(kBlock) void scatter_edges_kernel(const u64* tmp_keys,
-                                                               const u64* tmp_vals,
-                                                               const int32_t* off, int32_t* out_duv,
-                                                               uint64_t* out_cs, int64_t cap) {
+__global__ __launch_bounds__(256) void scatter_edges_kernel(const u64* tmp_keys,
+                                                            const u64* tmp_vals,
+                                                            const int32_t* off, int32_t* out_duv,
+                                                            uint64_t* out_cs, int64_t cap) {
   int32_t row = blockIdx.x;
   int64_t base = off[row];
   int32_t n = off[row + 1] - off[row];
-  for (int32_t x = threadIdx.x; x < n; x += kBlock) {
+  for (int32_t x = threadIdx.x; x < n; x += 256) {
     int64_t at = base + x;
     if (at >= cap) break;
     u64 key = tmp_keys[(int64_t)row * kTableCap + x];
@@ -643,8 +951,12 @@ constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-  size_t tok, pq, len, status, total;
+  size_t tok, pq, len, status, gram, total;
+  uint32_t n_buckets;           // per (problem, gram length); 0 in scan mode
+  size_t gram_words;
 };
+
+bool uses_index(const csd_config* c) { return c->flags != CSD_MATCH_SCAN; }
 
 int validate(const csd_config* c) {
   if (!c) return CSD_ERR_INVALID_ARG;
@@ -667,8 +979,20 @@ Layout make_layout(const csd_config* c) {
   size_t at = 0;
   l.tok = at;    at += align_up(cells * sizeof(int32_t));
   l.pq = at;     at += align_up(cells * sizeof(uint32_t));
-  l.len = at;    at += align_up(rows * sizeof(int32_t));
+  l.len = at;    at += align_up(2 * rows * sizeof(int32_t));
   l.status = at; at += align_up(4 * sizeof(uint32_t));
+  l.n_buckets = 0;
+  l.gram_words = 0;
+  l.gram = at;
+  if (uses_index(c)) {
+    // 15 slots per bucket and at least positions/8 buckets: load factor <= 8/15
+    uint64_t positions = (uint64_t)c->n_paths * c->max_len;
+    uint32_t nb = 4;
+    while ((uint64_t)nb * 8 < positions) nb <<= 1;
+    l.n_buckets = nb;
+    l.gram_words = (size_t)c->n_problems * c->max_query_len * nb * kBucketWords;
+    at += align_up(l.gram_words * sizeof(int32_t));
+  }
   l.total = at;
   return l;
 }
@@ -683,14 +1007,48 @@ uint32_t to_alpha_q(float alpha) {
 
 struct csd_index {
   csd_config cfg;
-  IndexView view;
+  IndexView view;               // len_old / len_new are filled per launch
+  int32_t* len[2];              // double-buffered lengths; `cur` is the valid one
+  int cur;
+  size_t gram_words;
+  bool indexed;
   uint32_t alpha_q;
   int64_t len_lo, len_hi;       // host-side bounds on every path's length
 };
 
 namespace {
 hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
-uint32_t blocks_for(int64_t n) { return (uint32_t)((n + kBlock - 1) / kBlock); }
+
+IndexView view_in_place(const csd_index* h) {     // lengths read and written in the same buffer
+  IndexView v = h->view;
+  v.len_old = h->len[h->cur];
+  v.len_new = h->len[h->cur];
+  return v;
+}
+
+int check_draft_args(const csd_index* h, int32_t query_len, int32_t draft_len) {
+  if (query_len < 1 || query_len > h->cfg.max_query_len) return CSD_ERR_INVALID_ARG;
+  if (draft_len < 1 || draft_len > h->cfg.max_draft_len) return CSD_ERR_INVALID_ARG;
+  return CSD_OK;
+}
+
+void launch_draft(const csd_index* h, const IndexView& v, const StepIn& in, const DraftArgs& a,
+                  hipStream_t st) {
+  int64_t rows = (int64_t)v.P * v.N;
+  if (h->indexed)
+    draft_kernel<kWave, true><<<xcd_grid(rows), kWave, 0, st>>>(v, in, a);
+  else
+    draft_kernel<kScanBlock, false><<<xcd_grid(rows), kScanBlock, 0, st>>>(v, in, a);
+}
+
+// Host-side bookkeeping shared by csd_append and csd_step.
+int note_append(csd_index* h, bool has_counts, int32_t n) {
+  if (!has_counts && h->len_lo + n > h->cfg.max_len) return CSD_ERR_CAPACITY;
+  if (!has_counts) h->len_lo += n;
+  h->len_hi += n;
+  if (h->len_hi > h->cfg.max_len) h->len_hi = h->cfg.max_len;
+  return CSD_OK;
+}
 }  // namespace
 
 extern "C" {
@@ -717,14 +1075,24 @@ int csd_create(const csd_config* cfg, void* d_workspace, size_t workspace_bytes,
   if (!h) return CSD_ERR_INVALID_ARG;
   h->cfg = *cfg;
   char* base = static_cast<char*>(d_workspace);
+  size_t rows = (size_t)cfg->n_problems * cfg->n_paths;
   h->view.tok = reinterpret_cast<int32_t*>(base + l.tok);
   h->view.pq = reinterpret_cast<uint32_t*>(base + l.pq);
-  h->view.len = reinterpret_cast<int32_t*>(base + l.len);
+  h->len[0] = reinterpret_cast<int32_t*>(base + l.len);
+  h->len[1] = h->len[0] + rows;
+  h->cur = 0;
+  h->view.len_old = h->len[0];
+  h->view.len_new = h->len[0];
   h->view.status = reinterpret_cast<uint32_t*>(base + l.status);
+  h->indexed = uses_index(cfg);
+  h->view.gram = h->indexed ? reinterpret_cast<int32_t*>(base + l.gram) : nullptr;
+  h->view.bucket_mask = h->indexed ? l.n_buckets - 1 : 0;
+  h->gram_words = l.gram_words;
   h->view.P = cfg->n_problems;
   h->view.N = cfg->n_paths;
   h->view.max_len = cfg->max_len;
   h->view.vocab = cfg->vocab;
+  h->view.kmax = cfg->max_query_len;
   h->alpha_q = to_alpha_q(cfg->alpha);
   rc = csd_reset(h, stream);
   if (rc != CSD_OK) {
@@ -743,8 +1111,12 @@ int csd_destroy(csd_index* index) {
 
 int csd_reset(csd_index* h, void* stream) {
   if (!h) return CSD_ERR_INVALID_ARG;
-  int64_t rows = (int64_t)h->view.P * h->view.N;
-  reset_kernel<<<blocks_for(rows), kBlock, 0, as_stream(stream)>>>(h->view);
+  int64_t work = (int64_t)h->view.P * h->view.N;
+  if ((int64_t)h->gram_words > work) work = (int64_t)h->gram_words;
+  int64_t blocks = (work + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  reset_kernel<<<(uint32_t)blocks, 256, 0, as_stream(stream)>>>(view_in_place(h),
+                                                                 (int64_t)h->gram_words);
   CSD_HIP(hipGetLastError());
   h->len_lo = h->len_hi = 0;
   return CSD_OK;
@@ -754,26 +1126,23 @@ int csd_append(csd_index* h, const int32_t* d_tokens, const float* d_probs,
                const int32_t* d_counts, int32_t n, void* stream) {
   if (!h || !d_tokens || n < 0) return CSD_ERR_INVALID_ARG;
   if (n == 0) return CSD_OK;
-  if (!d_counts && h->len_lo + n > h->cfg.max_len) return CSD_ERR_CAPACITY;
+  int rc = note_append(h, d_counts != nullptr, n);
+  if (rc != CSD_OK) return rc;
   int64_t rows = (int64_t)h->view.P * h->view.N;
-  append_kernel<<<blocks_for(rows), kBlock, 0, as_stream(stream)>>>(h->view, d_tokens, d_probs,
-                                                                     d_counts, n);
+  append_kernel<<<(uint32_t)rows, 256, 0, as_stream(stream)>>>(
+      view_in_place(h), StepIn{d_tokens, d_probs, d_counts, n});
   CSD_HIP(hipGetLastError());
-  if (!d_counts) h->len_lo += n;
-  h->len_hi += n;
-  if (h->len_hi > h->cfg.max_len) h->len_hi = h->cfg.max_len;
   return CSD_OK;
 }
 
 int csd_draft(csd_index* h, int32_t query_len, int32_t draft_len, int32_t* d_draft_tokens,
               int32_t* d_draft_len, float* d_token_scores, float* d_path_scores, void* stream) {
   if (!h || !d_draft_tokens || !d_draft_len) return CSD_ERR_INVALID_ARG;
-  if (query_len < 1 || query_len > h->cfg.max_query_len) return CSD_ERR_INVALID_ARG;
-  if (draft_len < 1 || draft_len > h->cfg.max_draft_len) return CSD_ERR_INVALID_ARG;
-  int64_t rows = (int64_t)h->view.P * h->view.N;
-  draft_kernel<<<xcd_grid(rows), kBlock, 0, as_stream(stream)>>>(
-      h->view, query_len, draft_len, h->alpha_q, h->cfg.score_mode, d_draft_tokens, d_draft_len,
-      d_token_scores, d_path_scores);
+  int rc = check_draft_args(h, query_len, draft_len);
+  if (rc != CSD_OK) return rc;
+  DraftArgs a{query_len, draft_len, h->alpha_q, h->cfg.score_mode, d_draft_tokens, d_draft_len,
+              d_token_scores, d_path_scores, nullptr, nullptr};
+  launch_draft(h, view_in_place(h), StepIn{nullptr, nullptr, nullptr, 0}, a, as_stream(stream));
   CSD_HIP(hipGetLastError());
   return CSD_OK;
 }
@@ -784,9 +1153,64 @@ int csd_accept(csd_index* h, const int32_t* d_draft_tokens, const int32_t* d_dra
     return CSD_ERR_INVALID_ARG;
   if (draft_len < 1 || draft_len > h->cfg.max_draft_len) return CSD_ERR_INVALID_ARG;
   int64_t rows = (int64_t)h->view.P * h->view.N;
-  accept_kernel<<<blocks_for(rows), kBlock, 0, as_stream(stream)>>>(
+  accept_kernel<<<(uint32_t)((rows + 255) / 256), 256, 0, as_stream(stream)>>>(
       rows, draft_len, d_draft_tokens, d_draft_len, d_targets, d_accept_len);
   CSD_HIP(hipGetLastError());
+  return CSD_OK;
+}
+
+int csd_step(csd_index* h, const int32_t* d_tokens, const float* d_probs, const int32_t* d_counts,
+             int32_t n, int32_t query_len, int32_t draft_len, int32_t* d_draft_tokens,
+             int32_t* d_draft_len, float* d_token_scores, float* d_path_scores,
+             const int32_t* d_targets, int32_t* d_accept_len, void* stream) {
+  if (!h || !d_tokens || n < 1 || n > CSD_MAX_STEP_TOKENS || !d_draft_tokens || !d_draft_len)
+    return CSD_ERR_INVALID_ARG;
+  if ((d_targets == nullptr) != (d_accept_len == nullptr)) return CSD_ERR_INVALID_ARG;
+  int rc = check_draft_args(h, query_len, draft_len);
+  if (rc != CSD_OK) return rc;
+  rc = note_append(h, d_counts != nullptr, n);
+  if (rc != CSD_OK) return rc;
+  IndexView v = h->view;
+  v.len_old = h->len[h->cur];
+  v.len_new = h->len[h->cur ^ 1];
+  DraftArgs a{query_len, draft_len, h->alpha_q, h->cfg.score_mode, d_draft_tokens, d_draft_len,
+              d_token_scores, d_path_scores, d_targets, d_accept_len};
+  launch_draft(h, v, StepIn{d_tokens, d_probs, d_counts, n}, a, as_stream(stream));
+  CSD_HIP(hipGetLastError());
+  h->cur ^= 1;
+  return CSD_OK;
+}
+
+int csd_replay(csd_index* h, int32_t n_steps, const int32_t* d_tokens, const float* d_probs,
+               int32_t query_len, int32_t draft_len, int32_t* d_draft_tokens, int32_t* d_draft_len,
+               float* d_token_scores, float* d_path_scores, const int32_t* d_targets,
+               int32_t* d_accept_len, int32_t fused, void* stream) {
+  if (!h || n_steps < 0 || !d_tokens || !d_draft_tokens || !d_draft_len)
+    return CSD_ERR_INVALID_ARG;
+  if ((d_targets == nullptr) != (d_accept_len == nullptr)) return CSD_ERR_INVALID_ARG;
+  int rc = check_draft_args(h, query_len, draft_len);
+  if (rc != CSD_OK) return rc;
+  if (h->len_lo + n_steps > h->cfg.max_len) return CSD_ERR_CAPACITY;
+  size_t rows = (size_t)h->view.P * h->view.N;
+  size_t L = (size_t)draft_len;
+  for (int32_t t = 0; t < n_steps; ++t) {
+    const int32_t* tk = d_tokens + t * rows;
+    const float* pr = d_probs ? d_probs + t * rows : nullptr;
+    int32_t* dt = d_draft_tokens + t * rows * L;
+    int32_t* dl = d_draft_len + t * rows;
+    float* ts = d_token_scores ? d_token_scores + t * rows * L : nullptr;
+    float* ps = d_path_scores ? d_path_scores + t * rows : nullptr;
+    const int32_t* tg = d_targets ? d_targets + t * rows * L : nullptr;
+    int32_t* al = d_accept_len ? d_accept_len + t * rows : nullptr;
+    if (fused) {
+      rc = csd_step(h, tk, pr, nullptr, 1, query_len, draft_len, dt, dl, ts, ps, tg, al, stream);
+    } else {
+      rc = csd_append(h, tk, pr, nullptr, 1, stream);
+      if (rc == CSD_OK) rc = csd_draft(h, query_len, draft_len, dt, dl, ts, ps, stream);
+      if (rc == CSD_OK && tg) rc = csd_accept(h, dt, dl, tg, draft_len, al, stream);
+    }
+    if (rc != CSD_OK) return rc;
+  }
   return CSD_OK;
 }
 
@@ -812,11 +1236,18 @@ int csd_dump_matches(csd_index* h, int32_t query_len, int32_t* d_match_je, int32
   if (e != hipSuccess) { (void)hipFree(bits); return hip_fail(e, "hipMalloc"); }
   int rc = CSD_OK;
   int32_t total = 0;
+  IndexView v = view_in_place(h);
+  const StepIn no_step{nullptr, nullptr, nullptr, 0};
   do {
     e = hipMemsetAsync(bits, 0, (size_t)rows * words * sizeof(uint32_t), st);
     if (e != hipSuccess) break;
-    dump_match_bits_kernel<<<xcd_grid(rows), kBlock, 0, st>>>(h->view, query_len, bits, words);
-    count_bits_kernel<<<rows, kBlock, 0, st>>>(bits, words, counts);
+    if (h->indexed)
+      dump_match_bits_kernel<kWave, true><<<xcd_grid(rows), kWave, 0, st>>>(v, no_step, query_len,
+                                                                            bits, words);
+    else
+      dump_match_bits_kernel<kScanBlock, false><<<xcd_grid(rows), kScanBlock, 0, st>>>(
+          v, no_step, query_len, bits, words);
+    count_bits_kernel<<<rows, 256, 0, st>>>(bits, words, counts);
     offsets_kernel<<<1, 1, 0, st>>>(counts, rows, d_match_off, counts + rows);
     expand_bits_kernel<<<rows, 64, 0, st>>>(bits, words, h->view.max_len, d_match_off, d_match_je,
                                             cap);
@@ -837,8 +1268,8 @@ int csd_dump_edges(csd_index* h, int32_t query_len, int32_t draft_len, int32_t* 
                    uint64_t* d_edge_cs, int32_t* d_edge_off, int64_t cap, void* stream) {
   if (!h || !d_edge_off || cap < 0 || (cap > 0 && (!d_edge_duv || !d_edge_cs)))
     return CSD_ERR_INVALID_ARG;
-  if (query_len < 1 || query_len > h->cfg.max_query_len) return CSD_ERR_INVALID_ARG;
-  if (draft_len < 1 || draft_len > h->cfg.max_draft_len) return CSD_ERR_INVALID_ARG;
+  int rc = check_draft_args(h, query_len, draft_len);
+  if (rc != CSD_OK) return rc;
   hipStream_t st = as_stream(stream);
   int32_t rows = h->view.P * h->view.N;
   u64* tmp = nullptr;
@@ -848,12 +1279,18 @@ int csd_dump_edges(csd_index* h, int32_t query_len, int32_t draft_len, int32_t* 
   hipError_t e = hipMalloc(&counts, ((size_t)rows + 1) * sizeof(int32_t));
   if (e != hipSuccess) { (void)hipFree(tmp); return hip_fail(e, "hipMalloc"); }
   int32_t tail[2] = {0, 0};   // total rows, bad flag
+  IndexView v = view_in_place(h);
+  const StepIn no_step{nullptr, nullptr, nullptr, 0};
   do {
-    dump_edge_rows_kernel<<<xcd_grid(rows), kBlock, 0, st>>>(h->view, query_len, draft_len, tmp,
-                                                             tmp + tmp_elems, counts);
+    if (h->indexed)
+      dump_edge_rows_kernel<kWave, true><<<xcd_grid(rows), kWave, 0, st>>>(
+          v, no_step, query_len, draft_len, tmp, tmp + tmp_elems, counts);
+    else
+      dump_edge_rows_kernel<kScanBlock, false><<<xcd_grid(rows), kScanBlock, 0, st>>>(
+          v, no_step, query_len, draft_len, tmp, tmp + tmp_elems, counts);
     offsets_kernel<<<1, 1, 0, st>>>(counts, rows, d_edge_off, counts + rows);
-    scatter_edges_kernel<<<rows, kBlock, 0, st>>>(tmp, tmp + tmp_elems, d_edge_off, d_edge_duv,
-                                                  d_edge_cs, cap);
+    scatter_edges_kernel<<<rows, 256, 0, st>>>(tmp, tmp + tmp_elems, d_edge_off, d_edge_duv,
+                                               d_edge_cs, cap);
     e = hipGetLastError();
     if (e != hipSuccess) break;
     e = hipMemcpyAsync(&tail[0], d_edge_off + rows, sizeof(int32_t), hipMemcpyDeviceToHost, st);

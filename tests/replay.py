@@ -7,9 +7,13 @@ from paper_2503_05330_amd import binding
 
 
 def gpu_replay(tokens, probs, k, L, alpha=1.0, score_mode=0, flags=0, steps=None, targets=None,
-               counts=None, n_per_step=1):
+               counts=None, n_per_step=1, how="calls"):
     """Appends n_per_step tokens per path per step (or counts[t] of them) and drafts after
-    every step.  Returns host arrays indexed by step, plus the final status bits."""
+    every step.  Returns host arrays indexed by step, plus the final status bits.
+    how: "calls"  = csd_append + csd_draft (+ csd_accept) per step,
+         "step"   = one fused csd_step per step,
+         "replay" / "replay_unfused" = one csd_replay call for all steps (n_per_step == 1,
+                    no counts)."""
     P, N, T = tokens.shape
     steps = steps if steps is not None else T // n_per_step
     dev = torch.device("cuda:0")
@@ -23,7 +27,20 @@ def gpu_replay(tokens, probs, k, L, alpha=1.0, score_mode=0, flags=0, steps=None
     lens = np.zeros((steps, P, N), dtype=np.int32)
     cur = np.zeros((P, N), dtype=np.int64)
     n = n_per_step
-    for t in range(steps):
+    if how.startswith("replay"):
+        assert n == 1 and counts is None
+        d_tok = torch.from_numpy(np.ascontiguousarray(tokens[:, :, :steps].transpose(2, 0, 1))).to(dev)
+        d_pr = None if probs is None else torch.from_numpy(
+            np.ascontiguousarray(probs[:, :, :steps].transpose(2, 0, 1))).to(dev)
+        d_tg = None if targets is None else torch.from_numpy(np.ascontiguousarray(targets[:steps])).to(dev)
+        out = dict(tokens=out_tok, length=out_len, token_scores=out_ts, path_scores=out_ps)
+        ix.replay(steps, d_tok, d_pr, k, L, out=out, targets=d_tg, accept_out=out_acc,
+                  fused=(how == "replay"))
+        lens[:] = (np.arange(steps) + 1)[:, None, None]
+        steps_to_run = 0
+    else:
+        steps_to_run = steps
+    for t in range(steps_to_run):
         cnt = counts[t].astype(np.int64) if counts is not None else np.full((P, N), n, np.int64)
         cnt = np.minimum(cnt, T - cur)
         # gather each path's next n tokens (ragged: path-local read position)
@@ -34,13 +51,18 @@ def gpu_replay(tokens, probs, k, L, alpha=1.0, score_mode=0, flags=0, steps=None
         if probs is not None:
             d_pr = torch.from_numpy(np.ascontiguousarray(np.take_along_axis(probs, idx, axis=2))).to(dev)
         d_cnt = torch.from_numpy(cnt.astype(np.int32)).to(dev) if counts is not None else None
-        ix.append(d_tok, d_pr, d_cnt, n)
         cur = cur + cnt
         lens[t] = cur
         out = dict(tokens=out_tok[t], length=out_len[t], token_scores=out_ts[t], path_scores=out_ps[t])
-        ix.draft(k, L, out=out)
-        if targets is not None:
-            ix.accept(out_tok[t], out_len[t], torch.from_numpy(targets[t]).to(dev), L, out=out_acc[t])
+        d_tg = torch.from_numpy(targets[t]).to(dev) if targets is not None else None
+        if how == "step":
+            ix.step(d_tok, d_pr, d_cnt, n, k, L, out=out, targets=d_tg,
+                    accept_out=out_acc[t] if targets is not None else None)
+        else:
+            ix.append(d_tok, d_pr, d_cnt, n)
+            ix.draft(k, L, out=out)
+            if targets is not None:
+                ix.accept(out_tok[t], out_len[t], d_tg, L, out=out_acc[t])
     status = ix.status()
     res = dict(draft=out_tok.cpu().numpy(), draft_len=out_len.cpu().numpy(),
                token_scores=out_ts.cpu().numpy(), path_scores=out_ps.cpu().numpy(),

@@ -31,7 +31,14 @@ def check_dumps(oracle, ix, tokens, probs, lens_t, k, L):
             assert np.array_equal(cs[eoff[r]:eoff[r + 1]], wcs), "edge weights row %d" % r
 
 
-def run_config(oracle, w, use_probs, alpha, mode, check_every=1, dump_at=(), flags=0, accept=False):
+SCAN, INDEX = binding.MATCH_SCAN, binding.MATCH_INDEX
+ALL_VARIANTS = ((INDEX, "replay"), (INDEX, "calls"), (SCAN, "step"), (SCAN, "replay_unfused"))
+
+
+def run_config(oracle, w, use_probs, alpha, mode, check_every=1, dump_at=(), accept=False,
+               variants=ALL_VARIANTS):
+    """Replays the workload once per (matcher, call pattern) variant and compares every
+    checked step of every variant with the oracle (computed once per step)."""
     tokens, probs = synth.make_paths(w)
     if not use_probs:
         probs = None
@@ -39,33 +46,42 @@ def run_config(oracle, w, use_probs, alpha, mode, check_every=1, dump_at=(), fla
     targets = None
     if accept:
         targets = np.stack([synth.make_noisy_targets(w, tokens, t + 1, w.draft_len) for t in range(T)])
-    print("replay", w.name, "P,N,T", tokens.shape, "probs", use_probs, "alpha", alpha, "mode", mode,
-          "flags", flags, flush=True)
-    got = gpu_replay(tokens, probs, w.query_len, w.draft_len, alpha, mode, flags, targets=targets)
-    assert got["status"] == 0
-    n_nonempty = 0
-    for t in list(range(0, T, check_every)) + [T - 1]:
-        want = oracle_step(oracle, tokens, probs, got["lens"][t], w.query_len, w.draft_len, alpha, mode,
-                           targets[t] if accept else None)
-        assert_step_equal(got, want, t, w.name)
-        n_nonempty += int((want["draft_len"] > 0).sum())
-    assert n_nonempty > 0
+    steps = sorted(set(list(range(0, T, check_every)) + [T - 1]))
+    want = {}
+    for t in steps:
+        lens_t = np.full(tokens.shape[:2], t + 1, dtype=np.int32)
+        want[t] = oracle_step(oracle, tokens, probs, lens_t, w.query_len, w.draft_len, alpha, mode,
+                              targets[t] if accept else None)
+    assert sum(int((x["draft_len"] > 0).sum()) for x in want.values()) > 0
+    got = None
+    for flags, how in variants:
+        print("replay", w.name, "P,N,T", tokens.shape, "probs", use_probs, "alpha", alpha, "mode", mode,
+              "flags", flags, "how", how, flush=True)
+        got = gpu_replay(tokens, probs, w.query_len, w.draft_len, alpha, mode, flags, targets=targets,
+                         how=how)
+        assert got["status"] == 0
+        for t in steps:
+            assert_step_equal(got, want[t], t, "%s flags=%d %s" % (w.name, flags, how))
     # intermediate results at chosen history lengths (fresh index, appended in one call)
-    for t in dump_at:
-        dev = torch.device("cuda:0")
-        ix = binding.Index(w.n_problems, w.n_paths, T, w.vocab, w.query_len, w.draft_len, alpha, mode,
-                           flags, device=dev)
-        ix.append(torch.from_numpy(np.ascontiguousarray(tokens[:, :, :t])).to(dev),
-                  None if probs is None else torch.from_numpy(np.ascontiguousarray(probs[:, :, :t])).to(dev),
-                  None, t)
-        lens_t = np.full(tokens.shape[:2], t, dtype=np.int32)
-        check_dumps(oracle, ix, tokens, probs, lens_t, w.query_len, w.draft_len)
-        for q in range(1, w.query_len):      # shorter queries at full history: many more matches
-            je, moff = ix.dump_matches(q)
-            for p in range(min(w.n_problems, 2)):
-                for i in range(w.n_paths):
-                    r = p * w.n_paths + i
-                    assert np.array_equal(je[moff[r]:moff[r + 1]], oracle.matches(tokens[p], lens_t[p], i, q))
+    for flags in sorted(set(f for f, _ in variants)):
+        for t in dump_at:
+            print("dumps", w.name, "flags", flags, "history", t, flush=True)
+            dev = torch.device("cuda:0")
+            ix = binding.Index(w.n_problems, w.n_paths, T, w.vocab, w.query_len, w.draft_len, alpha,
+                               mode, flags, device=dev)
+            ix.append(torch.from_numpy(np.ascontiguousarray(tokens[:, :, :t])).to(dev),
+                      None if probs is None else torch.from_numpy(np.ascontiguousarray(probs[:, :, :t])).to(dev),
+                      None, t)
+            lens_t = np.full(tokens.shape[:2], t, dtype=np.int32)
+            check_dumps(oracle, ix, tokens, probs, lens_t, w.query_len, w.draft_len)
+            for q in range(1, w.query_len):      # shorter queries at full history: many more matches
+                je, moff = ix.dump_matches(q)
+                for p in range(min(w.n_problems, 2)):
+                    for i in range(w.n_paths):
+                        r = p * w.n_paths + i
+                        assert np.array_equal(je[moff[r]:moff[r + 1]],
+                                              oracle.matches(tokens[p], lens_t[p], i, q))
+            assert ix.status() == 0
     return got
 
 
@@ -80,22 +96,25 @@ def test_c1_every_step_all_modes(oracle):
 def test_c2_every_step(oracle):
     w = synth.WORKLOADS["C2"]
     run_config(oracle, w, True, 1.0, 0, dump_at=(511, 1024))
-    run_config(oracle, w, False, 1.0, 1)
+    run_config(oracle, w, False, 1.0, 1, variants=((INDEX, "step"), (SCAN, "calls")))
 
 
 def test_c3_every_step(oracle):
     w = synth.WORKLOADS["C3"]
-    run_config(oracle, w, True, 1.0, 0, check_every=1, dump_at=(2048,))
+    run_config(oracle, w, True, 1.0, 0, check_every=1, dump_at=(2048,),
+               variants=((INDEX, "replay"), (SCAN, "replay")))
 
 
 def test_c4_batched_problems(oracle):
     w = synth.WORKLOADS["C4"]
-    run_config(oracle, w, True, 1.0, 0, check_every=4, dump_at=(1024,))
+    run_config(oracle, w, True, 1.0, 0, check_every=4, dump_at=(1024,),
+               variants=((INDEX, "replay"), (SCAN, "replay"), (INDEX, "replay_unfused")))
 
 
 def test_c5_sparse_matches_with_accept(oracle):
     w = synth.WORKLOADS["C5"]
-    got = run_config(oracle, w, True, 1.0, 0, check_every=16, dump_at=(4096,), accept=True)
+    got = run_config(oracle, w, True, 1.0, 0, check_every=16, dump_at=(4096,), accept=True,
+                     variants=((INDEX, "replay"), (SCAN, "replay"), (INDEX, "calls")))
     assert got["accept_len"].max() > 0
 
 
@@ -105,12 +124,17 @@ def test_ragged_appends(oracle):
         tokens, probs = synth.make_paths(w)
         steps = w.max_len // 2
         counts = synth.make_ragged_counts(w, 4, steps)
-        got = gpu_replay(tokens, probs, w.query_len, w.draft_len, steps=steps, counts=counts, n_per_step=4)
-        assert got["status"] in (0, binding.STATUS_CAPACITY)
-        assert got["lens"].max() > got["lens"].min()
-        for t in range(steps):
-            want = oracle_step(oracle, tokens, probs, got["lens"][t], w.query_len, w.draft_len, 1.0, 0)
-            assert_step_equal(got, want, t, "ragged " + name)
+        want = None
+        for flags, how in ((INDEX, "step"), (INDEX, "calls"), (SCAN, "step"), (SCAN, "calls")):
+            got = gpu_replay(tokens, probs, w.query_len, w.draft_len, flags=flags, steps=steps,
+                             counts=counts, n_per_step=4, how=how)
+            assert got["status"] in (0, binding.STATUS_CAPACITY)
+            assert got["lens"].max() > got["lens"].min()
+            if want is None:
+                want = [oracle_step(oracle, tokens, probs, got["lens"][t], w.query_len, w.draft_len, 1.0, 0)
+                        for t in range(steps)]
+            for t in range(steps):
+                assert_step_equal(got, want[t], t, "ragged %s flags=%d %s" % (name, flags, how))
 
 
 def test_query_len_longer_and_shorter_than_history(oracle):
@@ -119,21 +143,28 @@ def test_query_len_longer_and_shorter_than_history(oracle):
     w = synth.scaled(synth.WORKLOADS["C2"], max_len=300, query_len=8, draft_len=32)
     tokens, probs = synth.make_paths(w)
     dev = torch.device("cuda:0")
-    ix = binding.Index(1, w.n_paths, 300, w.vocab, 8, 32, 0.25, 0, 0, device=dev)
-    ix.append(torch.from_numpy(tokens).to(dev), torch.from_numpy(probs).to(dev), None, 300)
     lens = np.full((1, w.n_paths), 300, dtype=np.int32)
-    for k in range(1, 9):
-        for L in (1, 7, 32):
-            out = ix.draft(k, L)
-            want = oracle.draft_all(tokens, probs, lens, k, L, 0.25, 0)
-            got = dict(draft=out["tokens"].cpu().numpy()[None], draft_len=out["length"].cpu().numpy()[None],
-                       token_scores=out["token_scores"].cpu().numpy()[None],
-                       path_scores=out["path_scores"].cpu().numpy()[None])
-            assert_step_equal(got, want, 0, "k=%d L=%d" % (k, L))
+    for flags in (INDEX, SCAN):
+        ix = binding.Index(1, w.n_paths, 300, w.vocab, 8, 32, 0.25, 0, flags, device=dev)
+        ix.append(torch.from_numpy(tokens).to(dev), torch.from_numpy(probs).to(dev), None, 300)
+        for k in range(1, 9):
+            for L in (1, 7, 32):
+                out = ix.draft(k, L)
+                want = oracle.draft_all(tokens, probs, lens, k, L, 0.25, 0)
+                got = dict(draft=out["tokens"].cpu().numpy()[None], draft_len=out["length"].cpu().numpy()[None],
+                           token_scores=out["token_scores"].cpu().numpy()[None],
+                           path_scores=out["path_scores"].cpu().numpy()[None])
+                assert_step_equal(got, want, 0, "flags=%d k=%d L=%d" % (flags, k, L))
 
 
-def _one_shot(oracle, paths, probs, k, L, alpha=1.0, mode=0, flags=0):
-    """Appends whole (possibly ragged) paths in one call and compares one draft."""
+def _one_shot(oracle, paths, probs, k, L, alpha=1.0, mode=0, flags=None, fused=False):
+    """Appends whole (possibly ragged) paths in one call and compares one draft; by default
+    under both matchers (returns the last index)."""
+    if flags is None:
+        for f in (SCAN, INDEX):
+            for fu in (False, True):
+                res = _one_shot(oracle, paths, probs, k, L, alpha, mode, f, fu)
+        return res
     N = len(paths)
     T = max(len(p) for p in paths)
     tok = np.zeros((1, N, T), dtype=np.int32)
@@ -146,9 +177,13 @@ def _one_shot(oracle, paths, probs, k, L, alpha=1.0, mode=0, flags=0):
             pr[0, j, :len(p)] = probs[j]
     dev = torch.device("cuda:0")
     ix = binding.Index(1, N, T, int(tok.max()) + 1, max(k, 1), L, alpha, mode, flags, device=dev)
-    ix.append(torch.from_numpy(tok).to(dev), None if pr is None else torch.from_numpy(pr).to(dev),
-              torch.from_numpy(cnt).to(dev), T)
-    out = ix.draft(k, L)
+    d_tok, d_pr, d_cnt = (torch.from_numpy(tok).to(dev), None if pr is None else torch.from_numpy(pr).to(dev),
+                          torch.from_numpy(cnt).to(dev))
+    if fused:      # the whole history arrives in the very step that drafts from it
+        out = ix.step(d_tok, d_pr, d_cnt, T, k, L)
+    else:
+        ix.append(d_tok, d_pr, d_cnt, T)
+        out = ix.draft(k, L)
     want = oracle.draft_all(tok, pr, cnt, k, L, alpha, mode)
     got = dict(draft=out["tokens"].cpu().numpy()[None], draft_len=out["length"].cpu().numpy()[None],
                token_scores=out["token_scores"].cpu().numpy()[None],
