@@ -46,6 +46,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=64)
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 64 MiB copy kernel (reference for traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus %d is not supported "
@@ -75,53 +77,64 @@ def main():
                path_scores=torch.empty((P, N), dtype=torch.float32, device=dev))
     acc = torch.empty((P, N), dtype=torch.int32, device=dev)
 
-    def run_steps(n_steps, events=None):
-        """n_steps consecutive decode steps; the replay restarts from an empty
-        index whenever the paths are full."""
-        t = 0
-        for s in range(n_steps):
-            if t == T:
-                ix.reset()
-                t = 0
-            ix.append(d_tok[t], d_pr[t], None, 1)
-            if events is not None:
-                events[s][0].record()
-            ix.draft(k, L, out=out)
-            if events is not None:
-                events[s][1].record()
-            ix.accept(out["tokens"], out["length"], d_tg[t], L, out=acc)
-            t += 1
+    outs = dict(tokens=torch.empty((T, P, N, L), dtype=torch.int32, device=dev),
+                length=torch.empty((T, P, N), dtype=torch.int32, device=dev),
+                token_scores=torch.empty((T, P, N, L), dtype=torch.float32, device=dev),
+                path_scores=torch.empty((T, P, N), dtype=torch.float32, device=dev))
+    accs = torch.empty((T, P, N), dtype=torch.int32, device=dev)
+
+    def run_steps(n_steps, fused=True):
+        """n_steps consecutive decode steps issued by the library's host loop (one fused
+        launch per step); the replay restarts from an empty index whenever the paths are full."""
+        done = 0
+        while done < n_steps:
+            m = min(T, n_steps - done)
+            ix.reset()
+            ix.replay(m, d_tok, d_pr, k, L, out=outs, targets=d_tg, accept_out=accs, fused=fused)
+            done += m
+
+    if args.calibrate_copy:
+        src = torch.zeros(64 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        binding.debug_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
 
     run_steps(W)
-    ix.reset()
     torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
+    ev0.record()
     run_steps(K)
+    ev1.record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    launch_ms = ev0.elapsed_time(ev1) / K          # HIP events on the launch stream
 
-    # steady state at full history: the last 128 steps of a replay
-    ix.reset()
-    tail = min(128, T)
-    for t in range(T - tail):
-        ix.append(d_tok[t], d_pr[t], None, 1)
+    # the same steps as three launches each (append, draft, accept), and from Python per call
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    for t in range(T - tail, T):
-        ix.append(d_tok[t], d_pr[t], None, 1)
-        ix.draft(k, L, out=out)
-        ix.accept(out["tokens"], out["length"], d_tg[t], L, out=acc)
+    run_steps(min(K, T), fused=False)
+    torch.cuda.synchronize()
+    dt_unfused = (time.perf_counter() - t1) / min(K, T)
+    ix.reset()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for t in range(min(K, T)):
+        ix.step(d_tok[t], d_pr[t], None, 1, k, L, out=out, targets=d_tg[t], accept_out=acc)
+    torch.cuda.synchronize()
+    dt_python = (time.perf_counter() - t1) / min(K, T)
+
+    # steady state at full history: the last 128 steps of a replay
+    tail = min(128, T)
+    ix.reset()
+    ix.replay(T - tail, d_tok, d_pr, k, L, out=outs, targets=d_tg, accept_out=accs)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ix.replay(tail, d_tok[T - tail:], d_pr[T - tail:], k, L, out=outs, targets=d_tg[T - tail:],
+              accept_out=accs)
     torch.cuda.synchronize()
     dt_tail = time.perf_counter() - t1
-
-    # dominant kernel (draft): HIP events on the launch stream around every draft launch
-    ix.reset()
-    Ke = min(K, T)
-    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-              for _ in range(Ke)]
-    run_steps(Ke, events)
-    torch.cuda.synchronize()
-    draft_ms = float(np.mean([a.elapsed_time(b) for a, b in events]))
 
     # measured match counts (untimed, through the debug dump) -> algorithmic bytes
     ix.reset()
@@ -133,8 +146,8 @@ def main():
             m_total += int(off[-1])
             m_samples += 1
     matches_per_step = m_total / max(m_samples, 1)
-    b_step, b_draft = algorithmic_bytes(N * P, k, L, k, matches_per_step)
-    achieved = b_draft / (draft_ms * 1e-3) / 1e9
+    b_step, _ = algorithmic_bytes(N * P, k, L, k, matches_per_step)
+    achieved = b_step / (launch_ms * 1e-3) / 1e9
 
     res = {
         "metric": METRIC, "value": K / dt, "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": W,
@@ -145,11 +158,14 @@ def main():
                                % (w.name, P, N, T, w.vocab, k, L)},
         "us_per_step_mean_over_replay": dt / K * 1e6,
         "us_per_step_at_full_history": dt_tail / tail * 1e6,
+        "us_per_step_three_launches": dt_unfused * 1e6,
+        "us_per_step_python_per_call": dt_python * 1e6,
         "matches_per_step": matches_per_step,
         "algorithmic_bytes_per_step": b_step,
-        "roofline": {"bound": "hbm", "kernel": "draft_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "algorithmic_bytes_per_launch": b_draft, "avg_launch_us": draft_ms * 1e3},
+        "roofline": {"bound": "hbm", "kernel": "draft_kernel<64,true> (fused step: append+draft+accept)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": b_step, "avg_launch_us": launch_ms * 1e3},
     }
 
     if not args.no_cpu_baseline:

@@ -185,6 +185,12 @@ int csd_dump_matches(csd_index* index, int32_t query_len, int32_t* d_match_je,
 int csd_dump_edges(csd_index* index, int32_t query_len, int32_t draft_len, int32_t* d_edge_duv,
                    uint64_t* d_edge_cs, int32_t* d_edge_off, int64_t cap, void* stream);
 
+/* Measurement aid, not part of the method: copies `bytes` (a multiple of 16,
+ * both pointers 16-byte aligned) from d_src to d_dst with a plain copy kernel.
+ * Hardware traffic counters (bytes fetched / written per dispatch) are
+ * calibrated against this kernel of known size. */
+int csd_debug_copy(void* d_dst, const void* d_src, size_t bytes, void* stream);
+
 /* Text for a csd_error (and, for CSD_ERR_HIP, the last HIP error string). */
 const char* csd_strerror(int err);
 

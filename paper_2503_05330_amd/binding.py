@@ -20,7 +20,7 @@ OK, ERR_INVALID_ARG, ERR_CAPACITY, ERR_WORKSPACE, ERR_HIP, ERR_UNIMPLEMENTED = 0
 
 EXPORTS = ["csd_workspace_bytes", "csd_create", "csd_destroy", "csd_reset", "csd_append",
            "csd_draft", "csd_accept", "csd_step", "csd_replay", "csd_status", "csd_dump_matches",
-           "csd_dump_edges", "csd_strerror"]
+           "csd_dump_edges", "csd_debug_copy", "csd_strerror"]
 
 
 class Config(ctypes.Structure):
@@ -62,6 +62,7 @@ def load() -> ctypes.CDLL:
         lib.csd_status.argtypes = [_vp, ctypes.POINTER(ctypes.c_uint32), _vp]
         lib.csd_dump_matches.argtypes = [_vp, i32, _vp, _vp, i64, _vp]
         lib.csd_dump_edges.argtypes = [_vp, i32, i32, _vp, _vp, _vp, i64, _vp]
+        lib.csd_debug_copy.argtypes = [_vp, _vp, ctypes.c_size_t, _vp]
         lib.csd_strerror.argtypes = [ctypes.c_int]
         lib.csd_strerror.restype = ctypes.c_char_p
         for name in EXPORTS:
@@ -73,6 +74,14 @@ def load() -> ctypes.CDLL:
 
 def strerror(code: int) -> str:
     return load().csd_strerror(code).decode()
+
+
+def debug_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
+    """Plain device copy of known size (calibration of hardware traffic counters)."""
+    nbytes = src.numel() * src.element_size()
+    rc = load().csd_debug_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream())
+    if rc != OK:
+        raise CsdError(rc, "csd_debug_copy")
 
 
 def workspace_bytes(cfg: Config) -> int:

@@ -35,7 +35,9 @@ typedef unsigned long long u64;
 constexpr int kWave = 64;
 constexpr int kScanBlock = 256;             // threads per row when matches come from a scan
 constexpr int kMatchCap = 1024;             // matches kept in LDS; beyond -> streaming tier
-constexpr int kTableCap = 2048;             // LDS hash slots for DAG edges + nodes
+constexpr int kTableCap = 1024;             // LDS hash slots for DAG edges + nodes
+constexpr int kWinWords = 2048;             // LDS words for cached continuations of matches
+constexpr int kLenCache = 256;              // path lengths cached in LDS (more paths: read from memory)
 constexpr uint32_t kTokMask = (1u << 29) - 1;
 constexpr uint32_t kAnyTok = kTokMask;      // "any predecessor": marks node (in-weight) entries
 constexpr u64 kEmpty = ~0ull;
@@ -130,8 +132,10 @@ __device__ __forceinline__ Cand wave_argmax(Cand c) {
 struct IndexView {              // device state inside the caller's workspace
   int32_t* tok;                 // [P][N][max_len] token histories
   uint32_t* pq;                 // [P][N][max_len] quantised generation probabilities
-  const int32_t* len_old;       // [P][N] lengths before this launch
-  int32_t* len_new;             // [P][N] lengths after it (== len_old when nothing is appended)
+  const int32_t* meta_old;      // [P][N][meta_stride] before this launch: {length, last kmax
+                                //   tokens newest first}: one aligned load tells a path's end
+  int32_t* meta_new;            // same rows after it (may alias meta_old when nothing else reads)
+  int32_t meta_stride;          // ints per row: 1 + kmax rounded up to a multiple of 4
   uint32_t* status;             // sticky CSD_STATUS_* bits
   int32_t* gram;                // n-gram index [P][kmax][n_buckets][16], or null (scan mode)
   uint32_t bucket_mask;         // n_buckets - 1 (power of two)
@@ -152,13 +156,15 @@ struct StepIn {                 // tokens a step appends; n == 0: none
 struct Paths {
   const int32_t* tok;
   const uint32_t* pq;
-  const int32_t* len_old;
+  const int32_t* meta_old;
   const int32_t* st;
   const float* sp;
   const int32_t* sc;
-  int32_t n, N, max_len;
+  int32_t n, N, max_len, meta_stride;
 
-  __device__ __forceinline__ int32_t old_len(int32_t j) const { return len_old[j]; }
+  __device__ __forceinline__ int32_t old_len(int32_t j) const {
+    return meta_old[(int64_t)j * meta_stride];
+  }
   __device__ __forceinline__ int32_t new_len(int32_t j, int32_t old_j) const {
     if (n == 0) return old_j;
     int32_t c = sc ? sc[j] : n;
@@ -189,6 +195,9 @@ struct Slot {
 struct Lds {
   Slot table[kTableCap];
   Match match[kMatchCap];
+  int32_t win[kWinWords];       // per cached match: L continuation tokens, then their L probabilities
+  int32_t len_old[kLenCache];
+  int32_t len_new[kLenCache];
   Cand red[2][kScanBlock / kWave];
   int n_match;                  // total matches found (may exceed kMatchCap)
   int n_keys;                   // distinct keys in the table
@@ -221,66 +230,144 @@ struct Ctx {                    // one (problem, query path)
 struct GramHash {
   uint32_t h, step;
 };
-__device__ __forceinline__ GramHash gram_hash_begin(int g) { return GramHash{0x9E3779B9u * (uint32_t)g, 0u}; }
-__device__ __forceinline__ void gram_hash_add(u64& acc, int32_t token) {
+// The hash folds the gram's tokens newest first, so the hashes of all gram
+// lengths that end at one position come from one pass over the tokens.
+constexpr u64 kGramSeed = 0x243F6A8885A308D3ull;
+__device__ __forceinline__ u64 gram_hash_add(u64 acc, int32_t token) {
   acc = (acc ^ (u64)(uint32_t)token) * 0xD6E8FEB86659FD93ull;
-  acc ^= acc >> 32;
+  return acc ^ (acc >> 32);
 }
-__device__ __forceinline__ GramHash gram_hash_end(u64 acc) {
+__device__ __forceinline__ GramHash gram_hash_end(u64 acc, int g) {
+  acc ^= (u64)g * 0x9E3779B97F4A7C15ull;
   uint32_t a = mix_u64(acc);
   uint32_t b = mix_u64(acc ^ 0xA5A5A5A5A5A5A5A5ull);
   return GramHash{a, (b << 1) | 1u};
 }
-__device__ __forceinline__ const int32_t* gram_table(const int32_t* gram, int g, uint32_t mask) {
+__device__ __forceinline__ int32_t* gram_table(int32_t* gram, int g, uint32_t mask) {
   return gram + (int64_t)(g - 1) * ((int64_t)mask + 1) * kBucketWords;
 }
+__device__ __forceinline__ int32_t* gram_bucket(int32_t* tbl, GramHash gh, uint32_t r, uint32_t mask) {
+  return tbl + (int64_t)((gh.h + r * gh.step) & mask) * kBucketWords;
+}
 
-// Inserts posting `off` under hash gh of gram length g.  Bounded: at most
-// n_buckets attempts, and the tables hold more slots than there are positions.
-__device__ __forceinline__ void gram_insert(int32_t* gram, uint32_t mask, int g, GramHash gh,
-                                            int32_t off) {
-  int32_t* tbl = const_cast<int32_t*>(gram_table(gram, g, mask));
-  for (uint32_t r = 0; r <= mask; ++r) {
-    int32_t* b = tbl + (int64_t)((gh.h + r * gh.step) & mask) * kBucketWords;
-    int32_t c = atomicAdd(b, 1);
-    if (c < kBucketSlots) {
-      b[1 + c] = off;
-      return;
+// Slow path of an insert, by one whole wave: reads the fill counts of 64
+// buckets of the sequence per round trip, starting at bucket r0, and claims a
+// slot in the first one that is not full.  Bounded by the table size; the
+// tables hold more slots than there are positions.
+__device__ __forceinline__ void gram_insert_from(int32_t* tbl, uint32_t mask, GramHash gh,
+                                                 uint32_t r0, int32_t off, int lane) {
+  for (; r0 <= mask; r0 += kWave) {
+    uint32_t r = r0 + lane;
+    bool open = r <= mask && gram_bucket(tbl, gh, r, mask)[0] < kBucketSlots;
+    u64 m = __ballot(open);
+    while (m) {
+      uint32_t first = (uint32_t)__ffsll((long long)m) - 1u;
+      int32_t* b = gram_bucket(tbl, gh, r0 + first, mask);
+      int32_t c = 0;
+      if (lane == 0) c = atomicAdd(b, 1);
+      c = __builtin_amdgcn_readfirstlane(c);
+      if (c < kBucketSlots) {
+        if (lane == 0) b[1 + c] = off;
+        return;
+      }
+      m &= m - 1;                                   // filled up meanwhile: next open bucket
     }
   }
 }
 
-// Stores this row's share of the step (tokens, quantised probabilities, index
-// postings, new length).  Called by all threads of the row's workgroup.
+// Inserts the postings of position e of path i for every gram length
+// g = 1..kmax at once, by one whole wave.  Common case: two memory round trips
+// in total (64 fill counts per gram length in flight together, then one
+// atomic per gram length issued from different lanes).
+__device__ __forceinline__ void gram_insert_position(int32_t* gram, uint32_t mask, int32_t kmax,
+                                                     const Paths& y, int32_t i, int32_t e,
+                                                     int32_t old_i, int lane) {
+  GramHash gh[CSD_MAX_QUERY_LEN];
+  int32_t fill[CSD_MAX_QUERY_LEN];
+  u64 acc = kGramSeed;
+#pragma unroll
+  for (int g = 1; g <= CSD_MAX_QUERY_LEN; ++g) {
+    bool live = g <= kmax && g <= e;
+    acc = gram_hash_add(acc, live ? y.token(i, e - g, old_i) : 0);
+    gh[g - 1] = gram_hash_end(acc, g);
+    fill[g - 1] = kBucketSlots;
+    if (live && (uint32_t)lane <= mask)
+      fill[g - 1] = gram_bucket(gram_table(gram, g, mask), gh[g - 1], (uint32_t)lane, mask)[0];
+  }
+  // lane g-1 claims the slot for gram length g
+  int32_t my_first = -1;
+  GramHash my_gh{0u, 1u};
+#pragma unroll
+  for (int g = 1; g <= CSD_MAX_QUERY_LEN; ++g) {
+    u64 m = __ballot(fill[g - 1] < kBucketSlots);
+    if (lane == g - 1) {
+      my_first = m ? (int32_t)__ffsll((long long)m) - 1 : -1;
+      my_gh = gh[g - 1];
+    }
+  }
+  const int32_t off = i * y.max_len + e;
+  bool mine = lane < kmax && lane + 1 <= e;         // this lane's gram length exists
+  bool placed = !mine;
+  if (mine && my_first >= 0) {
+    int32_t* b = gram_bucket(gram_table(gram, lane + 1, mask), my_gh, (uint32_t)my_first, mask);
+    int32_t c = atomicAdd(b, 1);
+    if (c < kBucketSlots) {
+      b[1 + c] = off;
+      placed = true;
+    }
+  }
+  u64 todo = __ballot(!placed);                     // rare: long sequences, or lost a race
+  while (todo) {
+    int g = (int)__ffsll((long long)todo);          // lane index + 1 == gram length
+    todo &= todo - 1;
+    GramHash ghg;
+    ghg.h = (uint32_t)__builtin_amdgcn_readlane((int)my_gh.h, g - 1);
+    ghg.step = (uint32_t)__builtin_amdgcn_readlane((int)my_gh.step, g - 1);
+    int32_t from = __builtin_amdgcn_readlane(my_first, g - 1);
+    gram_insert_from(gram_table(gram, g, mask), mask, ghg, from < 0 ? kWave : (uint32_t)from, off,
+                     lane);
+  }
+}
+
 template <int BLOCK>
+__device__ __forceinline__ void block_sync() {
+  __syncthreads();   // a one-wave workgroup needs no hardware barrier: the compiler drops it
+}
+
+// Stores this row's share of the step (tokens, quantised probabilities, index
+// postings, new length and tail).  Called by all threads of the row's workgroup.
+template <int BLOCK, bool WITH_INDEX>
 __device__ __forceinline__ void append_row(const IndexView& ix, const Paths& y, int32_t p,
                                            int32_t i, int32_t old_i, int32_t new_i, int tid) {
   int64_t row = (int64_t)p * ix.N + i;
   int32_t cnt = new_i - old_i;
   uint32_t flags = 0;
+  // new meta row: word 0 = length, word 1+a = a-th token from the new end.  Every value is
+  // read before the barrier and written after it, so the row may be updated in place.
+  int32_t meta_val = 0;
+  if (tid == 0) meta_val = new_i;
+  else if (tid <= ix.kmax) {
+    int32_t a = tid - 1;
+    if (a < cnt) meta_val = y.st[(int64_t)i * y.n + cnt - 1 - a];
+    else if (a - cnt < ix.kmax && a < new_i) meta_val = y.meta_old[(int64_t)i * y.meta_stride + 1 + a - cnt];
+  }
   if (tid == 0) {
-    ix.len_new[row] = new_i;
     int32_t want = y.sc ? y.sc[i] : y.n;
     want = want < 0 ? 0 : (want > y.n ? y.n : want);
     if (want > cnt) flags |= CSD_STATUS_CAPACITY;
   }
+  block_sync<BLOCK>();
+  if (tid <= ix.kmax) ix.meta_new[row * ix.meta_stride + tid] = meta_val;
   for (int32_t t = tid; t < cnt; t += BLOCK) {
     int32_t v = y.st[(int64_t)i * y.n + t];
     if (v < 0 || v >= ix.vocab) flags |= CSD_STATUS_TOKEN_RANGE;
     ix.tok[row * ix.max_len + old_i + t] = v;
     ix.pq[row * ix.max_len + old_i + t] = y.sp ? quantize_prob(y.sp[(int64_t)i * y.n + t]) : 65536u;
   }
-  if (ix.gram) {
+  if (WITH_INDEX && ix.gram) {
     int32_t* gram = ix.gram + (int64_t)p * ix.kmax * ((int64_t)ix.bucket_mask + 1) * kBucketWords;
-    for (int32_t it = tid; it < cnt * ix.kmax; it += BLOCK) {
-      int32_t t = it / ix.kmax;
-      int32_t g = it - t * ix.kmax + 1;
-      int32_t e = old_i + t;                        // the new token is the successor
-      if (e < g) continue;                          // fewer than g tokens before it
-      u64 acc = gram_hash_begin(g).h;
-      for (int32_t a = g; a >= 1; --a) gram_hash_add(acc, y.token(i, e - a, old_i));
-      gram_insert(gram, ix.bucket_mask, g, gram_hash_end(acc), i * ix.max_len + e);
-    }
+    for (int32_t t = tid / kWave; t < cnt; t += BLOCK / kWave)     // one wave per new position
+      gram_insert_position(gram, ix.bucket_mask, ix.kmax, y, i, old_i + t, old_i, tid & 63);
   }
   if (flags) atomicOr(ix.status, flags);
 }
@@ -403,12 +490,12 @@ __device__ __forceinline__ void match_index(const Ctx& c, Sink& sink) {
     }
   }
   // (b) postings of earlier launches
-  u64 acc = gram_hash_begin(c.q).h;
+  u64 acc = kGramSeed;
 #pragma unroll
-  for (int a = CSD_MAX_QUERY_LEN - 1; a >= 0; --a)
-    if (a < c.q) gram_hash_add(acc, c.Q[a]);
-  GramHash gh = gram_hash_end(acc);
-  const int32_t* tbl = gram_table(c.gram, c.q, c.bucket_mask);
+  for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a)
+    if (a < c.q) acc = gram_hash_add(acc, c.Q[a]);
+  GramHash gh = gram_hash_end(acc, c.q);
+  const int32_t* tbl = gram_table(const_cast<int32_t*>(c.gram), c.q, c.bucket_mask);
   const int sub = lane & 15;          // word of the bucket this lane reads
   const int grp = lane >> 4;          // which of the 4 buckets of a batch
   uint32_t n_buckets = c.bucket_mask + 1;
@@ -444,11 +531,6 @@ __device__ __forceinline__ void match_index(const Ctx& c, Sink& sink) {
 }
 
 // ---------------------------------------------------------------- LDS hash table
-
-template <int BLOCK>
-__device__ __forceinline__ void block_sync() {
-  __syncthreads();   // a one-wave workgroup needs no hardware barrier: the compiler drops it
-}
 
 template <int BLOCK>
 __device__ __forceinline__ void table_clear(Lds& s, uint32_t mask, int tid) {
@@ -548,8 +630,14 @@ __device__ __forceinline__ bool layer_instance(const Ctx& c, Match m, int32_t d,
 
 // Eq. 5: every (match, layer) instance adds (1, p) to its edge (d,u,v) and to
 // its node (d,*,v).  Returns the table mask used.
+// Matches n_fresh .. n_fresh + win_cap - 1 of the list have their continuation cached in LDS.
+struct WinInfo {
+  int32_t n_fresh, win_cap;
+};
+
 template <int BLOCK>
-__device__ __forceinline__ uint32_t build_dag(Lds& s, const Ctx& c, int32_t M, int32_t L) {
+__device__ __forceinline__ uint32_t build_dag(Lds& s, const Ctx& c, int32_t M, int32_t L,
+                                              WinInfo wi) {
   uint32_t want = 4u * (uint32_t)M * (uint32_t)L;     // <= 50 % load without any merging
   uint32_t size = 64;
   while (size < want && size < (uint32_t)kTableCap) size <<= 1;
@@ -559,10 +647,22 @@ __device__ __forceinline__ uint32_t build_dag(Lds& s, const Ctx& c, int32_t M, i
   int32_t items = M * L;
   for (int32_t idx = c.tid; idx < items; idx += BLOCK) {
     int32_t d = idx / M + 1;
-    Match m = s.match[idx - (d - 1) * M];
+    int32_t mi = idx - (d - 1) * M;
+    Match m = s.match[mi];
     uint32_t u, v;
     u64 w;
-    if (layer_instance(c, m, d, u, v, w) && !s.overflow) {
+    bool alive;
+    int32_t ws = mi - wi.n_fresh;
+    if (ws >= 0 && ws < wi.win_cap) {                 // cached: no memory access
+      alive = d <= (int32_t)m.rem_new;
+      const int32_t* win = s.win + ws * 2 * L;
+      v = (uint32_t)win[d - 1];
+      u = d == 1 ? (uint32_t)c.Q[0] : (uint32_t)win[d - 2];
+      w = pack_cs(1u, (uint32_t)win[L + d - 1]);
+    } else {
+      alive = layer_instance(c, m, d, u, v, w);
+    }
+    if (alive && !s.overflow) {
       table_add(s, mask, dag_key(d, u, v), w);
       table_add(s, mask, dag_key(d, kAnyTok, v), w);
     }
@@ -678,7 +778,8 @@ __device__ __forceinline__ Ctx make_ctx(const IndexView& ix, const StepIn& in, i
   c.i = row - p * ix.N;
   c.y.tok = ix.tok + cells;
   c.y.pq = ix.pq + cells;
-  c.y.len_old = ix.len_old + (int64_t)p * ix.N;
+  c.y.meta_old = ix.meta_old + (int64_t)p * ix.N * ix.meta_stride;
+  c.y.meta_stride = ix.meta_stride;
   c.y.n = in.n;
   c.y.st = in.n ? in.tok + (int64_t)p * ix.N * in.n : nullptr;
   c.y.sp = (in.n && in.prob) ? in.prob + (int64_t)p * ix.N * in.n : nullptr;
@@ -697,7 +798,7 @@ __global__ __launch_bounds__(256) void reset_kernel(IndexView ix, int64_t gram_w
   int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
   int64_t stride = (int64_t)gridDim.x * 256;
   int64_t rows = (int64_t)ix.P * ix.N;
-  for (int64_t r = t; r < rows; r += stride) ix.len_new[r] = 0;
+  for (int64_t r = t; r < rows * ix.meta_stride; r += stride) ix.meta_new[r] = 0;
   for (int64_t w = t; w < gram_words; w += stride) ix.gram[w] = (w & (kBucketWords - 1)) ? -1 : 0;
   if (t == 0) *ix.status = 0u;
 }
@@ -709,9 +810,7 @@ __global__ __launch_bounds__(256) void append_kernel(IndexView ix, StepIn in) {
   Ctx c = make_ctx(ix, in, row, p);
   int32_t old_i = c.y.old_len(c.i);
   int32_t new_i = c.y.new_len(c.i, old_i);
-  // every thread has read the old length before thread 0 overwrites it (len_new may alias len_old)
-  __syncthreads();
-  append_row<256>(ix, c.y, p, c.i, old_i, new_i, c.tid);
+  append_row<256, true>(ix, c.y, p, c.i, old_i, new_i, c.tid);   // meta_new aliases meta_old here
 }
 
 struct DraftArgs {
@@ -739,7 +838,7 @@ __global__ __launch_bounds__(BLOCK) void draft_kernel(IndexView ix, StepIn in, D
   Ctx c = make_ctx(ix, in, row, p);
   int32_t old_i = c.y.old_len(c.i);
   c.len_i = c.y.new_len(c.i, old_i);
-  if (in.n > 0) append_row<BLOCK>(ix, c.y, p, c.i, old_i, c.len_i, c.tid);
+  if (in.n > 0) append_row<BLOCK, true>(ix, c.y, p, c.i, old_i, c.len_i, c.tid);
   load_query(c, a.k, old_i);
   if (c.tid == 0) s.n_match = 0;
   block_sync<BLOCK>();
@@ -754,7 +853,7 @@ __global__ __launch_bounds__(BLOCK) void draft_kernel(IndexView ix, StepIn in, D
     if (M > 0) {
       bool streaming = M > kMatchCap;
       if (!streaming) {
-        uint32_t mask = build_dag<BLOCK>(s, c, M, L);
+        uint32_t mask = build_dag<BLOCK>(s, c, M, L, WinInfo{M, 0});
         streaming = s.overflow != 0;
         if (!streaming) walk_dag<BLOCK>(s, c, mask, L, a.alpha_q, a.score_mode, o);
       }
@@ -778,6 +877,324 @@ __global__ __launch_bounds__(BLOCK) void draft_kernel(IndexView ix, StepIn in, D
   }
 }
 
+
+// ---------------------------------------------------------------- the one-wave step kernel
+//
+// Index mode runs one wave64 per (problem, path).  The step is a chain of
+// dependent memory round trips, and each launch starts with a cold L2 (the XCDs'
+// L2s are not coherent with each other across launches), so the kernel is laid
+// out to need only three of them before the LDS work:
+//   1. the meta rows (length + last tokens) of all paths and the step's input:
+//      the query, the index hashes and the matches among the newest positions
+//      all follow from these without touching the histories;
+//   2. the index buckets of the query (and the fill counts for the inserts);
+//   3. for every posting found, its verify tokens together with its whole
+//      continuation (tokens and probabilities), kept in LDS for the DAG build.
+
+struct Head {                   // a path's end before this step
+  int32_t old_len, new_len;
+  int32_t tail[CSD_MAX_QUERY_LEN];   // tail[a] = a-th token from the old end
+};
+
+__device__ __forceinline__ int32_t pick(const int32_t (&arr)[CSD_MAX_QUERY_LEN], int32_t idx) {
+  int32_t r = 0;
+#pragma unroll
+  for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) r = (idx == a) ? arr[a] : r;
+  return r;
+}
+
+__device__ __forceinline__ Head load_head(const Paths& y, int32_t kmax, int32_t j) {
+  Head h;
+  const int4* m = reinterpret_cast<const int4*>(y.meta_old + (int64_t)j * y.meta_stride);
+  int4 a = m[0];
+  int4 b = kmax > 3 ? m[1] : int4{0, 0, 0, 0};
+  int32_t c = kmax > 7 ? y.meta_old[(int64_t)j * y.meta_stride + 8] : 0;
+  h.old_len = a.x;
+  h.tail[0] = a.y; h.tail[1] = a.z; h.tail[2] = a.w;
+  h.tail[3] = b.x; h.tail[4] = b.y; h.tail[5] = b.z; h.tail[6] = b.w;
+  h.tail[7] = c;
+  h.new_len = y.new_len(j, h.old_len);
+  return h;
+}
+
+// Split-phase insert of ONE new position into all kmax tables: lanes 8g-8..8g-1
+// look at the first 8 buckets of gram length g's sequence.
+struct InsertTicket {
+  GramHash gh;                  // of this lane's gram length
+  int32_t fill;                 // fill count of bucket (lane & 7) of that sequence
+  int32_t first;                // first open bucket among the 8, or -1
+  int32_t claimed;              // slot the leader lane got from the atomic, or kBucketSlots
+  bool live;                    // this lane's gram length exists at this position
+};
+
+// Phase 1: hashes of the grams that end just before the new position (they are
+// the old tail) and the fill-count loads.
+__device__ __forceinline__ InsertTicket insert_begin(int32_t* gram, uint32_t mask, int32_t kmax,
+                                                     const Head& me, int lane) {
+  InsertTicket t;
+  const int g = (lane >> 3) + 1;
+  t.gh = GramHash{0u, 1u};
+  u64 acc = kGramSeed;
+#pragma unroll
+  for (int a = 1; a <= CSD_MAX_QUERY_LEN; ++a) {
+    acc = gram_hash_add(acc, me.tail[a - 1]);
+    GramHash gh = gram_hash_end(acc, a);
+    if (a == g) t.gh = gh;
+  }
+  t.live = g <= kmax && g <= me.old_len;
+  t.fill = kBucketSlots;
+  t.first = -1;
+  t.claimed = kBucketSlots;
+  uint32_t r = (uint32_t)(lane & 7);
+  if (t.live && r <= mask) t.fill = gram_bucket(gram_table(gram, g, mask), t.gh, r, mask)[0];
+  return t;
+}
+
+// Phase 2: the leader lane of each gram length claims a slot in the first open bucket.
+__device__ __forceinline__ void insert_claim(InsertTicket& t, int32_t* gram, uint32_t mask,
+                                             int lane) {
+  u64 open = __ballot(t.fill < kBucketSlots);
+  uint32_t mine = (uint32_t)(open >> (lane & ~7)) & 0xFFu;
+  t.first = mine ? (int32_t)__ffs((int)mine) - 1 : -1;
+  if (t.live && (lane & 7) == 0 && t.first >= 0)
+    t.claimed = atomicAdd(gram_bucket(gram_table(gram, (lane >> 3) + 1, mask), t.gh,
+                                      (uint32_t)t.first, mask), 1);
+}
+
+// Phase 3: store the posting; gram lengths whose first 8 buckets were full (or
+// that lost a race for the last slot) take the general wave-wide insert.
+__device__ __forceinline__ void insert_finish(const InsertTicket& t, int32_t* gram, uint32_t mask,
+                                              int32_t off, int lane) {
+  bool leader = t.live && (lane & 7) == 0;
+  bool placed = !leader;
+  if (leader && t.claimed < kBucketSlots) {
+    gram_bucket(gram_table(gram, (lane >> 3) + 1, mask), t.gh, (uint32_t)t.first, mask)[1 + t.claimed] = off;
+    placed = true;
+  }
+  u64 todo = __ballot(!placed);
+  while (todo) {
+    int src = (int)__ffsll((long long)todo) - 1;     // a leader lane: gram length src/8 + 1
+    todo &= todo - 1;
+    GramHash gh;
+    gh.h = (uint32_t)__builtin_amdgcn_readlane((int)t.gh.h, src);
+    gh.step = (uint32_t)__builtin_amdgcn_readlane((int)t.gh.step, src);
+    int32_t from = __builtin_amdgcn_readlane(t.first, src);
+    gram_insert_from(gram_table(gram, (src >> 3) + 1, mask), mask, gh, from < 0 ? 8u : (uint32_t)from,
+                     off, lane);
+  }
+}
+
+// Lengths of path j: from the LDS cache for the first kLenCache paths.
+__device__ __forceinline__ void lens_of(const Lds& s, const Paths& y, int32_t j, int32_t& old_j,
+                                        int32_t& new_j) {
+  if (j < kLenCache) {
+    old_j = s.len_old[j];
+    new_j = s.len_new[j];
+  } else {
+    old_j = y.old_len(j);
+    new_j = y.new_len(j, old_j);
+  }
+}
+
+// Appends the hits of all 64 lanes to the match list (one wave: the count lives
+// in a register).  Returns each hit's slot, -1 for lanes without one.
+__device__ __forceinline__ int32_t wave_push(Lds& s, int32_t& n_match, bool hit, Match m, int lane) {
+  u64 mask = __ballot(hit);
+  int32_t slot = n_match + (int32_t)__popcll(mask & ((1ull << lane) - 1ull));
+  n_match += (int32_t)__popcll(mask);
+  if (!hit) return -1;
+  if (slot < kMatchCap) s.match[slot] = m;
+  return slot;
+}
+
+// Eq. 3 through the hash index with the continuations fetched in the same
+// round trip as the verification.  Adds its hits behind the n_fresh matches
+// already listed; hit number x (0-based among these) gets window x.
+template <int LCAP>
+__device__ __forceinline__ void lookup_with_windows(Lds& s, const Ctx& c, int32_t L,
+                                                    int32_t win_cap, int32_t n_fresh,
+                                                    int32_t& n_match, GramHash gh, int32_t word) {
+  const int lane = c.tid;
+  const int32_t* tbl = gram_table(const_cast<int32_t*>(c.gram), c.q, c.bucket_mask);
+  const int sub = lane & 15;          // word of the bucket this lane reads
+  const int grp = lane >> 4;          // which of the 4 buckets of a batch
+  const uint32_t n_buckets = c.bucket_mask + 1;
+  for (uint32_t r0 = 0; r0 < n_buckets; r0 += 4) {
+    int32_t count = __shfl(word, lane & ~15);
+    bool full = count >= kBucketSlots;
+    bool seq_ends = __ballot(!full || r0 + grp >= n_buckets) != 0;
+    int32_t next_word = -1;           // next batch: in flight while this one is processed
+    if (!seq_ends && r0 + 4 + grp < n_buckets)
+      next_word = gram_bucket(const_cast<int32_t*>(tbl), gh, r0 + 4 + grp, c.bucket_mask)[sub];
+    bool cand = sub >= 1 && word >= 0 && (sub - 1) < (full ? kBucketSlots : count);
+    int32_t j = 0, e = 0, old_j = 0, new_j = 0;
+    if (cand) {
+      j = word / c.y.max_len;
+      e = word - j * c.y.max_len;
+      cand = j != c.i && j < c.y.N;
+    }
+    if (cand) {
+      lens_of(s, c.y, j, old_j, new_j);
+      cand = e < old_j;               // newer positions are matched directly, not looked up
+    }
+    int32_t wv[LCAP];
+    uint32_t wp[LCAP];
+    bool hit = cand;
+    int32_t rem = 0;
+    if (cand) {
+      const int32_t* row = c.y.tok + (int64_t)j * c.y.max_len;
+      int32_t tv[CSD_MAX_QUERY_LEN];
+#pragma unroll
+      for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) tv[a] = (a < c.q) ? row[e - 1 - a] : 0;
+      rem = new_j - e;
+      rem = rem < L ? rem : L;
+#pragma unroll
+      for (int d = 0; d < LCAP; ++d) {
+        wv[d] = 0;
+        wp[d] = 0;
+        if (d < rem) {
+          wv[d] = c.y.token(j, e + d, old_j);
+          wp[d] = c.y.prob(j, e + d, old_j);
+        }
+      }
+#pragma unroll
+      for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) hit = hit && (a >= c.q || tv[a] == c.Q[a]);
+    }
+    int32_t slot = wave_push(s, n_match, hit, make_match(c, j, e, old_j, new_j), lane);
+    int32_t w = slot - n_fresh;
+    if (slot >= 0 && w < win_cap) {
+      int32_t* win = s.win + w * 2 * L;
+#pragma unroll
+      for (int d = 0; d < LCAP; ++d)
+        if (d < rem) {
+          win[d] = wv[d];
+          win[L + d] = (int32_t)wp[d];
+        }
+    }
+    if (seq_ends) break;
+    word = next_word;
+  }
+}
+
+// The front end of a row handled by one wave: round trip 1 (heads, query, own
+// append), matches among the newest positions, index lookup with windows.
+// Returns the number of matches; wi tells build_dag which of them have windows.
+template <int LCAP>
+__device__ __forceinline__ int32_t wave_front_end(Lds& s, Ctx& c, const IndexView& ix, int32_t p,
+                                                  int32_t k, int32_t L, WinInfo& wi,
+                                                  InsertTicket& ticket, bool& ticket_used) {
+  const int lane = c.tid;
+  const Paths& y = c.y;
+  Head me = load_head(y, ix.kmax, c.i);                 // same address in every lane
+  const int32_t old_i = me.old_len, cnt_i = me.new_len - me.old_len;
+  c.len_i = me.new_len;
+  c.q = k < c.len_i ? k : c.len_i;
+#pragma unroll
+  for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) {
+    int32_t v = 0;
+    if (a < c.q) v = a < cnt_i ? y.st[(int64_t)c.i * y.n + cnt_i - 1 - a] : pick(me.tail, a - cnt_i);
+    c.Q[a] = v;
+  }
+  int32_t* gram = const_cast<int32_t*>(c.gram);
+  ticket_used = false;
+  if (y.n > 0) {        // also when this path takes no token: its meta row moves to the new buffer
+    append_row<kWave, false>(ix, y, p, c.i, old_i, me.new_len, lane);   // index part: below
+    if (cnt_i == 1) {
+      ticket = insert_begin(gram, c.bucket_mask, ix.kmax, me, lane);
+      ticket_used = true;
+    } else {
+      for (int32_t t = 0; t < cnt_i; ++t)
+        gram_insert_position(gram, c.bucket_mask, ix.kmax, y, c.i, old_i + t, old_i, lane);
+    }
+  }
+  // first batch of index buckets of the query (round trip 2, together with the fill counts)
+  GramHash gh{0u, 1u};
+  int32_t word = -1;
+  if (c.q > 0) {
+    u64 acc = kGramSeed;
+#pragma unroll
+    for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a)
+      if (a < c.q) acc = gram_hash_add(acc, c.Q[a]);
+    gh = gram_hash_end(acc, c.q);
+    if ((uint32_t)(lane >> 4) <= c.bucket_mask)
+      word = gram_bucket(gram_table(gram, c.q, c.bucket_mask), gh, (uint32_t)(lane >> 4),
+                         c.bucket_mask)[lane & 15];
+  }
+  // heads of all paths: lengths into LDS, matches among the positions appended by this launch
+  int32_t n_match = 0;
+  for (int32_t j0 = 0; j0 < y.N; j0 += kWave) {
+    int32_t j = j0 + lane;
+    bool have = j < y.N;
+    Head hj = load_head(y, ix.kmax, have ? j : 0);
+    if (have && j < kLenCache) {
+      s.len_old[j] = hj.old_len;
+      s.len_new[j] = hj.new_len;
+    }
+    bool live = have && j != c.i && c.q > 0;
+    if (y.n == 1) {                         // the usual decode step: compare the old tail
+      bool hit = live && hj.new_len > hj.old_len && hj.old_len >= c.q;
+#pragma unroll
+      for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) hit = hit && (a >= c.q || hj.tail[a] == c.Q[a]);
+      wave_push(s, n_match, hit, make_match(c, j, hj.old_len, hj.old_len, hj.new_len), lane);
+    } else {
+      for (int32_t t = 0; t < y.n; ++t) {
+        int32_t e = hj.old_len + t;
+        bool hit = live && e < hj.new_len && e >= c.q && gram_equals_query(c, j, e, hj.old_len);
+        wave_push(s, n_match, hit, make_match(c, j, e, hj.old_len, hj.new_len), lane);
+      }
+    }
+  }
+  if (ticket_used) insert_claim(ticket, gram, c.bucket_mask, lane);
+  wi.n_fresh = n_match;
+  wi.win_cap = kWinWords / (2 * L);
+  if (c.q > 0) lookup_with_windows<LCAP>(s, c, L, wi.win_cap, wi.n_fresh, n_match, gh, word);
+  if (lane == 0) s.n_match = n_match;
+  return n_match;
+}
+
+template <int LCAP>
+__global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn in, DraftArgs a) {
+  __shared__ Lds s;
+  int32_t row = xcd_row(ix.P * ix.N);
+  if (row < 0) return;
+  int32_t p;
+  Ctx c = make_ctx(ix, in, row, p);
+  const int32_t L = a.L;
+  int32_t target = (a.targets && c.tid < L) ? a.targets[(int64_t)row * L + c.tid] : 0;
+  WinInfo wi;
+  InsertTicket ticket;
+  bool ticket_used;
+  int32_t M = wave_front_end<LCAP>(s, c, ix, p, a.k, L, wi, ticket, ticket_used);
+  block_sync<kWave>();
+
+  DraftOut o;
+  if (M > 0) {
+    bool streaming = M > kMatchCap;
+    if (!streaming) {
+      uint32_t mask = build_dag<kWave>(s, c, M, L, wi);
+      streaming = s.overflow != 0;
+      if (!streaming) walk_dag<kWave>(s, c, mask, L, a.alpha_q, a.score_mode, o);
+    }
+    if (streaming) walk_streaming<kWave, true>(s, c, M, L, a.alpha_q, a.score_mode, ix.status, o);
+  }
+  bool live = c.tid < o.n;
+  if (c.tid < L) {
+    a.draft_tokens[(int64_t)row * L + c.tid] = live ? o.tok : -1;
+    if (a.token_scores) a.token_scores[(int64_t)row * L + c.tid] = live ? key_to_score(o.key) : 0.0f;
+  }
+  if (c.tid == 0) {
+    a.draft_len[row] = o.n;
+    if (a.path_scores) a.path_scores[row] = key_to_score(o.key_sum);
+  }
+  if (a.targets) {                      // "Draft acceptance": first lane whose token differs
+    u64 differs = __ballot(!(live && target == o.tok));
+    if (c.tid == 0) a.accept_len[row] = differs ? (int32_t)__ffsll((long long)differs) - 1 : kWave;
+  }
+  if (ticket_used)
+    insert_finish(ticket, const_cast<int32_t*>(c.gram), c.bucket_mask,
+                  c.i * ix.max_len + (c.len_i - 1), c.tid);
+}
+
 __global__ __launch_bounds__(256) void accept_kernel(int64_t rows, int32_t L,
                                                      const int32_t* draft_tokens,
                                                      const int32_t* draft_len,
@@ -789,6 +1206,14 @@ __global__ __launch_bounds__(256) void accept_kernel(int64_t rows, int32_t L,
   int32_t a = 0;
   while (a < n && draft_tokens[r * L + a] == targets[r * L + a]) ++a;
   accept_len[r] = a;
+}
+
+// Plain copy of n 16-byte words: the known-size kernel that hardware traffic
+// counters are calibrated against.
+__global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ src,
+                                                   uint4* __restrict__ dst, int64_t n) {
+  int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x; x < n; x += stride) dst[x] = src[x];
 }
 
 // ---- debug dumps ------------------------------------------------------------
@@ -806,6 +1231,28 @@ __global__ __launch_bounds__(BLOCK) void dump_match_bits_kernel(IndexView ix, St
   if (c.q <= 0) return;
   BitmapSink sink{bits + (int64_t)row * words};
   find_matches<BLOCK, INDEXED>(c, sink);
+}
+
+// Index mode: the matches as the step kernel's own front end finds them.
+__global__ __launch_bounds__(kWave) void dump_match_bits_wave_kernel(IndexView ix, StepIn in,
+                                                                     int32_t k, uint32_t* bits,
+                                                                     int32_t words) {
+  __shared__ Lds s;
+  int32_t row = xcd_row(ix.P * ix.N);
+  if (row < 0) return;
+  int32_t p;
+  Ctx c = make_ctx(ix, in, row, p);   // in.n == 0: nothing is being appended
+  WinInfo wi;
+  InsertTicket ticket;
+  bool ticket_used;
+  int32_t M = wave_front_end<8>(s, c, ix, p, k, 1, wi, ticket, ticket_used);
+  block_sync<kWave>();
+  BitmapSink sink{bits + (int64_t)row * words};
+  if (M <= kMatchCap) {
+    for (int32_t m = c.tid; m < M; m += kWave) sink.push(true, s.match[m]);
+  } else if (c.q > 0) {
+    match_index(c, sink);
+  }
 }
 
 // counts[row] = number of set bits of the row (one workgroup per row)
@@ -871,6 +1318,27 @@ __global__ __launch_bounds__(64) void expand_bits_kernel(const uint32_t* bits, i
 // Builds the tier-1 DAG tables of a row exactly as draft_kernel does and writes
 // the edge entries, sorted by key, to tmp rows of kTableCap entries.
 // counts[row] = number of edges, or -1 if the row needs the streaming tier.
+// Writes the edge entries of a finished tier-1 table, sorted by key, to the row's tmp slots.
+template <int BLOCK>
+__device__ __forceinline__ void emit_sorted_edges(Lds& s, uint32_t mask, int tid, int* n_edges,
+                                                  u64* ok, u64* ov) {
+  for (uint32_t h = tid; h <= mask; h += BLOCK) {
+    u64 key = s.table[h].key;
+    if (key == kEmpty || ((key >> 29) & kTokMask) == kAnyTok) continue;
+    int rank = 0;                                     // keys are distinct: rank = sorted position
+    for (uint32_t g = 0; g <= mask; ++g) {
+      u64 other = s.table[g].key;
+      if (other != kEmpty && ((other >> 29) & kTokMask) != kAnyTok && other < key) ++rank;
+    }
+    ok[rank] = key;
+    ov[rank] = s.table[h].val;
+    atomicAdd(n_edges, 1);
+  }
+}
+
+// Builds the tier-1 DAG tables of a row exactly as the step kernels do and writes
+// the edge entries, sorted by key, to tmp rows of kTableCap entries.
+// counts[row] = number of edges, or -1 if the row needs the streaming tier.
 template <int BLOCK, bool INDEXED>
 __global__ __launch_bounds__(BLOCK) void dump_edge_rows_kernel(IndexView ix, StepIn in, int32_t k,
                                                                int32_t L, u64* tmp_keys,
@@ -893,23 +1361,39 @@ __global__ __launch_bounds__(BLOCK) void dump_edge_rows_kernel(IndexView ix, Ste
   int32_t M = s.n_match;
   if (M == 0) { if (c.tid == 0) counts[row] = 0; return; }
   if (M > kMatchCap) { if (c.tid == 0) counts[row] = -1; return; }
-  uint32_t mask = build_dag<BLOCK>(s, c, M, L);
+  uint32_t mask = build_dag<BLOCK>(s, c, M, L, WinInfo{M, 0});
   if (s.overflow) { if (c.tid == 0) counts[row] = -1; return; }
-  u64* ok = tmp_keys + (int64_t)row * kTableCap;
-  u64* ov = tmp_vals + (int64_t)row * kTableCap;
-  for (uint32_t h = c.tid; h <= mask; h += BLOCK) {
-    u64 key = s.table[h].key;
-    if (key == kEmpty || ((key >> 29) & kTokMask) == kAnyTok) continue;
-    int rank = 0;                                     // keys are distinct: rank = sorted position
-    for (uint32_t g = 0; g <= mask; ++g) {
-      u64 other = s.table[g].key;
-      if (other != kEmpty && ((other >> 29) & kTokMask) != kAnyTok && other < key) ++rank;
-    }
-    ok[rank] = key;
-    ov[rank] = s.table[h].val;
-    atomicAdd(&n_edges, 1);
-  }
+  emit_sorted_edges<BLOCK>(s, mask, c.tid, &n_edges, tmp_keys + (int64_t)row * kTableCap,
+                           tmp_vals + (int64_t)row * kTableCap);
   block_sync<BLOCK>();
+  if (c.tid == 0) counts[row] = n_edges;
+}
+
+// Index mode: front end and DAG build of the step kernel itself.
+template <int LCAP>
+__global__ __launch_bounds__(kWave) void dump_edge_rows_wave_kernel(IndexView ix, StepIn in,
+                                                                    int32_t k, int32_t L,
+                                                                    u64* tmp_keys, u64* tmp_vals,
+                                                                    int32_t* counts) {
+  __shared__ Lds s;
+  __shared__ int n_edges;
+  int32_t row = xcd_row(ix.P * ix.N);
+  if (row < 0) return;
+  int32_t p;
+  Ctx c = make_ctx(ix, in, row, p);   // in.n == 0: nothing is being appended
+  if (c.tid == 0) n_edges = 0;
+  WinInfo wi;
+  InsertTicket ticket;
+  bool ticket_used;
+  int32_t M = wave_front_end<LCAP>(s, c, ix, p, k, L, wi, ticket, ticket_used);
+  block_sync<kWave>();
+  if (M == 0) { if (c.tid == 0) counts[row] = 0; return; }
+  if (M > kMatchCap) { if (c.tid == 0) counts[row] = -1; return; }
+  uint32_t mask = build_dag<kWave>(s, c, M, L, wi);
+  if (s.overflow) { if (c.tid == 0) counts[row] = -1; return; }
+  emit_sorted_edges<kWave>(s, mask, c.tid, &n_edges, tmp_keys + (int64_t)row * kTableCap,
+                           tmp_vals + (int64_t)row * kTableCap);
+  block_sync<kWave>();
   if (c.tid == 0) counts[row] = n_edges;
 }
 
@@ -951,7 +1435,8 @@ constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-  size_t tok, pq, len, status, gram, total;
+  size_t tok, pq, meta, status, gram, total;
+  int32_t meta_stride;
   uint32_t n_buckets;           // per (problem, gram length); 0 in scan mode
   size_t gram_words;
 };
@@ -979,7 +1464,8 @@ Layout make_layout(const csd_config* c) {
   size_t at = 0;
   l.tok = at;    at += align_up(cells * sizeof(int32_t));
   l.pq = at;     at += align_up(cells * sizeof(uint32_t));
-  l.len = at;    at += align_up(2 * rows * sizeof(int32_t));
+  l.meta_stride = (1 + c->max_query_len + 3) / 4 * 4;
+  l.meta = at;   at += 2 * align_up(rows * l.meta_stride * sizeof(int32_t));
   l.status = at; at += align_up(4 * sizeof(uint32_t));
   l.n_buckets = 0;
   l.gram_words = 0;
@@ -1007,8 +1493,8 @@ uint32_t to_alpha_q(float alpha) {
 
 struct csd_index {
   csd_config cfg;
-  IndexView view;               // len_old / len_new are filled per launch
-  int32_t* len[2];              // double-buffered lengths; `cur` is the valid one
+  IndexView view;               // meta_old / meta_new are filled per launch
+  int32_t* meta[2];             // double-buffered path ends (length + tail); `cur` is valid
   int cur;
   size_t gram_words;
   bool indexed;
@@ -1021,8 +1507,8 @@ hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
 IndexView view_in_place(const csd_index* h) {     // lengths read and written in the same buffer
   IndexView v = h->view;
-  v.len_old = h->len[h->cur];
-  v.len_new = h->len[h->cur];
+  v.meta_old = h->meta[h->cur];
+  v.meta_new = h->meta[h->cur];
   return v;
 }
 
@@ -1035,10 +1521,14 @@ int check_draft_args(const csd_index* h, int32_t query_len, int32_t draft_len) {
 void launch_draft(const csd_index* h, const IndexView& v, const StepIn& in, const DraftArgs& a,
                   hipStream_t st) {
   int64_t rows = (int64_t)v.P * v.N;
-  if (h->indexed)
-    draft_kernel<kWave, true><<<xcd_grid(rows), kWave, 0, st>>>(v, in, a);
-  else
+  if (!h->indexed)
     draft_kernel<kScanBlock, false><<<xcd_grid(rows), kScanBlock, 0, st>>>(v, in, a);
+  else if (a.L <= 8)
+    step_wave_kernel<8><<<xcd_grid(rows), kWave, 0, st>>>(v, in, a);
+  else if (a.L <= 16)
+    step_wave_kernel<16><<<xcd_grid(rows), kWave, 0, st>>>(v, in, a);
+  else
+    step_wave_kernel<32><<<xcd_grid(rows), kWave, 0, st>>>(v, in, a);
 }
 
 // Host-side bookkeeping shared by csd_append and csd_step.
@@ -1078,11 +1568,13 @@ int csd_create(const csd_config* cfg, void* d_workspace, size_t workspace_bytes,
   size_t rows = (size_t)cfg->n_problems * cfg->n_paths;
   h->view.tok = reinterpret_cast<int32_t*>(base + l.tok);
   h->view.pq = reinterpret_cast<uint32_t*>(base + l.pq);
-  h->len[0] = reinterpret_cast<int32_t*>(base + l.len);
-  h->len[1] = h->len[0] + rows;
+  h->meta[0] = reinterpret_cast<int32_t*>(base + l.meta);
+  h->meta[1] = reinterpret_cast<int32_t*>(base + l.meta +
+                                          align_up(rows * l.meta_stride * sizeof(int32_t)));
   h->cur = 0;
-  h->view.len_old = h->len[0];
-  h->view.len_new = h->len[0];
+  h->view.meta_old = h->meta[0];
+  h->view.meta_new = h->meta[0];
+  h->view.meta_stride = l.meta_stride;
   h->view.status = reinterpret_cast<uint32_t*>(base + l.status);
   h->indexed = uses_index(cfg);
   h->view.gram = h->indexed ? reinterpret_cast<int32_t*>(base + l.gram) : nullptr;
@@ -1111,7 +1603,7 @@ int csd_destroy(csd_index* index) {
 
 int csd_reset(csd_index* h, void* stream) {
   if (!h) return CSD_ERR_INVALID_ARG;
-  int64_t work = (int64_t)h->view.P * h->view.N;
+  int64_t work = (int64_t)h->view.P * h->view.N * h->view.meta_stride;
   if ((int64_t)h->gram_words > work) work = (int64_t)h->gram_words;
   int64_t blocks = (work + 255) / 256;
   if (blocks > 4096) blocks = 4096;
@@ -1171,8 +1663,8 @@ int csd_step(csd_index* h, const int32_t* d_tokens, const float* d_probs, const 
   rc = note_append(h, d_counts != nullptr, n);
   if (rc != CSD_OK) return rc;
   IndexView v = h->view;
-  v.len_old = h->len[h->cur];
-  v.len_new = h->len[h->cur ^ 1];
+  v.meta_old = h->meta[h->cur];
+  v.meta_new = h->meta[h->cur ^ 1];
   DraftArgs a{query_len, draft_len, h->alpha_q, h->cfg.score_mode, d_draft_tokens, d_draft_len,
               d_token_scores, d_path_scores, d_targets, d_accept_len};
   launch_draft(h, v, StepIn{d_tokens, d_probs, d_counts, n}, a, as_stream(stream));
@@ -1242,8 +1734,8 @@ int csd_dump_matches(csd_index* h, int32_t query_len, int32_t* d_match_je, int32
     e = hipMemsetAsync(bits, 0, (size_t)rows * words * sizeof(uint32_t), st);
     if (e != hipSuccess) break;
     if (h->indexed)
-      dump_match_bits_kernel<kWave, true><<<xcd_grid(rows), kWave, 0, st>>>(v, no_step, query_len,
-                                                                            bits, words);
+      dump_match_bits_wave_kernel<<<xcd_grid(rows), kWave, 0, st>>>(v, no_step, query_len, bits,
+                                                                    words);
     else
       dump_match_bits_kernel<kScanBlock, false><<<xcd_grid(rows), kScanBlock, 0, st>>>(
           v, no_step, query_len, bits, words);
@@ -1282,8 +1774,14 @@ int csd_dump_edges(csd_index* h, int32_t query_len, int32_t draft_len, int32_t* 
   IndexView v = view_in_place(h);
   const StepIn no_step{nullptr, nullptr, nullptr, 0};
   do {
-    if (h->indexed)
-      dump_edge_rows_kernel<kWave, true><<<xcd_grid(rows), kWave, 0, st>>>(
+    if (h->indexed && draft_len <= 8)
+      dump_edge_rows_wave_kernel<8><<<xcd_grid(rows), kWave, 0, st>>>(
+          v, no_step, query_len, draft_len, tmp, tmp + tmp_elems, counts);
+    else if (h->indexed && draft_len <= 16)
+      dump_edge_rows_wave_kernel<16><<<xcd_grid(rows), kWave, 0, st>>>(
+          v, no_step, query_len, draft_len, tmp, tmp + tmp_elems, counts);
+    else if (h->indexed)
+      dump_edge_rows_wave_kernel<32><<<xcd_grid(rows), kWave, 0, st>>>(
           v, no_step, query_len, draft_len, tmp, tmp + tmp_elems, counts);
     else
       dump_edge_rows_kernel<kScanBlock, false><<<xcd_grid(rows), kScanBlock, 0, st>>>(
@@ -1303,6 +1801,20 @@ int csd_dump_edges(csd_index* h, int32_t query_len, int32_t draft_len, int32_t* 
   (void)hipFree(counts);
   if (e != hipSuccess) return hip_fail(e, "csd_dump_edges");
   if ((int64_t)tail[0] > cap || tail[1] != 0) return CSD_ERR_CAPACITY;
+  return CSD_OK;
+}
+
+int csd_debug_copy(void* d_dst, const void* d_src, size_t bytes, void* stream) {
+  if (!d_dst || !d_src || bytes % 16 != 0) return CSD_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(d_dst) | reinterpret_cast<uintptr_t>(d_src)) % 16 != 0)
+    return CSD_ERR_INVALID_ARG;
+  int64_t n = (int64_t)(bytes / 16);
+  if (n == 0) return CSD_OK;
+  int64_t blocks = (n + 255) / 256;
+  if (blocks > 8192) blocks = 8192;
+  copy_kernel<<<(uint32_t)blocks, 256, 0, as_stream(stream)>>>(
+      static_cast<const uint4*>(d_src), static_cast<uint4*>(d_dst), n);
+  CSD_HIP(hipGetLastError());
   return CSD_OK;
 }
 
