@@ -1,0 +1,307 @@
+// csd — shared device definitions: constants, exact fixed-point weights,
+// wavefront reductions and the device-side view of the index state.
+//
+// Method: "Speculative Decoding for Multi-Sample Inference" — suffix match
+// across paths (Eq. 3), layered token DAG with aggregated edge weights (Eq. 5),
+// greedy layer-wise extraction (rule after Eq. 5, Algorithm 1).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <climits>
+#include <cstdint>
+
+#include "csd.h"
+
+namespace csd {
+
+typedef unsigned long long u64;
+
+constexpr int kWave = 64;
+constexpr int kScanBlock = 256;             // threads per row when matches come from a scan
+constexpr int kMatchCap = 1024;             // matches kept in LDS; beyond -> streaming tier
+constexpr int kTableCap = 1024;             // LDS hash slots for DAG edges + nodes
+constexpr int kWinWords = 2048;             // LDS words for cached continuations of matches
+constexpr int kLenCache = 256;              // path lengths cached in LDS (more paths: read memory)
+constexpr uint32_t kTokMask = (1u << 29) - 1;
+constexpr uint32_t kAnyTok = kTokMask;      // "any predecessor": marks node (in-weight) entries
+constexpr u64 kEmpty = ~0ull;
+constexpr int kMaxClassBits = 20;           // streaming tier: at most 2^20 token classes
+constexpr int kBucketWords = 16;            // one 64-byte line: [count, 15 postings]
+constexpr int kBucketSlots = kBucketWords - 1;
+
+// ---------------------------------------------------------------- exact weights
+
+// DAG table key: layer d (6 bits) | predecessor u (29) | token v (29).
+__device__ __forceinline__ u64 dag_key(int d, uint32_t u, uint32_t v) {
+  return ((u64)d << 58) | ((u64)(u & kTokMask) << 29) | (u64)(v & kTokMask);
+}
+__device__ __forceinline__ uint32_t key_v(u64 key) { return (uint32_t)key & kTokMask; }
+__device__ __forceinline__ uint32_t key_u(u64 key) { return (uint32_t)(key >> 29) & kTokMask; }
+// Slot hash of a key: two 32-bit multiplies, high bits folded down.
+__device__ __forceinline__ uint32_t dag_hash(u64 key) {
+  uint32_t h = (uint32_t)key * 0x9E3779B1u ^ (uint32_t)(key >> 29) * 0x85EBCA6Bu;
+  return h ^ (h >> 15);
+}
+// Eq. 5's two sums in one word: count C (high 24 bits) and probability sum S
+// in 1/65536 units (low 40 bits).  N*max_len <= 2^24 keeps both in range.
+__device__ __forceinline__ u64 pack_cs(uint32_t c, u64 s) { return ((u64)c << 40) | s; }
+__device__ __forceinline__ u64 cs_count(u64 w) { return w >> 40; }
+__device__ __forceinline__ u64 cs_sum(u64 w) { return w & ((1ull << 40) - 1); }
+
+// weight * 2^32 = alpha_q * S + (65536 - alpha_q) * C * 65536   (Eq. 5, fixed point)
+__device__ __forceinline__ u64 weight_key(u64 w, uint32_t alpha_q) {
+  return (u64)alpha_q * cs_sum(w) + (u64)(65536u - alpha_q) * (cs_count(w) << 16);
+}
+__device__ __forceinline__ float key_to_score(u64 key) {
+  return (float)((double)key * (1.0 / 4294967296.0));
+}
+
+// Probability -> multiple of 1/65536, round to nearest even, clamped, NaN -> 0.
+__device__ __forceinline__ uint32_t quantize_prob(float p) {
+  if (!(p == p)) return 0u;
+  float x = rintf(p * 65536.0f);   // power-of-two scaling is exact; rintf is half-to-even
+  x = fminf(fmaxf(x, 0.0f), 65536.0f);
+  return (uint32_t)x;
+}
+
+// ---------------------------------------------------------------- argmax reductions
+
+struct Cand {      // a successor proposed for the greedy step
+  u64 key;         // its weight * 2^32
+  int32_t v;       // its token id; INT_MAX = none
+};
+__device__ __forceinline__ Cand cand_none() { return Cand{0ull, INT_MAX}; }
+// larger weight wins, equal weights go to the lower token id
+__device__ __forceinline__ Cand cand_best(Cand a, Cand b) {
+  bool take_b = (b.key > a.key) || (b.key == a.key && b.v < a.v);
+  return take_b ? b : a;
+}
+__device__ __forceinline__ Cand cand_from_lane(Cand c, int src) {
+  Cand r;
+  uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)c.key, src);
+  uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(c.key >> 32), src);
+  r.key = ((u64)hi << 32) | lo;
+  r.v = __builtin_amdgcn_readlane(c.v, src);
+  return r;
+}
+
+// One DPP step: every lane combines its candidate with the one the lane-move
+// pattern CTRL delivers; lanes the pattern does not reach combine with "none".
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ Cand dpp_step(Cand c) {
+  const Cand none = cand_none();
+  Cand x;
+  uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp((int)(uint32_t)none.key, (int)(uint32_t)c.key,
+                                                      CTRL, ROW_MASK, 0xF, false);
+  uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp((int)(uint32_t)(none.key >> 32),
+                                                      (int)(uint32_t)(c.key >> 32), CTRL, ROW_MASK,
+                                                      0xF, false);
+  x.key = ((u64)hi << 32) | lo;
+  x.v = __builtin_amdgcn_update_dpp(none.v, c.v, CTRL, ROW_MASK, 0xF, false);
+  return cand_best(c, x);
+}
+
+// Argmax over the 64 lanes of a wave; every lane gets the result.  Few lanes
+// hold a candidate in practice: none or one is settled with a ballot and lane
+// reads.  Otherwise four row_shr steps scan each row of 16 lanes, row_bcast:15
+// and row_bcast:31 carry the row results up, and lane 63 ends with the total.
+__device__ __forceinline__ Cand wave_argmax(Cand c) {
+  u64 have = __ballot(c.v != INT_MAX);
+  if (have == 0) return cand_none();
+  if ((have & (have - 1)) == 0) return cand_from_lane(c, (int)__ffsll((long long)have) - 1);
+  c = dpp_step<0x111, 0xF>(c);   // row_shr:1
+  c = dpp_step<0x112, 0xF>(c);   // row_shr:2
+  c = dpp_step<0x114, 0xF>(c);   // row_shr:4
+  c = dpp_step<0x118, 0xF>(c);   // row_shr:8
+  c = dpp_step<0x142, 0xA>(c);   // row_bcast:15 into rows 1 and 3
+  c = dpp_step<0x143, 0xC>(c);   // row_bcast:31 into rows 2 and 3
+  return cand_from_lane(c, 63);
+}
+
+template <int BLOCK>
+__device__ __forceinline__ void block_sync() {
+  __syncthreads();   // a one-wave workgroup needs no hardware barrier: the compiler drops it
+}
+
+// ---------------------------------------------------------------- device state
+
+struct IndexView {              // device state inside the caller's workspace
+  int32_t* tok;                 // [P][N][max_len] token histories
+  uint32_t* pq;                 // [P][N][max_len] quantised generation probabilities
+  const int32_t* meta_old;      // [P][N][meta_stride] before this launch: {length, last kmax
+                                //   tokens newest first}: one aligned load tells a path's end
+  int32_t* meta_new;            // same rows after it (may alias meta_old when nothing else reads)
+  uint32_t* status;             // sticky CSD_STATUS_* bits
+  int32_t* gram;                // n-gram index [P][kmax][n_buckets][16], or null (scan mode)
+  uint32_t bucket_mask;         // n_buckets - 1 (power of two)
+  int32_t meta_stride;          // ints per meta row: 1 + kmax rounded up to a multiple of 4
+  int32_t eshift;               // positions are packed as (path << eshift) | index
+  int32_t P, N, max_len, vocab, kmax;
+};
+
+struct StepIn {                 // tokens a step appends; n == 0: none
+  const int32_t* tok;           // [P][N][n]
+  const float* prob;            // [P][N][n] or null
+  const int32_t* counts;        // [P][N] or null
+  int32_t n;
+};
+
+// One problem's paths as they are AFTER this step's append, readable while the
+// append is still in flight: positions below the old length come from the
+// history, newer ones straight from the step's input.  No workgroup ever reads
+// history cells that another workgroup of the same launch writes.
+struct Paths {
+  const int32_t* tok;
+  const uint32_t* pq;
+  const int32_t* meta_old;
+  const int32_t* st;
+  const float* sp;
+  const int32_t* sc;
+  int32_t n, N, max_len, meta_stride, eshift;
+
+  __device__ __forceinline__ int32_t old_len(int32_t j) const {
+    return meta_old[(int64_t)j * meta_stride];
+  }
+  __device__ __forceinline__ int32_t new_len(int32_t j, int32_t old_j) const {
+    if (n == 0) return old_j;
+    int32_t c = sc ? sc[j] : n;
+    c = c < 0 ? 0 : (c > n ? n : c);
+    int32_t room = max_len - old_j;
+    return old_j + (c < room ? c : room);
+  }
+  __device__ __forceinline__ int32_t cell(int32_t j, int32_t t) const {   // j, t < 2^24
+    return (int32_t)__umul24((uint32_t)j, (uint32_t)max_len) + t;
+  }
+  __device__ __forceinline__ int32_t token(int32_t j, int32_t t, int32_t old_j) const {
+    return t < old_j ? tok[cell(j, t)] : st[(int64_t)j * n + (t - old_j)];
+  }
+  __device__ __forceinline__ uint32_t prob(int32_t j, int32_t t, int32_t old_j) const {
+    if (t < old_j) return pq[cell(j, t)];
+    return sp ? quantize_prob(sp[(int64_t)j * n + (t - old_j)]) : 65536u;
+  }
+  __device__ __forceinline__ int32_t pos(int32_t j, int32_t e) const { return (j << eshift) | e; }
+  __device__ __forceinline__ int32_t pos_path(int32_t pos) const { return pos >> eshift; }
+  __device__ __forceinline__ int32_t pos_index(int32_t pos) const {
+    return pos & ((1 << eshift) - 1);
+  }
+};
+
+struct Match {                  // one element of the candidate pool (Eq. 3)
+  int32_t pos;                  // packed (j, e): e = index of the first continuation token
+  int16_t rem_new;              // new_len_j - e: continuation tokens that exist, clipped to 63
+  int16_t rel_old;              // old_len_j - e, clipped to [-32767, 63]; <= 0: e itself is new
+};
+
+struct Slot {
+  u64 key;
+  u64 val;
+};
+
+struct Lds {
+  Slot table[kTableCap];
+  Match match[kMatchCap];
+  int32_t win[kWinWords];       // per cached match: L continuation tokens, then their L probabilities
+  int32_t len_old[kLenCache];
+  int32_t len_new[kLenCache];
+  Cand red[2][kScanBlock / kWave];
+  int n_match;                  // total matches found (may exceed kMatchCap)
+  int overflow;                 // a DAG table region ran out of room
+};
+
+struct Ctx {                    // one (problem, query path)
+  Paths y;
+  const int32_t* gram;          // this problem's index tables, or null
+  uint32_t bucket_mask;
+  int32_t kmax;
+  int32_t i;                    // query path
+  int32_t len_i;                // its length after the append
+  int32_t q;                    // effective query length min(k, len_i)
+  int32_t Q[CSD_MAX_QUERY_LEN]; // Q[a] = a-th token from the end of path i
+  int tid;
+};
+
+struct DraftArgs {
+  int32_t k, L;
+  uint32_t alpha_q;
+  int32_t score_mode;
+  int32_t* draft_tokens;        // [P][N][L]
+  int32_t* draft_len;           // [P][N]
+  float* token_scores;          // [P][N][L] or null
+  float* path_scores;           // [P][N] or null
+  const int32_t* targets;       // [P][N][L] or null
+  int32_t* accept_len;          // [P][N] or null
+};
+
+struct DraftOut {               // what one thread contributes to the outputs
+  int32_t tok = -1;             // thread t keeps layer t+1
+  u64 key = 0;
+  u64 key_sum = 0;
+  int32_t n = 0;
+};
+
+__device__ __forceinline__ Match make_match(const Paths& y, int32_t j, int32_t e, int32_t old_j,
+                                            int32_t new_j) {
+  int32_t rn = new_j - e, ro = old_j - e;
+  Match m;
+  m.pos = y.pos(j, e);
+  m.rem_new = (int16_t)(rn > 63 ? 63 : rn);
+  m.rel_old = (int16_t)(ro < -32767 ? -32767 : (ro > 63 ? 63 : ro));
+  return m;
+}
+
+// The (u, v, p) instance that match m contributes to layer d, if it reaches it,
+// read from memory.
+__device__ __forceinline__ bool layer_instance(const Paths& y, Match m, int32_t d, uint32_t& u,
+                                               uint32_t& v, u64& w) {
+  if (d > (int32_t)m.rem_new) return false;        // the candidate has ended
+  int32_t j = y.pos_path(m.pos);
+  int32_t e = y.pos_index(m.pos);
+  // rel_old is exact unless clipped at 63 (a step appends at most 32767 tokens), and
+  // d <= 32 < 63: every index read below is then on the history side either way
+  int32_t old_j = e + (int32_t)m.rel_old;
+  u = (uint32_t)y.token(j, e + d - 2, old_j);
+  v = (uint32_t)y.token(j, e + d - 1, old_j);
+  w = pack_cs(1u, y.prob(j, e + d - 1, old_j));
+  return true;
+}
+
+// Workgroups are dealt round-robin to the 8 XCDs; this maps them back so that
+// each XCD works on a contiguous range of (problem, path) rows and the paths of
+// one problem share one L2.  The grid is padded to a multiple of 8.
+__device__ __forceinline__ int32_t xcd_row(int32_t rows) {
+  int32_t per_xcd = (int32_t)(gridDim.x >> 3);
+  int32_t r = (int32_t)(blockIdx.x & 7) * per_xcd + (int32_t)(blockIdx.x >> 3);
+  return r < rows ? r : -1;
+}
+inline uint32_t xcd_grid(int64_t rows) { return (uint32_t)((rows + 7) / 8 * 8); }
+
+__device__ __forceinline__ Ctx make_ctx(const IndexView& ix, const StepIn& in, int32_t row,
+                                        int32_t& p_out) {
+  Ctx c;
+  int32_t p = row / ix.N;
+  p_out = p;
+  int64_t cells = (int64_t)p * ix.N * ix.max_len;
+  c.i = row - p * ix.N;
+  c.y.tok = ix.tok + cells;
+  c.y.pq = ix.pq + cells;
+  c.y.meta_old = ix.meta_old + (int64_t)p * ix.N * ix.meta_stride;
+  c.y.meta_stride = ix.meta_stride;
+  c.y.eshift = ix.eshift;
+  c.y.n = in.n;
+  c.y.st = in.n ? in.tok + (int64_t)p * ix.N * in.n : nullptr;
+  c.y.sp = (in.n && in.prob) ? in.prob + (int64_t)p * ix.N * in.n : nullptr;
+  c.y.sc = (in.n && in.counts) ? in.counts + (int64_t)p * ix.N : nullptr;
+  c.y.N = ix.N;
+  c.y.max_len = ix.max_len;
+  c.gram = ix.gram ? ix.gram + (int64_t)p * ix.kmax * ((int64_t)ix.bucket_mask + 1) * kBucketWords
+                   : nullptr;
+  c.bucket_mask = ix.bucket_mask;
+  c.kmax = ix.kmax;
+  c.len_i = 0;
+  c.q = 0;
+  c.tid = threadIdx.x;
+  return c;
+}
+
+}  // namespace csd

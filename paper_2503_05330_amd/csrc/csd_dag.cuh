@@ -1,0 +1,257 @@
+// csd — the layered token DAG (Eq. 5) as LDS hash histograms, and the greedy
+// layer-wise walk over it (rule after Eq. 5, Algorithm 1).
+//
+// Two tiers with identical results (all sums are exact integers):
+//   tier 1  all L layers at once: layer d owns one region of the LDS table that
+//           holds its edges (d,u,v) and its nodes (d,*,v); after the build every
+//           edge's value is replaced by the weight the walk ranks it by, so one
+//           walk step is a single LDS read per lane plus a wave argmax;
+//   tier 2  bounded memory for any input: one layer at a time, and within a
+//           layer one class of tokens (by hash residue) at a time.
+#pragma once
+
+#include "csd_common.cuh"
+
+namespace csd {
+
+struct Region {                 // slots [base, base + mask] of the LDS table
+  uint32_t base, mask;
+};
+
+template <int BLOCK>
+__device__ __forceinline__ void table_clear(Lds& s, uint32_t n_slots, int tid) {
+  for (uint32_t h = tid; h < n_slots; h += BLOCK) s.table[h] = Slot{kEmpty, 0ull};
+  if (tid == 0) s.overflow = 0;
+}
+
+// table[key] += delta inside a region, inserting the key if new.  Sets
+// s.overflow when the region has no free slot (the caller then falls back) —
+// never spins.
+__device__ __forceinline__ void table_add(Lds& s, Region r, u64 key, u64 delta) {
+  uint32_t h = dag_hash(key) & r.mask;
+  for (uint32_t probe = 0; probe <= r.mask; ++probe) {
+    Slot* slot = &s.table[r.base + h];
+    u64 cur = slot->key;
+    if (cur == kEmpty) {
+      cur = atomicCAS(&slot->key, kEmpty, key);
+      if (cur == kEmpty) cur = key;
+    }
+    if (cur == key) {
+      atomicAdd(&slot->val, delta);
+      return;
+    }
+    h = (h + 1) & r.mask;
+  }
+  s.overflow = 1;
+}
+
+__device__ __forceinline__ u64 table_get(const Lds& s, Region r, u64 key) {
+  uint32_t h = dag_hash(key) & r.mask;
+  for (uint32_t probe = 0; probe <= r.mask; ++probe) {
+    Slot x = s.table[r.base + h];
+    if (x.key == key) return x.val;
+    if (x.key == kEmpty) return 0ull;
+    h = (h + 1) & r.mask;
+  }
+  return 0ull;
+}
+
+// Workgroup-wide argmax of the per-thread candidates; every thread gets the result.
+template <int BLOCK>
+__device__ __forceinline__ Cand block_argmax(Lds& s, Cand c, int tid, int parity) {
+  c = wave_argmax(c);
+  if (BLOCK == kWave) return c;
+  if ((tid & 63) == 0) s.red[parity][tid >> 6] = c;
+  __syncthreads();
+  Cand r = s.red[parity][0];
+#pragma unroll
+  for (int w = 1; w < BLOCK / kWave; ++w) r = cand_best(r, s.red[parity][w]);
+  return r;
+}
+
+__device__ __forceinline__ void note_choice(DraftOut& o, Cand best, int32_t d, int tid) {
+  if (tid == d - 1) {
+    o.tok = best.v;
+    o.key = best.key;
+  }
+  o.key_sum += best.key;
+  o.n = d;
+}
+
+// ---------------------------------------------------------------- tier 1: everything in LDS
+
+// Matches n_fresh .. n_fresh + win_cap - 1 of the list have their continuation cached in LDS.
+struct WinInfo {
+  int32_t n_fresh, win_cap;
+};
+
+struct Tier1 {                  // geometry of the table for one query
+  uint32_t region;              // slots per layer (power of two)
+  __device__ __forceinline__ Region layer(int32_t d) const {
+    return Region{(uint32_t)(d - 1) * region, region - 1};
+  }
+};
+
+__device__ __forceinline__ Tier1 tier1_geometry(int32_t M, int32_t L) {
+  uint32_t want = 4u * (uint32_t)M;                   // a layer holds <= 2M keys: <= 50 % load
+  uint32_t cap = (uint32_t)kTableCap / (uint32_t)L;   // what fits (rounded down to 2^x below)
+  uint32_t size = 8;
+  while (size < want && size * 2 <= cap) size <<= 1;
+  return Tier1{size};
+}
+
+// Eq. 5: every (match, layer) instance adds (1, p) to its edge (d,u,v) and to
+// its node (d,*,v).
+template <int BLOCK>
+__device__ __forceinline__ Tier1 build_dag(Lds& s, const Ctx& c, int32_t M, int32_t L, WinInfo wi) {
+  Tier1 t1 = tier1_geometry(M, L);
+  table_clear<BLOCK>(s, t1.region * (uint32_t)L, c.tid);
+  block_sync<BLOCK>();
+  int32_t items = M * L;
+  for (int32_t idx = c.tid; idx < items; idx += BLOCK) {
+    int32_t d = idx / M + 1;
+    int32_t mi = idx - (d - 1) * M;
+    Match m = s.match[mi];
+    uint32_t u, v;
+    u64 w;
+    bool alive;
+    int32_t ws = mi - wi.n_fresh;
+    if (ws >= 0 && ws < wi.win_cap) {                 // cached: no memory access
+      alive = d <= (int32_t)m.rem_new;
+      const int32_t* win = s.win + ws * 2 * L;
+      v = (uint32_t)win[d - 1];
+      u = d == 1 ? (uint32_t)c.Q[0] : (uint32_t)win[d - 2];
+      w = pack_cs(1u, (uint32_t)win[L + d - 1]);
+    } else {
+      alive = layer_instance(c.y, m, d, u, v, w);
+    }
+    if (alive && !s.overflow) {
+      Region r = t1.layer(d);
+      table_add(s, r, dag_key(d, u, v), w);
+      table_add(s, r, dag_key(d, kAnyTok, v), w);
+    }
+  }
+  block_sync<BLOCK>();
+  return t1;
+}
+
+// Replaces every edge's (C, S) by the weight the greedy step ranks it by:
+// the in-weight of its target node (score_mode 0) or its own weight (mode 1).
+template <int BLOCK>
+__device__ __forceinline__ void score_edges(Lds& s, Tier1 t1, int32_t L, uint32_t alpha_q,
+                                            int score_mode, int tid) {
+  uint32_t n_slots = t1.region * (uint32_t)L;
+  for (uint32_t h = tid; h < n_slots; h += BLOCK) {
+    Slot x = s.table[h];
+    if (x.key == kEmpty || key_u(x.key) == kAnyTok) continue;
+    int32_t d = (int32_t)(x.key >> 58);
+    u64 w = score_mode ? x.val : table_get(s, t1.layer(d), dag_key(d, kAnyTok, key_v(x.key)));
+    s.table[h].val = weight_key(w, alpha_q);          // only edge slots are rewritten
+  }
+  block_sync<BLOCK>();
+}
+
+// Greedy walk over the scored tables (rule after Eq. 5).
+template <int BLOCK>
+__device__ __forceinline__ void walk_dag(Lds& s, const Ctx& c, Tier1 t1, int32_t L, DraftOut& o) {
+  int32_t cur = c.Q[0];
+  for (int32_t d = 1; d <= L; ++d) {
+    Region r = t1.layer(d);
+    u64 want = dag_key(d, (uint32_t)cur, 0) >> 29;
+    Cand best = cand_none();
+    for (uint32_t h = c.tid; h <= r.mask; h += BLOCK) {
+      Slot x = s.table[r.base + h];
+      if ((x.key >> 29) == want) best = cand_best(best, Cand{x.val, (int32_t)key_v(x.key)});
+    }
+    best = block_argmax<BLOCK>(s, best, c.tid, d & 1);
+    if (best.v == INT_MAX) break;                     // leaf: no edge leaves cur
+    note_choice(o, best, d, c.tid);
+    cur = best.v;
+  }
+}
+
+// ---------------------------------------------------------------- tier 2: streaming, layer by layer
+
+// Successors of `cur` in layer d as held by a region with raw (C, S) values.
+template <int BLOCK>
+__device__ __forceinline__ Cand scan_successors(const Lds& s, Region r, int d, int32_t cur,
+                                                uint32_t alpha_q, int score_mode, int tid,
+                                                Cand best) {
+  u64 want = dag_key(d, (uint32_t)cur, 0) >> 29;
+  for (uint32_t h = tid; h <= r.mask; h += BLOCK) {
+    Slot x = s.table[r.base + h];
+    if ((x.key >> 29) != want) continue;
+    uint32_t v = key_v(x.key);
+    u64 w = score_mode ? x.val : table_get(s, r, dag_key(d, kAnyTok, v));
+    best = cand_best(best, Cand{weight_key(w, alpha_q), (int32_t)v});
+  }
+  return best;
+}
+
+// Same result as tier 1 with bounded memory for any input.  `each_match(f)`
+// calls f(Match) for every match (from the LDS list, or by matching again).
+template <int BLOCK, class EachMatch>
+__device__ __forceinline__ void walk_streaming(Lds& s, const Ctx& c, int32_t L, uint32_t alpha_q,
+                                               int score_mode, uint32_t* status, DraftOut& o,
+                                               EachMatch each_match) {
+  const Region all{0u, (uint32_t)kTableCap - 1u};
+  int32_t cur = c.Q[0];
+  int class_bits = 0;
+  int parity = 0;
+  for (int32_t d = 1; d <= L; ++d) {
+    Cand best;
+    bool failed;
+    do {
+      failed = false;
+      best = cand_none();
+      uint32_t n_class = 1u << class_bits;
+      for (uint32_t r = 0; r < n_class && !failed; ++r) {
+        block_sync<BLOCK>();                           // previous readers are done
+        table_clear<BLOCK>(s, kTableCap, c.tid);
+        block_sync<BLOCK>();
+        each_match([&](Match m) {
+          uint32_t u, v;
+          u64 w;
+          if (s.overflow || !layer_instance(c.y, m, d, u, v, w)) return;
+          if (((v * 0x9E3779B1u) >> 12 & (n_class - 1)) != r) return;
+          table_add(s, all, dag_key(d, kAnyTok, v), w);
+          if (u == (uint32_t)cur) table_add(s, all, dag_key(d, u, v), w);
+        });
+        block_sync<BLOCK>();
+        if (s.overflow) failed = true;                 // uniform: read after the barrier
+        else best = scan_successors<BLOCK>(s, all, d, cur, alpha_q, score_mode, c.tid, best);
+      }
+      if (failed) ++class_bits;
+    } while (failed && class_bits <= kMaxClassBits);
+    if (failed) {                                      // 2^20 classes did not suffice
+      if (c.tid == 0) atomicOr(status, CSD_STATUS_TABLE_FULL);
+      break;
+    }
+    parity ^= 1;
+    best = block_argmax<BLOCK>(s, best, c.tid, parity);
+    if (best.v == INT_MAX) break;
+    note_choice(o, best, d, c.tid);
+    cur = best.v;
+  }
+}
+
+// Writes the edge entries of a finished, unscored tier-1 table, sorted by key,
+// to ok / ov (debug dump).  Returns through *n_edges (an LDS counter).
+template <int BLOCK>
+__device__ __forceinline__ void emit_sorted_edges(Lds& s, uint32_t n_slots, int tid, int* n_edges,
+                                                  u64* ok, u64* ov) {
+  for (uint32_t h = tid; h < n_slots; h += BLOCK) {
+    u64 key = s.table[h].key;
+    if (key == kEmpty || key_u(key) == kAnyTok) continue;
+    int rank = 0;                                     // keys are distinct: rank = sorted position
+    for (uint32_t g = 0; g < n_slots; ++g) {
+      u64 other = s.table[g].key;
+      if (other != kEmpty && key_u(other) != kAnyTok && other < key) ++rank;
+    }
+    ok[rank] = key;
+    ov[rank] = s.table[h].val;
+    atomicAdd(n_edges, 1);
+  }
+}
+
+}  // namespace csd

@@ -1,0 +1,358 @@
+// csd — the kernels: reset, append, the decode step (one wave per path in index
+// mode, one 256-thread workgroup per path in scan mode), accept, and the
+// kernels behind the debug dumps.
+#pragma once
+
+#include "csd_common.cuh"
+#include "csd_dag.cuh"
+#include "csd_index.cuh"
+#include "csd_match.cuh"
+
+namespace csd {
+
+__global__ __launch_bounds__(256) void reset_kernel(IndexView ix, int64_t gram_words) {
+  int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  int64_t stride = (int64_t)gridDim.x * 256;
+  int64_t rows = (int64_t)ix.P * ix.N;
+  for (int64_t r = t; r < rows * ix.meta_stride; r += stride) ix.meta_new[r] = 0;
+  for (int64_t w = t; w < gram_words; w += stride) ix.gram[w] = (w & (kBucketWords - 1)) ? -1 : 0;
+  if (t == 0) *ix.status = 0u;
+}
+
+// Append only: one workgroup per (problem, path); the meta row is updated in place.
+__global__ __launch_bounds__(256) void append_kernel(IndexView ix, StepIn in) {
+  int32_t row = blockIdx.x;
+  int32_t p;
+  Ctx c = make_ctx(ix, in, row, p);
+  int32_t old_i = c.y.old_len(c.i);
+  int32_t new_i = c.y.new_len(c.i, old_i);
+  append_row<256, true>(ix, c.y, p, c.i, old_i, new_i, c.tid);
+}
+
+// Draft tokens, scores, length and (optionally) accept length of one row.
+// `target` is the lane's target token (lanes < L), loaded by the caller.
+template <int BLOCK>
+__device__ __forceinline__ void write_outputs(const DraftArgs& a, int32_t row, const DraftOut& o,
+                                              int tid) {
+  const int32_t L = a.L;
+  bool live = tid < o.n;
+  if (tid < L) {
+    a.draft_tokens[(int64_t)row * L + tid] = live ? o.tok : -1;
+    if (a.token_scores) a.token_scores[(int64_t)row * L + tid] = live ? key_to_score(o.key) : 0.0f;
+  }
+  if (tid == 0) {
+    a.draft_len[row] = o.n;
+    if (a.path_scores) a.path_scores[row] = key_to_score(o.key_sum);
+  }
+}
+
+// "Draft acceptance": the first lane whose draft token differs from its target.
+__device__ __forceinline__ void write_accept(const DraftArgs& a, int32_t row, const DraftOut& o,
+                                             int32_t target, int tid) {
+  bool same = tid < o.n && target == o.tok;
+  u64 differs = __ballot(!same);
+  if (tid == 0) a.accept_len[row] = differs ? (int32_t)__ffsll((long long)differs) - 1 : kWave;
+}
+
+// Scan mode.  One 256-thread workgroup per (problem, path): [append] -> match by
+// scan (Eq. 3) -> DAG (Eq. 5) -> greedy walk -> [accept].  With in.n > 0 the
+// launch also performs the step's append; every workgroup then reads the other
+// paths through `Paths`, which never touches cells written by this launch.
+__global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, StepIn in,
+                                                               DraftArgs a) {
+  constexpr int BLOCK = kScanBlock;
+  __shared__ Lds s;
+  int32_t row = xcd_row(ix.P * ix.N);
+  if (row < 0) return;
+  int32_t p;
+  Ctx c = make_ctx(ix, in, row, p);
+  int32_t old_i = c.y.old_len(c.i);
+  c.len_i = c.y.new_len(c.i, old_i);
+  if (in.n > 0) append_row<BLOCK, true>(ix, c.y, p, c.i, old_i, c.len_i, c.tid);
+  load_query(c, a.k, old_i);
+  if (c.tid == 0) s.n_match = 0;
+  block_sync<BLOCK>();
+
+  DraftOut o;
+  const int32_t L = a.L;
+  if (c.q > 0) {
+    ListSink sink{&s};
+    match_scan<BLOCK>(c, sink);
+    block_sync<BLOCK>();
+    int32_t M = s.n_match;
+    if (M > 0) {
+      bool streaming = M > kMatchCap;
+      if (!streaming) {
+        Tier1 t1 = build_dag<BLOCK>(s, c, M, L, WinInfo{M, 0});
+        streaming = s.overflow != 0;
+        if (!streaming) {
+          score_edges<BLOCK>(s, t1, L, a.alpha_q, a.score_mode, c.tid);
+          walk_dag<BLOCK>(s, c, t1, L, o);
+        }
+      }
+      if (streaming)
+        walk_streaming<BLOCK>(s, c, L, a.alpha_q, a.score_mode, ix.status, o, [&](auto f) {
+          if (M <= kMatchCap) {
+            for (int32_t m = c.tid; m < M; m += BLOCK) f(s.match[m]);
+          } else {
+            FnSink<decltype(f)> fs{f};
+            match_scan<BLOCK>(c, fs);
+          }
+        });
+    }
+  }
+  write_outputs<BLOCK>(a, row, o, c.tid);
+  if (a.targets && c.tid < kWave) {
+    int32_t target = c.tid < L ? a.targets[(int64_t)row * L + c.tid] : 0;
+    write_accept(a, row, o, target, c.tid);
+  }
+}
+
+// Index mode.  One wave64 per (problem, path): the front end (append, matches
+// with their continuations in LDS), DAG build, scoring, walk, outputs, accept,
+// and last the posting stores of the split-phase index insert.
+template <int LCAP>
+__global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn in, DraftArgs a) {
+  __shared__ Lds s;
+  int32_t row = xcd_row(ix.P * ix.N);
+  if (row < 0) return;
+  int32_t p;
+  Ctx c = make_ctx(ix, in, row, p);
+  const int32_t L = a.L;
+  int32_t target = (a.targets && c.tid < L) ? a.targets[(int64_t)row * L + c.tid] : 0;
+  WinInfo wi;
+  InsertTicket ticket;
+  bool ticket_used;
+  int32_t M = wave_front_end<LCAP>(s, c, ix, p, a.k, L, wi, ticket, ticket_used);
+  block_sync<kWave>();
+
+  DraftOut o;
+  if (M > 0) {
+    bool streaming = M > kMatchCap;
+    if (!streaming) {
+      Tier1 t1 = build_dag<kWave>(s, c, M, L, wi);
+      streaming = s.overflow != 0;
+      if (!streaming) {
+        score_edges<kWave>(s, t1, L, a.alpha_q, a.score_mode, c.tid);
+        walk_dag<kWave>(s, c, t1, L, o);
+      }
+    }
+    if (streaming)
+      walk_streaming<kWave>(s, c, L, a.alpha_q, a.score_mode, ix.status, o, [&](auto f) {
+        if (M <= kMatchCap) {
+          for (int32_t m = c.tid; m < M; m += kWave) f(s.match[m]);
+        } else {
+          FnSink<decltype(f)> fs{f};
+          match_index(c, fs);
+        }
+      });
+  }
+  write_outputs<kWave>(a, row, o, c.tid);
+  if (a.targets) write_accept(a, row, o, target, c.tid);
+  if (ticket_used)
+    insert_finish(ticket, const_cast<int32_t*>(c.gram), c.bucket_mask,
+                  c.y.pos(c.i, c.len_i - 1), c.tid);
+}
+
+__global__ __launch_bounds__(256) void accept_kernel(int64_t rows, int32_t L,
+                                                     const int32_t* draft_tokens,
+                                                     const int32_t* draft_len,
+                                                     const int32_t* targets, int32_t* accept_len) {
+  int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (r >= rows) return;
+  int32_t n = draft_len[r];
+  n = n < 0 ? 0 : (n > L ? L : n);
+  int32_t a = 0;
+  while (a < n && draft_tokens[r * L + a] == targets[r * L + a]) ++a;
+  accept_len[r] = a;
+}
+
+// Plain copy of n 16-byte words: the known-size kernel that hardware traffic
+// counters are calibrated against.
+__global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ src,
+                                                   uint4* __restrict__ dst, int64_t n) {
+  int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x; x < n; x += stride) dst[x] = src[x];
+}
+
+// ---- debug dumps ------------------------------------------------------------
+
+// Scan mode: marks every match of every row in a bitmap [rows][words].
+__global__ __launch_bounds__(kScanBlock) void dump_match_bits_scan_kernel(IndexView ix, StepIn in,
+                                                                          int32_t k, uint32_t* bits,
+                                                                          int32_t words) {
+  int32_t row = xcd_row(ix.P * ix.N);
+  if (row < 0) return;
+  int32_t p;
+  Ctx c = make_ctx(ix, in, row, p);   // in.n == 0: nothing is being appended
+  int32_t old_i = c.y.old_len(c.i);
+  c.len_i = old_i;
+  load_query(c, k, old_i);
+  if (c.q <= 0) return;
+  BitmapSink sink{bits + (int64_t)row * words};
+  match_scan<kScanBlock>(c, sink);
+}
+
+// Index mode: the matches as the step kernel's own front end finds them.
+__global__ __launch_bounds__(kWave) void dump_match_bits_wave_kernel(IndexView ix, StepIn in,
+                                                                     int32_t k, uint32_t* bits,
+                                                                     int32_t words) {
+  __shared__ Lds s;
+  int32_t row = xcd_row(ix.P * ix.N);
+  if (row < 0) return;
+  int32_t p;
+  Ctx c = make_ctx(ix, in, row, p);   // in.n == 0: nothing is being appended
+  WinInfo wi;
+  InsertTicket ticket;
+  bool ticket_used;
+  int32_t M = wave_front_end<8>(s, c, ix, p, k, 1, wi, ticket, ticket_used);
+  block_sync<kWave>();
+  BitmapSink sink{bits + (int64_t)row * words};
+  if (M <= kMatchCap) {
+    for (int32_t m = c.tid; m < M; m += kWave) sink.push(c.y, true, s.match[m]);
+  } else if (c.q > 0) {
+    match_index(c, sink);
+  }
+}
+
+// counts[row] = number of set bits of the row (one workgroup per row)
+__global__ __launch_bounds__(256) void count_bits_kernel(const uint32_t* bits, int32_t words,
+                                                         int32_t* counts) {
+  __shared__ int total;
+  if (threadIdx.x == 0) total = 0;
+  __syncthreads();
+  const uint32_t* b = bits + (int64_t)blockIdx.x * words;
+  int n = 0;
+  for (int32_t w = threadIdx.x; w < words; w += 256) n += __popc(b[w]);
+  atomicAdd(&total, n);
+  __syncthreads();
+  if (threadIdx.x == 0) counts[blockIdx.x] = total;
+}
+
+// off[0] = 0, off[r+1] = off[r] + max(counts[r], 0); *bad = 1 if any count < 0
+__global__ void offsets_kernel(const int32_t* counts, int32_t rows, int32_t* off, int32_t* bad) {
+  if (blockIdx.x != 0 || threadIdx.x != 0) return;
+  int32_t acc = 0, any_bad = 0;
+  off[0] = 0;
+  for (int32_t r = 0; r < rows; ++r) {
+    int32_t n = counts[r];
+    if (n < 0) { any_bad = 1; n = 0; }
+    acc += n;
+    off[r + 1] = acc;
+  }
+  *bad = any_bad;
+}
+
+// Expands each row's bitmap into ascending (j, e) pairs (one wave per row).
+__global__ __launch_bounds__(64) void expand_bits_kernel(const uint32_t* bits, int32_t words,
+                                                         int32_t max_len, const int32_t* off,
+                                                         int32_t* out_je, int64_t cap) {
+  const uint32_t* b = bits + (int64_t)blockIdx.x * words;
+  int64_t base = off[blockIdx.x];
+  int lane = threadIdx.x;
+  for (int32_t w0 = 0; w0 < words; w0 += 64) {
+    int32_t w = w0 + lane;
+    uint32_t x = w < words ? b[w] : 0u;
+    int n = __popc(x);
+    int incl = n;                                     // inclusive prefix sum over lanes
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      int y = __shfl_up(incl, o);
+      if (lane >= o) incl += y;
+    }
+    int64_t at = base + incl - n;
+    while (x) {
+      int bit = __ffs(x) - 1;
+      x &= x - 1;
+      int32_t pos = w * 32 + bit;
+      if (at < cap) {
+        out_je[2 * at] = pos / max_len;
+        out_je[2 * at + 1] = pos % max_len;
+      }
+      ++at;
+    }
+    base += __shfl(incl, 63);
+  }
+}
+
+// Scan mode: builds the tier-1 DAG tables of a row exactly as step_scan_kernel
+// does and writes the edge entries, sorted by key, to tmp rows of kTableCap
+// entries.  counts[row] = number of edges, or -1 if the row needs tier 2.
+__global__ __launch_bounds__(kScanBlock) void dump_edge_rows_scan_kernel(
+    IndexView ix, StepIn in, int32_t k, int32_t L, u64* tmp_keys, u64* tmp_vals, int32_t* counts) {
+  constexpr int BLOCK = kScanBlock;
+  __shared__ Lds s;
+  __shared__ int n_edges;
+  int32_t row = xcd_row(ix.P * ix.N);
+  if (row < 0) return;
+  int32_t p;
+  Ctx c = make_ctx(ix, in, row, p);   // in.n == 0: nothing is being appended
+  int32_t old_i = c.y.old_len(c.i);
+  c.len_i = old_i;
+  load_query(c, k, old_i);
+  if (c.tid == 0) { s.n_match = 0; n_edges = 0; }
+  block_sync<BLOCK>();
+  if (c.q <= 0) { if (c.tid == 0) counts[row] = 0; return; }
+  ListSink sink{&s};
+  match_scan<BLOCK>(c, sink);
+  block_sync<BLOCK>();
+  int32_t M = s.n_match;
+  if (M == 0) { if (c.tid == 0) counts[row] = 0; return; }
+  if (M > kMatchCap) { if (c.tid == 0) counts[row] = -1; return; }
+  Tier1 t1 = build_dag<BLOCK>(s, c, M, L, WinInfo{M, 0});
+  if (s.overflow) { if (c.tid == 0) counts[row] = -1; return; }
+  emit_sorted_edges<BLOCK>(s, t1.region * (uint32_t)L, c.tid, &n_edges,
+                           tmp_keys + (int64_t)row * kTableCap, tmp_vals + (int64_t)row * kTableCap);
+  block_sync<BLOCK>();
+  if (c.tid == 0) counts[row] = n_edges;
+}
+
+// Index mode: front end and DAG build of the step kernel itself.
+template <int LCAP>
+__global__ __launch_bounds__(kWave) void dump_edge_rows_wave_kernel(IndexView ix, StepIn in,
+                                                                    int32_t k, int32_t L,
+                                                                    u64* tmp_keys, u64* tmp_vals,
+                                                                    int32_t* counts) {
+  __shared__ Lds s;
+  __shared__ int n_edges;
+  int32_t row = xcd_row(ix.P * ix.N);
+  if (row < 0) return;
+  int32_t p;
+  Ctx c = make_ctx(ix, in, row, p);   // in.n == 0: nothing is being appended
+  if (c.tid == 0) n_edges = 0;
+  WinInfo wi;
+  InsertTicket ticket;
+  bool ticket_used;
+  int32_t M = wave_front_end<LCAP>(s, c, ix, p, k, L, wi, ticket, ticket_used);
+  block_sync<kWave>();
+  if (M == 0) { if (c.tid == 0) counts[row] = 0; return; }
+  if (M > kMatchCap) { if (c.tid == 0) counts[row] = -1; return; }
+  Tier1 t1 = build_dag<kWave>(s, c, M, L, wi);
+  if (s.overflow) { if (c.tid == 0) counts[row] = -1; return; }
+  emit_sorted_edges<kWave>(s, t1.region * (uint32_t)L, c.tid, &n_edges,
+                           tmp_keys + (int64_t)row * kTableCap, tmp_vals + (int64_t)row * kTableCap);
+  block_sync<kWave>();
+  if (c.tid == 0) counts[row] = n_edges;
+}
+
+__global__ __launch_bounds__(256) void scatter_edges_kernel(const u64* tmp_keys,
+                                                            const u64* tmp_vals,
+                                                            const int32_t* off, int32_t* out_duv,
+                                                            uint64_t* out_cs, int64_t cap) {
+  int32_t row = blockIdx.x;
+  int64_t base = off[row];
+  int32_t n = off[row + 1] - off[row];
+  for (int32_t x = threadIdx.x; x < n; x += 256) {
+    int64_t at = base + x;
+    if (at >= cap) break;
+    u64 key = tmp_keys[(int64_t)row * kTableCap + x];
+    u64 val = tmp_vals[(int64_t)row * kTableCap + x];
+    out_duv[3 * at] = (int32_t)(key >> 58);
+    out_duv[3 * at + 1] = (int32_t)key_u(key);
+    out_duv[3 * at + 2] = (int32_t)key_v(key);
+    out_cs[2 * at] = cs_count(val);
+    out_cs[2 * at + 1] = cs_sum(val);
+  }
+}
+
+}  // namespace csd

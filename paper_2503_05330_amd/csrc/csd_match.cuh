@@ -1,0 +1,414 @@
+// csd — cross-path suffix matching (Eq. 3): by exhaustive scan, through the
+// n-gram index (general form), and the one-wave front end of the decode step
+// that needs only three dependent memory round trips.
+#pragma once
+
+#include "csd_common.cuh"
+#include "csd_dag.cuh"
+#include "csd_index.cuh"
+
+namespace csd {
+
+__device__ __forceinline__ void load_query(Ctx& c, int32_t k, int32_t old_i) {
+  c.q = k < c.len_i ? k : c.len_i;
+#pragma unroll
+  for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a)
+    c.Q[a] = (a < c.q) ? c.y.token(c.i, c.len_i - 1 - a, old_i) : 0;
+}
+
+// Does the q-gram that ends just before index e of path j equal the query?
+// All q tokens are fetched at once (one memory round trip, not q).
+__device__ __forceinline__ bool gram_equals_query(const Ctx& c, int32_t j, int32_t e,
+                                                  int32_t old_j) {
+  int32_t t[CSD_MAX_QUERY_LEN];
+#pragma unroll
+  for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) t[a] = (a < c.q) ? c.y.token(j, e - 1 - a, old_j) : 0;
+  bool hit = true;
+#pragma unroll
+  for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) hit = hit && (a >= c.q || t[a] == c.Q[a]);
+  return hit;
+}
+
+__device__ __forceinline__ GramHash query_hash(const Ctx& c) {
+  uint32_t acc = kGramSeed;
+#pragma unroll
+  for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a)
+    if (a < c.q) acc = gram_hash_add(acc, c.Q[a]);
+  return gram_hash_end(acc, c.q);
+}
+
+// ---------------------------------------------------------------- match sinks
+
+// Compacts hits into the LDS match list with one LDS atomic per wave.
+// push() must be reached by all 64 lanes of a wave together.
+struct ListSink {
+  Lds* s;
+  __device__ __forceinline__ void push(const Paths&, bool hit, Match m) {
+    u64 mask = __ballot(hit);
+    if (mask == 0) return;
+    int lane = __lane_id();
+    int base = 0;
+    if (lane == 0) base = atomicAdd(&s->n_match, (int)__popcll(mask));
+    base = __builtin_amdgcn_readfirstlane(base);
+    int slot = base + (int)__popcll(mask & ((1ull << lane) - 1ull));
+    if (hit && slot < kMatchCap) s->match[slot] = m;
+  }
+};
+
+// Marks hits in a bitmap over all positions [N][max_len] of the problem (debug dump).
+struct BitmapSink {
+  uint32_t* bits;
+  __device__ __forceinline__ void push(const Paths& y, bool hit, Match m) {
+    if (!hit) return;
+    int32_t bit = y.cell(y.pos_path(m.pos), y.pos_index(m.pos));
+    atomicOr(&bits[bit >> 5], 1u << (bit & 31));
+  }
+};
+
+// Hands every hit to a callable (streaming tier).
+template <class F>
+struct FnSink {
+  F f;
+  __device__ __forceinline__ void push(const Paths&, bool hit, Match m) {
+    if (hit) f(m);
+  }
+};
+
+// ---------------------------------------------------------------- general matchers
+
+// Eq. 3 by exhaustive comparison: every position e of every other path j with
+// q <= e <= len_j - 1 is tested.  Trip counts are uniform over the workgroup;
+// four tiles are in flight at a time.
+template <int BLOCK, class Sink>
+__device__ __forceinline__ void match_scan(const Ctx& c, Sink& sink) {
+  constexpr int kUnroll = 4;
+  int32_t tiles_per_path = (c.y.max_len + BLOCK - 1) / BLOCK;
+  int32_t tiles = c.y.N * tiles_per_path;
+  for (int32_t g0 = 0; g0 < tiles; g0 += kUnroll) {
+    bool hit[kUnroll];
+    Match m[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      int32_t g = g0 + u;
+      int32_t j = g / tiles_per_path;
+      int32_t e = c.q + (g - j * tiles_per_path) * BLOCK + c.tid;
+      hit[u] = false;
+      m[u] = Match{0, 0, 0};
+      if (g < tiles && j != c.i) {
+        int32_t old_j = c.y.old_len(j);
+        int32_t new_j = c.y.new_len(j, old_j);
+        if (e < new_j) {
+          hit[u] = gram_equals_query(c, j, e, old_j);
+          m[u] = make_match(c.y, j, e, old_j, new_j);
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) sink.push(c.y, hit[u], m[u]);
+  }
+}
+
+// Eq. 3 through the hash index, by ONE wave, in its general form (any number
+// of new tokens, any sink).  Postings of earlier steps come from the gram's
+// bucket sequence; positions this very launch appends are not looked up (their
+// inserts may be in flight) but tested directly.
+template <class Sink>
+__device__ __forceinline__ void match_index(const Ctx& c, Sink& sink) {
+  const int lane = c.tid & 63;
+  if (c.y.n > 0) {                    // (a) positions appended by this launch
+    for (int32_t j0 = 0; j0 < c.y.N; j0 += kWave) {
+      int32_t j = j0 + lane;
+      bool live = j < c.y.N && j != c.i;
+      int32_t old_j = live ? c.y.old_len(j) : 0;
+      int32_t new_j = live ? c.y.new_len(j, old_j) : 0;
+      for (int32_t t = 0; t < c.y.n; ++t) {
+        int32_t e = old_j + t;
+        bool hit = live && e < new_j && e >= c.q && gram_equals_query(c, j, e, old_j);
+        sink.push(c.y, hit, make_match(c.y, j, e, old_j, new_j));
+      }
+    }
+  }
+  GramHash gh = query_hash(c);        // (b) postings of earlier launches
+  int32_t* tbl = gram_table(const_cast<int32_t*>(c.gram), c.q, c.bucket_mask);
+  const int sub = lane & 15;          // word of the bucket this lane reads
+  const int grp = lane >> 4;          // which of the 4 buckets of a batch
+  uint32_t n_buckets = c.bucket_mask + 1;
+  for (uint32_t r0 = 0; r0 < n_buckets; r0 += 4) {
+    uint32_t r = r0 + grp;
+    int32_t word = -1;
+    if (r < n_buckets) word = gram_bucket(tbl, gh, r, c.bucket_mask)[sub];
+    int32_t count = __shfl(word, lane & ~15);
+    bool full = count >= kBucketSlots;
+    bool cand = sub >= 1 && word >= 0 && (sub - 1) < (full ? kBucketSlots : count);
+    int32_t j = 0, e = 0, old_j = 0, new_j = 0;
+    bool hit = false;
+    if (cand) {
+      j = c.y.pos_path(word);
+      e = c.y.pos_index(word);
+      if (j != c.i && j < c.y.N) {
+        old_j = c.y.old_len(j);
+        if (e < old_j) {                 // postings at or beyond old_j belong to case (a)
+          new_j = c.y.new_len(j, old_j);
+          hit = gram_equals_query(c, j, e, old_j);
+        }
+      }
+    }
+    sink.push(c.y, hit, make_match(c.y, j, e, old_j, new_j));
+    if (__ballot(!full || r >= n_buckets) != 0) break;
+  }
+}
+
+// ---------------------------------------------------------------- the one-wave front end
+//
+// Index mode runs one wave64 per (problem, path).  The step is a chain of
+// dependent memory round trips, and every launch starts with a cold L2, so the
+// front end is laid out to need only three of them before the LDS work:
+//   1. the meta rows (length + last tokens) of all paths and the step's input:
+//      the query, the index hashes, the own append and the matches among the
+//      newest positions all follow from these without touching the histories;
+//   2. the index buckets of the query (and the fill counts for the inserts);
+//   3. for every posting found, its verify tokens together with its whole
+//      continuation (tokens and probabilities), kept in LDS for the DAG build.
+
+struct Head {                   // a path's end before this step
+  int32_t old_len, new_len;
+  int32_t tail[CSD_MAX_QUERY_LEN];   // tail[a] = a-th token from the old end
+};
+
+__device__ __forceinline__ int32_t pick(const int32_t (&arr)[CSD_MAX_QUERY_LEN], int32_t idx) {
+  int32_t r = 0;
+#pragma unroll
+  for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) r = (idx == a) ? arr[a] : r;
+  return r;
+}
+
+__device__ __forceinline__ Head load_head(const Paths& y, int32_t kmax, int32_t j) {
+  Head h;
+  const int4* m = reinterpret_cast<const int4*>(y.meta_old + (int64_t)j * y.meta_stride);
+  int4 a = m[0];
+  int4 b = kmax > 3 ? m[1] : int4{0, 0, 0, 0};
+  int32_t c = kmax > 7 ? y.meta_old[(int64_t)j * y.meta_stride + 8] : 0;
+  h.old_len = a.x;
+  h.tail[0] = a.y; h.tail[1] = a.z; h.tail[2] = a.w;
+  h.tail[3] = b.x; h.tail[4] = b.y; h.tail[5] = b.z; h.tail[6] = b.w;
+  h.tail[7] = c;
+  h.new_len = y.new_len(j, h.old_len);
+  return h;
+}
+
+// Lengths of path j: from the LDS cache for the first kLenCache paths.
+__device__ __forceinline__ void lens_of(const Lds& s, const Paths& y, int32_t j, int32_t& old_j,
+                                        int32_t& new_j) {
+  if (j < kLenCache) {
+    old_j = s.len_old[j];
+    new_j = s.len_new[j];
+  } else {
+    old_j = y.old_len(j);
+    new_j = y.new_len(j, old_j);
+  }
+}
+
+// Appends the hits of all 64 lanes to the match list (one wave: the count lives
+// in a register).  Returns each hit's slot, -1 for lanes without one.
+__device__ __forceinline__ int32_t wave_push(Lds& s, int32_t& n_match, bool hit, Match m, int lane) {
+  u64 mask = __ballot(hit);
+  int32_t slot = n_match + (int32_t)__popcll(mask & ((1ull << lane) - 1ull));
+  n_match += (int32_t)__popcll(mask);
+  if (!hit) return -1;
+  if (slot < kMatchCap) s.match[slot] = m;
+  return slot;
+}
+
+// The own row's append when the step carries one token per path, from values
+// already in registers (no further loads).
+__device__ __forceinline__ void append_own_single(const IndexView& ix, const Paths& y, int64_t row,
+                                                  int32_t i, const Head& me, int32_t st_i,
+                                                  float sp_i, int lane) {
+  int32_t cnt = me.new_len - me.old_len;                 // 0 or 1
+  if (lane <= ix.kmax) {
+    int32_t a = lane - 1;
+    int32_t v = 0;
+    if (lane == 0) v = me.new_len;
+    else if (a < cnt) v = st_i;
+    else if (a < me.new_len) v = pick(me.tail, a - cnt);
+    ix.meta_new[row * ix.meta_stride + lane] = v;
+  }
+  if (lane == 0) {
+    uint32_t flags = 0;
+    if (cnt == 1) {
+      ix.tok[row * ix.max_len + me.old_len] = st_i;
+      ix.pq[row * ix.max_len + me.old_len] = y.sp ? quantize_prob(sp_i) : 65536u;
+      if (st_i < 0 || st_i >= ix.vocab) flags |= CSD_STATUS_TOKEN_RANGE;
+    } else if (!y.sc || y.sc[i] >= 1) {
+      flags |= CSD_STATUS_CAPACITY;                      // a token was offered but the path is full
+    }
+    if (flags) atomicOr(ix.status, flags);
+  }
+}
+
+// Eq. 3 through the hash index with the continuations fetched in the same
+// round trip as the verification.  Adds its hits behind the n_fresh matches
+// already listed; hit number x (0-based among these) gets window x.
+template <int LCAP>
+__device__ __forceinline__ void lookup_with_windows(Lds& s, const Ctx& c, int32_t L,
+                                                    int32_t win_cap, int32_t n_fresh,
+                                                    int32_t& n_match, GramHash gh, int32_t word) {
+  const int lane = c.tid;
+  const Paths& y = c.y;
+  int32_t* tbl = gram_table(const_cast<int32_t*>(c.gram), c.q, c.bucket_mask);
+  const int sub = lane & 15;          // word of the bucket this lane reads
+  const int grp = lane >> 4;          // which of the 4 buckets of a batch
+  const uint32_t n_buckets = c.bucket_mask + 1;
+  for (uint32_t r0 = 0; r0 < n_buckets; r0 += 4) {
+    int32_t count = __shfl(word, lane & ~15);
+    bool full = count >= kBucketSlots;
+    bool seq_ends = __ballot(!full || r0 + grp >= n_buckets) != 0;
+    int32_t next_word = -1;           // next batch: in flight while this one is processed
+    if (!seq_ends && r0 + 4 + grp < n_buckets)
+      next_word = gram_bucket(tbl, gh, r0 + 4 + grp, c.bucket_mask)[sub];
+    bool cand = sub >= 1 && word >= 0 && (sub - 1) < (full ? kBucketSlots : count);
+    int32_t j = y.pos_path(word), e = y.pos_index(word), old_j = 0, new_j = 0;
+    cand = cand && j != c.i && j < y.N;
+    if (cand) {
+      lens_of(s, y, j, old_j, new_j);
+      cand = e < old_j;               // newer positions are matched directly, not looked up
+    }
+    int32_t wv[LCAP];
+    uint32_t wp[LCAP];
+#pragma unroll
+    for (int d = 0; d < LCAP; ++d) {
+      wv[d] = 0;
+      wp[d] = 0;
+    }
+    bool hit = cand;
+    int32_t rem = 0, n_hist = 0;
+    if (cand) {
+      const int32_t* hrow = y.tok + y.cell(j, e);        // history of path j at the posting
+      const uint32_t* prow = y.pq + y.cell(j, e);
+      int32_t tv[CSD_MAX_QUERY_LEN];
+#pragma unroll
+      for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) tv[a] = (a < c.q) ? hrow[-1 - a] : 0;
+      rem = new_j - e;
+      rem = rem < L ? rem : L;
+      n_hist = old_j - e;             // >= 1: continuation tokens that are already history
+      n_hist = n_hist < rem ? n_hist : rem;
+#pragma unroll
+      for (int d = 0; d < LCAP; ++d)
+        if (d < n_hist) {
+          wv[d] = hrow[d];
+          wp[d] = prow[d];
+        }
+#pragma unroll
+      for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) hit = hit && (a >= c.q || tv[a] == c.Q[a]);
+    }
+    if (__ballot(hit && rem > n_hist) != 0) {            // rare: runs into this step's new tokens
+#pragma unroll
+      for (int d = 0; d < LCAP; ++d)
+        if (hit && d >= n_hist && d < rem) {
+          wv[d] = y.token(j, e + d, old_j);
+          wp[d] = y.prob(j, e + d, old_j);
+        }
+    }
+    int32_t slot = wave_push(s, n_match, hit, make_match(y, j, e, old_j, new_j), lane);
+    int32_t w = slot - n_fresh;
+    if (slot >= 0 && w < win_cap) {
+      int32_t* win = s.win + w * 2 * L;
+#pragma unroll
+      for (int d = 0; d < LCAP; ++d)
+        if (d < rem) {
+          win[d] = wv[d];
+          win[L + d] = (int32_t)wp[d];
+        }
+    }
+    if (seq_ends) break;
+    word = next_word;
+  }
+}
+
+// The front end of a row handled by one wave: round trip 1 (heads, query, own
+// append), matches among the newest positions, index lookup with windows.
+// Returns the number of matches; wi tells build_dag which of them have windows;
+// the ticket, if used, must be finished with insert_finish by the caller.
+template <int LCAP>
+__device__ __forceinline__ int32_t wave_front_end(Lds& s, Ctx& c, const IndexView& ix, int32_t p,
+                                                  int32_t k, int32_t L, WinInfo& wi,
+                                                  InsertTicket& ticket, bool& ticket_used) {
+  const int lane = c.tid;
+  const Paths& y = c.y;
+  const int64_t row = (int64_t)p * ix.N + c.i;
+  // ---- round trip 1: every load here has an address known from the kernel arguments
+  Head me = load_head(y, ix.kmax, c.i);                 // same address in every lane
+  Head hj = load_head(y, ix.kmax, lane < y.N ? lane : 0);
+  int32_t st_i = 0;
+  float sp_i = 1.0f;
+  if (y.n == 1) {
+    st_i = y.st[c.i];
+    if (y.sp) sp_i = y.sp[c.i];
+  }
+  const int32_t old_i = me.old_len, cnt_i = me.new_len - me.old_len;
+  c.len_i = me.new_len;
+  c.q = k < c.len_i ? k : c.len_i;
+#pragma unroll
+  for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) {
+    int32_t v = 0;
+    if (a < c.q) {
+      if (a >= cnt_i) v = pick(me.tail, a - cnt_i);
+      else v = y.n == 1 ? st_i : y.st[(int64_t)c.i * y.n + cnt_i - 1 - a];
+    }
+    c.Q[a] = v;
+  }
+  int32_t* gram = const_cast<int32_t*>(c.gram);
+  ticket_used = false;
+  if (y.n > 0) {        // also when this path takes no token: its meta row moves to the new buffer
+    if (y.n == 1) append_own_single(ix, y, row, c.i, me, st_i, sp_i, lane);
+    else append_row<kWave, false>(ix, y, p, c.i, old_i, me.new_len, lane);
+    if (cnt_i == 1) {   // the grams that end before the new position are the old tail
+      ticket = insert_begin(gram, c.bucket_mask, ix.kmax, me.tail, old_i, lane);
+      ticket_used = true;
+    } else {
+      for (int32_t t = 0; t < cnt_i; ++t)
+        gram_insert_position(gram, c.bucket_mask, ix.kmax, y, c.i, old_i + t, old_i, lane);
+    }
+  }
+  // ---- round trip 2 starts: first batch of the query's buckets (with the fill counts above)
+  GramHash gh{0u, 1u};
+  int32_t word = -1;
+  if (c.q > 0) {
+    gh = query_hash(c);
+    if ((uint32_t)(lane >> 4) <= c.bucket_mask)
+      word = gram_bucket(gram_table(gram, c.q, c.bucket_mask), gh, (uint32_t)(lane >> 4),
+                         c.bucket_mask)[lane & 15];
+  }
+  // heads of all paths: lengths into LDS, matches among the positions appended by this launch
+  int32_t n_match = 0;
+  for (int32_t j0 = 0; j0 < y.N; j0 += kWave) {
+    int32_t j = j0 + lane;
+    bool have = j < y.N;
+    if (j0 > 0) hj = load_head(y, ix.kmax, have ? j : 0);
+    if (have && j < kLenCache) {
+      s.len_old[j] = hj.old_len;
+      s.len_new[j] = hj.new_len;
+    }
+    bool live = have && j != c.i && c.q > 0;
+    if (y.n == 1) {                         // the usual decode step: compare the old tail
+      bool hit = live && hj.new_len > hj.old_len && hj.old_len >= c.q;
+#pragma unroll
+      for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) hit = hit && (a >= c.q || hj.tail[a] == c.Q[a]);
+      wave_push(s, n_match, hit, make_match(y, j, hj.old_len, hj.old_len, hj.new_len), lane);
+    } else {
+      for (int32_t t = 0; t < y.n; ++t) {
+        int32_t e = hj.old_len + t;
+        bool hit = live && e < hj.new_len && e >= c.q && gram_equals_query(c, j, e, hj.old_len);
+        wave_push(s, n_match, hit, make_match(y, j, e, hj.old_len, hj.new_len), lane);
+      }
+    }
+  }
+  if (ticket_used) insert_claim(ticket, gram, c.bucket_mask, lane);
+  wi.n_fresh = n_match;
+  wi.win_cap = kWinWords / (2 * L);
+  if (c.q > 0) lookup_with_windows<LCAP>(s, c, L, wi.win_cap, wi.n_fresh, n_match, gh, word);
+  if (lane == 0) s.n_match = n_match;
+  return n_match;
+}
+
+}  // namespace csd
