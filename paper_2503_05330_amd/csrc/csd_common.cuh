@@ -200,6 +200,7 @@ struct Slot {
 
 struct Lds {
   Slot table[kTableCap];
+  uint16_t link[kTableCap];     // edge slot -> slot of its target node (tier 1)
   Match match[kMatchCap];
   int32_t win[kWinWords];       // per cached match: L continuation tokens, then their L probabilities
   int32_t len_old[kLenCache];

@@ -3,9 +3,9 @@
 //
 // Two tiers with identical results (all sums are exact integers):
 //   tier 1  all L layers at once: layer d owns one region of the LDS table that
-//           holds its edges (d,u,v) and its nodes (d,*,v); after the build every
-//           edge's value is replaced by the weight the walk ranks it by, so one
-//           walk step is a single LDS read per lane plus a wave argmax;
+//           holds its edges (d,u,v) -> (count, probability sum) and its nodes
+//           (d,*,v) -> in-weight; every edge slot links to its target node, so
+//           the walk can fetch all ranks before its serial part starts;
 //   tier 2  bounded memory for any input: one layer at a time, and within a
 //           layer one class of tokens (by hash residue) at a time.
 #pragma once
@@ -24,10 +24,10 @@ __device__ __forceinline__ void table_clear(Lds& s, uint32_t n_slots, int tid) {
   if (tid == 0) s.overflow = 0;
 }
 
-// table[key] += delta inside a region, inserting the key if new.  Sets
-// s.overflow when the region has no free slot (the caller then falls back) —
-// never spins.
-__device__ __forceinline__ void table_add(Lds& s, Region r, u64 key, u64 delta) {
+// table[key] += delta inside a region, inserting the key if new; returns the
+// slot.  Sets s.overflow when the region has no free slot (the caller then
+// falls back) — never spins.
+__device__ __forceinline__ uint32_t table_add(Lds& s, Region r, u64 key, u64 delta) {
   uint32_t h = dag_hash(key) & r.mask;
   for (uint32_t probe = 0; probe <= r.mask; ++probe) {
     Slot* slot = &s.table[r.base + h];
@@ -38,11 +38,12 @@ __device__ __forceinline__ void table_add(Lds& s, Region r, u64 key, u64 delta) 
     }
     if (cur == key) {
       atomicAdd(&slot->val, delta);
-      return;
+      return r.base + h;
     }
     h = (h + 1) & r.mask;
   }
   s.overflow = 1;
+  return r.base;
 }
 
 __device__ __forceinline__ u64 table_get(const Lds& s, Region r, u64 key) {
@@ -100,10 +101,14 @@ __device__ __forceinline__ Tier1 tier1_geometry(int32_t M, int32_t L) {
   return Tier1{size};
 }
 
-// Eq. 5: every (match, layer) instance adds (1, p) to its edge (d,u,v) and to
-// its node (d,*,v).
+// Eq. 5: every (match, layer) instance adds (1, p) to its edge (d,u,v) and its
+// weight to its node (d,*,v).  The weight is linear in (count, probability
+// sum), so a node's value is directly the in-weight the walk ranks by:
+// sum over instances of  alpha_q * p + (65536 - alpha_q) * 65536.  Every edge
+// slot also records where its target node sits (s.link).
 template <int BLOCK>
-__device__ __forceinline__ Tier1 build_dag(Lds& s, const Ctx& c, int32_t M, int32_t L, WinInfo wi) {
+__device__ __forceinline__ Tier1 build_dag(Lds& s, const Ctx& c, int32_t M, int32_t L, WinInfo wi,
+                                           uint32_t alpha_q) {
   Tier1 t1 = tier1_geometry(M, L);
   table_clear<BLOCK>(s, t1.region * (uint32_t)L, c.tid);
   block_sync<BLOCK>();
@@ -127,41 +132,67 @@ __device__ __forceinline__ Tier1 build_dag(Lds& s, const Ctx& c, int32_t M, int3
     }
     if (alive && !s.overflow) {
       Region r = t1.layer(d);
-      table_add(s, r, dag_key(d, u, v), w);
-      table_add(s, r, dag_key(d, kAnyTok, v), w);
+      uint32_t edge = table_add(s, r, dag_key(d, u, v), w);
+      uint32_t node = table_add(s, r, dag_key(d, kAnyTok, v), weight_key(w, alpha_q));
+      s.link[edge] = (uint16_t)node;                  // all instances of an edge agree
     }
   }
   block_sync<BLOCK>();
   return t1;
 }
 
-// Replaces every edge's (C, S) by the weight the greedy step ranks it by:
-// the in-weight of its target node (score_mode 0) or its own weight (mode 1).
-template <int BLOCK>
-__device__ __forceinline__ void score_edges(Lds& s, Tier1 t1, int32_t L, uint32_t alpha_q,
-                                            int score_mode, int tid) {
-  uint32_t n_slots = t1.region * (uint32_t)L;
-  for (uint32_t h = tid; h < n_slots; h += BLOCK) {
-    Slot x = s.table[h];
-    if (x.key == kEmpty || key_u(x.key) == kAnyTok) continue;
-    int32_t d = (int32_t)(x.key >> 58);
-    u64 w = score_mode ? x.val : table_get(s, t1.layer(d), dag_key(d, kAnyTok, key_v(x.key)));
-    s.table[h].val = weight_key(w, alpha_q);          // only edge slots are rewritten
-  }
-  block_sync<BLOCK>();
+// The weight the greedy step ranks edge slot `e` by: the in-weight of its
+// target node (score_mode 0, the rule after Eq. 5) or its own weight (mode 1).
+__device__ __forceinline__ u64 edge_rank(const Lds& s, uint32_t e, u64 edge_val, uint32_t alpha_q,
+                                         int score_mode) {
+  return score_mode ? weight_key(edge_val, alpha_q) : s.table[s.link[e]].val;
 }
 
-// Greedy walk over the scored tables (rule after Eq. 5).
-template <int BLOCK>
-__device__ __forceinline__ void walk_dag(Lds& s, const Ctx& c, Tier1 t1, int32_t L, DraftOut& o) {
+// Greedy walk over the finished tables (rule after Eq. 5).  When a layer's
+// region fits the wave (one slot per lane) every lane fetches its slot of ALL
+// layers, and the ranks behind them, before the walk starts: the serial part is
+// then a compare, a ballot and a lane read per layer, with no memory latency.
+template <int BLOCK, int LCAP>
+__device__ __forceinline__ void walk_dag(Lds& s, const Ctx& c, Tier1 t1, int32_t L,
+                                         uint32_t alpha_q, int score_mode, DraftOut& o) {
   int32_t cur = c.Q[0];
+  if (BLOCK == kWave && t1.region <= (uint32_t)kWave) {
+    u64 key[LCAP], rank[LCAP];
+    const bool mine = (uint32_t)c.tid < t1.region;
+#pragma unroll
+    for (int d = 1; d <= LCAP; ++d) {
+      key[d - 1] = kEmpty;
+      rank[d - 1] = 0;
+      if (d <= L && mine) {
+        uint32_t e = (uint32_t)(d - 1) * t1.region + (uint32_t)c.tid;
+        Slot x = s.table[e];
+        key[d - 1] = x.key;
+        if (x.key != kEmpty && key_u(x.key) != kAnyTok)
+          rank[d - 1] = edge_rank(s, e, x.val, alpha_q, score_mode);
+      }
+    }
+#pragma unroll
+    for (int d = 1; d <= LCAP; ++d) {
+      if (d > L) break;
+      u64 want = dag_key(d, (uint32_t)cur, 0) >> 29;
+      Cand best = cand_none();
+      if ((key[d - 1] >> 29) == want) best = Cand{rank[d - 1], (int32_t)key_v(key[d - 1])};
+      best = wave_argmax(best);
+      if (best.v == INT_MAX) break;                   // leaf: no edge leaves cur
+      note_choice(o, best, d, c.tid);
+      cur = best.v;
+    }
+    return;
+  }
   for (int32_t d = 1; d <= L; ++d) {
     Region r = t1.layer(d);
     u64 want = dag_key(d, (uint32_t)cur, 0) >> 29;
     Cand best = cand_none();
     for (uint32_t h = c.tid; h <= r.mask; h += BLOCK) {
       Slot x = s.table[r.base + h];
-      if ((x.key >> 29) == want) best = cand_best(best, Cand{x.val, (int32_t)key_v(x.key)});
+      if ((x.key >> 29) == want)
+        best = cand_best(best, Cand{edge_rank(s, r.base + h, x.val, alpha_q, score_mode),
+                                    (int32_t)key_v(x.key)});
     }
     best = block_argmax<BLOCK>(s, best, c.tid, d & 1);
     if (best.v == INT_MAX) break;                     // leaf: no edge leaves cur

@@ -83,12 +83,9 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
     if (M > 0) {
       bool streaming = M > kMatchCap;
       if (!streaming) {
-        Tier1 t1 = build_dag<BLOCK>(s, c, M, L, WinInfo{M, 0});
+        Tier1 t1 = build_dag<BLOCK>(s, c, M, L, WinInfo{M, 0}, a.alpha_q);
         streaming = s.overflow != 0;
-        if (!streaming) {
-          score_edges<BLOCK>(s, t1, L, a.alpha_q, a.score_mode, c.tid);
-          walk_dag<BLOCK>(s, c, t1, L, o);
-        }
+        if (!streaming) walk_dag<BLOCK, 1>(s, c, t1, L, a.alpha_q, a.score_mode, o);
       }
       if (streaming)
         walk_streaming<BLOCK>(s, c, L, a.alpha_q, a.score_mode, ix.status, o, [&](auto f) {
@@ -130,12 +127,9 @@ __global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn i
   if (M > 0) {
     bool streaming = M > kMatchCap;
     if (!streaming) {
-      Tier1 t1 = build_dag<kWave>(s, c, M, L, wi);
+      Tier1 t1 = build_dag<kWave>(s, c, M, L, wi, a.alpha_q);
       streaming = s.overflow != 0;
-      if (!streaming) {
-        score_edges<kWave>(s, t1, L, a.alpha_q, a.score_mode, c.tid);
-        walk_dag<kWave>(s, c, t1, L, o);
-      }
+      if (!streaming) walk_dag<kWave, LCAP>(s, c, t1, L, a.alpha_q, a.score_mode, o);
     }
     if (streaming)
       walk_streaming<kWave>(s, c, L, a.alpha_q, a.score_mode, ix.status, o, [&](auto f) {
@@ -147,11 +141,12 @@ __global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn i
         }
       });
   }
-  write_outputs<kWave>(a, row, o, c.tid);
-  if (a.targets) write_accept(a, row, o, target, c.tid);
+  // the posting stores wait on atomics issued long ago: do them before the output stores
   if (ticket_used)
     insert_finish(ticket, const_cast<int32_t*>(c.gram), c.bucket_mask,
                   c.y.pos(c.i, c.len_i - 1), c.tid);
+  write_outputs<kWave>(a, row, o, c.tid);
+  if (a.targets) write_accept(a, row, o, target, c.tid);
 }
 
 __global__ __launch_bounds__(256) void accept_kernel(int64_t rows, int32_t L,
@@ -299,7 +294,7 @@ __global__ __launch_bounds__(kScanBlock) void dump_edge_rows_scan_kernel(
   int32_t M = s.n_match;
   if (M == 0) { if (c.tid == 0) counts[row] = 0; return; }
   if (M > kMatchCap) { if (c.tid == 0) counts[row] = -1; return; }
-  Tier1 t1 = build_dag<BLOCK>(s, c, M, L, WinInfo{M, 0});
+  Tier1 t1 = build_dag<BLOCK>(s, c, M, L, WinInfo{M, 0}, 0u);
   if (s.overflow) { if (c.tid == 0) counts[row] = -1; return; }
   emit_sorted_edges<BLOCK>(s, t1.region * (uint32_t)L, c.tid, &n_edges,
                            tmp_keys + (int64_t)row * kTableCap, tmp_vals + (int64_t)row * kTableCap);
@@ -327,7 +322,7 @@ __global__ __launch_bounds__(kWave) void dump_edge_rows_wave_kernel(IndexView ix
   block_sync<kWave>();
   if (M == 0) { if (c.tid == 0) counts[row] = 0; return; }
   if (M > kMatchCap) { if (c.tid == 0) counts[row] = -1; return; }
-  Tier1 t1 = build_dag<kWave>(s, c, M, L, wi);
+  Tier1 t1 = build_dag<kWave>(s, c, M, L, wi, 0u);
   if (s.overflow) { if (c.tid == 0) counts[row] = -1; return; }
   emit_sorted_edges<kWave>(s, t1.region * (uint32_t)L, c.tid, &n_edges,
                            tmp_keys + (int64_t)row * kTableCap, tmp_vals + (int64_t)row * kTableCap);
