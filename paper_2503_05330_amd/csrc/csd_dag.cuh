@@ -157,19 +157,27 @@ __device__ __forceinline__ void walk_dag(Lds& s, const Ctx& c, Tier1 t1, int32_t
                                          uint32_t alpha_q, int score_mode, DraftOut& o) {
   int32_t cur = c.Q[0];
   if (BLOCK == kWave && t1.region <= (uint32_t)kWave) {
+    // Three rounds of independent LDS reads (slot, link, linked node), none of them behind a
+    // branch, so that the reads of all layers are in flight together.
     u64 key[LCAP], rank[LCAP];
+    uint32_t at[LCAP], node[LCAP];
     const bool mine = (uint32_t)c.tid < t1.region;
 #pragma unroll
+    for (int d = 1; d <= LCAP; ++d)
+      at[d - 1] = (d <= L && mine) ? (uint32_t)(d - 1) * t1.region + (uint32_t)c.tid : 0u;
+#pragma unroll
     for (int d = 1; d <= LCAP; ++d) {
-      key[d - 1] = kEmpty;
-      rank[d - 1] = 0;
-      if (d <= L && mine) {
-        uint32_t e = (uint32_t)(d - 1) * t1.region + (uint32_t)c.tid;
-        Slot x = s.table[e];
-        key[d - 1] = x.key;
-        if (x.key != kEmpty && key_u(x.key) != kAnyTok)
-          rank[d - 1] = edge_rank(s, e, x.val, alpha_q, score_mode);
-      }
+      Slot x = s.table[at[d - 1]];
+      key[d - 1] = (d <= L && mine) ? x.key : kEmpty;
+      rank[d - 1] = x.val;
+      node[d - 1] = (uint32_t)s.link[at[d - 1]] & (uint32_t)(kTableCap - 1);   // stale links stay in range
+    }
+    if (score_mode == 0) {
+#pragma unroll
+      for (int d = 1; d <= LCAP; ++d) rank[d - 1] = s.table[node[d - 1]].val;
+    } else {
+#pragma unroll
+      for (int d = 1; d <= LCAP; ++d) rank[d - 1] = weight_key(rank[d - 1], alpha_q);
     }
 #pragma unroll
     for (int d = 1; d <= LCAP; ++d) {
