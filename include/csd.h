@@ -68,7 +68,9 @@ typedef enum {
 /* csd_config.flags: how matches are found (Eq. 3).  Both give identical results. */
 #define CSD_MATCH_AUTO 0   /* library picks                                         */
 #define CSD_MATCH_SCAN 1   /* compare the query against every history position      */
-#define CSD_MATCH_INDEX 2  /* look the query up in the incremental n-gram hash index */
+#define CSD_MATCH_INDEX 2  /* look the query up in the incremental n-gram hash index, which
+                              holds grams of max_query_len tokens: set max_query_len to the
+                              query_len the decode loop uses; shorter queries are scanned */
 
 /* Sticky device-side status bits, read with csd_status. */
 #define CSD_STATUS_CAPACITY 1u     /* an append was clipped at max_len               */
@@ -135,7 +137,8 @@ int csd_draft(csd_index* index, int32_t query_len, int32_t draft_len, int32_t* d
 int csd_accept(csd_index* index, const int32_t* d_draft_tokens, const int32_t* d_draft_len,
                const int32_t* d_targets, int32_t draft_len, int32_t* d_accept_len, void* stream);
 
-/* One decoding step in ONE launch: csd_append(d_tokens, d_probs, d_counts, n),
+/* One decoding step in ONE launch (two when n > 1 with the index matcher):
+ * csd_append(d_tokens, d_probs, d_counts, n),
  * then csd_draft(query_len, draft_len, ...) on the grown paths, then, if
  * d_targets is given, csd_accept of the fresh drafts (Algorithm 1 run at step t
  * of the generation, followed by the check of "Draft acceptance").  Results are

@@ -99,7 +99,7 @@ Layout make_layout(const csd_config* c) {
     uint32_t nb = 4;
     while ((uint64_t)nb * 8 < positions) nb <<= 1;
     l.n_buckets = nb;
-    l.gram_words = (size_t)c->n_problems * c->max_query_len * nb * kBucketWords;
+    l.gram_words = (size_t)c->n_problems * nb * kBucketWords;
     at += align_up(l.gram_words * sizeof(int32_t));
   }
   l.total = at;
@@ -286,11 +286,20 @@ int csd_step(csd_index* h, const int32_t* d_tokens, const float* d_probs, const 
   if (rc != CSD_OK) return rc;
   rc = note_append(h, d_counts != nullptr, n);
   if (rc != CSD_OK) return rc;
+  DraftArgs a{query_len, draft_len, h->alpha_q, h->cfg.score_mode, d_draft_tokens, d_draft_len,
+              d_token_scores, d_path_scores, d_targets, d_accept_len};
+  if (h->indexed && n != 1) {
+    // the one-wave kernel fuses the append of ONE token per path; longer steps append first
+    int64_t rows = (int64_t)h->view.P * h->view.N;
+    append_kernel<<<(uint32_t)rows, 256, 0, as_stream(stream)>>>(
+        view_in_place(h), StepIn{d_tokens, d_probs, d_counts, n});
+    launch_draft(h, view_in_place(h), StepIn{nullptr, nullptr, nullptr, 0}, a, as_stream(stream));
+    CSD_HIP(hipGetLastError());
+    return CSD_OK;
+  }
   IndexView v = h->view;
   v.meta_old = h->meta[h->cur];
   v.meta_new = h->meta[h->cur ^ 1];
-  DraftArgs a{query_len, draft_len, h->alpha_q, h->cfg.score_mode, d_draft_tokens, d_draft_len,
-              d_token_scores, d_path_scores, d_targets, d_accept_len};
   launch_draft(h, v, StepIn{d_tokens, d_probs, d_counts, n}, a, as_stream(stream));
   CSD_HIP(hipGetLastError());
   h->cur ^= 1;

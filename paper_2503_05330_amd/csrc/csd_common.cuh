@@ -133,7 +133,7 @@ struct IndexView {              // device state inside the caller's workspace
                                 //   tokens newest first}: one aligned load tells a path's end
   int32_t* meta_new;            // same rows after it (may alias meta_old when nothing else reads)
   uint32_t* status;             // sticky CSD_STATUS_* bits
-  int32_t* gram;                // n-gram index [P][kmax][n_buckets][16], or null (scan mode)
+  int32_t* gram;                // kmax-gram index [P][n_buckets][16], or null (scan mode)
   uint32_t bucket_mask;         // n_buckets - 1 (power of two)
   int32_t meta_stride;          // ints per meta row: 1 + kmax rounded up to a multiple of 4
   int32_t eshift;               // positions are packed as (path << eshift) | index
@@ -295,8 +295,7 @@ __device__ __forceinline__ Ctx make_ctx(const IndexView& ix, const StepIn& in, i
   c.y.sc = (in.n && in.counts) ? in.counts + (int64_t)p * ix.N : nullptr;
   c.y.N = ix.N;
   c.y.max_len = ix.max_len;
-  c.gram = ix.gram ? ix.gram + (int64_t)p * ix.kmax * ((int64_t)ix.bucket_mask + 1) * kBucketWords
-                   : nullptr;
+  c.gram = ix.gram ? ix.gram + (int64_t)p * ((int64_t)ix.bucket_mask + 1) * kBucketWords : nullptr;
   c.bucket_mask = ix.bucket_mask;
   c.kmax = ix.kmax;
   c.len_i = 0;

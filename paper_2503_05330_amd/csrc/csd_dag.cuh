@@ -113,8 +113,12 @@ __device__ __forceinline__ Tier1 build_dag(Lds& s, const Ctx& c, int32_t M, int3
   table_clear<BLOCK>(s, t1.region * (uint32_t)L, c.tid);
   block_sync<BLOCK>();
   int32_t items = M * L;
+  const float inv_m = 1.0f / (float)M;
   for (int32_t idx = c.tid; idx < items; idx += BLOCK) {
-    int32_t d = idx / M + 1;
+    int32_t d = (int32_t)((float)idx * inv_m);        // idx / M for idx < 2^15, fixed up below
+    d += (d + 1) * M <= idx;
+    d -= d * M > idx;
+    d += 1;
     int32_t mi = idx - (d - 1) * M;
     Match m = s.match[mi];
     uint32_t u, v;

@@ -1,15 +1,16 @@
 // csd — the incrementally updated n-gram hash index (the "dynamic draft pool"
 // of the Method section made searchable) and the append of a step's tokens.
 //
-// For every gram length g = 1..kmax one table of 64-byte buckets
-// [count, 15 postings].  A posting (j, e) — "the g tokens before index e of
-// path j" — is stored under the hash of those g tokens when token e is
-// appended, so a query finds its matches (Eq. 3) without scanning histories.
-// Bucket r of a gram's probe sequence is (h + r * step) mod n_buckets with an
-// odd step; an insert goes into the first bucket of the sequence that is not
-// full, so a lookup may stop at the first bucket that is not full.  Hash
-// collisions are harmless: every posting is verified against the history
-// before it counts.
+// One table of 64-byte buckets [count, 15 postings] per problem, for grams of
+// length kmax (the configured maximum query length; shorter queries, which a
+// decode loop only issues while a path is shorter than kmax, are matched by
+// scan).  A posting (j, e) — "the kmax tokens before index e of path j" — is
+// stored under the hash of those tokens when token e is appended, so a query
+// finds its matches (Eq. 3) without scanning histories.  Bucket r of a gram's
+// probe sequence is (h + r * step) mod n_buckets with an odd step; an insert
+// goes into the first bucket of the sequence that is not full, so a lookup may
+// stop at the first bucket that is not full.  Hash collisions are harmless:
+// every posting is verified against the history before it counts.
 #pragma once
 
 #include "csd_common.cuh"
@@ -33,12 +34,17 @@ __device__ __forceinline__ GramHash gram_hash_end(uint32_t acc, int g) {
   uint32_t step = ((x * 0x27D4EB2Fu) >> 7) | 1u;
   return GramHash{h, step};
 }
-__device__ __forceinline__ int32_t* gram_table(int32_t* gram, int g, uint32_t mask) {
-  return gram + (int64_t)(g - 1) * ((int64_t)mask + 1) * kBucketWords;
-}
 __device__ __forceinline__ int32_t* gram_bucket(int32_t* tbl, GramHash gh, uint32_t r,
                                                 uint32_t mask) {
   return tbl + (int64_t)((gh.h + r * gh.step) & mask) * kBucketWords;
+}
+
+// Forces a loaded value to be waited for here and not earlier: everything that
+// uses it depends on this statement.  Lets independent loads issued before it
+// share one memory round trip.
+template <class T>
+__device__ __forceinline__ void consume_here(T& v) {
+  asm volatile("" : "+v"(v));
 }
 
 // General insert, by one whole wave: reads the fill counts of 64 buckets of
@@ -66,87 +72,71 @@ __device__ __forceinline__ void gram_insert_from(int32_t* tbl, uint32_t mask, Gr
   }
 }
 
-// Inserts the postings of position e of path i for every gram length
-// g = 1..kmax, by one whole wave (used for bulk appends).
+// Inserts the posting of position e of path i (e >= kmax), by one whole wave
+// (used for bulk appends).
 __device__ __forceinline__ void gram_insert_position(int32_t* gram, uint32_t mask, int32_t kmax,
                                                      const Paths& y, int32_t i, int32_t e,
                                                      int32_t old_i, int lane) {
+  if (e < kmax) return;
   uint32_t acc = kGramSeed;
-  for (int32_t g = 1; g <= kmax && g <= e; ++g) {
-    acc = gram_hash_add(acc, y.token(i, e - g, old_i));
-    gram_insert_from(gram_table(gram, g, mask), mask, gram_hash_end(acc, g), 0u, y.pos(i, e), lane);
-  }
+  for (int32_t g = 1; g <= kmax; ++g) acc = gram_hash_add(acc, y.token(i, e - g, old_i));
+  gram_insert_from(gram, mask, gram_hash_end(acc, kmax), 0u, y.pos(i, e), lane);
 }
 
-// Split-phase insert of ONE new position into all kmax tables by one wave, so
-// that its two memory round trips overlap the lookup's: lanes 8g-8 .. 8g-1 look
-// at the first 8 buckets of gram length g's sequence.
+// Split-phase insert of ONE new position by one wave, so that its two memory
+// round trips overlap the lookup's: lanes 0..15 look at the first 16 buckets of
+// the gram's sequence.
+constexpr int kInsertLanes = 16;
 struct InsertTicket {
-  GramHash gh;                  // of this lane's gram length
-  int32_t fill;                 // fill count of bucket (lane & 7) of that sequence
-  int32_t first;                // first open bucket among the 8, or -1
-  int32_t claimed;              // slot the leader lane got from the atomic, or kBucketSlots
-  bool live;                    // this lane's gram length exists at this position
+  GramHash gh;
+  int32_t fill;                 // fill count of bucket `lane` of the sequence (lanes < 16)
+  int32_t first;                // first open bucket among the 16, or -1
+  int32_t claimed;              // lane 0: slot the atomic returned, or kBucketSlots
+  bool live;                    // the position has kmax tokens before it
 };
 
-// Phase 1: hashes of the grams that end just before the new position (tail[a] =
-// a-th token before it) and the fill-count loads.
+// Phase 1: hash of the gram that ends just before the new position (tail[a] =
+// a-th token before it) and the fill-count loads (not waited for here).
 __device__ __forceinline__ InsertTicket insert_begin(int32_t* gram, uint32_t mask, int32_t kmax,
                                                      const int32_t (&tail)[CSD_MAX_QUERY_LEN],
                                                      int32_t n_before, int lane) {
   InsertTicket t;
-  const int g = (lane >> 3) + 1;
-  t.gh = GramHash{0u, 1u};
   uint32_t acc = kGramSeed;
 #pragma unroll
-  for (int a = 1; a <= CSD_MAX_QUERY_LEN; ++a) {
-    if (a <= kmax) {                                // uniform: longer grams are not indexed
-      acc = gram_hash_add(acc, tail[a - 1]);
-      if (a == g) t.gh = gram_hash_end(acc, a);
-    }
-  }
-  t.live = g <= kmax && g <= n_before;
-  t.fill = kBucketSlots;
+  for (int a = 1; a <= CSD_MAX_QUERY_LEN; ++a)
+    if (a <= kmax) acc = gram_hash_add(acc, tail[a - 1]);
+  t.gh = gram_hash_end(acc, kmax);
+  t.live = kmax <= n_before;
   t.first = -1;
   t.claimed = kBucketSlots;
-  uint32_t r = (uint32_t)(lane & 7);
-  if (t.live && r <= mask) t.fill = gram_bucket(gram_table(gram, g, mask), t.gh, r, mask)[0];
+  uint32_t r = (uint32_t)(lane & (kInsertLanes - 1));   // every lane loads: no branch, no early wait
+  t.fill = gram_bucket(gram, t.gh, r <= mask ? r : 0u, mask)[0];
   return t;
 }
 
-// Phase 2: the leader lane of each gram length claims a slot in the first open bucket.
+// Phase 2: lane 0 claims a slot in the first open bucket.
 __device__ __forceinline__ void insert_claim(InsertTicket& t, int32_t* gram, uint32_t mask,
                                              int lane) {
-  u64 open = __ballot(t.fill < kBucketSlots);
-  uint32_t mine = (uint32_t)(open >> (lane & ~7)) & 0xFFu;
-  t.first = mine ? (int32_t)__ffs((int)mine) - 1 : -1;
-  if (t.live && (lane & 7) == 0 && t.first >= 0)
-    t.claimed = atomicAdd(gram_bucket(gram_table(gram, (lane >> 3) + 1, mask), t.gh,
-                                      (uint32_t)t.first, mask), 1);
+  consume_here(t.fill);
+  bool open = t.live && lane < kInsertLanes && (uint32_t)lane <= mask && t.fill < kBucketSlots;
+  u64 m = __ballot(open);
+  t.first = m ? (int32_t)__ffsll((long long)m) - 1 : -1;
+  if (t.live && lane == 0 && t.first >= 0)
+    t.claimed = atomicAdd(gram_bucket(gram, t.gh, (uint32_t)t.first, mask), 1);
 }
 
-// Phase 3: store the posting; gram lengths whose first 8 buckets were full (or
-// that lost a race for the last slot) take the general insert.
+// Phase 3: store the posting; if the first 16 buckets were full (or the last
+// slot was lost in a race) take the general insert.
 __device__ __forceinline__ void insert_finish(const InsertTicket& t, int32_t* gram, uint32_t mask,
                                               int32_t pos, int lane) {
-  bool leader = t.live && (lane & 7) == 0;
-  bool placed = !leader;
-  if (leader && t.claimed < kBucketSlots) {
-    gram_bucket(gram_table(gram, (lane >> 3) + 1, mask), t.gh, (uint32_t)t.first,
-                mask)[1 + t.claimed] = pos;
-    placed = true;
+  if (!t.live) return;
+  int32_t claimed = __builtin_amdgcn_readfirstlane(t.claimed);
+  if (claimed < kBucketSlots) {
+    if (lane == 0) gram_bucket(gram, t.gh, (uint32_t)t.first, mask)[1 + claimed] = pos;
+    return;
   }
-  u64 todo = __ballot(!placed);
-  while (todo) {
-    int src = (int)__ffsll((long long)todo) - 1;     // a leader lane: gram length src/8 + 1
-    todo &= todo - 1;
-    GramHash gh;
-    gh.h = (uint32_t)__builtin_amdgcn_readlane((int)t.gh.h, src);
-    gh.step = (uint32_t)__builtin_amdgcn_readlane((int)t.gh.step, src);
-    int32_t from = __builtin_amdgcn_readlane(t.first, src);
-    gram_insert_from(gram_table(gram, (src >> 3) + 1, mask), mask, gh,
-                     from < 0 ? 8u : (uint32_t)from, pos, lane);
-  }
+  gram_insert_from(gram, mask, t.gh, t.first < 0 ? (uint32_t)kInsertLanes : (uint32_t)t.first, pos,
+                   lane);
 }
 
 // Stores this row's share of the step (tokens, quantised probabilities, index
@@ -181,7 +171,7 @@ __device__ __forceinline__ void append_row(const IndexView& ix, const Paths& y, 
     ix.pq[row * ix.max_len + old_i + t] = y.sp ? quantize_prob(y.sp[(int64_t)i * y.n + t]) : 65536u;
   }
   if (WITH_INDEX && ix.gram) {
-    int32_t* gram = ix.gram + (int64_t)p * ix.kmax * ((int64_t)ix.bucket_mask + 1) * kBucketWords;
+    int32_t* gram = ix.gram + (int64_t)p * ((int64_t)ix.bucket_mask + 1) * kBucketWords;
     for (int32_t t = tid / kWave; t < cnt; t += BLOCK / kWave)     // one wave per new position
       gram_insert_position(gram, ix.bucket_mask, ix.kmax, y, i, old_i + t, old_i, tid & 63);
   }

@@ -137,7 +137,8 @@ __global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn i
           for (int32_t m = c.tid; m < M; m += kWave) f(s.match[m]);
         } else {
           FnSink<decltype(f)> fs{f};
-          match_index(c, fs);
+          if (c.q == c.kmax) match_index(c, fs);
+          else match_scan<kWave>(c, fs);
         }
       });
   }
@@ -205,8 +206,10 @@ __global__ __launch_bounds__(kWave) void dump_match_bits_wave_kernel(IndexView i
   BitmapSink sink{bits + (int64_t)row * words};
   if (M <= kMatchCap) {
     for (int32_t m = c.tid; m < M; m += kWave) sink.push(c.y, true, s.match[m]);
-  } else if (c.q > 0) {
+  } else if (c.q == c.kmax) {
     match_index(c, sink);
+  } else if (c.q > 0) {
+    match_scan<kWave>(c, sink);
   }
 }
 

@@ -128,8 +128,8 @@ __device__ __forceinline__ void match_index(const Ctx& c, Sink& sink) {
       }
     }
   }
-  GramHash gh = query_hash(c);        // (b) postings of earlier launches
-  int32_t* tbl = gram_table(const_cast<int32_t*>(c.gram), c.q, c.bucket_mask);
+  GramHash gh = query_hash(c);        // (b) postings of earlier launches (needs c.q == kmax)
+  int32_t* tbl = const_cast<int32_t*>(c.gram);
   const int sub = lane & 15;          // word of the bucket this lane reads
   const int grp = lane >> 4;          // which of the 4 buckets of a batch
   uint32_t n_buckets = c.bucket_mask + 1;
@@ -166,9 +166,11 @@ __device__ __forceinline__ void match_index(const Ctx& c, Sink& sink) {
 //   1. the meta rows (length + last tokens) of all paths and the step's input:
 //      the query, the index hashes, the own append and the matches among the
 //      newest positions all follow from these without touching the histories;
-//   2. the index buckets of the query (and the fill counts for the inserts);
+//   2. the index buckets of the query, and the fill counts for the insert;
 //   3. for every posting found, its verify tokens together with its whole
-//      continuation (tokens and probabilities), kept in LDS for the DAG build.
+//      continuation (tokens and probabilities), kept in LDS for the DAG build;
+//      the insert's atomic travels with these.
+// It handles steps that append at most one token per path (in.n <= 1).
 
 struct Head {                   // a path's end before this step
   int32_t old_len, new_len;
@@ -219,6 +221,15 @@ __device__ __forceinline__ int32_t wave_push(Lds& s, int32_t& n_match, bool hit,
   return slot;
 }
 
+struct WaveListSink {           // match list of a one-wave row; push() by all 64 lanes together
+  Lds* s;
+  int32_t* n_match;
+  int lane;
+  __device__ __forceinline__ void push(const Paths&, bool hit, Match m) {
+    wave_push(*s, *n_match, hit, m, lane);
+  }
+};
+
 // The own row's append when the step carries one token per path, from values
 // already in registers (no further loads).
 __device__ __forceinline__ void append_own_single(const IndexView& ix, const Paths& y, int64_t row,
@@ -247,7 +258,8 @@ __device__ __forceinline__ void append_own_single(const IndexView& ix, const Pat
 }
 
 // Eq. 3 through the hash index with the continuations fetched in the same
-// round trip as the verification.  Adds its hits behind the n_fresh matches
+// round trip as the verification.  `word` is the lane's word of the first batch
+// of 4 buckets, already requested.  Adds its hits behind the n_fresh matches
 // already listed; hit number x (0-based among these) gets window x.
 template <int LCAP>
 __device__ __forceinline__ void lookup_with_windows(Lds& s, const Ctx& c, int32_t L,
@@ -255,17 +267,21 @@ __device__ __forceinline__ void lookup_with_windows(Lds& s, const Ctx& c, int32_
                                                     int32_t& n_match, GramHash gh, int32_t word) {
   const int lane = c.tid;
   const Paths& y = c.y;
-  int32_t* tbl = gram_table(const_cast<int32_t*>(c.gram), c.q, c.bucket_mask);
+  int32_t* tbl = const_cast<int32_t*>(c.gram);
   const int sub = lane & 15;          // word of the bucket this lane reads
   const int grp = lane >> 4;          // which of the 4 buckets of a batch
   const uint32_t n_buckets = c.bucket_mask + 1;
   for (uint32_t r0 = 0; r0 < n_buckets; r0 += 4) {
+    consume_here(word);
+    if (r0 + grp >= n_buckets) word = -1;
     int32_t count = __shfl(word, lane & ~15);
     bool full = count >= kBucketSlots;
     bool seq_ends = __ballot(!full || r0 + grp >= n_buckets) != 0;
     int32_t next_word = -1;           // next batch: in flight while this one is processed
-    if (!seq_ends && r0 + 4 + grp < n_buckets)
-      next_word = gram_bucket(tbl, gh, r0 + 4 + grp, c.bucket_mask)[sub];
+    if (!seq_ends) {
+      uint32_t r = r0 + 4 + grp;
+      next_word = gram_bucket(tbl, gh, r < n_buckets ? r : 0u, c.bucket_mask)[sub];
+    }
     bool cand = sub >= 1 && word >= 0 && (sub - 1) < (full ? kBucketSlots : count);
     int32_t j = y.pos_path(word), e = y.pos_index(word), old_j = 0, new_j = 0;
     cand = cand && j != c.i && j < y.N;
@@ -336,6 +352,7 @@ __device__ __forceinline__ int32_t wave_front_end(Lds& s, Ctx& c, const IndexVie
   const int lane = c.tid;
   const Paths& y = c.y;
   const int64_t row = (int64_t)p * ix.N + c.i;
+  int32_t* gram = const_cast<int32_t*>(c.gram);
   // ---- round trip 1: every load here has an address known from the kernel arguments
   Head me = load_head(y, ix.kmax, c.i);                 // same address in every lane
   Head hj = load_head(y, ix.kmax, lane < y.N ? lane : 0);
@@ -351,35 +368,22 @@ __device__ __forceinline__ int32_t wave_front_end(Lds& s, Ctx& c, const IndexVie
 #pragma unroll
   for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) {
     int32_t v = 0;
-    if (a < c.q) {
-      if (a >= cnt_i) v = pick(me.tail, a - cnt_i);
-      else v = y.n == 1 ? st_i : y.st[(int64_t)c.i * y.n + cnt_i - 1 - a];
-    }
+    if (a < c.q) v = a < cnt_i ? st_i : pick(me.tail, a - cnt_i);
     c.Q[a] = v;
   }
-  int32_t* gram = const_cast<int32_t*>(c.gram);
-  ticket_used = false;
-  if (y.n > 0) {        // also when this path takes no token: its meta row moves to the new buffer
-    if (y.n == 1) append_own_single(ix, y, row, c.i, me, st_i, sp_i, lane);
-    else append_row<kWave, false>(ix, y, p, c.i, old_i, me.new_len, lane);
-    if (cnt_i == 1) {   // the grams that end before the new position are the old tail
-      ticket = insert_begin(gram, c.bucket_mask, ix.kmax, me.tail, old_i, lane);
-      ticket_used = true;
-    } else {
-      for (int32_t t = 0; t < cnt_i; ++t)
-        gram_insert_position(gram, c.bucket_mask, ix.kmax, y, c.i, old_i + t, old_i, lane);
-    }
-  }
-  // ---- round trip 2 starts: first batch of the query's buckets (with the fill counts above)
+  const bool use_index = c.q == ix.kmax;                // shorter queries: scan (short paths)
+  // ---- round trip 2 is requested: fill counts for the insert, first 4 buckets of the query
+  ticket_used = cnt_i == 1;
+  if (ticket_used) ticket = insert_begin(gram, c.bucket_mask, ix.kmax, me.tail, old_i, lane);
   GramHash gh{0u, 1u};
   int32_t word = -1;
-  if (c.q > 0) {
+  if (use_index) {
     gh = query_hash(c);
-    if ((uint32_t)(lane >> 4) <= c.bucket_mask)
-      word = gram_bucket(gram_table(gram, c.q, c.bucket_mask), gh, (uint32_t)(lane >> 4),
-                         c.bucket_mask)[lane & 15];
+    uint32_t r = (uint32_t)(lane >> 4);
+    word = gram_bucket(gram, gh, r <= c.bucket_mask ? r : 0u, c.bucket_mask)[lane & 15];
   }
-  // heads of all paths: lengths into LDS, matches among the positions appended by this launch
+  // ---- while it travels: own append, lengths into LDS, matches among the new positions
+  if (y.n == 1) append_own_single(ix, y, row, c.i, me, st_i, sp_i, lane);
   int32_t n_match = 0;
   for (int32_t j0 = 0; j0 < y.N; j0 += kWave) {
     int32_t j = j0 + lane;
@@ -389,24 +393,22 @@ __device__ __forceinline__ int32_t wave_front_end(Lds& s, Ctx& c, const IndexVie
       s.len_old[j] = hj.old_len;
       s.len_new[j] = hj.new_len;
     }
-    bool live = have && j != c.i && c.q > 0;
-    if (y.n == 1) {                         // the usual decode step: compare the old tail
-      bool hit = live && hj.new_len > hj.old_len && hj.old_len >= c.q;
+    // a position appended by this very launch matches when the old tail before it is the query
+    bool hit = use_index && have && j != c.i && hj.new_len > hj.old_len && hj.old_len >= c.q;
 #pragma unroll
-      for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) hit = hit && (a >= c.q || hj.tail[a] == c.Q[a]);
-      wave_push(s, n_match, hit, make_match(y, j, hj.old_len, hj.old_len, hj.new_len), lane);
-    } else {
-      for (int32_t t = 0; t < y.n; ++t) {
-        int32_t e = hj.old_len + t;
-        bool hit = live && e < hj.new_len && e >= c.q && gram_equals_query(c, j, e, hj.old_len);
-        wave_push(s, n_match, hit, make_match(y, j, e, hj.old_len, hj.new_len), lane);
-      }
-    }
+    for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) hit = hit && (a >= c.q || hj.tail[a] == c.Q[a]);
+    wave_push(s, n_match, hit, make_match(y, j, hj.old_len, hj.old_len, hj.new_len), lane);
   }
-  if (ticket_used) insert_claim(ticket, gram, c.bucket_mask, lane);
+  if (ticket_used) insert_claim(ticket, gram, c.bucket_mask, lane);   // round trip 3 starts
   wi.n_fresh = n_match;
-  wi.win_cap = kWinWords / (2 * L);
-  if (c.q > 0) lookup_with_windows<LCAP>(s, c, L, wi.win_cap, wi.n_fresh, n_match, gh, word);
+  wi.win_cap = use_index ? kWinWords / (2 * L) : 0;
+  if (use_index) {
+    lookup_with_windows<LCAP>(s, c, L, wi.win_cap, wi.n_fresh, n_match, gh, word);
+  } else if (c.q > 0) {
+    WaveListSink sink{&s, &n_match, lane};
+    match_scan<kWave>(c, sink);                         // covers old and new positions alike
+    wi.n_fresh = n_match;
+  }
   if (lane == 0) s.n_match = n_match;
   return n_match;
 }
