@@ -39,6 +39,17 @@ def algorithmic_bytes(N, k, L, kmax, matches_per_step):
     return per_step, draft_only
 
 
+def measured_traffic(workload):
+    """HBM bytes per launch of the step kernel from the committed rocprofv3 counter runs
+    (FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy kernel of known size)."""
+    path = os.path.join(ROOT, "profiles", "step_wave_kernel_%s_traffic.json" % workload)
+    try:
+        with open(path) as f:
+            return json.load(f)["traffic_bytes_per_launch"]
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -162,9 +173,9 @@ def main():
         "us_per_step_python_per_call": dt_python * 1e6,
         "matches_per_step": matches_per_step,
         "algorithmic_bytes_per_step": b_step,
-        "roofline": {"bound": "hbm", "kernel": "draft_kernel<64,true> (fused step: append+draft+accept)",
+        "roofline": {"bound": "hbm", "kernel": "csd::step_wave_kernel (one launch per step: append+draft+accept)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(w.name),
                      "algorithmic_bytes_per_launch": b_step, "avg_launch_us": launch_ms * 1e3},
     }
 

@@ -267,15 +267,27 @@ __device__ __forceinline__ bool layer_instance(const Paths& y, Match m, int32_t 
   return true;
 }
 
-// Workgroups are dealt round-robin to the 8 XCDs; this maps them back so that
-// each XCD works on a contiguous range of (problem, path) rows and the paths of
-// one problem share one L2.  The grid is padded to a multiple of 8.
+// Workgroups are dealt round-robin to the 8 XCDs (workgroup b runs on XCD b mod 8), and
+// each XCD has its own L2, cold at every launch.  Rows (problem, path) are therefore laid
+// out so that (a) each XCD works on a contiguous range of rows: the paths of one problem
+// share one L2; (b) no more XCDs are used than it takes to give every row a CU of its own
+// (32 CUs per XCD): with few rows, one L2 fetches the kernel's code and the shared data
+// once instead of eight times.  Workgroups dealt to the unused XCDs exit at once.
+__host__ __device__ __forceinline__ int32_t xcds_used(int64_t rows) {
+  int64_t x = (rows + 31) / 32;
+  return (int32_t)(x < 1 ? 1 : (x > 8 ? 8 : x));
+}
 __device__ __forceinline__ int32_t xcd_row(int32_t rows) {
+  int32_t xcd = (int32_t)(blockIdx.x & 7);
+  if (xcd >= xcds_used(rows)) return -1;
   int32_t per_xcd = (int32_t)(gridDim.x >> 3);
-  int32_t r = (int32_t)(blockIdx.x & 7) * per_xcd + (int32_t)(blockIdx.x >> 3);
+  int32_t r = xcd * per_xcd + (int32_t)(blockIdx.x >> 3);
   return r < rows ? r : -1;
 }
-inline uint32_t xcd_grid(int64_t rows) { return (uint32_t)((rows + 7) / 8 * 8); }
+inline uint32_t xcd_grid(int64_t rows) {
+  int64_t x = xcds_used(rows);
+  return (uint32_t)((rows + x - 1) / x * 8);
+}
 
 __device__ __forceinline__ Ctx make_ctx(const IndexView& ix, const StepIn& in, int32_t row,
                                         int32_t& p_out) {
