@@ -25,18 +25,16 @@ METRIC = "draft steps/sec (all N paths) and µs/step at N=16×1024 tok; % HBM ro
 HBM_PEAK_GBS = 8000.0
 
 
-def algorithmic_bytes(N, k, L, kmax, matches_per_step):
-    """Bytes the method has to move per step (not the bytes a scan would touch):
-    per path: step input + history store + index entries, one 64-byte index bucket per
-    query, the outputs; per match: its posting, the tokens compared, L continuation
-    tokens with their probabilities."""
-    b_app = 4 + 4 + 4 + 4 + 8 * kmax
-    b_lkp = 64
-    b_out = 8 * L + 8 + 4 * L + 4          # draft tokens+scores, length+path score, targets, accept
-    b_match = 4 + 4 * k + L * (4 + 4)
-    per_step = N * (b_app + b_lkp + b_out) + matches_per_step * b_match
-    draft_only = N * (b_lkp + 8 * L + 8) + matches_per_step * b_match
-    return per_step, draft_only
+def algorithmic_bytes(n_paths, k, L, kmax, matches_per_step):
+    """Bytes the method has to move per step (not the bytes a scan would touch).
+    Per path: step input (token + probability), history store (token + quantised
+    probability), its meta row read and written (length + kmax tail tokens), one index
+    entry (posting + fill count), one 64-byte index bucket for the lookup, the outputs
+    (L draft tokens + L scores + length + path score), L targets and the accept length.
+    Per match: its posting, the k verify tokens, L continuation tokens with probabilities."""
+    b_path = 8 + 8 + 8 * (1 + kmax) + 8 + 64 + (8 * L + 8) + (4 * L + 4)
+    b_match = 4 + 4 * k + 8 * L
+    return n_paths * b_path + matches_per_step * b_match
 
 
 def measured_traffic(workload):
@@ -157,7 +155,7 @@ def main():
             m_total += int(off[-1])
             m_samples += 1
     matches_per_step = m_total / max(m_samples, 1)
-    b_step, _ = algorithmic_bytes(N * P, k, L, k, matches_per_step)
+    b_step = algorithmic_bytes(N * P, k, L, k, matches_per_step)
     achieved = b_step / (launch_ms * 1e-3) / 1e9
 
     res = {
