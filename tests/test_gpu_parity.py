@@ -275,3 +275,54 @@ def test_determinism_two_runs_identical(oracle):
     b = gpu_replay(tokens, probs, 3, 8, steps=400)
     for key in ("draft", "draft_len", "token_scores", "path_scores"):
         assert np.array_equal(a[key], b[key])
+
+
+def test_many_paths_beyond_one_wave_and_length_cache(oracle):
+    """N = 300 paths: more than one 64-lane chunk of heads and more than the 256 lengths
+    cached on chip; ragged lengths; both matchers; fused single-token steps and one-shot."""
+    rng = np.random.default_rng(11)
+    N, T, k, L = 300, 40, 2, 4
+    base = rng.integers(0, 30, size=T)
+    tokens = np.tile(base, (1, N, 1)).astype(np.int32)
+    flip = rng.random(tokens.shape) < 0.2
+    tokens[flip] = rng.integers(0, 30, size=int(flip.sum()))
+    probs = rng.random(tokens.shape).astype(np.float32)
+    for flags, how in ((INDEX, "replay"), (SCAN, "step"), (INDEX, "calls")):
+        got = gpu_replay(tokens, probs, k, L, 0.7, 0, flags, how=how)
+        assert got["status"] == 0
+        for t in range(0, T, 3):
+            want = oracle.draft_all(tokens, probs, got["lens"][t], k, L, 0.7, 0)
+            assert_step_equal(got, want, t, "N=300 flags=%d %s" % (flags, how))
+    ix = got["index"]
+    je, off = ix.dump_matches(k, cap=1 << 22)
+    lens = got["lens"][-1]
+    for i in (0, 63, 64, 255, 256, 299):
+        assert np.array_equal(je[off[i]:off[i + 1]], oracle.matches(tokens[0], lens[0], i, k))
+
+
+def test_maximum_positions_per_problem(oracle):
+    """N * max_len = 2^24, the largest geometry the library accepts: positions pack into
+    24 + bits, the index has 2^21 buckets.  Only a few tokens are appended (the oracle scans)."""
+    N, T, k, L = 4096, 4096, 3, 4
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(3)
+    n = 6
+    step = rng.integers(0, 5, size=(1, N, n)).astype(np.int32)
+    for flags in (INDEX, SCAN):
+        ix = binding.Index(1, N, T, 5, k, L, 1.0, 0, flags, device=dev)
+        ix.append(torch.from_numpy(step).to(dev), None, None, n)
+        out = ix.draft(k, L)
+        tok = np.zeros((1, N, T), dtype=np.int32)
+        tok[:, :, :n] = step
+        lens = np.full((1, N), n, dtype=np.int32)
+        rows = [0, 1, 63, 64, 2047, 4095]
+        got_tok = out["tokens"].cpu().numpy()
+        got_len = out["length"].cpu().numpy()
+        got_ts = out["token_scores"].cpu().numpy()
+        for i in rows:
+            d, nd, ts, ps = oracle.draft(tok[0], None, lens[0], i, k, L)
+            assert got_len[0, i] == nd and got_tok[0, i].tolist() == d.tolist(), (flags, i)
+            np.testing.assert_allclose(got_ts[0, i], ts, rtol=1e-6)
+        assert ix.status() == 0
+        del ix, out
+        torch.cuda.empty_cache()
