@@ -38,23 +38,25 @@ def _load():
         lib.oracle_quantize_prob.argtypes = [ctypes.c_float]
         lib.oracle_alpha_q.restype = ctypes.c_uint32
         lib.oracle_alpha_q.argtypes = [ctypes.c_double]
+        lib.oracle_edit_distance.restype = ctypes.c_int32
+        lib.oracle_edit_distance.argtypes = [_i32p, ctypes.c_int32, _i32p, ctypes.c_int32]
         lib.oracle_matches.restype = ctypes.c_int64
         lib.oracle_matches.argtypes = [_i32p, _i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
-                                       ctypes.c_int32, _i32p, ctypes.c_int64]
+                                       ctypes.c_int32, ctypes.c_int32, _i32p, ctypes.c_int64]
         lib.oracle_edges.restype = ctypes.c_int64
         lib.oracle_edges.argtypes = [_i32p, _f32p, _i32p, ctypes.c_int32, ctypes.c_int32,
-                                     ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _i32p, _u64p,
-                                     ctypes.c_int64]
+                                     ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                     _i32p, _u64p, ctypes.c_int64]
         lib.oracle_draft.restype = ctypes.c_int32
         lib.oracle_draft.argtypes = [_i32p, _f32p, _i32p, ctypes.c_int32, ctypes.c_int32,
-                                     ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_uint32,
-                                     ctypes.c_int32, _i32p, _f32p, _f32p]
+                                     ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                     ctypes.c_uint32, ctypes.c_int32, _i32p, _f32p, _f32p]
         lib.oracle_accept.restype = ctypes.c_int32
         lib.oracle_accept.argtypes = [_i32p, ctypes.c_int32, _i32p]
         lib.oracle_draft_all.restype = None
         lib.oracle_draft_all.argtypes = [_i32p, _f32p, _i32p, ctypes.c_int32, ctypes.c_int32,
                                          ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
-                                         ctypes.c_uint32, ctypes.c_int32, _i32p, _i32p, _f32p, _f32p,
+                                         ctypes.c_int32, ctypes.c_uint32, ctypes.c_int32, _i32p, _i32p, _f32p, _f32p,
                                          _i32p, _i32p]
         _lib = lib
     return _lib
@@ -80,7 +82,13 @@ def alpha_q(alpha: float) -> int:
     return int(_load().oracle_alpha_q(float(alpha)))
 
 
-def matches(tok, length, i, k):
+def edit_distance(a, b) -> int:
+    a, ap = _i32(list(a) + [0])
+    b, bp = _i32(list(b) + [0])
+    return int(_load().oracle_edit_distance(ap, len(a) - 1, bp, len(b) - 1))
+
+
+def matches(tok, length, i, k, eps=0):
     """(j, e) rows of path i's match set for one problem: tok [N][max_len], length [N]."""
     tok, tp = _i32(tok)
     length, lp = _i32(length)
@@ -88,26 +96,26 @@ def matches(tok, length, i, k):
     lib = _load()
     cap = max(1, N * max_len)
     out = np.empty((cap, 2), dtype=np.int32)
-    n = lib.oracle_matches(tp, lp, N, max_len, i, k, out.ctypes.data_as(_i32p), cap)
+    n = lib.oracle_matches(tp, lp, N, max_len, i, k, eps, out.ctypes.data_as(_i32p), cap)
     return out[:n].copy()
 
 
-def edges(tok, prob, length, i, k, L):
+def edges(tok, prob, length, i, k, L, eps=0):
     """Edge rows of path i's DAG: (duv int32 [n][3], cs uint64 [n][2]) sorted by (d, u, v)."""
     tok, tp = _i32(tok)
     prob, pp = _f32(prob)
     length, lp = _i32(length)
     N, max_len = tok.shape
     lib = _load()
-    n = lib.oracle_edges(tp, pp, lp, N, max_len, i, k, L, None, None, 0)
+    n = lib.oracle_edges(tp, pp, lp, N, max_len, i, k, eps, L, None, None, 0)
     duv = np.empty((max(n, 1), 3), dtype=np.int32)
     cs = np.empty((max(n, 1), 2), dtype=np.uint64)
-    lib.oracle_edges(tp, pp, lp, N, max_len, i, k, L, duv.ctypes.data_as(_i32p),
+    lib.oracle_edges(tp, pp, lp, N, max_len, i, k, eps, L, duv.ctypes.data_as(_i32p),
                      cs.ctypes.data_as(_u64p), n)
     return duv[:n].copy(), cs[:n].copy()
 
 
-def draft(tok, prob, length, i, k, L, alpha=1.0, score_mode=0):
+def draft(tok, prob, length, i, k, L, alpha=1.0, score_mode=0, eps=0):
     """Draft of path i for one problem -> (tokens [L], draft_len, token_scores [L], path_score)."""
     tok, tp = _i32(tok)
     prob, pp = _f32(prob)
@@ -117,7 +125,7 @@ def draft(tok, prob, length, i, k, L, alpha=1.0, score_mode=0):
     ts = np.empty(L, dtype=np.float32)
     ps = ctypes.c_float(0.0)
     lib = _load()
-    n = lib.oracle_draft(tp, pp, lp, N, max_len, i, k, L, lib.oracle_alpha_q(float(alpha)),
+    n = lib.oracle_draft(tp, pp, lp, N, max_len, i, k, eps, L, lib.oracle_alpha_q(float(alpha)),
                          score_mode, d.ctypes.data_as(_i32p), ts.ctypes.data_as(_f32p),
                          ctypes.byref(ps))
     return d, int(n), ts, np.float32(ps.value)
@@ -129,7 +137,7 @@ def accept(draft_tokens, draft_len, target) -> int:
     return int(_load().oracle_accept(dp, int(draft_len), tp))
 
 
-def draft_all(tok, prob, length, k, L, alpha=1.0, score_mode=0, target=None):
+def draft_all(tok, prob, length, k, L, alpha=1.0, score_mode=0, target=None, eps=0):
     """All paths of all problems: tok [P][N][max_len], prob same or None, length [P][N].
 
     Returns dict(draft [P][N][L], draft_len [P][N], token_scores [P][N][L],
@@ -149,7 +157,7 @@ def draft_all(tok, prob, length, k, L, alpha=1.0, score_mode=0, target=None):
         alp = al.ctypes.data_as(_i32p)
     else:
         tgp, al, alp = None, None, None
-    lib.oracle_draft_all(tp, pp, lp, P, N, max_len, k, L, lib.oracle_alpha_q(float(alpha)),
+    lib.oracle_draft_all(tp, pp, lp, P, N, max_len, k, eps, L, lib.oracle_alpha_q(float(alpha)),
                          score_mode, d.ctypes.data_as(_i32p), dl.ctypes.data_as(_i32p),
                          ts.ctypes.data_as(_f32p), ps.ctypes.data_as(_f32p), tgp, alp)
     return dict(draft=d, draft_len=dl, token_scores=ts, path_scores=ps, accept_len=al)

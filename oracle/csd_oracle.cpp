@@ -54,6 +54,15 @@
  *  R10 token_score[d] = key / 2^32 as float, path_score = (sum of keys)/2^32.
  *  R11 Accept length = number of leading draft tokens equal to the targets,
  *      in [0, draft_len]; no bonus token (Table 1's values never exceed L).
+ *  R12 Fuzzy suffix matching (Eq. 4), tolerance eps >= 0: position e of path j
+ *      (0 <= e < len_j) is a match when SOME substring of path j that ends just
+ *      before e, of any length l with l <= e, is within Levenshtein distance
+ *      eps of the query (unit costs for substitution, insertion, deletion).
+ *      Only lengths q-eps .. q+eps can qualify.  Each e counts once, however
+ *      many substrings qualify.  eps = 0 is the exact match of Eq. 3.
+ *  R13 With eps > 0 the token before a match need not be the last query token,
+ *      so the DAG's root is the query itself: the predecessor of EVERY
+ *      layer-1 token is the last query token (for eps = 0 this is R9).
  *
  * Build: g++ -O2 -shared -fPIC -o libcsd_oracle.so csd_oracle.cpp
  */
@@ -97,20 +106,41 @@ struct Paths {
   }
 };
 
-/* Algorithm 1, the search loop (Eq. 3): the candidate pool of path i. */
-std::vector<Candidate> candidate_pool(const Paths& Y, int32_t i, int32_t k, int32_t* q_out) {
+/* Levenshtein distance between a[0..na) and b[0..nb): the textbook dynamic
+ * programme over the (na+1) x (nb+1) table, unit costs. */
+int32_t edit_distance(const int32_t* a, int32_t na, const int32_t* b, int32_t nb) {
+  std::vector<std::vector<int32_t> > D(na + 1, std::vector<int32_t>(nb + 1, 0));
+  for (int32_t x = 0; x <= na; ++x) D[x][0] = x;
+  for (int32_t y = 0; y <= nb; ++y) D[0][y] = y;
+  for (int32_t x = 1; x <= na; ++x)
+    for (int32_t y = 1; y <= nb; ++y) {
+      int32_t best = D[x - 1][y - 1] + (a[x - 1] != b[y - 1] ? 1 : 0);   /* substitute / keep */
+      if (D[x - 1][y] + 1 < best) best = D[x - 1][y] + 1;                /* delete from a     */
+      if (D[x][y - 1] + 1 < best) best = D[x][y - 1] + 1;                /* insert into a     */
+      D[x][y] = best;
+    }
+  return D[na][nb];
+}
+
+/* Algorithm 1, the search loop (Eq. 3, with Eq. 4's tolerance): the candidate
+ * pool of path i. */
+std::vector<Candidate> candidate_pool(const Paths& Y, int32_t i, int32_t k, int32_t eps,
+                                      int32_t* q_out) {
   std::vector<Candidate> pool;
   int32_t len_i = Y.len[i];
   int32_t q = k < len_i ? k : len_i;                       /* R3 */
   *q_out = q;
   if (q <= 0) return pool;
+  const int32_t* query = Y.tok + (int64_t)i * Y.max_len + (len_i - q);
   for (int32_t j = 0; j < Y.N; ++j) {
     if (j == i) continue;                                  /* R3 */
-    for (int32_t e = q; e <= Y.len[j] - 1; ++e) {          /* R1, R2 */
-      bool same = true;
-      for (int32_t a = 0; a < q; ++a)
-        if (Y.token(j, e - q + a) != Y.token(i, len_i - q + a)) same = false;
-      if (same) pool.push_back(Candidate{j, e});
+    const int32_t* yj = Y.tok + (int64_t)j * Y.max_len;
+    for (int32_t e = 0; e <= Y.len[j] - 1; ++e) {          /* R1, R2 */
+      bool match = false;
+      /* R12: substrings ending before e; |l - q| <= distance, so only these lengths can do */
+      for (int32_t l = (q > eps ? q - eps : 0); l <= q + eps && l <= e && !match; ++l)
+        if (edit_distance(query, q, yj + (e - l), l) <= eps) match = true;
+      if (match) pool.push_back(Candidate{j, e});
     }
   }
   return pool;                                             /* ascending (j, e) */
@@ -119,13 +149,14 @@ std::vector<Candidate> candidate_pool(const Paths& Y, int32_t i, int32_t k, int3
 typedef std::map<std::pair<int32_t, int32_t>, Weight> EdgeTable;   /* (u, v) -> weight */
 
 /* Algorithm 1, DAG construction (Eq. 5): edges[d-1] is the table of layer d. */
-std::vector<EdgeTable> build_dag(const Paths& Y, const std::vector<Candidate>& pool, int32_t L) {
+std::vector<EdgeTable> build_dag(const Paths& Y, const std::vector<Candidate>& pool, int32_t L,
+                                 int32_t root) {
   std::vector<EdgeTable> edges(L > 0 ? L : 0);
   for (int32_t d = 1; d <= L; ++d) {
     for (const Candidate& c : pool) {
       int32_t t = c.e + d - 1;                 /* d-th token after the match */
       if (t >= Y.len[c.j]) continue;           /* this candidate has ended   */
-      int32_t u = Y.token(c.j, t - 1);         /* R9 for d = 1               */
+      int32_t u = d == 1 ? root : Y.token(c.j, t - 1);   /* R9, R13 */
       int32_t v = Y.token(c.j, t);
       Weight& w = edges[d - 1][std::make_pair(u, v)];
       w.C += 1;                                /* R4, R6 */
@@ -145,6 +176,11 @@ extern "C" {
 
 uint32_t oracle_quantize_prob(float p) { return quantize_prob(p); }
 
+/* Levenshtein distance of two token strings (R12), exposed so that it can be pinned. */
+int32_t oracle_edit_distance(const int32_t* a, int32_t na, const int32_t* b, int32_t nb) {
+  return edit_distance(a, na, b, nb);
+}
+
 /* alpha in [0,1] -> alpha_q in [0, 65536] (R7). */
 uint32_t oracle_alpha_q(double alpha) {
   double x = std::nearbyint(alpha * 65536.0);
@@ -156,10 +192,10 @@ uint32_t oracle_alpha_q(double alpha) {
 /* Match set of path i (Eq. 3) as (j, e) rows in ascending order.  Returns the
  * number of matches; writes at most cap rows. */
 int64_t oracle_matches(const int32_t* tok, const int32_t* len, int32_t N, int32_t max_len,
-                       int32_t i, int32_t k, int32_t* out_je, int64_t cap) {
+                       int32_t i, int32_t k, int32_t eps, int32_t* out_je, int64_t cap) {
   Paths Y{tok, nullptr, len, N, max_len};
   int32_t q;
-  std::vector<Candidate> pool = candidate_pool(Y, i, k, &q);
+  std::vector<Candidate> pool = candidate_pool(Y, i, k, eps, &q);
   for (int64_t m = 0; m < (int64_t)pool.size() && m < cap; ++m) {
     out_je[2 * m] = pool[m].j;
     out_je[2 * m + 1] = pool[m].e;
@@ -170,12 +206,12 @@ int64_t oracle_matches(const int32_t* tok, const int32_t* len, int32_t N, int32_
 /* Edge tables of path i's DAG (Eq. 5) as rows (d, u, v) / (C, S) sorted by
  * (d, u, v).  Returns the number of rows; writes at most cap rows. */
 int64_t oracle_edges(const int32_t* tok, const float* prob, const int32_t* len, int32_t N,
-                     int32_t max_len, int32_t i, int32_t k, int32_t L,
+                     int32_t max_len, int32_t i, int32_t k, int32_t eps, int32_t L,
                      int32_t* out_duv, uint64_t* out_cs, int64_t cap) {
   Paths Y{tok, prob, len, N, max_len};
   int32_t q;
-  std::vector<Candidate> pool = candidate_pool(Y, i, k, &q);
-  std::vector<EdgeTable> edges = build_dag(Y, pool, L);
+  std::vector<Candidate> pool = candidate_pool(Y, i, k, eps, &q);
+  std::vector<EdgeTable> edges = build_dag(Y, pool, L, Y.token(i, Y.len[i] - 1));
   int64_t n = 0;
   for (int32_t d = 1; d <= L; ++d) {
     for (const auto& kv : edges[d - 1]) {
@@ -195,16 +231,16 @@ int64_t oracle_edges(const int32_t* tok, const float* prob, const int32_t* len, 
 /* Draft of path i (Algorithm 1 as a whole).  draft[L] is padded with -1,
  * token_scores[L] with 0.  Returns the draft length. */
 int32_t oracle_draft(const int32_t* tok, const float* prob, const int32_t* len, int32_t N,
-                     int32_t max_len, int32_t i, int32_t k, int32_t L, uint32_t alpha_q,
+                     int32_t max_len, int32_t i, int32_t k, int32_t eps, int32_t L, uint32_t alpha_q,
                      int32_t score_mode, int32_t* draft, float* token_scores,
                      float* path_score) {
   for (int32_t d = 0; d < L; ++d) { draft[d] = -1; token_scores[d] = 0.0f; }
   *path_score = 0.0f;
   Paths Y{tok, prob, len, N, max_len};
   int32_t q;
-  std::vector<Candidate> pool = candidate_pool(Y, i, k, &q);
+  std::vector<Candidate> pool = candidate_pool(Y, i, k, eps, &q);
   if (pool.empty()) return 0;
-  std::vector<EdgeTable> edges = build_dag(Y, pool, L);
+  std::vector<EdgeTable> edges = build_dag(Y, pool, L, Y.token(i, Y.len[i] - 1));
 
   int32_t cur = Y.token(i, Y.len[i] - 1);        /* R9: root = last query token */
   uint64_t key_sum = 0;
@@ -252,8 +288,8 @@ int32_t oracle_accept(const int32_t* draft, int32_t draft_len, const int32_t* ta
 /* Convenience loop used for replays and for timing: every path of every
  * problem.  Arrays are [P][N][...]; target / accept_len may be null. */
 void oracle_draft_all(const int32_t* tok, const float* prob, const int32_t* len, int32_t P,
-                      int32_t N, int32_t max_len, int32_t k, int32_t L, uint32_t alpha_q,
-                      int32_t score_mode, int32_t* draft, int32_t* draft_len,
+                      int32_t N, int32_t max_len, int32_t k, int32_t eps, int32_t L,
+                      uint32_t alpha_q, int32_t score_mode, int32_t* draft, int32_t* draft_len,
                       float* token_scores, float* path_scores, const int32_t* target,
                       int32_t* accept_len) {
   for (int32_t p = 0; p < P; ++p) {
@@ -262,7 +298,7 @@ void oracle_draft_all(const int32_t* tok, const float* prob, const int32_t* len,
     const int32_t* ln = len + (int64_t)p * N;
     for (int32_t i = 0; i < N; ++i) {
       int64_t r = (int64_t)p * N + i;
-      draft_len[r] = oracle_draft(tk, pr, ln, N, max_len, i, k, L, alpha_q, score_mode,
+      draft_len[r] = oracle_draft(tk, pr, ln, N, max_len, i, k, eps, L, alpha_q, score_mode,
                                   draft + r * L, token_scores + r * L, path_scores + r);
       if (target && accept_len)
         accept_len[r] = oracle_accept(draft + r * L, draft_len[r], target + r * L);

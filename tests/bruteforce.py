@@ -8,6 +8,7 @@ a real-valued alpha, and the greedy rule is evaluated on those rationals.
 """
 from collections import defaultdict
 from fractions import Fraction
+from functools import lru_cache
 
 
 def quant(p):
@@ -17,43 +18,71 @@ def quant(p):
     return max(0, min(65536, round(float(p) * 65536.0)))
 
 
-def match_set(paths, i, k):
+def within_one_edit(a, b):
+    """Levenshtein(a, b) <= 1 without dynamic programming: equal, one substitution, or one
+    string is the other with a single element removed."""
+    a, b = tuple(a), tuple(b)
+    if a == b:
+        return True
+    if len(a) == len(b):
+        return sum(x != y for x, y in zip(a, b)) == 1
+    if len(a) > len(b):
+        a, b = b, a
+    return len(b) - len(a) == 1 and any(b[:x] + b[x + 1:] == a for x in range(len(b)))
+
+
+@lru_cache(maxsize=None)
+def lev(a, b):
+    """Levenshtein distance by its recursive definition (tuples)."""
+    if not a:
+        return len(b)
+    if not b:
+        return len(a)
+    return min(lev(a[1:], b[1:]) + (a[0] != b[0]), lev(a[1:], b) + 1, lev(a, b[1:]) + 1)
+
+
+def match_set(paths, i, k, eps=0):
     yi = paths[i]
     q = min(k, len(yi))
     if q == 0:
         return q, set()
     suffix = tuple(yi[len(yi) - q:])
-    return q, {(j, e) for j, yj in enumerate(paths) if j != i
-               for e in range(q, len(yj)) if tuple(yj[e - q:e]) == suffix}
+    if eps == 0:
+        return q, {(j, e) for j, yj in enumerate(paths) if j != i
+                   for e in range(q, len(yj)) if tuple(yj[e - q:e]) == suffix}
+    near = within_one_edit if eps == 1 else (lambda a, b: lev(tuple(a), tuple(b)) <= eps)
+    return q, {(j, e) for j, yj in enumerate(paths) if j != i for e in range(len(yj))
+               if any(near(suffix, yj[e - l:e]) for l in range(0, e + 1))}
 
 
-def candidates(paths, probs, i, k, L):
-    """Each candidate = [(predecessor, token, prob_fraction), ...] of length <= L."""
-    _, M = match_set(paths, i, k)
+def candidates(paths, probs, i, k, L, eps=0):
+    """Each candidate = [(predecessor, token, prob_fraction), ...] of length <= L.  The
+    predecessor of a candidate's first token is the query's last token (the DAG's root)."""
+    _, M = match_set(paths, i, k, eps)
     out = []
     for (j, e) in M:
         seq = []
         for t in range(e, min(e + L, len(paths[j]))):
             p = Fraction(quant(probs[j][t]), 65536) if probs is not None else Fraction(1)
-            seq.append((paths[j][t - 1], paths[j][t], p))
+            seq.append((paths[i][-1] if t == e else paths[j][t - 1], paths[j][t], p))
         out.append(seq)
     return out
 
 
-def edge_tables(paths, probs, i, k, L):
+def edge_tables(paths, probs, i, k, L, eps=0):
     """{(d, u, v): [count, prob_sum_fraction]} with d = 1..L."""
     E = defaultdict(lambda: [0, Fraction(0)])
-    for seq in candidates(paths, probs, i, k, L):
+    for seq in candidates(paths, probs, i, k, L, eps):
         for d, (u, v, p) in enumerate(seq, start=1):
             E[(d, u, v)][0] += 1
             E[(d, u, v)][1] += p
     return dict(E)
 
 
-def draft(paths, probs, i, k, L, alpha=Fraction(1), score_mode=0):
+def draft(paths, probs, i, k, L, alpha=Fraction(1), score_mode=0, eps=0):
     """Returns (tokens, scores) with scores as exact Fractions."""
     alpha = Fraction(alpha)
-    E = edge_tables(paths, probs, i, k, L)
+    E = edge_tables(paths, probs, i, k, L, eps)
     if not E:
         return [], []
 

@@ -301,3 +301,80 @@ def test_generator_is_seeded_and_shaped():
         assert (a == b).all() and (pa == pb).all()
         assert a.shape == (w.n_problems, w.n_paths, w.max_len) and a.dtype == np.int32
         assert a.min() >= 0 and a.max() < w.vocab and pa.min() > 0 and pa.max() <= 1
+
+
+# ---------------------------------------------------------------- fuzzy suffix matching (Eq. 4)
+def test_edit_distance_textbook_values(oracle):
+    word = lambda w: [ord(c) for c in w]
+    assert oracle.edit_distance(word("kitten"), word("sitting")) == 3
+    assert oracle.edit_distance(word("flaw"), word("lawn")) == 2
+    assert oracle.edit_distance(word("intention"), word("execution")) == 5
+    assert oracle.edit_distance([], word("abc")) == 3 and oracle.edit_distance(word("abc"), []) == 3
+    assert oracle.edit_distance(word("abc"), word("abc")) == 0
+    rng = np.random.default_rng(4)
+    for _ in range(300):
+        a = tuple(rng.integers(0, 3, size=int(rng.integers(0, 7))).tolist())
+        b = tuple(rng.integers(0, 3, size=int(rng.integers(0, 7))).tolist())
+        assert oracle.edit_distance(a, b) == bf.lev(a, b) == bf.lev(b, a)
+        assert (oracle.edit_distance(a, b) <= 1) == bf.within_one_edit(a, b)
+
+
+def test_fuzzy_hand_cases(oracle):
+    # query (1,2,3); the other path holds it with one substitution, one deletion, one insertion
+    paths = [[9, 1, 2, 3],
+             [1, 7, 3, 50, 0, 1, 3, 51, 0, 1, 2, 8, 3, 52, 0, 4, 4, 4, 53]]
+    tok, _, ln = pack(paths)
+    exact = oracle.matches(tok, ln, 0, 3, 0)
+    assert len(exact) == 0
+    fuzzy = oracle.matches(tok, ln, 0, 3, 1)
+    # after (1,7,3): e=3; after (1,3): e=7; after (1,2): e=11; after (1,2,8): e=12; after (1,2,8,3): e=13
+    assert fuzzy.tolist() == [[1, 3], [1, 7], [1, 11], [1, 12], [1, 13]]
+    d, n, ts, _ = oracle.draft(tok, None, ln, 0, 3, 1, 1.0, 0, eps=1)
+    # layer 1 hangs under the query whatever token precedes the match: 50, 51, 8, 3, 52
+    assert n == 1 and d[0] == 3 and ts[0] == 1.0
+    duv, cs = oracle.edges(tok, None, ln, 0, 3, 1, eps=1)
+    assert duv.tolist() == [[1, 3, 3], [1, 3, 8], [1, 3, 50], [1, 3, 51], [1, 3, 52]]
+    assert (cs[:, 0] == 1).all()
+
+
+def test_fuzzy_tolerance_zero_is_exact_and_sets_grow(oracle):
+    w = synth.scaled(synth.WORKLOADS["C1"], vocab=40, pool=8, max_len=80)
+    tokens, probs = synth.make_paths(w)
+    ln = np.array([80, 61, 80, 33], dtype=np.int32)
+    for i in range(4):
+        for k in (1, 2, 3):
+            m0 = {tuple(r) for r in oracle.matches(tokens[0], ln, i, k, 0).tolist()}
+            m1 = {tuple(r) for r in oracle.matches(tokens[0], ln, i, k, 1).tolist()}
+            m2 = {tuple(r) for r in oracle.matches(tokens[0], ln, i, k, 2).tolist()}
+            assert m0 <= m1 <= m2
+            if k >= 2:       # one edit always admits the exact matches of the (k-1)-suffix
+                short = {tuple(r) for r in oracle.matches(tokens[0], ln, i, k - 1, 0).tolist()}
+                assert short <= m1
+
+
+def test_fuzzy_brute_force_tiny_inputs(oracle):
+    rng = np.random.default_rng(777)
+    n_more = 0
+    for case in range(500):
+        paths, probs = _random_case(rng)
+        use_probs = case % 2 == 0
+        k = int(rng.integers(1, 5))
+        L = int(rng.integers(1, 6))
+        eps = 1 if case % 5 else 2
+        alpha = Fraction(int(rng.integers(0, 5)), 4)
+        mode = int(rng.integers(0, 2))
+        tok, pr, ln = pack(paths, probs if use_probs else None, max_len=26)
+        for i in range(len(paths)):
+            q, M = bf.match_set(paths, i, k, eps)
+            assert oracle.matches(tok, ln, i, k, eps).tolist() == [list(m) for m in sorted(M)]
+            n_more += len(M) > len(bf.match_set(paths, i, k, 0)[1])
+            E = bf.edge_tables(paths, probs if use_probs else None, i, k, L, eps)
+            duv, cs = oracle.edges(tok, pr, ln, i, k, L, eps)
+            assert [tuple(r) for r in duv.tolist()] == sorted(E)
+            for r, c in zip(duv.tolist(), cs):
+                assert int(c[0]) == E[tuple(r)][0] and Fraction(int(c[1]), 65536) == E[tuple(r)][1]
+            toks, scores = bf.draft(paths, probs if use_probs else None, i, k, L, alpha, mode, eps)
+            d, n, ts, ps = oracle.draft(tok, pr, ln, i, k, L, float(alpha), mode, eps)
+            assert d[:n].tolist() == toks and n == len(toks)
+            assert ts[:n].tolist() == [float(np.float32(float(s))) for s in scores]
+    assert n_more > 200
