@@ -88,6 +88,12 @@ typedef struct {
   int32_t score_mode;     /* 0: greedy step ranks successors by node in-weight
                              sum_u w(u,v) (the rule after Eq. 5); 1: by w(cur,v)      */
   int32_t flags;          /* CSD_MATCH_*; all other bits must be 0                    */
+  int32_t max_edits;      /* Eq. 4's edit-distance tolerance of the suffix match: 0 = exact
+                             (Eq. 3), 1 = one substitution, insertion or deletion (the
+                             paper's experiments use 1).  With 1 a position e of another
+                             path matches when some substring ending just before e is
+                             within one edit of the query, each e counting once, and
+                             matches are found by scan (CSD_MATCH_INDEX is refused).   */
 } csd_config;
 
 /* Size in bytes of the device workspace csd_create needs for this config. */

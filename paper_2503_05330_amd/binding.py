@@ -28,7 +28,7 @@ class Config(ctypes.Structure):
                 ("max_len", ctypes.c_int32), ("vocab", ctypes.c_int32),
                 ("max_query_len", ctypes.c_int32), ("max_draft_len", ctypes.c_int32),
                 ("alpha", ctypes.c_float), ("score_mode", ctypes.c_int32),
-                ("flags", ctypes.c_int32)]
+                ("flags", ctypes.c_int32), ("max_edits", ctypes.c_int32)]
 
 
 class CsdError(RuntimeError):
@@ -110,9 +110,9 @@ class Index:
     """The draft pool of P problems x N paths on the current device."""
 
     def __init__(self, n_problems, n_paths, max_len, vocab, max_query_len, max_draft_len,
-                 alpha=1.0, score_mode=0, flags=MATCH_AUTO, device="cuda"):
+                 alpha=1.0, score_mode=0, flags=MATCH_AUTO, device="cuda", max_edits=0):
         self.cfg = Config(n_problems, n_paths, max_len, vocab, max_query_len, max_draft_len,
-                          alpha, score_mode, flags)
+                          alpha, score_mode, flags, max_edits)
         self.P, self.N = n_problems, n_paths
         self.rows = n_problems * n_paths
         self.device = torch.device(device)

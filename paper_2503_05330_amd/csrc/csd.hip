@@ -62,7 +62,7 @@ struct Layout {
   size_t gram_words;
 };
 
-bool uses_index(const csd_config* c) { return c->flags != CSD_MATCH_SCAN; }
+bool uses_index(const csd_config* c) { return c->flags != CSD_MATCH_SCAN && c->max_edits == 0; }
 
 int validate(const csd_config* c) {
   if (!c) return CSD_ERR_INVALID_ARG;
@@ -75,6 +75,9 @@ int validate(const csd_config* c) {
   if ((int64_t)c->n_paths * c->max_len > CSD_MAX_POSITIONS) return CSD_ERR_INVALID_ARG;
   if ((int64_t)c->n_problems * c->n_paths > (1 << 24)) return CSD_ERR_INVALID_ARG;
   if (c->flags < 0 || c->flags > CSD_MATCH_INDEX) return CSD_ERR_UNIMPLEMENTED;
+  if (c->max_edits < 0) return CSD_ERR_INVALID_ARG;
+  if (c->max_edits > 1) return CSD_ERR_UNIMPLEMENTED;
+  if (c->max_edits == 1 && c->flags == CSD_MATCH_INDEX) return CSD_ERR_UNIMPLEMENTED;
   return CSD_OK;
 }
 
@@ -209,6 +212,7 @@ int csd_create(const csd_config* cfg, void* d_workspace, size_t workspace_bytes,
   h->view.max_len = cfg->max_len;
   h->view.vocab = cfg->vocab;
   h->view.kmax = cfg->max_query_len;
+  h->view.eps = cfg->max_edits;
   h->alpha_q = to_alpha_q(cfg->alpha);
   rc = csd_reset(h, stream);
   if (rc != CSD_OK) {

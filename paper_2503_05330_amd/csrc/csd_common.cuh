@@ -138,6 +138,7 @@ struct IndexView {              // device state inside the caller's workspace
   int32_t meta_stride;          // ints per meta row: 1 + kmax rounded up to a multiple of 4
   int32_t eshift;               // positions are packed as (path << eshift) | index
   int32_t P, N, max_len, vocab, kmax;
+  int32_t eps;                  // edit tolerance (0 = exact match)
 };
 
 struct StepIn {                 // tokens a step appends; n == 0: none
@@ -217,6 +218,7 @@ struct Ctx {                    // one (problem, query path)
   int32_t kmax;
   int32_t i;                    // query path
   int32_t len_i;                // its length after the append
+  int32_t eps;                  // edit tolerance of the match (Eq. 4): 0 or 1
   int32_t q;                    // effective query length min(k, len_i)
   int32_t Q[CSD_MAX_QUERY_LEN]; // Q[a] = a-th token from the end of path i
   int tid;
@@ -253,15 +255,17 @@ __device__ __forceinline__ Match make_match(const Paths& y, int32_t j, int32_t e
 
 // The (u, v, p) instance that match m contributes to layer d, if it reaches it,
 // read from memory.
-__device__ __forceinline__ bool layer_instance(const Paths& y, Match m, int32_t d, uint32_t& u,
-                                               uint32_t& v, u64& w) {
+// The predecessor of a layer-1 token is `root` (the last query token): the
+// DAG hangs under the query, whatever token precedes a fuzzy match.
+__device__ __forceinline__ bool layer_instance(const Paths& y, Match m, int32_t d, uint32_t root,
+                                               uint32_t& u, uint32_t& v, u64& w) {
   if (d > (int32_t)m.rem_new) return false;        // the candidate has ended
   int32_t j = y.pos_path(m.pos);
   int32_t e = y.pos_index(m.pos);
   // rel_old is exact unless clipped at 63 (a step appends at most 32767 tokens), and
   // d <= 32 < 63: every index read below is then on the history side either way
   int32_t old_j = e + (int32_t)m.rel_old;
-  u = (uint32_t)y.token(j, e + d - 2, old_j);
+  u = d == 1 ? root : (uint32_t)y.token(j, e + d - 2, old_j);
   v = (uint32_t)y.token(j, e + d - 1, old_j);
   w = pack_cs(1u, y.prob(j, e + d - 1, old_j));
   return true;
@@ -310,6 +314,7 @@ __device__ __forceinline__ Ctx make_ctx(const IndexView& ix, const StepIn& in, i
   c.gram = ix.gram ? ix.gram + (int64_t)p * ((int64_t)ix.bucket_mask + 1) * kBucketWords : nullptr;
   c.bucket_mask = ix.bucket_mask;
   c.kmax = ix.kmax;
+  c.eps = ix.eps;
   c.len_i = 0;
   c.q = 0;
   c.tid = threadIdx.x;

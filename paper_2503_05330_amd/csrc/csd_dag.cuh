@@ -132,7 +132,7 @@ __device__ __forceinline__ Tier1 build_dag(Lds& s, const Ctx& c, int32_t M, int3
       u = d == 1 ? (uint32_t)c.Q[0] : (uint32_t)win[d - 2];
       w = pack_cs(1u, (uint32_t)win[L + d - 1]);
     } else {
-      alive = layer_instance(c.y, m, d, u, v, w);
+      alive = layer_instance(c.y, m, d, (uint32_t)c.Q[0], u, v, w);
     }
     if (alive && !s.overflow) {
       Region r = t1.layer(d);
@@ -255,7 +255,7 @@ __device__ __forceinline__ void walk_streaming(Lds& s, const Ctx& c, int32_t L, 
         each_match([&](Match m) {
           uint32_t u, v;
           u64 w;
-          if (s.overflow || !layer_instance(c.y, m, d, u, v, w)) return;
+          if (s.overflow || !layer_instance(c.y, m, d, (uint32_t)c.Q[0], u, v, w)) return;
           if (((v * 0x9E3779B1u) >> 12 & (n_class - 1)) != r) return;
           table_add(s, all, dag_key(d, kAnyTok, v), w);
           if (u == (uint32_t)cur) table_add(s, all, dag_key(d, u, v), w);

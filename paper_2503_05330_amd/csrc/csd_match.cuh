@@ -29,6 +29,52 @@ __device__ __forceinline__ bool gram_equals_query(const Ctx& c, int32_t j, int32
   return hit;
 }
 
+// Eq. 4 with tolerance 1: is SOME substring of path j that ends just before
+// index e within one edit (substitution, insertion or deletion) of the query?
+// With t[a] = a-th token before e (newest first, like Q): the tokens newer than
+// the edit agree in place, the older ones agree in place (substitution), one
+// step further back (the text has an extra token) or one step closer (the text
+// lacks a token).
+__device__ __forceinline__ bool gram_near_query(const Ctx& c, int32_t j, int32_t e, int32_t old_j) {
+  constexpr int K = CSD_MAX_QUERY_LEN;
+  const int32_t q = c.q;
+  int32_t t[K + 1];
+#pragma unroll
+  for (int a = 0; a <= K; ++a) t[a] = (a <= q && a < e) ? c.y.token(j, e - 1 - a, old_j) : 0;
+  // pre[p]: t[a] == Q[a] for all a < p.  same/back/fwd[p]: the agreement of the older part
+  // a > p (same, fwd) or a >= p (back) at shift 0 / +1 / -1, scanned from the oldest token.
+  int32_t Q[K + 1];                                        // Q[K] only pads the unrolled loops
+#pragma unroll
+  for (int a = 0; a <= K; ++a) Q[a] = a < K ? c.Q[a < K ? a : 0] : 0;
+  bool pre[K + 1], same[K + 1], back[K + 1], fwd[K + 1];
+  pre[0] = true;
+#pragma unroll
+  for (int a = 0; a < K; ++a) pre[a + 1] = pre[a] && (a >= q || t[a] == Q[a]);
+  same[K] = back[K] = fwd[K] = true;
+#pragma unroll
+  for (int a = K - 1; a >= 0; --a) {
+    same[a] = same[a + 1] && (a + 1 >= q || t[a + 1] == Q[a + 1]);
+    back[a] = back[a + 1] && (a >= q || t[a + 1] == Q[a]);
+    fwd[a] = fwd[a + 1] && (a + 1 >= q || t[a] == Q[a + 1]);
+  }
+  bool hit = false;
+#pragma unroll
+  for (int p = 0; p <= K; ++p) {
+    if (p < q) {
+      hit = hit || (e >= q && pre[p] && same[p]);          // Q[p] substituted (or kept)
+      hit = hit || (e >= q - 1 && pre[p] && fwd[p]);       // the text lacks Q[p]
+    }
+    if (p <= q) hit = hit || (e >= q + 1 && pre[p] && back[p]);   // extra text token at p
+  }
+  return hit;
+}
+
+// The match predicate of the scan: exact (Eq. 3) or within one edit (Eq. 4).
+__device__ __forceinline__ bool position_matches(const Ctx& c, int32_t j, int32_t e,
+                                                 int32_t old_j) {
+  return c.eps == 0 ? gram_equals_query(c, j, e, old_j) : gram_near_query(c, j, e, old_j);
+}
+
 __device__ __forceinline__ GramHash query_hash(const Ctx& c) {
   uint32_t acc = kGramSeed;
 #pragma unroll
@@ -76,12 +122,13 @@ struct FnSink {
 
 // ---------------------------------------------------------------- general matchers
 
-// Eq. 3 by exhaustive comparison: every position e of every other path j with
-// q <= e <= len_j - 1 is tested.  Trip counts are uniform over the workgroup;
+// Eq. 3 / Eq. 4 by exhaustive comparison: every position e of every other path
+// j with q - eps <= e <= len_j - 1 is tested.  Trip counts are uniform over the workgroup;
 // four tiles are in flight at a time.
 template <int BLOCK, class Sink>
 __device__ __forceinline__ void match_scan(const Ctx& c, Sink& sink) {
   constexpr int kUnroll = 4;
+  const int32_t first_e = c.q > c.eps ? c.q - c.eps : 0;   // shortest substring that can match
   int32_t tiles_per_path = (c.y.max_len + BLOCK - 1) / BLOCK;
   int32_t tiles = c.y.N * tiles_per_path;
   for (int32_t g0 = 0; g0 < tiles; g0 += kUnroll) {
@@ -91,14 +138,14 @@ __device__ __forceinline__ void match_scan(const Ctx& c, Sink& sink) {
     for (int u = 0; u < kUnroll; ++u) {
       int32_t g = g0 + u;
       int32_t j = g / tiles_per_path;
-      int32_t e = c.q + (g - j * tiles_per_path) * BLOCK + c.tid;
+      int32_t e = first_e + (g - j * tiles_per_path) * BLOCK + c.tid;
       hit[u] = false;
       m[u] = Match{0, 0, 0};
       if (g < tiles && j != c.i) {
         int32_t old_j = c.y.old_len(j);
         int32_t new_j = c.y.new_len(j, old_j);
         if (e < new_j) {
-          hit[u] = gram_equals_query(c, j, e, old_j);
+          hit[u] = position_matches(c, j, e, old_j);
           m[u] = make_match(c.y, j, e, old_j, new_j);
         }
       }

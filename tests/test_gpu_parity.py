@@ -326,3 +326,78 @@ def test_maximum_positions_per_problem(oracle):
         assert ix.status() == 0
         del ix, out
         torch.cuda.empty_cache()
+
+
+# ---------------------------------------------------------------- fuzzy suffix matching (Eq. 4, one edit)
+def _fuzzy_replay(oracle, w, check_every, hows, dump_at=(), edges=True):
+    tokens, probs = synth.make_paths(w)
+    T, k, L = w.max_len, w.query_len, w.draft_len
+    steps = sorted(set(list(range(0, T, check_every)) + [0, 1, 2, 3, T - 1]))
+    want = {t: oracle.draft_all(tokens, probs, np.full(tokens.shape[:2], t + 1, dtype=np.int32), k, L,
+                                1.0, 0, eps=1) for t in steps}
+    exact_nonempty = sum(int((oracle.draft_all(tokens, probs, np.full(tokens.shape[:2], t + 1, dtype=np.int32),
+                                               k, L, 1.0, 0)["draft_len"] > 0).sum()) for t in steps[::4])
+    fuzzy_nonempty = sum(int((want[t]["draft_len"] > 0).sum()) for t in steps[::4])
+    assert fuzzy_nonempty > exact_nonempty           # the tolerance finds more
+    for how in hows:
+        print("fuzzy replay", w.name, how, flush=True)
+        got = gpu_replay(tokens, probs, k, L, 1.0, 0, 0, how=how, max_edits=1)
+        assert got["status"] == 0
+        for t in steps:
+            assert_step_equal(got, want[t], t, "fuzzy %s %s" % (w.name, how))
+    dev = torch.device("cuda:0")
+    for t in dump_at:
+        ix = binding.Index(w.n_problems, w.n_paths, T, w.vocab, k, L, 1.0, 0, 0, device=dev, max_edits=1)
+        ix.append(torch.from_numpy(np.ascontiguousarray(tokens[:, :, :t])).to(dev),
+                  torch.from_numpy(np.ascontiguousarray(probs[:, :, :t])).to(dev), None, t)
+        lens_t = np.full(tokens.shape[:2], t, dtype=np.int32)
+        for q in range(1, k + 1):
+            je, moff = ix.dump_matches(q, cap=1 << 22)
+            for i in range(w.n_paths):
+                assert np.array_equal(je[moff[i]:moff[i + 1]], oracle.matches(tokens[0], lens_t[0], i, q, 1)), (q, i)
+        if not edges:        # rows whose tables exceed the on-chip tier are not dumpable
+            continue
+        duv, cs, eoff = ix.dump_edges(k, L)
+        for i in range(w.n_paths):
+            wduv, wcs = oracle.edges(tokens[0], probs[0], lens_t[0], i, k, L, 1)
+            assert np.array_equal(duv[eoff[i]:eoff[i + 1]], wduv) and np.array_equal(cs[eoff[i]:eoff[i + 1]], wcs)
+
+
+def test_fuzzy_c1_every_step(oracle):
+    _fuzzy_replay(oracle, synth.WORKLOADS["C1"], 1, ("replay", "calls"), dump_at=(7, 256))
+
+
+def test_fuzzy_c2_sampled_steps(oracle):
+    _fuzzy_replay(oracle, synth.WORKLOADS["C2"], 32, ("replay",), dump_at=(300,), edges=False)
+
+
+def test_fuzzy_small_cases(oracle):
+    """Hand cases and tiny random inputs, including queries of one token (every position of
+    every other path is within one edit of it) and matches at index 0."""
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(21)
+    cases = [([[9, 1, 2, 3], [1, 7, 3, 50, 0, 1, 3, 51, 0, 1, 2, 8, 3, 52, 0, 4, 4, 4, 53]], 3, 4),
+             ([[5], [6, 7, 8], [5, 5]], 1, 3), ([[1, 2], [2, 9], [], [1, 9, 2, 4]], 2, 2)]
+    for _ in range(60):
+        n = int(rng.integers(2, 5))
+        cases.append(([rng.integers(0, 4, size=int(rng.integers(0, 20))).tolist() for _ in range(n)],
+                      int(rng.integers(1, 5)), int(rng.integers(1, 6))))
+    for paths, k, L in cases:
+        N, T = len(paths), max(1, max(len(p) for p in paths))
+        tok = np.zeros((1, N, T), dtype=np.int32)
+        cnt = np.array([[len(p) for p in paths]], dtype=np.int32)
+        for j, p in enumerate(paths):
+            tok[0, j, :len(p)] = p
+        pr = (rng.integers(1, 9, size=tok.shape) / 8.0).astype(np.float32)
+        ix = binding.Index(1, N, T, 64, k, L, 0.5, 0, 0, device=dev, max_edits=1)
+        ix.append(torch.from_numpy(tok).to(dev), torch.from_numpy(pr).to(dev), torch.from_numpy(cnt).to(dev), T)
+        out = ix.draft(k, L)
+        want = oracle.draft_all(tok, pr, cnt, k, L, 0.5, 0, eps=1)
+        got = dict(draft=out["tokens"].cpu().numpy()[None], draft_len=out["length"].cpu().numpy()[None],
+                   token_scores=out["token_scores"].cpu().numpy()[None],
+                   path_scores=out["path_scores"].cpu().numpy()[None])
+        assert_step_equal(got, want, 0, "fuzzy case %s k=%d L=%d" % (paths, k, L))
+        je, off = ix.dump_matches(k)
+        for i in range(N):
+            assert np.array_equal(je[off[i]:off[i + 1]], oracle.matches(tok[0], cnt[0], i, k, 1)), (paths, k, i)
+        assert ix.status() == 0
