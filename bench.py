@@ -54,6 +54,9 @@ def main():
     ap.add_argument("--steps", type=int, default=1024)
     ap.add_argument("--warmup", type=int, default=64)
     ap.add_argument("--workload", default="C2")
+    ap.add_argument("--max-edits", type=int, default=0,
+                    help="edit tolerance of the suffix match (0 = exact, the headline; 1 = fuzzy, by scan)")
+    ap.add_argument("--matcher", choices=("auto", "scan", "index"), default="auto")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 64 MiB copy kernel (reference for traffic counters)")
@@ -79,7 +82,8 @@ def main():
     d_pr = torch.from_numpy(np.ascontiguousarray(probs.transpose(2, 0, 1))).to(dev)
     tg = np.stack([synth.make_targets(tokens, min(t + 1, T), L) for t in range(T)])
     d_tg = torch.from_numpy(tg).to(dev)
-    ix = binding.Index(P, N, T, w.vocab, k, L, 1.0, 0, 0, device=dev)
+    ix = binding.Index(P, N, T, w.vocab, k, L, 1.0, 0, {"auto": 0, "scan": 1, "index": 2}[args.matcher],
+                       device=dev, max_edits=args.max_edits)
     out = dict(tokens=torch.empty((P, N, L), dtype=torch.int32, device=dev),
                length=torch.empty((P, N), dtype=torch.int32, device=dev),
                token_scores=torch.empty((P, N, L), dtype=torch.float32, device=dev),
@@ -163,8 +167,8 @@ def main():
         "ms_per_step": dt / K * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "u64", "data": "synthetic",
         "config": {"workload": "%s: P=%d problems x N=%d paths x %d tokens, vocab %d, query %d, draft %d, "
-                               "probs supplied, alpha 1; step = append 1 token/path + draft all paths + accept"
-                               % (w.name, P, N, T, w.vocab, k, L)},
+                               "probs supplied, alpha 1, max_edits %d; step = append 1 token/path + draft all "
+                               "paths + accept" % (w.name, P, N, T, w.vocab, k, L, args.max_edits)},
         "us_per_step_mean_over_replay": dt / K * 1e6,
         "us_per_step_at_full_history": dt_tail / tail * 1e6,
         "us_per_step_three_launches": dt_unfused * 1e6,
@@ -185,7 +189,7 @@ def main():
             c0 = time.perf_counter()
             for t in range(T):
                 lens = np.full((P, N), t + 1, dtype=np.int32)
-                oracle.draft_all(tokens, probs, lens, k, L, 1.0, 0, tg[t])
+                oracle.draft_all(tokens, probs, lens, k, L, 1.0, 0, tg[t], eps=args.max_edits)
             t_cpu += time.perf_counter() - c0
             n_done += T
             reps += 1
