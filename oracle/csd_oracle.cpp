@@ -137,9 +137,15 @@ std::vector<Candidate> candidate_pool(const Paths& Y, int32_t i, int32_t k, int3
     const int32_t* yj = Y.tok + (int64_t)j * Y.max_len;
     for (int32_t e = 0; e <= Y.len[j] - 1; ++e) {          /* R1, R2 */
       bool match = false;
-      /* R12: substrings ending before e; |l - q| <= distance, so only these lengths can do */
-      for (int32_t l = (q > eps ? q - eps : 0); l <= q + eps && l <= e && !match; ++l)
-        if (edit_distance(query, q, yj + (e - l), l) <= eps) match = true;
+      if (eps == 0) {
+        /* Eq. 3 as it stands: the q tokens before e are the query (distance 0 is equality) */
+        match = e >= q;
+        for (int32_t a = 0; a < q && match; ++a) match = yj[e - q + a] == query[a];
+      } else {
+        /* R12: substrings ending before e; |l - q| <= distance, so only these lengths can do */
+        for (int32_t l = (q > eps ? q - eps : 0); l <= q + eps && l <= e && !match; ++l)
+          if (edit_distance(query, q, yj + (e - l), l) <= eps) match = true;
+      }
       if (match) pool.push_back(Candidate{j, e});
     }
   }
