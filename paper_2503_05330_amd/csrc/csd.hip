@@ -86,7 +86,9 @@ Layout make_layout(const csd_config* c) {
   size_t cells = (size_t)c->n_problems * c->n_paths * c->max_len;
   size_t rows = (size_t)c->n_problems * c->n_paths;
   size_t at = 0;
-  l.tok = at;    at += align_up(cells * sizeof(int32_t));
+  // + 8 cells: lanes of the scan that have no position still load the first six cells of
+  // their problem's first path, and a span may read two cells past its path
+  l.tok = at;    at += align_up((cells + 8) * sizeof(int32_t));
   l.pq = at;     at += align_up(cells * sizeof(uint32_t));
   l.meta_stride = (1 + c->max_query_len + 3) / 4 * 4;
   l.eshift = 1;
@@ -147,8 +149,12 @@ int check_draft_args(const csd_index* h, int32_t query_len, int32_t draft_len) {
 void launch_draft(const csd_index* h, const IndexView& v, const StepIn& in, const DraftArgs& a,
                   hipStream_t st) {
   int64_t rows = (int64_t)v.P * v.N;
-  if (!h->indexed)
-    step_scan_kernel<<<xcd_grid(rows), kScanBlock, 0, st>>>(v, in, a);
+  if (!h->indexed && a.L <= 8)
+    step_scan_kernel<8><<<xcd_grid(rows), kScanBlock, 0, st>>>(v, in, a);
+  else if (!h->indexed && a.L <= 16)
+    step_scan_kernel<16><<<xcd_grid(rows), kScanBlock, 0, st>>>(v, in, a);
+  else if (!h->indexed)     // longer drafts: the walk's register-resident fast path is left out
+    step_scan_kernel<1><<<xcd_grid(rows), kScanBlock, 0, st>>>(v, in, a);
   else if (a.L <= 8)
     step_wave_kernel<8><<<xcd_grid(rows), kWave, 0, st>>>(v, in, a);
   else if (a.L <= 16)
@@ -403,7 +409,7 @@ int csd_dump_edges(csd_index* h, int32_t query_len, int32_t draft_len, int32_t* 
   int32_t rows = h->view.P * h->view.N;
   u64* tmp = nullptr;
   int32_t* counts = nullptr;
-  size_t tmp_elems = (size_t)rows * kTableCap;
+  size_t tmp_elems = (size_t)rows * kDumpStride;
   CSD_HIP(hipMalloc(&tmp, 2 * tmp_elems * sizeof(u64)));
   hipError_t e = hipMalloc(&counts, ((size_t)rows + 1) * sizeof(int32_t));
   if (e != hipSuccess) { (void)hipFree(tmp); return hip_fail(e, "hipMalloc"); }

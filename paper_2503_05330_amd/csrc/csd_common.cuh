@@ -18,10 +18,8 @@ namespace csd {
 typedef unsigned long long u64;
 
 constexpr int kWave = 64;
-constexpr int kScanBlock = 256;             // threads per row when matches come from a scan
-constexpr int kMatchCap = 1024;             // matches kept in LDS; beyond -> streaming tier
-constexpr int kTableCap = 1024;             // LDS hash slots for DAG edges + nodes
-constexpr int kWinWords = 2048;             // LDS words for cached continuations of matches
+constexpr int kScanBlock = 1024;            // threads per row when matches come from a scan
+constexpr int kDumpStride = 4096;           // debug dump: entries per row of its staging buffers
 constexpr int kLenCache = 256;              // path lengths cached in LDS (more paths: read memory)
 constexpr uint32_t kTokMask = (1u << 29) - 1;
 constexpr uint32_t kAnyTok = kTokMask;      // "any predecessor": marks node (in-weight) entries
@@ -174,12 +172,22 @@ struct Paths {
   __device__ __forceinline__ int32_t cell(int32_t j, int32_t t) const {   // j, t < 2^24
     return (int32_t)__umul24((uint32_t)j, (uint32_t)max_len) + t;
   }
+  // Both readers select the address first and then issue ONE load outside any branch, so
+  // that the loads of an unrolled loop all travel together instead of one per branch.
   __device__ __forceinline__ int32_t token(int32_t j, int32_t t, int32_t old_j) const {
-    return t < old_j ? tok[cell(j, t)] : st[(int64_t)j * n + (t - old_j)];
+    bool hist = t < old_j;
+    const int32_t* base = hist ? tok : st;
+    int64_t off = hist ? (int64_t)cell(j, t) : (int64_t)j * n + (t - old_j);
+    return base[off];
   }
   __device__ __forceinline__ uint32_t prob(int32_t j, int32_t t, int32_t old_j) const {
-    if (t < old_j) return pq[cell(j, t)];
-    return sp ? quantize_prob(sp[(int64_t)j * n + (t - old_j)]) : 65536u;
+    bool hist = t < old_j;
+    bool given = !hist && sp != nullptr;
+    const uint32_t* base = given ? reinterpret_cast<const uint32_t*>(sp) : pq;
+    int64_t off = hist ? (int64_t)cell(j, t) : (given ? (int64_t)j * n + (t - old_j) : 0);
+    uint32_t word = base[off];
+    if (hist) return word;
+    return given ? quantize_prob(__uint_as_float(word)) : 65536u;
   }
   __device__ __forceinline__ int32_t pos(int32_t j, int32_t e) const { return (j << eshift) | e; }
   __device__ __forceinline__ int32_t pos_path(int32_t pos) const { return pos >> eshift; }
@@ -199,17 +207,29 @@ struct Slot {
   u64 val;
 };
 
-struct Lds {
-  Slot table[kTableCap];
-  uint16_t link[kTableCap];     // edge slot -> slot of its target node (tier 1)
-  Match match[kMatchCap];
-  int32_t win[kWinWords];       // per cached match: L continuation tokens, then their L probabilities
+// On-chip state of one row.  TABLE = hash slots for DAG edges + nodes (power of
+// two), MATCH = matches kept (beyond: streaming tier), WIN = words for cached
+// continuations of matches, WAVES = waves of the workgroup.
+template <int TABLE, int MATCH, int WIN, int WAVES>
+struct LdsT {
+  static constexpr int kTable = TABLE;
+  static constexpr int kMatch = MATCH;
+  static constexpr int kWin = WIN;
+  Slot table[TABLE];
+  uint16_t link[TABLE];         // edge slot -> slot of its target node (tier 1)
+  Match match[MATCH];
+  int32_t win[WIN];             // per cached match: L continuation tokens, then their L probabilities
   int32_t len_old[kLenCache];
   int32_t len_new[kLenCache];
-  Cand red[2][kScanBlock / kWave];
-  int n_match;                  // total matches found (may exceed kMatchCap)
+  Cand red[2][WAVES];
+  int n_match;                  // total matches found (may exceed MATCH)
   int overflow;                 // a DAG table region ran out of room
 };
+// One wave per row (index mode): 38 KB, four rows share a CU's LDS.
+typedef LdsT<1024, 1024, 2048, 1> LdsWave;
+// One 1024-thread workgroup per row (scan mode, where a fuzzy query can have
+// thousands of matches): 108 KB, one row per CU.
+typedef LdsT<4096, 4096, 16, kScanBlock / kWave> LdsScan;
 
 struct Ctx {                    // one (problem, query path)
   Paths y;
@@ -265,7 +285,8 @@ __device__ __forceinline__ bool layer_instance(const Paths& y, Match m, int32_t 
   // rel_old is exact unless clipped at 63 (a step appends at most 32767 tokens), and
   // d <= 32 < 63: every index read below is then on the history side either way
   int32_t old_j = e + (int32_t)m.rel_old;
-  u = d == 1 ? root : (uint32_t)y.token(j, e + d - 2, old_j);
+  uint32_t before = (uint32_t)y.token(j, e + (d >= 2 ? d - 2 : 0), old_j);   // no branch around the load
+  u = d == 1 ? root : before;
   v = (uint32_t)y.token(j, e + d - 1, old_j);
   w = pack_cs(1u, y.prob(j, e + d - 1, old_j));
   return true;

@@ -18,8 +18,16 @@ struct Region {                 // slots [base, base + mask] of the LDS table
   uint32_t base, mask;
 };
 
+// Orders the workgroup's LDS traffic only: unlike __syncthreads() it does not
+// wait for global loads in flight, so a prefetch can stay in the air across it.
 template <int BLOCK>
-__device__ __forceinline__ void table_clear(Lds& s, uint32_t n_slots, int tid) {
+__device__ __forceinline__ void lds_barrier() {
+  if (BLOCK == kWave) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  else asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+template <int BLOCK, class LDS>
+__device__ __forceinline__ void table_clear(LDS& s, uint32_t n_slots, int tid) {
   for (uint32_t h = tid; h < n_slots; h += BLOCK) s.table[h] = Slot{kEmpty, 0ull};
   if (tid == 0) s.overflow = 0;
 }
@@ -27,7 +35,8 @@ __device__ __forceinline__ void table_clear(Lds& s, uint32_t n_slots, int tid) {
 // table[key] += delta inside a region, inserting the key if new; returns the
 // slot.  Sets s.overflow when the region has no free slot (the caller then
 // falls back) — never spins.
-__device__ __forceinline__ uint32_t table_add(Lds& s, Region r, u64 key, u64 delta) {
+template <class LDS>
+__device__ __forceinline__ uint32_t table_add(LDS& s, Region r, u64 key, u64 delta) {
   uint32_t h = dag_hash(key) & r.mask;
   for (uint32_t probe = 0; probe <= r.mask; ++probe) {
     Slot* slot = &s.table[r.base + h];
@@ -46,7 +55,8 @@ __device__ __forceinline__ uint32_t table_add(Lds& s, Region r, u64 key, u64 del
   return r.base;
 }
 
-__device__ __forceinline__ u64 table_get(const Lds& s, Region r, u64 key) {
+template <class LDS>
+__device__ __forceinline__ u64 table_get(const LDS& s, Region r, u64 key) {
   uint32_t h = dag_hash(key) & r.mask;
   for (uint32_t probe = 0; probe <= r.mask; ++probe) {
     Slot x = s.table[r.base + h];
@@ -58,16 +68,14 @@ __device__ __forceinline__ u64 table_get(const Lds& s, Region r, u64 key) {
 }
 
 // Workgroup-wide argmax of the per-thread candidates; every thread gets the result.
-template <int BLOCK>
-__device__ __forceinline__ Cand block_argmax(Lds& s, Cand c, int tid, int parity) {
+template <int BLOCK, class LDS>
+__device__ __forceinline__ Cand block_argmax(LDS& s, Cand c, int tid, int parity) {
   c = wave_argmax(c);
   if (BLOCK == kWave) return c;
   if ((tid & 63) == 0) s.red[parity][tid >> 6] = c;
-  __syncthreads();
-  Cand r = s.red[parity][0];
-#pragma unroll
-  for (int w = 1; w < BLOCK / kWave; ++w) r = cand_best(r, s.red[parity][w]);
-  return r;
+  lds_barrier<BLOCK>();
+  int lane = tid & 63;                                  // every wave reduces the waves' results
+  return wave_argmax(lane < BLOCK / kWave ? s.red[parity][lane] : cand_none());
 }
 
 __device__ __forceinline__ void note_choice(DraftOut& o, Cand best, int32_t d, int tid) {
@@ -93,9 +101,9 @@ struct Tier1 {                  // geometry of the table for one query
   }
 };
 
-__device__ __forceinline__ Tier1 tier1_geometry(int32_t M, int32_t L) {
+__device__ __forceinline__ Tier1 tier1_geometry(int32_t M, int32_t L, int table_cap) {
   uint32_t want = 4u * (uint32_t)M;                   // a layer holds <= 2M keys: <= 50 % load
-  uint32_t cap = (uint32_t)kTableCap / (uint32_t)L;   // what fits (rounded down to 2^x below)
+  uint32_t cap = (uint32_t)table_cap / (uint32_t)L;   // what fits (rounded down to 2^x below)
   uint32_t size = 8;
   while (size < want && size * 2 <= cap) size <<= 1;
   return Tier1{size};
@@ -106,10 +114,10 @@ __device__ __forceinline__ Tier1 tier1_geometry(int32_t M, int32_t L) {
 // sum), so a node's value is directly the in-weight the walk ranks by:
 // sum over instances of  alpha_q * p + (65536 - alpha_q) * 65536.  Every edge
 // slot also records where its target node sits (s.link).
-template <int BLOCK>
-__device__ __forceinline__ Tier1 build_dag(Lds& s, const Ctx& c, int32_t M, int32_t L, WinInfo wi,
+template <int BLOCK, class LDS>
+__device__ __forceinline__ Tier1 build_dag(LDS& s, const Ctx& c, int32_t M, int32_t L, WinInfo wi,
                                            uint32_t alpha_q) {
-  Tier1 t1 = tier1_geometry(M, L);
+  Tier1 t1 = tier1_geometry(M, L, LDS::kTable);
   table_clear<BLOCK>(s, t1.region * (uint32_t)L, c.tid);
   block_sync<BLOCK>();
   int32_t items = M * L;
@@ -145,22 +153,58 @@ __device__ __forceinline__ Tier1 build_dag(Lds& s, const Ctx& c, int32_t M, int3
   return t1;
 }
 
-// The weight the greedy step ranks edge slot `e` by: the in-weight of its
-// target node (score_mode 0, the rule after Eq. 5) or its own weight (mode 1).
-__device__ __forceinline__ u64 edge_rank(const Lds& s, uint32_t e, u64 edge_val, uint32_t alpha_q,
-                                         int score_mode) {
-  return score_mode ? weight_key(edge_val, alpha_q) : s.table[s.link[e]].val;
+// Replaces the value of every edge slot by the weight the greedy step ranks it
+// by: the in-weight of its target node (score_mode 0, the rule after Eq. 5) or
+// its own weight (mode 1).  Node slots are only read.  The caller synchronises.
+template <int BLOCK, class LDS>
+__device__ __forceinline__ void score_edges(LDS& s, uint32_t n_slots, uint32_t alpha_q,
+                                            int score_mode, int tid) {
+#pragma unroll 4
+  for (uint32_t h = tid; h < n_slots; h += BLOCK) {
+    Slot x = s.table[h];
+    uint32_t node = (uint32_t)s.link[h] & (uint32_t)(LDS::kTable - 1);   // stale links stay in range
+    u64 in_weight = s.table[node].val;
+    if (x.key != kEmpty && key_u(x.key) != kAnyTok)
+      s.table[h].val = score_mode ? weight_key(x.val, alpha_q) : in_weight;
+  }
+}
+
+// Greedy walk (rule after Eq. 5) over tables whose edges score_edges() has scored.
+template <int BLOCK, class LDS>
+__device__ __forceinline__ void walk_scored(LDS& s, const Ctx& c, Tier1 t1, int32_t L, DraftOut& o) {
+  int32_t cur = c.Q[0];
+  for (int32_t d = 1; d <= L; ++d) {
+    Region r = t1.layer(d);
+    u64 want = dag_key(d, (uint32_t)cur, 0) >> 29;
+    Cand best = cand_none();
+#pragma unroll 4
+    for (uint32_t h = c.tid; h <= r.mask; h += BLOCK) {
+      Slot x = s.table[r.base + h];
+      if ((x.key >> 29) == want) best = cand_best(best, Cand{x.val, (int32_t)key_v(x.key)});
+    }
+    best = block_argmax<BLOCK>(s, best, c.tid, d & 1);
+    if (best.v == INT_MAX) break;                     // leaf: no edge leaves cur
+    note_choice(o, best, d, c.tid);
+    cur = best.v;
+  }
+}
+
+// Does the one-wave walk below keep all layers in registers?
+template <int LCAP>
+__device__ __forceinline__ bool walk_fits_registers(Tier1 t1, int32_t L) {
+  return t1.region <= (uint32_t)kWave && L <= LCAP;
 }
 
 // Greedy walk over the finished tables (rule after Eq. 5).  When a layer's
 // region fits the wave (one slot per lane) every lane fetches its slot of ALL
 // layers, and the ranks behind them, before the walk starts: the serial part is
 // then a compare, a ballot and a lane read per layer, with no memory latency.
-template <int BLOCK, int LCAP>
-__device__ __forceinline__ void walk_dag(Lds& s, const Ctx& c, Tier1 t1, int32_t L,
+// Larger tables are scored in place first and then searched layer by layer.
+template <int BLOCK, int LCAP, class LDS>
+__device__ __forceinline__ void walk_dag(LDS& s, const Ctx& c, Tier1 t1, int32_t L,
                                          uint32_t alpha_q, int score_mode, DraftOut& o) {
   int32_t cur = c.Q[0];
-  if (BLOCK == kWave && t1.region <= (uint32_t)kWave) {
+  if (BLOCK == kWave && walk_fits_registers<LCAP>(t1, L)) {
     // Three rounds of independent LDS reads (slot, link, linked node), none of them behind a
     // branch, so that the reads of all layers are in flight together.
     u64 key[LCAP], rank[LCAP];
@@ -174,7 +218,7 @@ __device__ __forceinline__ void walk_dag(Lds& s, const Ctx& c, Tier1 t1, int32_t
       Slot x = s.table[at[d - 1]];
       key[d - 1] = (d <= L && mine) ? x.key : kEmpty;
       rank[d - 1] = x.val;
-      node[d - 1] = (uint32_t)s.link[at[d - 1]] & (uint32_t)(kTableCap - 1);   // stale links stay in range
+      node[d - 1] = (uint32_t)s.link[at[d - 1]] & (uint32_t)(LDS::kTable - 1);   // stale links stay in range
     }
     if (score_mode == 0) {
 #pragma unroll
@@ -183,41 +227,33 @@ __device__ __forceinline__ void walk_dag(Lds& s, const Ctx& c, Tier1 t1, int32_t
 #pragma unroll
       for (int d = 1; d <= LCAP; ++d) rank[d - 1] = weight_key(rank[d - 1], alpha_q);
     }
+    bool going = true;                                // no `break`: the loop must unroll fully
 #pragma unroll
     for (int d = 1; d <= LCAP; ++d) {
-      if (d > L) break;
-      u64 want = dag_key(d, (uint32_t)cur, 0) >> 29;
-      Cand best = cand_none();
-      if ((key[d - 1] >> 29) == want) best = Cand{rank[d - 1], (int32_t)key_v(key[d - 1])};
-      best = wave_argmax(best);
-      if (best.v == INT_MAX) break;                   // leaf: no edge leaves cur
-      note_choice(o, best, d, c.tid);
-      cur = best.v;
+      if (d <= L && going) {
+        u64 want = dag_key(d, (uint32_t)cur, 0) >> 29;
+        Cand best = cand_none();
+        if ((key[d - 1] >> 29) == want) best = Cand{rank[d - 1], (int32_t)key_v(key[d - 1])};
+        best = wave_argmax(best);
+        going = best.v != INT_MAX;                    // leaf: no edge leaves cur
+        if (going) {
+          note_choice(o, best, d, c.tid);
+          cur = best.v;
+        }
+      }
     }
     return;
   }
-  for (int32_t d = 1; d <= L; ++d) {
-    Region r = t1.layer(d);
-    u64 want = dag_key(d, (uint32_t)cur, 0) >> 29;
-    Cand best = cand_none();
-    for (uint32_t h = c.tid; h <= r.mask; h += BLOCK) {
-      Slot x = s.table[r.base + h];
-      if ((x.key >> 29) == want)
-        best = cand_best(best, Cand{edge_rank(s, r.base + h, x.val, alpha_q, score_mode),
-                                    (int32_t)key_v(x.key)});
-    }
-    best = block_argmax<BLOCK>(s, best, c.tid, d & 1);
-    if (best.v == INT_MAX) break;                     // leaf: no edge leaves cur
-    note_choice(o, best, d, c.tid);
-    cur = best.v;
-  }
+  score_edges<BLOCK>(s, t1.region * (uint32_t)L, alpha_q, score_mode, c.tid);
+  block_sync<BLOCK>();
+  walk_scored<BLOCK>(s, c, t1, L, o);
 }
 
-// ---------------------------------------------------------------- tier 2: streaming, layer by layer
+// ---------------------------------------------------------------- layer by layer
 
 // Successors of `cur` in layer d as held by a region with raw (C, S) values.
-template <int BLOCK>
-__device__ __forceinline__ Cand scan_successors(const Lds& s, Region r, int d, int32_t cur,
+template <int BLOCK, class LDS>
+__device__ __forceinline__ Cand scan_successors(const LDS& s, Region r, int d, int32_t cur,
                                                 uint32_t alpha_q, int score_mode, int tid,
                                                 Cand best) {
   u64 want = dag_key(d, (uint32_t)cur, 0) >> 29;
@@ -231,13 +267,64 @@ __device__ __forceinline__ Cand scan_successors(const Lds& s, Region r, int d, i
   return best;
 }
 
+// Tier 1b, for M <= BLOCK matches whose L layers do not fit the table together
+// (a fuzzy query: many matches with unrelated continuations).  Thread m owns
+// match m.  The layers are built and walked one at a time in a single region —
+// a layer holds at most 2M keys, which a table of 4 * BLOCK slots takes at half
+// load — and the tokens of layer d + 1 are in flight while layer d is built
+// and searched.  Same result as tier 1: all sums are exact.
+template <int BLOCK, class LDS>
+__device__ __forceinline__ void walk_layers(LDS& s, const Ctx& c, int32_t M, int32_t L,
+                                            uint32_t alpha_q, int score_mode, DraftOut& o) {
+  static_assert(LDS::kTable >= 4 * BLOCK, "a layer of BLOCK matches must fit at half load");
+  int32_t rem = 0, j = 0, e = 0, old_j = 1;
+  if (c.tid < M) {
+    Match m = s.match[c.tid];
+    rem = (int32_t)m.rem_new < L ? (int32_t)m.rem_new : L;
+    j = c.y.pos_path(m.pos);
+    e = c.y.pos_index(m.pos);
+    old_j = e + (int32_t)m.rel_old;                   // exact wherever it decides (see layer_instance)
+  }
+  uint32_t size = 64;
+  while (size < 4u * (uint32_t)M) size <<= 1;         // <= 4 * BLOCK <= LDS::kTable
+  const Region r{0u, size - 1u};
+  int32_t cur = c.Q[0];
+  uint32_t u = (uint32_t)c.Q[0];
+  // lanes whose candidate has ended read cell 0 of path 0: every lane loads, nothing branches
+  int32_t v_next = c.y.token(rem >= 1 ? j : 0, rem >= 1 ? e : 0, rem >= 1 ? old_j : 1);
+  uint32_t p_next = c.y.prob(rem >= 1 ? j : 0, rem >= 1 ? e : 0, rem >= 1 ? old_j : 1);
+  for (int32_t d = 1; d <= L; ++d) {
+    uint32_t v = (uint32_t)v_next;
+    u64 w = pack_cs(1u, p_next);
+    bool more = d < rem;
+    v_next = c.y.token(more ? j : 0, more ? e + d : 0, more ? old_j : 1);
+    p_next = c.y.prob(more ? j : 0, more ? e + d : 0, more ? old_j : 1);
+    lds_barrier<BLOCK>();                             // readers of the previous layer are done
+    table_clear<BLOCK>(s, size, c.tid);
+    lds_barrier<BLOCK>();
+    if (d <= rem) {
+      table_add(s, r, dag_key(d, kAnyTok, v), w);
+      if (u == (uint32_t)cur) table_add(s, r, dag_key(d, u, v), w);
+    }
+    lds_barrier<BLOCK>();
+    Cand best = scan_successors<BLOCK>(s, r, d, cur, alpha_q, score_mode, c.tid, cand_none());
+    best = block_argmax<BLOCK>(s, best, c.tid, d & 1);
+    if (best.v == INT_MAX) break;                     // leaf: no edge leaves cur
+    note_choice(o, best, d, c.tid);
+    cur = best.v;
+    u = v;
+  }
+}
+
+// ---------------------------------------------------------------- tier 2: streaming
+
 // Same result as tier 1 with bounded memory for any input.  `each_match(f)`
 // calls f(Match) for every match (from the LDS list, or by matching again).
-template <int BLOCK, class EachMatch>
-__device__ __forceinline__ void walk_streaming(Lds& s, const Ctx& c, int32_t L, uint32_t alpha_q,
+template <int BLOCK, class LDS, class EachMatch>
+__device__ __forceinline__ void walk_streaming(LDS& s, const Ctx& c, int32_t L, uint32_t alpha_q,
                                                int score_mode, uint32_t* status, DraftOut& o,
                                                EachMatch each_match) {
-  const Region all{0u, (uint32_t)kTableCap - 1u};
+  const Region all{0u, (uint32_t)LDS::kTable - 1u};
   int32_t cur = c.Q[0];
   int class_bits = 0;
   int parity = 0;
@@ -250,7 +337,7 @@ __device__ __forceinline__ void walk_streaming(Lds& s, const Ctx& c, int32_t L, 
       uint32_t n_class = 1u << class_bits;
       for (uint32_t r = 0; r < n_class && !failed; ++r) {
         block_sync<BLOCK>();                           // previous readers are done
-        table_clear<BLOCK>(s, kTableCap, c.tid);
+        table_clear<BLOCK>(s, LDS::kTable, c.tid);
         block_sync<BLOCK>();
         each_match([&](Match m) {
           uint32_t u, v;
@@ -280,8 +367,8 @@ __device__ __forceinline__ void walk_streaming(Lds& s, const Ctx& c, int32_t L, 
 
 // Writes the edge entries of a finished, unscored tier-1 table, sorted by key,
 // to ok / ov (debug dump).  Returns through *n_edges (an LDS counter).
-template <int BLOCK>
-__device__ __forceinline__ void emit_sorted_edges(Lds& s, uint32_t n_slots, int tid, int* n_edges,
+template <int BLOCK, class LDS>
+__device__ __forceinline__ void emit_sorted_edges(LDS& s, uint32_t n_slots, int tid, int* n_edges,
                                                   u64* ok, u64* ov) {
   for (uint32_t h = tid; h < n_slots; h += BLOCK) {
     u64 key = s.table[h].key;

@@ -54,46 +54,91 @@ __device__ __forceinline__ void write_accept(const DraftArgs& a, int32_t row, co
   if (tid == 0) a.accept_len[row] = differs ? (int32_t)__ffsll((long long)differs) - 1 : kWave;
 }
 
-// Scan mode.  One 256-thread workgroup per (problem, path): [append] -> match by
-// scan (Eq. 3) -> DAG (Eq. 5) -> greedy walk -> [accept].  With in.n > 0 the
-// launch also performs the step's append; every workgroup then reads the other
-// paths through `Paths`, which never touches cells written by this launch.
+// Lengths of the first kLenCache paths into LDS (the scan reads them per tile).
+// The caller synchronises the workgroup before using them.
+template <int BLOCK, class LDS>
+__device__ __forceinline__ void cache_lens(LDS& s, const Paths& y, int tid) {
+  for (int32_t j = tid; j < y.N && j < kLenCache; j += BLOCK) {
+    int32_t old_j = y.old_len(j);
+    s.len_old[j] = old_j;
+    s.len_new[j] = y.new_len(j, old_j);
+  }
+}
+
+// Scan mode.  One 1024-thread workgroup per (problem, path): [append] -> match
+// by scan (Eq. 3, or Eq. 4 with one edit) -> DAG (Eq. 5) -> greedy walk ->
+// [accept].  With in.n > 0 the launch also performs the step's append; every
+// workgroup then reads the other paths through `Paths`, which never touches
+// cells written by this launch.  The histories are read straight from memory:
+// the q + 1 tokens a position compares are shared with its neighbours in the
+// wave, so all but the first load of a line hit the CU's vector cache, and no
+// workgroup barrier is needed per tile as staging through LDS would.
+template <int LCAP>
 __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, StepIn in,
                                                                DraftArgs a) {
   constexpr int BLOCK = kScanBlock;
-  __shared__ Lds s;
+  __shared__ LdsScan s;
   int32_t row = xcd_row(ix.P * ix.N);
   if (row < 0) return;
   int32_t p;
   Ctx c = make_ctx(ix, in, row, p);
-  int32_t old_i = c.y.old_len(c.i);
-  c.len_i = c.y.new_len(c.i, old_i);
+  Head me = load_head(c.y, ix.kmax, c.i);               // length and newest tokens in one read
+  int32_t st_i = in.n == 1 ? c.y.st[c.i] : 0;
+  const int32_t old_i = me.old_len;
+  c.len_i = me.new_len;
+  cache_lens<BLOCK>(s, c.y, c.tid);
   if (in.n > 0) append_row<BLOCK, true>(ix, c.y, p, c.i, old_i, c.len_i, c.tid);
-  load_query(c, a.k, old_i);
+  if (in.n <= 1) {                                       // the query follows from what is loaded
+    int32_t cnt_i = c.len_i - old_i;
+    c.q = a.k < c.len_i ? a.k : c.len_i;
+#pragma unroll
+    for (int x = 0; x < CSD_MAX_QUERY_LEN; ++x) {
+      int32_t v = 0;
+      if (x < c.q) v = x < cnt_i ? st_i : pick(me.tail, x - cnt_i);
+      c.Q[x] = v;
+    }
+  } else {
+    load_query(c, a.k, old_i);
+  }
   if (c.tid == 0) s.n_match = 0;
   block_sync<BLOCK>();
 
   DraftOut o;
   const int32_t L = a.L;
   if (c.q > 0) {
-    ListSink sink{&s};
-    match_scan<BLOCK>(c, sink);
+    ListSink<LdsScan> sink{&s};
+    match_scan_any<BLOCK>(s, c, sink);
     block_sync<BLOCK>();
     int32_t M = s.n_match;
     if (M > 0) {
-      bool streaming = M > kMatchCap;
-      if (!streaming) {
+      // tier 1 when every layer's region is sure to hold its <= 2M keys; else layer by
+      // layer with one thread per match (M <= BLOCK); else streaming
+      bool done = false;
+      if (2u * (uint32_t)M <= tier1_geometry(M, L, LdsScan::kTable).region) {
         Tier1 t1 = build_dag<BLOCK>(s, c, M, L, WinInfo{M, 0}, a.alpha_q);
-        streaming = s.overflow != 0;
-        if (!streaming) walk_dag<BLOCK, 1>(s, c, t1, L, a.alpha_q, a.score_mode, o);
+        done = s.overflow == 0;
+        // every thread helps to score large tables; one wave then walks them without
+        // workgroup barriers (and it is wave 0 that writes the outputs)
+        const bool small = walk_fits_registers<LCAP>(t1, L);
+        if (done && !small) {
+          score_edges<BLOCK>(s, t1.region * (uint32_t)L, a.alpha_q, a.score_mode, c.tid);
+          block_sync<BLOCK>();
+        }
+        if (done && c.tid < kWave) {
+          if (small) walk_dag<kWave, LCAP>(s, c, t1, L, a.alpha_q, a.score_mode, o);
+          else walk_scored<kWave>(s, c, t1, L, o);
+        }
+      } else if (M <= BLOCK) {
+        walk_layers<BLOCK>(s, c, M, L, a.alpha_q, a.score_mode, o);
+        done = true;
       }
-      if (streaming)
+      if (!done)
         walk_streaming<BLOCK>(s, c, L, a.alpha_q, a.score_mode, ix.status, o, [&](auto f) {
-          if (M <= kMatchCap) {
+          if (M <= LdsScan::kMatch) {
             for (int32_t m = c.tid; m < M; m += BLOCK) f(s.match[m]);
           } else {
             FnSink<decltype(f)> fs{f};
-            match_scan<BLOCK>(c, fs);
+            match_scan_any<BLOCK>(s, c, fs);
           }
         });
     }
@@ -110,7 +155,7 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
 // and last the posting stores of the split-phase index insert.
 template <int LCAP>
 __global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn in, DraftArgs a) {
-  __shared__ Lds s;
+  __shared__ LdsWave s;
   int32_t row = xcd_row(ix.P * ix.N);
   if (row < 0) return;
   int32_t p;
@@ -125,7 +170,7 @@ __global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn i
 
   DraftOut o;
   if (M > 0) {
-    bool streaming = M > kMatchCap;
+    bool streaming = M > LdsWave::kMatch;
     if (!streaming) {
       Tier1 t1 = build_dag<kWave>(s, c, M, L, wi, a.alpha_q);
       streaming = s.overflow != 0;
@@ -133,12 +178,12 @@ __global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn i
     }
     if (streaming)
       walk_streaming<kWave>(s, c, L, a.alpha_q, a.score_mode, ix.status, o, [&](auto f) {
-        if (M <= kMatchCap) {
+        if (M <= LdsWave::kMatch) {
           for (int32_t m = c.tid; m < M; m += kWave) f(s.match[m]);
         } else {
           FnSink<decltype(f)> fs{f};
           if (c.q == c.kmax) match_index(c, fs);
-          else match_scan<kWave>(c, fs);
+          else match_scan<kWave, false>(s, c, fs);
         }
       });
   }
@@ -177,6 +222,7 @@ __global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ src
 __global__ __launch_bounds__(kScanBlock) void dump_match_bits_scan_kernel(IndexView ix, StepIn in,
                                                                           int32_t k, uint32_t* bits,
                                                                           int32_t words) {
+  __shared__ LdsScan s;
   int32_t row = xcd_row(ix.P * ix.N);
   if (row < 0) return;
   int32_t p;
@@ -184,16 +230,18 @@ __global__ __launch_bounds__(kScanBlock) void dump_match_bits_scan_kernel(IndexV
   int32_t old_i = c.y.old_len(c.i);
   c.len_i = old_i;
   load_query(c, k, old_i);
+  cache_lens<kScanBlock>(s, c.y, c.tid);
+  block_sync<kScanBlock>();
   if (c.q <= 0) return;
   BitmapSink sink{bits + (int64_t)row * words};
-  match_scan<kScanBlock>(c, sink);
+  match_scan_any<kScanBlock>(s, c, sink);
 }
 
 // Index mode: the matches as the step kernel's own front end finds them.
 __global__ __launch_bounds__(kWave) void dump_match_bits_wave_kernel(IndexView ix, StepIn in,
                                                                      int32_t k, uint32_t* bits,
                                                                      int32_t words) {
-  __shared__ Lds s;
+  __shared__ LdsWave s;
   int32_t row = xcd_row(ix.P * ix.N);
   if (row < 0) return;
   int32_t p;
@@ -204,12 +252,12 @@ __global__ __launch_bounds__(kWave) void dump_match_bits_wave_kernel(IndexView i
   int32_t M = wave_front_end<8>(s, c, ix, p, k, 1, wi, ticket, ticket_used);
   block_sync<kWave>();
   BitmapSink sink{bits + (int64_t)row * words};
-  if (M <= kMatchCap) {
+  if (M <= LdsWave::kMatch) {
     for (int32_t m = c.tid; m < M; m += kWave) sink.push(c.y, true, s.match[m]);
   } else if (c.q == c.kmax) {
     match_index(c, sink);
   } else if (c.q > 0) {
-    match_scan<kWave>(c, sink);
+    match_scan<kWave, false>(s, c, sink);
   }
 }
 
@@ -274,12 +322,13 @@ __global__ __launch_bounds__(64) void expand_bits_kernel(const uint32_t* bits, i
 }
 
 // Scan mode: builds the tier-1 DAG tables of a row exactly as step_scan_kernel
-// does and writes the edge entries, sorted by key, to tmp rows of kTableCap
-// entries.  counts[row] = number of edges, or -1 if the row needs tier 2.
+// does and writes the edge entries, sorted by key, to tmp rows of kDumpStride
+// entries.  counts[row] = number of edges, or -1 if the row's DAG does not fit
+// the table as a whole.
 __global__ __launch_bounds__(kScanBlock) void dump_edge_rows_scan_kernel(
     IndexView ix, StepIn in, int32_t k, int32_t L, u64* tmp_keys, u64* tmp_vals, int32_t* counts) {
   constexpr int BLOCK = kScanBlock;
-  __shared__ Lds s;
+  __shared__ LdsScan s;
   __shared__ int n_edges;
   int32_t row = xcd_row(ix.P * ix.N);
   if (row < 0) return;
@@ -288,19 +337,20 @@ __global__ __launch_bounds__(kScanBlock) void dump_edge_rows_scan_kernel(
   int32_t old_i = c.y.old_len(c.i);
   c.len_i = old_i;
   load_query(c, k, old_i);
+  cache_lens<BLOCK>(s, c.y, c.tid);
   if (c.tid == 0) { s.n_match = 0; n_edges = 0; }
   block_sync<BLOCK>();
   if (c.q <= 0) { if (c.tid == 0) counts[row] = 0; return; }
-  ListSink sink{&s};
-  match_scan<BLOCK>(c, sink);
+  ListSink<LdsScan> sink{&s};
+  match_scan_any<BLOCK>(s, c, sink);
   block_sync<BLOCK>();
   int32_t M = s.n_match;
   if (M == 0) { if (c.tid == 0) counts[row] = 0; return; }
-  if (M > kMatchCap) { if (c.tid == 0) counts[row] = -1; return; }
+  if (M > LdsScan::kMatch) { if (c.tid == 0) counts[row] = -1; return; }
   Tier1 t1 = build_dag<BLOCK>(s, c, M, L, WinInfo{M, 0}, 0u);
   if (s.overflow) { if (c.tid == 0) counts[row] = -1; return; }
   emit_sorted_edges<BLOCK>(s, t1.region * (uint32_t)L, c.tid, &n_edges,
-                           tmp_keys + (int64_t)row * kTableCap, tmp_vals + (int64_t)row * kTableCap);
+                           tmp_keys + (int64_t)row * kDumpStride, tmp_vals + (int64_t)row * kDumpStride);
   block_sync<BLOCK>();
   if (c.tid == 0) counts[row] = n_edges;
 }
@@ -311,7 +361,7 @@ __global__ __launch_bounds__(kWave) void dump_edge_rows_wave_kernel(IndexView ix
                                                                     int32_t k, int32_t L,
                                                                     u64* tmp_keys, u64* tmp_vals,
                                                                     int32_t* counts) {
-  __shared__ Lds s;
+  __shared__ LdsWave s;
   __shared__ int n_edges;
   int32_t row = xcd_row(ix.P * ix.N);
   if (row < 0) return;
@@ -324,11 +374,11 @@ __global__ __launch_bounds__(kWave) void dump_edge_rows_wave_kernel(IndexView ix
   int32_t M = wave_front_end<LCAP>(s, c, ix, p, k, L, wi, ticket, ticket_used);
   block_sync<kWave>();
   if (M == 0) { if (c.tid == 0) counts[row] = 0; return; }
-  if (M > kMatchCap) { if (c.tid == 0) counts[row] = -1; return; }
+  if (M > LdsWave::kMatch) { if (c.tid == 0) counts[row] = -1; return; }
   Tier1 t1 = build_dag<kWave>(s, c, M, L, wi, 0u);
   if (s.overflow) { if (c.tid == 0) counts[row] = -1; return; }
   emit_sorted_edges<kWave>(s, t1.region * (uint32_t)L, c.tid, &n_edges,
-                           tmp_keys + (int64_t)row * kTableCap, tmp_vals + (int64_t)row * kTableCap);
+                           tmp_keys + (int64_t)row * kDumpStride, tmp_vals + (int64_t)row * kDumpStride);
   block_sync<kWave>();
   if (c.tid == 0) counts[row] = n_edges;
 }
@@ -343,8 +393,8 @@ __global__ __launch_bounds__(256) void scatter_edges_kernel(const u64* tmp_keys,
   for (int32_t x = threadIdx.x; x < n; x += 256) {
     int64_t at = base + x;
     if (at >= cap) break;
-    u64 key = tmp_keys[(int64_t)row * kTableCap + x];
-    u64 val = tmp_vals[(int64_t)row * kTableCap + x];
+    u64 key = tmp_keys[(int64_t)row * kDumpStride + x];
+    u64 val = tmp_vals[(int64_t)row * kDumpStride + x];
     out_duv[3 * at] = (int32_t)(key >> 58);
     out_duv[3 * at + 1] = (int32_t)key_u(key);
     out_duv[3 * at + 2] = (int32_t)key_v(key);

@@ -16,13 +16,35 @@ __device__ __forceinline__ void load_query(Ctx& c, int32_t k, int32_t old_i) {
     c.Q[a] = (a < c.q) ? c.y.token(c.i, c.len_i - 1 - a, old_i) : 0;
 }
 
-// Does the q-gram that ends just before index e of path j equal the query?
-// All q tokens are fetched at once (one memory round trip, not q).
+// t[a] = the a-th token before index e of path j for a < min(want, e), else 0.
+// All loads are issued together (one memory round trip).  When the tokens of
+// every calling lane are history and exist (the rule, unless a path is very
+// short or the launch appends several tokens), they come from one address with
+// fixed offsets; otherwise each is located on its own.
+template <int NT>
+__device__ __forceinline__ void tokens_before(const Ctx& c, int32_t j, int32_t e, int32_t old_j,
+                                              int32_t want, int32_t (&t)[NT]) {
+  bool deep = e <= old_j && e >= NT;
+  if (__ballot(!deep) == 0) {
+    const int32_t* newest = c.y.tok + c.y.cell(j, e - 1);
+#pragma unroll
+    for (int a = 0; a < NT; ++a) t[a] = newest[-a];
+  } else {
+#pragma unroll
+    for (int a = 0; a < NT; ++a) {                         // every lane loads; unused ones read cell 0
+      bool has = a < want && a < e;
+      t[a] = c.y.token(has ? j : 0, has ? e - 1 - a : 0, has ? old_j : 1);
+    }
+  }
+#pragma unroll
+  for (int a = 0; a < NT; ++a) t[a] = (a < want && a < e) ? t[a] : 0;
+}
+
+// Does the q-gram that ends just before index e >= q of path j equal the query?
 __device__ __forceinline__ bool gram_equals_query(const Ctx& c, int32_t j, int32_t e,
                                                   int32_t old_j) {
   int32_t t[CSD_MAX_QUERY_LEN];
-#pragma unroll
-  for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) t[a] = (a < c.q) ? c.y.token(j, e - 1 - a, old_j) : 0;
+  tokens_before(c, j, e, old_j, c.q, t);
   bool hit = true;
 #pragma unroll
   for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) hit = hit && (a >= c.q || t[a] == c.Q[a]);
@@ -39,8 +61,7 @@ __device__ __forceinline__ bool gram_near_query(const Ctx& c, int32_t j, int32_t
   constexpr int K = CSD_MAX_QUERY_LEN;
   const int32_t q = c.q;
   int32_t t[K + 1];
-#pragma unroll
-  for (int a = 0; a <= K; ++a) t[a] = (a <= q && a < e) ? c.y.token(j, e - 1 - a, old_j) : 0;
+  tokens_before(c, j, e, old_j, q + 1, t);
   // pre[p]: t[a] == Q[a] for all a < p.  same/back/fwd[p]: the agreement of the older part
   // a > p (same, fwd) or a >= p (back) at shift 0 / +1 / -1, scanned from the oldest token.
   int32_t Q[K + 1];                                        // Q[K] only pads the unrolled loops
@@ -69,12 +90,6 @@ __device__ __forceinline__ bool gram_near_query(const Ctx& c, int32_t j, int32_t
   return hit;
 }
 
-// The match predicate of the scan: exact (Eq. 3) or within one edit (Eq. 4).
-__device__ __forceinline__ bool position_matches(const Ctx& c, int32_t j, int32_t e,
-                                                 int32_t old_j) {
-  return c.eps == 0 ? gram_equals_query(c, j, e, old_j) : gram_near_query(c, j, e, old_j);
-}
-
 __device__ __forceinline__ GramHash query_hash(const Ctx& c) {
   uint32_t acc = kGramSeed;
 #pragma unroll
@@ -87,8 +102,9 @@ __device__ __forceinline__ GramHash query_hash(const Ctx& c) {
 
 // Compacts hits into the LDS match list with one LDS atomic per wave.
 // push() must be reached by all 64 lanes of a wave together.
+template <class LDS>
 struct ListSink {
-  Lds* s;
+  LDS* s;
   __device__ __forceinline__ void push(const Paths&, bool hit, Match m) {
     u64 mask = __ballot(hit);
     if (mask == 0) return;
@@ -97,7 +113,7 @@ struct ListSink {
     if (lane == 0) base = atomicAdd(&s->n_match, (int)__popcll(mask));
     base = __builtin_amdgcn_readfirstlane(base);
     int slot = base + (int)__popcll(mask & ((1ull << lane) - 1ull));
-    if (hit && slot < kMatchCap) s->match[slot] = m;
+    if (hit && slot < LDS::kMatch) s->match[slot] = m;
   }
 };
 
@@ -122,37 +138,158 @@ struct FnSink {
 
 // ---------------------------------------------------------------- general matchers
 
-// Eq. 3 / Eq. 4 by exhaustive comparison: every position e of every other path
-// j with q - eps <= e <= len_j - 1 is tested.  Trip counts are uniform over the workgroup;
-// four tiles are in flight at a time.
-template <int BLOCK, class Sink>
-__device__ __forceinline__ void match_scan(const Ctx& c, Sink& sink) {
-  constexpr int kUnroll = 4;
-  const int32_t first_e = c.q > c.eps ? c.q - c.eps : 0;   // shortest substring that can match
-  int32_t tiles_per_path = (c.y.max_len + BLOCK - 1) / BLOCK;
-  int32_t tiles = c.y.N * tiles_per_path;
-  for (int32_t g0 = 0; g0 < tiles; g0 += kUnroll) {
-    bool hit[kUnroll];
-    Match m[kUnroll];
+// Lengths of path j: from the LDS cache for the first kLenCache paths.
+template <class LDS>
+__device__ __forceinline__ void lens_of(const LDS& s, const Paths& y, int32_t j, int32_t& old_j,
+                                        int32_t& new_j) {
+  if (j < kLenCache) {
+    old_j = s.len_old[j];
+    new_j = s.len_new[j];
+  } else {
+    old_j = y.old_len(j);
+    new_j = y.new_len(j, old_j);
+  }
+}
+
+// The scan's filter: can a position match at all, judged by the three newest
+// tokens before it (t[0] newest; all three exist)?
+//   Exact: they must equal the query's newest tokens; for q <= 3 that already
+//   is the answer.
+//   One edit, q >= 3: the edit touches at most one of the three newest query
+//   tokens, so two of them survive, in place or one place off.  The cases: no
+//   edit among the newest two (t0=Q0, t1=Q1); Q0 or Q1 substituted (t1=Q1,
+//   t2=Q2 / t0=Q0, t2=Q2); the text lacks Q0 or Q1 (t0=Q1, t1=Q2 / t0=Q0,
+//   t1=Q2); the text has an extra token before Q0 or between Q0 and Q1
+//   (t1=Q0, t2=Q1 / t0=Q0, t2=Q1).  Shorter queries get a weaker test or none.
+constexpr int kFilterTokens = 3;
+template <bool FUZZY>
+__device__ __forceinline__ bool may_match(const Ctx& c, const int32_t (&t)[kFilterTokens]) {
+  if (!FUZZY) {
+    bool ok = true;
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      int32_t g = g0 + u;
-      int32_t j = g / tiles_per_path;
-      int32_t e = first_e + (g - j * tiles_per_path) * BLOCK + c.tid;
-      hit[u] = false;
-      m[u] = Match{0, 0, 0};
-      if (g < tiles && j != c.i) {
-        int32_t old_j = c.y.old_len(j);
-        int32_t new_j = c.y.new_len(j, old_j);
-        if (e < new_j) {
-          hit[u] = position_matches(c, j, e, old_j);
-          m[u] = make_match(c.y, j, e, old_j, new_j);
-        }
+    for (int a = 0; a < kFilterTokens; ++a) ok = ok && (a >= c.q || t[a] == c.Q[a]);
+    return ok;
+  }
+  if (c.q < 2) return true;
+  if (c.q < 3) return t[0] == c.Q[0] || t[0] == c.Q[1] || t[1] == c.Q[0] || t[1] == c.Q[1];
+  bool c0 = t[0] == c.Q[0], c1 = t[1] == c.Q[1], c2 = t[2] == c.Q[2];
+  bool a01 = t[0] == c.Q[1], a12 = t[1] == c.Q[2], b10 = t[1] == c.Q[0], b21 = t[2] == c.Q[1];
+  return (c0 && (c1 || c2 || a12 || b21)) || (c1 && c2) || (a01 && a12) || (b10 && b21);
+}
+
+// Eq. 3 (FUZZY = false) or Eq. 4 with one edit (FUZZY = true) by exhaustive
+// comparison: every position e of every other path j with q - eps <= e <=
+// len_j - 1 is tested.  s.len_old / s.len_new hold the lengths of the first
+// kLenCache paths.
+//
+// A row's positions all pass through one CU, and what bounds the scan there is
+// instruction issue, so the common case is kept lean.  The paths are cut into
+// spans of 256 positions, dealt round-robin to the workgroup's waves; a lane
+// takes four consecutive positions and fetches the six tokens they look at
+// (three before the first .. the one before the last) with two 12-byte loads,
+// outside any branch; the loads of four spans travel together.  A position
+// with three history tokens before it is filtered on those; where the filter
+// does not settle the answer, and for the few positions it does not cover (the
+// first three of a path, which are only pre-filtered, and those that touch
+// tokens this launch appends), the full comparison runs once per round for the
+// lanes' next candidate, until no lane of the wave has one left.  Hits are pushed in no particular order; every wave
+// runs its own trip counts (push() is a wave-level operation).
+template <int BLOCK, bool FUZZY, class LDS, class Sink>
+__device__ __forceinline__ void match_scan(const LDS& s, const Ctx& c, Sink& sink) {
+  constexpr int kWaves = BLOCK / kWave;
+  constexpr int kPerLane = 4;                              // consecutive positions of a lane
+  constexpr int kSpan = kWave * kPerLane;                  // positions of a span
+  constexpr int kSpans = 4;                                // spans in flight: 16 candidate bits
+  const int lane = c.tid & 63, wave = c.tid >> 6;
+  const int32_t first_e = FUZZY ? (c.q > 1 ? c.q - 1 : 0) : c.q;   // shortest substring that can match
+  const int32_t spans_per_path = (c.y.max_len + kSpan - 1) / kSpan;
+  const int32_t spans = c.y.N * spans_per_path;            // < 2^24
+  const float inv_spp = 1.0f / (float)spans_per_path;
+  const bool filter_decides = !FUZZY && c.q <= kFilterTokens;
+  // span number g -> its path and the first position of this lane in it
+  auto locate = [&](int32_t g, int32_t& j, int32_t& e0) {
+    j = (int32_t)((float)g * inv_spp);                     // g / spans_per_path, fixed up below
+    j += (j + 1) * spans_per_path <= g;
+    j -= j * spans_per_path > g;
+    e0 = (g - j * spans_per_path) * kSpan + lane * kPerLane;
+  };
+  for (int32_t g0 = wave; g0 < spans; g0 += kWaves * kSpans) {
+    int32_t w[kSpans][2 * kFilterTokens];                  // tokens e0 - 3 .. e0 + 2 (first lane: 0 .. 5)
+    // bit 4u + r, for position r of span u: is a candidate / was filtered / lies among the
+    // first three of its path; bit u of firsts: this lane starts span u's path
+    uint32_t todo = 0, filtered = 0, early = 0, firsts = 0;
+#pragma unroll
+    for (int u = 0; u < kSpans; ++u) {
+      int32_t g = g0 + u * kWaves, j, e0, old_j = 0, new_j = 0;
+      locate(g, j, e0);
+      bool on = g < spans && j != c.i;                     // uniform over the wave
+      if (on) lens_of(s, c.y, j, old_j, new_j);
+      // the lane that starts a path has no three tokens before its positions: it reads the
+      // path's first six instead, which serve its fourth position and pre-filter the others
+      bool first = on && e0 == 0 && old_j >= kFilterTokens;
+      bool lane_ok = on && (first || (e0 >= kFilterTokens && e0 < new_j));
+      // lanes without filtered positions read the first six cells of path 0 (the token
+      // array is padded for that, and for the two cells a span may read past its path)
+      const int32_t* at = c.y.tok + (lane_ok ? c.y.cell(j, first ? kFilterTokens : e0) : kFilterTokens);
+#pragma unroll
+      for (int x = 0; x < 2 * kFilterTokens; ++x) w[u][x] = at[x - kFilterTokens];
+      firsts |= first ? (1u << u) : 0u;
+#pragma unroll
+      for (int r = 0; r < kPerLane; ++r) {
+        int32_t e = e0 + r;
+        bool live = on && e >= first_e && e < new_j;
+        bool lean = live && lane_ok && e >= kFilterTokens && e <= old_j;   // its three tokens are history
+        bool head = live && first && r < kFilterTokens;
+        filtered |= lean ? (1u << (4 * u + r)) : 0u;
+        early |= head ? (1u << (4 * u + r)) : 0u;
+        todo |= (live && !lean && !head) ? (1u << (4 * u + r)) : 0u;
       }
     }
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) sink.push(c.y, hit[u], m[u]);
+    for (int u = 0; u < kSpans; ++u) {
+      const bool fs = (firsts >> u & 1u) != 0;
+#pragma unroll
+      for (int r = 0; r < kPerLane; ++r) {
+        const uint32_t bit = 1u << (4 * u + r);
+        int32_t t[kFilterTokens] = {w[u][2 + r], w[u][1 + r], w[u][r]};   // newest first
+        if (r == kFilterTokens) {                          // position 3 of a first lane: tokens 2, 1, 0
+          t[0] = fs ? w[u][2] : t[0];
+          t[1] = fs ? w[u][1] : t[1];
+          t[2] = fs ? w[u][0] : t[2];
+        }
+        todo |= ((filtered & bit) && may_match<FUZZY>(c, t)) ? bit : 0u;
+        if (r < kFilterTokens) {                           // position r < 3 of a first lane: tokens r-1 .. 0
+          int32_t t0 = w[u][r >= 1 ? r - 1 : 0], t1 = w[u][r >= 2 ? r - 2 : 0];
+          bool pass = r == 0;
+          if (r >= 1) {
+            pass = t0 == c.Q[0];
+            if (FUZZY) pass = pass || c.q < 2 || t0 == c.Q[1] || (r >= 2 && (t1 == c.Q[0] || t1 == c.Q[1]));
+          }
+          todo |= ((early & bit) && pass) ? bit : 0u;
+        }
+      }
+    }
+    while (__ballot(todo != 0) != 0) {                     // uniform over the wave
+      bool have = todo != 0;
+      int32_t bit = have ? (int32_t)__ffs(todo) - 1 : 0;
+      todo &= todo - 1u;                                   // 0 stays 0
+      int32_t j, e, old_j = 1, new_j = 1;
+      locate(g0 + (bit >> 2) * kWaves, j, e);
+      e += bit & 3;
+      bool hit = have;
+      if (have) lens_of(s, c.y, j, old_j, new_j);
+      if (have && !(filter_decides && (filtered >> bit & 1u)))
+        hit = FUZZY ? gram_near_query(c, j, e, old_j) : gram_equals_query(c, j, e, old_j);
+      sink.push(c.y, hit, make_match(c.y, j, e, old_j, new_j));
+    }
   }
+}
+
+// The scan with the configured tolerance.
+template <int BLOCK, class LDS, class Sink>
+__device__ __forceinline__ void match_scan_any(const LDS& s, const Ctx& c, Sink& sink) {
+  if (c.eps == 0) match_scan<BLOCK, false>(s, c, sink);
+  else match_scan<BLOCK, true>(s, c, sink);
 }
 
 // Eq. 3 through the hash index, by ONE wave, in its general form (any number
@@ -245,31 +382,21 @@ __device__ __forceinline__ Head load_head(const Paths& y, int32_t kmax, int32_t 
   return h;
 }
 
-// Lengths of path j: from the LDS cache for the first kLenCache paths.
-__device__ __forceinline__ void lens_of(const Lds& s, const Paths& y, int32_t j, int32_t& old_j,
-                                        int32_t& new_j) {
-  if (j < kLenCache) {
-    old_j = s.len_old[j];
-    new_j = s.len_new[j];
-  } else {
-    old_j = y.old_len(j);
-    new_j = y.new_len(j, old_j);
-  }
-}
-
 // Appends the hits of all 64 lanes to the match list (one wave: the count lives
 // in a register).  Returns each hit's slot, -1 for lanes without one.
-__device__ __forceinline__ int32_t wave_push(Lds& s, int32_t& n_match, bool hit, Match m, int lane) {
+template <class LDS>
+__device__ __forceinline__ int32_t wave_push(LDS& s, int32_t& n_match, bool hit, Match m, int lane) {
   u64 mask = __ballot(hit);
   int32_t slot = n_match + (int32_t)__popcll(mask & ((1ull << lane) - 1ull));
   n_match += (int32_t)__popcll(mask);
   if (!hit) return -1;
-  if (slot < kMatchCap) s.match[slot] = m;
+  if (slot < LDS::kMatch) s.match[slot] = m;
   return slot;
 }
 
+template <class LDS>
 struct WaveListSink {           // match list of a one-wave row; push() by all 64 lanes together
-  Lds* s;
+  LDS* s;
   int32_t* n_match;
   int lane;
   __device__ __forceinline__ void push(const Paths&, bool hit, Match m) {
@@ -308,8 +435,8 @@ __device__ __forceinline__ void append_own_single(const IndexView& ix, const Pat
 // round trip as the verification.  `word` is the lane's word of the first batch
 // of 4 buckets, already requested.  Adds its hits behind the n_fresh matches
 // already listed; hit number x (0-based among these) gets window x.
-template <int LCAP>
-__device__ __forceinline__ void lookup_with_windows(Lds& s, const Ctx& c, int32_t L,
+template <int LCAP, class LDS>
+__device__ __forceinline__ void lookup_with_windows(LDS& s, const Ctx& c, int32_t L,
                                                     int32_t win_cap, int32_t n_fresh,
                                                     int32_t& n_match, GramHash gh, int32_t word) {
   const int lane = c.tid;
@@ -392,8 +519,8 @@ __device__ __forceinline__ void lookup_with_windows(Lds& s, const Ctx& c, int32_
 // append), matches among the newest positions, index lookup with windows.
 // Returns the number of matches; wi tells build_dag which of them have windows;
 // the ticket, if used, must be finished with insert_finish by the caller.
-template <int LCAP>
-__device__ __forceinline__ int32_t wave_front_end(Lds& s, Ctx& c, const IndexView& ix, int32_t p,
+template <int LCAP, class LDS>
+__device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexView& ix, int32_t p,
                                                   int32_t k, int32_t L, WinInfo& wi,
                                                   InsertTicket& ticket, bool& ticket_used) {
   const int lane = c.tid;
@@ -448,12 +575,12 @@ __device__ __forceinline__ int32_t wave_front_end(Lds& s, Ctx& c, const IndexVie
   }
   if (ticket_used) insert_claim(ticket, gram, c.bucket_mask, lane);   // round trip 3 starts
   wi.n_fresh = n_match;
-  wi.win_cap = use_index ? kWinWords / (2 * L) : 0;
+  wi.win_cap = use_index ? LDS::kWin / (2 * L) : 0;
   if (use_index) {
     lookup_with_windows<LCAP>(s, c, L, wi.win_cap, wi.n_fresh, n_match, gh, word);
   } else if (c.q > 0) {
-    WaveListSink sink{&s, &n_match, lane};
-    match_scan<kWave>(c, sink);                         // covers old and new positions alike
+    WaveListSink<LDS> sink{&s, &n_match, lane};
+    match_scan<kWave, false>(s, c, sink);               // covers old and new positions alike
     wi.n_fresh = n_match;
   }
   if (lane == 0) s.n_match = n_match;
