@@ -382,6 +382,10 @@ def test_fuzzy_small_cases(oracle):
         n = int(rng.integers(2, 5))
         cases.append(([rng.integers(0, 4, size=int(rng.integers(0, 20))).tolist() for _ in range(n)],
                       int(rng.integers(1, 5)), int(rng.integers(1, 6))))
+    for _ in range(40):      # longer paths over three symbols, queries up to the maximum length
+        n = int(rng.integers(2, 6))
+        cases.append(([rng.integers(0, 3, size=int(rng.integers(0, 48))).tolist() for _ in range(n)],
+                      int(rng.integers(1, 9)), int(rng.integers(1, 6))))
     for paths, k, L in cases:
         N, T = len(paths), max(1, max(len(p) for p in paths))
         tok = np.zeros((1, N, T), dtype=np.int32)
@@ -401,3 +405,22 @@ def test_fuzzy_small_cases(oracle):
         for i in range(N):
             assert np.array_equal(je[off[i]:off[i + 1]], oracle.matches(tok[0], cnt[0], i, k, 1)), (paths, k, i)
         assert ix.status() == 0
+
+
+def test_fuzzy_ragged_multi_token_steps(oracle):
+    """Steps that append 0..4 tokens per path: the scan then meets positions whose compared
+    tokens are partly history and partly this launch's input."""
+    w = synth.WORKLOADS["C1"]
+    tokens, probs = synth.make_paths(w)
+    steps = w.max_len // 2
+    counts = synth.make_ragged_counts(w, 4, steps)
+    want = None
+    for how in ("step", "calls"):
+        got = gpu_replay(tokens, probs, w.query_len, w.draft_len, steps=steps, counts=counts,
+                         n_per_step=4, how=how, max_edits=1)
+        assert got["status"] in (0, binding.STATUS_CAPACITY)
+        if want is None:
+            want = [oracle.draft_all(tokens, probs, got["lens"][t], w.query_len, w.draft_len, 1.0, 0, eps=1)
+                    for t in range(steps)]
+        for t in range(steps):
+            assert_step_equal(got, want[t], t, "fuzzy ragged %s" % how)
