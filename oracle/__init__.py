@@ -50,13 +50,14 @@ def _load():
         lib.oracle_draft.restype = ctypes.c_int32
         lib.oracle_draft.argtypes = [_i32p, _f32p, _i32p, ctypes.c_int32, ctypes.c_int32,
                                      ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
-                                     ctypes.c_uint32, ctypes.c_int32, _i32p, _f32p, _f32p]
+                                     ctypes.c_uint32, ctypes.c_int32, ctypes.c_int32, _i32p, _f32p, _f32p]
         lib.oracle_accept.restype = ctypes.c_int32
         lib.oracle_accept.argtypes = [_i32p, ctypes.c_int32, _i32p]
         lib.oracle_draft_all.restype = None
         lib.oracle_draft_all.argtypes = [_i32p, _f32p, _i32p, ctypes.c_int32, ctypes.c_int32,
                                          ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
-                                         ctypes.c_int32, ctypes.c_uint32, ctypes.c_int32, _i32p, _i32p, _f32p, _f32p,
+                                         ctypes.c_int32, ctypes.c_uint32, ctypes.c_int32, ctypes.c_int32,
+                                         _i32p, _i32p, _f32p, _f32p,
                                          _i32p, _i32p]
         _lib = lib
     return _lib
@@ -115,8 +116,9 @@ def edges(tok, prob, length, i, k, L, eps=0):
     return duv[:n].copy(), cs[:n].copy()
 
 
-def draft(tok, prob, length, i, k, L, alpha=1.0, score_mode=0, eps=0):
-    """Draft of path i for one problem -> (tokens [L], draft_len, token_scores [L], path_score)."""
+def draft(tok, prob, length, i, k, L, alpha=1.0, score_mode=0, eps=0, pool_mode=0):
+    """Draft of path i for one problem -> (tokens [L], draft_len, token_scores [L], path_score).
+    pool_mode: 0 = DAG (the method), 1 = prefix tree, 2 = list (the ablation's variants)."""
     tok, tp = _i32(tok)
     prob, pp = _f32(prob)
     length, lp = _i32(length)
@@ -126,7 +128,7 @@ def draft(tok, prob, length, i, k, L, alpha=1.0, score_mode=0, eps=0):
     ps = ctypes.c_float(0.0)
     lib = _load()
     n = lib.oracle_draft(tp, pp, lp, N, max_len, i, k, eps, L, lib.oracle_alpha_q(float(alpha)),
-                         score_mode, d.ctypes.data_as(_i32p), ts.ctypes.data_as(_f32p),
+                         score_mode, pool_mode, d.ctypes.data_as(_i32p), ts.ctypes.data_as(_f32p),
                          ctypes.byref(ps))
     return d, int(n), ts, np.float32(ps.value)
 
@@ -137,7 +139,7 @@ def accept(draft_tokens, draft_len, target) -> int:
     return int(_load().oracle_accept(dp, int(draft_len), tp))
 
 
-def draft_all(tok, prob, length, k, L, alpha=1.0, score_mode=0, target=None, eps=0):
+def draft_all(tok, prob, length, k, L, alpha=1.0, score_mode=0, target=None, eps=0, pool_mode=0):
     """All paths of all problems: tok [P][N][max_len], prob same or None, length [P][N].
 
     Returns dict(draft [P][N][L], draft_len [P][N], token_scores [P][N][L],
@@ -158,6 +160,6 @@ def draft_all(tok, prob, length, k, L, alpha=1.0, score_mode=0, target=None, eps
     else:
         tgp, al, alp = None, None, None
     lib.oracle_draft_all(tp, pp, lp, P, N, max_len, k, eps, L, lib.oracle_alpha_q(float(alpha)),
-                         score_mode, d.ctypes.data_as(_i32p), dl.ctypes.data_as(_i32p),
+                         score_mode, pool_mode, d.ctypes.data_as(_i32p), dl.ctypes.data_as(_i32p),
                          ts.ctypes.data_as(_f32p), ps.ctypes.data_as(_f32p), tgp, alp)
     return dict(draft=d, draft_len=dl, token_scores=ts, path_scores=ps, accept_len=al)

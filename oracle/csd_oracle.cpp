@@ -63,6 +63,19 @@
  *  R13 With eps > 0 the token before a match need not be the last query token,
  *      so the DAG's root is the query itself: the predecessor of EVERY
  *      layer-1 token is the last query token (for eps = 0 this is R9).
+ *  R14 Tree pool (pool_mode 1; the ablation's "tree", which the paper names
+ *      but does not define): the candidates' continuations form a prefix
+ *      tree — candidates share a node as long as ALL their tokens so far are
+ *      equal, not just the last one as in the DAG.  A child's weight is
+ *      Eq. 5's weight over the candidates that pass through it.  The draft
+ *      descends from the root to the heaviest child (ties: lowest token id)
+ *      until L tokens or a leaf.  score_mode does not apply.
+ *  R15 List pool (pool_mode 2; the ablation's "list"): the candidates are
+ *      not merged at all.  The draft is the continuation (at most L tokens)
+ *      of ONE candidate: the one whose tokens' weights — Eq. 5 with a single
+ *      instance each, alpha*p + (1-alpha)*1 — add up to the most; ties go to
+ *      the first candidate in (path, position) order.  token_score is each
+ *      token's own weight.  score_mode does not apply.
  *
  * Build: g++ -O2 -shared -fPIC -o libcsd_oracle.so csd_oracle.cpp
  */
@@ -234,23 +247,14 @@ int64_t oracle_edges(const int32_t* tok, const float* prob, const int32_t* len, 
   return n;
 }
 
-/* Draft of path i (Algorithm 1 as a whole).  draft[L] is padded with -1,
- * token_scores[L] with 0.  Returns the draft length. */
-int32_t oracle_draft(const int32_t* tok, const float* prob, const int32_t* len, int32_t N,
-                     int32_t max_len, int32_t i, int32_t k, int32_t eps, int32_t L, uint32_t alpha_q,
-                     int32_t score_mode, int32_t* draft, float* token_scores,
-                     float* path_score) {
-  for (int32_t d = 0; d < L; ++d) { draft[d] = -1; token_scores[d] = 0.0f; }
-  *path_score = 0.0f;
-  Paths Y{tok, prob, len, N, max_len};
-  int32_t q;
-  std::vector<Candidate> pool = candidate_pool(Y, i, k, eps, &q);
-  if (pool.empty()) return 0;
-  std::vector<EdgeTable> edges = build_dag(Y, pool, L, Y.token(i, Y.len[i] - 1));
+typedef std::vector<std::pair<int32_t, uint64_t> > Draft;   /* (token, key) per layer */
 
-  int32_t cur = Y.token(i, Y.len[i] - 1);        /* R9: root = last query token */
-  uint64_t key_sum = 0;
-  int32_t n = 0;
+/* The greedy extraction rule after Eq. 5 on the layered DAG (R8, R9, R13). */
+Draft draft_from_dag(const Paths& Y, const std::vector<Candidate>& pool, int32_t L, int32_t root,
+                     uint32_t alpha_q, int32_t score_mode) {
+  std::vector<EdgeTable> edges = build_dag(Y, pool, L, root);
+  Draft out;
+  int32_t cur = root;
   for (int32_t d = 1; d <= L; ++d) {
     const EdgeTable& E = edges[d - 1];
     /* node in-weights of this layer: sum over all predecessors u (R8) */
@@ -274,10 +278,96 @@ int32_t oracle_draft(const int32_t* tok, const float* prob, const int32_t* len, 
       }
     }
     if (!found) break;                           /* leaf, or the layer is empty */
-    draft[n] = best_v;
-    token_scores[n] = (float)((double)best_key / 4294967296.0);   /* R10 */
-    key_sum += best_key;
+    out.push_back(std::make_pair(best_v, best_key));
     cur = best_v;
+  }
+  return out;
+}
+
+/* R14: greedy descent of the candidates' prefix tree.  `here` holds the
+ * candidates that pass through the current tree node. */
+Draft draft_from_tree(const Paths& Y, const std::vector<Candidate>& pool, int32_t L,
+                      uint32_t alpha_q) {
+  Draft out;
+  std::vector<Candidate> here = pool;            /* the root: every candidate */
+  for (int32_t d = 1; d <= L; ++d) {
+    std::map<int32_t, Weight> child;             /* token -> weight of that child */
+    for (const Candidate& c : here) {
+      int32_t t = c.e + d - 1;
+      if (t >= Y.len[c.j]) continue;             /* this candidate has ended */
+      Weight& w = child[Y.token(c.j, t)];
+      w.C += 1;
+      w.S += Y.pq(c.j, t);
+    }
+    bool found = false;
+    int32_t best_v = 0;
+    uint64_t best_key = 0;
+    for (const auto& kv : child) {               /* ascending token id */
+      uint64_t key = weight_key(kv.second, alpha_q);
+      if (!found || key > best_key) {
+        found = true;
+        best_v = kv.first;
+        best_key = key;
+      }
+    }
+    if (!found) break;                           /* leaf */
+    out.push_back(std::make_pair(best_v, best_key));
+    std::vector<Candidate> below;
+    for (const Candidate& c : here)
+      if (c.e + d - 1 < Y.len[c.j] && Y.token(c.j, c.e + d - 1) == best_v) below.push_back(c);
+    here = below;
+  }
+  return out;
+}
+
+/* R15: the single heaviest candidate of the unmerged list. */
+Draft draft_from_list(const Paths& Y, const std::vector<Candidate>& pool, int32_t L,
+                      uint32_t alpha_q) {
+  bool found = false;
+  uint64_t best_total = 0;
+  Draft best;
+  for (const Candidate& c : pool) {              /* ascending (j, e) */
+    Draft mine;
+    uint64_t total = 0;
+    for (int32_t d = 1; d <= L && c.e + d - 1 < Y.len[c.j]; ++d) {
+      Weight w;
+      w.C = 1;
+      w.S = Y.pq(c.j, c.e + d - 1);
+      mine.push_back(std::make_pair(Y.token(c.j, c.e + d - 1), weight_key(w, alpha_q)));
+      total += weight_key(w, alpha_q);
+    }
+    if (!found || total > best_total) {          /* strict >: the first candidate wins ties */
+      found = true;
+      best_total = total;
+      best = mine;
+    }
+  }
+  return best;
+}
+
+/* Draft of path i (Algorithm 1 as a whole) from the pool organised as a DAG
+ * (pool_mode 0, the method), a prefix tree (1) or a list (2).  draft[L] is
+ * padded with -1, token_scores[L] with 0.  Returns the draft length. */
+int32_t oracle_draft(const int32_t* tok, const float* prob, const int32_t* len, int32_t N,
+                     int32_t max_len, int32_t i, int32_t k, int32_t eps, int32_t L, uint32_t alpha_q,
+                     int32_t score_mode, int32_t pool_mode, int32_t* draft, float* token_scores,
+                     float* path_score) {
+  for (int32_t d = 0; d < L; ++d) { draft[d] = -1; token_scores[d] = 0.0f; }
+  *path_score = 0.0f;
+  Paths Y{tok, prob, len, N, max_len};
+  int32_t q;
+  std::vector<Candidate> pool = candidate_pool(Y, i, k, eps, &q);
+  if (pool.empty()) return 0;
+  int32_t root = Y.token(i, Y.len[i] - 1);       /* R9: root = last query token */
+  Draft chosen = pool_mode == 1 ? draft_from_tree(Y, pool, L, alpha_q)
+               : pool_mode == 2 ? draft_from_list(Y, pool, L, alpha_q)
+                                : draft_from_dag(Y, pool, L, root, alpha_q, score_mode);
+  uint64_t key_sum = 0;
+  int32_t n = 0;
+  for (const auto& tk : chosen) {
+    draft[n] = tk.first;
+    token_scores[n] = (float)((double)tk.second / 4294967296.0);   /* R10 */
+    key_sum += tk.second;
     ++n;
   }
   *path_score = (float)((double)key_sum / 4294967296.0);
@@ -295,9 +385,9 @@ int32_t oracle_accept(const int32_t* draft, int32_t draft_len, const int32_t* ta
  * problem.  Arrays are [P][N][...]; target / accept_len may be null. */
 void oracle_draft_all(const int32_t* tok, const float* prob, const int32_t* len, int32_t P,
                       int32_t N, int32_t max_len, int32_t k, int32_t eps, int32_t L,
-                      uint32_t alpha_q, int32_t score_mode, int32_t* draft, int32_t* draft_len,
-                      float* token_scores, float* path_scores, const int32_t* target,
-                      int32_t* accept_len) {
+                      uint32_t alpha_q, int32_t score_mode, int32_t pool_mode, int32_t* draft,
+                      int32_t* draft_len, float* token_scores, float* path_scores,
+                      const int32_t* target, int32_t* accept_len) {
   for (int32_t p = 0; p < P; ++p) {
     const int32_t* tk = tok + (int64_t)p * N * max_len;
     const float* pr = prob ? prob + (int64_t)p * N * max_len : nullptr;
@@ -305,7 +395,7 @@ void oracle_draft_all(const int32_t* tok, const float* prob, const int32_t* len,
     for (int32_t i = 0; i < N; ++i) {
       int64_t r = (int64_t)p * N + i;
       draft_len[r] = oracle_draft(tk, pr, ln, N, max_len, i, k, eps, L, alpha_q, score_mode,
-                                  draft + r * L, token_scores + r * L, path_scores + r);
+                                  pool_mode, draft + r * L, token_scores + r * L, path_scores + r);
       if (target && accept_len)
         accept_len[r] = oracle_accept(draft + r * L, draft_len[r], target + r * L);
     }

@@ -114,3 +114,43 @@ def accept(draft_tokens, target):
             break
         a += 1
     return a
+
+
+def tree_draft(paths, probs, i, k, L, alpha=Fraction(1), eps=0):
+    """The ablation's tree pool: an explicit prefix tree (nested dicts) of the candidates'
+    continuations; each node carries [count, prob_sum] of the candidates through it; the draft
+    is the greedy descent to the heaviest child (ties: lowest token id)."""
+    alpha = Fraction(alpha)
+    root = {}                                   # token -> [count, prob_sum, children]
+    for seq in candidates(paths, probs, i, k, L, eps):
+        node = root
+        for (_, v, p) in seq:
+            entry = node.setdefault(v, [0, Fraction(0), {}])
+            entry[0] += 1
+            entry[1] += p
+            node = entry[2]
+    toks, scores = [], []
+    node = root
+    while node and len(toks) < L:
+        weight = {v: alpha * ent[1] + (1 - alpha) * ent[0] for v, ent in node.items()}
+        best = max(weight.values())
+        v_star = min(v for v in weight if weight[v] == best)
+        toks.append(v_star)
+        scores.append(best)
+        node = node[v_star][2]
+    return toks, scores
+
+
+def list_draft(paths, probs, i, k, L, alpha=Fraction(1), eps=0):
+    """The ablation's list pool: the continuation of the single candidate whose tokens'
+    weights (alpha * p + (1 - alpha) each) add up to the most; ties: first in (j, e) order."""
+    alpha = Fraction(alpha)
+    _, M = match_set(paths, i, k, eps)
+    best_key, best = None, ([], [])
+    for (j, e) in sorted(M):
+        toks = list(paths[j][e:e + L])
+        ws = [alpha * (Fraction(quant(probs[j][t]), 65536) if probs is not None else Fraction(1)) + (1 - alpha)
+              for t in range(e, e + len(toks))]
+        if best_key is None or sum(ws) > best_key:
+            best_key, best = sum(ws), (toks, ws)
+    return best

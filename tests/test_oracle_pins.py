@@ -378,3 +378,75 @@ def test_fuzzy_brute_force_tiny_inputs(oracle):
             assert d[:n].tolist() == toks and n == len(toks)
             assert ts[:n].tolist() == [float(np.float32(float(s))) for s in scores]
     assert n_more > 200
+
+
+# ---------------------------------------------------------------- tree and list pools (the ablation's variants)
+def test_pool_modes_hand_case(oracle):
+    # query (1, 2); continuations in the other paths: [5,6,7] twice, [5,8,9] once, [4,6,7] once.
+    paths = [[1, 2],
+             [1, 2, 5, 6, 7, 0, 1, 2, 5, 6, 7],
+             [1, 2, 5, 8, 9, 3, 3, 1, 2, 4, 6, 7]]
+    tok, _, ln = pack(paths)
+    dag = oracle.draft(tok, None, ln, 0, 2, 3, 1.0, 0, pool_mode=0)
+    tree = oracle.draft(tok, None, ln, 0, 2, 3, 1.0, 0, pool_mode=1)
+    lst = oracle.draft(tok, None, ln, 0, 2, 3, 1.0, 0, pool_mode=2)
+    # DAG: layer 1 {5: 3, 4: 1}; layer 2 after 5: 6 (in-weight 3, merging the 6 after 4); layer 3: 7 (3)
+    assert dag[0][:dag[1]].tolist() == [5, 6, 7] and dag[2][:3].tolist() == [3.0, 3.0, 3.0]
+    # tree: 5 (3 candidates) -> 6 (2 of them; the 6 after 4 is another branch) -> 7 (2)
+    assert tree[0][:tree[1]].tolist() == [5, 6, 7] and tree[2][:3].tolist() == [3.0, 2.0, 2.0]
+    # list: every candidate weighs 3 (three tokens of weight 1): the first one, path 1 at e = 2
+    assert lst[0][:lst[1]].tolist() == [5, 6, 7] and lst[2][:3].tolist() == [1.0, 1.0, 1.0]
+    assert float(lst[3]) == 3.0 and float(tree[3]) == 7.0 and float(dag[3]) == 9.0
+
+
+def test_pool_modes_differ_where_they_should(oracle):
+    # after query (1): candidates [2,3] x2 (paths 1, 2) and [4,3] x3 ... the DAG merges the 3s of layer 2
+    paths = [[1], [1, 2, 3], [1, 2, 3], [1, 4, 9], [1, 4, 9, 9], [1, 4, 8]]
+    tok, _, ln = pack(paths)
+    tree = oracle.draft(tok, None, ln, 0, 1, 2, 1.0, 0, pool_mode=1)
+    assert tree[0][:tree[1]].tolist() == [4, 9] and tree[2][:2].tolist() == [3.0, 2.0]
+    lst = oracle.draft(tok, None, ln, 0, 1, 3, 1.0, 0, pool_mode=2)
+    # the longest continuation wins under alpha = 1 without probabilities: path 4, [4, 9, 9]
+    assert lst[0][:lst[1]].tolist() == [4, 9, 9]
+    # with probabilities the list follows the most probable single candidate
+    probs = [[1.0], [1.0, 0.875, 0.875], [1.0, 0.5, 0.5], [1.0, 0.25, 0.25], [1.0, 0.25, 0.25, 0.25], [1.0, 0.5, 0.5]]
+    tok, pr, ln = pack(paths, probs)
+    lst = oracle.draft(tok, pr, ln, 0, 1, 3, 1.0, 0, pool_mode=2)
+    assert lst[0][:lst[1]].tolist() == [2, 3] and float(lst[3]) == 1.75
+
+
+def test_pool_modes_brute_force_tiny_inputs(oracle):
+    rng = np.random.default_rng(4242)
+    n_tree_differs = n_list_differs = 0
+    for case in range(600):
+        paths, probs = _random_case(rng)
+        use_probs = case % 2 == 0
+        k = int(rng.integers(1, 4))
+        L = int(rng.integers(1, 6))
+        eps = 1 if case % 4 == 0 else 0
+        alpha = Fraction(int(rng.integers(0, 5)), 4)
+        tok, pr, ln = pack(paths, probs if use_probs else None, max_len=26)
+        for i in range(len(paths)):
+            pp = probs if use_probs else None
+            dag = oracle.draft(tok, pr, ln, i, k, L, float(alpha), 1, eps, 0)
+            for mode, brute in ((1, bf.tree_draft), (2, bf.list_draft)):
+                toks, scores = brute(paths, pp, i, k, L, alpha, eps)
+                d, n, ts, ps = oracle.draft(tok, pr, ln, i, k, L, float(alpha), 0, eps, mode)
+                assert d[:n].tolist() == toks and (d[n:] == -1).all()
+                assert ts[:n].tolist() == [float(np.float32(float(s))) for s in scores]
+                assert float(ps) == float(np.float32(float(sum(scores, Fraction(0)))))
+                if mode == 1:
+                    n_tree_differs += d[:n].tolist() != dag[0][:dag[1]].tolist()
+                else:
+                    n_list_differs += d[:n].tolist() != dag[0][:dag[1]].tolist()
+            # a tree or list draft is the start of a real continuation; the first token of the
+            # tree is the DAG's first token (layer 1 is the same tally under edge scoring)
+            _, M = bf.match_set(paths, i, k, eps)
+            tree = oracle.draft(tok, pr, ln, i, k, L, float(alpha), 0, eps, 1)
+            lst = oracle.draft(tok, pr, ln, i, k, L, float(alpha), 0, eps, 2)
+            for d, n, _, _ in (tree, lst):
+                assert n == 0 or any(list(paths[j][e:e + n]) == d[:n].tolist() for (j, e) in M)
+            assert (tree[1] > 0) == (dag[1] > 0) == (lst[1] > 0) == (len(M) > 0)
+            if dag[1] > 0:
+                assert tree[0][0] == dag[0][0] and tree[2][0] == dag[2][0]
+    assert n_tree_differs > 20 and n_list_differs > 20
