@@ -57,6 +57,9 @@ def main():
     ap.add_argument("--max-edits", type=int, default=0,
                     help="edit tolerance of the suffix match (0 = exact, the headline; 1 = fuzzy, by scan)")
     ap.add_argument("--matcher", choices=("auto", "scan", "index"), default="auto")
+    ap.add_argument("--pool", choices=("dag", "tree", "list"), default="dag",
+                    help="organisation of the candidate pool (dag = the method, the headline; tree and "
+                         "list are the variants of the paper's ablation)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 64 MiB copy kernel (reference for traffic counters)")
@@ -83,7 +86,8 @@ def main():
     tg = np.stack([synth.make_targets(tokens, min(t + 1, T), L) for t in range(T)])
     d_tg = torch.from_numpy(tg).to(dev)
     ix = binding.Index(P, N, T, w.vocab, k, L, 1.0, 0, {"auto": 0, "scan": 1, "index": 2}[args.matcher],
-                       device=dev, max_edits=args.max_edits)
+                       device=dev, max_edits=args.max_edits,
+                       pool_mode={"dag": 0, "tree": 1, "list": 2}[args.pool])
     out = dict(tokens=torch.empty((P, N, L), dtype=torch.int32, device=dev),
                length=torch.empty((P, N), dtype=torch.int32, device=dev),
                token_scores=torch.empty((P, N, L), dtype=torch.float32, device=dev),
@@ -167,8 +171,9 @@ def main():
         "ms_per_step": dt / K * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "u64", "data": "synthetic",
         "config": {"workload": "%s: P=%d problems x N=%d paths x %d tokens, vocab %d, query %d, draft %d, "
-                               "probs supplied, alpha 1, max_edits %d; step = append 1 token/path + draft all "
-                               "paths + accept" % (w.name, P, N, T, w.vocab, k, L, args.max_edits)},
+                               "probs supplied, alpha 1, max_edits %d, pool %s; step = append 1 token/path + "
+                               "draft all paths + accept" % (w.name, P, N, T, w.vocab, k, L, args.max_edits,
+                                                             args.pool)},
         "us_per_step_mean_over_replay": dt / K * 1e6,
         "us_per_step_at_full_history": dt_tail / tail * 1e6,
         "us_per_step_three_launches": dt_unfused * 1e6,
@@ -189,7 +194,8 @@ def main():
             c0 = time.perf_counter()
             for t in range(T):
                 lens = np.full((P, N), t + 1, dtype=np.int32)
-                oracle.draft_all(tokens, probs, lens, k, L, 1.0, 0, tg[t], eps=args.max_edits)
+                oracle.draft_all(tokens, probs, lens, k, L, 1.0, 0, tg[t], eps=args.max_edits,
+                                 pool_mode={"dag": 0, "tree": 1, "list": 2}[args.pool])
             t_cpu += time.perf_counter() - c0
             n_done += T
             reps += 1

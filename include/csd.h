@@ -67,6 +67,10 @@ typedef enum {
 
 /* csd_config.flags: how matches are found (Eq. 3).  Both give identical results. */
 #define CSD_MATCH_AUTO 0   /* library picks                                         */
+#define CSD_POOL_DAG 0
+#define CSD_POOL_TREE 1
+#define CSD_POOL_LIST 2
+
 #define CSD_MATCH_SCAN 1   /* compare the query against every history position      */
 #define CSD_MATCH_INDEX 2  /* look the query up in the incremental n-gram hash index, which
                               holds grams of max_query_len tokens: set max_query_len to the
@@ -94,6 +98,16 @@ typedef struct {
                              path matches when some substring ending just before e is
                              within one edit of the query, each e counting once, and
                              matches are found by scan (CSD_MATCH_INDEX is refused).   */
+  int32_t pool_mode;      /* how the candidate pool is organised before the greedy
+                             extraction: CSD_POOL_DAG (the method: equal tokens of a layer
+                             are one node, Eq. 5), CSD_POOL_TREE (prefix tree: candidates
+                             share a node only while all their tokens so far are equal; a
+                             child's weight is Eq. 5's over the candidates through it) or
+                             CSD_POOL_LIST (no merging: the continuation of the single
+                             candidate whose tokens' weights alpha*p + (1-alpha) add up to
+                             the most, ties to the first in (path, position) order).
+                             TREE and LIST are the variants the paper's ablation compares
+                             the DAG with; score_mode does not apply to them.          */
 } csd_config;
 
 /* Size in bytes of the device workspace csd_create needs for this config. */

@@ -15,6 +15,7 @@ import torch
 from .build import LIBRARY, build_library
 
 MATCH_AUTO, MATCH_SCAN, MATCH_INDEX = 0, 1, 2
+POOL_DAG, POOL_TREE, POOL_LIST = 0, 1, 2
 STATUS_CAPACITY, STATUS_TOKEN_RANGE, STATUS_TABLE_FULL = 1, 2, 4
 OK, ERR_INVALID_ARG, ERR_CAPACITY, ERR_WORKSPACE, ERR_HIP, ERR_UNIMPLEMENTED = 0, -1, -2, -3, -4, -5
 
@@ -28,7 +29,8 @@ class Config(ctypes.Structure):
                 ("max_len", ctypes.c_int32), ("vocab", ctypes.c_int32),
                 ("max_query_len", ctypes.c_int32), ("max_draft_len", ctypes.c_int32),
                 ("alpha", ctypes.c_float), ("score_mode", ctypes.c_int32),
-                ("flags", ctypes.c_int32), ("max_edits", ctypes.c_int32)]
+                ("flags", ctypes.c_int32), ("max_edits", ctypes.c_int32),
+                ("pool_mode", ctypes.c_int32)]
 
 
 class CsdError(RuntimeError):
@@ -110,9 +112,10 @@ class Index:
     """The draft pool of P problems x N paths on the current device."""
 
     def __init__(self, n_problems, n_paths, max_len, vocab, max_query_len, max_draft_len,
-                 alpha=1.0, score_mode=0, flags=MATCH_AUTO, device="cuda", max_edits=0):
+                 alpha=1.0, score_mode=0, flags=MATCH_AUTO, device="cuda", max_edits=0,
+                 pool_mode=POOL_DAG):
         self.cfg = Config(n_problems, n_paths, max_len, vocab, max_query_len, max_draft_len,
-                          alpha, score_mode, flags, max_edits)
+                          alpha, score_mode, flags, max_edits, pool_mode)
         self.P, self.N = n_problems, n_paths
         self.rows = n_problems * n_paths
         self.device = torch.device(device)

@@ -76,6 +76,7 @@ int validate(const csd_config* c) {
   if ((int64_t)c->n_problems * c->n_paths > (1 << 24)) return CSD_ERR_INVALID_ARG;
   if (c->flags < 0 || c->flags > CSD_MATCH_INDEX) return CSD_ERR_UNIMPLEMENTED;
   if (c->max_edits < 0) return CSD_ERR_INVALID_ARG;
+  if (c->pool_mode < CSD_POOL_DAG || c->pool_mode > CSD_POOL_LIST) return CSD_ERR_INVALID_ARG;
   if (c->max_edits > 1) return CSD_ERR_UNIMPLEMENTED;
   if (c->max_edits == 1 && c->flags == CSD_MATCH_INDEX) return CSD_ERR_UNIMPLEMENTED;
   return CSD_OK;
@@ -149,18 +150,24 @@ int check_draft_args(const csd_index* h, int32_t query_len, int32_t draft_len) {
 void launch_draft(const csd_index* h, const IndexView& v, const StepIn& in, const DraftArgs& a,
                   hipStream_t st) {
   int64_t rows = (int64_t)v.P * v.N;
-  if (!h->indexed && a.L <= 8)
-    step_scan_kernel<8><<<xcd_grid(rows), kScanBlock, 0, st>>>(v, in, a);
+  const uint32_t grid = xcd_grid(rows);
+  if (a.pool_mode != CSD_POOL_DAG) {                    // tree and list pools: the general kernels
+    if (!h->indexed) step_scan_kernel<1, true><<<grid, kScanBlock, 0, st>>>(v, in, a);
+    else if (a.L <= 8) step_wave_kernel<8, true><<<grid, kWave, 0, st>>>(v, in, a);
+    else if (a.L <= 16) step_wave_kernel<16, true><<<grid, kWave, 0, st>>>(v, in, a);
+    else step_wave_kernel<32, true><<<grid, kWave, 0, st>>>(v, in, a);
+  } else if (!h->indexed && a.L <= 8)
+    step_scan_kernel<8, false><<<grid, kScanBlock, 0, st>>>(v, in, a);
   else if (!h->indexed && a.L <= 16)
-    step_scan_kernel<16><<<xcd_grid(rows), kScanBlock, 0, st>>>(v, in, a);
+    step_scan_kernel<16, false><<<grid, kScanBlock, 0, st>>>(v, in, a);
   else if (!h->indexed)     // longer drafts: the walk's register-resident fast path is left out
-    step_scan_kernel<1><<<xcd_grid(rows), kScanBlock, 0, st>>>(v, in, a);
+    step_scan_kernel<1, false><<<grid, kScanBlock, 0, st>>>(v, in, a);
   else if (a.L <= 8)
-    step_wave_kernel<8><<<xcd_grid(rows), kWave, 0, st>>>(v, in, a);
+    step_wave_kernel<8, false><<<grid, kWave, 0, st>>>(v, in, a);
   else if (a.L <= 16)
-    step_wave_kernel<16><<<xcd_grid(rows), kWave, 0, st>>>(v, in, a);
+    step_wave_kernel<16, false><<<grid, kWave, 0, st>>>(v, in, a);
   else
-    step_wave_kernel<32><<<xcd_grid(rows), kWave, 0, st>>>(v, in, a);
+    step_wave_kernel<32, false><<<grid, kWave, 0, st>>>(v, in, a);
 }
 
 // Host-side bookkeeping shared by csd_append and csd_step.
@@ -266,7 +273,8 @@ int csd_draft(csd_index* h, int32_t query_len, int32_t draft_len, int32_t* d_dra
   if (!h || !d_draft_tokens || !d_draft_len) return CSD_ERR_INVALID_ARG;
   int rc = check_draft_args(h, query_len, draft_len);
   if (rc != CSD_OK) return rc;
-  DraftArgs a{query_len, draft_len, h->alpha_q, h->cfg.score_mode, d_draft_tokens, d_draft_len,
+  DraftArgs a{query_len, draft_len, h->alpha_q, h->cfg.score_mode, h->cfg.pool_mode,
+              d_draft_tokens, d_draft_len,
               d_token_scores, d_path_scores, nullptr, nullptr};
   launch_draft(h, view_in_place(h), StepIn{nullptr, nullptr, nullptr, 0}, a, as_stream(stream));
   CSD_HIP(hipGetLastError());
@@ -296,7 +304,8 @@ int csd_step(csd_index* h, const int32_t* d_tokens, const float* d_probs, const 
   if (rc != CSD_OK) return rc;
   rc = note_append(h, d_counts != nullptr, n);
   if (rc != CSD_OK) return rc;
-  DraftArgs a{query_len, draft_len, h->alpha_q, h->cfg.score_mode, d_draft_tokens, d_draft_len,
+  DraftArgs a{query_len, draft_len, h->alpha_q, h->cfg.score_mode, h->cfg.pool_mode,
+              d_draft_tokens, d_draft_len,
               d_token_scores, d_path_scores, d_targets, d_accept_len};
   if (h->indexed && n != 1) {
     // the one-wave kernel fuses the append of ONE token per path; longer steps append first

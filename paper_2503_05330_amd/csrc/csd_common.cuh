@@ -222,6 +222,7 @@ struct LdsT {
   int32_t len_old[kLenCache];
   int32_t len_new[kLenCache];
   Cand red[2][WAVES];
+  int32_t chosen[CSD_MAX_DRAFT_LEN];   // the draft so far (tree pool)
   int n_match;                  // total matches found (may exceed MATCH)
   int overflow;                 // a DAG table region ran out of room
 };
@@ -248,6 +249,7 @@ struct DraftArgs {
   int32_t k, L;
   uint32_t alpha_q;
   int32_t score_mode;
+  int32_t pool_mode;            // CSD_POOL_*
   int32_t* draft_tokens;        // [P][N][L]
   int32_t* draft_len;           // [P][N]
   float* token_scores;          // [P][N][L] or null

@@ -365,6 +365,128 @@ __device__ __forceinline__ void walk_streaming(LDS& s, const Ctx& c, int32_t L, 
   }
 }
 
+// ---------------------------------------------------------------- tree and list pools
+//
+// The variants the paper's ablation compares the DAG with.  Both read the same
+// candidate pool.  `each_match(f)` calls f(Match, index in the LDS match list
+// or -1) for every match.
+
+// Token and quantised probability of the d-th continuation token (d >= 1) of a
+// match that reaches it: from the match's LDS window if it has one, else from memory.
+template <class LDS>
+__device__ __forceinline__ void continuation_at(const LDS& s, const Ctx& c, WinInfo wi, int32_t L,
+                                                int32_t mi, Match m, int32_t d, uint32_t& v,
+                                                uint32_t& p) {
+  int32_t ws = mi - wi.n_fresh;
+  if (mi >= 0 && ws >= 0 && ws < wi.win_cap) {
+    const int32_t* win = s.win + ws * 2 * L;
+    v = (uint32_t)win[d - 1];
+    p = (uint32_t)win[L + d - 1];
+  } else {
+    int32_t j = c.y.pos_path(m.pos), e = c.y.pos_index(m.pos);
+    int32_t old_j = e + (int32_t)m.rel_old;           // exact wherever it decides (see layer_instance)
+    v = (uint32_t)c.y.token(j, e + d - 1, old_j);
+    p = c.y.prob(j, e + d - 1, old_j);
+  }
+}
+
+// Prefix tree: candidates share a node only while ALL their tokens so far are
+// equal.  Greedy descent: at depth d the candidates that carry the draft so
+// far vote for their next token with Eq. 5's weight; the heaviest child wins
+// (ties: lowest token id).  Matches in the LDS list keep an "on the draft so
+// far" flag (in s.link, which only the DAG tiers use otherwise); matches that
+// are re-found instead of stored compare their whole prefix.  A layer that
+// does not fit the table is split into token classes, as in the streaming tier.
+template <int BLOCK, class LDS, class EachMatch>
+__device__ __forceinline__ void walk_tree(LDS& s, const Ctx& c, WinInfo wi, int32_t M, int32_t L,
+                                          uint32_t alpha_q, uint32_t* status, DraftOut& o,
+                                          EachMatch each_match) {
+  uint32_t size = 64;
+  while (size < 4u * (uint32_t)M && size < (uint32_t)LDS::kTable) size <<= 1;
+  const Region all{0u, size - 1u};
+  for (int32_t m = c.tid; m < M && m < LDS::kMatch; m += BLOCK) s.link[m] = 1;
+  int32_t cur = c.Q[0];                               // only labels the table keys of a depth
+  int class_bits = 0;
+  int parity = 0;
+  for (int32_t d = 1; d <= L; ++d) {
+    Cand best;
+    bool failed;
+    do {
+      failed = false;
+      best = cand_none();
+      uint32_t n_class = 1u << class_bits;
+      for (uint32_t r = 0; r < n_class && !failed; ++r) {
+        block_sync<BLOCK>();                           // previous readers are done; flags and chosen[] visible
+        table_clear<BLOCK>(s, size, c.tid);
+        block_sync<BLOCK>();
+        each_match([&](Match m, int32_t mi) {
+          if (s.overflow || d > (int32_t)m.rem_new) return;
+          uint32_t v, p, before = 0, unused;
+          continuation_at(s, c, wi, L, mi, m, d, v, p);
+          if (d >= 2) continuation_at(s, c, wi, L, mi, m, d - 1, before, unused);
+          bool on = d == 1 || before == (uint32_t)s.chosen[d - 2];
+          if (mi >= 0) {
+            on = on && s.link[mi] != 0;                // the flag covers depths 1 .. d-2
+            s.link[mi] = on ? 1 : 0;                   // now 1 .. d-1 (idempotent over classes)
+          } else {
+            for (int32_t x = 1; x + 1 < d && on; ++x) {
+              continuation_at(s, c, wi, L, mi, m, x, before, unused);
+              on = before == (uint32_t)s.chosen[x - 1];
+            }
+          }
+          if (!on || ((v * 0x9E3779B1u) >> 12 & (n_class - 1)) != r) return;
+          table_add(s, all, dag_key(d, (uint32_t)cur, v), pack_cs(1u, p));
+        });
+        block_sync<BLOCK>();
+        if (s.overflow) failed = true;                 // uniform: read after the barrier
+        else best = scan_successors<BLOCK>(s, all, d, cur, alpha_q, 1, c.tid, best);
+      }
+      if (failed) ++class_bits;
+    } while (failed && class_bits <= kMaxClassBits);
+    if (failed) {
+      if (c.tid == 0) atomicOr(status, CSD_STATUS_TABLE_FULL);
+      break;
+    }
+    parity ^= 1;
+    best = block_argmax<BLOCK>(s, best, c.tid, parity);
+    if (best.v == INT_MAX) break;                     // leaf: no candidate goes on
+    note_choice(o, best, d, c.tid);
+    if (c.tid == 0) s.chosen[d - 1] = best.v;
+    cur = best.v;
+  }
+}
+
+// List: no merging.  The draft is the continuation of the single candidate
+// whose tokens' weights (Eq. 5 with one instance each) add up to the most;
+// ties go to the first candidate in (path, position) order.
+template <int BLOCK, class LDS, class EachMatch>
+__device__ __forceinline__ void walk_list(LDS& s, const Ctx& c, WinInfo wi, int32_t L,
+                                          uint32_t alpha_q, DraftOut& o, EachMatch each_match) {
+  Cand best = cand_none();
+  each_match([&](Match m, int32_t mi) {
+    int32_t rem = (int32_t)m.rem_new < L ? (int32_t)m.rem_new : L;
+    u64 total = 0;
+#pragma unroll 4
+    for (int32_t d = 1; d <= rem; ++d) {
+      uint32_t v, p;
+      continuation_at(s, c, wi, L, mi, m, d, v, p);
+      total += weight_key(pack_cs(1u, p), alpha_q);
+    }
+    best = cand_best(best, Cand{total, m.pos});       // packed (path, index): ascending = (j, e) order
+  });
+  best = block_argmax<BLOCK>(s, best, c.tid, 0);
+  if (best.v == INT_MAX) return;
+  int32_t j = c.y.pos_path(best.v), e = c.y.pos_index(best.v), old_j, new_j;
+  lens_of(s, c.y, j, old_j, new_j);
+  int32_t rem = new_j - e < L ? new_j - e : L;
+  if (c.tid < rem) {
+    o.tok = c.y.token(j, e + c.tid, old_j);
+    o.key = weight_key(pack_cs(1u, c.y.prob(j, e + c.tid, old_j)), alpha_q);
+  }
+  o.key_sum = best.key;
+  o.n = rem;
+}
+
 // Writes the edge entries of a finished, unscored tier-1 table, sorted by key,
 // to ok / ov (debug dump).  Returns through *n_edges (an LDS counter).
 template <int BLOCK, class LDS>

@@ -73,7 +73,9 @@ __device__ __forceinline__ void cache_lens(LDS& s, const Paths& y, int tid) {
 // the q + 1 tokens a position compares are shared with its neighbours in the
 // wave, so all but the first load of a line hit the CU's vector cache, and no
 // workgroup barrier is needed per tile as staging through LDS would.
-template <int LCAP>
+// POOLS: also compiled for the tree and list pools (kept out of the DAG-only
+// kernels, whose code and register footprint they would enlarge).
+template <int LCAP, bool POOLS>
 __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, StepIn in,
                                                                DraftArgs a) {
   constexpr int BLOCK = kScanBlock;
@@ -110,7 +112,21 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
     match_scan_any<BLOCK>(s, c, sink);
     block_sync<BLOCK>();
     int32_t M = s.n_match;
-    if (M > 0) {
+    if (POOLS && M > 0 && a.pool_mode != CSD_POOL_DAG) {
+      auto each = [&](auto f) {
+        if (M <= LdsScan::kMatch) {
+          for (int32_t m = c.tid; m < M; m += BLOCK) f(s.match[m], m);
+        } else {
+          auto g = [&](Match found) { f(found, -1); };
+          FnSink<decltype(g)> fs{g};
+          match_scan_any<BLOCK>(s, c, fs);
+        }
+      };
+      if (a.pool_mode == CSD_POOL_TREE)
+        walk_tree<BLOCK>(s, c, WinInfo{M, 0}, M, L, a.alpha_q, ix.status, o, each);
+      else
+        walk_list<BLOCK>(s, c, WinInfo{M, 0}, L, a.alpha_q, o, each);
+    } else if (M > 0) {
       // tier 1 when every layer's region is sure to hold its <= 2M keys; else layer by
       // layer with one thread per match (M <= BLOCK); else streaming
       bool done = false;
@@ -153,7 +169,7 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
 // Index mode.  One wave64 per (problem, path): the front end (append, matches
 // with their continuations in LDS), DAG build, scoring, walk, outputs, accept,
 // and last the posting stores of the split-phase index insert.
-template <int LCAP>
+template <int LCAP, bool POOLS>
 __global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn in, DraftArgs a) {
   __shared__ LdsWave s;
   int32_t row = xcd_row(ix.P * ix.N);
@@ -169,7 +185,20 @@ __global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn i
   block_sync<kWave>();
 
   DraftOut o;
-  if (M > 0) {
+  if (POOLS && M > 0 && a.pool_mode != CSD_POOL_DAG) {
+    auto each = [&](auto f) {
+      if (M <= LdsWave::kMatch) {
+        for (int32_t m = c.tid; m < M; m += kWave) f(s.match[m], m);
+      } else {
+        auto g = [&](Match found) { f(found, -1); };
+        FnSink<decltype(g)> fs{g};
+        if (c.q == c.kmax) match_index(c, fs);
+        else match_scan<kWave, false>(s, c, fs);
+      }
+    };
+    if (a.pool_mode == CSD_POOL_TREE) walk_tree<kWave>(s, c, wi, M, L, a.alpha_q, ix.status, o, each);
+    else walk_list<kWave>(s, c, wi, L, a.alpha_q, o, each);
+  } else if (M > 0) {
     bool streaming = M > LdsWave::kMatch;
     if (!streaming) {
       Tier1 t1 = build_dag<kWave>(s, c, M, L, wi, a.alpha_q);

@@ -7,7 +7,7 @@ from paper_2503_05330_amd import binding
 
 
 def gpu_replay(tokens, probs, k, L, alpha=1.0, score_mode=0, flags=0, steps=None, targets=None,
-               counts=None, n_per_step=1, how="calls", max_edits=0):
+               counts=None, n_per_step=1, how="calls", max_edits=0, pool_mode=0):
     """Appends n_per_step tokens per path per step (or counts[t] of them) and drafts after
     every step.  Returns host arrays indexed by step, plus the final status bits.
     how: "calls"  = csd_append + csd_draft (+ csd_accept) per step,
@@ -18,7 +18,7 @@ def gpu_replay(tokens, probs, k, L, alpha=1.0, score_mode=0, flags=0, steps=None
     steps = steps if steps is not None else T // n_per_step
     dev = torch.device("cuda:0")
     ix = binding.Index(P, N, T, int(tokens.max()) + 1 if tokens.size else 1, k, L, alpha,
-                       score_mode, flags, device=dev, max_edits=max_edits)
+                       score_mode, flags, device=dev, max_edits=max_edits, pool_mode=pool_mode)
     out_tok = torch.empty((steps, P, N, L), dtype=torch.int32, device=dev)
     out_len = torch.empty((steps, P, N), dtype=torch.int32, device=dev)
     out_ts = torch.empty((steps, P, N, L), dtype=torch.float32, device=dev)

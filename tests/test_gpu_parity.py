@@ -157,13 +157,15 @@ def test_query_len_longer_and_shorter_than_history(oracle):
                 assert_step_equal(got, want, 0, "flags=%d k=%d L=%d" % (flags, k, L))
 
 
-def _one_shot(oracle, paths, probs, k, L, alpha=1.0, mode=0, flags=None, fused=False):
+def _one_shot(oracle, paths, probs, k, L, alpha=1.0, mode=0, flags=None, fused=False, pool_mode=0, eps=0):
     """Appends whole (possibly ragged) paths in one call and compares one draft; by default
     under both matchers (returns the last index)."""
     if flags is None:
         for f in (SCAN, INDEX):
             for fu in (False, True):
-                res = _one_shot(oracle, paths, probs, k, L, alpha, mode, f, fu)
+                if eps and f == INDEX:
+                    continue                    # fuzzy matching is found by scan
+                res = _one_shot(oracle, paths, probs, k, L, alpha, mode, f, fu, pool_mode, eps)
         return res
     N = len(paths)
     T = max(len(p) for p in paths)
@@ -176,7 +178,8 @@ def _one_shot(oracle, paths, probs, k, L, alpha=1.0, mode=0, flags=None, fused=F
         if probs is not None:
             pr[0, j, :len(p)] = probs[j]
     dev = torch.device("cuda:0")
-    ix = binding.Index(1, N, T, int(tok.max()) + 1, max(k, 1), L, alpha, mode, flags, device=dev)
+    ix = binding.Index(1, N, T, int(tok.max()) + 1, max(k, 1), L, alpha, mode, flags, device=dev,
+                       max_edits=eps, pool_mode=pool_mode)
     d_tok, d_pr, d_cnt = (torch.from_numpy(tok).to(dev), None if pr is None else torch.from_numpy(pr).to(dev),
                           torch.from_numpy(cnt).to(dev))
     if fused:      # the whole history arrives in the very step that drafts from it
@@ -184,7 +187,7 @@ def _one_shot(oracle, paths, probs, k, L, alpha=1.0, mode=0, flags=None, fused=F
     else:
         ix.append(d_tok, d_pr, d_cnt, T)
         out = ix.draft(k, L)
-    want = oracle.draft_all(tok, pr, cnt, k, L, alpha, mode)
+    want = oracle.draft_all(tok, pr, cnt, k, L, alpha, mode, eps=eps, pool_mode=pool_mode)
     got = dict(draft=out["tokens"].cpu().numpy()[None], draft_len=out["length"].cpu().numpy()[None],
                token_scores=out["token_scores"].cpu().numpy()[None],
                path_scores=out["path_scores"].cpu().numpy()[None])
@@ -424,3 +427,52 @@ def test_fuzzy_ragged_multi_token_steps(oracle):
                     for t in range(steps)]
         for t in range(steps):
             assert_step_equal(got, want[t], t, "fuzzy ragged %s" % how)
+
+
+# ---------------------------------------------------------------- tree and list pools (the ablation's variants)
+@pytest.mark.parametrize("pool_mode", [binding.POOL_TREE, binding.POOL_LIST])
+def test_pool_modes_replay(oracle, pool_mode):
+    for name, every, variants in (("C1", 1, ((INDEX, "replay"), (SCAN, "step"), (INDEX, "calls"))),
+                                  ("C2", 8, ((INDEX, "replay"), (SCAN, "replay")))):
+        w = synth.WORKLOADS[name]
+        tokens, probs = synth.make_paths(w)
+        T, k, L = w.max_len, w.query_len, w.draft_len
+        targets = np.stack([synth.make_noisy_targets(w, tokens, t + 1, L) for t in range(T)])
+        steps = sorted(set(list(range(0, T, every)) + [T - 1]))
+        for alpha, use_probs in ((1.0, True), (0.5, True), (1.0, False)):
+            pr = probs if use_probs else None
+            want = {t: oracle.draft_all(tokens, pr, np.full(tokens.shape[:2], t + 1, dtype=np.int32), k, L,
+                                        alpha, 0, targets[t], pool_mode=pool_mode) for t in steps}
+            if name == "C2":      # with enough candidates the pool structures give different drafts
+                dag = {t: oracle.draft_all(tokens, pr, np.full(tokens.shape[:2], t + 1, dtype=np.int32), k, L,
+                                           alpha, 0) for t in steps}
+                assert sum(not np.array_equal(dag[t]["draft"], want[t]["draft"]) for t in dag) >= 5
+            for flags, how in variants:
+                print("pool", pool_mode, name, "alpha", alpha, "probs", use_probs, flags, how, flush=True)
+                got = gpu_replay(tokens, pr, k, L, alpha, 0, flags, targets=targets, how=how,
+                                 pool_mode=pool_mode)
+                assert got["status"] == 0
+                for t in steps:
+                    assert_step_equal(got, want[t], t, "pool %d %s %d %s" % (pool_mode, name, flags, how))
+
+
+@pytest.mark.parametrize("pool_mode", [binding.POOL_TREE, binding.POOL_LIST])
+def test_pool_modes_small_and_degenerate_cases(oracle, pool_mode):
+    rng = np.random.default_rng(99 + pool_mode)
+    for _ in range(40):
+        n = int(rng.integers(2, 6))
+        paths = [rng.integers(0, 4, size=int(rng.integers(0, 40))).tolist() for _ in range(n)]
+        probs = [(rng.integers(1, 9, size=len(p)) / 8.0).tolist() for p in paths]
+        k, L = int(rng.integers(1, 5)), int(rng.integers(1, 9))
+        _one_shot(oracle, paths, probs, k, L, float(rng.integers(0, 5)) / 4, 0, pool_mode=pool_mode,
+                  eps=int(rng.integers(0, 2)))
+    # more matches than the on-chip list holds: candidates are re-found and compare whole prefixes
+    _one_shot(oracle, [[5] * 700] * 4, None, 3, 8, pool_mode=pool_mode)
+    # a frequent query token followed by random continuations: one depth of the tree holds
+    # thousands of distinct children
+    body = [np.random.default_rng(j).integers(10, 4000, size=(500, 6)) for j in range(5)]
+    for b in body:
+        b[:, 0] = 7
+    paths = [b.reshape(-1).tolist() for b in body]
+    paths[0] = paths[0][:-5]
+    _one_shot(oracle, paths, None, 1, 6, pool_mode=pool_mode)
