@@ -59,6 +59,11 @@ def _load():
                                          ctypes.c_int32, ctypes.c_uint32, ctypes.c_int32, ctypes.c_int32,
                                          _i32p, _i32p, _f32p, _f32p,
                                          _i32p, _i32p]
+        lib.oracle_accept_loop.restype = None
+        lib.oracle_accept_loop.argtypes = [_i32p, _f32p, _i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                           ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_uint32,
+                                           ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _i32p, _i32p,
+                                           _i32p, _i32p]
         _lib = lib
     return _lib
 
@@ -163,3 +168,24 @@ def draft_all(tok, prob, length, k, L, alpha=1.0, score_mode=0, target=None, eps
                          score_mode, pool_mode, d.ctypes.data_as(_i32p), dl.ctypes.data_as(_i32p),
                          ts.ctypes.data_as(_f32p), ps.ctypes.data_as(_f32p), tgp, alp)
     return dict(draft=d, draft_len=dl, token_scores=ts, path_scores=ps, accept_len=al)
+
+
+def accept_loop(future_tok, future_prob, length, k, L, n_steps, alpha=1.0, score_mode=0, eps=0, pool_mode=0):
+    """The propose / verify / accept loop with every path's own future standing in for the
+    model.  future_tok [P][N][max_len], length [P][N] = lengths on entry.  Returns dict(draft
+    [S][P][N][L], draft_len, accept_len, path_len [S][P][N], final_len [P][N])."""
+    tok, tp = _i32(future_tok)
+    prob, pp = _f32(future_prob)
+    length = np.array(length, dtype=np.int32, copy=True, order="C")
+    P, N, max_len = tok.shape
+    assert L <= 64
+    d = np.empty((n_steps, P, N, L), dtype=np.int32)
+    dl = np.empty((n_steps, P, N), dtype=np.int32)
+    al = np.empty((n_steps, P, N), dtype=np.int32)
+    pl = np.empty((n_steps, P, N), dtype=np.int32)
+    lib = _load()
+    lib.oracle_accept_loop(tp, pp, length.ctypes.data_as(_i32p), P, N, max_len, k, eps, L,
+                           lib.oracle_alpha_q(float(alpha)), score_mode, pool_mode, n_steps,
+                           d.ctypes.data_as(_i32p), dl.ctypes.data_as(_i32p), al.ctypes.data_as(_i32p),
+                           pl.ctypes.data_as(_i32p))
+    return dict(draft=d, draft_len=dl, accept_len=al, path_len=pl, final_len=length)

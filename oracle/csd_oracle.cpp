@@ -402,4 +402,47 @@ void oracle_draft_all(const int32_t* tok, const float* prob, const int32_t* len,
   }
 }
 
+/* The propose / verify / accept loop of speculative decoding (Background
+ * section; "Draft acceptance") around the draft construction, with a stand-in
+ * for the model: what the model samples for path i is that path's own future,
+ * future_tok[p][i][...].  Every step, every path first appends the tokens the
+ * previous step settled — the accepted draft tokens plus the one token the
+ * model emits itself (1 token at the first step), clipped at max_len — then
+ * drafts from the pool of all paths, and its draft is checked against its
+ * next L future tokens (-1 beyond the end never matches).  len [P][N] holds the
+ * lengths on entry and on exit; outputs are [n_steps][P][N][...]. */
+void oracle_accept_loop(const int32_t* future_tok, const float* future_prob, int32_t* len, int32_t P,
+                        int32_t N, int32_t max_len, int32_t k, int32_t eps, int32_t L,
+                        uint32_t alpha_q, int32_t score_mode, int32_t pool_mode, int32_t n_steps,
+                        int32_t* draft, int32_t* draft_len, int32_t* accept_len,
+                        int32_t* path_len) {
+  int64_t rows = (int64_t)P * N;
+  std::vector<int32_t> settled(rows, 0);          /* accept length of the previous step */
+  std::vector<int32_t> target(L > 0 ? L : 0);
+  for (int32_t s = 0; s < n_steps; ++s) {
+    for (int64_t r = 0; r < rows; ++r) {          /* append phase: all paths */
+      int32_t grow = settled[r] + 1;
+      if (grow > max_len - len[r]) grow = max_len - len[r];
+      len[r] += grow;
+      path_len[s * rows + r] = len[r];
+    }
+    for (int32_t p = 0; p < P; ++p) {             /* draft + acceptance phase */
+      const int32_t* tk = future_tok + (int64_t)p * N * max_len;
+      const float* pr = future_prob ? future_prob + (int64_t)p * N * max_len : nullptr;
+      const int32_t* ln = len + (int64_t)p * N;
+      for (int32_t i = 0; i < N; ++i) {
+        int64_t r = (int64_t)p * N + i;
+        int64_t o = s * rows + r;
+        float unused_scores[64], unused_total;
+        draft_len[o] = oracle_draft(tk, pr, ln, N, max_len, i, k, eps, L, alpha_q, score_mode,
+                                    pool_mode, draft + o * L, unused_scores, &unused_total);
+        for (int32_t d = 0; d < L; ++d)
+          target[d] = ln[i] + d < max_len ? tk[(int64_t)i * max_len + ln[i] + d] : -1;
+        accept_len[o] = oracle_accept(draft + o * L, draft_len[o], target.data());
+        settled[r] = accept_len[o];
+      }
+    }
+  }
+}
+
 }  /* extern "C" */

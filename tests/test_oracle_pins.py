@@ -450,3 +450,62 @@ def test_pool_modes_brute_force_tiny_inputs(oracle):
             if dag[1] > 0:
                 assert tree[0][0] == dag[0][0] and tree[2][0] == dag[2][0]
     assert n_tree_differs > 20 and n_list_differs > 20
+
+
+# ---------------------------------------------------------------- the propose / verify / accept loop
+def test_accept_loop_closed_forms(oracle):
+    T, N, k, L = 60, 4, 3, 5
+    seq = np.arange(100, 100 + T, dtype=np.int32)           # no repeated q-gram
+    tok = np.tile(seq, (1, N, 1))
+    # (a) identical paths in lockstep: the suffix sits at the END of every other path, so it
+    # has no successor there: no match, nothing accepted, one token per step
+    r = oracle.accept_loop(tok, None, np.zeros((1, N), np.int32), k, L, 20)
+    assert (r["draft_len"] == 0).all() and (r["accept_len"] == 0).all()
+    assert (r["path_len"][:, 0, :] == (np.arange(20) + 1)[:, None]).all()
+    # (b) the other paths are complete: path 0 drafts its own future and all of it is accepted
+    lens = np.array([[k, T, T, T]], np.int32)
+    r = oracle.accept_loop(tok, None, lens, k, L, 12)
+    want_len, settled = k, 0
+    for s in range(12):
+        want_len = min(T, want_len + settled + 1)
+        assert r["path_len"][s, 0, 0] == want_len and (r["path_len"][s, 0, 1:] == T).all()
+        settled = min(L, T - want_len)
+        assert r["accept_len"][s, 0, 0] == settled == r["draft_len"][s, 0, 0]
+        assert r["draft"][s, 0, 0, :settled].tolist() == seq[want_len:want_len + settled].tolist()
+    assert r["final_len"][0, 0] == T
+
+
+def test_accept_loop_is_the_composition_of_its_steps(oracle):
+    w = synth.WORKLOADS["C1"]
+    tokens, probs = synth.make_paths(w)
+    k, L, S = w.query_len, w.draft_len, 90
+    for eps, pool_mode in ((0, 0), (1, 0), (0, 1), (0, 2)):
+        r = oracle.accept_loop(tokens, probs, np.zeros(tokens.shape[:2], np.int32), k, L, S, eps=eps,
+                               pool_mode=pool_mode)
+        prev_len = np.zeros(tokens.shape[:2], np.int64)
+        prev_acc = np.zeros(tokens.shape[:2], np.int64)
+        for s in range(S):
+            lens = np.minimum(prev_len + prev_acc + 1, w.max_len)
+            assert np.array_equal(r["path_len"][s], lens)
+            step = oracle.draft_all(tokens, probs, lens.astype(np.int32), k, L, eps=eps, pool_mode=pool_mode)
+            assert np.array_equal(step["draft"], r["draft"][s]) and np.array_equal(step["draft_len"], r["draft_len"][s])
+            for i in range(w.n_paths):
+                future = tokens[0, i, lens[0, i]:lens[0, i] + L].tolist()
+                n = int(step["draft_len"][0, i])
+                assert r["accept_len"][s, 0, i] == bf.accept(step["draft"][0, i, :n].tolist(), future)
+            prev_len, prev_acc = lens, r["accept_len"][s].astype(np.int64)
+        assert r["accept_len"].sum() > 0 and r["path_len"][-1].max() > r["path_len"][-1].min() > S - 1
+
+
+def test_accept_length_grows_with_the_number_of_paths(oracle):
+    """The paper's qualitative finding (sample-size analysis): more parallel paths give longer
+    accepted drafts.  On the synthetic pool of C2 the mean accept length per step rises
+    monotonically from N = 2 to 16."""
+    w = synth.WORKLOADS["C2"]
+    tokens, probs = synth.make_paths(w)
+    mean = {}
+    for N in (2, 4, 8, 16):
+        r = oracle.accept_loop(tokens[:, :N], probs[:, :N], np.zeros((1, N), np.int32), w.query_len,
+                               w.draft_len, 400)
+        mean[N] = r["accept_len"].mean()
+    assert mean[2] < mean[4] < mean[8] < mean[16] and mean[16] > 3 * mean[2]
