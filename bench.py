@@ -153,6 +153,24 @@ def main():
     torch.cuda.synchronize()
     dt_tail = time.perf_counter() - t1
 
+    # the propose / verify / accept loop with each path's own future as the model: paths accept
+    # different numbers of tokens, so their lengths diverge and steps append several tokens
+    d_future_tok = torch.from_numpy(tokens).to(dev)
+    d_future_pr = torch.from_numpy(probs).to(dev)
+    loop_steps = T
+    ix.reset()
+    loop = ix.accept_loop(loop_steps, d_future_tok, d_future_pr, k, L)       # warm-up
+    torch.cuda.synchronize()
+    ix.reset()
+    t1 = time.perf_counter()
+    loop = ix.accept_loop(loop_steps, d_future_tok, d_future_pr, k, L, out=loop)
+    torch.cuda.synchronize()
+    dt_loop = time.perf_counter() - t1
+    path_len = loop["path_len"].cpu().numpy().reshape(loop_steps, -1)
+    growing = np.concatenate([np.ones((1, path_len.shape[1]), bool), path_len[:-1] < T])
+    steps_to_finish = int(growing.any(axis=1).sum())
+    accept_mean = float(loop["accept"].cpu().numpy().reshape(loop_steps, -1)[growing].mean())
+
     # measured match counts (untimed, through the debug dump) -> algorithmic bytes
     ix.reset()
     m_total, m_samples = 0, 0
@@ -178,6 +196,10 @@ def main():
         "us_per_step_at_full_history": dt_tail / tail * 1e6,
         "us_per_step_three_launches": dt_unfused * 1e6,
         "us_per_step_python_per_call": dt_python * 1e6,
+        "accept_loop": {"us_per_step": dt_loop / loop_steps * 1e6, "steps_until_all_paths_full": steps_to_finish,
+                        "mean_accept_len_while_growing": accept_mean,
+                        "note": "csd_accept_loop: draft -> accept against the path's own future -> append "
+                                "accepted + 1; synthetic stand-in for the model"},
         "matches_per_step": matches_per_step,
         "algorithmic_bytes_per_step": b_step,
         "roofline": {"bound": "hbm", "kernel": "csd::step_wave_kernel (one launch per step: append+draft+accept)",

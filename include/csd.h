@@ -185,6 +185,30 @@ int csd_replay(csd_index* index, int32_t n_steps, const int32_t* d_tokens, const
                int32_t* d_draft_len, float* d_token_scores, float* d_path_scores,
                const int32_t* d_targets, int32_t* d_accept_len, int32_t fused, void* stream);
 
+/* The propose / verify / accept loop of speculative decoding (Background
+ * section: the draft is verified and the longest correct prefix kept; "Draft
+ * acceptance") around the draft construction, with a stand-in for the model:
+ * what the model samples for a path is that path's own future,
+ * d_future_tokens [P][N][max_len] (d_future_probs likewise, may be NULL).
+ * Starting from the index's current state, every step (i) appends to every
+ * path the tokens the previous step settled — its accept length plus the one
+ * token the model emits itself; 1 token at the first step — clipped at max_len,
+ * (ii) drafts for every path from the pool of all paths, (iii) checks each draft
+ * against the path's next draft_len future tokens.  Path lengths diverge as
+ * paths accept different numbers of tokens.  A host loop inside the library:
+ * per step one small kernel that gathers the step's input and csd_step with
+ * draft_len + 1 tokens per path and counts.
+ *   d_scratch: device memory, 4-byte aligned, scratch_bytes >=
+ *     P*N*(3*draft_len + 3)*4 (step tokens, probabilities, targets, counts);
+ *   d_draft_tokens [n_steps][P][N][draft_len], d_draft_len, d_accept_len and
+ *   d_path_len (lengths after the step's append) [n_steps][P][N].
+ * Errors: CSD_ERR_INVALID_ARG, CSD_ERR_WORKSPACE (scratch too small or
+ * misaligned).  Only enqueues. */
+int csd_accept_loop(csd_index* index, int32_t n_steps, const int32_t* d_future_tokens,
+                    const float* d_future_probs, int32_t query_len, int32_t draft_len,
+                    void* d_scratch, size_t scratch_bytes, int32_t* d_draft_tokens,
+                    int32_t* d_draft_len, int32_t* d_accept_len, int32_t* d_path_len, void* stream);
+
 /* Waits for `stream` and copies the sticky CSD_STATUS_* bits to *host_flags. */
 int csd_status(csd_index* index, uint32_t* host_flags, void* stream);
 

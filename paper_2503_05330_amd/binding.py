@@ -20,7 +20,8 @@ STATUS_CAPACITY, STATUS_TOKEN_RANGE, STATUS_TABLE_FULL = 1, 2, 4
 OK, ERR_INVALID_ARG, ERR_CAPACITY, ERR_WORKSPACE, ERR_HIP, ERR_UNIMPLEMENTED = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ["csd_workspace_bytes", "csd_create", "csd_destroy", "csd_reset", "csd_append",
-           "csd_draft", "csd_accept", "csd_step", "csd_replay", "csd_status", "csd_dump_matches",
+           "csd_draft", "csd_accept", "csd_step", "csd_replay", "csd_accept_loop", "csd_status",
+           "csd_dump_matches",
            "csd_dump_edges", "csd_debug_copy", "csd_strerror"]
 
 
@@ -61,6 +62,8 @@ def load() -> ctypes.CDLL:
         lib.csd_accept.argtypes = [_vp, _vp, _vp, _vp, i32, _vp, _vp]
         lib.csd_step.argtypes = [_vp, _vp, _vp, _vp, i32, i32, i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
         lib.csd_replay.argtypes = [_vp, i32, _vp, _vp, i32, i32, _vp, _vp, _vp, _vp, _vp, _vp, i32, _vp]
+        lib.csd_accept_loop.argtypes = [_vp, i32, _vp, _vp, i32, i32, _vp, ctypes.c_size_t, _vp, _vp, _vp, _vp,
+                                        _vp]
         lib.csd_status.argtypes = [_vp, ctypes.POINTER(ctypes.c_uint32), _vp]
         lib.csd_dump_matches.argtypes = [_vp, i32, _vp, _vp, i64, _vp]
         lib.csd_dump_edges.argtypes = [_vp, i32, i32, _vp, _vp, _vp, i64, _vp]
@@ -226,6 +229,29 @@ class Index:
                                       _ptr(accept_out, torch.int32, S * self.rows),
                                       1 if fused else 0, _stream()), "csd_replay")
         out["accept"] = accept_out
+        return out
+
+    def accept_loop(self, n_steps, future_tokens, future_probs, query_len, draft_len, out=None):
+        """n_steps of the propose / verify / accept loop with each path's own future
+        (future_tokens / future_probs [P][N][max_len]) standing in for the model.  Returns
+        dict(tokens [S][P][N][L], length, accept, path_len [S][P][N])."""
+        L, S = draft_len, n_steps
+        if out is None:
+            out = dict(tokens=torch.empty((S, self.P, self.N, L), dtype=torch.int32, device=self.device))
+            for name in ("length", "accept", "path_len"):
+                out[name] = torch.empty((S, self.P, self.N), dtype=torch.int32, device=self.device)
+        cells = self.rows * self.cfg.max_len
+        nbytes = self.rows * (3 * L + 3) * 4
+        scratch = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self._check(load().csd_accept_loop(self._h, S, _ptr(future_tokens, torch.int32, cells),
+                                           _ptr(future_probs, torch.float32, cells), query_len, L,
+                                           scratch.data_ptr(), nbytes,
+                                           _ptr(out["tokens"], torch.int32, S * self.rows * L),
+                                           _ptr(out["length"], torch.int32, S * self.rows),
+                                           _ptr(out["accept"], torch.int32, S * self.rows),
+                                           _ptr(out["path_len"], torch.int32, S * self.rows), _stream()),
+                    "csd_accept_loop")
+        out["_scratch"] = scratch        # enqueued work still uses it
         return out
 
     def status(self) -> int:

@@ -358,6 +358,39 @@ int csd_replay(csd_index* h, int32_t n_steps, const int32_t* d_tokens, const flo
   return CSD_OK;
 }
 
+int csd_accept_loop(csd_index* h, int32_t n_steps, const int32_t* d_future_tokens,
+                    const float* d_future_probs, int32_t query_len, int32_t draft_len,
+                    void* d_scratch, size_t scratch_bytes, int32_t* d_draft_tokens,
+                    int32_t* d_draft_len, int32_t* d_accept_len, int32_t* d_path_len, void* stream) {
+  if (!h || n_steps < 0 || !d_future_tokens || !d_scratch || !d_draft_tokens || !d_draft_len ||
+      !d_accept_len || !d_path_len)
+    return CSD_ERR_INVALID_ARG;
+  int rc = check_draft_args(h, query_len, draft_len);
+  if (rc != CSD_OK) return rc;
+  const size_t rows = (size_t)h->view.P * h->view.N;
+  const size_t L = (size_t)draft_len, n = L + 1;
+  if (scratch_bytes < rows * (2 * n + L + 1) * 4 || (reinterpret_cast<uintptr_t>(d_scratch) & 3))
+    return CSD_ERR_WORKSPACE;
+  int32_t* step_tok = static_cast<int32_t*>(d_scratch);
+  float* step_prob = reinterpret_cast<float*>(step_tok + rows * n);
+  int32_t* targets = reinterpret_cast<int32_t*>(step_prob + rows * n);
+  int32_t* step_cnt = targets + rows * L;
+  hipStream_t st = as_stream(stream);
+  for (int32_t s = 0; s < n_steps; ++s) {
+    const int32_t* settled = s > 0 ? d_accept_len + (size_t)(s - 1) * rows : nullptr;
+    advance_kernel<<<(uint32_t)((rows + 255) / 256), 256, 0, st>>>(
+        (int64_t)rows, h->cfg.max_len, (int32_t)n, draft_len, h->meta[h->cur], h->view.meta_stride,
+        settled, d_future_tokens, d_future_probs, step_tok, d_future_probs ? step_prob : nullptr,
+        step_cnt, targets, d_path_len + (size_t)s * rows);
+    CSD_HIP(hipGetLastError());
+    rc = csd_step(h, step_tok, d_future_probs ? step_prob : nullptr, step_cnt, (int32_t)n, query_len,
+                  draft_len, d_draft_tokens + (size_t)s * rows * L, d_draft_len + (size_t)s * rows,
+                  nullptr, nullptr, targets, d_accept_len + (size_t)s * rows, stream);
+    if (rc != CSD_OK) return rc;
+  }
+  return CSD_OK;
+}
+
 int csd_status(csd_index* h, uint32_t* host_flags, void* stream) {
   if (!h || !host_flags) return CSD_ERR_INVALID_ARG;
   CSD_HIP(hipMemcpyAsync(host_flags, h->view.status, sizeof(uint32_t), hipMemcpyDeviceToHost,

@@ -237,6 +237,40 @@ __global__ __launch_bounds__(256) void accept_kernel(int64_t rows, int32_t L,
   accept_len[r] = a;
 }
 
+// The stand-in model of the accept-driven loop: what the model samples for a
+// path is the path's own future.  Per row: the step's input — the tokens the
+// previous step settled (its accepted draft tokens plus the one token the model
+// emits itself), i.e. the next n of the path's future with a count, clipped at
+// max_len — and the targets the coming draft will be checked against, the L
+// future tokens behind them (-1 beyond the end).
+__global__ __launch_bounds__(256) void advance_kernel(int64_t rows, int32_t max_len, int32_t n,
+                                                      int32_t L, const int32_t* meta,
+                                                      int32_t meta_stride, const int32_t* settled,
+                                                      const int32_t* future_tok,
+                                                      const float* future_prob, int32_t* step_tok,
+                                                      float* step_prob, int32_t* step_cnt,
+                                                      int32_t* targets, int32_t* path_len) {
+  int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (r >= rows) return;
+  int32_t len = meta[r * meta_stride];
+  int32_t grow = (settled ? settled[r] : 0) + 1;
+  grow = grow < 1 ? 1 : (grow > n ? n : grow);
+  int32_t room = max_len - len;
+  grow = grow < room ? grow : room;
+  step_cnt[r] = grow;
+  path_len[r] = len + grow;
+  const int32_t* ft = future_tok + r * max_len;
+  for (int32_t t = 0; t < n; ++t) {
+    bool in = len + t < max_len;
+    step_tok[r * n + t] = in ? ft[len + t] : 0;
+    if (step_prob) step_prob[r * n + t] = in ? future_prob[r * max_len + len + t] : 0.0f;
+  }
+  for (int32_t d = 0; d < L; ++d) {
+    int32_t t = len + grow + d;
+    targets[r * L + d] = t < max_len ? ft[t] : -1;
+  }
+}
+
 // Plain copy of n 16-byte words: the known-size kernel that hardware traffic
 // counters are calibrated against.
 __global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ src,

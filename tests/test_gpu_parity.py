@@ -476,3 +476,44 @@ def test_pool_modes_small_and_degenerate_cases(oracle, pool_mode):
     paths = [b.reshape(-1).tolist() for b in body]
     paths[0] = paths[0][:-5]
     _one_shot(oracle, paths, None, 1, 6, pool_mode=pool_mode)
+
+
+# ---------------------------------------------------------------- the propose / verify / accept loop
+def _accept_loop_case(oracle, w, n_steps, flags, eps=0, pool_mode=0, use_probs=True, warm=None):
+    tokens, probs = synth.make_paths(w)
+    pr = probs if use_probs else None
+    dev = torch.device("cuda:0")
+    P, N, T, k, L = w.n_problems, w.n_paths, w.max_len, w.query_len, w.draft_len
+    ix = binding.Index(P, N, T, w.vocab, k, L, 1.0, 0, flags, device=dev, max_edits=eps, pool_mode=pool_mode)
+    lens0 = np.zeros((P, N), np.int32)
+    if warm is not None:                          # start from ragged, partly filled paths
+        lens0 = warm.astype(np.int32)
+        n0 = int(lens0.max())
+        ix.append(torch.from_numpy(np.ascontiguousarray(tokens[:, :, :n0])).to(dev),
+                  None if pr is None else torch.from_numpy(np.ascontiguousarray(pr[:, :, :n0])).to(dev),
+                  torch.from_numpy(lens0).to(dev), n0)
+    got = ix.accept_loop(n_steps, torch.from_numpy(tokens).to(dev),
+                         None if pr is None else torch.from_numpy(pr).to(dev), k, L)
+    want = oracle.accept_loop(tokens, pr, lens0, k, L, n_steps, eps=eps, pool_mode=pool_mode)
+    what = "%s flags=%d eps=%d pool=%d" % (w.name, flags, eps, pool_mode)
+    assert np.array_equal(got["path_len"].cpu().numpy(), want["path_len"]), what
+    assert np.array_equal(got["length"].cpu().numpy(), want["draft_len"]), what
+    assert np.array_equal(got["tokens"].cpu().numpy(), want["draft"]), what
+    assert np.array_equal(got["accept"].cpu().numpy(), want["accept_len"]), what
+    assert ix.status() in (0, binding.STATUS_CAPACITY)
+    return want
+
+
+def test_accept_loop_diverging_path_lengths(oracle):
+    c1, c2, c4 = (synth.WORKLOADS[n] for n in ("C1", "C2", "C4"))
+    for flags in (INDEX, SCAN):
+        want = _accept_loop_case(oracle, c1, 200, flags)
+        assert want["accept_len"].sum() > 0 and want["path_len"][-1].max() > want["path_len"][-1].min()
+        _accept_loop_case(oracle, c1, 120, flags, use_probs=False,
+                          warm=np.array([[40, 3, 0, 17]]))
+    _accept_loop_case(oracle, c1, 200, SCAN, eps=1)
+    _accept_loop_case(oracle, c1, 200, INDEX, pool_mode=binding.POOL_TREE)
+    _accept_loop_case(oracle, c1, 200, SCAN, eps=1, pool_mode=binding.POOL_LIST)
+    want = _accept_loop_case(oracle, c2, 700, INDEX)          # runs every path to its full length
+    assert (want["final_len"] == c2.max_len).all()
+    _accept_loop_case(oracle, synth.scaled(c4, n_problems=6), 60, INDEX)
