@@ -48,6 +48,38 @@ def measured_traffic(workload):
         return None
 
 
+def batch_sweep(binding, torch, dev, w, tokens, probs, matches_per_problem_step, flags, max_edits):
+    """Step time with P copies of the workload's first problem in one index (the problems are
+    independent; every copy has its own memory).  256 steps from an empty index per point."""
+    N, T, k, L = w.n_paths, w.max_len, w.query_len, w.draft_len
+    S = min(256, T)
+    points = []
+    for P in (1, 4, 16, 64, 256, 1024, 4096):
+        tok = np.ascontiguousarray(np.broadcast_to(tokens[0, :, :S].T[:, None, :], (S, P, N)))
+        pr = np.ascontiguousarray(np.broadcast_to(probs[0, :, :S].T[:, None, :], (S, P, N)))
+        d_tok, d_pr = torch.from_numpy(tok).to(dev), torch.from_numpy(pr).to(dev)
+        ix = binding.Index(P, N, T, w.vocab, k, L, 1.0, 0, flags, device=dev, max_edits=max_edits)
+        outs = dict(tokens=torch.empty((S, P, N, L), dtype=torch.int32, device=dev),
+                    length=torch.empty((S, P, N), dtype=torch.int32, device=dev),
+                    token_scores=torch.empty((S, P, N, L), dtype=torch.float32, device=dev),
+                    path_scores=torch.empty((S, P, N), dtype=torch.float32, device=dev))
+        ix.replay(S, d_tok, d_pr, k, L, out=outs)                 # warm-up
+        torch.cuda.synchronize()
+        ix.reset()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        ix.replay(S, d_tok, d_pr, k, L, out=outs)
+        ev1.record()
+        torch.cuda.synchronize()
+        us = ev0.elapsed_time(ev1) / S * 1e3
+        # matches grow about linearly with history: a replay of S of T steps sees S/T of the mean
+        b = algorithmic_bytes(N * P, k, L, k, matches_per_problem_step * P * S / T) - 4 * L * N * P
+        points.append({"problems": P, "rows": P * N, "us_per_step": us,
+                       "problem_steps_per_s": P / us * 1e6, "algorithmic_GBps": b / us / 1e3})
+        del ix, outs, d_tok, d_pr
+    return points
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -61,6 +93,9 @@ def main():
                     help="organisation of the candidate pool (dag = the method, the headline; tree and "
                          "list are the variants of the paper's ablation)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--batch-sweep", action="store_true",
+                    help="also time the step with 1..4096 copies of the workload's first problem in one "
+                         "index (throughput against batch size)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 64 MiB copy kernel (reference for traffic counters)")
     args = ap.parse_args()
@@ -207,6 +242,10 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(w.name),
                      "algorithmic_bytes_per_launch": b_step, "avg_launch_us": launch_ms * 1e3},
     }
+
+    if args.batch_sweep:
+        res["batch_sweep"] = batch_sweep(binding, torch, dev, w, tokens, probs, matches_per_step / P,
+                                         {"auto": 0, "scan": 1, "index": 2}[args.matcher], args.max_edits)
 
     if not args.no_cpu_baseline:
         import oracle

@@ -147,27 +147,33 @@ int check_draft_args(const csd_index* h, int32_t query_len, int32_t draft_len) {
   return CSD_OK;
 }
 
+// From this many rows on (256 CUs x 4 rows of the regular layout are resident at once) the
+// one-wave kernel runs with the small LDS layout.
+constexpr int64_t kSmallLdsRows = 2048;
+
 void launch_draft(const csd_index* h, const IndexView& v, const StepIn& in, const DraftArgs& a,
                   hipStream_t st) {
   int64_t rows = (int64_t)v.P * v.N;
   const uint32_t grid = xcd_grid(rows);
   if (a.pool_mode != CSD_POOL_DAG) {                    // tree and list pools: the general kernels
     if (!h->indexed) step_scan_kernel<1, true><<<grid, kScanBlock, 0, st>>>(v, in, a);
-    else if (a.L <= 8) step_wave_kernel<8, true><<<grid, kWave, 0, st>>>(v, in, a);
-    else if (a.L <= 16) step_wave_kernel<16, true><<<grid, kWave, 0, st>>>(v, in, a);
-    else step_wave_kernel<32, true><<<grid, kWave, 0, st>>>(v, in, a);
+    else if (a.L <= 8) step_wave_kernel<8, true, LdsWave><<<grid, kWave, 0, st>>>(v, in, a);
+    else if (a.L <= 16) step_wave_kernel<16, true, LdsWave><<<grid, kWave, 0, st>>>(v, in, a);
+    else step_wave_kernel<32, true, LdsWave><<<grid, kWave, 0, st>>>(v, in, a);
   } else if (!h->indexed && a.L <= 8)
     step_scan_kernel<8, false><<<grid, kScanBlock, 0, st>>>(v, in, a);
   else if (!h->indexed && a.L <= 16)
     step_scan_kernel<16, false><<<grid, kScanBlock, 0, st>>>(v, in, a);
   else if (!h->indexed)     // longer drafts: the walk's register-resident fast path is left out
     step_scan_kernel<1, false><<<grid, kScanBlock, 0, st>>>(v, in, a);
+  else if (a.L <= 8 && rows >= kSmallLdsRows)   // more rows than fit the chip at once
+    step_wave_kernel<8, false, LdsWaveSmall><<<grid, kWave, 0, st>>>(v, in, a);
   else if (a.L <= 8)
-    step_wave_kernel<8, false><<<grid, kWave, 0, st>>>(v, in, a);
+    step_wave_kernel<8, false, LdsWave><<<grid, kWave, 0, st>>>(v, in, a);
   else if (a.L <= 16)
-    step_wave_kernel<16, false><<<grid, kWave, 0, st>>>(v, in, a);
+    step_wave_kernel<16, false, LdsWave><<<grid, kWave, 0, st>>>(v, in, a);
   else
-    step_wave_kernel<32, false><<<grid, kWave, 0, st>>>(v, in, a);
+    step_wave_kernel<32, false, LdsWave><<<grid, kWave, 0, st>>>(v, in, a);
 }
 
 // Host-side bookkeeping shared by csd_append and csd_step.

@@ -228,6 +228,10 @@ struct LdsT {
 };
 // One wave per row (index mode): 38 KB, four rows share a CU's LDS.
 typedef LdsT<1024, 1024, 2048, 1> LdsWave;
+// The same for large batches, where the number of rows resident on a CU bounds
+// the throughput: 13 KB, twelve rows per CU.  Rows with more than 256 matches or
+// more than 32 distinct keys in a layer take the streaming tier.
+typedef LdsT<256, 256, 1024, 1> LdsWaveSmall;
 // One 1024-thread workgroup per row (scan mode, where a fuzzy query can have
 // thousands of matches): 108 KB, one row per CU.
 typedef LdsT<4096, 4096, 16, kScanBlock / kWave> LdsScan;

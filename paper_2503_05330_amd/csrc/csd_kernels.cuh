@@ -169,9 +169,9 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
 // Index mode.  One wave64 per (problem, path): the front end (append, matches
 // with their continuations in LDS), DAG build, scoring, walk, outputs, accept,
 // and last the posting stores of the split-phase index insert.
-template <int LCAP, bool POOLS>
+template <int LCAP, bool POOLS, class LDS>
 __global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn in, DraftArgs a) {
-  __shared__ LdsWave s;
+  __shared__ LDS s;
   int32_t row = xcd_row(ix.P * ix.N);
   if (row < 0) return;
   int32_t p;
@@ -187,7 +187,7 @@ __global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn i
   DraftOut o;
   if (POOLS && M > 0 && a.pool_mode != CSD_POOL_DAG) {
     auto each = [&](auto f) {
-      if (M <= LdsWave::kMatch) {
+      if (M <= LDS::kMatch) {
         for (int32_t m = c.tid; m < M; m += kWave) f(s.match[m], m);
       } else {
         auto g = [&](Match found) { f(found, -1); };
@@ -199,7 +199,7 @@ __global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn i
     if (a.pool_mode == CSD_POOL_TREE) walk_tree<kWave>(s, c, wi, M, L, a.alpha_q, ix.status, o, each);
     else walk_list<kWave>(s, c, wi, L, a.alpha_q, o, each);
   } else if (M > 0) {
-    bool streaming = M > LdsWave::kMatch;
+    bool streaming = M > LDS::kMatch;
     if (!streaming) {
       Tier1 t1 = build_dag<kWave>(s, c, M, L, wi, a.alpha_q);
       streaming = s.overflow != 0;
@@ -207,7 +207,7 @@ __global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn i
     }
     if (streaming)
       walk_streaming<kWave>(s, c, L, a.alpha_q, a.score_mode, ix.status, o, [&](auto f) {
-        if (M <= LdsWave::kMatch) {
+        if (M <= LDS::kMatch) {
           for (int32_t m = c.tid; m < M; m += kWave) f(s.match[m]);
         } else {
           FnSink<decltype(f)> fs{f};

@@ -517,3 +517,25 @@ def test_accept_loop_diverging_path_lengths(oracle):
     want = _accept_loop_case(oracle, c2, 700, INDEX)          # runs every path to its full length
     assert (want["final_len"] == c2.max_len).all()
     _accept_loop_case(oracle, synth.scaled(c4, n_problems=6), 60, INDEX)
+
+
+def test_large_batch_uses_the_small_on_chip_layout(oracle):
+    """2048+ rows per launch run the one-wave kernel with its small LDS layout (more rows
+    resident per CU).  Rows that do not fit it (two problems of constant paths: thousands of
+    matches; rows with many distinct continuations) must take the bounded-memory tier."""
+    w = synth.scaled(synth.WORKLOADS["C4"], n_problems=130, max_len=192)
+    tokens, probs = synth.make_paths(w)
+    tokens[7] = 11                                         # constant paths
+    tokens[99, :, :] = tokens[99, :1, :]                   # identical paths
+    rng = np.random.default_rng(3)
+    tokens[50, :, ::3] = 5                                 # a frequent token with varied successors
+    tokens[50, :, 1::3] = rng.integers(100, 130, size=tokens[50, :, 1::3].shape)
+    assert tokens.shape[0] * tokens.shape[1] >= 2048
+    T, k, L = w.max_len, w.query_len, w.draft_len
+    targets = np.stack([synth.make_noisy_targets(w, tokens, t + 1, L) for t in range(T)])
+    got = gpu_replay(tokens, probs, k, L, flags=INDEX, targets=targets, how="replay")
+    assert got["status"] == 0
+    for t in sorted(set(list(range(0, T, 24)) + [T - 1])):
+        lens_t = np.full(tokens.shape[:2], t + 1, dtype=np.int32)
+        want = oracle.draft_all(tokens, probs, lens_t, k, L, 1.0, 0, targets[t])
+        assert_step_equal(got, want, t, "large batch")
