@@ -96,8 +96,12 @@ typedef struct {
                              (Eq. 3), 1 = one substitution, insertion or deletion (the
                              paper's experiments use 1).  With 1 a position e of another
                              path matches when some substring ending just before e is
-                             within one edit of the query, each e counting once, and
-                             matches are found by scan (CSD_MATCH_INDEX is refused).   */
+                             within one edit of the query, each e counting once.  Such
+                             matches are found by scan, or through the index, which then
+                             files every position under the max_query_len + 1 variants
+                             of its gram (the gram itself and the gram without one of its
+                             tokens): CSD_MATCH_AUTO takes the index from max_query_len 4
+                             on, CSD_MATCH_INDEX from 2 on (1: CSD_ERR_UNIMPLEMENTED).  */
   int32_t pool_mode;      /* how the candidate pool is organised before the greedy
                              extraction: CSD_POOL_DAG (the method: equal tokens of a layer
                              are one node, Eq. 5), CSD_POOL_TREE (prefix tree: candidates

@@ -138,7 +138,11 @@ class Index:
             load().csd_destroy(self._h)
             self._h = None
 
-    __del__ = close
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:       # interpreter shutdown: module globals may already be gone
+            pass
 
     def _check(self, rc, what):
         if rc != OK:

@@ -62,7 +62,19 @@ struct Layout {
   size_t gram_words;
 };
 
-bool uses_index(const csd_config* c) { return c->flags != CSD_MATCH_SCAN && c->max_edits == 0; }
+// One-edit matching can go through the index when the query has at least two tokens (with
+// one token every position is within one edit: a scan's job).  The index files positions
+// under grams of max_query_len - 1 tokens then; for three-token queries those are pairs,
+// the chains of frequent pairs get long, and the scan is the faster matcher: CSD_MATCH_AUTO
+// takes the index from four tokens on.
+bool uses_index(const csd_config* c) {
+  if (c->flags == CSD_MATCH_SCAN) return false;
+  if (c->max_edits == 0) return true;
+  return c->max_query_len >= (c->flags == CSD_MATCH_INDEX ? 2 : 4);
+}
+int32_t tail_len_of(const csd_config* c) {
+  return c->max_query_len + ((uses_index(c) && c->max_edits > 0) ? 1 : 0);
+}
 
 int validate(const csd_config* c) {
   if (!c) return CSD_ERR_INVALID_ARG;
@@ -78,7 +90,7 @@ int validate(const csd_config* c) {
   if (c->max_edits < 0) return CSD_ERR_INVALID_ARG;
   if (c->pool_mode < CSD_POOL_DAG || c->pool_mode > CSD_POOL_LIST) return CSD_ERR_INVALID_ARG;
   if (c->max_edits > 1) return CSD_ERR_UNIMPLEMENTED;
-  if (c->max_edits == 1 && c->flags == CSD_MATCH_INDEX) return CSD_ERR_UNIMPLEMENTED;
+  if (c->max_edits == 1 && c->flags == CSD_MATCH_INDEX && c->max_query_len < 2) return CSD_ERR_UNIMPLEMENTED;
   return CSD_OK;
 }
 
@@ -91,7 +103,7 @@ Layout make_layout(const csd_config* c) {
   // their problem's first path, and a span may read two cells past its path
   l.tok = at;    at += align_up((cells + 8) * sizeof(int32_t));
   l.pq = at;     at += align_up(cells * sizeof(uint32_t));
-  l.meta_stride = (1 + c->max_query_len + 3) / 4 * 4;
+  l.meta_stride = (1 + tail_len_of(c) + 3) / 4 * 4;
   l.eshift = 1;
   while ((1 << l.eshift) < c->max_len) ++l.eshift;
   l.meta = at;   at += 2 * align_up(rows * l.meta_stride * sizeof(int32_t));
@@ -101,7 +113,8 @@ Layout make_layout(const csd_config* c) {
   l.gram = at;
   if (uses_index(c)) {
     // 15 slots per bucket and at least positions/8 buckets: load factor <= 8/15
-    uint64_t positions = (uint64_t)c->n_paths * c->max_len;
+    // (one-edit matching stores max_query_len + 1 postings per position)
+    uint64_t positions = (uint64_t)c->n_paths * c->max_len * (c->max_edits > 0 ? c->max_query_len + 1 : 1);
     uint32_t nb = 4;
     while ((uint64_t)nb * 8 < positions) nb <<= 1;
     l.n_buckets = nb;
@@ -155,11 +168,15 @@ void launch_draft(const csd_index* h, const IndexView& v, const StepIn& in, cons
                   hipStream_t st) {
   int64_t rows = (int64_t)v.P * v.N;
   const uint32_t grid = xcd_grid(rows);
-  if (a.pool_mode != CSD_POOL_DAG) {                    // tree and list pools: the general kernels
+  if (h->indexed && v.eps > 0) {                         // one edit through the variant index
+    if (a.L <= 8) step_wave_kernel<8, true, LdsWaveFuzzy, true><<<grid, kWave, 0, st>>>(v, in, a);
+    else if (a.L <= 16) step_wave_kernel<16, true, LdsWaveFuzzy, true><<<grid, kWave, 0, st>>>(v, in, a);
+    else step_wave_kernel<32, true, LdsWaveFuzzy, true><<<grid, kWave, 0, st>>>(v, in, a);
+  } else if (a.pool_mode != CSD_POOL_DAG) {             // tree and list pools: the general kernels
     if (!h->indexed) step_scan_kernel<1, true><<<grid, kScanBlock, 0, st>>>(v, in, a);
-    else if (a.L <= 8) step_wave_kernel<8, true, LdsWave><<<grid, kWave, 0, st>>>(v, in, a);
-    else if (a.L <= 16) step_wave_kernel<16, true, LdsWave><<<grid, kWave, 0, st>>>(v, in, a);
-    else step_wave_kernel<32, true, LdsWave><<<grid, kWave, 0, st>>>(v, in, a);
+    else if (a.L <= 8) step_wave_kernel<8, true, LdsWave, false><<<grid, kWave, 0, st>>>(v, in, a);
+    else if (a.L <= 16) step_wave_kernel<16, true, LdsWave, false><<<grid, kWave, 0, st>>>(v, in, a);
+    else step_wave_kernel<32, true, LdsWave, false><<<grid, kWave, 0, st>>>(v, in, a);
   } else if (!h->indexed && a.L <= 8)
     step_scan_kernel<8, false><<<grid, kScanBlock, 0, st>>>(v, in, a);
   else if (!h->indexed && a.L <= 16)
@@ -167,13 +184,13 @@ void launch_draft(const csd_index* h, const IndexView& v, const StepIn& in, cons
   else if (!h->indexed)     // longer drafts: the walk's register-resident fast path is left out
     step_scan_kernel<1, false><<<grid, kScanBlock, 0, st>>>(v, in, a);
   else if (a.L <= 8 && rows >= kSmallLdsRows)   // more rows than fit the chip at once
-    step_wave_kernel<8, false, LdsWaveSmall><<<grid, kWave, 0, st>>>(v, in, a);
+    step_wave_kernel<8, false, LdsWaveSmall, false><<<grid, kWave, 0, st>>>(v, in, a);
   else if (a.L <= 8)
-    step_wave_kernel<8, false, LdsWave><<<grid, kWave, 0, st>>>(v, in, a);
+    step_wave_kernel<8, false, LdsWave, false><<<grid, kWave, 0, st>>>(v, in, a);
   else if (a.L <= 16)
-    step_wave_kernel<16, false, LdsWave><<<grid, kWave, 0, st>>>(v, in, a);
+    step_wave_kernel<16, false, LdsWave, false><<<grid, kWave, 0, st>>>(v, in, a);
   else
-    step_wave_kernel<32, false, LdsWave><<<grid, kWave, 0, st>>>(v, in, a);
+    step_wave_kernel<32, false, LdsWave, false><<<grid, kWave, 0, st>>>(v, in, a);
 }
 
 // Host-side bookkeeping shared by csd_append and csd_step.
@@ -220,6 +237,7 @@ int csd_create(const csd_config* cfg, void* d_workspace, size_t workspace_bytes,
   h->view.meta_old = h->meta[0];
   h->view.meta_new = h->meta[0];
   h->view.meta_stride = l.meta_stride;
+  h->view.tail_len = tail_len_of(cfg);
   h->view.eshift = l.eshift;
   h->view.status = reinterpret_cast<uint32_t*>(base + l.status);
   h->indexed = uses_index(cfg);
@@ -424,9 +442,12 @@ int csd_dump_matches(csd_index* h, int32_t query_len, int32_t* d_match_je, int32
   do {
     e = hipMemsetAsync(bits, 0, (size_t)rows * words * sizeof(uint32_t), st);
     if (e != hipSuccess) break;
-    if (h->indexed)
-      dump_match_bits_wave_kernel<<<xcd_grid(rows), kWave, 0, st>>>(v, no_step, query_len, bits,
-                                                                    words);
+    if (h->indexed && v.eps > 0)
+      dump_match_bits_wave_kernel<true><<<xcd_grid(rows), kWave, 0, st>>>(v, no_step, query_len,
+                                                                          bits, words);
+    else if (h->indexed)
+      dump_match_bits_wave_kernel<false><<<xcd_grid(rows), kWave, 0, st>>>(v, no_step, query_len,
+                                                                           bits, words);
     else
       dump_match_bits_scan_kernel<<<xcd_grid(rows), kScanBlock, 0, st>>>(v, no_step, query_len,
                                                                         bits, words);
@@ -465,14 +486,17 @@ int csd_dump_edges(csd_index* h, int32_t query_len, int32_t draft_len, int32_t* 
   IndexView v = view_in_place(h);
   const StepIn no_step{nullptr, nullptr, nullptr, 0};
   do {
-    if (h->indexed && draft_len <= 8)
-      dump_edge_rows_wave_kernel<8><<<xcd_grid(rows), kWave, 0, st>>>(
+    if (h->indexed && v.eps > 0)
+      dump_edge_rows_wave_kernel<32, true><<<xcd_grid(rows), kWave, 0, st>>>(
+          v, no_step, query_len, draft_len, tmp, tmp + tmp_elems, counts);
+    else if (h->indexed && draft_len <= 8)
+      dump_edge_rows_wave_kernel<8, false><<<xcd_grid(rows), kWave, 0, st>>>(
           v, no_step, query_len, draft_len, tmp, tmp + tmp_elems, counts);
     else if (h->indexed && draft_len <= 16)
-      dump_edge_rows_wave_kernel<16><<<xcd_grid(rows), kWave, 0, st>>>(
+      dump_edge_rows_wave_kernel<16, false><<<xcd_grid(rows), kWave, 0, st>>>(
           v, no_step, query_len, draft_len, tmp, tmp + tmp_elems, counts);
     else if (h->indexed)
-      dump_edge_rows_wave_kernel<32><<<xcd_grid(rows), kWave, 0, st>>>(
+      dump_edge_rows_wave_kernel<32, false><<<xcd_grid(rows), kWave, 0, st>>>(
           v, no_step, query_len, draft_len, tmp, tmp + tmp_elems, counts);
     else
       dump_edge_rows_scan_kernel<<<xcd_grid(rows), kScanBlock, 0, st>>>(

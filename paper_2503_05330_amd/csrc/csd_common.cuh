@@ -27,6 +27,7 @@ constexpr u64 kEmpty = ~0ull;
 constexpr int kMaxClassBits = 20;           // streaming tier: at most 2^20 token classes
 constexpr int kBucketWords = 16;            // one 64-byte line: [count, 15 postings]
 constexpr int kBucketSlots = kBucketWords - 1;
+constexpr int kTailCap = CSD_MAX_QUERY_LEN + 1;   // most tokens a meta row keeps
 
 // ---------------------------------------------------------------- exact weights
 
@@ -117,6 +118,15 @@ __device__ __forceinline__ Cand wave_argmax(Cand c) {
   return cand_from_lane(c, 63);
 }
 
+// arr[idx] without indexing registers by a variable (0 when idx is out of range)
+template <int SIZE>
+__device__ __forceinline__ int32_t pick(const int32_t (&arr)[SIZE], int32_t idx) {
+  int32_t r = 0;
+#pragma unroll
+  for (int a = 0; a < SIZE; ++a) r = (idx == a) ? arr[a] : r;
+  return r;
+}
+
 template <int BLOCK>
 __device__ __forceinline__ void block_sync() {
   __syncthreads();   // a one-wave workgroup needs no hardware barrier: the compiler drops it
@@ -127,13 +137,15 @@ __device__ __forceinline__ void block_sync() {
 struct IndexView {              // device state inside the caller's workspace
   int32_t* tok;                 // [P][N][max_len] token histories
   uint32_t* pq;                 // [P][N][max_len] quantised generation probabilities
-  const int32_t* meta_old;      // [P][N][meta_stride] before this launch: {length, last kmax
+  const int32_t* meta_old;      // [P][N][meta_stride] before this launch: {length, last tail_len
                                 //   tokens newest first}: one aligned load tells a path's end
   int32_t* meta_new;            // same rows after it (may alias meta_old when nothing else reads)
   uint32_t* status;             // sticky CSD_STATUS_* bits
   int32_t* gram;                // kmax-gram index [P][n_buckets][16], or null (scan mode)
   uint32_t bucket_mask;         // n_buckets - 1 (power of two)
-  int32_t meta_stride;          // ints per meta row: 1 + kmax rounded up to a multiple of 4
+  int32_t meta_stride;          // ints per meta row: 1 + tail_len rounded up to a multiple of 4
+  int32_t tail_len;             // newest tokens kept in a meta row: kmax, or kmax + 1 when the
+                                //   index serves one-edit matching (a match may look one further back)
   int32_t eshift;               // positions are packed as (path << eshift) | index
   int32_t P, N, max_len, vocab, kmax;
   int32_t eps;                  // edit tolerance (0 = exact match)
@@ -216,7 +228,8 @@ struct LdsT {
   static constexpr int kMatch = MATCH;
   static constexpr int kWin = WIN;
   Slot table[TABLE];
-  uint16_t link[TABLE];         // edge slot -> slot of its target node (tier 1)
+  uint16_t link[TABLE > MATCH ? TABLE : MATCH];   // edge slot -> slot of its target node (tier 1);
+                                // the tree pool keeps one flag per listed match here
   Match match[MATCH];
   int32_t win[WIN];             // per cached match: L continuation tokens, then their L probabilities
   int32_t len_old[kLenCache];
@@ -232,6 +245,9 @@ typedef LdsT<1024, 1024, 2048, 1> LdsWave;
 // the throughput: 13 KB, twelve rows per CU.  Rows with more than 256 matches or
 // more than 32 distinct keys in a layer take the streaming tier.
 typedef LdsT<256, 256, 1024, 1> LdsWaveSmall;
+// One wave per row with one-edit matching through the index: such queries have
+// many more matches, so the list is longer (66 KB, two rows per CU).
+typedef LdsT<1024, 4096, 2048, 1> LdsWaveFuzzy;
 // One 1024-thread workgroup per row (scan mode, where a fuzzy query can have
 // thousands of matches): 108 KB, one row per CU.
 typedef LdsT<4096, 4096, 16, kScanBlock / kWave> LdsScan;

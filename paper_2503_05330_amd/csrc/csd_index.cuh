@@ -98,7 +98,7 @@ struct InsertTicket {
 // Phase 1: hash of the gram that ends just before the new position (tail[a] =
 // a-th token before it) and the fill-count loads (not waited for here).
 __device__ __forceinline__ InsertTicket insert_begin(int32_t* gram, uint32_t mask, int32_t kmax,
-                                                     const int32_t (&tail)[CSD_MAX_QUERY_LEN],
+                                                     const int32_t (&tail)[kTailCap],
                                                      int32_t n_before, int lane) {
   InsertTicket t;
   uint32_t acc = kGramSeed;
@@ -139,6 +139,115 @@ __device__ __forceinline__ void insert_finish(const InsertTicket& t, int32_t* gr
                    lane);
 }
 
+// ---------------------------------------------------------------- one-edit matching (Eq. 4) through the index
+//
+// Variant v of a gram G[0 .. kmax) (newest token first): v = 0 is the gram
+// itself, v >= 1 the gram without G[v-1].  Two strings within one edit of each
+// other share a variant (delete the substituted token from both; delete the
+// extra token from the longer one), so a position whose kmax-gram is filed
+// under all its kmax + 1 variants is found by looking up the query's variants.
+// The converse does not hold, and a position can be found several times:
+// candidates are verified and de-duplicated by the matcher.
+// A posting of the variant index carries the number of the variant it was
+// filed under above the packed position (which needs at most 25 bits): chains
+// of different variants can share a bucket, and the matcher must tell them apart.
+constexpr int kVariantShift = 26;
+__device__ __forceinline__ int32_t variant_posting(int32_t pos, int32_t v) {
+  return pos | (v << kVariantShift);
+}
+
+template <int SIZE>
+__device__ __forceinline__ GramHash variant_hash(const int32_t (&G)[SIZE], int32_t kmax, int32_t v) {
+  uint32_t acc = kGramSeed;
+#pragma unroll
+  for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a)
+    if (a < kmax && a != v - 1) acc = gram_hash_add(acc, G[a]);
+  return gram_hash_end(acc, v == 0 ? kmax : kmax - 1);
+}
+// Variant v >= 2 is the same string as variant v - 1 when the two dropped tokens are equal.
+template <int SIZE>
+__device__ __forceinline__ bool variant_is_new(const int32_t (&G)[SIZE], int32_t v) {
+  return v < 2 || pick(G, v - 1) != pick(G, v - 2);
+}
+
+// Files position e of path i (e >= kmax) under every variant of the gram
+// before it, by one whole wave (bulk appends).
+__device__ __forceinline__ void gram_insert_variants(int32_t* gram, uint32_t mask, int32_t kmax,
+                                                     const Paths& y, int32_t i, int32_t e,
+                                                     int32_t old_i, int lane) {
+  if (e < kmax) return;
+  int32_t G[CSD_MAX_QUERY_LEN];
+#pragma unroll
+  for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) G[a] = y.token(i, a < kmax ? e - 1 - a : e - 1, old_i);
+  for (int32_t v = 0; v <= kmax; ++v)
+    if (variant_is_new(G, v))
+      gram_insert_from(gram, mask, variant_hash(G, kmax, v), 0u, variant_posting(y.pos(i, e), v), lane);
+}
+
+// Split-phase insert of ONE new position under its variants: the four groups
+// of 16 lanes take variants 0..3 (fill counts of the first 16 buckets of each
+// chain in one round trip, one slot claim per group); further variants
+// (kmax >= 4) and groups whose quick claim failed use the general insert.
+struct VariantTicket {
+  GramHash gh;                  // of this lane's group's variant
+  int32_t fill;                 // fill count of bucket (lane & 15) of that chain
+  int32_t first;                // first open bucket among the 16, or -1
+  int32_t claimed;              // group leader: slot the atomic returned, or kBucketSlots
+  bool live;                    // this group has a variant to file
+  bool any;                     // the position has kmax tokens before it
+};
+
+__device__ __forceinline__ VariantTicket variants_begin(int32_t* gram, uint32_t mask, int32_t kmax,
+                                                        const int32_t (&tail)[kTailCap],
+                                                        int32_t n_before, int lane) {
+  VariantTicket t;
+  const int32_t v = lane >> 4;
+  t.gh = variant_hash(tail, kmax, v);
+  t.any = kmax <= n_before;
+  t.live = t.any && v <= kmax && variant_is_new(tail, v);
+  t.first = -1;
+  t.claimed = kBucketSlots;
+  uint32_t r = (uint32_t)(lane & 15);                   // every lane loads: no branch, no early wait
+  t.fill = gram_bucket(gram, t.gh, r <= mask ? r : 0u, mask)[0];
+  return t;
+}
+
+__device__ __forceinline__ void variants_claim(VariantTicket& t, int32_t* gram, uint32_t mask,
+                                               int lane) {
+  consume_here(t.fill);
+  bool open = t.live && (uint32_t)(lane & 15) <= mask && t.fill < kBucketSlots;
+  uint32_t mine = (uint32_t)(__ballot(open) >> (lane & 48)) & 0xFFFFu;   // this group's 16 lanes
+  t.first = mine ? (int32_t)__ffs(mine) - 1 : -1;
+  if (t.live && (lane & 15) == 0 && t.first >= 0)
+    t.claimed = atomicAdd(gram_bucket(gram, t.gh, (uint32_t)t.first, mask), 1);
+}
+
+// Variants beyond the four the groups take (kmax >= 4): the general insert.
+__device__ __forceinline__ void variants_beyond_four(const VariantTicket& t, int32_t* gram,
+                                                     uint32_t mask, int32_t kmax,
+                                                     const int32_t (&tail)[kTailCap], int32_t pos,
+                                                     int lane) {
+  if (!t.any) return;
+  for (int32_t v = 4; v <= kmax; ++v)
+    if (variant_is_new(tail, v))
+      gram_insert_from(gram, mask, variant_hash(tail, kmax, v), 0u, variant_posting(pos, v), lane);
+}
+
+__device__ __forceinline__ void variants_finish(const VariantTicket& t, int32_t* gram, uint32_t mask,
+                                                int32_t pos, int lane) {
+  if (!t.any) return;
+  bool stored = t.live && (lane & 15) == 0 && t.claimed < kBucketSlots;
+  if (stored) gram_bucket(gram, t.gh, (uint32_t)t.first, mask)[1 + t.claimed] = variant_posting(pos, lane >> 4);
+  int32_t retry = (t.live && !stored) ? 1 : 0;          // meaningful on the group leaders
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    if (__shfl(retry, 16 * g) == 0) continue;           // uniform over the wave
+    GramHash gh{(uint32_t)__shfl((int)t.gh.h, 16 * g), (uint32_t)__shfl((int)t.gh.step, 16 * g)};
+    int32_t first = __shfl(t.first, 16 * g);
+    gram_insert_from(gram, mask, gh, first < 0 ? 16u : (uint32_t)first, variant_posting(pos, g), lane);
+  }
+}
+
 // Stores this row's share of the step (tokens, quantised probabilities, index
 // postings, new length and tail), reading the step input from memory.  Called
 // by all threads of the row's workgroup; handles any number of new tokens.
@@ -152,7 +261,7 @@ __device__ __forceinline__ void append_row(const IndexView& ix, const Paths& y, 
   // read before the barrier and written after it, so the row may be updated in place.
   int32_t meta_val = 0;
   if (tid == 0) meta_val = new_i;
-  else if (tid <= ix.kmax) {
+  else if (tid <= ix.tail_len) {
     int32_t a = tid - 1;
     if (a < cnt) meta_val = y.st[(int64_t)i * y.n + cnt - 1 - a];
     else if (a < new_i) meta_val = y.meta_old[(int64_t)i * y.meta_stride + 1 + a - cnt];
@@ -163,7 +272,7 @@ __device__ __forceinline__ void append_row(const IndexView& ix, const Paths& y, 
     if (want > cnt) flags |= CSD_STATUS_CAPACITY;
   }
   block_sync<BLOCK>();
-  if (tid <= ix.kmax) ix.meta_new[row * ix.meta_stride + tid] = meta_val;
+  if (tid <= ix.tail_len) ix.meta_new[row * ix.meta_stride + tid] = meta_val;
   for (int32_t t = tid; t < cnt; t += BLOCK) {
     int32_t v = y.st[(int64_t)i * y.n + t];
     if (v < 0 || v >= ix.vocab) flags |= CSD_STATUS_TOKEN_RANGE;
@@ -172,8 +281,10 @@ __device__ __forceinline__ void append_row(const IndexView& ix, const Paths& y, 
   }
   if (WITH_INDEX && ix.gram) {
     int32_t* gram = ix.gram + (int64_t)p * ((int64_t)ix.bucket_mask + 1) * kBucketWords;
-    for (int32_t t = tid / kWave; t < cnt; t += BLOCK / kWave)     // one wave per new position
-      gram_insert_position(gram, ix.bucket_mask, ix.kmax, y, i, old_i + t, old_i, tid & 63);
+    for (int32_t t = tid / kWave; t < cnt; t += BLOCK / kWave) {   // one wave per new position
+      if (ix.eps > 0) gram_insert_variants(gram, ix.bucket_mask, ix.kmax, y, i, old_i + t, old_i, tid & 63);
+      else gram_insert_position(gram, ix.bucket_mask, ix.kmax, y, i, old_i + t, old_i, tid & 63);
+    }
   }
   if (flags) atomicOr(ix.status, flags);
 }

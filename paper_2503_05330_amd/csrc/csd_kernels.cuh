@@ -84,7 +84,7 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
   if (row < 0) return;
   int32_t p;
   Ctx c = make_ctx(ix, in, row, p);
-  Head me = load_head(c.y, ix.kmax, c.i);               // length and newest tokens in one read
+  Head me = load_head(c.y, ix.tail_len, c.i);           // length and newest tokens in one read
   int32_t st_i = in.n == 1 ? c.y.st[c.i] : 0;
   const int32_t old_i = me.old_len;
   c.len_i = me.new_len;
@@ -169,7 +169,9 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
 // Index mode.  One wave64 per (problem, path): the front end (append, matches
 // with their continuations in LDS), DAG build, scoring, walk, outputs, accept,
 // and last the posting stores of the split-phase index insert.
-template <int LCAP, bool POOLS, class LDS>
+// FUZZY: the index files every position under its gram's variants and matching tolerates
+// one edit (Eq. 4).
+template <int LCAP, bool POOLS, class LDS, bool FUZZY>
 __global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn in, DraftArgs a) {
   __shared__ LDS s;
   int32_t row = xcd_row(ix.P * ix.N);
@@ -180,19 +182,23 @@ __global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn i
   int32_t target = (a.targets && c.tid < L) ? a.targets[(int64_t)row * L + c.tid] : 0;
   WinInfo wi;
   InsertTicket ticket;
+  VariantTicket tickets;
   bool ticket_used;
-  int32_t M = wave_front_end<LCAP>(s, c, ix, p, a.k, L, wi, ticket, ticket_used);
+  int32_t M = FUZZY ? wave_front_end_fuzzy<LCAP>(s, c, ix, p, a.k, L, wi, tickets, ticket_used)
+                    : wave_front_end<LCAP>(s, c, ix, p, a.k, L, wi, ticket, ticket_used);
   block_sync<kWave>();
 
   DraftOut o;
   if (POOLS && M > 0 && a.pool_mode != CSD_POOL_DAG) {
     auto each = [&](auto f) {
       if (M <= LDS::kMatch) {
+#pragma unroll 4
         for (int32_t m = c.tid; m < M; m += kWave) f(s.match[m], m);
       } else {
         auto g = [&](Match found) { f(found, -1); };
         FnSink<decltype(g)> fs{g};
-        if (c.q == c.kmax) match_index(c, fs);
+        if (FUZZY) match_scan<kWave, true>(s, c, fs);
+        else if (c.q == c.kmax) match_index(c, fs);
         else match_scan<kWave, false>(s, c, fs);
       }
     };
@@ -208,16 +214,21 @@ __global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn i
     if (streaming)
       walk_streaming<kWave>(s, c, L, a.alpha_q, a.score_mode, ix.status, o, [&](auto f) {
         if (M <= LDS::kMatch) {
+#pragma unroll 4
           for (int32_t m = c.tid; m < M; m += kWave) f(s.match[m]);
         } else {
           FnSink<decltype(f)> fs{f};
-          if (c.q == c.kmax) match_index(c, fs);
+          if (FUZZY) match_scan<kWave, true>(s, c, fs);
+          else if (c.q == c.kmax) match_index(c, fs);
           else match_scan<kWave, false>(s, c, fs);
         }
       });
   }
   // the posting stores wait on atomics issued long ago: do them before the output stores
-  if (ticket_used)
+  if (ticket_used && FUZZY)
+    variants_finish(tickets, const_cast<int32_t*>(c.gram), c.bucket_mask, c.y.pos(c.i, c.len_i - 1),
+                    c.tid);
+  else if (ticket_used)
     insert_finish(ticket, const_cast<int32_t*>(c.gram), c.bucket_mask,
                   c.y.pos(c.i, c.len_i - 1), c.tid);
   write_outputs<kWave>(a, row, o, c.tid);
@@ -301,6 +312,7 @@ __global__ __launch_bounds__(kScanBlock) void dump_match_bits_scan_kernel(IndexV
 }
 
 // Index mode: the matches as the step kernel's own front end finds them.
+template <bool FUZZY>
 __global__ __launch_bounds__(kWave) void dump_match_bits_wave_kernel(IndexView ix, StepIn in,
                                                                      int32_t k, uint32_t* bits,
                                                                      int32_t words) {
@@ -311,12 +323,16 @@ __global__ __launch_bounds__(kWave) void dump_match_bits_wave_kernel(IndexView i
   Ctx c = make_ctx(ix, in, row, p);   // in.n == 0: nothing is being appended
   WinInfo wi;
   InsertTicket ticket;
+  VariantTicket tickets;
   bool ticket_used;
-  int32_t M = wave_front_end<8>(s, c, ix, p, k, 1, wi, ticket, ticket_used);
+  int32_t M = FUZZY ? wave_front_end_fuzzy<8>(s, c, ix, p, k, 1, wi, tickets, ticket_used)
+                    : wave_front_end<8>(s, c, ix, p, k, 1, wi, ticket, ticket_used);
   block_sync<kWave>();
   BitmapSink sink{bits + (int64_t)row * words};
   if (M <= LdsWave::kMatch) {
     for (int32_t m = c.tid; m < M; m += kWave) sink.push(c.y, true, s.match[m]);
+  } else if (FUZZY) {
+    if (c.q > 0) match_scan<kWave, true>(s, c, sink);
   } else if (c.q == c.kmax) {
     match_index(c, sink);
   } else if (c.q > 0) {
@@ -419,7 +435,7 @@ __global__ __launch_bounds__(kScanBlock) void dump_edge_rows_scan_kernel(
 }
 
 // Index mode: front end and DAG build of the step kernel itself.
-template <int LCAP>
+template <int LCAP, bool FUZZY>
 __global__ __launch_bounds__(kWave) void dump_edge_rows_wave_kernel(IndexView ix, StepIn in,
                                                                     int32_t k, int32_t L,
                                                                     u64* tmp_keys, u64* tmp_vals,
@@ -433,8 +449,10 @@ __global__ __launch_bounds__(kWave) void dump_edge_rows_wave_kernel(IndexView ix
   if (c.tid == 0) n_edges = 0;
   WinInfo wi;
   InsertTicket ticket;
+  VariantTicket tickets;
   bool ticket_used;
-  int32_t M = wave_front_end<LCAP>(s, c, ix, p, k, L, wi, ticket, ticket_used);
+  int32_t M = FUZZY ? wave_front_end_fuzzy<LCAP>(s, c, ix, p, k, L, wi, tickets, ticket_used)
+                    : wave_front_end<LCAP>(s, c, ix, p, k, L, wi, ticket, ticket_used);
   block_sync<kWave>();
   if (M == 0) { if (c.tid == 0) counts[row] = 0; return; }
   if (M > LdsWave::kMatch) { if (c.tid == 0) counts[row] = -1; return; }

@@ -57,11 +57,11 @@ __device__ __forceinline__ bool gram_equals_query(const Ctx& c, int32_t j, int32
 // the edit agree in place, the older ones agree in place (substitution), one
 // step further back (the text has an extra token) or one step closer (the text
 // lacks a token).
-__device__ __forceinline__ bool gram_near_query(const Ctx& c, int32_t j, int32_t e, int32_t old_j) {
+// t[a] = the a-th token before e for a < min(q + 1, e), else 0.
+__device__ __forceinline__ bool near_query(const Ctx& c, int32_t e,
+                                           const int32_t (&t)[CSD_MAX_QUERY_LEN + 1]) {
   constexpr int K = CSD_MAX_QUERY_LEN;
   const int32_t q = c.q;
-  int32_t t[K + 1];
-  tokens_before(c, j, e, old_j, q + 1, t);
   // pre[p]: t[a] == Q[a] for all a < p.  same/back/fwd[p]: the agreement of the older part
   // a > p (same, fwd) or a >= p (back) at shift 0 / +1 / -1, scanned from the oldest token.
   int32_t Q[K + 1];                                        // Q[K] only pads the unrolled loops
@@ -88,6 +88,12 @@ __device__ __forceinline__ bool gram_near_query(const Ctx& c, int32_t j, int32_t
     if (p <= q) hit = hit || (e >= q + 1 && pre[p] && back[p]);   // extra text token at p
   }
   return hit;
+}
+
+__device__ __forceinline__ bool gram_near_query(const Ctx& c, int32_t j, int32_t e, int32_t old_j) {
+  int32_t t[CSD_MAX_QUERY_LEN + 1];
+  tokens_before(c, j, e, old_j, c.q + 1, t);
+  return near_query(c, e, t);
 }
 
 __device__ __forceinline__ GramHash query_hash(const Ctx& c) {
@@ -358,26 +364,22 @@ __device__ __forceinline__ void match_index(const Ctx& c, Sink& sink) {
 
 struct Head {                   // a path's end before this step
   int32_t old_len, new_len;
-  int32_t tail[CSD_MAX_QUERY_LEN];   // tail[a] = a-th token from the old end
+  int32_t tail[kTailCap];       // tail[a] = a-th token from the old end (tail_len of them are kept)
 };
 
-__device__ __forceinline__ int32_t pick(const int32_t (&arr)[CSD_MAX_QUERY_LEN], int32_t idx) {
-  int32_t r = 0;
-#pragma unroll
-  for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) r = (idx == a) ? arr[a] : r;
-  return r;
-}
-
-__device__ __forceinline__ Head load_head(const Paths& y, int32_t kmax, int32_t j) {
+__device__ __forceinline__ Head load_head(const Paths& y, int32_t tail_len, int32_t j) {
   Head h;
-  const int4* m = reinterpret_cast<const int4*>(y.meta_old + (int64_t)j * y.meta_stride);
+  const int32_t* row = y.meta_old + (int64_t)j * y.meta_stride;
+  const int4* m = reinterpret_cast<const int4*>(row);
   int4 a = m[0];
-  int4 b = kmax > 3 ? m[1] : int4{0, 0, 0, 0};
-  int32_t c = kmax > 7 ? y.meta_old[(int64_t)j * y.meta_stride + 8] : 0;
+  int4 b = tail_len > 3 ? m[1] : int4{0, 0, 0, 0};
+  int32_t c8 = tail_len > 7 ? row[8] : 0;
+  int32_t c9 = tail_len > 8 ? row[9] : 0;
   h.old_len = a.x;
   h.tail[0] = a.y; h.tail[1] = a.z; h.tail[2] = a.w;
   h.tail[3] = b.x; h.tail[4] = b.y; h.tail[5] = b.z; h.tail[6] = b.w;
-  h.tail[7] = c;
+  h.tail[7] = c8;
+  h.tail[8] = c9;
   h.new_len = y.new_len(j, h.old_len);
   return h;
 }
@@ -410,7 +412,7 @@ __device__ __forceinline__ void append_own_single(const IndexView& ix, const Pat
                                                   int32_t i, const Head& me, int32_t st_i,
                                                   float sp_i, int lane) {
   int32_t cnt = me.new_len - me.old_len;                 // 0 or 1
-  if (lane <= ix.kmax) {
+  if (lane <= ix.tail_len) {
     int32_t a = lane - 1;
     int32_t v = 0;
     if (lane == 0) v = me.new_len;
@@ -528,8 +530,8 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
   const int64_t row = (int64_t)p * ix.N + c.i;
   int32_t* gram = const_cast<int32_t*>(c.gram);
   // ---- round trip 1: every load here has an address known from the kernel arguments
-  Head me = load_head(y, ix.kmax, c.i);                 // same address in every lane
-  Head hj = load_head(y, ix.kmax, lane < y.N ? lane : 0);
+  Head me = load_head(y, ix.tail_len, c.i);             // same address in every lane
+  Head hj = load_head(y, ix.tail_len, lane < y.N ? lane : 0);
   int32_t st_i = 0;
   float sp_i = 1.0f;
   if (y.n == 1) {
@@ -562,7 +564,7 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
   for (int32_t j0 = 0; j0 < y.N; j0 += kWave) {
     int32_t j = j0 + lane;
     bool have = j < y.N;
-    if (j0 > 0) hj = load_head(y, ix.kmax, have ? j : 0);
+    if (j0 > 0) hj = load_head(y, ix.tail_len, have ? j : 0);
     if (have && j < kLenCache) {
       s.len_old[j] = hj.old_len;
       s.len_new[j] = hj.new_len;
@@ -581,6 +583,273 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
   } else if (c.q > 0) {
     WaveListSink<LDS> sink{&s, &n_match, lane};
     match_scan<kWave, false>(s, c, sink);               // covers old and new positions alike
+    wi.n_fresh = n_match;
+  }
+  if (lane == 0) s.n_match = n_match;
+  return n_match;
+}
+
+// ---------------------------------------------------------------- one edit through the index
+
+// Does a posting found in the chain of the query's variant u — filed there as
+// variant v of the gram G[0 .. q) before its position (newest first, like Q) —
+// count?  It does if the two variants are the same string (chains can share a
+// bucket, and hashes collide) and no earlier variant of the query is a variant
+// of G as well: a position is filed under every distinct variant of its gram,
+// so it turns up once for every variant it shares with the query, and is
+// counted for the first.  (Variant 0: the string itself; w >= 1: without its
+// token w-1.)
+//   Q - a == G - b  (a <= b)  <=>  Q, G agree before a and after b, and
+//                                  Q[x+1] == G[x] for a <= x < b;
+//   Q - a == G - b  (a >  b)  <=>  they agree before b and after a, and
+//                                  Q[x] == G[x+1] for b <= x < a.
+// With P / S the first / last index where Q and G differ, the b that asks
+// least of a given a is max(a, S) in the first case, min(a - 1, P) in the second.
+__device__ __forceinline__ bool variant_counts(const Ctx& c, const int32_t (&G)[CSD_MAX_QUERY_LEN + 1],
+                                               int32_t u, int32_t v) {
+  constexpr int K = CSD_MAX_QUERY_LEN;
+  const int32_t q = c.q;
+  int32_t P = q, S = -1;                                 // first / last mismatch
+  int32_t up[K + 1], down[K + 1];      // failures of Q[x+1]==G[x] / Q[x]==G[x+1] among x < index
+  up[0] = down[0] = 0;
+#pragma unroll
+  for (int x = 0; x < K; ++x) {
+    bool differ = x < q && c.Q[x] != G[x];
+    P = (differ && P == q) ? x : P;
+    S = differ ? x : S;
+    bool in = x + 1 < q;
+    up[x + 1] = up[x] + ((in && c.Q[x + 1 < K ? x + 1 : x] != G[x]) ? 1 : 0);
+    down[x + 1] = down[x] + ((in && c.Q[x] != G[x + 1]) ? 1 : 0);
+  }
+  if (S < 0) return u == 0 && v == 0;                    // the gram is the query: counted there
+  if (u == 0 || v == 0 || v > q) return false;           // strings of different lengths
+  // the same string?
+  const int32_t a0 = u - 1, b0 = v - 1;
+  bool same = a0 <= b0 ? (a0 <= P && b0 >= S && pick(up, b0) == pick(up, a0))
+                       : (b0 <= P && a0 >= S && pick(down, a0) == pick(down, b0));
+  // an earlier variant of the query that G shares?
+  bool earlier = false;
+#pragma unroll
+  for (int a = 0; a < K; ++a) {
+    if (a >= q) continue;
+    int32_t b1 = a > S ? a : S;                          // Q - a == G - b1 ?
+    bool first = a <= P && pick(up, b1) == up[a];
+    int32_t b2 = a - 1 < P ? a - 1 : P;                  // Q - a == G - b2 ?
+    bool second = a >= 1 && a >= S && down[a] == pick(down, b2);
+    earlier = earlier || (a < a0 && (first || second));
+  }
+  return same && !earlier;
+}
+
+// One batch of the variant lookup: this lane's word of a bucket (word 0 = fill
+// count, held by the first lane of each group of 16; -1 everywhere for an idle
+// group).  Every posting fetches the tokens the predicate looks at together
+// with its continuation (one round trip, as in lookup_with_windows); a verified
+// position counts once, whichever variants led to it (my_u: the variant whose
+// chain this bucket belongs to).  Returns whether the group's bucket was full
+// (its chain goes on).
+template <int LCAP, class LDS>
+__device__ __forceinline__ bool consume_variant_bucket(LDS& s, const Ctx& c, int32_t L,
+                                                       int32_t win_cap, int32_t n_fresh,
+                                                       int32_t& n_match, int32_t my_u,
+                                                       int32_t word) {
+  constexpr int K = CSD_MAX_QUERY_LEN;
+  const int lane = c.tid;
+  const Paths& y = c.y;
+  const int sub = lane & 15;          // word of the bucket this lane reads
+  int32_t count = __shfl(word, lane & ~15);
+  bool full = count >= kBucketSlots;
+  bool cand = sub >= 1 && word >= 0 && (sub - 1) < (full ? kBucketSlots : count);
+  const int32_t filed_as = word >> kVariantShift;       // variant of its gram the posting stands for
+  const int32_t pos = word & ((1 << kVariantShift) - 1);
+  int32_t j = y.pos_path(pos), e = y.pos_index(pos), old_j = 0, new_j = 0;
+  cand = cand && j != c.i && j < y.N && e >= c.q;       // postings are filed for e >= kmax only
+  if (cand) {
+    lens_of(s, y, j, old_j, new_j);
+    cand = e < old_j;                 // newer positions are matched directly, not looked up
+  }
+  int32_t tv[K + 1];
+  int32_t wv[LCAP];
+  uint32_t wp[LCAP];
+#pragma unroll
+  for (int a = 0; a <= K; ++a) tv[a] = 0;
+#pragma unroll
+  for (int d = 0; d < LCAP; ++d) {
+    wv[d] = 0;
+    wp[d] = 0;
+  }
+  int32_t rem = 0, n_hist = 0;
+  if (cand) {
+    const int32_t* hrow = y.tok + y.cell(j, e);          // history of path j at the posting
+    const uint32_t* prow = y.pq + y.cell(j, e);
+#pragma unroll
+    for (int a = 0; a <= K; ++a)                         // e >= q: only token q may not exist
+      if (a <= c.q) tv[a] = hrow[a < e ? -1 - a : -1];
+    rem = new_j - e;
+    rem = rem < L ? rem : L;
+    n_hist = old_j - e;               // >= 1: continuation tokens that are already history
+    n_hist = n_hist < rem ? n_hist : rem;
+#pragma unroll
+    for (int d = 0; d < LCAP; ++d)
+      if (d < n_hist) {
+        wv[d] = hrow[d];
+        wp[d] = prow[d];
+      }
+#pragma unroll
+    for (int a = 0; a <= K; ++a) tv[a] = (a <= c.q && a < e) ? tv[a] : 0;
+  }
+  // each position once: for the first variant it shares with the query
+  bool hit = cand && near_query(c, e, tv) && variant_counts(c, tv, my_u, filed_as);
+  if (__ballot(hit && rem > n_hist) != 0) {              // rare: runs into this step's new tokens
+#pragma unroll
+    for (int d = 0; d < LCAP; ++d)
+      if (hit && d >= n_hist && d < rem) {
+        wv[d] = y.token(j, e + d, old_j);
+        wp[d] = y.prob(j, e + d, old_j);
+      }
+  }
+  int32_t slot = wave_push(s, n_match, hit, make_match(y, j, e, old_j, new_j), lane);
+  int32_t w = slot - n_fresh;
+  if (slot >= 0 && w < win_cap) {
+    int32_t* win = s.win + w * 2 * L;
+#pragma unroll
+    for (int d = 0; d < LCAP; ++d)
+      if (d < rem) {
+        win[d] = wv[d];
+        win[L + d] = (int32_t)wp[d];
+      }
+  }
+  return full;
+}
+
+// Eq. 4 (one edit) through the index.  Bucket 0 of the chains of four of the
+// query's variants is read at a time, one variant per group of 16 lanes; a
+// chain that goes on is then walked by the whole wave, four buckets per batch
+// with the next batch in flight (reading past the end of a chain is harmless:
+// buckets behind the first one that is not full are empty).  `word` is the
+// lane's word of bucket 0 of its group's first variant, already requested.
+template <int LCAP, class LDS>
+__device__ __forceinline__ void lookup_variants_with_windows(LDS& s, const Ctx& c, int32_t L,
+                                                             int32_t win_cap, int32_t n_fresh,
+                                                             int32_t& n_match, int32_t word) {
+  const int lane = c.tid;
+  int32_t* tbl = const_cast<int32_t*>(c.gram);
+  const int sub = lane & 15;
+  const int grp = lane >> 4;
+  const uint32_t n_buckets = c.bucket_mask + 1;
+  for (int32_t pass = 0; pass * 4 <= c.q; ++pass) {
+    const int32_t u = pass * 4 + grp;
+    const bool active = u <= c.q && variant_is_new(c.Q, u);
+    if (pass > 0) word = gram_bucket(tbl, variant_hash(c.Q, c.q, u), 0u, c.bucket_mask)[sub];
+    consume_here(word);
+    if (!active) word = -1;           // idle groups see an empty bucket
+    bool full = consume_variant_bucket<LCAP>(s, c, L, win_cap, n_fresh, n_match, u, word);
+    const u64 goes_on = __ballot(active && full && sub == 0);       // bit 16 g: group g's chain
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      if ((goes_on >> (16 * g) & 1ull) == 0) continue;              // uniform over the wave
+      const GramHash gh = variant_hash(c.Q, c.q, pass * 4 + g);     // the same in every lane
+      uint32_t r0 = 1;
+      int32_t tail = gram_bucket(tbl, gh, r0 + grp < n_buckets ? r0 + grp : 0u, c.bucket_mask)[sub];
+      for (; r0 < n_buckets; r0 += 4) {
+        consume_here(tail);
+        if (r0 + grp >= n_buckets) tail = -1;
+        uint32_t rn = r0 + 4 + grp;                                 // next batch: in flight meanwhile
+        int32_t next_tail = gram_bucket(tbl, gh, rn < n_buckets ? rn : 0u, c.bucket_mask)[sub];
+        bool tail_full = consume_variant_bucket<LCAP>(s, c, L, win_cap, n_fresh, n_match,
+                                                      pass * 4 + g, tail);
+        if (__ballot(!tail_full) != 0) break;                       // the chain ends in this batch
+        tail = next_tail;
+      }
+    }
+  }
+}
+
+// The front end of a row handled by one wave when matching tolerates one edit
+// and the index files every position under its gram's variants.  Same three
+// round trips as wave_front_end.  Matched directly, without the index: the
+// position this launch appends to each other path (from the old tails, which
+// keep kmax + 1 tokens for that) and position kmax - 1 of each other path (the
+// only one with fewer than kmax tokens before it that can match a kmax-token
+// query).  Returns the number of matches.
+template <int LCAP, class LDS>
+__device__ __forceinline__ int32_t wave_front_end_fuzzy(LDS& s, Ctx& c, const IndexView& ix,
+                                                        int32_t p, int32_t k, int32_t L, WinInfo& wi,
+                                                        VariantTicket& ticket, bool& ticket_used) {
+  constexpr int K = CSD_MAX_QUERY_LEN;
+  const int lane = c.tid;
+  const Paths& y = c.y;
+  const int64_t row = (int64_t)p * ix.N + c.i;
+  int32_t* gram = const_cast<int32_t*>(c.gram);
+  // ---- round trip 1: every load here has an address known from the kernel arguments
+  Head me = load_head(y, ix.tail_len, c.i);             // same address in every lane
+  Head hj = load_head(y, ix.tail_len, lane < y.N ? lane : 0);
+  int32_t first_tokens[K];                              // tokens kmax-2 .. 0 of path `lane`, newest first
+#pragma unroll
+  for (int a = 0; a < K; ++a)
+    first_tokens[a] = y.tok[y.cell(lane < y.N ? lane : 0, a < ix.kmax - 1 ? ix.kmax - 2 - a : 0)];
+  int32_t st_i = 0;
+  float sp_i = 1.0f;
+  if (y.n == 1) {
+    st_i = y.st[c.i];
+    if (y.sp) sp_i = y.sp[c.i];
+  }
+  const int32_t old_i = me.old_len, cnt_i = me.new_len - me.old_len;
+  c.len_i = me.new_len;
+  c.q = k < c.len_i ? k : c.len_i;
+#pragma unroll
+  for (int a = 0; a < K; ++a) {
+    int32_t v = 0;
+    if (a < c.q) v = a < cnt_i ? st_i : pick(me.tail, a - cnt_i);
+    c.Q[a] = v;
+  }
+  const bool use_index = c.q == ix.kmax;                // shorter queries: scan (short paths)
+  // ---- round trip 2 is requested: fill counts for the insert, bucket 0 of the first 4 variants
+  ticket_used = cnt_i == 1;
+  if (ticket_used) ticket = variants_begin(gram, c.bucket_mask, ix.kmax, me.tail, old_i, lane);
+  int32_t word = -1;
+  if (use_index)
+    word = gram_bucket(gram, variant_hash(c.Q, c.q, lane >> 4), 0u, c.bucket_mask)[lane & 15];
+  // ---- while it travels: own append, lengths into LDS, matches that need no index
+  if (y.n == 1) append_own_single(ix, y, row, c.i, me, st_i, sp_i, lane);
+  int32_t n_match = 0;
+  for (int32_t j0 = 0; j0 < y.N; j0 += kWave) {
+    int32_t j = j0 + lane;
+    bool have = j < y.N;
+    if (j0 > 0) {
+      hj = load_head(y, ix.tail_len, have ? j : 0);
+#pragma unroll
+      for (int a = 0; a < K; ++a)
+        first_tokens[a] = y.tok[y.cell(have ? j : 0, a < ix.kmax - 1 ? ix.kmax - 2 - a : 0)];
+    }
+    if (have && j < kLenCache) {
+      s.len_old[j] = hj.old_len;
+      s.len_new[j] = hj.new_len;
+    }
+    const bool other = use_index && have && j != c.i;
+    int32_t t[K + 1];
+    // the position appended by this very launch: the tokens before it are the old tail
+#pragma unroll
+    for (int a = 0; a <= K; ++a) t[a] = (a <= c.q && a < hj.old_len) ? hj.tail[a] : 0;
+    bool hit = other && hj.new_len > hj.old_len && near_query(c, hj.old_len, t);
+    wave_push(s, n_match, hit, make_match(y, j, hj.old_len, hj.old_len, hj.new_len), lane);
+    // position kmax - 1, if it is history: no posting exists for it
+#pragma unroll
+    for (int a = 0; a <= K; ++a) t[a] = (a < K && a < ix.kmax - 1) ? first_tokens[a < K ? a : 0] : 0;
+    hit = other && ix.kmax - 1 < hj.old_len && near_query(c, ix.kmax - 1, t);
+    wave_push(s, n_match, hit, make_match(y, j, ix.kmax - 1, hj.old_len, hj.new_len), lane);
+  }
+  if (ticket_used) {
+    variants_claim(ticket, gram, c.bucket_mask, lane);                  // round trip 3 starts
+    variants_beyond_four(ticket, gram, c.bucket_mask, ix.kmax, me.tail, y.pos(c.i, old_i), lane);
+  }
+  wi.n_fresh = n_match;
+  wi.win_cap = use_index ? LDS::kWin / (2 * L) : 0;
+  if (use_index) {
+    lookup_variants_with_windows<LCAP>(s, c, L, wi.win_cap, wi.n_fresh, n_match, word);
+  } else if (c.q > 0) {
+    WaveListSink<LDS> sink{&s, &n_match, lane};
+    match_scan<kWave, true>(s, c, sink);                // covers old and new positions alike
     wi.n_fresh = n_match;
   }
   if (lane == 0) s.n_match = n_match;

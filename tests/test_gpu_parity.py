@@ -163,8 +163,8 @@ def _one_shot(oracle, paths, probs, k, L, alpha=1.0, mode=0, flags=None, fused=F
     if flags is None:
         for f in (SCAN, INDEX):
             for fu in (False, True):
-                if eps and f == INDEX:
-                    continue                    # fuzzy matching is found by scan
+                if eps and f == INDEX and k < 2:
+                    continue                    # one-token queries with one edit are found by scan
                 res = _one_shot(oracle, paths, probs, k, L, alpha, mode, f, fu, pool_mode, eps)
         return res
     N = len(paths)
@@ -342,15 +342,15 @@ def _fuzzy_replay(oracle, w, check_every, hows, dump_at=(), edges=True):
                                                k, L, 1.0, 0)["draft_len"] > 0).sum()) for t in steps[::4])
     fuzzy_nonempty = sum(int((want[t]["draft_len"] > 0).sum()) for t in steps[::4])
     assert fuzzy_nonempty > exact_nonempty           # the tolerance finds more
-    for how in hows:
-        print("fuzzy replay", w.name, how, flush=True)
-        got = gpu_replay(tokens, probs, k, L, 1.0, 0, 0, how=how, max_edits=1)
+    for flags, how in hows:          # INDEX: the variant index; SCAN: exhaustive comparison
+        print("fuzzy replay", w.name, flags, how, flush=True)
+        got = gpu_replay(tokens, probs, k, L, 1.0, 0, flags, how=how, max_edits=1)
         assert got["status"] == 0
         for t in steps:
-            assert_step_equal(got, want[t], t, "fuzzy %s %s" % (w.name, how))
+            assert_step_equal(got, want[t], t, "fuzzy %s %d %s" % (w.name, flags, how))
     dev = torch.device("cuda:0")
-    for t in dump_at:
-        ix = binding.Index(w.n_problems, w.n_paths, T, w.vocab, k, L, 1.0, 0, 0, device=dev, max_edits=1)
+    for flags, t in [(f, t) for f in (INDEX, SCAN) for t in dump_at]:
+        ix = binding.Index(w.n_problems, w.n_paths, T, w.vocab, k, L, 1.0, 0, flags, device=dev, max_edits=1)
         ix.append(torch.from_numpy(np.ascontiguousarray(tokens[:, :, :t])).to(dev),
                   torch.from_numpy(np.ascontiguousarray(probs[:, :, :t])).to(dev), None, t)
         lens_t = np.full(tokens.shape[:2], t, dtype=np.int32)
@@ -367,11 +367,19 @@ def _fuzzy_replay(oracle, w, check_every, hows, dump_at=(), edges=True):
 
 
 def test_fuzzy_c1_every_step(oracle):
-    _fuzzy_replay(oracle, synth.WORKLOADS["C1"], 1, ("replay", "calls"), dump_at=(7, 256))
+    _fuzzy_replay(oracle, synth.WORKLOADS["C1"], 1,
+                  ((INDEX, "replay"), (INDEX, "calls"), (SCAN, "replay"), (SCAN, "calls")), dump_at=(7, 256))
 
 
 def test_fuzzy_c2_sampled_steps(oracle):
-    _fuzzy_replay(oracle, synth.WORKLOADS["C2"], 32, ("replay",), dump_at=(300,), edges=False)
+    _fuzzy_replay(oracle, synth.WORKLOADS["C2"], 32, ((INDEX, "replay"), (SCAN, "replay"), (INDEX, "step")),
+                  dump_at=(300,), edges=False)
+
+
+def test_fuzzy_c3_longer_query_through_the_index(oracle):
+    # query of 4 tokens: five gram variants per position, the fifth filed by the general insert
+    _fuzzy_replay(oracle, synth.scaled(synth.WORKLOADS["C3"], max_len=512), 16, ((INDEX, "replay"),),
+                  dump_at=(200,), edges=False)
 
 
 def test_fuzzy_small_cases(oracle):
@@ -389,21 +397,21 @@ def test_fuzzy_small_cases(oracle):
         n = int(rng.integers(2, 6))
         cases.append(([rng.integers(0, 3, size=int(rng.integers(0, 48))).tolist() for _ in range(n)],
                       int(rng.integers(1, 9)), int(rng.integers(1, 6))))
-    for paths, k, L in cases:
+    for (paths, k, L), flags in [(c, f) for c in cases for f in ((INDEX if c[1] >= 2 else 0), SCAN)]:
         N, T = len(paths), max(1, max(len(p) for p in paths))
         tok = np.zeros((1, N, T), dtype=np.int32)
         cnt = np.array([[len(p) for p in paths]], dtype=np.int32)
         for j, p in enumerate(paths):
             tok[0, j, :len(p)] = p
         pr = (rng.integers(1, 9, size=tok.shape) / 8.0).astype(np.float32)
-        ix = binding.Index(1, N, T, 64, k, L, 0.5, 0, 0, device=dev, max_edits=1)
+        ix = binding.Index(1, N, T, 64, k, L, 0.5, 0, flags, device=dev, max_edits=1)
         ix.append(torch.from_numpy(tok).to(dev), torch.from_numpy(pr).to(dev), torch.from_numpy(cnt).to(dev), T)
         out = ix.draft(k, L)
         want = oracle.draft_all(tok, pr, cnt, k, L, 0.5, 0, eps=1)
         got = dict(draft=out["tokens"].cpu().numpy()[None], draft_len=out["length"].cpu().numpy()[None],
                    token_scores=out["token_scores"].cpu().numpy()[None],
                    path_scores=out["path_scores"].cpu().numpy()[None])
-        assert_step_equal(got, want, 0, "fuzzy case %s k=%d L=%d" % (paths, k, L))
+        assert_step_equal(got, want, 0, "fuzzy case %s k=%d L=%d flags=%d" % (paths, k, L, flags))
         je, off = ix.dump_matches(k)
         for i in range(N):
             assert np.array_equal(je[off[i]:off[i + 1]], oracle.matches(tok[0], cnt[0], i, k, 1)), (paths, k, i)
@@ -418,15 +426,15 @@ def test_fuzzy_ragged_multi_token_steps(oracle):
     steps = w.max_len // 2
     counts = synth.make_ragged_counts(w, 4, steps)
     want = None
-    for how in ("step", "calls"):
-        got = gpu_replay(tokens, probs, w.query_len, w.draft_len, steps=steps, counts=counts,
+    for flags, how in ((SCAN, "step"), (SCAN, "calls"), (INDEX, "step"), (INDEX, "calls")):
+        got = gpu_replay(tokens, probs, w.query_len, w.draft_len, flags=flags, steps=steps, counts=counts,
                          n_per_step=4, how=how, max_edits=1)
         assert got["status"] in (0, binding.STATUS_CAPACITY)
         if want is None:
             want = [oracle.draft_all(tokens, probs, got["lens"][t], w.query_len, w.draft_len, 1.0, 0, eps=1)
                     for t in range(steps)]
         for t in range(steps):
-            assert_step_equal(got, want[t], t, "fuzzy ragged %s" % how)
+            assert_step_equal(got, want[t], t, "fuzzy ragged %d %s" % (flags, how))
 
 
 # ---------------------------------------------------------------- tree and list pools (the ablation's variants)
