@@ -56,21 +56,27 @@ constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-  size_t tok, pq, meta, status, gram, total;
+  size_t tok, pq, meta, status, gram, slices, total;
+  int32_t n_slices;             // workgroups that share a row's scan (scan mode, few rows)
   int32_t meta_stride, eshift;
   uint32_t n_buckets;           // per (problem, gram length); 0 in scan mode
   size_t gram_words;
 };
 
+// Rows (problem, path) up to which a row's scan is shared by several workgroups.
+constexpr int64_t kSlicedScanRows = 128;
+
 // One-edit matching can go through the index when the query has at least two tokens (with
 // one token every position is within one edit: a scan's job).  The index files positions
 // under grams of max_query_len - 1 tokens then; for three-token queries those are pairs,
-// the chains of frequent pairs get long, and the scan is the faster matcher: CSD_MATCH_AUTO
-// takes the index from four tokens on.
+// the chains of frequent pairs get long, and the scan is the faster matcher; with few rows
+// the sliced scan is as fast as the index for longer queries too.  CSD_MATCH_AUTO therefore
+// takes the index from four query tokens on when there are too many rows to slice the scan.
 bool uses_index(const csd_config* c) {
   if (c->flags == CSD_MATCH_SCAN) return false;
   if (c->max_edits == 0) return true;
-  return c->max_query_len >= (c->flags == CSD_MATCH_INDEX ? 2 : 4);
+  if (c->flags == CSD_MATCH_INDEX) return c->max_query_len >= 2;
+  return c->max_query_len >= 4 && (int64_t)c->n_problems * c->n_paths > kSlicedScanRows;
 }
 int32_t tail_len_of(const csd_config* c) {
   return c->max_query_len + ((uses_index(c) && c->max_edits > 0) ? 1 : 0);
@@ -121,6 +127,17 @@ Layout make_layout(const csd_config* c) {
     l.gram_words = (size_t)c->n_problems * nb * kBucketWords;
     at += align_up(l.gram_words * sizeof(int32_t));
   }
+  // scan mode with few rows: a row's scan is shared by up to 8 workgroups (at most 256 in all)
+  l.n_slices = 1;
+  l.slices = at;
+  // (the hand-over between the slices costs about 5 us: worth it for one-edit matching and
+  // for long histories)
+  if (!uses_index(c) && rows <= (size_t)kSlicedScanRows &&
+      (c->max_edits > 0 || (int64_t)c->n_paths * c->max_len >= 32768)) {
+    while (l.n_slices < 8 && rows * (size_t)l.n_slices * 2 <= 256) l.n_slices *= 2;
+    if (l.n_slices > 1)
+      at += align_up(rows * LdsScan::kMatch * sizeof(Match)) + 2 * align_up(rows * sizeof(int32_t));
+  }
   l.total = at;
   return l;
 }
@@ -139,6 +156,7 @@ struct csd_index {
   int32_t* meta[2];             // double-buffered path ends (length + tail); `cur` is valid
   int cur;
   size_t gram_words;
+  ScanSlices slices;
   bool indexed;
   uint32_t alpha_q;
   int64_t len_lo, len_hi;       // host-side bounds on every path's length
@@ -168,21 +186,24 @@ void launch_draft(const csd_index* h, const IndexView& v, const StepIn& in, cons
                   hipStream_t st) {
   int64_t rows = (int64_t)v.P * v.N;
   const uint32_t grid = xcd_grid(rows);
+  // scan mode, few rows: n_slices workgroups per row, the rows dealt to the 8 XCDs
+  const ScanSlices sl = h->slices;
+  const uint32_t scan_grid = sl.n > 1 ? (uint32_t)((rows + 7) / 8 * sl.n * 8) : grid;
   if (h->indexed && v.eps > 0) {                         // one edit through the variant index
     if (a.L <= 8) step_wave_kernel<8, true, LdsWaveFuzzy, true><<<grid, kWave, 0, st>>>(v, in, a);
     else if (a.L <= 16) step_wave_kernel<16, true, LdsWaveFuzzy, true><<<grid, kWave, 0, st>>>(v, in, a);
     else step_wave_kernel<32, true, LdsWaveFuzzy, true><<<grid, kWave, 0, st>>>(v, in, a);
   } else if (a.pool_mode != CSD_POOL_DAG) {             // tree and list pools: the general kernels
-    if (!h->indexed) step_scan_kernel<1, true><<<grid, kScanBlock, 0, st>>>(v, in, a);
+    if (!h->indexed) step_scan_kernel<1, true><<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
     else if (a.L <= 8) step_wave_kernel<8, true, LdsWave, false><<<grid, kWave, 0, st>>>(v, in, a);
     else if (a.L <= 16) step_wave_kernel<16, true, LdsWave, false><<<grid, kWave, 0, st>>>(v, in, a);
     else step_wave_kernel<32, true, LdsWave, false><<<grid, kWave, 0, st>>>(v, in, a);
   } else if (!h->indexed && a.L <= 8)
-    step_scan_kernel<8, false><<<grid, kScanBlock, 0, st>>>(v, in, a);
+    step_scan_kernel<8, false><<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
   else if (!h->indexed && a.L <= 16)
-    step_scan_kernel<16, false><<<grid, kScanBlock, 0, st>>>(v, in, a);
+    step_scan_kernel<16, false><<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
   else if (!h->indexed)     // longer drafts: the walk's register-resident fast path is left out
-    step_scan_kernel<1, false><<<grid, kScanBlock, 0, st>>>(v, in, a);
+    step_scan_kernel<1, false><<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
   else if (a.L <= 8 && rows >= kSmallLdsRows)   // more rows than fit the chip at once
     step_wave_kernel<8, false, LdsWaveSmall, false><<<grid, kWave, 0, st>>>(v, in, a);
   else if (a.L <= 8)
@@ -244,6 +265,14 @@ int csd_create(const csd_config* cfg, void* d_workspace, size_t workspace_bytes,
   h->view.gram = h->indexed ? reinterpret_cast<int32_t*>(base + l.gram) : nullptr;
   h->view.bucket_mask = h->indexed ? l.n_buckets - 1 : 0;
   h->gram_words = l.gram_words;
+  h->slices = ScanSlices{l.n_slices, nullptr, nullptr, nullptr};
+  if (l.n_slices > 1) {
+    h->slices.matches = reinterpret_cast<Match*>(base + l.slices);
+    h->slices.count = reinterpret_cast<int32_t*>(base + l.slices +
+                                                 align_up(rows * LdsScan::kMatch * sizeof(Match)));
+    h->slices.ticket = reinterpret_cast<uint32_t*>(
+        reinterpret_cast<char*>(h->slices.count) + align_up(rows * sizeof(int32_t)));
+  }
   h->view.P = cfg->n_problems;
   h->view.N = cfg->n_paths;
   h->view.max_len = cfg->max_len;
@@ -273,7 +302,7 @@ int csd_reset(csd_index* h, void* stream) {
   int64_t blocks = (work + 255) / 256;
   if (blocks > 4096) blocks = 4096;
   reset_kernel<<<(uint32_t)blocks, 256, 0, as_stream(stream)>>>(view_in_place(h),
-                                                                 (int64_t)h->gram_words);
+                                                                 (int64_t)h->gram_words, h->slices);
   CSD_HIP(hipGetLastError());
   h->len_lo = h->len_hi = 0;
   return CSD_OK;

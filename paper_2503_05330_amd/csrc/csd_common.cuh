@@ -151,6 +151,19 @@ struct IndexView {              // device state inside the caller's workspace
   int32_t eps;                  // edit tolerance (0 = exact match)
 };
 
+struct Match;
+
+// A row's scan shared by several workgroups ("slices"), all on one XCD: every
+// slice adds the matches it finds to the row's list in memory; the slice that
+// finishes last (a ticket counter tells it; nobody waits) goes on with the
+// whole list.  n == 1: one workgroup per row, nothing of this is used.
+struct ScanSlices {
+  int32_t n;                    // slices per row (power of two)
+  Match* matches;               // [rows][LdsScan::kMatch]
+  int32_t* count;               // [rows] matches listed so far; the last slice zeroes it again
+  uint32_t* ticket;             // [rows] slices finished, over all launches
+};
+
 struct StepIn {                 // tokens a step appends; n == 0: none
   const int32_t* tok;           // [P][N][n]
   const float* prob;            // [P][N][n] or null

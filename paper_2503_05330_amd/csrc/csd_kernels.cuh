@@ -10,10 +10,15 @@
 
 namespace csd {
 
-__global__ __launch_bounds__(256) void reset_kernel(IndexView ix, int64_t gram_words) {
+__global__ __launch_bounds__(256) void reset_kernel(IndexView ix, int64_t gram_words, ScanSlices sl) {
   int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
   int64_t stride = (int64_t)gridDim.x * 256;
   int64_t rows = (int64_t)ix.P * ix.N;
+  if (sl.n > 1)
+    for (int64_t r = t; r < rows; r += stride) {
+      sl.count[r] = 0;
+      sl.ticket[r] = 0u;
+    }
   for (int64_t r = t; r < rows * ix.meta_stride; r += stride) ix.meta_new[r] = 0;
   for (int64_t w = t; w < gram_words; w += stride) ix.gram[w] = (w & (kBucketWords - 1)) ? -1 : 0;
   if (t == 0) *ix.status = 0u;
@@ -75,12 +80,24 @@ __device__ __forceinline__ void cache_lens(LDS& s, const Paths& y, int tid) {
 // workgroup barrier is needed per tile as staging through LDS would.
 // POOLS: also compiled for the tree and list pools (kept out of the DAG-only
 // kernels, whose code and register footprint they would enlarge).
+// With sl.n > 1 a row's scan is shared by sl.n workgroups (few rows: the scan is
+// bound by instruction issue on the row's CU, and most CUs would be idle); the
+// one that finishes last does the rest of the row's work.
 template <int LCAP, bool POOLS>
 __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, StepIn in,
-                                                               DraftArgs a) {
+                                                               DraftArgs a, ScanSlices sl) {
   constexpr int BLOCK = kScanBlock;
   __shared__ LdsScan s;
-  int32_t row = xcd_row(ix.P * ix.N);
+  __shared__ int32_t sh_base, sh_total, sh_last;
+  int32_t row, slice = 0;
+  if (sl.n == 1) {
+    row = xcd_row(ix.P * ix.N);
+  } else {                              // XCD x takes rows x, x + 8, ..: a row's slices share an L2
+    int32_t idx = (int32_t)(blockIdx.x >> 3);
+    slice = idx & (sl.n - 1);
+    row = (idx / sl.n) * 8 + (int32_t)(blockIdx.x & 7);
+    if (row >= ix.P * ix.N) row = -1;
+  }
   if (row < 0) return;
   int32_t p;
   Ctx c = make_ctx(ix, in, row, p);
@@ -89,7 +106,7 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
   const int32_t old_i = me.old_len;
   c.len_i = me.new_len;
   cache_lens<BLOCK>(s, c.y, c.tid);
-  if (in.n > 0) append_row<BLOCK, true>(ix, c.y, p, c.i, old_i, c.len_i, c.tid);
+  if (in.n > 0 && slice == 0) append_row<BLOCK, true>(ix, c.y, p, c.i, old_i, c.len_i, c.tid);
   if (in.n <= 1) {                                       // the query follows from what is loaded
     int32_t cnt_i = c.len_i - old_i;
     c.q = a.k < c.len_i ? a.k : c.len_i;
@@ -109,9 +126,34 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
   const int32_t L = a.L;
   if (c.q > 0) {
     ListSink<LdsScan> sink{&s};
-    match_scan_any<BLOCK>(s, c, sink);
+    match_scan_any<BLOCK>(s, c, sink, slice, sl.n);
     block_sync<BLOCK>();
     int32_t M = s.n_match;
+    if (sl.n > 1) {
+      // hand this slice's matches to the row's list in memory
+      Match* listed = sl.matches + (int64_t)row * LdsScan::kMatch;
+      if (c.tid == 0) sh_base = atomicAdd(&sl.count[row], M);
+      block_sync<BLOCK>();
+      for (int32_t m = c.tid; m < M && m < LdsScan::kMatch; m += BLOCK)
+        if (sh_base + m < LdsScan::kMatch) listed[sh_base + m] = s.match[m];
+      block_sync<BLOCK>();              // every wave's stores have left the CU
+      if (c.tid == 0) {
+        // one wave fences for the workgroup (a device-scope fence writes the L2 back: sixteen
+        // of them in a row cost more than the scan): list entries before ticket, ticket
+        // before the reads below
+        __threadfence();
+        uint32_t drawn = atomicAdd(&sl.ticket[row], 1u);
+        sh_last = (drawn & (uint32_t)(sl.n - 1)) == (uint32_t)(sl.n - 1);
+        sh_total = sh_last ? atomicExch(&sl.count[row], 0) : 0;   // the next launch starts at 0
+        __threadfence();
+      }
+      block_sync<BLOCK>();
+      if (!sh_last) return;             // the last slice goes on with all matches of the row
+      M = sh_total;
+      for (int32_t m = c.tid; m < M && m < LdsScan::kMatch; m += BLOCK) s.match[m] = listed[m];
+      if (c.tid == 0) s.n_match = M;
+      block_sync<BLOCK>();
+    }
     if (POOLS && M > 0 && a.pool_mode != CSD_POOL_DAG) {
       auto each = [&](auto f) {
         if (M <= LdsScan::kMatch) {

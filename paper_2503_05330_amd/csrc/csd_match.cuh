@@ -198,15 +198,18 @@ __device__ __forceinline__ bool may_match(const Ctx& c, const int32_t (&t)[kFilt
 // does not settle the answer, and for the few positions it does not cover (the
 // first three of a path, which are only pre-filtered, and those that touch
 // tokens this launch appends), the full comparison runs once per round for the
-// lanes' next candidate, until no lane of the wave has one left.  Hits are pushed in no particular order; every wave
-// runs its own trip counts (push() is a wave-level operation).
+// lanes' next candidate, until no lane of the wave has one left.  Hits are
+// pushed in no particular order; every wave runs its own trip counts (push() is
+// a wave-level operation).  A row's scan can be shared by n_slices workgroups:
+// this one, number `slice`, takes every n_slices-th share of the spans.
 template <int BLOCK, bool FUZZY, class LDS, class Sink>
-__device__ __forceinline__ void match_scan(const LDS& s, const Ctx& c, Sink& sink) {
-  constexpr int kWaves = BLOCK / kWave;
+__device__ __forceinline__ void match_scan(const LDS& s, const Ctx& c, Sink& sink, int32_t slice = 0,
+                                           int32_t n_slices = 1) {
+  const int32_t n_waves = (BLOCK / kWave) * n_slices;       // waves that share the row
   constexpr int kPerLane = 4;                              // consecutive positions of a lane
   constexpr int kSpan = kWave * kPerLane;                  // positions of a span
   constexpr int kSpans = 4;                                // spans in flight: 16 candidate bits
-  const int lane = c.tid & 63, wave = c.tid >> 6;
+  const int lane = c.tid & 63, wave = slice * (BLOCK / kWave) + (c.tid >> 6);
   const int32_t first_e = FUZZY ? (c.q > 1 ? c.q - 1 : 0) : c.q;   // shortest substring that can match
   const int32_t spans_per_path = (c.y.max_len + kSpan - 1) / kSpan;
   const int32_t spans = c.y.N * spans_per_path;            // < 2^24
@@ -219,14 +222,14 @@ __device__ __forceinline__ void match_scan(const LDS& s, const Ctx& c, Sink& sin
     j -= j * spans_per_path > g;
     e0 = (g - j * spans_per_path) * kSpan + lane * kPerLane;
   };
-  for (int32_t g0 = wave; g0 < spans; g0 += kWaves * kSpans) {
+  for (int32_t g0 = wave; g0 < spans; g0 += n_waves * kSpans) {
     int32_t w[kSpans][2 * kFilterTokens];                  // tokens e0 - 3 .. e0 + 2 (first lane: 0 .. 5)
     // bit 4u + r, for position r of span u: is a candidate / was filtered / lies among the
     // first three of its path; bit u of firsts: this lane starts span u's path
     uint32_t todo = 0, filtered = 0, early = 0, firsts = 0;
 #pragma unroll
     for (int u = 0; u < kSpans; ++u) {
-      int32_t g = g0 + u * kWaves, j, e0, old_j = 0, new_j = 0;
+      int32_t g = g0 + u * n_waves, j, e0, old_j = 0, new_j = 0;
       locate(g, j, e0);
       bool on = g < spans && j != c.i;                     // uniform over the wave
       if (on) lens_of(s, c.y, j, old_j, new_j);
@@ -280,7 +283,7 @@ __device__ __forceinline__ void match_scan(const LDS& s, const Ctx& c, Sink& sin
       int32_t bit = have ? (int32_t)__ffs(todo) - 1 : 0;
       todo &= todo - 1u;                                   // 0 stays 0
       int32_t j, e, old_j = 1, new_j = 1;
-      locate(g0 + (bit >> 2) * kWaves, j, e);
+      locate(g0 + (bit >> 2) * n_waves, j, e);
       e += bit & 3;
       bool hit = have;
       if (have) lens_of(s, c.y, j, old_j, new_j);
@@ -293,9 +296,10 @@ __device__ __forceinline__ void match_scan(const LDS& s, const Ctx& c, Sink& sin
 
 // The scan with the configured tolerance.
 template <int BLOCK, class LDS, class Sink>
-__device__ __forceinline__ void match_scan_any(const LDS& s, const Ctx& c, Sink& sink) {
-  if (c.eps == 0) match_scan<BLOCK, false>(s, c, sink);
-  else match_scan<BLOCK, true>(s, c, sink);
+__device__ __forceinline__ void match_scan_any(const LDS& s, const Ctx& c, Sink& sink,
+                                               int32_t slice = 0, int32_t n_slices = 1) {
+  if (c.eps == 0) match_scan<BLOCK, false>(s, c, sink, slice, n_slices);
+  else match_scan<BLOCK, true>(s, c, sink, slice, n_slices);
 }
 
 // Eq. 3 through the hash index, by ONE wave, in its general form (any number
