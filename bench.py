@@ -37,10 +37,10 @@ def algorithmic_bytes(n_paths, k, L, kmax, matches_per_step):
     return n_paths * b_path + matches_per_step * b_match
 
 
-def measured_traffic(workload):
+def measured_traffic(kernel, workload):
     """HBM bytes per launch of the step kernel from the committed rocprofv3 counter runs
     (FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy kernel of known size)."""
-    path = os.path.join(ROOT, "profiles", "step_wave_kernel_%s_traffic.json" % workload)
+    path = os.path.join(ROOT, "profiles", "%s_%s_traffic.json" % (kernel, workload))
     try:
         with open(path) as f:
             return json.load(f)["traffic_bytes_per_launch"]
@@ -219,6 +219,12 @@ def main():
     b_step = algorithmic_bytes(N * P, k, L, k, matches_per_step)
     achieved = b_step / (launch_ms * 1e-3) / 1e9
 
+    # which kernel the configuration runs (the library's choice, mirrored here for the report)
+    rows = P * N
+    by_scan = args.matcher == "scan" or (args.max_edits > 0 and args.matcher == "auto"
+                                          and not (k >= 4 and rows > 128))
+    kernel = "step_scan_kernel" if by_scan else "step_wave_kernel"
+    variant = w.name + ("_one_edit" if args.max_edits else "") + ("" if args.pool == "dag" else "_" + args.pool)
     res = {
         "metric": METRIC, "value": K / dt, "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": dt / K * 1e3, "higher_is_better": True, "scaling": "weak",
@@ -237,9 +243,9 @@ def main():
                                 "accepted + 1; synthetic stand-in for the model"},
         "matches_per_step": matches_per_step,
         "algorithmic_bytes_per_step": b_step,
-        "roofline": {"bound": "hbm", "kernel": "csd::step_wave_kernel (one launch per step: append+draft+accept)",
+        "roofline": {"bound": "hbm", "kernel": "csd::%s (one launch per step: append+draft+accept)" % kernel,
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(w.name),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(kernel, variant),
                      "algorithmic_bytes_per_launch": b_step, "avg_launch_us": launch_ms * 1e3},
     }
 
