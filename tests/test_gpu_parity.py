@@ -547,3 +547,42 @@ def test_large_batch_uses_the_small_on_chip_layout(oracle):
         lens_t = np.full(tokens.shape[:2], t + 1, dtype=np.int32)
         want = oracle.draft_all(tokens, probs, lens_t, k, L, 1.0, 0, targets[t])
         assert_step_equal(got, want, t, "large batch")
+
+
+def test_random_configurations_against_the_oracle(oracle):
+    """Differential test over random small configurations: geometry, query and draft lengths,
+    alpha, scoring, tolerance, pool structure, matcher and call pattern all vary together."""
+    rng = np.random.default_rng(20250305)
+    for case in range(250):
+        P, N = int(rng.integers(1, 4)), int(rng.integers(1, 9))
+        T = int(rng.integers(4, 90))
+        V = int(rng.choice([3, 5, 40, 1000]))
+        k, L = int(rng.integers(1, 9)), int(rng.integers(1, 33))
+        eps, pool_mode, mode = int(rng.integers(0, 2)), int(rng.integers(0, 3)), int(rng.integers(0, 2))
+        alpha = float(rng.integers(0, 9)) / 8
+        flags = int(rng.choice([0, SCAN, INDEX]))
+        if eps and flags == INDEX and k < 2:
+            flags = 0
+        n_per_step = int(rng.choice([1, 1, 2, 5]))
+        how = str(rng.choice(["calls", "step"]))
+        use_probs = bool(rng.integers(0, 2))
+        # paths: a few shared segments in random order, with noise, so that matches exist
+        segs = [rng.integers(0, V, size=int(rng.integers(2, 9))) for _ in range(4)]
+        tokens = np.zeros((P, N, T), dtype=np.int32)
+        for p in range(P):
+            for j in range(N):
+                seq = np.concatenate([segs[int(x)] for x in rng.integers(0, 4, size=T)])[:T]
+                noise = rng.random(T) < 0.1
+                tokens[p, j] = np.where(noise, rng.integers(0, V, size=T), seq)
+        probs = (rng.integers(1, 17, size=tokens.shape) / 16.0).astype(np.float32) if use_probs else None
+        steps = T // n_per_step
+        counts = rng.integers(0, n_per_step + 1, size=(steps, P, N)).astype(np.int32) if n_per_step > 1 else None
+        what = "case %d: P%d N%d T%d V%d k%d L%d eps%d pool%d mode%d alpha%.3f flags%d n%d %s probs%d" % (
+            case, P, N, T, V, k, L, eps, pool_mode, mode, alpha, flags, n_per_step, how, use_probs)
+        print(what, flush=True)
+        got = gpu_replay(tokens, probs, k, L, alpha, mode, flags, steps=steps, counts=counts,
+                         n_per_step=n_per_step, how=how, max_edits=eps, pool_mode=pool_mode)
+        assert got["status"] in (0, binding.STATUS_CAPACITY), what
+        for t in range(steps):
+            want = oracle.draft_all(tokens, probs, got["lens"][t], k, L, alpha, mode, eps=eps, pool_mode=pool_mode)
+            assert_step_equal(got, want, t, what)
