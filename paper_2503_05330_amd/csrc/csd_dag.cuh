@@ -318,13 +318,36 @@ __device__ __forceinline__ void walk_layers(LDS& s, const Ctx& c, int32_t M, int
 
 // ---------------------------------------------------------------- tier 2: streaming
 
+// Token and quantised probability of the d-th continuation token (d >= 1) of a
+// match that reaches it: from the match's LDS window if it has one, else from memory.
+template <class LDS>
+__device__ __forceinline__ void continuation_at(const LDS& s, const Ctx& c, WinInfo wi, int32_t L,
+                                                int32_t mi, Match m, int32_t d, uint32_t& v,
+                                                uint32_t& p) {
+  int32_t ws = mi - wi.n_fresh;
+  if (mi >= 0 && ws >= 0 && ws < wi.win_cap) {
+    const int32_t* win = s.win + ws * 2 * L;
+    v = (uint32_t)win[d - 1];
+    p = (uint32_t)win[L + d - 1];
+  } else {
+    int32_t j = c.y.pos_path(m.pos), e = c.y.pos_index(m.pos);
+    int32_t old_j = e + (int32_t)m.rel_old;           // exact wherever it decides (see layer_instance)
+    v = (uint32_t)c.y.token(j, e + d - 1, old_j);
+    p = c.y.prob(j, e + d - 1, old_j);
+  }
+}
+
 // Same result as tier 1 with bounded memory for any input.  `each_match(f)`
-// calls f(Match) for every match (from the LDS list, or by matching again).
+// calls f(Match, index in the LDS match list or -1) for every match (from the
+// list, or by matching again); listed matches with a window are read from LDS.
+// M (the number of matches) only sizes the table region.
 template <int BLOCK, class LDS, class EachMatch>
-__device__ __forceinline__ void walk_streaming(LDS& s, const Ctx& c, int32_t L, uint32_t alpha_q,
-                                               int score_mode, uint32_t* status, DraftOut& o,
-                                               EachMatch each_match) {
-  const Region all{0u, (uint32_t)LDS::kTable - 1u};
+__device__ __forceinline__ void walk_streaming(LDS& s, const Ctx& c, WinInfo wi, int32_t M, int32_t L,
+                                               uint32_t alpha_q, int score_mode, uint32_t* status,
+                                               DraftOut& o, EachMatch each_match) {
+  uint32_t size = 64;
+  while (size < 4u * (uint32_t)M && size < (uint32_t)LDS::kTable) size <<= 1;
+  const Region all{0u, size - 1u};
   int32_t cur = c.Q[0];
   int class_bits = 0;
   int parity = 0;
@@ -337,13 +360,15 @@ __device__ __forceinline__ void walk_streaming(LDS& s, const Ctx& c, int32_t L, 
       uint32_t n_class = 1u << class_bits;
       for (uint32_t r = 0; r < n_class && !failed; ++r) {
         block_sync<BLOCK>();                           // previous readers are done
-        table_clear<BLOCK>(s, LDS::kTable, c.tid);
+        table_clear<BLOCK>(s, size, c.tid);
         block_sync<BLOCK>();
-        each_match([&](Match m) {
-          uint32_t u, v;
-          u64 w;
-          if (s.overflow || !layer_instance(c.y, m, d, (uint32_t)c.Q[0], u, v, w)) return;
+        each_match([&](Match m, int32_t mi) {
+          if (s.overflow || d > (int32_t)m.rem_new) return;
+          uint32_t u = (uint32_t)c.Q[0], v, p, unused;
+          continuation_at(s, c, wi, L, mi, m, d, v, p);
+          if (d >= 2) continuation_at(s, c, wi, L, mi, m, d - 1, u, unused);
           if (((v * 0x9E3779B1u) >> 12 & (n_class - 1)) != r) return;
+          u64 w = pack_cs(1u, p);
           table_add(s, all, dag_key(d, kAnyTok, v), w);
           if (u == (uint32_t)cur) table_add(s, all, dag_key(d, u, v), w);
         });
@@ -370,25 +395,6 @@ __device__ __forceinline__ void walk_streaming(LDS& s, const Ctx& c, int32_t L, 
 // The variants the paper's ablation compares the DAG with.  Both read the same
 // candidate pool.  `each_match(f)` calls f(Match, index in the LDS match list
 // or -1) for every match.
-
-// Token and quantised probability of the d-th continuation token (d >= 1) of a
-// match that reaches it: from the match's LDS window if it has one, else from memory.
-template <class LDS>
-__device__ __forceinline__ void continuation_at(const LDS& s, const Ctx& c, WinInfo wi, int32_t L,
-                                                int32_t mi, Match m, int32_t d, uint32_t& v,
-                                                uint32_t& p) {
-  int32_t ws = mi - wi.n_fresh;
-  if (mi >= 0 && ws >= 0 && ws < wi.win_cap) {
-    const int32_t* win = s.win + ws * 2 * L;
-    v = (uint32_t)win[d - 1];
-    p = (uint32_t)win[L + d - 1];
-  } else {
-    int32_t j = c.y.pos_path(m.pos), e = c.y.pos_index(m.pos);
-    int32_t old_j = e + (int32_t)m.rel_old;           // exact wherever it decides (see layer_instance)
-    v = (uint32_t)c.y.token(j, e + d - 1, old_j);
-    p = c.y.prob(j, e + d - 1, old_j);
-  }
-}
 
 // Prefix tree: candidates share a node only while ALL their tokens so far are
 // equal.  Greedy descent: at depth d the candidates that carry the draft so

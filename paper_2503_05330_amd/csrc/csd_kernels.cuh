@@ -191,11 +191,12 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
         done = true;
       }
       if (!done)
-        walk_streaming<BLOCK>(s, c, L, a.alpha_q, a.score_mode, ix.status, o, [&](auto f) {
+        walk_streaming<BLOCK>(s, c, WinInfo{M, 0}, M, L, a.alpha_q, a.score_mode, ix.status, o, [&](auto f) {
           if (M <= LdsScan::kMatch) {
-            for (int32_t m = c.tid; m < M; m += BLOCK) f(s.match[m]);
+            for (int32_t m = c.tid; m < M; m += BLOCK) f(s.match[m], m);
           } else {
-            FnSink<decltype(f)> fs{f};
+            auto g = [&](Match found) { f(found, -1); };
+            FnSink<decltype(g)> fs{g};
             match_scan_any<BLOCK>(s, c, fs);
           }
         });
@@ -254,12 +255,13 @@ __global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn i
       if (!streaming) walk_dag<kWave, LCAP>(s, c, t1, L, a.alpha_q, a.score_mode, o);
     }
     if (streaming)
-      walk_streaming<kWave>(s, c, L, a.alpha_q, a.score_mode, ix.status, o, [&](auto f) {
+      walk_streaming<kWave>(s, c, wi, M, L, a.alpha_q, a.score_mode, ix.status, o, [&](auto f) {
         if (M <= LDS::kMatch) {
 #pragma unroll 4
-          for (int32_t m = c.tid; m < M; m += kWave) f(s.match[m]);
+          for (int32_t m = c.tid; m < M; m += kWave) f(s.match[m], m);
         } else {
-          FnSink<decltype(f)> fs{f};
+          auto g = [&](Match found) { f(found, -1); };
+          FnSink<decltype(g)> fs{g};
           if (FUZZY) match_scan<kWave, true>(s, c, fs);
           else if (c.q == c.kmax) match_index(c, fs);
           else match_scan<kWave, false>(s, c, fs);
