@@ -240,9 +240,7 @@ __global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn i
       } else {
         auto g = [&](Match found) { f(found, -1); };
         FnSink<decltype(g)> fs{g};
-        if (FUZZY) match_scan<kWave, true>(s, c, fs);
-        else if (c.q == c.kmax) match_index(c, fs);
-        else match_scan<kWave, false>(s, c, fs);
+        match_plain<FUZZY>(s, c, fs);
       }
     };
     if (a.pool_mode == CSD_POOL_TREE) walk_tree<kWave>(s, c, wi, M, L, a.alpha_q, ix.status, o, each);
@@ -262,9 +260,7 @@ __global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn i
         } else {
           auto g = [&](Match found) { f(found, -1); };
           FnSink<decltype(g)> fs{g};
-          if (FUZZY) match_scan<kWave, true>(s, c, fs);
-          else if (c.q == c.kmax) match_index(c, fs);
-          else match_scan<kWave, false>(s, c, fs);
+          match_plain<FUZZY>(s, c, fs);
         }
       });
   }
@@ -375,12 +371,8 @@ __global__ __launch_bounds__(kWave) void dump_match_bits_wave_kernel(IndexView i
   BitmapSink sink{bits + (int64_t)row * words};
   if (M <= LdsWave::kMatch) {
     for (int32_t m = c.tid; m < M; m += kWave) sink.push(c.y, true, s.match[m]);
-  } else if (FUZZY) {
-    if (c.q > 0) match_scan<kWave, true>(s, c, sink);
-  } else if (c.q == c.kmax) {
-    match_index(c, sink);
   } else if (c.q > 0) {
-    match_scan<kWave, false>(s, c, sink);
+    match_plain<FUZZY>(s, c, sink);
   }
 }
 

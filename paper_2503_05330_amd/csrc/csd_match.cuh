@@ -302,53 +302,26 @@ __device__ __forceinline__ void match_scan_any(const LDS& s, const Ctx& c, Sink&
   else match_scan<BLOCK, true>(s, c, sink, slice, n_slices);
 }
 
-// Eq. 3 through the hash index, by ONE wave, in its general form (any number
-// of new tokens, any sink).  Postings of earlier steps come from the gram's
-// bucket sequence; positions this very launch appends are not looked up (their
-// inserts may be in flight) but tested directly.
-template <class Sink>
-__device__ __forceinline__ void match_index(const Ctx& c, Sink& sink) {
+// Eq. 3 / Eq. 4 by ONE wave, position by position, in as little code as
+// possible.  The one-wave kernels use it where they cannot use the index: for
+// queries shorter than the indexed grams (a path's first steps) and to re-find
+// matches that did not fit the on-chip list.  Both are rare, and the code of a
+// kernel that every launch fetches through cold caches is worth keeping small:
+// with the tiled scan inlined in these places the common step was 8 % slower.
+template <bool FUZZY, class LDS, class Sink>
+__device__ __forceinline__ void match_plain(const LDS& s, const Ctx& c, Sink& sink) {
   const int lane = c.tid & 63;
-  if (c.y.n > 0) {                    // (a) positions appended by this launch
-    for (int32_t j0 = 0; j0 < c.y.N; j0 += kWave) {
-      int32_t j = j0 + lane;
-      bool live = j < c.y.N && j != c.i;
-      int32_t old_j = live ? c.y.old_len(j) : 0;
-      int32_t new_j = live ? c.y.new_len(j, old_j) : 0;
-      for (int32_t t = 0; t < c.y.n; ++t) {
-        int32_t e = old_j + t;
-        bool hit = live && e < new_j && e >= c.q && gram_equals_query(c, j, e, old_j);
-        sink.push(c.y, hit, make_match(c.y, j, e, old_j, new_j));
-      }
+  const int32_t first_e = FUZZY ? (c.q > 1 ? c.q - 1 : 0) : c.q;   // shortest substring that can match
+  for (int32_t j = 0; j < c.y.N; ++j) {
+    if (j == c.i) continue;
+    int32_t old_j, new_j;
+    lens_of(s, c.y, j, old_j, new_j);
+    for (int32_t e0 = first_e; e0 < new_j; e0 += kWave) {  // trip counts are uniform over the wave
+      int32_t e = e0 + lane;
+      bool hit = false;
+      if (e < new_j) hit = FUZZY ? gram_near_query(c, j, e, old_j) : gram_equals_query(c, j, e, old_j);
+      sink.push(c.y, hit, make_match(c.y, j, e, old_j, new_j));
     }
-  }
-  GramHash gh = query_hash(c);        // (b) postings of earlier launches (needs c.q == kmax)
-  int32_t* tbl = const_cast<int32_t*>(c.gram);
-  const int sub = lane & 15;          // word of the bucket this lane reads
-  const int grp = lane >> 4;          // which of the 4 buckets of a batch
-  uint32_t n_buckets = c.bucket_mask + 1;
-  for (uint32_t r0 = 0; r0 < n_buckets; r0 += 4) {
-    uint32_t r = r0 + grp;
-    int32_t word = -1;
-    if (r < n_buckets) word = gram_bucket(tbl, gh, r, c.bucket_mask)[sub];
-    int32_t count = __shfl(word, lane & ~15);
-    bool full = count >= kBucketSlots;
-    bool cand = sub >= 1 && word >= 0 && (sub - 1) < (full ? kBucketSlots : count);
-    int32_t j = 0, e = 0, old_j = 0, new_j = 0;
-    bool hit = false;
-    if (cand) {
-      j = c.y.pos_path(word);
-      e = c.y.pos_index(word);
-      if (j != c.i && j < c.y.N) {
-        old_j = c.y.old_len(j);
-        if (e < old_j) {                 // postings at or beyond old_j belong to case (a)
-          new_j = c.y.new_len(j, old_j);
-          hit = gram_equals_query(c, j, e, old_j);
-        }
-      }
-    }
-    sink.push(c.y, hit, make_match(c.y, j, e, old_j, new_j));
-    if (__ballot(!full || r >= n_buckets) != 0) break;
   }
 }
 
@@ -586,7 +559,7 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
     lookup_with_windows<LCAP>(s, c, L, wi.win_cap, wi.n_fresh, n_match, gh, word);
   } else if (c.q > 0) {
     WaveListSink<LDS> sink{&s, &n_match, lane};
-    match_scan<kWave, false>(s, c, sink);               // covers old and new positions alike
+    match_plain<false>(s, c, sink);                     // covers old and new positions alike
     wi.n_fresh = n_match;
   }
   if (lane == 0) s.n_match = n_match;
@@ -853,7 +826,7 @@ __device__ __forceinline__ int32_t wave_front_end_fuzzy(LDS& s, Ctx& c, const In
     lookup_variants_with_windows<LCAP>(s, c, L, wi.win_cap, wi.n_fresh, n_match, word);
   } else if (c.q > 0) {
     WaveListSink<LDS> sink{&s, &n_match, lane};
-    match_scan<kWave, true>(s, c, sink);                // covers old and new positions alike
+    match_plain<true>(s, c, sink);                      // covers old and new positions alike
     wi.n_fresh = n_match;
   }
   if (lane == 0) s.n_match = n_match;
