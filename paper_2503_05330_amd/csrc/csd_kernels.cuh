@@ -235,7 +235,6 @@ __global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn i
   if (POOLS && M > 0 && a.pool_mode != CSD_POOL_DAG) {
     auto each = [&](auto f) {
       if (M <= LDS::kMatch) {
-#pragma unroll 4
         for (int32_t m = c.tid; m < M; m += kWave) f(s.match[m], m);
       } else {
         auto g = [&](Match found) { f(found, -1); };
@@ -255,7 +254,6 @@ __global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn i
     if (streaming)
       walk_streaming<kWave>(s, c, wi, M, L, a.alpha_q, a.score_mode, ix.status, o, [&](auto f) {
         if (M <= LDS::kMatch) {
-#pragma unroll 4
           for (int32_t m = c.tid; m < M; m += kWave) f(s.match[m], m);
         } else {
           auto g = [&](Match found) { f(found, -1); };
