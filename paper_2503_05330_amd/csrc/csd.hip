@@ -194,16 +194,20 @@ void launch_draft(const csd_index* h, const IndexView& v, const StepIn& in, cons
     else if (a.L <= 16) step_wave_kernel<16, true, LdsWaveFuzzy, true><<<grid, kWave, 0, st>>>(v, in, a);
     else step_wave_kernel<32, true, LdsWaveFuzzy, true><<<grid, kWave, 0, st>>>(v, in, a);
   } else if (a.pool_mode != CSD_POOL_DAG) {             // tree and list pools: the general kernels
-    if (!h->indexed) step_scan_kernel<1, true><<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
+    if (!h->indexed && v.eps > 0) step_scan_kernel<1, true, true><<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
+    else if (!h->indexed) step_scan_kernel<1, true, false><<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
     else if (a.L <= 8) step_wave_kernel<8, true, LdsWave, false><<<grid, kWave, 0, st>>>(v, in, a);
     else if (a.L <= 16) step_wave_kernel<16, true, LdsWave, false><<<grid, kWave, 0, st>>>(v, in, a);
     else step_wave_kernel<32, true, LdsWave, false><<<grid, kWave, 0, st>>>(v, in, a);
   } else if (!h->indexed && a.L <= 8)
-    step_scan_kernel<8, false><<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
+    (v.eps > 0 ? step_scan_kernel<8, false, true> : step_scan_kernel<8, false, false>)
+        <<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
   else if (!h->indexed && a.L <= 16)
-    step_scan_kernel<16, false><<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
+    (v.eps > 0 ? step_scan_kernel<16, false, true> : step_scan_kernel<16, false, false>)
+        <<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
   else if (!h->indexed)     // longer drafts: the walk's register-resident fast path is left out
-    step_scan_kernel<1, false><<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
+    (v.eps > 0 ? step_scan_kernel<1, false, true> : step_scan_kernel<1, false, false>)
+        <<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
   else if (a.L <= 8 && rows >= kSmallLdsRows)   // more rows than fit the chip at once
     step_wave_kernel<8, false, LdsWaveSmall, false><<<grid, kWave, 0, st>>>(v, in, a);
   else if (a.L <= 8)

@@ -83,7 +83,9 @@ __device__ __forceinline__ void cache_lens(LDS& s, const Paths& y, int tid) {
 // With sl.n > 1 a row's scan is shared by sl.n workgroups (few rows: the scan is
 // bound by instruction issue on the row's CU, and most CUs would be idle); the
 // one that finishes last does the rest of the row's work.
-template <int LCAP, bool POOLS>
+// FUZZY: matching tolerates one edit (compiled apart from the exact kernel: code a launch
+// does not run still costs it time).
+template <int LCAP, bool POOLS, bool FUZZY>
 __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, StepIn in,
                                                                DraftArgs a, ScanSlices sl) {
   constexpr int BLOCK = kScanBlock;
@@ -126,7 +128,7 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
   const int32_t L = a.L;
   if (c.q > 0) {
     ListSink<LdsScan> sink{&s};
-    match_scan_any<BLOCK>(s, c, sink, slice, sl.n);
+    match_scan<BLOCK, FUZZY>(s, c, sink, slice, sl.n);
     block_sync<BLOCK>();
     int32_t M = s.n_match;
     if (sl.n > 1) {
@@ -161,7 +163,7 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
         } else {
           auto g = [&](Match found) { f(found, -1); };
           FnSink<decltype(g)> fs{g};
-          match_scan_any<BLOCK>(s, c, fs);
+          match_scan<BLOCK, FUZZY>(s, c, fs);
         }
       };
       if (a.pool_mode == CSD_POOL_TREE)
@@ -197,7 +199,7 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
           } else {
             auto g = [&](Match found) { f(found, -1); };
             FnSink<decltype(g)> fs{g};
-            match_scan_any<BLOCK>(s, c, fs);
+            match_scan<BLOCK, FUZZY>(s, c, fs);
           }
         });
     }
