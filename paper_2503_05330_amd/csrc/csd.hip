@@ -105,10 +105,12 @@ Layout make_layout(const csd_config* c) {
   size_t cells = (size_t)c->n_problems * c->n_paths * c->max_len;
   size_t rows = (size_t)c->n_problems * c->n_paths;
   size_t at = 0;
-  // + 8 cells: lanes of the scan that have no position still load the first six cells of
-  // their problem's first path, and a span may read two cells past its path
-  l.tok = at;    at += align_up((cells + 8) * sizeof(int32_t));
-  l.pq = at;     at += align_up(cells * sizeof(uint32_t));
+  // + 32 cells: the index lookup loads a match's whole continuation window (up to
+  // CSD_MAX_DRAFT_LEN cells) wherever the path ends; lanes of the scan that have no position
+  // load the first six cells of their problem's first path, and a span may read two cells
+  // past its path
+  l.tok = at;    at += align_up((cells + CSD_MAX_DRAFT_LEN) * sizeof(int32_t));
+  l.pq = at;     at += align_up((cells + CSD_MAX_DRAFT_LEN) * sizeof(uint32_t));
   l.meta_stride = (1 + tail_len_of(c) + 3) / 4 * 4;
   l.eshift = 1;
   while ((1 << l.eshift) < c->max_len) ++l.eshift;
@@ -190,15 +192,15 @@ void launch_draft(const csd_index* h, const IndexView& v, const StepIn& in, cons
   const ScanSlices sl = h->slices;
   const uint32_t scan_grid = sl.n > 1 ? (uint32_t)((rows + 7) / 8 * sl.n * 8) : grid;
   if (h->indexed && v.eps > 0) {                         // one edit through the variant index
-    if (a.L <= 8) step_wave_kernel<8, true, LdsWaveFuzzy, true><<<grid, kWave, 0, st>>>(v, in, a);
-    else if (a.L <= 16) step_wave_kernel<16, true, LdsWaveFuzzy, true><<<grid, kWave, 0, st>>>(v, in, a);
-    else step_wave_kernel<32, true, LdsWaveFuzzy, true><<<grid, kWave, 0, st>>>(v, in, a);
+    if (a.L <= 8) step_wave_kernel<8, true, LdsWaveFuzzy, true, CSD_MAX_QUERY_LEN><<<grid, kWave, 0, st>>>(v, in, a);
+    else if (a.L <= 16) step_wave_kernel<16, true, LdsWaveFuzzy, true, CSD_MAX_QUERY_LEN><<<grid, kWave, 0, st>>>(v, in, a);
+    else step_wave_kernel<32, true, LdsWaveFuzzy, true, CSD_MAX_QUERY_LEN><<<grid, kWave, 0, st>>>(v, in, a);
   } else if (a.pool_mode != CSD_POOL_DAG) {             // tree and list pools: the general kernels
     if (!h->indexed && v.eps > 0) step_scan_kernel<1, true, true><<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
     else if (!h->indexed) step_scan_kernel<1, true, false><<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
-    else if (a.L <= 8) step_wave_kernel<8, true, LdsWave, false><<<grid, kWave, 0, st>>>(v, in, a);
-    else if (a.L <= 16) step_wave_kernel<16, true, LdsWave, false><<<grid, kWave, 0, st>>>(v, in, a);
-    else step_wave_kernel<32, true, LdsWave, false><<<grid, kWave, 0, st>>>(v, in, a);
+    else if (a.L <= 8) step_wave_kernel<8, true, LdsWave, false, CSD_MAX_QUERY_LEN><<<grid, kWave, 0, st>>>(v, in, a);
+    else if (a.L <= 16) step_wave_kernel<16, true, LdsWave, false, CSD_MAX_QUERY_LEN><<<grid, kWave, 0, st>>>(v, in, a);
+    else step_wave_kernel<32, true, LdsWave, false, CSD_MAX_QUERY_LEN><<<grid, kWave, 0, st>>>(v, in, a);
   } else if (!h->indexed && a.L <= 8)
     (v.eps > 0 ? step_scan_kernel<8, false, true> : step_scan_kernel<8, false, false>)
         <<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
@@ -208,14 +210,23 @@ void launch_draft(const csd_index* h, const IndexView& v, const StepIn& in, cons
   else if (!h->indexed)     // longer drafts: the walk's register-resident fast path is left out
     (v.eps > 0 ? step_scan_kernel<1, false, true> : step_scan_kernel<1, false, false>)
         <<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
-  else if (a.L <= 8 && rows >= kSmallLdsRows)   // more rows than fit the chip at once
-    step_wave_kernel<8, false, LdsWaveSmall, false><<<grid, kWave, 0, st>>>(v, in, a);
+  else if (v.kmax <= 4) {                        // the usual gram lengths: loops unrolled to 4
+    if (a.L <= 8 && rows >= kSmallLdsRows)       // more rows than fit the chip at once
+      step_wave_kernel<8, false, LdsWaveSmall, false, 4><<<grid, kWave, 0, st>>>(v, in, a);
+    else if (a.L <= 8)
+      step_wave_kernel<8, false, LdsWave, false, 4><<<grid, kWave, 0, st>>>(v, in, a);
+    else if (a.L <= 16)
+      step_wave_kernel<16, false, LdsWave, false, 4><<<grid, kWave, 0, st>>>(v, in, a);
+    else
+      step_wave_kernel<32, false, LdsWave, false, 4><<<grid, kWave, 0, st>>>(v, in, a);
+  } else if (a.L <= 8 && rows >= kSmallLdsRows)
+    step_wave_kernel<8, false, LdsWaveSmall, false, 8><<<grid, kWave, 0, st>>>(v, in, a);
   else if (a.L <= 8)
-    step_wave_kernel<8, false, LdsWave, false><<<grid, kWave, 0, st>>>(v, in, a);
+    step_wave_kernel<8, false, LdsWave, false, 8><<<grid, kWave, 0, st>>>(v, in, a);
   else if (a.L <= 16)
-    step_wave_kernel<16, false, LdsWave, false><<<grid, kWave, 0, st>>>(v, in, a);
+    step_wave_kernel<16, false, LdsWave, false, 8><<<grid, kWave, 0, st>>>(v, in, a);
   else
-    step_wave_kernel<32, false, LdsWave, false><<<grid, kWave, 0, st>>>(v, in, a);
+    step_wave_kernel<32, false, LdsWave, false, 8><<<grid, kWave, 0, st>>>(v, in, a);
 }
 
 // Host-side bookkeeping shared by csd_append and csd_step.

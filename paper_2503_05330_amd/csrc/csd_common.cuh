@@ -118,6 +118,16 @@ __device__ __forceinline__ Cand wave_argmax(Cand c) {
   return cand_from_lane(c, 63);
 }
 
+// arr[idx] for idx < N without indexing registers by a variable (0 when idx is out of range)
+template <int N, int SIZE>
+__device__ __forceinline__ int32_t pick_n(const int32_t (&arr)[SIZE], int32_t idx) {
+  static_assert(N <= SIZE, "pick_n reads arr[0 .. N)");
+  int32_t r = 0;
+#pragma unroll
+  for (int a = 0; a < N; ++a) r = (idx == a) ? arr[a] : r;
+  return r;
+}
+
 // arr[idx] without indexing registers by a variable (0 when idx is out of range)
 template <int SIZE>
 __device__ __forceinline__ int32_t pick(const int32_t (&arr)[SIZE], int32_t idx) {

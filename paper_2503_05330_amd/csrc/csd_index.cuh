@@ -97,13 +97,14 @@ struct InsertTicket {
 
 // Phase 1: hash of the gram that ends just before the new position (tail[a] =
 // a-th token before it) and the fill-count loads (not waited for here).
+template <int QC>
 __device__ __forceinline__ InsertTicket insert_begin(int32_t* gram, uint32_t mask, int32_t kmax,
                                                      const int32_t (&tail)[kTailCap],
                                                      int32_t n_before, int lane) {
   InsertTicket t;
   uint32_t acc = kGramSeed;
 #pragma unroll
-  for (int a = 1; a <= CSD_MAX_QUERY_LEN; ++a)
+  for (int a = 1; a <= QC; ++a)
     if (a <= kmax) acc = gram_hash_add(acc, tail[a - 1]);
   t.gh = gram_hash_end(acc, kmax);
   t.live = kmax <= n_before;

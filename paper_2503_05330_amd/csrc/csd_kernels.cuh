@@ -216,7 +216,8 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
 // and last the posting stores of the split-phase index insert.
 // FUZZY: the index files every position under its gram's variants and matching tolerates
 // one edit (Eq. 4).
-template <int LCAP, bool POOLS, class LDS, bool FUZZY>
+// QC: compile-time bound (4 or 8) of the index's gram length.
+template <int LCAP, bool POOLS, class LDS, bool FUZZY, int QC>
 __global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn in, DraftArgs a) {
   __shared__ LDS s;
   int32_t row = xcd_row(ix.P * ix.N);
@@ -230,7 +231,7 @@ __global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn i
   VariantTicket tickets;
   bool ticket_used;
   int32_t M = FUZZY ? wave_front_end_fuzzy<LCAP>(s, c, ix, p, a.k, L, wi, tickets, ticket_used)
-                    : wave_front_end<LCAP>(s, c, ix, p, a.k, L, wi, ticket, ticket_used);
+                    : wave_front_end<LCAP, QC>(s, c, ix, p, a.k, L, wi, ticket, ticket_used);
   block_sync<kWave>();
 
   DraftOut o;
@@ -366,7 +367,7 @@ __global__ __launch_bounds__(kWave) void dump_match_bits_wave_kernel(IndexView i
   VariantTicket tickets;
   bool ticket_used;
   int32_t M = FUZZY ? wave_front_end_fuzzy<8>(s, c, ix, p, k, 1, wi, tickets, ticket_used)
-                    : wave_front_end<8>(s, c, ix, p, k, 1, wi, ticket, ticket_used);
+                    : wave_front_end<8, CSD_MAX_QUERY_LEN>(s, c, ix, p, k, 1, wi, ticket, ticket_used);
   block_sync<kWave>();
   BitmapSink sink{bits + (int64_t)row * words};
   if (M <= LdsWave::kMatch) {
@@ -488,7 +489,7 @@ __global__ __launch_bounds__(kWave) void dump_edge_rows_wave_kernel(IndexView ix
   VariantTicket tickets;
   bool ticket_used;
   int32_t M = FUZZY ? wave_front_end_fuzzy<LCAP>(s, c, ix, p, k, L, wi, tickets, ticket_used)
-                    : wave_front_end<LCAP>(s, c, ix, p, k, L, wi, ticket, ticket_used);
+                    : wave_front_end<LCAP, CSD_MAX_QUERY_LEN>(s, c, ix, p, k, L, wi, ticket, ticket_used);
   block_sync<kWave>();
   if (M == 0) { if (c.tid == 0) counts[row] = 0; return; }
   if (M > LdsWave::kMatch) { if (c.tid == 0) counts[row] = -1; return; }

@@ -96,10 +96,11 @@ __device__ __forceinline__ bool gram_near_query(const Ctx& c, int32_t j, int32_t
   return near_query(c, e, t);
 }
 
+template <int QC>
 __device__ __forceinline__ GramHash query_hash(const Ctx& c) {
   uint32_t acc = kGramSeed;
 #pragma unroll
-  for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a)
+  for (int a = 0; a < QC; ++a)
     if (a < c.q) acc = gram_hash_add(acc, c.Q[a]);
   return gram_hash_end(acc, c.q);
 }
@@ -344,14 +345,16 @@ struct Head {                   // a path's end before this step
   int32_t tail[kTailCap];       // tail[a] = a-th token from the old end (tail_len of them are kept)
 };
 
+// QC: compile-time bound of tail_len (the words beyond it are not looked at).
+template <int QC = kTailCap>
 __device__ __forceinline__ Head load_head(const Paths& y, int32_t tail_len, int32_t j) {
   Head h;
   const int32_t* row = y.meta_old + (int64_t)j * y.meta_stride;
   const int4* m = reinterpret_cast<const int4*>(row);
   int4 a = m[0];
-  int4 b = tail_len > 3 ? m[1] : int4{0, 0, 0, 0};
-  int32_t c8 = tail_len > 7 ? row[8] : 0;
-  int32_t c9 = tail_len > 8 ? row[9] : 0;
+  int4 b = (QC > 3 && tail_len > 3) ? m[1] : int4{0, 0, 0, 0};
+  int32_t c8 = (QC > 7 && tail_len > 7) ? row[8] : 0;
+  int32_t c9 = (QC > 8 && tail_len > 8) ? row[9] : 0;
   h.old_len = a.x;
   h.tail[0] = a.y; h.tail[1] = a.z; h.tail[2] = a.w;
   h.tail[3] = b.x; h.tail[4] = b.y; h.tail[5] = b.z; h.tail[6] = b.w;
@@ -385,6 +388,7 @@ struct WaveListSink {           // match list of a one-wave row; push() by all 6
 
 // The own row's append when the step carries one token per path, from values
 // already in registers (no further loads).
+template <int QC = kTailCap>
 __device__ __forceinline__ void append_own_single(const IndexView& ix, const Paths& y, int64_t row,
                                                   int32_t i, const Head& me, int32_t st_i,
                                                   float sp_i, int lane) {
@@ -394,7 +398,7 @@ __device__ __forceinline__ void append_own_single(const IndexView& ix, const Pat
     int32_t v = 0;
     if (lane == 0) v = me.new_len;
     else if (a < cnt) v = st_i;
-    else if (a < me.new_len) v = pick(me.tail, a - cnt);
+    else if (a < me.new_len) v = pick_n<QC>(me.tail, a - cnt);
     ix.meta_new[row * ix.meta_stride + lane] = v;
   }
   if (lane == 0) {
@@ -414,7 +418,7 @@ __device__ __forceinline__ void append_own_single(const IndexView& ix, const Pat
 // round trip as the verification.  `word` is the lane's word of the first batch
 // of 4 buckets, already requested.  Adds its hits behind the n_fresh matches
 // already listed; hit number x (0-based among these) gets window x.
-template <int LCAP, class LDS>
+template <int LCAP, int QC, class LDS>
 __device__ __forceinline__ void lookup_with_windows(LDS& s, const Ctx& c, int32_t L,
                                                     int32_t win_cap, int32_t n_fresh,
                                                     int32_t& n_match, GramHash gh, int32_t word) {
@@ -454,21 +458,22 @@ __device__ __forceinline__ void lookup_with_windows(LDS& s, const Ctx& c, int32_
     if (cand) {
       const int32_t* hrow = y.tok + y.cell(j, e);        // history of path j at the posting
       const uint32_t* prow = y.pq + y.cell(j, e);
-      int32_t tv[CSD_MAX_QUERY_LEN];
+      int32_t tv[QC];
 #pragma unroll
-      for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) tv[a] = (a < c.q) ? hrow[-1 - a] : 0;
+      for (int a = 0; a < QC; ++a) tv[a] = hrow[a < c.q ? -1 - a : -1];   // e >= q: all exist
       rem = new_j - e;
       rem = rem < L ? rem : L;
       n_hist = old_j - e;             // >= 1: continuation tokens that are already history
       n_hist = n_hist < rem ? n_hist : rem;
+      // the whole window with a few wide loads, whatever part of it is valid: what lies
+      // beyond n_hist is replaced below or never looked at (the arrays are padded for it)
 #pragma unroll
-      for (int d = 0; d < LCAP; ++d)
-        if (d < n_hist) {
-          wv[d] = hrow[d];
-          wp[d] = prow[d];
-        }
+      for (int d = 0; d < LCAP; ++d) {
+        wv[d] = hrow[d];
+        wp[d] = prow[d];
+      }
 #pragma unroll
-      for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) hit = hit && (a >= c.q || tv[a] == c.Q[a]);
+      for (int a = 0; a < QC; ++a) hit = hit && (a >= c.q || tv[a] == c.Q[a]);
     }
     if (__ballot(hit && rem > n_hist) != 0) {            // rare: runs into this step's new tokens
 #pragma unroll
@@ -482,12 +487,20 @@ __device__ __forceinline__ void lookup_with_windows(LDS& s, const Ctx& c, int32_
     int32_t w = slot - n_fresh;
     if (slot >= 0 && w < win_cap) {
       int32_t* win = s.win + w * 2 * L;
+      if (L == LCAP) {                // the whole window at once; entries beyond rem are never read
 #pragma unroll
-      for (int d = 0; d < LCAP; ++d)
-        if (d < rem) {
+        for (int d = 0; d < LCAP; ++d) {
           win[d] = wv[d];
-          win[L + d] = (int32_t)wp[d];
+          win[LCAP + d] = (int32_t)wp[d];
         }
+      } else {
+#pragma unroll
+        for (int d = 0; d < LCAP; ++d)
+          if (d < rem) {
+            win[d] = wv[d];
+            win[L + d] = (int32_t)wp[d];
+          }
+      }
     }
     if (seq_ends) break;
     word = next_word;
@@ -498,7 +511,10 @@ __device__ __forceinline__ void lookup_with_windows(LDS& s, const Ctx& c, int32_
 // append), matches among the newest positions, index lookup with windows.
 // Returns the number of matches; wi tells build_dag which of them have windows;
 // the ticket, if used, must be finished with insert_finish by the caller.
-template <int LCAP, class LDS>
+// QC: compile-time bound of the index's gram length kmax (4 or 8): the loops
+// over query tokens are unrolled to it, and the common step is bound by the
+// instructions one wave issues.
+template <int LCAP, int QC, class LDS>
 __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexView& ix, int32_t p,
                                                   int32_t k, int32_t L, WinInfo& wi,
                                                   InsertTicket& ticket, bool& ticket_used) {
@@ -507,8 +523,8 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
   const int64_t row = (int64_t)p * ix.N + c.i;
   int32_t* gram = const_cast<int32_t*>(c.gram);
   // ---- round trip 1: every load here has an address known from the kernel arguments
-  Head me = load_head(y, ix.tail_len, c.i);             // same address in every lane
-  Head hj = load_head(y, ix.tail_len, lane < y.N ? lane : 0);
+  Head me = load_head<QC>(y, ix.tail_len, c.i);         // same address in every lane
+  Head hj = load_head<QC>(y, ix.tail_len, lane < y.N ? lane : 0);
   int32_t st_i = 0;
   float sp_i = 1.0f;
   if (y.n == 1) {
@@ -521,27 +537,27 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
 #pragma unroll
   for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) {
     int32_t v = 0;
-    if (a < c.q) v = a < cnt_i ? st_i : pick(me.tail, a - cnt_i);
+    if (a < QC && a < c.q) v = a < cnt_i ? st_i : pick_n<QC>(me.tail, a - cnt_i);
     c.Q[a] = v;
   }
   const bool use_index = c.q == ix.kmax;                // shorter queries: scan (short paths)
   // ---- round trip 2 is requested: fill counts for the insert, first 4 buckets of the query
   ticket_used = cnt_i == 1;
-  if (ticket_used) ticket = insert_begin(gram, c.bucket_mask, ix.kmax, me.tail, old_i, lane);
+  if (ticket_used) ticket = insert_begin<QC>(gram, c.bucket_mask, ix.kmax, me.tail, old_i, lane);
   GramHash gh{0u, 1u};
   int32_t word = -1;
   if (use_index) {
-    gh = query_hash(c);
+    gh = query_hash<QC>(c);
     uint32_t r = (uint32_t)(lane >> 4);
     word = gram_bucket(gram, gh, r <= c.bucket_mask ? r : 0u, c.bucket_mask)[lane & 15];
   }
   // ---- while it travels: own append, lengths into LDS, matches among the new positions
-  if (y.n == 1) append_own_single(ix, y, row, c.i, me, st_i, sp_i, lane);
+  if (y.n == 1) append_own_single<QC>(ix, y, row, c.i, me, st_i, sp_i, lane);
   int32_t n_match = 0;
   for (int32_t j0 = 0; j0 < y.N; j0 += kWave) {
     int32_t j = j0 + lane;
     bool have = j < y.N;
-    if (j0 > 0) hj = load_head(y, ix.tail_len, have ? j : 0);
+    if (j0 > 0) hj = load_head<QC>(y, ix.tail_len, have ? j : 0);
     if (have && j < kLenCache) {
       s.len_old[j] = hj.old_len;
       s.len_new[j] = hj.new_len;
@@ -549,14 +565,14 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
     // a position appended by this very launch matches when the old tail before it is the query
     bool hit = use_index && have && j != c.i && hj.new_len > hj.old_len && hj.old_len >= c.q;
 #pragma unroll
-    for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) hit = hit && (a >= c.q || hj.tail[a] == c.Q[a]);
+    for (int a = 0; a < QC; ++a) hit = hit && (a >= c.q || hj.tail[a] == c.Q[a]);
     wave_push(s, n_match, hit, make_match(y, j, hj.old_len, hj.old_len, hj.new_len), lane);
   }
   if (ticket_used) insert_claim(ticket, gram, c.bucket_mask, lane);   // round trip 3 starts
   wi.n_fresh = n_match;
   wi.win_cap = use_index ? LDS::kWin / (2 * L) : 0;
   if (use_index) {
-    lookup_with_windows<LCAP>(s, c, L, wi.win_cap, wi.n_fresh, n_match, gh, word);
+    lookup_with_windows<LCAP, QC>(s, c, L, wi.win_cap, wi.n_fresh, n_match, gh, word);
   } else if (c.q > 0) {
     WaveListSink<LDS> sink{&s, &n_match, lane};
     match_plain<false>(s, c, sink);                     // covers old and new positions alike
