@@ -153,6 +153,69 @@ __device__ __forceinline__ Tier1 build_dag(LDS& s, const Ctx& c, int32_t M, int3
   return t1;
 }
 
+// Tier 0, for one wave and M * L <= 64: no tables at all.  Lane (d-1) * M + m
+// holds instance (layer d, match m) — its predecessor u, its token v and its
+// weight — and each layer of the walk is a few ballots and lane reads: the
+// successors of the current node are the instances of the layer with u == cur;
+// a successor's rank is the sum of the weights of the layer's instances with
+// the same token (its in-weight; score_mode 1: of those with u == cur only).
+// Same sums as the tables of tier 1, in exact integers, so the same draft.
+template <class LDS>
+__device__ __forceinline__ void walk_instances(LDS& s, const Ctx& c, int32_t M, int32_t L, WinInfo wi,
+                                               uint32_t alpha_q, int score_mode, DraftOut& o) {
+  const int lane = c.tid;
+  const int32_t items = M * L;                        // <= 64
+  int32_t d_mine = (int32_t)((float)lane * (1.0f / (float)M));   // lane / M, fixed up below
+  d_mine += (d_mine + 1) * M <= lane;
+  d_mine -= d_mine * M > lane;
+  d_mine += 1;
+  const int32_t mi = lane - (d_mine - 1) * M;
+  uint32_t u = kAnyTok, v = 0;
+  u64 key = 0;
+  bool alive = false;
+  if (lane < items) {
+    Match m = s.match[mi];
+    u64 w;
+    int32_t ws = mi - wi.n_fresh;
+    if (ws >= 0 && ws < wi.win_cap) {                 // cached: no memory access
+      alive = d_mine <= (int32_t)m.rem_new;
+      const int32_t* win = s.win + ws * 2 * L;
+      v = (uint32_t)win[d_mine - 1];
+      u = d_mine == 1 ? (uint32_t)c.Q[0] : (uint32_t)win[d_mine - 2];
+      w = pack_cs(1u, (uint32_t)win[L + d_mine - 1]);
+    } else {
+      alive = layer_instance(c.y, m, d_mine, (uint32_t)c.Q[0], u, v, w);
+    }
+    key = weight_key(w, alpha_q);
+  }
+  const uint32_t key_lo = (uint32_t)key, key_hi = (uint32_t)(key >> 32);
+  int32_t cur = c.Q[0];
+  for (int32_t d = 1; d <= L; ++d) {
+    const bool in_layer = alive && d_mine == d;
+    const u64 from_cur = __ballot(in_layer && u == (uint32_t)cur);
+    u64 todo = from_cur;
+    Cand best = cand_none();
+    while (todo) {                                    // one round per distinct successor token
+      const int src = (int)__ffsll((long long)todo) - 1;
+      const uint32_t vt = (uint32_t)__builtin_amdgcn_readlane((int)v, src);
+      const u64 same = __ballot(in_layer && v == vt);
+      u64 group = score_mode ? (same & from_cur) : same;
+      u64 sum = 0;
+      while (group) {                                 // at most M instances
+        const int g = (int)__ffsll((long long)group) - 1;
+        sum += ((u64)(uint32_t)__builtin_amdgcn_readlane((int)key_hi, g) << 32) |
+               (u64)(uint32_t)__builtin_amdgcn_readlane((int)key_lo, g);
+        group &= group - 1;
+      }
+      best = cand_best(best, Cand{sum, (int32_t)vt});
+      todo &= ~same;
+    }
+    if (best.v == INT_MAX) break;                     // leaf: no edge leaves cur
+    note_choice(o, best, d, c.tid);
+    cur = best.v;
+  }
+}
+
 // Replaces the value of every edge slot by the weight the greedy step ranks it
 // by: the in-weight of its target node (score_mode 0, the rule after Eq. 5) or
 // its own weight (mode 1).  Node slots are only read.  The caller synchronises.
