@@ -153,29 +153,32 @@ __device__ __forceinline__ Tier1 build_dag(LDS& s, const Ctx& c, int32_t M, int3
   return t1;
 }
 
-// Tier 0, for one wave and M * L <= 64: no tables at all.  Lane (d-1) * M + m
-// holds instance (layer d, match m) — its predecessor u, its token v and its
-// weight — and each layer of the walk is a few ballots and lane reads: the
-// successors of the current node are the instances of the layer with u == cur;
-// a successor's rank is the sum of the weights of the layer's instances with
-// the same token (its in-weight; score_mode 1: of those with u == cur only).
-// Same sums as the tables of tier 1, in exact integers, so the same draft.
+// Smallest g with 2^g >= M (M >= 1).
+__device__ __forceinline__ int lanes_log2(int32_t M) { return M <= 1 ? 0 : 32 - __clz(M - 1); }
+
+// Tier 0, for one wave and few matches: no tables at all.  Every layer owns an
+// aligned group of G = 2^g lanes (M <= G, G * L <= 64); lane (d-1) * G + m holds
+// instance (layer d, match m): its predecessor u, its token v and its weight.
+// Before the walk every lane sums the weights of the lanes of its group with the
+// same token (the in-weight of its node; score_mode 1: with the same u as well:
+// the weight of its edge) in G - 1 exchanges with lane ^ 1 .. lane ^ (G-1).  The
+// serial part of a layer is then a compare, a ballot and three lane reads when
+// all successors of the current node are the same token, which is the common
+// case.  Same sums as the tables of tier 1, in exact integers: the same draft.
 template <class LDS>
-__device__ __forceinline__ void walk_instances(LDS& s, const Ctx& c, int32_t M, int32_t L, WinInfo wi,
-                                               uint32_t alpha_q, int score_mode, DraftOut& o) {
+__device__ __forceinline__ void walk_instances(LDS& s, const Ctx& c, int32_t M, int32_t L, int g,
+                                               WinInfo wi, uint32_t alpha_q, int score_mode,
+                                               DraftOut& o) {
+  constexpr uint32_t kDeadU = 0xFFFFFFFEu, kDeadV = 0xFFFFFFFFu;   // no token: ids are < 2^29
   const int lane = c.tid;
-  const int32_t items = M * L;                        // <= 64
-  int32_t d_mine = (int32_t)((float)lane * (1.0f / (float)M));   // lane / M, fixed up below
-  d_mine += (d_mine + 1) * M <= lane;
-  d_mine -= d_mine * M > lane;
-  d_mine += 1;
-  const int32_t mi = lane - (d_mine - 1) * M;
-  uint32_t u = kAnyTok, v = 0;
+  const int32_t G = 1 << g;
+  const int32_t d_mine = (lane >> g) + 1, mi = lane & (G - 1);
+  uint32_t u = kDeadU, v = kDeadV;
   u64 key = 0;
-  bool alive = false;
-  if (lane < items) {
+  if (mi < M && d_mine <= L) {
     Match m = s.match[mi];
     u64 w;
+    bool alive;
     int32_t ws = mi - wi.n_fresh;
     if (ws >= 0 && ws < wi.win_cap) {                 // cached: no memory access
       alive = d_mine <= (int32_t)m.rem_new;
@@ -186,33 +189,59 @@ __device__ __forceinline__ void walk_instances(LDS& s, const Ctx& c, int32_t M, 
     } else {
       alive = layer_instance(c.y, m, d_mine, (uint32_t)c.Q[0], u, v, w);
     }
-    key = weight_key(w, alpha_q);
+    key = alive ? weight_key(w, alpha_q) : 0ull;
+    u = alive ? u : kDeadU;
+    v = alive ? v : kDeadV;
   }
-  const uint32_t key_lo = (uint32_t)key, key_hi = (uint32_t)(key >> 32);
+  auto from = [](int addr, uint32_t x) { return (uint32_t)__builtin_amdgcn_ds_bpermute(addr, (int)x); };
+  auto from64 = [&](int addr, u64 x) {
+    return ((u64)from(addr, (uint32_t)(x >> 32)) << 32) | from(addr, (uint32_t)x);
+  };
+  auto lane64 = [](u64 x, int src) {
+    return ((u64)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(x >> 32), src) << 32) |
+           (u64)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)x, src);
+  };
+  u64 rank = key;
+  for (int r = 1; r < G; ++r) {
+    const int addr = (lane ^ r) << 2;
+    uint32_t pv = from(addr, v), pu = from(addr, u);
+    u64 pk = from64(addr, key);
+    bool add = pv == v && (score_mode == 0 || pu == u);
+    rank += add ? pk : 0ull;
+  }
   int32_t cur = c.Q[0];
+  int32_t chosen = 0;                                 // lane d-1: the lane layer d's choice sits in
+  u64 layer = G >= 64 ? ~0ull : (1ull << G) - 1;
   for (int32_t d = 1; d <= L; ++d) {
-    const bool in_layer = alive && d_mine == d;
-    const u64 from_cur = __ballot(in_layer && u == (uint32_t)cur);
-    u64 todo = from_cur;
-    Cand best = cand_none();
-    while (todo) {                                    // one round per distinct successor token
-      const int src = (int)__ffsll((long long)todo) - 1;
-      const uint32_t vt = (uint32_t)__builtin_amdgcn_readlane((int)v, src);
-      const u64 same = __ballot(in_layer && v == vt);
-      u64 group = score_mode ? (same & from_cur) : same;
-      u64 sum = 0;
-      while (group) {                                 // at most M instances
-        const int g = (int)__ffsll((long long)group) - 1;
-        sum += ((u64)(uint32_t)__builtin_amdgcn_readlane((int)key_hi, g) << 32) |
-               (u64)(uint32_t)__builtin_amdgcn_readlane((int)key_lo, g);
-        group &= group - 1;
+    const u64 cand = __ballot(u == (uint32_t)cur) & layer;
+    if (!cand) break;                                 // leaf: no edge leaves cur
+    int src = (int)__ffsll((long long)cand) - 1;
+    uint32_t vt = (uint32_t)__builtin_amdgcn_readlane((int)v, src);
+    u64 best = lane64(rank, src);
+    u64 rest = cand & ~__ballot(v == vt);
+    while (rest) {                                    // the matches disagree: one round per token
+      const int other = (int)__ffsll((long long)rest) - 1;
+      const uint32_t vo = (uint32_t)__builtin_amdgcn_readlane((int)v, other);
+      const u64 ko = lane64(rank, other);
+      rest &= ~__ballot(v == vo);
+      if (ko > best || (ko == best && vo < vt)) {     // larger weight, then lower token id
+        best = ko;
+        vt = vo;
+        src = other;
       }
-      best = cand_best(best, Cand{sum, (int32_t)vt});
-      todo &= ~same;
     }
-    if (best.v == INT_MAX) break;                     // leaf: no edge leaves cur
-    note_choice(o, best, d, c.tid);
-    cur = best.v;
+    chosen = lane == d - 1 ? src : chosen;
+    o.key_sum += best;
+    o.n = d;
+    cur = (int32_t)vt;
+    layer = (layer << (G - 1)) << 1;
+  }
+  const int addr = chosen << 2;
+  const uint32_t tok = from(addr, v);
+  const u64 k = from64(addr, rank);
+  if (lane < o.n) {
+    o.tok = (int32_t)tok;
+    o.key = k;
   }
 }
 

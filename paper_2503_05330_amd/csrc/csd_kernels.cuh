@@ -247,8 +247,8 @@ __global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn i
     };
     if (a.pool_mode == CSD_POOL_TREE) walk_tree<kWave>(s, c, wi, M, L, a.alpha_q, ix.status, o, each);
     else walk_list<kWave>(s, c, wi, L, a.alpha_q, o, each);
-  } else if (M > 0 && M * L <= kWave) {
-    walk_instances(s, c, M, L, wi, a.alpha_q, a.score_mode, o);      // few matches: no tables
+  } else if (M > 0 && M <= kWave && (L << lanes_log2(M)) <= kWave) {
+    walk_instances(s, c, M, L, lanes_log2(M), wi, a.alpha_q, a.score_mode, o);   // few matches: no tables
   } else if (M > 0) {
     bool streaming = M > LDS::kMatch;
     if (!streaming) {
