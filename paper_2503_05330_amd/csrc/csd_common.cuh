@@ -64,6 +64,11 @@ __device__ __forceinline__ uint32_t quantize_prob(float p) {
   return (uint32_t)x;
 }
 
+// Lanes of the wave for which the condition holds.  Ballots of single compares combined with
+// scalar ANDs are cheaper than one ballot of a compound condition, which the compiler turns
+// into a select and a second compare.
+__device__ __forceinline__ u64 wave_ballot(bool b) { return __builtin_amdgcn_ballot_w64(b); }
+
 // ---------------------------------------------------------------- argmax reductions
 
 struct Cand {      // a successor proposed for the greedy step
@@ -106,7 +111,7 @@ __device__ __forceinline__ Cand dpp_step(Cand c) {
 // reads.  Otherwise four row_shr steps scan each row of 16 lanes, row_bcast:15
 // and row_bcast:31 carry the row results up, and lane 63 ends with the total.
 __device__ __forceinline__ Cand wave_argmax(Cand c) {
-  u64 have = __ballot(c.v != INT_MAX);
+  u64 have = wave_ballot(c.v != INT_MAX);
   if (have == 0) return cand_none();
   if ((have & (have - 1)) == 0) return cand_from_lane(c, (int)__ffsll((long long)have) - 1);
   c = dpp_step<0x111, 0xF>(c);   // row_shr:1
@@ -116,6 +121,31 @@ __device__ __forceinline__ Cand wave_argmax(Cand c) {
   c = dpp_step<0x142, 0xA>(c);   // row_bcast:15 into rows 1 and 3
   c = dpp_step<0x143, 0xC>(c);   // row_bcast:31 into rows 2 and 3
   return cand_from_lane(c, 63);
+}
+
+// x in the lanes of the mask, 0 in the others.  (The two idle cycles behind it: a DPP
+// instruction may not read a register sooner after it was written, and the compiler does
+// not look into an asm statement to see that this one writes it.)
+__device__ __forceinline__ uint32_t lanes_of(u64 mask, uint32_t x) {
+  uint32_t r;
+  asm("v_cndmask_b32_e64 %0, 0, %1, %2\n\ts_nop 1" : "=v"(r) : "v"(x), "s"(mask));
+  return r;
+}
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_add(uint32_t x) {   // lanes the pattern does not reach add 0
+  return x + (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, ROW_MASK, 0xF, false);
+}
+
+// Sum over the 64 lanes of a wave (the same lane moves as wave_argmax); every lane gets it.
+__device__ __forceinline__ uint32_t wave_sum(uint32_t x) {
+  x = dpp_add<0x111, 0xF>(x);    // row_shr:1
+  x = dpp_add<0x112, 0xF>(x);    // row_shr:2
+  x = dpp_add<0x114, 0xF>(x);    // row_shr:4
+  x = dpp_add<0x118, 0xF>(x);    // row_shr:8
+  x = dpp_add<0x142, 0xA>(x);    // row_bcast:15 into rows 1 and 3
+  x = dpp_add<0x143, 0xC>(x);    // row_bcast:31 into rows 2 and 3
+  return (uint32_t)__builtin_amdgcn_readlane((int)x, 63);
 }
 
 // arr[idx] for idx < N without indexing registers by a variable (0 when idx is out of range)

@@ -89,9 +89,11 @@ __device__ __forceinline__ void note_choice(DraftOut& o, Cand best, int32_t d, i
 
 // ---------------------------------------------------------------- tier 1: everything in LDS
 
-// Matches n_fresh .. n_fresh + win_cap - 1 of the list have their continuation cached in LDS.
+// Matches n_fresh .. win_cap - 1 of the list have their continuation cached in LDS (match x in
+// window x).
 struct WinInfo {
   int32_t n_fresh, win_cap;
+  __device__ __forceinline__ bool cached(int32_t mi) const { return mi >= n_fresh && mi < win_cap; }
 };
 
 struct Tier1 {                  // geometry of the table for one query
@@ -132,8 +134,8 @@ __device__ __forceinline__ Tier1 build_dag(LDS& s, const Ctx& c, int32_t M, int3
     uint32_t u, v;
     u64 w;
     bool alive;
-    int32_t ws = mi - wi.n_fresh;
-    if (ws >= 0 && ws < wi.win_cap) {                 // cached: no memory access
+    const int32_t ws = mi;
+    if (wi.cached(mi)) {                              // no memory access
       alive = d <= (int32_t)m.rem_new;
       const int32_t* win = s.win + ws * 2 * L;
       v = (uint32_t)win[d - 1];
@@ -179,8 +181,8 @@ __device__ __forceinline__ void walk_instances(LDS& s, const Ctx& c, int32_t M, 
     Match m = s.match[mi];
     u64 w;
     bool alive;
-    int32_t ws = mi - wi.n_fresh;
-    if (ws >= 0 && ws < wi.win_cap) {                 // cached: no memory access
+    const int32_t ws = mi;
+    if (wi.cached(mi)) {                              // no memory access
       alive = d_mine <= (int32_t)m.rem_new;
       const int32_t* win = s.win + ws * 2 * L;
       v = (uint32_t)win[d_mine - 1];
@@ -213,17 +215,17 @@ __device__ __forceinline__ void walk_instances(LDS& s, const Ctx& c, int32_t M, 
   int32_t chosen = 0;                                 // lane d-1: the lane layer d's choice sits in
   u64 layer = G >= 64 ? ~0ull : (1ull << G) - 1;
   for (int32_t d = 1; d <= L; ++d) {
-    const u64 cand = __ballot(u == (uint32_t)cur) & layer;
+    const u64 cand = wave_ballot(u == (uint32_t)cur) & layer;
     if (!cand) break;                                 // leaf: no edge leaves cur
     int src = (int)__ffsll((long long)cand) - 1;
     uint32_t vt = (uint32_t)__builtin_amdgcn_readlane((int)v, src);
     u64 best = lane64(rank, src);
-    u64 rest = cand & ~__ballot(v == vt);
+    u64 rest = cand & ~wave_ballot(v == vt);
     while (rest) {                                    // the matches disagree: one round per token
       const int other = (int)__ffsll((long long)rest) - 1;
       const uint32_t vo = (uint32_t)__builtin_amdgcn_readlane((int)v, other);
       const u64 ko = lane64(rank, other);
-      rest &= ~__ballot(v == vo);
+      rest &= ~wave_ballot(v == vo);
       if (ko > best || (ko == best && vo < vt)) {     // larger weight, then lower token id
         best = ko;
         vt = vo;
@@ -242,6 +244,62 @@ __device__ __forceinline__ void walk_instances(LDS& s, const Ctx& c, int32_t M, 
   if (lane < o.n) {
     o.tok = (int32_t)tok;
     o.key = k;
+  }
+}
+
+// Tier 0 for up to 64 matches that all have (or get) an LDS window: lane m holds
+// match m and reads its continuation one layer ahead of the walk.  A layer's
+// successors are the lanes whose previous token is the current node; a
+// successor's count is the population of a ballot, its probability sum one wave
+// reduction, and from the two follows its weight (Eq. 5) exactly as the tables
+// of tier 1 would hold it.  Matches without a window (found among the newest
+// positions) write theirs first.
+template <class LDS>
+__device__ __forceinline__ void walk_matches(LDS& s, const Ctx& c, int32_t M, int32_t L, WinInfo wi,
+                                             uint32_t alpha_q, int score_mode, DraftOut& o) {
+  const int lane = c.tid;
+  int32_t rem = 0;                                    // layers this lane's match reaches
+  int32_t* win = s.win + (lane < M ? lane : 0) * 2 * L;
+  if (lane < M) {
+    Match m = s.match[lane];
+    rem = (int32_t)m.rem_new < L ? (int32_t)m.rem_new : L;
+    if (!wi.cached(lane)) {
+      for (int32_t d = 1; d <= rem; ++d) {
+        uint32_t u, v;
+        u64 w;
+        layer_instance(c.y, m, d, 0u, u, v, w);
+        win[d - 1] = (int32_t)v;
+        win[L + d - 1] = (int32_t)cs_sum(w);
+      }
+    }
+  }
+  uint32_t u = (uint32_t)c.Q[0], v = (uint32_t)win[0], p = (uint32_t)win[L];
+  int32_t cur = c.Q[0];
+  const uint32_t per_count = 65536u - alpha_q;        // Eq. 5 in fixed point, as weight_key()
+  for (int32_t d = 1; d <= L; ++d) {
+    const int32_t ahead = d < L ? d : L - 1;          // layer d + 1 travels while d is decided
+    const uint32_t v_next = (uint32_t)win[ahead], p_next = (uint32_t)win[L + ahead];
+    const u64 alive = wave_ballot(d <= rem);
+    const u64 cand = wave_ballot(u == (uint32_t)cur) & alive;
+    if (!cand) break;                                 // leaf: no edge leaves cur
+    const u64 counted = score_mode ? cand : alive;    // whose weight a successor's rank sums
+    u64 todo = cand;
+    auto successor = [&]() {                          // the token of todo's first lane, and its rank
+      const int src = (int)__ffsll((long long)todo) - 1;
+      const uint32_t vt = (uint32_t)__builtin_amdgcn_readlane((int)v, src);
+      const u64 same = wave_ballot(v == vt) & counted;
+      const uint32_t count = (uint32_t)__popcll(same);
+      const uint32_t sum = wave_sum(lanes_of(same, p));
+      todo &= ~same;
+      return Cand{(u64)alpha_q * sum + ((u64)(per_count * count) << 16), (int32_t)vt};
+    };
+    Cand best = successor();
+    while (todo) best = cand_best(best, successor()); // the matches disagree: one round per token
+    note_choice(o, best, d, lane);
+    cur = best.v;
+    u = v;
+    v = v_next;
+    p = p_next;
   }
 }
 
@@ -416,8 +474,8 @@ template <class LDS>
 __device__ __forceinline__ void continuation_at(const LDS& s, const Ctx& c, WinInfo wi, int32_t L,
                                                 int32_t mi, Match m, int32_t d, uint32_t& v,
                                                 uint32_t& p) {
-  int32_t ws = mi - wi.n_fresh;
-  if (mi >= 0 && ws >= 0 && ws < wi.win_cap) {
+  const int32_t ws = mi;
+  if (wi.cached(mi)) {
     const int32_t* win = s.win + ws * 2 * L;
     v = (uint32_t)win[d - 1];
     p = (uint32_t)win[L + d - 1];

@@ -56,7 +56,7 @@ __device__ __forceinline__ void gram_insert_from(int32_t* tbl, uint32_t mask, Gr
   for (; r0 <= mask; r0 += kWave) {
     uint32_t r = r0 + lane;
     bool open = r <= mask && gram_bucket(tbl, gh, r, mask)[0] < kBucketSlots;
-    u64 m = __ballot(open);
+    u64 m = wave_ballot(open);
     while (m) {
       uint32_t first = (uint32_t)__ffsll((long long)m) - 1u;
       int32_t* b = gram_bucket(tbl, gh, r0 + first, mask);
@@ -120,7 +120,7 @@ __device__ __forceinline__ void insert_claim(InsertTicket& t, int32_t* gram, uin
                                              int lane) {
   consume_here(t.fill);
   bool open = t.live && lane < kInsertLanes && (uint32_t)lane <= mask && t.fill < kBucketSlots;
-  u64 m = __ballot(open);
+  u64 m = wave_ballot(open);
   t.first = m ? (int32_t)__ffsll((long long)m) - 1 : -1;
   if (t.live && lane == 0 && t.first >= 0)
     t.claimed = atomicAdd(gram_bucket(gram, t.gh, (uint32_t)t.first, mask), 1);
@@ -217,7 +217,7 @@ __device__ __forceinline__ void variants_claim(VariantTicket& t, int32_t* gram, 
                                                int lane) {
   consume_here(t.fill);
   bool open = t.live && (uint32_t)(lane & 15) <= mask && t.fill < kBucketSlots;
-  uint32_t mine = (uint32_t)(__ballot(open) >> (lane & 48)) & 0xFFFFu;   // this group's 16 lanes
+  uint32_t mine = (uint32_t)(wave_ballot(open) >> (lane & 48)) & 0xFFFFu;   // this group's 16 lanes
   t.first = mine ? (int32_t)__ffs(mine) - 1 : -1;
   if (t.live && (lane & 15) == 0 && t.first >= 0)
     t.claimed = atomicAdd(gram_bucket(gram, t.gh, (uint32_t)t.first, mask), 1);

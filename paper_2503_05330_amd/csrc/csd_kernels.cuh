@@ -55,7 +55,7 @@ __device__ __forceinline__ void write_outputs(const DraftArgs& a, int32_t row, c
 __device__ __forceinline__ void write_accept(const DraftArgs& a, int32_t row, const DraftOut& o,
                                              int32_t target, int tid) {
   bool same = tid < o.n && target == o.tok;
-  u64 differs = __ballot(!same);
+  u64 differs = wave_ballot(!same);
   if (tid == 0) a.accept_len[row] = differs ? (int32_t)__ffsll((long long)differs) - 1 : kWave;
 }
 
@@ -249,6 +249,8 @@ __global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn i
     else walk_list<kWave>(s, c, wi, L, a.alpha_q, o, each);
   } else if (M > 0 && M <= kWave && (L << lanes_log2(M)) <= kWave) {
     walk_instances(s, c, M, L, lanes_log2(M), wi, a.alpha_q, a.score_mode, o);   // few matches: no tables
+  } else if (M > 0 && M <= kWave && M <= LDS::kWin / (2 * L)) {
+    walk_matches(s, c, M, L, wi, a.alpha_q, a.score_mode, o);                    // one lane per match
   } else if (M > 0) {
     bool streaming = M > LDS::kMatch;
     if (!streaming) {

@@ -25,7 +25,7 @@ template <int NT>
 __device__ __forceinline__ void tokens_before(const Ctx& c, int32_t j, int32_t e, int32_t old_j,
                                               int32_t want, int32_t (&t)[NT]) {
   bool deep = e <= old_j && e >= NT;
-  if (__ballot(!deep) == 0) {
+  if (wave_ballot(!deep) == 0) {
     const int32_t* newest = c.y.tok + c.y.cell(j, e - 1);
 #pragma unroll
     for (int a = 0; a < NT; ++a) t[a] = newest[-a];
@@ -113,7 +113,7 @@ template <class LDS>
 struct ListSink {
   LDS* s;
   __device__ __forceinline__ void push(const Paths&, bool hit, Match m) {
-    u64 mask = __ballot(hit);
+    u64 mask = wave_ballot(hit);
     if (mask == 0) return;
     int lane = __lane_id();
     int base = 0;
@@ -279,7 +279,7 @@ __device__ __forceinline__ void match_scan(const LDS& s, const Ctx& c, Sink& sin
         }
       }
     }
-    while (__ballot(todo != 0) != 0) {                     // uniform over the wave
+    while (wave_ballot(todo != 0) != 0) {                     // uniform over the wave
       bool have = todo != 0;
       int32_t bit = have ? (int32_t)__ffs(todo) - 1 : 0;
       todo &= todo - 1u;                                   // 0 stays 0
@@ -368,7 +368,7 @@ __device__ __forceinline__ Head load_head(const Paths& y, int32_t tail_len, int3
 // in a register).  Returns each hit's slot, -1 for lanes without one.
 template <class LDS>
 __device__ __forceinline__ int32_t wave_push(LDS& s, int32_t& n_match, bool hit, Match m, int lane) {
-  u64 mask = __ballot(hit);
+  u64 mask = wave_ballot(hit);
   int32_t slot = n_match + (int32_t)__popcll(mask & ((1ull << lane) - 1ull));
   n_match += (int32_t)__popcll(mask);
   if (!hit) return -1;
@@ -417,7 +417,7 @@ __device__ __forceinline__ void append_own_single(const IndexView& ix, const Pat
 // Eq. 3 through the hash index with the continuations fetched in the same
 // round trip as the verification.  `word` is the lane's word of the first batch
 // of 4 buckets, already requested.  Adds its hits behind the n_fresh matches
-// already listed; hit number x (0-based among these) gets window x.
+// already listed; match number x of the list gets window x (if x < win_cap).
 template <int LCAP, int QC, class LDS>
 __device__ __forceinline__ void lookup_with_windows(LDS& s, const Ctx& c, int32_t L,
                                                     int32_t win_cap, int32_t n_fresh,
@@ -433,7 +433,7 @@ __device__ __forceinline__ void lookup_with_windows(LDS& s, const Ctx& c, int32_
     if (r0 + grp >= n_buckets) word = -1;
     int32_t count = __shfl(word, lane & ~15);
     bool full = count >= kBucketSlots;
-    bool seq_ends = __ballot(!full || r0 + grp >= n_buckets) != 0;
+    bool seq_ends = wave_ballot(!full || r0 + grp >= n_buckets) != 0;
     int32_t next_word = -1;           // next batch: in flight while this one is processed
     if (!seq_ends) {
       uint32_t r = r0 + 4 + grp;
@@ -475,7 +475,7 @@ __device__ __forceinline__ void lookup_with_windows(LDS& s, const Ctx& c, int32_
 #pragma unroll
       for (int a = 0; a < QC; ++a) hit = hit && (a >= c.q || tv[a] == c.Q[a]);
     }
-    if (__ballot(hit && rem > n_hist) != 0) {            // rare: runs into this step's new tokens
+    if (wave_ballot(hit && rem > n_hist) != 0) {            // rare: runs into this step's new tokens
 #pragma unroll
       for (int d = 0; d < LCAP; ++d)
         if (hit && d >= n_hist && d < rem) {
@@ -484,7 +484,7 @@ __device__ __forceinline__ void lookup_with_windows(LDS& s, const Ctx& c, int32_
         }
     }
     int32_t slot = wave_push(s, n_match, hit, make_match(y, j, e, old_j, new_j), lane);
-    int32_t w = slot - n_fresh;
+    int32_t w = slot;                 // a match's window has the match's number
     if (slot >= 0 && w < win_cap) {
       int32_t* win = s.win + w * 2 * L;
       if (L == LCAP) {                // the whole window at once; entries beyond rem are never read
@@ -693,7 +693,7 @@ __device__ __forceinline__ bool consume_variant_bucket(LDS& s, const Ctx& c, int
   }
   // each position once: for the first variant it shares with the query
   bool hit = cand && near_query(c, e, tv) && variant_counts(c, tv, my_u, filed_as);
-  if (__ballot(hit && rem > n_hist) != 0) {              // rare: runs into this step's new tokens
+  if (wave_ballot(hit && rem > n_hist) != 0) {              // rare: runs into this step's new tokens
 #pragma unroll
     for (int d = 0; d < LCAP; ++d)
       if (hit && d >= n_hist && d < rem) {
@@ -702,7 +702,7 @@ __device__ __forceinline__ bool consume_variant_bucket(LDS& s, const Ctx& c, int
       }
   }
   int32_t slot = wave_push(s, n_match, hit, make_match(y, j, e, old_j, new_j), lane);
-  int32_t w = slot - n_fresh;
+  int32_t w = slot;                   // a match's window has the match's number
   if (slot >= 0 && w < win_cap) {
     int32_t* win = s.win + w * 2 * L;
 #pragma unroll
@@ -737,7 +737,7 @@ __device__ __forceinline__ void lookup_variants_with_windows(LDS& s, const Ctx& 
     consume_here(word);
     if (!active) word = -1;           // idle groups see an empty bucket
     bool full = consume_variant_bucket<LCAP>(s, c, L, win_cap, n_fresh, n_match, u, word);
-    const u64 goes_on = __ballot(active && full && sub == 0);       // bit 16 g: group g's chain
+    const u64 goes_on = wave_ballot(active && full && sub == 0);       // bit 16 g: group g's chain
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       if ((goes_on >> (16 * g) & 1ull) == 0) continue;              // uniform over the wave
@@ -751,7 +751,7 @@ __device__ __forceinline__ void lookup_variants_with_windows(LDS& s, const Ctx& 
         int32_t next_tail = gram_bucket(tbl, gh, rn < n_buckets ? rn : 0u, c.bucket_mask)[sub];
         bool tail_full = consume_variant_bucket<LCAP>(s, c, L, win_cap, n_fresh, n_match,
                                                       pass * 4 + g, tail);
-        if (__ballot(!tail_full) != 0) break;                       // the chain ends in this batch
+        if (wave_ballot(!tail_full) != 0) break;                       // the chain ends in this batch
         tail = next_tail;
       }
     }
