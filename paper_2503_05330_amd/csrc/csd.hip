@@ -198,9 +198,9 @@ void launch_draft(const csd_index* h, const IndexView& v, const StepIn& in, cons
   } else if (a.pool_mode != CSD_POOL_DAG) {             // tree and list pools: the general kernels
     if (!h->indexed && v.eps > 0) step_scan_kernel<1, true, true><<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
     else if (!h->indexed) step_scan_kernel<1, true, false><<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
-    else if (a.L <= 8) step_wave_kernel<8, true, LdsWave, false, CSD_MAX_QUERY_LEN><<<grid, kWave, 0, st>>>(v, in, a);
-    else if (a.L <= 16) step_wave_kernel<16, true, LdsWave, false, CSD_MAX_QUERY_LEN><<<grid, kWave, 0, st>>>(v, in, a);
-    else step_wave_kernel<32, true, LdsWave, false, CSD_MAX_QUERY_LEN><<<grid, kWave, 0, st>>>(v, in, a);
+    else if (a.L <= 8) step_wave_kernel<8, true, LdsWave, false, CSD_MAX_QUERY_LEN><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
+    else if (a.L <= 16) step_wave_kernel<16, true, LdsWave, false, CSD_MAX_QUERY_LEN><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
+    else step_wave_kernel<32, true, LdsWave, false, CSD_MAX_QUERY_LEN><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
   } else if (!h->indexed && a.L <= 8)
     (v.eps > 0 ? step_scan_kernel<8, false, true> : step_scan_kernel<8, false, false>)
         <<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
@@ -212,21 +212,21 @@ void launch_draft(const csd_index* h, const IndexView& v, const StepIn& in, cons
         <<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
   else if (v.kmax <= 4) {                        // the usual gram lengths: loops unrolled to 4
     if (a.L <= 8 && rows >= kSmallLdsRows)       // more rows than fit the chip at once
-      step_wave_kernel<8, false, LdsWaveSmall, false, 4><<<grid, kWave, 0, st>>>(v, in, a);
+      step_wave_kernel<8, false, LdsWaveSmall, false, 4><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
     else if (a.L <= 8)
-      step_wave_kernel<8, false, LdsWave, false, 4><<<grid, kWave, 0, st>>>(v, in, a);
+      step_wave_kernel<8, false, LdsWave, false, 4><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
     else if (a.L <= 16)
-      step_wave_kernel<16, false, LdsWave, false, 4><<<grid, kWave, 0, st>>>(v, in, a);
+      step_wave_kernel<16, false, LdsWave, false, 4><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
     else
-      step_wave_kernel<32, false, LdsWave, false, 4><<<grid, kWave, 0, st>>>(v, in, a);
+      step_wave_kernel<32, false, LdsWave, false, 4><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
   } else if (a.L <= 8 && rows >= kSmallLdsRows)
-    step_wave_kernel<8, false, LdsWaveSmall, false, 8><<<grid, kWave, 0, st>>>(v, in, a);
+    step_wave_kernel<8, false, LdsWaveSmall, false, 8><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
   else if (a.L <= 8)
-    step_wave_kernel<8, false, LdsWave, false, 8><<<grid, kWave, 0, st>>>(v, in, a);
+    step_wave_kernel<8, false, LdsWave, false, 8><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
   else if (a.L <= 16)
-    step_wave_kernel<16, false, LdsWave, false, 8><<<grid, kWave, 0, st>>>(v, in, a);
+    step_wave_kernel<16, false, LdsWave, false, 8><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
   else
-    step_wave_kernel<32, false, LdsWave, false, 8><<<grid, kWave, 0, st>>>(v, in, a);
+    step_wave_kernel<32, false, LdsWave, false, 8><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
 }
 
 // Host-side bookkeeping shared by csd_append and csd_step.

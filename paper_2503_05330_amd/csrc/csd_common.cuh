@@ -167,9 +167,12 @@ __device__ __forceinline__ int32_t pick(const int32_t (&arr)[SIZE], int32_t idx)
   return r;
 }
 
+// BLOCK == kWave: code run by one wave on its own (a wave's LDS accesses execute in order),
+// possibly beside other waves of the workgroup that do something else: no hardware barrier.
 template <int BLOCK>
 __device__ __forceinline__ void block_sync() {
-  __syncthreads();   // a one-wave workgroup needs no hardware barrier: the compiler drops it
+  if (BLOCK == kWave) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  else __syncthreads();
 }
 
 // ---------------------------------------------------------------- device state

@@ -217,13 +217,27 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
 // FUZZY: the index files every position under its gram's variants and matching tolerates
 // one edit (Eq. 4).
 // QC: compile-time bound (4 or 8) of the index's gram length.
+// Exact matching runs two waves per row (on two SIMDs of the CU): the second does the row's
+// append and index insert, which the draft does not depend on, so that they leave the critical
+// path of the first.  The two never meet at a barrier.
+constexpr int step_wave_threads(bool fuzzy) { return fuzzy ? kWave : 2 * kWave; }
+
 template <int LCAP, bool POOLS, class LDS, bool FUZZY, int QC>
-__global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn in, DraftArgs a) {
+__global__ __launch_bounds__(step_wave_threads(FUZZY)) void step_wave_kernel(IndexView ix, StepIn in,
+                                                                             DraftArgs a) {
+  constexpr bool SPLIT = step_wave_threads(FUZZY) > kWave;
   __shared__ LDS s;
   int32_t row = xcd_row(ix.P * ix.N);
   if (row < 0) return;
   int32_t p;
   Ctx c = make_ctx(ix, in, row, p);
+  if (SPLIT) {
+    c.tid = (int)(threadIdx.x & (kWave - 1));
+    if (__builtin_amdgcn_readfirstlane((int)threadIdx.x) >= kWave) {
+      wave_append<QC>(c, ix, p);
+      return;
+    }
+  }
   const int32_t L = a.L;
   int32_t target = (a.targets && c.tid < L) ? a.targets[(int64_t)row * L + c.tid] : 0;
   WinInfo wi;
@@ -231,7 +245,7 @@ __global__ __launch_bounds__(kWave) void step_wave_kernel(IndexView ix, StepIn i
   VariantTicket tickets;
   bool ticket_used;
   int32_t M = FUZZY ? wave_front_end_fuzzy<LCAP>(s, c, ix, p, a.k, L, wi, tickets, ticket_used)
-                    : wave_front_end<LCAP, QC>(s, c, ix, p, a.k, L, wi, ticket, ticket_used);
+                    : wave_front_end<LCAP, QC, !SPLIT>(s, c, ix, p, a.k, L, wi, ticket, ticket_used);
   block_sync<kWave>();
 
   DraftOut o;

@@ -514,7 +514,9 @@ __device__ __forceinline__ void lookup_with_windows(LDS& s, const Ctx& c, int32_
 // QC: compile-time bound of the index's gram length kmax (4 or 8): the loops
 // over query tokens are unrolled to it, and the common step is bound by the
 // instructions one wave issues.
-template <int LCAP, int QC, class LDS>
+// APPENDS: the wave also appends the row's token and files it in the index (false: another
+// wave of the workgroup does, see wave_append).
+template <int LCAP, int QC, bool APPENDS = true, class LDS>
 __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexView& ix, int32_t p,
                                                   int32_t k, int32_t L, WinInfo& wi,
                                                   InsertTicket& ticket, bool& ticket_used) {
@@ -529,7 +531,7 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
   float sp_i = 1.0f;
   if (y.n == 1) {
     st_i = y.st[c.i];
-    if (y.sp) sp_i = y.sp[c.i];
+    if (APPENDS && y.sp) sp_i = y.sp[c.i];
   }
   const int32_t old_i = me.old_len, cnt_i = me.new_len - me.old_len;
   c.len_i = me.new_len;
@@ -542,7 +544,7 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
   }
   const bool use_index = c.q == ix.kmax;                // shorter queries: scan (short paths)
   // ---- round trip 2 is requested: fill counts for the insert, first 4 buckets of the query
-  ticket_used = cnt_i == 1;
+  ticket_used = APPENDS && cnt_i == 1;
   if (ticket_used) ticket = insert_begin<QC>(gram, c.bucket_mask, ix.kmax, me.tail, old_i, lane);
   GramHash gh{0u, 1u};
   int32_t word = -1;
@@ -552,7 +554,7 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
     word = gram_bucket(gram, gh, r <= c.bucket_mask ? r : 0u, c.bucket_mask)[lane & 15];
   }
   // ---- while it travels: own append, lengths into LDS, matches among the new positions
-  if (y.n == 1) append_own_single<QC>(ix, y, row, c.i, me, st_i, sp_i, lane);
+  if (APPENDS && y.n == 1) append_own_single<QC>(ix, y, row, c.i, me, st_i, sp_i, lane);
   int32_t n_match = 0;
   for (int32_t j0 = 0; j0 < y.N; j0 += kWave) {
     int32_t j = j0 + lane;
@@ -580,6 +582,30 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
   }
   if (lane == 0) s.n_match = n_match;
   return n_match;
+}
+
+// The writing half of a step that appends one token per path, run by a wave of its own beside
+// the one that drafts: the row's token goes to the history and the meta row, its position to
+// the index.  Nothing the drafting waves of this launch read is written here: they take
+// positions from the old lengths on from the step's input, and ignore newer postings.
+template <int QC>
+__device__ __forceinline__ void wave_append(const Ctx& c, const IndexView& ix, int32_t p) {
+  const int lane = c.tid;
+  const Paths& y = c.y;
+  if (y.n != 1) return;
+  const int64_t row = (int64_t)p * ix.N + c.i;
+  int32_t* gram = const_cast<int32_t*>(c.gram);
+  Head me = load_head<QC>(y, ix.tail_len, c.i);
+  const int32_t st_i = y.st[c.i];
+  const float sp_i = y.sp ? y.sp[c.i] : 1.0f;
+  const bool ticket_used = me.new_len - me.old_len == 1;
+  InsertTicket ticket;
+  if (ticket_used) ticket = insert_begin<QC>(gram, c.bucket_mask, ix.kmax, me.tail, me.old_len, lane);
+  append_own_single<QC>(ix, y, row, c.i, me, st_i, sp_i, lane);
+  if (ticket_used) {
+    insert_claim(ticket, gram, c.bucket_mask, lane);
+    insert_finish(ticket, gram, c.bucket_mask, y.pos(c.i, me.new_len - 1), lane);
+  }
 }
 
 // ---------------------------------------------------------------- one edit through the index
