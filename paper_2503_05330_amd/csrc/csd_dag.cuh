@@ -161,19 +161,23 @@ __device__ __forceinline__ int lanes_log2(int32_t M) { return M <= 1 ? 0 : 32 - 
 // Tier 0, for one wave and few matches: no tables at all.  Every layer owns an
 // aligned group of G = 2^g lanes (M <= G, G * L <= 64); lane (d-1) * G + m holds
 // instance (layer d, match m): its predecessor u, its token v and its weight.
-// Before the walk every lane sums the weights of the lanes of its group with the
-// same token (the in-weight of its node; score_mode 1: with the same u as well:
-// the weight of its edge) in G - 1 exchanges with lane ^ 1 .. lane ^ (G-1).  The
-// serial part of a layer is then a compare, a ballot and three lane reads when
-// all successors of the current node are the same token, which is the common
-// case.  Same sums as the tables of tier 1, in exact integers: the same draft.
-template <class LDS>
-__device__ __forceinline__ void walk_instances(LDS& s, const Ctx& c, int32_t M, int32_t L, int g,
+// All lanes work out, in exchanges with the lanes of their own and of the next
+// group (lane ^ r), what the walk needs: the weight of the lanes of the group
+// with the same token (the in-weight of the lane's node; score_mode 1: with the
+// same u as well: the weight of its edge), whether the lane's edge is the one
+// the greedy step takes out of u, and which lane the walk goes on to from it.
+// The walk itself is then one lane read per layer.  Same sums as the tables of
+// tier 1, in exact integers: the same draft.
+// G is a template parameter so that the exchange loops unroll and their lane permutes travel
+// together instead of one round trip through the LDS crossbar per iteration.
+template <int G, class LDS>
+__device__ __forceinline__ void walk_instances(LDS& s, const Ctx& c, int32_t M, int32_t L,
                                                WinInfo wi, uint32_t alpha_q, int score_mode,
                                                DraftOut& o) {
   constexpr uint32_t kDeadU = 0xFFFFFFFEu, kDeadV = 0xFFFFFFFFu;   // no token: ids are < 2^29
+  static_assert(G >= 1 && G <= kWave && (G & (G - 1)) == 0, "a group is a power of two of lanes");
+  constexpr int g = G == 1 ? 0 : G == 2 ? 1 : G == 4 ? 2 : G == 8 ? 3 : G == 16 ? 4 : G == 32 ? 5 : 6;
   const int lane = c.tid;
-  const int32_t G = 1 << g;
   const int32_t d_mine = (lane >> g) + 1, mi = lane & (G - 1);
   uint32_t u = kDeadU, v = kDeadV;
   u64 key = 0;
@@ -203,7 +207,9 @@ __device__ __forceinline__ void walk_instances(LDS& s, const Ctx& c, int32_t M, 
     return ((u64)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(x >> 32), src) << 32) |
            (u64)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)x, src);
   };
+  // rank: the weight the greedy step ranks this lane's edge by
   u64 rank = key;
+#pragma unroll
   for (int r = 1; r < G; ++r) {
     const int addr = (lane ^ r) << 2;
     uint32_t pv = from(addr, v), pu = from(addr, u);
@@ -211,32 +217,37 @@ __device__ __forceinline__ void walk_instances(LDS& s, const Ctx& c, int32_t M, 
     bool add = pv == v && (score_mode == 0 || pu == u);
     rank += add ? pk : 0ull;
   }
-  int32_t cur = c.Q[0];
+  // winner: no lane of the group with the same predecessor has a larger rank, or the same
+  // rank and a lower token id (lanes with the same u and v are all winners, or none is)
+  bool winner = u != kDeadU;
+#pragma unroll
+  for (int r = 1; r < G; ++r) {
+    const int addr = (lane ^ r) << 2;
+    uint32_t pv = from(addr, v), pu = from(addr, u);
+    u64 pr = from64(addr, rank);
+    bool beats = pu == u && (pr > rank || (pr == rank && pv < v));
+    winner = winner && !beats;
+  }
+  // succ: the lane the walk moves to from this one: the first winner of the next layer's group
+  // whose predecessor is this lane's token
+  const uint32_t wu = winner ? u : kDeadU;
+  int32_t succ = kWave;
+#pragma unroll
+  for (int r = 0; r < G; ++r) {
+    const int partner = (lane + G) ^ r;
+    uint32_t pu = from(partner << 2, wu);
+    succ = (pu == v && partner < succ) ? partner : succ;
+  }
+  succ = (winner && d_mine < L && succ < kWave) ? succ : -1;
+  // the serial part: one lane read per layer
+  const u64 first = wave_ballot(winner) & (G >= kWave ? ~0ull : (1ull << G) - 1);
+  int32_t at = first ? (int32_t)__ffsll((long long)first) - 1 : -1;
   int32_t chosen = 0;                                 // lane d-1: the lane layer d's choice sits in
-  u64 layer = G >= 64 ? ~0ull : (1ull << G) - 1;
-  for (int32_t d = 1; d <= L; ++d) {
-    const u64 cand = wave_ballot(u == (uint32_t)cur) & layer;
-    if (!cand) break;                                 // leaf: no edge leaves cur
-    int src = (int)__ffsll((long long)cand) - 1;
-    uint32_t vt = (uint32_t)__builtin_amdgcn_readlane((int)v, src);
-    u64 best = lane64(rank, src);
-    u64 rest = cand & ~wave_ballot(v == vt);
-    while (rest) {                                    // the matches disagree: one round per token
-      const int other = (int)__ffsll((long long)rest) - 1;
-      const uint32_t vo = (uint32_t)__builtin_amdgcn_readlane((int)v, other);
-      const u64 ko = lane64(rank, other);
-      rest &= ~wave_ballot(v == vo);
-      if (ko > best || (ko == best && vo < vt)) {     // larger weight, then lower token id
-        best = ko;
-        vt = vo;
-        src = other;
-      }
-    }
-    chosen = lane == d - 1 ? src : chosen;
-    o.key_sum += best;
+  for (int32_t d = 1; d <= L && at >= 0; ++d) {
+    chosen = lane == d - 1 ? at : chosen;
+    o.key_sum += lane64(rank, at);
     o.n = d;
-    cur = (int32_t)vt;
-    layer = (layer << (G - 1)) << 1;
+    at = __builtin_amdgcn_readlane(succ, at);
   }
   const int addr = chosen << 2;
   const uint32_t tok = from(addr, v);

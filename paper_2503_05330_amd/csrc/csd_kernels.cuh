@@ -261,8 +261,13 @@ __global__ __launch_bounds__(step_wave_threads(FUZZY)) void step_wave_kernel(Ind
     };
     if (a.pool_mode == CSD_POOL_TREE) walk_tree<kWave>(s, c, wi, M, L, a.alpha_q, ix.status, o, each);
     else walk_list<kWave>(s, c, wi, L, a.alpha_q, o, each);
-  } else if (M > 0 && M <= kWave && (L << lanes_log2(M)) <= kWave) {
-    walk_instances(s, c, M, L, lanes_log2(M), wi, a.alpha_q, a.score_mode, o);   // few matches: no tables
+  } else if (M > 0 && M <= 8 && (L << lanes_log2(M)) <= kWave) {                   // few matches: no tables
+    switch (lanes_log2(M)) {
+      case 0: walk_instances<1>(s, c, M, L, wi, a.alpha_q, a.score_mode, o); break;
+      case 1: walk_instances<2>(s, c, M, L, wi, a.alpha_q, a.score_mode, o); break;
+      case 2: walk_instances<4>(s, c, M, L, wi, a.alpha_q, a.score_mode, o); break;
+      default: walk_instances<8>(s, c, M, L, wi, a.alpha_q, a.score_mode, o); break;
+    }
   } else if (M > 0 && M <= kWave && M <= LDS::kWin / (2 * L)) {
     walk_matches(s, c, M, L, wi, a.alpha_q, a.score_mode, o);                    // one lane per match
   } else if (M > 0) {
