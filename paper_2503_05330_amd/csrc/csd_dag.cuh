@@ -265,12 +265,14 @@ __device__ __forceinline__ void walk_instances(LDS& s, const Ctx& c, int32_t M, 
 // reduction, and from the two follows its weight (Eq. 5) exactly as the tables
 // of tier 1 would hold it.  Matches without a window (found among the newest
 // positions) write theirs first.
+// `windows`: M windows of 2 L words (s.win, or any other LDS the caller has free).
 template <class LDS>
 __device__ __forceinline__ void walk_matches(LDS& s, const Ctx& c, int32_t M, int32_t L, WinInfo wi,
-                                             uint32_t alpha_q, int score_mode, DraftOut& o) {
+                                             int32_t* windows, uint32_t alpha_q, int score_mode,
+                                             DraftOut& o) {
   const int lane = c.tid;
   int32_t rem = 0;                                    // layers this lane's match reaches
-  int32_t* win = s.win + (lane < M ? lane : 0) * 2 * L;
+  int32_t* win = windows + (lane < M ? lane : 0) * 2 * L;
   if (lane < M) {
     Match m = s.match[lane];
     rem = (int32_t)m.rem_new < L ? (int32_t)m.rem_new : L;

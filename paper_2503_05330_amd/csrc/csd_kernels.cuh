@@ -174,7 +174,23 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
       // tier 1 when every layer's region is sure to hold its <= 2M keys; else layer by
       // layer with one thread per match (M <= BLOCK); else streaming
       bool done = false;
-      if (2u * (uint32_t)M <= tier1_geometry(M, L, LdsScan::kTable).region) {
+      if (M <= kWave) {
+        // one lane of wave 0 per match, no tables: all threads fetch the continuations into
+        // windows (laid over the unused table), one (match, layer) instance each
+        int32_t* windows = reinterpret_cast<int32_t*>(s.table);
+        for (int32_t idx = c.tid; idx < M * L; idx += BLOCK) {
+          const int32_t mi = idx / L, d = idx - mi * L + 1;
+          uint32_t u, v;
+          u64 w;
+          if (layer_instance(c.y, s.match[mi], d, 0u, u, v, w)) {
+            windows[mi * 2 * L + d - 1] = (int32_t)v;
+            windows[mi * 2 * L + L + d - 1] = (int32_t)cs_sum(w);
+          }
+        }
+        block_sync<BLOCK>();
+        if (c.tid < kWave) walk_matches(s, c, M, L, WinInfo{0, M}, windows, a.alpha_q, a.score_mode, o);
+        done = true;
+      } else if (2u * (uint32_t)M <= tier1_geometry(M, L, LdsScan::kTable).region) {
         Tier1 t1 = build_dag<BLOCK>(s, c, M, L, WinInfo{M, 0}, a.alpha_q);
         done = s.overflow == 0;
         // every thread helps to score large tables; one wave then walks them without
@@ -269,7 +285,7 @@ __global__ __launch_bounds__(step_wave_threads(FUZZY)) void step_wave_kernel(Ind
       default: walk_instances<8>(s, c, M, L, wi, a.alpha_q, a.score_mode, o); break;
     }
   } else if (M > 0 && M <= kWave && M <= LDS::kWin / (2 * L)) {
-    walk_matches(s, c, M, L, wi, a.alpha_q, a.score_mode, o);                    // one lane per match
+    walk_matches(s, c, M, L, wi, s.win, a.alpha_q, a.score_mode, o);             // one lane per match
   } else if (M > 0) {
     bool streaming = M > LDS::kMatch;
     if (!streaming) {

@@ -416,12 +416,12 @@ __device__ __forceinline__ void append_own_single(const IndexView& ix, const Pat
 
 // Eq. 3 through the hash index with the continuations fetched in the same
 // round trip as the verification.  `word` is the lane's word of the first batch
-// of 4 buckets, already requested.  Adds its hits behind the n_fresh matches
-// already listed; match number x of the list gets window x (if x < win_cap).
+// of 4 buckets, already requested.  Adds its hits behind the matches already
+// listed; match number x of the list gets window x (if x < win_cap).
 template <int LCAP, int QC, class LDS>
 __device__ __forceinline__ void lookup_with_windows(LDS& s, const Ctx& c, int32_t L,
-                                                    int32_t win_cap, int32_t n_fresh,
-                                                    int32_t& n_match, GramHash gh, int32_t word) {
+                                                    int32_t win_cap, int32_t& n_match,
+                                                    GramHash gh, int32_t word) {
   const int lane = c.tid;
   const Paths& y = c.y;
   int32_t* tbl = const_cast<int32_t*>(c.gram);
@@ -574,7 +574,7 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
   wi.n_fresh = n_match;
   wi.win_cap = use_index ? LDS::kWin / (2 * L) : 0;
   if (use_index) {
-    lookup_with_windows<LCAP, QC>(s, c, L, wi.win_cap, wi.n_fresh, n_match, gh, word);
+    lookup_with_windows<LCAP, QC>(s, c, L, wi.win_cap, n_match, gh, word);
   } else if (c.q > 0) {
     WaveListSink<LDS> sink{&s, &n_match, lane};
     match_plain<false>(s, c, sink);                     // covers old and new positions alike
@@ -669,9 +669,8 @@ __device__ __forceinline__ bool variant_counts(const Ctx& c, const int32_t (&G)[
 // (its chain goes on).
 template <int LCAP, class LDS>
 __device__ __forceinline__ bool consume_variant_bucket(LDS& s, const Ctx& c, int32_t L,
-                                                       int32_t win_cap, int32_t n_fresh,
-                                                       int32_t& n_match, int32_t my_u,
-                                                       int32_t word) {
+                                                       int32_t win_cap, int32_t& n_match,
+                                                       int32_t my_u, int32_t word) {
   constexpr int K = CSD_MAX_QUERY_LEN;
   const int lane = c.tid;
   const Paths& y = c.y;
@@ -749,8 +748,8 @@ __device__ __forceinline__ bool consume_variant_bucket(LDS& s, const Ctx& c, int
 // lane's word of bucket 0 of its group's first variant, already requested.
 template <int LCAP, class LDS>
 __device__ __forceinline__ void lookup_variants_with_windows(LDS& s, const Ctx& c, int32_t L,
-                                                             int32_t win_cap, int32_t n_fresh,
-                                                             int32_t& n_match, int32_t word) {
+                                                             int32_t win_cap, int32_t& n_match,
+                                                             int32_t word) {
   const int lane = c.tid;
   int32_t* tbl = const_cast<int32_t*>(c.gram);
   const int sub = lane & 15;
@@ -762,7 +761,7 @@ __device__ __forceinline__ void lookup_variants_with_windows(LDS& s, const Ctx& 
     if (pass > 0) word = gram_bucket(tbl, variant_hash(c.Q, c.q, u), 0u, c.bucket_mask)[sub];
     consume_here(word);
     if (!active) word = -1;           // idle groups see an empty bucket
-    bool full = consume_variant_bucket<LCAP>(s, c, L, win_cap, n_fresh, n_match, u, word);
+    bool full = consume_variant_bucket<LCAP>(s, c, L, win_cap, n_match, u, word);
     const u64 goes_on = wave_ballot(active && full && sub == 0);       // bit 16 g: group g's chain
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
@@ -775,7 +774,7 @@ __device__ __forceinline__ void lookup_variants_with_windows(LDS& s, const Ctx& 
         if (r0 + grp >= n_buckets) tail = -1;
         uint32_t rn = r0 + 4 + grp;                                 // next batch: in flight meanwhile
         int32_t next_tail = gram_bucket(tbl, gh, rn < n_buckets ? rn : 0u, c.bucket_mask)[sub];
-        bool tail_full = consume_variant_bucket<LCAP>(s, c, L, win_cap, n_fresh, n_match,
+        bool tail_full = consume_variant_bucket<LCAP>(s, c, L, win_cap, n_match,
                                                       pass * 4 + g, tail);
         if (wave_ballot(!tail_full) != 0) break;                       // the chain ends in this batch
         tail = next_tail;
@@ -865,7 +864,7 @@ __device__ __forceinline__ int32_t wave_front_end_fuzzy(LDS& s, Ctx& c, const In
   wi.n_fresh = n_match;
   wi.win_cap = use_index ? LDS::kWin / (2 * L) : 0;
   if (use_index) {
-    lookup_variants_with_windows<LCAP>(s, c, L, wi.win_cap, wi.n_fresh, n_match, word);
+    lookup_variants_with_windows<LCAP>(s, c, L, wi.win_cap, n_match, word);
   } else if (c.q > 0) {
     WaveListSink<LDS> sink{&s, &n_match, lane};
     match_plain<true>(s, c, sink);                      // covers old and new positions alike
