@@ -6,6 +6,8 @@
 // greedy layer-wise extraction (rule after Eq. 5, Algorithm 1).
 #pragma once
 
+#include <type_traits>
+
 #include <hip/hip_runtime.h>
 
 #include <climits>
@@ -121,6 +123,28 @@ __device__ __forceinline__ Cand wave_argmax(Cand c) {
   c = dpp_step<0x142, 0xA>(c);   // row_bcast:15 into rows 1 and 3
   c = dpp_step<0x143, 0xC>(c);   // row_bcast:31 into rows 2 and 3
   return cand_from_lane(c, 63);
+}
+
+// x of lane (lane ^ R): within a quad of lanes one DPP move, else through the LDS crossbar.
+template <int R>
+__device__ __forceinline__ uint32_t from_xor_lane(int lane, uint32_t x) {
+  static_assert(R >= 1 && R < kWave, "another lane of the wave");
+  constexpr int kQuadPerm = R == 1 ? 0xB1 : R == 2 ? 0x4E : 0x1B;   // [1,0,3,2] [2,3,0,1] [3,2,1,0]
+  if (R <= 3) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, kQuadPerm, 0xF, 0xF, true);
+  return (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ R) << 2, (int)x);
+}
+template <int R>
+__device__ __forceinline__ u64 from_xor_lane64(int lane, u64 x) {
+  return ((u64)from_xor_lane<R>(lane, (uint32_t)(x >> 32)) << 32) | from_xor_lane<R>(lane, (uint32_t)x);
+}
+
+// f(integral_constant<int, FIRST>) ... f(integral_constant<int, LAST - 1>)
+template <int FIRST, int LAST, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (FIRST < LAST) {
+    f(std::integral_constant<int, FIRST>{});
+    static_for<FIRST + 1, LAST>(f);
+  }
 }
 
 // x in the lanes of the mask, 0 in the others.  (The two idle cycles behind it: a DPP

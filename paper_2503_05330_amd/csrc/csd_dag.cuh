@@ -209,25 +209,21 @@ __device__ __forceinline__ void walk_instances(LDS& s, const Ctx& c, int32_t M, 
   };
   // rank: the weight the greedy step ranks this lane's edge by
   u64 rank = key;
-#pragma unroll
-  for (int r = 1; r < G; ++r) {
-    const int addr = (lane ^ r) << 2;
-    uint32_t pv = from(addr, v), pu = from(addr, u);
-    u64 pk = from64(addr, key);
+  static_for<1, G>([&](auto r) {
+    uint32_t pv = from_xor_lane<r()>(lane, v), pu = from_xor_lane<r()>(lane, u);
+    u64 pk = from_xor_lane64<r()>(lane, key);
     bool add = pv == v && (score_mode == 0 || pu == u);
     rank += add ? pk : 0ull;
-  }
+  });
   // winner: no lane of the group with the same predecessor has a larger rank, or the same
   // rank and a lower token id (lanes with the same u and v are all winners, or none is)
   bool winner = u != kDeadU;
-#pragma unroll
-  for (int r = 1; r < G; ++r) {
-    const int addr = (lane ^ r) << 2;
-    uint32_t pv = from(addr, v), pu = from(addr, u);
-    u64 pr = from64(addr, rank);
+  static_for<1, G>([&](auto r) {
+    uint32_t pv = from_xor_lane<r()>(lane, v), pu = from_xor_lane<r()>(lane, u);
+    u64 pr = from_xor_lane64<r()>(lane, rank);
     bool beats = pu == u && (pr > rank || (pr == rank && pv < v));
     winner = winner && !beats;
-  }
+  });
   // succ: the lane the walk moves to from this one: the first winner of the next layer's group
   // whose predecessor is this lane's token
   const uint32_t wu = winner ? u : kDeadU;
