@@ -446,6 +446,19 @@ int csd_accept_loop(csd_index* h, int32_t n_steps, const int32_t* d_future_token
   hipStream_t st = as_stream(stream);
   for (int32_t s = 0; s < n_steps; ++s) {
     const int32_t* settled = s > 0 ? d_accept_len + (size_t)(s - 1) * rows : nullptr;
+    if (h->indexed) {                   // two launches: step input + append, then the draft
+      rc = note_append(h, true, (int32_t)n);
+      if (rc != CSD_OK) return rc;
+      advance_append_kernel<<<(uint32_t)rows, 256, 0, st>>>(
+          view_in_place(h), (int32_t)n, draft_len, settled, d_future_tokens, d_future_probs, step_tok,
+          d_future_probs ? step_prob : nullptr, step_cnt, targets, d_path_len + (size_t)s * rows);
+      DraftArgs a{query_len, draft_len, h->alpha_q, h->cfg.score_mode, h->cfg.pool_mode,
+                  d_draft_tokens + (size_t)s * rows * L, d_draft_len + (size_t)s * rows,
+                  nullptr, nullptr, targets, d_accept_len + (size_t)s * rows};
+      launch_draft(h, view_in_place(h), StepIn{nullptr, nullptr, nullptr, 0}, a, st);
+      CSD_HIP(hipGetLastError());
+      continue;
+    }
     advance_kernel<<<(uint32_t)((rows + 255) / 256), 256, 0, st>>>(
         (int64_t)rows, h->cfg.max_len, (int32_t)n, draft_len, h->meta[h->cur], h->view.meta_stride,
         settled, d_future_tokens, d_future_probs, step_tok, d_future_probs ? step_prob : nullptr,

@@ -362,6 +362,43 @@ __global__ __launch_bounds__(256) void advance_kernel(int64_t rows, int32_t max_
   }
 }
 
+// advance_kernel and append_kernel in one launch (index mode): one workgroup per row works out
+// the row's step input, writes it where the draft launch behind it finds the targets, and
+// appends it.  The meta row is read before, and updated after, the workgroup's barrier.
+__global__ __launch_bounds__(256) void advance_append_kernel(
+    IndexView ix, int32_t n, int32_t L, const int32_t* settled, const int32_t* future_tok,
+    const float* future_prob, int32_t* step_tok, float* step_prob, int32_t* step_cnt,
+    int32_t* targets, int32_t* path_len) {
+  const int64_t r = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int32_t max_len = ix.max_len;
+  const int32_t len = ix.meta_old[r * ix.meta_stride];
+  int32_t grow = (settled ? settled[r] : 0) + 1;
+  grow = grow < 1 ? 1 : (grow > n ? n : grow);
+  const int32_t room = max_len - len;
+  grow = grow < room ? grow : room;
+  if (tid == 0) {
+    step_cnt[r] = grow;
+    path_len[r] = len + grow;
+  }
+  const int32_t* ft = future_tok + r * max_len;
+  for (int32_t t = tid; t < n; t += 256) {
+    bool in = len + t < max_len;
+    step_tok[r * n + t] = in ? ft[len + t] : 0;
+    if (step_prob) step_prob[r * n + t] = in ? future_prob[r * max_len + len + t] : 0.0f;
+  }
+  for (int32_t d = tid; d < L; d += 256) {
+    int32_t t = len + grow + d;
+    targets[r * L + d] = t < max_len ? ft[t] : -1;
+  }
+  __syncthreads();                      // the step input is read back by this workgroup below
+  int32_t p;
+  Ctx c = make_ctx(ix, StepIn{step_tok, step_prob, step_cnt, n}, (int32_t)r, p);
+  int32_t old_i = c.y.old_len(c.i);
+  int32_t new_i = c.y.new_len(c.i, old_i);
+  append_row<256, true>(ix, c.y, p, c.i, old_i, new_i, c.tid);
+}
+
 // Plain copy of n 16-byte words: the known-size kernel that hardware traffic
 // counters are calibrated against.
 __global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ src,
