@@ -262,7 +262,9 @@ __device__ __forceinline__ void walk_instances(LDS& s, const Ctx& c, int32_t M, 
 // of tier 1 would hold it.  Matches without a window (found among the newest
 // positions) write theirs first.
 // `windows`: M windows of 2 L words (s.win, or any other LDS the caller has free).
-template <class LDS>
+// TREE: the prefix-tree pool instead of the DAG: a layer's successors are the lanes whose
+// whole continuation so far is the draft so far, and only they count for a successor's weight.
+template <bool TREE = false, class LDS>
 __device__ __forceinline__ void walk_matches(LDS& s, const Ctx& c, int32_t M, int32_t L, WinInfo wi,
                                              int32_t* windows, uint32_t alpha_q, int score_mode,
                                              DraftOut& o) {
@@ -284,14 +286,15 @@ __device__ __forceinline__ void walk_matches(LDS& s, const Ctx& c, int32_t M, in
   }
   uint32_t u = (uint32_t)c.Q[0], v = (uint32_t)win[0], p = (uint32_t)win[L];
   int32_t cur = c.Q[0];
+  bool on_draft = lane < M;
   const uint32_t per_count = 65536u - alpha_q;        // Eq. 5 in fixed point, as weight_key()
   for (int32_t d = 1; d <= L; ++d) {
     const int32_t ahead = d < L ? d : L - 1;          // layer d + 1 travels while d is decided
     const uint32_t v_next = (uint32_t)win[ahead], p_next = (uint32_t)win[L + ahead];
     const u64 alive = wave_ballot(d <= rem);
-    const u64 cand = wave_ballot(u == (uint32_t)cur) & alive;
+    const u64 cand = (TREE ? wave_ballot(on_draft) : wave_ballot(u == (uint32_t)cur)) & alive;
     if (!cand) break;                                 // leaf: no edge leaves cur
-    const u64 counted = score_mode ? cand : alive;    // whose weight a successor's rank sums
+    const u64 counted = (TREE || score_mode) ? cand : alive;   // whose weight a successor's rank sums
     u64 todo = cand;
     auto successor = [&]() {                          // the token of todo's first lane, and its rank
       const int src = (int)__ffsll((long long)todo) - 1;
@@ -306,6 +309,7 @@ __device__ __forceinline__ void walk_matches(LDS& s, const Ctx& c, int32_t M, in
     while (todo) best = cand_best(best, successor()); // the matches disagree: one round per token
     note_choice(o, best, d, lane);
     cur = best.v;
+    if (TREE) on_draft = on_draft && v == (uint32_t)best.v;
     u = v;
     v = v_next;
     p = p_next;

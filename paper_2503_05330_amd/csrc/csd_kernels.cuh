@@ -70,6 +70,23 @@ __device__ __forceinline__ void cache_lens(LDS& s, const Paths& y, int tid) {
   }
 }
 
+// The continuations of the M <= 64 listed matches into windows of 2 L words (tokens, then
+// probabilities), one (match, layer) instance per thread; ends with a workgroup barrier.
+template <int BLOCK, class LDS>
+__device__ __forceinline__ void fetch_windows(LDS& s, const Ctx& c, int32_t M, int32_t L,
+                                              int32_t* windows) {
+  for (int32_t idx = c.tid; idx < M * L; idx += BLOCK) {
+    const int32_t mi = idx / L, d = idx - mi * L + 1;
+    uint32_t u, v;
+    u64 w;
+    if (layer_instance(c.y, s.match[mi], d, 0u, u, v, w)) {
+      windows[mi * 2 * L + d - 1] = (int32_t)v;
+      windows[mi * 2 * L + L + d - 1] = (int32_t)cs_sum(w);
+    }
+  }
+  block_sync<BLOCK>();
+}
+
 // Scan mode.  One 1024-thread workgroup per (problem, path): [append] -> match
 // by scan (Eq. 3, or Eq. 4 with one edit) -> DAG (Eq. 5) -> greedy walk ->
 // [accept].  With in.n > 0 the launch also performs the step's append; every
@@ -166,10 +183,16 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
           match_scan<BLOCK, FUZZY>(s, c, fs);
         }
       };
-      if (a.pool_mode == CSD_POOL_TREE)
+      if (a.pool_mode == CSD_POOL_TREE && M <= kWave) {
+        int32_t* windows = reinterpret_cast<int32_t*>(s.table);
+        fetch_windows<BLOCK>(s, c, M, L, windows);
+        if (c.tid < kWave)
+          walk_matches<true>(s, c, M, L, WinInfo{0, M}, windows, a.alpha_q, a.score_mode, o);
+      } else if (a.pool_mode == CSD_POOL_TREE) {
         walk_tree<BLOCK>(s, c, WinInfo{M, 0}, M, L, a.alpha_q, ix.status, o, each);
-      else
+      } else {
         walk_list<BLOCK>(s, c, WinInfo{M, 0}, L, a.alpha_q, o, each);
+      }
     } else if (M > 0) {
       // tier 1 when every layer's region is sure to hold its <= 2M keys; else layer by
       // layer with one thread per match (M <= BLOCK); else streaming
@@ -178,16 +201,7 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
         // one lane of wave 0 per match, no tables: all threads fetch the continuations into
         // windows (laid over the unused table), one (match, layer) instance each
         int32_t* windows = reinterpret_cast<int32_t*>(s.table);
-        for (int32_t idx = c.tid; idx < M * L; idx += BLOCK) {
-          const int32_t mi = idx / L, d = idx - mi * L + 1;
-          uint32_t u, v;
-          u64 w;
-          if (layer_instance(c.y, s.match[mi], d, 0u, u, v, w)) {
-            windows[mi * 2 * L + d - 1] = (int32_t)v;
-            windows[mi * 2 * L + L + d - 1] = (int32_t)cs_sum(w);
-          }
-        }
-        block_sync<BLOCK>();
+        fetch_windows<BLOCK>(s, c, M, L, windows);
         if (c.tid < kWave) walk_matches(s, c, M, L, WinInfo{0, M}, windows, a.alpha_q, a.score_mode, o);
         done = true;
       } else if (2u * (uint32_t)M <= tier1_geometry(M, L, LdsScan::kTable).region) {
@@ -275,8 +289,12 @@ __global__ __launch_bounds__(step_wave_threads(FUZZY)) void step_wave_kernel(Ind
         match_plain<FUZZY>(s, c, fs);
       }
     };
-    if (a.pool_mode == CSD_POOL_TREE) walk_tree<kWave>(s, c, wi, M, L, a.alpha_q, ix.status, o, each);
-    else walk_list<kWave>(s, c, wi, L, a.alpha_q, o, each);
+    if (a.pool_mode == CSD_POOL_TREE && M <= kWave && M <= LDS::kWin / (2 * L))
+      walk_matches<true>(s, c, M, L, wi, s.win, a.alpha_q, a.score_mode, o);   // one lane per match
+    else if (a.pool_mode == CSD_POOL_TREE)
+      walk_tree<kWave>(s, c, wi, M, L, a.alpha_q, ix.status, o, each);
+    else
+      walk_list<kWave>(s, c, wi, L, a.alpha_q, o, each);
   } else if (M > 0 && M <= 8 && (L << lanes_log2(M)) <= kWave) {                   // few matches: no tables
     switch (lanes_log2(M)) {
       case 0: walk_instances<1>(s, c, M, L, wi, a.alpha_q, a.score_mode, o); break;
