@@ -594,3 +594,44 @@ def test_random_configurations_against_the_oracle(oracle):
         for t in range(steps):
             want = oracle.draft_all(tokens, probs, got["lens"][t], k, L, alpha, mode, eps=eps, pool_mode=pool_mode)
             assert_step_equal(got, want, t, what)
+
+
+def test_match_counts_across_the_walk_forms(oracle):
+    """Rows whose match counts sweep from 0 to hundreds within one replay, so that every form
+    of the DAG walk (lanes = instances, lanes = matches, LDS tables) and the hand-overs between
+    them (8 | 9 and 64 | 65 matches at L = 8, fewer for longer drafts) are crossed many times,
+    under both scoring modes, the tree pool, and both matchers."""
+    rng = np.random.default_rng(8964)
+    P, N, T, V, k = 2, 8, 120, 3, 2
+    motif = rng.integers(0, V, size=12)
+    tokens = np.zeros((P, N, T), dtype=np.int32)
+    for p in range(P):
+        for j in range(N):
+            seq = np.tile(np.roll(motif, int(rng.integers(0, 12))), T // 12 + 1)[:T]
+            noise = rng.random(T) < (0.02 + 0.03 * j)
+            tokens[p, j] = np.where(noise, rng.integers(0, V, size=T), seq)
+    probs = (rng.integers(1, 17, size=tokens.shape) / 16.0).astype(np.float32)
+    seen = set()
+    for L, mode, pool_mode, flags in [(8, 0, 0, INDEX), (8, 1, 0, INDEX), (8, 0, 1, INDEX), (8, 0, 0, SCAN),
+                                      (8, 1, 1, SCAN), (1, 0, 0, INDEX), (4, 1, 0, INDEX), (16, 0, 0, INDEX),
+                                      (32, 1, 0, INDEX), (32, 0, 1, INDEX), (16, 0, 0, SCAN)]:
+        what = "L%d mode%d pool%d flags%d" % (L, mode, pool_mode, flags)
+        print(what, flush=True)
+        got = gpu_replay(tokens, probs, k, L, 0.75, mode, flags, pool_mode=pool_mode)
+        for t in range(T):
+            lens_t = np.full((P, N), t + 1, dtype=np.int32)
+            want = oracle.draft_all(tokens, probs, lens_t, k, L, 0.75, mode, pool_mode=pool_mode)
+            assert_step_equal(got, want, t, what)
+    # the sweep is what the test is for: count the matches of every row and step on the CPU
+    for t in range(k, T):
+        for j in range(N):
+            q = tokens[0, j, t - k + 1:t + 1]
+            m = 0
+            for o in range(N):
+                if o == j:
+                    continue
+                h = tokens[0, o, :t + 1]
+                for e in range(k, t + 1):
+                    m += int(np.array_equal(h[e - k:e], q))
+            seen.add(min(m, 65) if m > 9 else m)
+    assert {0, 1, 2, 4, 8, 9, 65} <= seen, sorted(seen)
