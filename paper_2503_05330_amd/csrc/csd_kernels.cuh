@@ -139,8 +139,8 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
     load_query(c, a.k, old_i);
   }
   if (c.tid == 0) s.n_match = 0;
-  block_sync<BLOCK>();
-
+  lds_barrier<BLOCK>();                 // lengths and the empty list are in LDS; the append's stores,
+                                        // which nothing in this launch reads, need not have landed
   DraftOut o;
   const int32_t L = a.L;
   if (c.q > 0) {
