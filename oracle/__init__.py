@@ -42,28 +42,29 @@ def _load():
         lib.oracle_edit_distance.argtypes = [_i32p, ctypes.c_int32, _i32p, ctypes.c_int32]
         lib.oracle_matches.restype = ctypes.c_int64
         lib.oracle_matches.argtypes = [_i32p, _i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
-                                       ctypes.c_int32, ctypes.c_int32, _i32p, ctypes.c_int64]
+                                       ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _i32p, ctypes.c_int64]
         lib.oracle_edges.restype = ctypes.c_int64
         lib.oracle_edges.argtypes = [_i32p, _f32p, _i32p, ctypes.c_int32, ctypes.c_int32,
                                      ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
-                                     _i32p, _u64p, ctypes.c_int64]
+                                     ctypes.c_int32, _i32p, _u64p, ctypes.c_int64]
         lib.oracle_draft.restype = ctypes.c_int32
         lib.oracle_draft.argtypes = [_i32p, _f32p, _i32p, ctypes.c_int32, ctypes.c_int32,
                                      ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
-                                     ctypes.c_uint32, ctypes.c_int32, ctypes.c_int32, _i32p, _f32p, _f32p]
+                                     ctypes.c_uint32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                     _i32p, _f32p, _f32p]
         lib.oracle_accept.restype = ctypes.c_int32
         lib.oracle_accept.argtypes = [_i32p, ctypes.c_int32, _i32p]
         lib.oracle_draft_all.restype = None
         lib.oracle_draft_all.argtypes = [_i32p, _f32p, _i32p, ctypes.c_int32, ctypes.c_int32,
                                          ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                          ctypes.c_int32, ctypes.c_uint32, ctypes.c_int32, ctypes.c_int32,
-                                         _i32p, _i32p, _f32p, _f32p,
+                                         ctypes.c_int32, _i32p, _i32p, _f32p, _f32p,
                                          _i32p, _i32p]
         lib.oracle_accept_loop.restype = None
         lib.oracle_accept_loop.argtypes = [_i32p, _f32p, _i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                            ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_uint32,
-                                           ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _i32p, _i32p,
-                                           _i32p, _i32p]
+                                           ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                           _i32p, _i32p, _i32p, _i32p]
         _lib = lib
     return _lib
 
@@ -94,7 +95,11 @@ def edit_distance(a, b) -> int:
     return int(_load().oracle_edit_distance(ap, len(a) - 1, bp, len(b) - 1))
 
 
-def matches(tok, length, i, k, eps=0):
+def _extras(include_self, backoff) -> int:
+    return (1 if include_self else 0) | (2 if backoff else 0)
+
+
+def matches(tok, length, i, k, eps=0, include_self=False):
     """(j, e) rows of path i's match set for one problem: tok [N][max_len], length [N]."""
     tok, tp = _i32(tok)
     length, lp = _i32(length)
@@ -102,26 +107,29 @@ def matches(tok, length, i, k, eps=0):
     lib = _load()
     cap = max(1, N * max_len)
     out = np.empty((cap, 2), dtype=np.int32)
-    n = lib.oracle_matches(tp, lp, N, max_len, i, k, eps, out.ctypes.data_as(_i32p), cap)
+    n = lib.oracle_matches(tp, lp, N, max_len, i, k, eps, _extras(include_self, False),
+                           out.ctypes.data_as(_i32p), cap)
     return out[:n].copy()
 
 
-def edges(tok, prob, length, i, k, L, eps=0):
+def edges(tok, prob, length, i, k, L, eps=0, include_self=False):
     """Edge rows of path i's DAG: (duv int32 [n][3], cs uint64 [n][2]) sorted by (d, u, v)."""
     tok, tp = _i32(tok)
     prob, pp = _f32(prob)
     length, lp = _i32(length)
     N, max_len = tok.shape
     lib = _load()
-    n = lib.oracle_edges(tp, pp, lp, N, max_len, i, k, eps, L, None, None, 0)
+    ex = _extras(include_self, False)
+    n = lib.oracle_edges(tp, pp, lp, N, max_len, i, k, eps, ex, L, None, None, 0)
     duv = np.empty((max(n, 1), 3), dtype=np.int32)
     cs = np.empty((max(n, 1), 2), dtype=np.uint64)
-    lib.oracle_edges(tp, pp, lp, N, max_len, i, k, eps, L, duv.ctypes.data_as(_i32p),
+    lib.oracle_edges(tp, pp, lp, N, max_len, i, k, eps, ex, L, duv.ctypes.data_as(_i32p),
                      cs.ctypes.data_as(_u64p), n)
     return duv[:n].copy(), cs[:n].copy()
 
 
-def draft(tok, prob, length, i, k, L, alpha=1.0, score_mode=0, eps=0, pool_mode=0):
+def draft(tok, prob, length, i, k, L, alpha=1.0, score_mode=0, eps=0, pool_mode=0, include_self=False,
+          backoff=False):
     """Draft of path i for one problem -> (tokens [L], draft_len, token_scores [L], path_score).
     pool_mode: 0 = DAG (the method), 1 = prefix tree, 2 = list (the ablation's variants)."""
     tok, tp = _i32(tok)
@@ -133,8 +141,8 @@ def draft(tok, prob, length, i, k, L, alpha=1.0, score_mode=0, eps=0, pool_mode=
     ps = ctypes.c_float(0.0)
     lib = _load()
     n = lib.oracle_draft(tp, pp, lp, N, max_len, i, k, eps, L, lib.oracle_alpha_q(float(alpha)),
-                         score_mode, pool_mode, d.ctypes.data_as(_i32p), ts.ctypes.data_as(_f32p),
-                         ctypes.byref(ps))
+                         score_mode, pool_mode, _extras(include_self, backoff), d.ctypes.data_as(_i32p),
+                         ts.ctypes.data_as(_f32p), ctypes.byref(ps))
     return d, int(n), ts, np.float32(ps.value)
 
 
@@ -144,7 +152,8 @@ def accept(draft_tokens, draft_len, target) -> int:
     return int(_load().oracle_accept(dp, int(draft_len), tp))
 
 
-def draft_all(tok, prob, length, k, L, alpha=1.0, score_mode=0, target=None, eps=0, pool_mode=0):
+def draft_all(tok, prob, length, k, L, alpha=1.0, score_mode=0, target=None, eps=0, pool_mode=0,
+              include_self=False, backoff=False):
     """All paths of all problems: tok [P][N][max_len], prob same or None, length [P][N].
 
     Returns dict(draft [P][N][L], draft_len [P][N], token_scores [P][N][L],
@@ -165,12 +174,13 @@ def draft_all(tok, prob, length, k, L, alpha=1.0, score_mode=0, target=None, eps
     else:
         tgp, al, alp = None, None, None
     lib.oracle_draft_all(tp, pp, lp, P, N, max_len, k, eps, L, lib.oracle_alpha_q(float(alpha)),
-                         score_mode, pool_mode, d.ctypes.data_as(_i32p), dl.ctypes.data_as(_i32p),
-                         ts.ctypes.data_as(_f32p), ps.ctypes.data_as(_f32p), tgp, alp)
+                         score_mode, pool_mode, _extras(include_self, backoff), d.ctypes.data_as(_i32p),
+                         dl.ctypes.data_as(_i32p), ts.ctypes.data_as(_f32p), ps.ctypes.data_as(_f32p), tgp, alp)
     return dict(draft=d, draft_len=dl, token_scores=ts, path_scores=ps, accept_len=al)
 
 
-def accept_loop(future_tok, future_prob, length, k, L, n_steps, alpha=1.0, score_mode=0, eps=0, pool_mode=0):
+def accept_loop(future_tok, future_prob, length, k, L, n_steps, alpha=1.0, score_mode=0, eps=0, pool_mode=0,
+                include_self=False, backoff=False):
     """The propose / verify / accept loop with every path's own future standing in for the
     model.  future_tok [P][N][max_len], length [P][N] = lengths on entry.  Returns dict(draft
     [S][P][N][L], draft_len, accept_len, path_len [S][P][N], final_len [P][N])."""
@@ -185,7 +195,8 @@ def accept_loop(future_tok, future_prob, length, k, L, n_steps, alpha=1.0, score
     pl = np.empty((n_steps, P, N), dtype=np.int32)
     lib = _load()
     lib.oracle_accept_loop(tp, pp, length.ctypes.data_as(_i32p), P, N, max_len, k, eps, L,
-                           lib.oracle_alpha_q(float(alpha)), score_mode, pool_mode, n_steps,
+                           lib.oracle_alpha_q(float(alpha)), score_mode, pool_mode,
+                           _extras(include_self, backoff), n_steps,
                            d.ctypes.data_as(_i32p), dl.ctypes.data_as(_i32p), al.ctypes.data_as(_i32p),
                            pl.ctypes.data_as(_i32p))
     return dict(draft=d, draft_len=dl, accept_len=al, path_len=pl, final_len=length)

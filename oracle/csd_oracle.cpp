@@ -31,7 +31,7 @@
  *  R2  Any position of path j's current history qualifies, also beyond
  *      path i's own length (Eq. 3's t' <= t only says "already generated").
  *  R3  q = min(k, len_i); q = 0 gives an empty draft.  Path i itself is
- *      never searched (j != i, Eq. 3).
+ *      never searched (j != i, Eq. 3) — unless R17 is switched on.
  *  R4  Candidates are a multiset: every (j, e) is one instance of Eq. 5's
  *      sum, even when two continuations hold the same tokens.
  *  R5  p_theta(v_i | u_i) is the probability the model assigned to token v
@@ -76,6 +76,14 @@
  *      instance each, alpha*p + (1-alpha)*1 — add up to the most; ties go to
  *      the first candidate in (path, position) order.  token_score is each
  *      token's own weight.  score_mode does not apply.
+ *  R17 Self-history (not in the paper; retrieval / prompt-lookup style
+ *      drafting; `extras` bit 0): path i's own history is searched like any
+ *      other path's.  The occurrence of the query at the very end of path i
+ *      has no successor and is therefore no match (R1).
+ *  R18 Query back-off (not in the paper; `extras` bit 1): if the q-token query
+ *      has no match, the query is shortened by its OLDEST token, down to one
+ *      token, until its match set is non-empty; the draft is built from the
+ *      first non-empty set.  No length with a match: empty draft.
  *
  * Build: g++ -O2 -shared -fPIC -o libcsd_oracle.so csd_oracle.cpp
  */
@@ -138,7 +146,7 @@ int32_t edit_distance(const int32_t* a, int32_t na, const int32_t* b, int32_t nb
 /* Algorithm 1, the search loop (Eq. 3, with Eq. 4's tolerance): the candidate
  * pool of path i. */
 std::vector<Candidate> candidate_pool(const Paths& Y, int32_t i, int32_t k, int32_t eps,
-                                      int32_t* q_out) {
+                                      bool include_self, int32_t* q_out) {
   std::vector<Candidate> pool;
   int32_t len_i = Y.len[i];
   int32_t q = k < len_i ? k : len_i;                       /* R3 */
@@ -146,7 +154,7 @@ std::vector<Candidate> candidate_pool(const Paths& Y, int32_t i, int32_t k, int3
   if (q <= 0) return pool;
   const int32_t* query = Y.tok + (int64_t)i * Y.max_len + (len_i - q);
   for (int32_t j = 0; j < Y.N; ++j) {
-    if (j == i) continue;                                  /* R3 */
+    if (j == i && !include_self) continue;                 /* R3; R17 */
     const int32_t* yj = Y.tok + (int64_t)j * Y.max_len;
     for (int32_t e = 0; e <= Y.len[j] - 1; ++e) {          /* R1, R2 */
       bool match = false;
@@ -163,6 +171,19 @@ std::vector<Candidate> candidate_pool(const Paths& Y, int32_t i, int32_t k, int3
     }
   }
   return pool;                                             /* ascending (j, e) */
+}
+
+/* The pool a draft is built from: that of the k-token query, or with back-off
+ * (R18) that of the longest shorter query that has one. */
+std::vector<Candidate> pool_for_draft(const Paths& Y, int32_t i, int32_t k, int32_t eps,
+                                      int32_t extras) {
+  const bool include_self = (extras & 1) != 0, back_off = (extras & 2) != 0;
+  int32_t q;
+  std::vector<Candidate> pool = candidate_pool(Y, i, k, eps, include_self, &q);
+  if (back_off)
+    for (int32_t shorter = q - 1; pool.empty() && shorter >= 1; --shorter)
+      pool = candidate_pool(Y, i, shorter, eps, include_self, &q);
+  return pool;
 }
 
 typedef std::map<std::pair<int32_t, int32_t>, Weight> EdgeTable;   /* (u, v) -> weight */
@@ -211,10 +232,11 @@ uint32_t oracle_alpha_q(double alpha) {
 /* Match set of path i (Eq. 3) as (j, e) rows in ascending order.  Returns the
  * number of matches; writes at most cap rows. */
 int64_t oracle_matches(const int32_t* tok, const int32_t* len, int32_t N, int32_t max_len,
-                       int32_t i, int32_t k, int32_t eps, int32_t* out_je, int64_t cap) {
+                       int32_t i, int32_t k, int32_t eps, int32_t extras, int32_t* out_je,
+                       int64_t cap) {
   Paths Y{tok, nullptr, len, N, max_len};
   int32_t q;
-  std::vector<Candidate> pool = candidate_pool(Y, i, k, eps, &q);
+  std::vector<Candidate> pool = candidate_pool(Y, i, k, eps, (extras & 1) != 0, &q);
   for (int64_t m = 0; m < (int64_t)pool.size() && m < cap; ++m) {
     out_je[2 * m] = pool[m].j;
     out_je[2 * m + 1] = pool[m].e;
@@ -225,11 +247,11 @@ int64_t oracle_matches(const int32_t* tok, const int32_t* len, int32_t N, int32_
 /* Edge tables of path i's DAG (Eq. 5) as rows (d, u, v) / (C, S) sorted by
  * (d, u, v).  Returns the number of rows; writes at most cap rows. */
 int64_t oracle_edges(const int32_t* tok, const float* prob, const int32_t* len, int32_t N,
-                     int32_t max_len, int32_t i, int32_t k, int32_t eps, int32_t L,
+                     int32_t max_len, int32_t i, int32_t k, int32_t eps, int32_t extras, int32_t L,
                      int32_t* out_duv, uint64_t* out_cs, int64_t cap) {
   Paths Y{tok, prob, len, N, max_len};
   int32_t q;
-  std::vector<Candidate> pool = candidate_pool(Y, i, k, eps, &q);
+  std::vector<Candidate> pool = candidate_pool(Y, i, k, eps, (extras & 1) != 0, &q);
   std::vector<EdgeTable> edges = build_dag(Y, pool, L, Y.token(i, Y.len[i] - 1));
   int64_t n = 0;
   for (int32_t d = 1; d <= L; ++d) {
@@ -350,13 +372,12 @@ Draft draft_from_list(const Paths& Y, const std::vector<Candidate>& pool, int32_
  * padded with -1, token_scores[L] with 0.  Returns the draft length. */
 int32_t oracle_draft(const int32_t* tok, const float* prob, const int32_t* len, int32_t N,
                      int32_t max_len, int32_t i, int32_t k, int32_t eps, int32_t L, uint32_t alpha_q,
-                     int32_t score_mode, int32_t pool_mode, int32_t* draft, float* token_scores,
-                     float* path_score) {
+                     int32_t score_mode, int32_t pool_mode, int32_t extras, int32_t* draft,
+                     float* token_scores, float* path_score) {
   for (int32_t d = 0; d < L; ++d) { draft[d] = -1; token_scores[d] = 0.0f; }
   *path_score = 0.0f;
   Paths Y{tok, prob, len, N, max_len};
-  int32_t q;
-  std::vector<Candidate> pool = candidate_pool(Y, i, k, eps, &q);
+  std::vector<Candidate> pool = pool_for_draft(Y, i, k, eps, extras);
   if (pool.empty()) return 0;
   int32_t root = Y.token(i, Y.len[i] - 1);       /* R9: root = last query token */
   Draft chosen = pool_mode == 1 ? draft_from_tree(Y, pool, L, alpha_q)
@@ -385,8 +406,8 @@ int32_t oracle_accept(const int32_t* draft, int32_t draft_len, const int32_t* ta
  * problem.  Arrays are [P][N][...]; target / accept_len may be null. */
 void oracle_draft_all(const int32_t* tok, const float* prob, const int32_t* len, int32_t P,
                       int32_t N, int32_t max_len, int32_t k, int32_t eps, int32_t L,
-                      uint32_t alpha_q, int32_t score_mode, int32_t pool_mode, int32_t* draft,
-                      int32_t* draft_len, float* token_scores, float* path_scores,
+                      uint32_t alpha_q, int32_t score_mode, int32_t pool_mode, int32_t extras,
+                      int32_t* draft, int32_t* draft_len, float* token_scores, float* path_scores,
                       const int32_t* target, int32_t* accept_len) {
   for (int32_t p = 0; p < P; ++p) {
     const int32_t* tk = tok + (int64_t)p * N * max_len;
@@ -395,7 +416,8 @@ void oracle_draft_all(const int32_t* tok, const float* prob, const int32_t* len,
     for (int32_t i = 0; i < N; ++i) {
       int64_t r = (int64_t)p * N + i;
       draft_len[r] = oracle_draft(tk, pr, ln, N, max_len, i, k, eps, L, alpha_q, score_mode,
-                                  pool_mode, draft + r * L, token_scores + r * L, path_scores + r);
+                                  pool_mode, extras, draft + r * L, token_scores + r * L,
+                                  path_scores + r);
       if (target && accept_len)
         accept_len[r] = oracle_accept(draft + r * L, draft_len[r], target + r * L);
     }
@@ -413,8 +435,8 @@ void oracle_draft_all(const int32_t* tok, const float* prob, const int32_t* len,
  * lengths on entry and on exit; outputs are [n_steps][P][N][...]. */
 void oracle_accept_loop(const int32_t* future_tok, const float* future_prob, int32_t* len, int32_t P,
                         int32_t N, int32_t max_len, int32_t k, int32_t eps, int32_t L,
-                        uint32_t alpha_q, int32_t score_mode, int32_t pool_mode, int32_t n_steps,
-                        int32_t* draft, int32_t* draft_len, int32_t* accept_len,
+                        uint32_t alpha_q, int32_t score_mode, int32_t pool_mode, int32_t extras,
+                        int32_t n_steps, int32_t* draft, int32_t* draft_len, int32_t* accept_len,
                         int32_t* path_len) {
   int64_t rows = (int64_t)P * N;
   std::vector<int32_t> settled(rows, 0);          /* accept length of the previous step */
@@ -435,7 +457,7 @@ void oracle_accept_loop(const int32_t* future_tok, const float* future_prob, int
         int64_t o = s * rows + r;
         float unused_scores[64], unused_total;
         draft_len[o] = oracle_draft(tk, pr, ln, N, max_len, i, k, eps, L, alpha_q, score_mode,
-                                    pool_mode, draft + o * L, unused_scores, &unused_total);
+                                    pool_mode, extras, draft + o * L, unused_scores, &unused_total);
         for (int32_t d = 0; d < L; ++d)
           target[d] = ln[i] + d < max_len ? tk[(int64_t)i * max_len + ln[i] + d] : -1;
         accept_len[o] = oracle_accept(draft + o * L, draft_len[o], target.data());

@@ -41,24 +41,36 @@ def lev(a, b):
     return min(lev(a[1:], b[1:]) + (a[0] != b[0]), lev(a[1:], b) + 1, lev(a, b[1:]) + 1)
 
 
-def match_set(paths, i, k, eps=0):
+def match_set(paths, i, k, eps=0, include_self=False):
+    """include_self: path i's own history is searched too (a match still needs a successor, so
+    the query's own occurrence at the end of path i never counts)."""
     yi = paths[i]
     q = min(k, len(yi))
     if q == 0:
         return q, set()
     suffix = tuple(yi[len(yi) - q:])
+    searched = [(j, yj) for j, yj in enumerate(paths) if j != i or include_self]
     if eps == 0:
-        return q, {(j, e) for j, yj in enumerate(paths) if j != i
+        return q, {(j, e) for j, yj in searched
                    for e in range(q, len(yj)) if tuple(yj[e - q:e]) == suffix}
     near = within_one_edit if eps == 1 else (lambda a, b: lev(tuple(a), tuple(b)) <= eps)
-    return q, {(j, e) for j, yj in enumerate(paths) if j != i for e in range(len(yj))
+    return q, {(j, e) for j, yj in searched for e in range(len(yj))
                if any(near(suffix, yj[e - l:e]) for l in range(0, e + 1))}
 
 
-def candidates(paths, probs, i, k, L, eps=0):
+def backed_off_k(paths, i, k, eps=0, include_self=False):
+    """Query back-off: the largest query length <= k whose match set is not empty (k itself if
+    there is none: the draft is empty either way)."""
+    for shorter in range(min(k, len(paths[i])), 0, -1):
+        if match_set(paths, i, shorter, eps, include_self)[1]:
+            return shorter
+    return k
+
+
+def candidates(paths, probs, i, k, L, eps=0, include_self=False):
     """Each candidate = [(predecessor, token, prob_fraction), ...] of length <= L.  The
     predecessor of a candidate's first token is the query's last token (the DAG's root)."""
-    _, M = match_set(paths, i, k, eps)
+    _, M = match_set(paths, i, k, eps, include_self)
     out = []
     for (j, e) in M:
         seq = []
@@ -69,20 +81,22 @@ def candidates(paths, probs, i, k, L, eps=0):
     return out
 
 
-def edge_tables(paths, probs, i, k, L, eps=0):
+def edge_tables(paths, probs, i, k, L, eps=0, include_self=False):
     """{(d, u, v): [count, prob_sum_fraction]} with d = 1..L."""
     E = defaultdict(lambda: [0, Fraction(0)])
-    for seq in candidates(paths, probs, i, k, L, eps):
+    for seq in candidates(paths, probs, i, k, L, eps, include_self):
         for d, (u, v, p) in enumerate(seq, start=1):
             E[(d, u, v)][0] += 1
             E[(d, u, v)][1] += p
     return dict(E)
 
 
-def draft(paths, probs, i, k, L, alpha=Fraction(1), score_mode=0, eps=0):
+def draft(paths, probs, i, k, L, alpha=Fraction(1), score_mode=0, eps=0, include_self=False, backoff=False):
     """Returns (tokens, scores) with scores as exact Fractions."""
     alpha = Fraction(alpha)
-    E = edge_tables(paths, probs, i, k, L, eps)
+    if backoff:
+        k = backed_off_k(paths, i, k, eps, include_self)
+    E = edge_tables(paths, probs, i, k, L, eps, include_self)
     if not E:
         return [], []
 
@@ -116,13 +130,15 @@ def accept(draft_tokens, target):
     return a
 
 
-def tree_draft(paths, probs, i, k, L, alpha=Fraction(1), eps=0):
+def tree_draft(paths, probs, i, k, L, alpha=Fraction(1), eps=0, include_self=False, backoff=False):
     """The ablation's tree pool: an explicit prefix tree (nested dicts) of the candidates'
     continuations; each node carries [count, prob_sum] of the candidates through it; the draft
     is the greedy descent to the heaviest child (ties: lowest token id)."""
     alpha = Fraction(alpha)
+    if backoff:
+        k = backed_off_k(paths, i, k, eps, include_self)
     root = {}                                   # token -> [count, prob_sum, children]
-    for seq in candidates(paths, probs, i, k, L, eps):
+    for seq in candidates(paths, probs, i, k, L, eps, include_self):
         node = root
         for (_, v, p) in seq:
             entry = node.setdefault(v, [0, Fraction(0), {}])
@@ -141,11 +157,13 @@ def tree_draft(paths, probs, i, k, L, alpha=Fraction(1), eps=0):
     return toks, scores
 
 
-def list_draft(paths, probs, i, k, L, alpha=Fraction(1), eps=0):
+def list_draft(paths, probs, i, k, L, alpha=Fraction(1), eps=0, include_self=False, backoff=False):
     """The ablation's list pool: the continuation of the single candidate whose tokens'
     weights (alpha * p + (1 - alpha) each) add up to the most; ties: first in (j, e) order."""
     alpha = Fraction(alpha)
-    _, M = match_set(paths, i, k, eps)
+    if backoff:
+        k = backed_off_k(paths, i, k, eps, include_self)
+    _, M = match_set(paths, i, k, eps, include_self)
     best_key, best = None, ([], [])
     for (j, e) in sorted(M):
         toks = list(paths[j][e:e + L])

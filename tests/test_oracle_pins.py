@@ -509,3 +509,86 @@ def test_accept_length_grows_with_the_number_of_paths(oracle):
                                w.draft_len, 400)
         mean[N] = r["accept_len"].mean()
     assert mean[2] < mean[4] < mean[8] < mean[16] and mean[16] > 3 * mean[2]
+
+
+# ---------------------------------------------------------------- self-history and query back-off
+def test_self_history_and_back_off_hand_cases(oracle):
+    # one periodic path: without its own history there is nothing to search; with it the two
+    # earlier occurrences of (2, 3) both continue 1 2 3, so every layer counts 2 (then 1)
+    tok, _, ln = pack([[1, 2, 3, 1, 2, 3, 1, 2, 3]])
+    assert oracle.draft(tok, None, ln, 0, 2, 4)[1] == 0
+    assert oracle.matches(tok, ln, 0, 2, include_self=True).tolist() == [[0, 3], [0, 6]]
+    d, n, ts, _ = oracle.draft(tok, None, ln, 0, 2, 4, include_self=True)
+    assert d[:n].tolist() == [1, 2, 3, 1] and ts[:n].tolist() == [2.0, 2.0, 2.0, 1.0]
+    # the query's own occurrence at the end of the path has no successor: never a match
+    tok, _, ln = pack([[4, 5, 6]])
+    assert oracle.matches(tok, ln, 0, 2, include_self=True).tolist() == []
+    # back-off: (2, 3, 9) occurs nowhere else, (3, 9) does, and is followed by 7 8
+    tok, _, ln = pack([[1, 2, 3, 9], [5, 3, 9, 7, 8], [9, 6, 6]])
+    assert oracle.draft(tok, None, ln, 0, 3, 3)[1] == 0
+    d, n, _, _ = oracle.draft(tok, None, ln, 0, 3, 3, backoff=True)
+    assert d[:n].tolist() == [7, 8]
+    assert d.tolist() == oracle.draft(tok, None, ln, 0, 2, 3)[0].tolist()
+    # ... and stops at the first non-empty set: the one-token query (9) would also see path 2
+    assert oracle.draft(tok, None, ln, 0, 1, 3)[0][:1].tolist() == [6]
+    # nothing at any length: empty
+    tok, _, ln = pack([[1, 2, 3], [4, 5, 6]])
+    assert oracle.draft(tok, None, ln, 0, 3, 3, backoff=True)[1] == 0
+
+
+def test_self_history_and_back_off_brute_force_tiny_inputs(oracle):
+    rng = np.random.default_rng(1718)
+    n_self_differs = n_backed_off = 0
+    for case in range(700):
+        paths, probs = _random_case(rng)
+        use_probs = case % 2 == 0
+        k = int(rng.integers(1, 5))
+        L = int(rng.integers(1, 6))
+        eps = 1 if case % 5 == 0 else 0
+        alpha = Fraction(int(rng.integers(0, 5)), 4)
+        mode = int(rng.integers(0, 2))
+        inc, back = bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
+        tok, pr, ln = pack(paths, probs if use_probs else None, max_len=26)
+        pp = probs if use_probs else None
+        for i in range(len(paths)):
+            _, M = bf.match_set(paths, i, k, eps, inc)
+            assert oracle.matches(tok, ln, i, k, eps, include_self=inc).tolist() == [list(m) for m in sorted(M)]
+            E = bf.edge_tables(paths, pp, i, k, L, eps, inc)
+            duv, _ = oracle.edges(tok, pr, ln, i, k, L, eps, include_self=inc)
+            assert [tuple(r) for r in duv.tolist()] == sorted(E)
+            for pool_mode, brute in ((0, None), (1, bf.tree_draft), (2, bf.list_draft)):
+                if brute is None:
+                    toks, scores = bf.draft(paths, pp, i, k, L, alpha, mode, eps, inc, back)
+                else:
+                    toks, scores = brute(paths, pp, i, k, L, alpha, eps, inc, back)
+                d, n, ts, ps = oracle.draft(tok, pr, ln, i, k, L, float(alpha), mode, eps, pool_mode,
+                                            include_self=inc, backoff=back)
+                assert d[:n].tolist() == toks and (d[n:] == -1).all()
+                assert ts[:n].tolist() == [float(np.float32(float(s))) for s in scores]
+                assert float(ps) == float(np.float32(float(sum(scores, Fraction(0)))))
+            plain = oracle.draft(tok, pr, ln, i, k, L, float(alpha), mode, eps, 0)
+            both = oracle.draft(tok, pr, ln, i, k, L, float(alpha), mode, eps, 0, include_self=inc, backoff=back)
+            # neither option can empty a draft, and back-off changes nothing where k has matches
+            assert both[1] > 0 or plain[1] == 0
+            if plain[1] > 0 and not inc:
+                assert both[0].tolist() == plain[0].tolist()
+            n_self_differs += inc and not back and both[0].tolist() != plain[0].tolist()
+            n_backed_off += back and bf.backed_off_k(paths, i, k, eps, inc) < min(k, len(paths[i]))
+    assert n_self_differs > 20 and n_backed_off > 20
+
+
+def test_options_reach_the_batched_entry_points(oracle):
+    w = synth.scaled(synth.WORKLOADS["C1"], max_len=48)
+    tokens, probs = synth.make_paths(w)
+    lens = np.full(tokens.shape[:2], 40, dtype=np.int32)
+    for inc, back in ((True, False), (False, True), (True, True)):
+        allp = oracle.draft_all(tokens, probs, lens, 3, 5, 1.0, 0, include_self=inc, backoff=back)
+        for i in range(w.n_paths):
+            d, n, ts, ps = oracle.draft(tokens[0], probs[0], lens[0], i, 3, 5, 1.0, 0, include_self=inc, backoff=back)
+            assert allp["draft"][0, i].tolist() == d.tolist() and allp["draft_len"][0, i] == n
+    # the accept loop with both options: every step is the draft of the lengths it reports
+    start = np.full(tokens.shape[:2], 8, dtype=np.int32)
+    run = oracle.accept_loop(tokens, probs, start, 3, 5, 6, include_self=True, backoff=True)
+    for s in range(6):
+        step = oracle.draft_all(tokens, probs, run["path_len"][s], 3, 5, 1.0, 0, include_self=True, backoff=True)
+        assert step["draft"].tolist() == run["draft"][s].tolist()
