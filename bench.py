@@ -92,6 +92,10 @@ def main():
     ap.add_argument("--pool", choices=("dag", "tree", "list"), default="dag",
                     help="organisation of the candidate pool (dag = the method, the headline; tree and "
                          "list are the variants of the paper's ablation)")
+    ap.add_argument("--include-self", action="store_true",
+                    help="also search a path's own history (not in the paper; not the headline)")
+    ap.add_argument("--backoff", action="store_true",
+                    help="shorten a query without matches until it has some (not in the paper; not the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--batch-sweep", action="store_true",
                     help="also time the step with 1..4096 copies of the workload's first problem in one "
@@ -120,7 +124,9 @@ def main():
     d_pr = torch.from_numpy(np.ascontiguousarray(probs.transpose(2, 0, 1))).to(dev)
     tg = np.stack([synth.make_targets(tokens, min(t + 1, T), L) for t in range(T)])
     d_tg = torch.from_numpy(tg).to(dev)
-    ix = binding.Index(P, N, T, w.vocab, k, L, 1.0, 0, {"auto": 0, "scan": 1, "index": 2}[args.matcher],
+    flags = {"auto": 0, "scan": 1, "index": 2}[args.matcher]
+    flags |= (binding.INCLUDE_SELF if args.include_self else 0) | (binding.QUERY_BACKOFF if args.backoff else 0)
+    ix = binding.Index(P, N, T, w.vocab, k, L, 1.0, 0, flags,
                        device=dev, max_edits=args.max_edits,
                        pool_mode={"dag": 0, "tree": 1, "list": 2}[args.pool])
     out = dict(tokens=torch.empty((P, N, L), dtype=torch.int32, device=dev),
@@ -221,18 +227,20 @@ def main():
 
     # which kernel the configuration runs (the library's choice, mirrored here for the report)
     rows = P * N
-    by_scan = args.matcher == "scan" or (args.max_edits > 0 and args.matcher == "auto"
-                                          and not (k >= 4 and rows > 128))
+    by_scan = args.matcher == "scan" or (args.matcher == "auto" and args.backoff) or (
+        args.max_edits > 0 and args.matcher == "auto" and not (k >= 4 and rows > 128))
     kernel = "step_scan_kernel" if by_scan else "step_wave_kernel"
     variant = w.name + ("_one_edit" if args.max_edits else "") + ("" if args.pool == "dag" else "_" + args.pool)
+    variant += ("_self" if args.include_self else "") + ("_backoff" if args.backoff else "")
     res = {
         "metric": METRIC, "value": K / dt, "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": dt / K * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "u64", "data": "synthetic",
         "config": {"workload": "%s: P=%d problems x N=%d paths x %d tokens, vocab %d, query %d, draft %d, "
-                               "probs supplied, alpha 1, max_edits %d, pool %s; step = append 1 token/path + "
+                               "probs supplied, alpha 1, max_edits %d, pool %s%s%s; step = append 1 token/path + "
                                "draft all paths + accept" % (w.name, P, N, T, w.vocab, k, L, args.max_edits,
-                                                             args.pool)},
+                                                             args.pool, ", own history" if args.include_self else "",
+                                                             ", query back-off" if args.backoff else "")},
         "us_per_step_mean_over_replay": dt / K * 1e6,
         "us_per_step_at_full_history": dt_tail / tail * 1e6,
         "us_per_step_three_launches": dt_unfused * 1e6,
@@ -250,8 +258,8 @@ def main():
     }
 
     if args.batch_sweep:
-        res["batch_sweep"] = batch_sweep(binding, torch, dev, w, tokens, probs, matches_per_step / P,
-                                         {"auto": 0, "scan": 1, "index": 2}[args.matcher], args.max_edits)
+        res["batch_sweep"] = batch_sweep(binding, torch, dev, w, tokens, probs, matches_per_step / P, flags,
+                                         args.max_edits)
 
     if not args.no_cpu_baseline:
         import oracle
@@ -262,7 +270,8 @@ def main():
             for t in range(T):
                 lens = np.full((P, N), t + 1, dtype=np.int32)
                 oracle.draft_all(tokens, probs, lens, k, L, 1.0, 0, tg[t], eps=args.max_edits,
-                                 pool_mode={"dag": 0, "tree": 1, "list": 2}[args.pool])
+                                 pool_mode={"dag": 0, "tree": 1, "list": 2}[args.pool],
+                                 include_self=args.include_self, backoff=args.backoff)
             t_cpu += time.perf_counter() - c0
             n_done += T
             reps += 1

@@ -76,6 +76,16 @@ typedef enum {
                               holds grams of max_query_len tokens: set max_query_len to the
                               query_len the decode loop uses; shorter queries are scanned */
 
+/* csd_config.flags, options that may be OR-ed to a CSD_MATCH_* value.  Neither is in the
+ * paper; they are what retrieval-style drafting from a single sequence does. */
+#define CSD_INCLUDE_SELF 4   /* path i's own history is searched like any other path's
+                                (the query's own occurrence at the end of path i has no
+                                successor and never counts)                             */
+#define CSD_QUERY_BACKOFF 8  /* a query without matches is shortened by its oldest token,
+                                down to one token, until it has some; the draft is built
+                                from the first non-empty match set.  Shortened queries are
+                                always scanned: CSD_MATCH_AUTO picks the scan with this.  */
+
 /* Sticky device-side status bits, read with csd_status. */
 #define CSD_STATUS_CAPACITY 1u     /* an append was clipped at max_len               */
 #define CSD_STATUS_TOKEN_RANGE 2u  /* a token id outside [0, vocab) was appended     */
@@ -91,7 +101,8 @@ typedef struct {
   float alpha;            /* Eq. 5's alpha in [0,1]; the paper's experiments use 1    */
   int32_t score_mode;     /* 0: greedy step ranks successors by node in-weight
                              sum_u w(u,v) (the rule after Eq. 5); 1: by w(cur,v)      */
-  int32_t flags;          /* CSD_MATCH_*; all other bits must be 0                    */
+  int32_t flags;          /* one CSD_MATCH_* value, optionally | CSD_INCLUDE_SELF and/or
+                             | CSD_QUERY_BACKOFF; all other bits must be 0            */
   int32_t max_edits;      /* Eq. 4's edit-distance tolerance of the suffix match: 0 = exact
                              (Eq. 3), 1 = one substitution, insertion or deletion (the
                              paper's experiments use 1).  With 1 a position e of another

@@ -15,6 +15,7 @@ import torch
 from .build import LIBRARY, build_library
 
 MATCH_AUTO, MATCH_SCAN, MATCH_INDEX = 0, 1, 2
+INCLUDE_SELF, QUERY_BACKOFF = 4, 8      # options OR-ed to a MATCH_* value
 POOL_DAG, POOL_TREE, POOL_LIST = 0, 1, 2
 STATUS_CAPACITY, STATUS_TOKEN_RANGE, STATUS_TABLE_FULL = 1, 2, 4
 OK, ERR_INVALID_ARG, ERR_CAPACITY, ERR_WORKSPACE, ERR_HIP, ERR_UNIMPLEMENTED = 0, -1, -2, -3, -4, -5

@@ -72,10 +72,14 @@ constexpr int64_t kSlicedScanRows = 128;
 // the chains of frequent pairs get long, and the scan is the faster matcher; with few rows
 // the sliced scan is as fast as the index for longer queries too.  CSD_MATCH_AUTO therefore
 // takes the index from four query tokens on when there are too many rows to slice the scan.
+// With query back-off a query without matches is searched again in shorter forms, which the
+// index (grams of max_query_len tokens only) cannot serve: CSD_MATCH_AUTO takes the scan then.
+int matcher_of(const csd_config* c) { return c->flags & 3; }
 bool uses_index(const csd_config* c) {
-  if (c->flags == CSD_MATCH_SCAN) return false;
+  if (matcher_of(c) == CSD_MATCH_SCAN) return false;
+  if (matcher_of(c) == CSD_MATCH_AUTO && (c->flags & CSD_QUERY_BACKOFF)) return false;
   if (c->max_edits == 0) return true;
-  if (c->flags == CSD_MATCH_INDEX) return c->max_query_len >= 2;
+  if (matcher_of(c) == CSD_MATCH_INDEX) return c->max_query_len >= 2;
   return c->max_query_len >= 4 && (int64_t)c->n_problems * c->n_paths > kSlicedScanRows;
 }
 int32_t tail_len_of(const csd_config* c) {
@@ -92,11 +96,12 @@ int validate(const csd_config* c) {
   if (c->score_mode != 0 && c->score_mode != 1) return CSD_ERR_INVALID_ARG;
   if ((int64_t)c->n_paths * c->max_len > CSD_MAX_POSITIONS) return CSD_ERR_INVALID_ARG;
   if ((int64_t)c->n_problems * c->n_paths > (1 << 24)) return CSD_ERR_INVALID_ARG;
-  if (c->flags < 0 || c->flags > CSD_MATCH_INDEX) return CSD_ERR_UNIMPLEMENTED;
+  if (c->flags < 0 || c->flags > (3 | CSD_INCLUDE_SELF | CSD_QUERY_BACKOFF) || matcher_of(c) > CSD_MATCH_INDEX)
+    return CSD_ERR_UNIMPLEMENTED;
   if (c->max_edits < 0) return CSD_ERR_INVALID_ARG;
   if (c->pool_mode < CSD_POOL_DAG || c->pool_mode > CSD_POOL_LIST) return CSD_ERR_INVALID_ARG;
   if (c->max_edits > 1) return CSD_ERR_UNIMPLEMENTED;
-  if (c->max_edits == 1 && c->flags == CSD_MATCH_INDEX && c->max_query_len < 2) return CSD_ERR_UNIMPLEMENTED;
+  if (c->max_edits == 1 && matcher_of(c) == CSD_MATCH_INDEX && c->max_query_len < 2) return CSD_ERR_UNIMPLEMENTED;
   return CSD_OK;
 }
 
@@ -134,7 +139,7 @@ Layout make_layout(const csd_config* c) {
   l.slices = at;
   // (the hand-over between the slices costs about 5 us: worth it for one-edit matching and
   // for long histories)
-  if (!uses_index(c) && rows <= (size_t)kSlicedScanRows &&
+  if (!uses_index(c) && rows <= (size_t)kSlicedScanRows && !(c->flags & CSD_QUERY_BACKOFF) &&
       (c->max_edits > 0 || (int64_t)c->n_paths * c->max_len >= 32768)) {
     while (l.n_slices < 8 && rows * (size_t)l.n_slices * 2 <= 256) l.n_slices *= 2;
     if (l.n_slices > 1)
@@ -195,7 +200,7 @@ void launch_draft(const csd_index* h, const IndexView& v, const StepIn& in, cons
     if (a.L <= 8) step_wave_kernel<8, true, LdsWaveFuzzy, true, CSD_MAX_QUERY_LEN><<<grid, kWave, 0, st>>>(v, in, a);
     else if (a.L <= 16) step_wave_kernel<16, true, LdsWaveFuzzy, true, CSD_MAX_QUERY_LEN><<<grid, kWave, 0, st>>>(v, in, a);
     else step_wave_kernel<32, true, LdsWaveFuzzy, true, CSD_MAX_QUERY_LEN><<<grid, kWave, 0, st>>>(v, in, a);
-  } else if (a.pool_mode != CSD_POOL_DAG) {             // tree and list pools: the general kernels
+  } else if (a.pool_mode != CSD_POOL_DAG || v.options != 0) {   // tree and list pools, own history, back-off: the general kernels
     if (!h->indexed && v.eps > 0) step_scan_kernel<1, true, true><<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
     else if (!h->indexed) step_scan_kernel<1, true, false><<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
     else if (a.L <= 8) step_wave_kernel<8, true, LdsWave, false, CSD_MAX_QUERY_LEN><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
@@ -294,6 +299,7 @@ int csd_create(const csd_config* cfg, void* d_workspace, size_t workspace_bytes,
   h->view.vocab = cfg->vocab;
   h->view.kmax = cfg->max_query_len;
   h->view.eps = cfg->max_edits;
+  h->view.options = (cfg->flags >> 2) & 3;
   h->alpha_q = to_alpha_q(cfg->alpha);
   rc = csd_reset(h, stream);
   if (rc != CSD_OK) {

@@ -216,6 +216,8 @@ struct IndexView {              // device state inside the caller's workspace
   int32_t eshift;               // positions are packed as (path << eshift) | index
   int32_t P, N, max_len, vocab, kmax;
   int32_t eps;                  // edit tolerance (0 = exact match)
+  int32_t options;              // bit 0: a path's own history is searched too; bit 1: a query
+                                //   without matches is shortened by its oldest token until it has some
 };
 
 struct Match;
@@ -338,6 +340,7 @@ struct Ctx {                    // one (problem, query path)
   uint32_t bucket_mask;
   int32_t kmax;
   int32_t i;                    // query path
+  int32_t skip;                 // the path that is not searched: i, or -1 (own history included)
   int32_t len_i;                // its length after the append
   int32_t eps;                  // edit tolerance of the match (Eq. 4): 0 or 1
   int32_t q;                    // effective query length min(k, len_i)
@@ -423,6 +426,7 @@ __device__ __forceinline__ Ctx make_ctx(const IndexView& ix, const StepIn& in, i
   p_out = p;
   int64_t cells = (int64_t)p * ix.N * ix.max_len;
   c.i = row - p * ix.N;
+  c.skip = (ix.options & 1) ? -1 : c.i;
   c.y.tok = ix.tok + cells;
   c.y.pq = ix.pq + cells;
   c.y.meta_old = ix.meta_old + (int64_t)p * ix.N * ix.meta_stride;

@@ -148,6 +148,17 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
     match_scan<BLOCK, FUZZY>(s, c, sink, slice, sl.n);
     block_sync<BLOCK>();
     int32_t M = s.n_match;
+    if (POOLS && (ix.options & 2)) {
+      // query back-off (never with slices): no match, so the query loses its oldest token and
+      // the scan runs again; every thread sees the same M and q, so the barriers pair up
+      while (M == 0 && c.q > 1) {
+        block_sync<BLOCK>();            // everybody has read the count before anybody pushes again
+        --c.q;
+        match_scan<BLOCK, FUZZY>(s, c, sink);
+        block_sync<BLOCK>();
+        M = s.n_match;
+      }
+    }
     if (sl.n > 1) {
       // hand this slice's matches to the row's list in memory
       Match* listed = sl.matches + (int64_t)row * LdsScan::kMatch;
@@ -275,8 +286,20 @@ __global__ __launch_bounds__(step_wave_threads(FUZZY)) void step_wave_kernel(Ind
   VariantTicket tickets;
   bool ticket_used;
   int32_t M = FUZZY ? wave_front_end_fuzzy<LCAP>(s, c, ix, p, a.k, L, wi, tickets, ticket_used)
-                    : wave_front_end<LCAP, QC, !SPLIT>(s, c, ix, p, a.k, L, wi, ticket, ticket_used);
+                    : wave_front_end<LCAP, QC, !SPLIT, POOLS>(s, c, ix, p, a.k, L, wi, ticket, ticket_used);
   block_sync<kWave>();
+  if (POOLS && (ix.options & 2)) {
+    // query back-off: no match, so the query loses its oldest token and the histories are
+    // searched again (position by position: the index holds grams of max_query_len tokens only)
+    while (M == 0 && c.q > 1) {
+      --c.q;
+      WaveListSink<LDS> sink{&s, &M, c.tid};
+      match_plain<FUZZY>(s, c, sink);
+      wi = WinInfo{M, 0};
+      if (c.tid == 0) s.n_match = M;
+      block_sync<kWave>();
+    }
+  }
 
   DraftOut o;
   if (POOLS && M > 0 && a.pool_mode != CSD_POOL_DAG) {
@@ -461,7 +484,7 @@ __global__ __launch_bounds__(kWave) void dump_match_bits_wave_kernel(IndexView i
   VariantTicket tickets;
   bool ticket_used;
   int32_t M = FUZZY ? wave_front_end_fuzzy<8>(s, c, ix, p, k, 1, wi, tickets, ticket_used)
-                    : wave_front_end<8, CSD_MAX_QUERY_LEN>(s, c, ix, p, k, 1, wi, ticket, ticket_used);
+                    : wave_front_end<8, CSD_MAX_QUERY_LEN, true, true>(s, c, ix, p, k, 1, wi, ticket, ticket_used);
   block_sync<kWave>();
   BitmapSink sink{bits + (int64_t)row * words};
   if (M <= LdsWave::kMatch) {
@@ -583,7 +606,7 @@ __global__ __launch_bounds__(kWave) void dump_edge_rows_wave_kernel(IndexView ix
   VariantTicket tickets;
   bool ticket_used;
   int32_t M = FUZZY ? wave_front_end_fuzzy<LCAP>(s, c, ix, p, k, L, wi, tickets, ticket_used)
-                    : wave_front_end<LCAP, CSD_MAX_QUERY_LEN>(s, c, ix, p, k, L, wi, ticket, ticket_used);
+                    : wave_front_end<LCAP, CSD_MAX_QUERY_LEN, true, true>(s, c, ix, p, k, L, wi, ticket, ticket_used);
   block_sync<kWave>();
   if (M == 0) { if (c.tid == 0) counts[row] = 0; return; }
   if (M > LdsWave::kMatch) { if (c.tid == 0) counts[row] = -1; return; }

@@ -232,7 +232,7 @@ __device__ __forceinline__ void match_scan(const LDS& s, const Ctx& c, Sink& sin
     for (int u = 0; u < kSpans; ++u) {
       int32_t g = g0 + u * n_waves, j, e0, old_j = 0, new_j = 0;
       locate(g, j, e0);
-      bool on = g < spans && j != c.i;                     // uniform over the wave
+      bool on = g < spans && j != c.skip;                  // uniform over the wave
       if (on) lens_of(s, c.y, j, old_j, new_j);
       // the lane that starts a path has no three tokens before its positions: it reads the
       // path's first six instead, which serve its fourth position and pre-filter the others
@@ -314,7 +314,7 @@ __device__ __forceinline__ void match_plain(const LDS& s, const Ctx& c, Sink& si
   const int lane = c.tid & 63;
   const int32_t first_e = FUZZY ? (c.q > 1 ? c.q - 1 : 0) : c.q;   // shortest substring that can match
   for (int32_t j = 0; j < c.y.N; ++j) {
-    if (j == c.i) continue;
+    if (j == c.skip) continue;
     int32_t old_j, new_j;
     lens_of(s, c.y, j, old_j, new_j);
     for (int32_t e0 = first_e; e0 < new_j; e0 += kWave) {  // trip counts are uniform over the wave
@@ -418,7 +418,8 @@ __device__ __forceinline__ void append_own_single(const IndexView& ix, const Pat
 // round trip as the verification.  `word` is the lane's word of the first batch
 // of 4 buckets, already requested.  Adds its hits behind the matches already
 // listed; match number x of the list gets window x (if x < win_cap).
-template <int LCAP, int QC, class LDS>
+// GENERAL: also compiled for the options (own history searched): kept out of the usual kernels.
+template <int LCAP, int QC, bool GENERAL = false, class LDS>
 __device__ __forceinline__ void lookup_with_windows(LDS& s, const Ctx& c, int32_t L,
                                                     int32_t win_cap, int32_t& n_match,
                                                     GramHash gh, int32_t word) {
@@ -441,7 +442,7 @@ __device__ __forceinline__ void lookup_with_windows(LDS& s, const Ctx& c, int32_
     }
     bool cand = sub >= 1 && word >= 0 && (sub - 1) < (full ? kBucketSlots : count);
     int32_t j = y.pos_path(word), e = y.pos_index(word), old_j = 0, new_j = 0;
-    cand = cand && j != c.i && j < y.N;
+    cand = cand && j != (GENERAL ? c.skip : c.i) && j < y.N;
     if (cand) {
       lens_of(s, y, j, old_j, new_j);
       cand = e < old_j;               // newer positions are matched directly, not looked up
@@ -516,7 +517,7 @@ __device__ __forceinline__ void lookup_with_windows(LDS& s, const Ctx& c, int32_
 // instructions one wave issues.
 // APPENDS: the wave also appends the row's token and files it in the index (false: another
 // wave of the workgroup does, see wave_append).
-template <int LCAP, int QC, bool APPENDS = true, class LDS>
+template <int LCAP, int QC, bool APPENDS = true, bool GENERAL = false, class LDS>
 __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexView& ix, int32_t p,
                                                   int32_t k, int32_t L, WinInfo& wi,
                                                   InsertTicket& ticket, bool& ticket_used) {
@@ -565,7 +566,8 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
       s.len_new[j] = hj.new_len;
     }
     // a position appended by this very launch matches when the old tail before it is the query
-    bool hit = use_index && have && j != c.i && hj.new_len > hj.old_len && hj.old_len >= c.q;
+    bool hit = use_index && have && j != (GENERAL ? c.skip : c.i) && hj.new_len > hj.old_len &&
+               hj.old_len >= c.q;
 #pragma unroll
     for (int a = 0; a < QC; ++a) hit = hit && (a >= c.q || hj.tail[a] == c.Q[a]);
     wave_push(s, n_match, hit, make_match(y, j, hj.old_len, hj.old_len, hj.new_len), lane);
@@ -574,7 +576,7 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
   wi.n_fresh = n_match;
   wi.win_cap = use_index ? LDS::kWin / (2 * L) : 0;
   if (use_index) {
-    lookup_with_windows<LCAP, QC>(s, c, L, wi.win_cap, n_match, gh, word);
+    lookup_with_windows<LCAP, QC, GENERAL>(s, c, L, wi.win_cap, n_match, gh, word);
   } else if (c.q > 0) {
     WaveListSink<LDS> sink{&s, &n_match, lane};
     match_plain<false>(s, c, sink);                     // covers old and new positions alike
@@ -681,7 +683,7 @@ __device__ __forceinline__ bool consume_variant_bucket(LDS& s, const Ctx& c, int
   const int32_t filed_as = word >> kVariantShift;       // variant of its gram the posting stands for
   const int32_t pos = word & ((1 << kVariantShift) - 1);
   int32_t j = y.pos_path(pos), e = y.pos_index(pos), old_j = 0, new_j = 0;
-  cand = cand && j != c.i && j < y.N && e >= c.q;       // postings are filed for e >= kmax only
+  cand = cand && j != c.skip && j < y.N && e >= c.q;    // postings are filed for e >= kmax only
   if (cand) {
     lens_of(s, y, j, old_j, new_j);
     cand = e < old_j;                 // newer positions are matched directly, not looked up
@@ -844,7 +846,7 @@ __device__ __forceinline__ int32_t wave_front_end_fuzzy(LDS& s, Ctx& c, const In
       s.len_old[j] = hj.old_len;
       s.len_new[j] = hj.new_len;
     }
-    const bool other = use_index && have && j != c.i;
+    const bool other = use_index && have && j != c.skip;
     int32_t t[K + 1];
     // the position appended by this very launch: the tokens before it are the old tail
 #pragma unroll

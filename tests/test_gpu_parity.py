@@ -571,6 +571,8 @@ def test_random_configurations_against_the_oracle(oracle):
         flags = int(rng.choice([0, SCAN, INDEX]))
         if eps and flags == INDEX and k < 2:
             flags = 0
+        include_self, backoff = bool(case % 3 == 1), bool(case % 4 == 2)   # the options, in a third / a quarter
+        flags |= (binding.INCLUDE_SELF if include_self else 0) | (binding.QUERY_BACKOFF if backoff else 0)
         n_per_step = int(rng.choice([1, 1, 2, 5]))
         how = str(rng.choice(["calls", "step"]))
         use_probs = bool(rng.integers(0, 2))
@@ -592,7 +594,8 @@ def test_random_configurations_against_the_oracle(oracle):
                          n_per_step=n_per_step, how=how, max_edits=eps, pool_mode=pool_mode)
         assert got["status"] in (0, binding.STATUS_CAPACITY), what
         for t in range(steps):
-            want = oracle.draft_all(tokens, probs, got["lens"][t], k, L, alpha, mode, eps=eps, pool_mode=pool_mode)
+            want = oracle.draft_all(tokens, probs, got["lens"][t], k, L, alpha, mode, eps=eps, pool_mode=pool_mode,
+                                    include_self=include_self, backoff=backoff)
             assert_step_equal(got, want, t, what)
 
 
@@ -635,3 +638,49 @@ def test_match_counts_across_the_walk_forms(oracle):
                     m += int(np.array_equal(h[e - k:e], q))
             seen.add(min(m, 65) if m > 9 else m)
     assert {0, 1, 2, 4, 8, 9, 65} <= seen, sorted(seen)
+
+
+@pytest.mark.parametrize("include_self,backoff", [(True, False), (False, True), (True, True)])
+def test_self_history_and_query_back_off(oracle, include_self, backoff):
+    """The two retrieval-style options (neither is in the paper): every step of C1 and sampled
+    steps of C2 under both matchers, all pools and both tolerances; one path on its own."""
+    opts = (binding.INCLUDE_SELF if include_self else 0) | (binding.QUERY_BACKOFF if backoff else 0)
+    w = synth.WORKLOADS["C1"]
+    tokens, probs = synth.make_paths(w)
+    T = w.max_len
+    for matcher, eps, pool_mode, mode in [(0, 0, 0, 0), (SCAN, 0, 0, 1), (INDEX, 0, 0, 0), (INDEX, 0, 1, 0),
+                                          (SCAN, 0, 2, 0), (SCAN, 1, 0, 0), (INDEX, 1, 0, 0), (0, 1, 1, 0)]:
+        what = "C1 opts%d matcher%d eps%d pool%d mode%d" % (opts, matcher, eps, pool_mode, mode)
+        print(what, flush=True)
+        got = gpu_replay(tokens, probs, w.query_len, w.draft_len, 1.0, mode, matcher | opts, max_edits=eps,
+                         pool_mode=pool_mode)
+        for t in range(T):
+            lens_t = np.full(tokens.shape[:2], t + 1, dtype=np.int32)
+            want = oracle.draft_all(tokens, probs, lens_t, w.query_len, w.draft_len, 1.0, mode, eps=eps,
+                                    pool_mode=pool_mode, include_self=include_self, backoff=backoff)
+            assert_step_equal(got, want, t, what)
+    w = synth.WORKLOADS["C2"]
+    tokens, probs = synth.make_paths(w)
+    for matcher in (0, INDEX):
+        what = "C2 opts%d matcher%d" % (opts, matcher)
+        print(what, flush=True)
+        got = gpu_replay(tokens, probs, w.query_len, w.draft_len, 1.0, 0, matcher | opts, steps=400)
+        for t in list(range(0, 40)) + list(range(43, 400, 17)):
+            lens_t = np.full(tokens.shape[:2], t + 1, dtype=np.int32)
+            want = oracle.draft_all(tokens, probs, lens_t, w.query_len, w.draft_len, 1.0, 0,
+                                    include_self=include_self, backoff=backoff)
+            assert_step_equal(got, want, t, what)
+    # one path alone: nothing to search without its own history
+    rng = np.random.default_rng(5)
+    motif = rng.integers(0, 50, size=7)
+    tokens = np.tile(motif, 12)[None, None, :80].astype(np.int32)
+    tokens[0, 0, rng.integers(0, 80, size=6)] = 99
+    for matcher in (SCAN, INDEX):
+        got = gpu_replay(tokens, None, 3, 6, 1.0, 0, matcher | opts)
+        n_drafts = 0
+        for t in range(80):
+            lens_t = np.full((1, 1), t + 1, dtype=np.int32)
+            want = oracle.draft_all(tokens, None, lens_t, 3, 6, 1.0, 0, include_self=include_self, backoff=backoff)
+            assert_step_equal(got, want, t, "single path opts%d matcher%d" % (opts, matcher))
+            n_drafts += int(want["draft_len"][0, 0] > 0)
+        assert (n_drafts > 40) == include_self
