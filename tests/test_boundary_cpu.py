@@ -40,15 +40,17 @@ def test_workspace_size_and_validation(lib):
     for bad in bad_cases:
         cfg = b.Config(**{**good, **bad})
         assert lib.csd_workspace_bytes(ctypes.byref(cfg), ctypes.byref(out)) == b.ERR_INVALID_ARG, bad
-    cfg = b.Config(**{**good, "flags": 8})
-    assert lib.csd_workspace_bytes(ctypes.byref(cfg), ctypes.byref(out)) == b.ERR_UNIMPLEMENTED
+    for unknown in (16, 3, 3 | b.INCLUDE_SELF, -1):        # an unknown option bit; no such matcher
+        cfg = b.Config(**{**good, "flags": unknown})
+        assert lib.csd_workspace_bytes(ctypes.byref(cfg), ctypes.byref(out)) == b.ERR_UNIMPLEMENTED, unknown
     for bad, code in ((dict(max_edits=-1), b.ERR_INVALID_ARG), (dict(max_edits=2), b.ERR_UNIMPLEMENTED),
                       (dict(max_edits=1, flags=b.MATCH_INDEX, max_query_len=1), b.ERR_UNIMPLEMENTED),
                       (dict(pool_mode=-1), b.ERR_INVALID_ARG), (dict(pool_mode=3), b.ERR_INVALID_ARG)):
         cfg = b.Config(**{**good, **bad})
         assert lib.csd_workspace_bytes(ctypes.byref(cfg), ctypes.byref(out)) == code, bad
     for fine in (dict(max_edits=1), dict(max_edits=1, flags=b.MATCH_INDEX), dict(pool_mode=b.POOL_TREE),
-                 dict(pool_mode=b.POOL_LIST, max_edits=1)):
+                 dict(pool_mode=b.POOL_LIST, max_edits=1), dict(flags=b.INCLUDE_SELF),
+                 dict(flags=b.MATCH_INDEX | b.QUERY_BACKOFF), dict(flags=b.MATCH_SCAN | b.INCLUDE_SELF | b.QUERY_BACKOFF)):
         cfg = b.Config(**{**good, **fine})
         assert lib.csd_workspace_bytes(ctypes.byref(cfg), ctypes.byref(out)) == b.OK, fine
     assert lib.csd_workspace_bytes(None, ctypes.byref(out)) == b.ERR_INVALID_ARG
