@@ -9,12 +9,15 @@
 // Nothing here is a dense contraction, so there is no MFMA: the work is
 // integer compares, hash lookups, LDS hash-histogram atomics and wavefront
 // reductions.  The step is latency-bound (a chain of a few dependent memory
-// round trips per path, then serial LDS work in one wave), so the design
+// round trips per path, then the serial work of one wave), so the design
 // minimises round trips, barriers and instruction count:
 //   * one launch per decode step (append + draft + accept fused),
-//   * one wave64 per (problem, path): no workgroup barriers on the hot path,
+//   * per (problem, path) one wave64 that drafts and one that appends: no
+//     workgroup barriers on the hot path,
 //   * matches come from an incrementally updated n-gram hash index,
-//   * DAG tables live in LDS, argmax reductions use ballots and DPP lane moves.
+//   * the DAG of a row with up to 64 matches lives in the lanes of the wave
+//     (sums by lane exchanges, ballots and DPP reductions); LDS tables take
+//     the rows with more.
 //
 // Exactness: every weight is an integer (probabilities are quantised to
 // 1/65536 at append), so atomics may accumulate in any order and the result is

@@ -1,8 +1,11 @@
-// csd — the layered token DAG (Eq. 5) as LDS hash histograms, and the greedy
-// layer-wise walk over it (rule after Eq. 5, Algorithm 1).
+// csd — the layered token DAG (Eq. 5) and the greedy layer-wise walk over it
+// (rule after Eq. 5, Algorithm 1).
 //
-// Two tiers with identical results (all sums are exact integers):
-//   tier 1  all L layers at once: layer d owns one region of the LDS table that
+// Forms with identical results (all sums are exact integers):
+//   tier 0  one wave, no tables: the DAG lives in the lanes.  walk_instances:
+//           a lane per (match, layer) instance, for up to 8 matches;
+//           walk_matches: a lane per match, for up to 64;
+//   tier 1  LDS hash histograms, all L layers at once: layer d owns one region of the LDS table that
 //           holds its edges (d,u,v) -> (count, probability sum) and its nodes
 //           (d,*,v) -> in-weight; every edge slot links to its target node, so
 //           the walk can fetch all ranks before its serial part starts;

@@ -1,6 +1,7 @@
-// csd — the kernels: reset, append, the decode step (one wave per path in index
-// mode, one 256-thread workgroup per path in scan mode), accept, and the
-// kernels behind the debug dumps.
+// csd — the kernels: reset, append, the decode step (a drafting and an
+// appending wave per path in index mode, one 1024-thread workgroup per path —
+// or several, sharing its scan — in scan mode), accept, the stand-in model of
+// the accept-driven loop, and the kernels behind the debug dumps.
 #pragma once
 
 #include "csd_common.cuh"
@@ -252,9 +253,11 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
   }
 }
 
-// Index mode.  One wave64 per (problem, path): the front end (append, matches
-// with their continuations in LDS), DAG build, scoring, walk, outputs, accept,
-// and last the posting stores of the split-phase index insert.
+// Index mode.  Per (problem, path) one wave64 runs the front end (matches with
+// their continuations in LDS), the DAG and its walk in one of three forms
+// (lanes = instances, lanes = matches, LDS tables), outputs and accept; the
+// append and the split-phase index insert are done by the same wave (one-edit
+// matching) or by a second one (exact matching, see below).
 // FUZZY: the index files every position under its gram's variants and matching tolerates
 // one edit (Eq. 4).
 // QC: compile-time bound (4 or 8) of the index's gram length.

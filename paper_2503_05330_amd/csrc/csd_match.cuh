@@ -328,17 +328,18 @@ __device__ __forceinline__ void match_plain(const LDS& s, const Ctx& c, Sink& si
 
 // ---------------------------------------------------------------- the one-wave front end
 //
-// Index mode runs one wave64 per (problem, path).  The step is a chain of
+// In index mode one wave64 drafts for a (problem, path).  The step is a chain of
 // dependent memory round trips, and every launch starts with a cold L2, so the
-// front end is laid out to need only three of them before the LDS work:
+// front end is laid out to need only three of them before the walk:
 //   1. the meta rows (length + last tokens) of all paths and the step's input:
 //      the query, the index hashes, the own append and the matches among the
 //      newest positions all follow from these without touching the histories;
 //   2. the index buckets of the query, and the fill counts for the insert;
 //   3. for every posting found, its verify tokens together with its whole
-//      continuation (tokens and probabilities), kept in LDS for the DAG build;
+//      continuation (tokens and probabilities), kept in LDS for the DAG;
 //      the insert's atomic travels with these.
-// It handles steps that append at most one token per path (in.n <= 1).
+// It handles steps that append at most one token per path (in.n <= 1).  With
+// exact matching the append and the insert are another wave's (wave_append).
 
 struct Head {                   // a path's end before this step
   int32_t old_len, new_len;
