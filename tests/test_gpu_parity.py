@@ -684,3 +684,19 @@ def test_self_history_and_query_back_off(oracle, include_self, backoff):
             assert_step_equal(got, want, t, "single path opts%d matcher%d" % (opts, matcher))
             n_drafts += int(want["draft_len"][0, 0] > 0)
         assert (n_drafts > 40) == include_self
+
+
+def test_scores_are_bit_equal_to_the_oracle(oracle):
+    """Both sides hold a score as the same exact integer and round it to float once, so the
+    floats agree in every bit (the other tests allow 1e-6 relative): C1 and the first 300
+    steps of C2, with probabilities and a fractional alpha, so that the sums have low bits."""
+    for name, steps, alpha in (("C1", None, 0.625), ("C2", 300, 0.3), ("C1", None, 1.0)):
+        w = synth.WORKLOADS[name]
+        tokens, probs = synth.make_paths(w)
+        steps = steps or w.max_len
+        got = gpu_replay(tokens, probs, w.query_len, w.draft_len, alpha, 0, 0, steps=steps)
+        for t in range(steps):
+            lens_t = np.full(tokens.shape[:2], t + 1, dtype=np.int32)
+            want = oracle.draft_all(tokens, probs, lens_t, w.query_len, w.draft_len, alpha, 0)
+            assert got["token_scores"][t].tobytes() == want["token_scores"].tobytes(), (name, t)
+            assert got["path_scores"][t].tobytes() == want["path_scores"].tobytes(), (name, t)
