@@ -270,6 +270,8 @@ template <int LCAP, bool POOLS, class LDS, bool FUZZY, int QC>
 __global__ __launch_bounds__(step_wave_threads(FUZZY)) void step_wave_kernel(IndexView ix, StepIn in,
                                                                              DraftArgs a) {
   constexpr bool SPLIT = step_wave_threads(FUZZY) > kWave;
+  static_assert(sizeof(IndexView) + sizeof(StepIn) + sizeof(DraftArgs) >= 196, "four lines of arguments");
+  fetch_kernel_arguments();
   __shared__ LDS s;
   int32_t row = xcd_row(ix.P * ix.N);
   if (row < 0) return;

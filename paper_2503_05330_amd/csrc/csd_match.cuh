@@ -526,15 +526,27 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
   const Paths& y = c.y;
   const int64_t row = (int64_t)p * ix.N + c.i;
   int32_t* gram = const_cast<int32_t*>(c.gram);
-  // ---- round trip 1: every load here has an address known from the kernel arguments
-  Head me = load_head<QC>(y, ix.tail_len, c.i);         // same address in every lane
-  Head hj = load_head<QC>(y, ix.tail_len, lane < y.N ? lane : 0);
-  int32_t st_i = 0;
-  float sp_i = 1.0f;
-  if (y.n == 1) {
-    st_i = y.st[c.i];
-    if (APPENDS && y.sp) sp_i = y.sp[c.i];
+  // ---- round trip 1: every load here has an address known from the kernel arguments.  They
+  // are per-lane loads issued together; the row's own head and step token are then read from
+  // lane i (a load of their own, with the same address in every lane, would be a scalar one
+  // whose round trip the compiler puts BEFORE these)
+  const int32_t jl = lane < y.N ? lane : 0;
+  int32_t st_j = y.n == 1 ? y.st[jl] : 0;               // (before the head: its lengths wait for it)
+  Head hj = load_head<QC>(y, ix.tail_len, jl);
+  Head me;
+  int32_t st_i;
+  if (c.i < kWave) {
+    me.old_len = __builtin_amdgcn_readlane(hj.old_len, c.i);
+    me.new_len = __builtin_amdgcn_readlane(hj.new_len, c.i);
+#pragma unroll
+    for (int a = 0; a < kTailCap; ++a) me.tail[a] = a < QC ? __builtin_amdgcn_readlane(hj.tail[a], c.i) : 0;
+    st_i = __builtin_amdgcn_readlane(st_j, c.i);
+  } else {
+    me = load_head<QC>(y, ix.tail_len, c.i);
+    st_i = y.n == 1 ? y.st[c.i] : 0;
   }
+  float sp_i = 1.0f;
+  if (APPENDS && y.n == 1 && y.sp) sp_i = y.sp[c.i];
   const int32_t old_i = me.old_len, cnt_i = me.new_len - me.old_len;
   c.len_i = me.new_len;
   c.q = k < c.len_i ? k : c.len_i;
