@@ -107,6 +107,7 @@ template <int LCAP, bool POOLS, bool FUZZY>
 __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, StepIn in,
                                                                DraftArgs a, ScanSlices sl) {
   constexpr int BLOCK = kScanBlock;
+  fetch_kernel_arguments();
   __shared__ LdsScan s;
   __shared__ int32_t sh_base, sh_total, sh_last;
   int32_t row, slice = 0;
