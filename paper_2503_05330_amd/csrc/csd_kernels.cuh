@@ -122,8 +122,8 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
   if (row < 0) return;
   int32_t p;
   Ctx c = make_ctx(ix, in, row, p);
+  int32_t st_i = in.n == 1 ? c.y.st[c.i] : 0;           // (first: the head's lengths wait for its load)
   Head me = load_head(c.y, ix.tail_len, c.i);           // length and newest tokens in one read
-  int32_t st_i = in.n == 1 ? c.y.st[c.i] : 0;
   const int32_t old_i = me.old_len;
   c.len_i = me.new_len;
   cache_lens<BLOCK>(s, c.y, c.tid);

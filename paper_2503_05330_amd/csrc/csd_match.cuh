@@ -352,10 +352,15 @@ __device__ __forceinline__ Head load_head(const Paths& y, int32_t tail_len, int3
   Head h;
   const int32_t* row = y.meta_old + (int64_t)j * y.meta_stride;
   const int4* m = reinterpret_cast<const int4*>(row);
+  // words the row does not have are not read: their loads go to word 0 instead, so that no
+  // load sits behind a branch and all of them travel together
   int4 a = m[0];
-  int4 b = (QC > 3 && tail_len > 3) ? m[1] : int4{0, 0, 0, 0};
-  int32_t c8 = (QC > 7 && tail_len > 7) ? row[8] : 0;
-  int32_t c9 = (QC > 8 && tail_len > 8) ? row[9] : 0;
+  int4 b = QC > 3 ? m[tail_len > 3 ? 1 : 0] : int4{0, 0, 0, 0};
+  int32_t c8 = QC > 7 ? row[tail_len > 7 ? 8 : 0] : 0;
+  int32_t c9 = QC > 8 ? row[tail_len > 8 ? 9 : 0] : 0;
+  if (tail_len <= 3) b = int4{0, 0, 0, 0};
+  if (tail_len <= 7) c8 = 0;
+  if (tail_len <= 8) c9 = 0;
   h.old_len = a.x;
   h.tail[0] = a.y; h.tail[1] = a.z; h.tail[2] = a.w;
   h.tail[3] = b.x; h.tail[4] = b.y; h.tail[5] = b.z; h.tail[6] = b.w;
