@@ -435,6 +435,9 @@ __device__ __forceinline__ void lookup_with_windows(LDS& s, const Ctx& c, int32_
   const int sub = lane & 15;          // word of the bucket this lane reads
   const int grp = lane >> 4;          // which of the 4 buckets of a batch
   const uint32_t n_buckets = c.bucket_mask + 1;
+  int32_t query_oldest_first[QC];     // [x] = Q[q - 1 - x]
+#pragma unroll
+  for (int x = 0; x < QC; ++x) query_oldest_first[x] = pick_n<QC>(c.Q, c.q - 1 - x);
   for (uint32_t r0 = 0; r0 < n_buckets; r0 += 4) {
     consume_here(word);
     if (r0 + grp >= n_buckets) word = -1;
@@ -465,9 +468,12 @@ __device__ __forceinline__ void lookup_with_windows(LDS& s, const Ctx& c, int32_
     if (cand) {
       const int32_t* hrow = y.tok + y.cell(j, e);        // history of path j at the posting
       const uint32_t* prow = y.pq + y.cell(j, e);
-      int32_t tv[QC];
+      // the gram before the posting as ONE run of QC tokens from e - q on (e >= q: inside the
+      // path; the run may reach into the continuation, which is padded): loaded token by token
+      // behind the comparisons, every token was a dependent fetch of its own
+      int32_t gram_at[QC];
 #pragma unroll
-      for (int a = 0; a < QC; ++a) tv[a] = hrow[a < c.q ? -1 - a : -1];   // e >= q: all exist
+      for (int x = 0; x < QC; ++x) gram_at[x] = hrow[x - c.q];
       rem = new_j - e;
       rem = rem < L ? rem : L;
       n_hist = old_j - e;             // >= 1: continuation tokens that are already history
@@ -479,8 +485,10 @@ __device__ __forceinline__ void lookup_with_windows(LDS& s, const Ctx& c, int32_
         wv[d] = hrow[d];
         wp[d] = prow[d];
       }
+      int32_t differ = 0;             // (OR of differences: no comparison behind a branch)
 #pragma unroll
-      for (int a = 0; a < QC; ++a) hit = hit && (a >= c.q || tv[a] == c.Q[a]);
+      for (int x = 0; x < QC; ++x) differ |= x < c.q ? (gram_at[x] ^ query_oldest_first[x]) : 0;
+      hit = differ == 0;
     }
     if (wave_ballot(hit && rem > n_hist) != 0) {            // rare: runs into this step's new tokens
 #pragma unroll
