@@ -132,15 +132,26 @@ __device__ __forceinline__ Cand wave_argmax(Cand c) {
 // Left to itself the compiler fetches the arguments where control flow first needs them, one
 // line after the other, and every line is a miss in the scalar cache of a fresh launch: three
 // memory round trips in a row before the first load of data can be issued.  After this call
-// the compiler's own argument loads hit.  The block must be at least 196 bytes long.
+// the compiler's own argument loads hit.  BYTES: size of the kernel's explicit arguments (only
+// lines that hold some of them are touched; at most the first four).
+template <size_t BYTES>
 __device__ __forceinline__ void fetch_kernel_arguments() {
+  static_assert(BYTES > 128, "meant for argument blocks of three lines or more");
   int32_t a, b, c, d;
-  asm volatile(
-      "s_load_dword %0, %4, 0x0\n\ts_load_dword %1, %4, 0x40\n\ts_load_dword %2, %4, 0x80\n\t"
-      "s_load_dword %3, %4, 0xc0\n\ts_waitcnt lgkmcnt(0)"
-      : "=&s"(a), "=&s"(b), "=&s"(c), "=&s"(d)
-      : "s"(__builtin_amdgcn_kernarg_segment_ptr())
-      : "memory");
+  if (BYTES > 192)
+    asm volatile(
+        "s_load_dword %0, %4, 0x0\n\ts_load_dword %1, %4, 0x40\n\ts_load_dword %2, %4, 0x80\n\t"
+        "s_load_dword %3, %4, 0xc0\n\ts_waitcnt lgkmcnt(0)"
+        : "=&s"(a), "=&s"(b), "=&s"(c), "=&s"(d)
+        : "s"(__builtin_amdgcn_kernarg_segment_ptr())
+        : "memory");
+  else
+    asm volatile(
+        "s_load_dword %0, %3, 0x0\n\ts_load_dword %1, %3, 0x40\n\ts_load_dword %2, %3, 0x80\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&s"(a), "=&s"(b), "=&s"(c)
+        : "s"(__builtin_amdgcn_kernarg_segment_ptr())
+        : "memory");
 }
 
 // x of lane (lane ^ R): within a quad of lanes one DPP move, else through the LDS crossbar.

@@ -107,7 +107,7 @@ template <int LCAP, bool POOLS, bool FUZZY>
 __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, StepIn in,
                                                                DraftArgs a, ScanSlices sl) {
   constexpr int BLOCK = kScanBlock;
-  fetch_kernel_arguments();
+  fetch_kernel_arguments<sizeof(IndexView) + sizeof(StepIn) + sizeof(DraftArgs) + sizeof(ScanSlices)>();
   __shared__ LdsScan s;
   __shared__ int32_t sh_base, sh_total, sh_last;
   int32_t row, slice = 0;
@@ -271,8 +271,7 @@ template <int LCAP, bool POOLS, class LDS, bool FUZZY, int QC>
 __global__ __launch_bounds__(step_wave_threads(FUZZY)) void step_wave_kernel(IndexView ix, StepIn in,
                                                                              DraftArgs a) {
   constexpr bool SPLIT = step_wave_threads(FUZZY) > kWave;
-  static_assert(sizeof(IndexView) + sizeof(StepIn) + sizeof(DraftArgs) >= 196, "four lines of arguments");
-  fetch_kernel_arguments();
+  fetch_kernel_arguments<sizeof(IndexView) + sizeof(StepIn) + sizeof(DraftArgs)>();
   __shared__ LDS s;
   int32_t row = xcd_row(ix.P * ix.N);
   if (row < 0) return;
@@ -416,6 +415,7 @@ __global__ __launch_bounds__(256) void advance_append_kernel(
     IndexView ix, int32_t n, int32_t L, const int32_t* settled, const int32_t* future_tok,
     const float* future_prob, int32_t* step_tok, float* step_prob, int32_t* step_cnt,
     int32_t* targets, int32_t* path_len) {
+  fetch_kernel_arguments<sizeof(IndexView) + 2 * sizeof(int32_t) + 9 * sizeof(void*)>();
   const int64_t r = blockIdx.x;
   const int tid = threadIdx.x;
   const int32_t max_len = ix.max_len;
