@@ -4,7 +4,7 @@
 // Forms with identical results (all sums are exact integers):
 //   tier 0  one wave, no tables: the DAG lives in the lanes.  walk_instances:
 //           a lane per (match, layer) instance, for up to 8 matches;
-//           walk_matches: a lane per match, for up to 64;
+//           walk_matches: a lane per match (or per two), for up to 128;
 //   tier 1  LDS hash histograms, all L layers at once: layer d owns one region of the LDS table that
 //           holds its edges (d,u,v) -> (count, probability sum) and its nodes
 //           (d,*,v) -> in-weight; every edge slot links to its target node, so
@@ -257,8 +257,8 @@ __device__ __forceinline__ void walk_instances(LDS& s, const Ctx& c, int32_t M, 
   }
 }
 
-// Tier 0 for up to 64 matches that all have (or get) an LDS window: lane m holds
-// match m and reads its continuation one layer ahead of the walk.  A layer's
+// Tier 0 for up to 64 R matches that all have (or get) an LDS window: lane m holds
+// match m (and m + 64, ..) and reads its continuation one layer ahead of the walk.  A layer's
 // successors are the lanes whose previous token is the current node; a
 // successor's count is the population of a ballot, its probability sum one wave
 // reduction, and from the two follows its weight (Eq. 5) exactly as the tables
@@ -267,55 +267,98 @@ __device__ __forceinline__ void walk_instances(LDS& s, const Ctx& c, int32_t M, 
 // `windows`: M windows of 2 L words (s.win, or any other LDS the caller has free).
 // TREE: the prefix-tree pool instead of the DAG: a layer's successors are the lanes whose
 // whole continuation so far is the draft so far, and only they count for a successor's weight.
-template <bool TREE = false, class LDS>
+// R: matches per lane (lane l holds matches l, l + 64, ..): up to 64 R matches.
+template <bool TREE = false, int R = 1, class LDS>
 __device__ __forceinline__ void walk_matches(LDS& s, const Ctx& c, int32_t M, int32_t L, WinInfo wi,
                                              int32_t* windows, uint32_t alpha_q, int score_mode,
                                              DraftOut& o) {
   const int lane = c.tid;
-  int32_t rem = 0;                                    // layers this lane's match reaches
-  int32_t* win = windows + (lane < M ? lane : 0) * 2 * L;
-  if (lane < M) {
-    Match m = s.match[lane];
-    rem = (int32_t)m.rem_new < L ? (int32_t)m.rem_new : L;
-    if (!wi.cached(lane)) {
-      for (int32_t d = 1; d <= rem; ++d) {
-        uint32_t u, v;
-        u64 w;
-        layer_instance(c.y, m, d, 0u, u, v, w);
-        win[d - 1] = (int32_t)v;
-        win[L + d - 1] = (int32_t)cs_sum(w);
+  int32_t rem[R];                                     // layers this lane's matches reach
+  const int32_t* win[R];
+  uint32_t u[R], v[R], p[R];
+  bool on_draft[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int32_t mi = lane + r * kWave;
+    int32_t* mine = windows + (mi < M ? mi : 0) * 2 * L;
+    rem[r] = 0;
+    if (mi < M) {
+      Match m = s.match[mi];
+      rem[r] = (int32_t)m.rem_new < L ? (int32_t)m.rem_new : L;
+      if (!wi.cached(mi)) {
+        for (int32_t d = 1; d <= rem[r]; ++d) {
+          uint32_t uu, vv;
+          u64 w;
+          layer_instance(c.y, m, d, 0u, uu, vv, w);
+          mine[d - 1] = (int32_t)vv;
+          mine[L + d - 1] = (int32_t)cs_sum(w);
+        }
       }
     }
+    win[r] = mine;
+    on_draft[r] = mi < M;
   }
-  uint32_t u = (uint32_t)c.Q[0], v = (uint32_t)win[0], p = (uint32_t)win[L];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    u[r] = (uint32_t)c.Q[0];
+    v[r] = (uint32_t)win[r][0];
+    p[r] = (uint32_t)win[r][L];
+  }
   int32_t cur = c.Q[0];
-  bool on_draft = lane < M;
   const uint32_t per_count = 65536u - alpha_q;        // Eq. 5 in fixed point, as weight_key()
   for (int32_t d = 1; d <= L; ++d) {
     const int32_t ahead = d < L ? d : L - 1;          // layer d + 1 travels while d is decided
-    const uint32_t v_next = (uint32_t)win[ahead], p_next = (uint32_t)win[L + ahead];
-    const u64 alive = wave_ballot(d <= rem);
-    const u64 cand = (TREE ? wave_ballot(on_draft) : wave_ballot(u == (uint32_t)cur)) & alive;
-    if (!cand) break;                                 // leaf: no edge leaves cur
-    const u64 counted = (TREE || score_mode) ? cand : alive;   // whose weight a successor's rank sums
-    u64 todo = cand;
-    auto successor = [&]() {                          // the token of todo's first lane, and its rank
-      const int src = (int)__ffsll((long long)todo) - 1;
-      const uint32_t vt = (uint32_t)__builtin_amdgcn_readlane((int)v, src);
-      const u64 same = wave_ballot(v == vt) & counted;
-      const uint32_t count = (uint32_t)__popcll(same);
-      const uint32_t sum = wave_sum(lanes_of(same, p));
-      todo &= ~same;
+    uint32_t v_next[R], p_next[R];
+    u64 counted[R], todo[R], any = 0;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      v_next[r] = (uint32_t)win[r][ahead];
+      p_next[r] = (uint32_t)win[r][L + ahead];
+      const u64 alive = wave_ballot(d <= rem[r]);
+      const u64 cand = (TREE ? wave_ballot(on_draft[r]) : wave_ballot(u[r] == (uint32_t)cur)) & alive;
+      counted[r] = (TREE || score_mode) ? cand : alive;   // whose weight a successor's rank sums
+      todo[r] = cand;
+      any |= cand;
+    }
+    if (!any) break;                                  // leaf: no edge leaves cur
+    auto successor = [&]() {                          // the token of the first lane left, and its rank
+      uint32_t vt = 0;
+      bool found = false;
+#pragma unroll
+      for (int r = 0; r < R; ++r) {                   // (uniform: todo is a scalar)
+        if (!found && todo[r] != 0) {
+          vt = (uint32_t)__builtin_amdgcn_readlane((int)v[r], (int)__ffsll((long long)todo[r]) - 1);
+          found = true;
+        }
+      }
+      uint32_t count = 0, mine = 0;
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        const u64 same = wave_ballot(v[r] == vt) & counted[r];
+        count += (uint32_t)__popcll(same);
+        mine += lanes_of(same, p[r]);
+        todo[r] &= ~same;
+      }
+      const uint32_t sum = wave_sum(mine);
       return Cand{(u64)alpha_q * sum + ((u64)(per_count * count) << 16), (int32_t)vt};
     };
+    auto left = [&]() {
+      u64 x = 0;
+#pragma unroll
+      for (int r = 0; r < R; ++r) x |= todo[r];
+      return x;
+    };
     Cand best = successor();
-    while (todo) best = cand_best(best, successor()); // the matches disagree: one round per token
+    while (left()) best = cand_best(best, successor());   // the matches disagree: one round per token
     note_choice(o, best, d, lane);
     cur = best.v;
-    if (TREE) on_draft = on_draft && v == (uint32_t)best.v;
-    u = v;
-    v = v_next;
-    p = p_next;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      if (TREE) on_draft[r] = on_draft[r] && v[r] == (uint32_t)best.v;
+      u[r] = v[r];
+      v[r] = v_next[r];
+      p[r] = p_next[r];
+    }
   }
 }
 

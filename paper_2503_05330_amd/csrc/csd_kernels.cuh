@@ -71,7 +71,7 @@ __device__ __forceinline__ void cache_lens(LDS& s, const Paths& y, int tid) {
   }
 }
 
-// The continuations of the M <= 64 listed matches into windows of 2 L words (tokens, then
+// The continuations of the M listed matches into windows of 2 L words (tokens, then
 // probabilities), one (match, layer) instance per thread; ends with a workgroup barrier.
 template <int BLOCK, class LDS>
 __device__ __forceinline__ void fetch_windows(LDS& s, const Ctx& c, int32_t M, int32_t L,
@@ -212,7 +212,9 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
       bool done = false;
       if (M <= kWave) {
         // one lane of wave 0 per match, no tables: all threads fetch the continuations into
-        // windows (laid over the unused table), one (match, layer) instance each
+        // windows (laid over the unused table), one (match, layer) instance each.  (More matches
+        // per lane do not pay here: with one-edit matching most continuations differ, and a
+        // layer then costs one round per match.)
         int32_t* windows = reinterpret_cast<int32_t*>(s.table);
         fetch_windows<BLOCK>(s, c, M, L, windows);
         if (c.tid < kWave) walk_matches(s, c, M, L, WinInfo{0, M}, windows, a.alpha_q, a.score_mode, o);
@@ -332,6 +334,8 @@ __global__ __launch_bounds__(step_wave_threads(FUZZY)) void step_wave_kernel(Ind
     }
   } else if (M > 0 && M <= kWave && M <= LDS::kWin / (2 * L)) {
     walk_matches(s, c, M, L, wi, s.win, a.alpha_q, a.score_mode, o);             // one lane per match
+  } else if (M > 0 && M <= 2 * kWave && M <= LDS::kWin / (2 * L)) {
+    walk_matches<false, 2>(s, c, M, L, wi, s.win, a.alpha_q, a.score_mode, o);   // two matches per lane
   } else if (M > 0) {
     bool streaming = M > LDS::kMatch;
     if (!streaming) {

@@ -601,11 +601,12 @@ def test_random_configurations_against_the_oracle(oracle):
 
 def test_match_counts_across_the_walk_forms(oracle):
     """Rows whose match counts sweep from 0 to hundreds within one replay, so that every form
-    of the DAG walk (lanes = instances, lanes = matches, LDS tables) and the hand-overs between
-    them (8 | 9 and 64 | 65 matches at L = 8, fewer for longer drafts) are crossed many times,
+    of the DAG walk (lanes = instances, lanes = one, two or four matches, LDS tables) and the
+    hand-overs between them (8 | 9, 64 | 65, 128 | 129 and 256 | 257 matches at L = 8, fewer for
+    longer drafts) are crossed many times,
     under both scoring modes, the tree pool, and both matchers."""
     rng = np.random.default_rng(8964)
-    P, N, T, V, k = 2, 8, 120, 3, 2
+    P, N, T, V, k = 2, 8, 240, 3, 2
     motif = rng.integers(0, V, size=12)
     tokens = np.zeros((P, N, T), dtype=np.int32)
     for p in range(P):
@@ -636,8 +637,8 @@ def test_match_counts_across_the_walk_forms(oracle):
                 h = tokens[0, o, :t + 1]
                 for e in range(k, t + 1):
                     m += int(np.array_equal(h[e - k:e], q))
-            seen.add(min(m, 65) if m > 9 else m)
-    assert {0, 1, 2, 4, 8, 9, 65} <= seen, sorted(seen)
+            seen.add(m if m <= 9 else 10 if m <= 64 else 65 if m <= 128 else 129 if m <= 256 else 257)
+    assert {0, 1, 2, 4, 8, 9, 10, 65, 129, 257} <= seen, sorted(seen)
 
 
 @pytest.mark.parametrize("include_self,backoff", [(True, False), (False, True), (True, True)])
