@@ -174,7 +174,8 @@ int csd_draft(csd_index* index, int32_t query_len, int32_t draft_len, int32_t* d
 int csd_accept(csd_index* index, const int32_t* d_draft_tokens, const int32_t* d_draft_len,
                const int32_t* d_targets, int32_t draft_len, int32_t* d_accept_len, void* stream);
 
-/* One decoding step in ONE launch (two when n > 1 with the index matcher):
+/* One decoding step in ONE launch (two with the index matcher when n > 64, or n > 1
+ * with one-edit matching):
  * csd_append(d_tokens, d_probs, d_counts, n),
  * then csd_draft(query_len, draft_len, ...) on the grown paths, then, if
  * d_targets is given, csd_accept of the fresh drafts (Algorithm 1 run at step t

@@ -191,6 +191,9 @@ int check_draft_args(const csd_index* h, int32_t query_len, int32_t draft_len) {
 // From this many rows on (256 CUs x 4 rows of the regular layout are resident at once) the
 // one-wave kernel runs with the small LDS layout.
 constexpr int64_t kSmallLdsRows = 2048;
+// Steps of up to this many tokens per path run fused in the one-wave kernel (a lane per new
+// position: at most a wave's worth).
+constexpr int32_t kFusedStepTokens = kWave;
 
 void launch_draft(const csd_index* h, const IndexView& v, const StepIn& in, const DraftArgs& a,
                   hipStream_t st) {
@@ -203,7 +206,7 @@ void launch_draft(const csd_index* h, const IndexView& v, const StepIn& in, cons
     if (a.L <= 8) step_wave_kernel<8, true, LdsWaveFuzzy, true, CSD_MAX_QUERY_LEN><<<grid, kWave, 0, st>>>(v, in, a);
     else if (a.L <= 16) step_wave_kernel<16, true, LdsWaveFuzzy, true, CSD_MAX_QUERY_LEN><<<grid, kWave, 0, st>>>(v, in, a);
     else step_wave_kernel<32, true, LdsWaveFuzzy, true, CSD_MAX_QUERY_LEN><<<grid, kWave, 0, st>>>(v, in, a);
-  } else if (a.pool_mode != CSD_POOL_DAG || v.options != 0) {   // tree and list pools, own history, back-off: the general kernels
+  } else if (a.pool_mode != CSD_POOL_DAG || v.options != 0 || in.n > 1) {   // tree and list pools, own history, back-off, steps of several tokens: the general kernels
     if (!h->indexed && v.eps > 0) step_scan_kernel<1, true, true><<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
     else if (!h->indexed) step_scan_kernel<1, true, false><<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
     else if (a.L <= 8) step_wave_kernel<8, true, LdsWave, false, CSD_MAX_QUERY_LEN><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
@@ -384,8 +387,9 @@ int csd_step(csd_index* h, const int32_t* d_tokens, const float* d_probs, const 
   DraftArgs a{query_len, draft_len, h->alpha_q, h->cfg.score_mode, h->cfg.pool_mode,
               d_draft_tokens, d_draft_len,
               d_token_scores, d_path_scores, d_targets, d_accept_len};
-  if (h->indexed && n != 1) {
-    // the one-wave kernel fuses the append of ONE token per path; longer steps append first
+  if (h->indexed && n != 1 && (h->view.eps > 0 || n > kFusedStepTokens)) {
+    // the one-wave kernels fuse the append of a few tokens per path (exact matching) or of
+    // one (one-edit matching); longer steps append first, with a workgroup per row
     int64_t rows = (int64_t)h->view.P * h->view.N;
     append_kernel<<<(uint32_t)rows, 256, 0, as_stream(stream)>>>(
         view_in_place(h), StepIn{d_tokens, d_probs, d_counts, n});

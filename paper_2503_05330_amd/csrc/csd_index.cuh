@@ -83,6 +83,42 @@ __device__ __forceinline__ void gram_insert_position(int32_t* gram, uint32_t mas
   gram_insert_from(gram, mask, gram_hash_end(acc, kmax), 0u, y.pos(i, e), lane);
 }
 
+// Inserts the postings of the cnt <= 64 positions old_i .. old_i + cnt - 1 of path i by one
+// wave, a lane per position: every lane hashes its gram, reads the fill count of its first
+// bucket and claims a slot there — three round trips for all of them together.  A lane whose
+// first buckets are full (rare) leaves its posting to the whole wave.
+__device__ __forceinline__ void gram_insert_lanes(int32_t* gram, uint32_t mask, int32_t kmax,
+                                                  const Paths& y, int32_t i, int32_t old_i,
+                                                  int32_t cnt, int lane) {
+  const int32_t e = old_i + lane;
+  const bool mine = lane < cnt && e >= kmax;
+  uint32_t acc = kGramSeed;
+  for (int32_t g = 1; g <= kmax; ++g)                  // (idle lanes read the path's first token)
+    acc = gram_hash_add(acc, y.token(i, mine ? e - g : 0, old_i));
+  const GramHash gh = gram_hash_end(acc, kmax);
+  const int32_t pos = y.pos(i, e);
+  bool todo = mine;
+  for (uint32_t r = 0; r < 4u && r <= mask; ++r) {
+    if (wave_ballot(todo) == 0) return;
+    int32_t* b = gram_bucket(gram, gh, r, mask);
+    if (todo && b[0] < kBucketSlots) {
+      const int32_t c = atomicAdd(b, 1);
+      if (c < kBucketSlots) {
+        b[1 + c] = pos;
+        todo = false;
+      }
+    }
+  }
+  u64 left = wave_ballot(todo);
+  while (left) {                                       // their first four buckets were full
+    const int t = (int)__ffsll((long long)left) - 1;
+    left &= left - 1;
+    const GramHash g{(uint32_t)__builtin_amdgcn_readlane((int)gh.h, t),
+                     (uint32_t)__builtin_amdgcn_readlane((int)gh.step, t)};
+    gram_insert_from(gram, mask, g, 4u, __builtin_amdgcn_readlane(pos, t), lane);
+  }
+}
+
 // Split-phase insert of ONE new position by one wave, so that its two memory
 // round trips overlap the lookup's: lanes 0..3 look at the first four buckets of
 // the gram's sequence (sixteen were no faster and fetched twelve more lines per row).
@@ -282,9 +318,13 @@ __device__ __forceinline__ void append_row(const IndexView& ix, const Paths& y, 
   }
   if (WITH_INDEX && ix.gram) {
     int32_t* gram = ix.gram + (int64_t)p * ((int64_t)ix.bucket_mask + 1) * kBucketWords;
-    for (int32_t t = tid / kWave; t < cnt; t += BLOCK / kWave) {   // one wave per new position
-      if (ix.eps > 0) gram_insert_variants(gram, ix.bucket_mask, ix.kmax, y, i, old_i + t, old_i, tid & 63);
-      else gram_insert_position(gram, ix.bucket_mask, ix.kmax, y, i, old_i + t, old_i, tid & 63);
+    if (BLOCK == kWave && ix.eps == 0 && cnt <= kWave) {            // one wave: a lane per new position
+      gram_insert_lanes(gram, ix.bucket_mask, ix.kmax, y, i, old_i, cnt, tid);
+    } else {
+      for (int32_t t = tid / kWave; t < cnt; t += BLOCK / kWave) {   // one wave per new position
+        if (ix.eps > 0) gram_insert_variants(gram, ix.bucket_mask, ix.kmax, y, i, old_i + t, old_i, tid & 63);
+        else gram_insert_position(gram, ix.bucket_mask, ix.kmax, y, i, old_i + t, old_i, tid & 63);
+      }
     }
   }
   if (flags) atomicOr(ix.status, flags);

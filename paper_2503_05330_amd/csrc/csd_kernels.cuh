@@ -282,7 +282,7 @@ __global__ __launch_bounds__(step_wave_threads(FUZZY)) void step_wave_kernel(Ind
   if (SPLIT) {
     c.tid = (int)(threadIdx.x & (kWave - 1));
     if (__builtin_amdgcn_readfirstlane((int)threadIdx.x) >= kWave) {
-      wave_append<QC>(c, ix, p);
+      wave_append<QC, POOLS>(c, ix, p);
       return;
     }
   }

@@ -338,7 +338,9 @@ __device__ __forceinline__ void match_plain(const LDS& s, const Ctx& c, Sink& si
 //   3. for every posting found, its verify tokens together with its whole
 //      continuation (tokens and probabilities), kept in LDS for the DAG;
 //      the insert's atomic travels with these.
-// It handles steps that append at most one token per path (in.n <= 1).  With
+// It is laid out for steps that append at most one token per path (in.n <= 1); the general
+// kernels also take longer steps, at the price of one more round trip (the query then comes
+// from the step's input, and the appended positions are matched one lane per position).  With
 // exact matching the append and the insert are another wave's (wave_append).
 
 struct Head {                   // a path's end before this step
@@ -562,6 +564,7 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
   if (APPENDS && y.n == 1 && y.sp) sp_i = y.sp[c.i];
   const int32_t old_i = me.old_len, cnt_i = me.new_len - me.old_len;
   c.len_i = me.new_len;
+  const bool multi = GENERAL && y.n > 1;                // a step of several tokens per path
   c.q = k < c.len_i ? k : c.len_i;
 #pragma unroll
   for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) {
@@ -569,6 +572,7 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
     if (a < QC && a < c.q) v = a < cnt_i ? st_i : pick_n<QC>(me.tail, a - cnt_i);
     c.Q[a] = v;
   }
+  if (multi) load_query(c, k, old_i);                   // (one more round trip: from the step's input)
   const bool use_index = c.q == ix.kmax;                // shorter queries: scan (short paths)
   // ---- round trip 2 is requested: fill counts for the insert, first 4 buckets of the query
   ticket_used = APPENDS && cnt_i == 1;
@@ -592,11 +596,29 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
       s.len_new[j] = hj.new_len;
     }
     // a position appended by this very launch matches when the old tail before it is the query
-    bool hit = use_index && have && j != (GENERAL ? c.skip : c.i) && hj.new_len > hj.old_len &&
-               hj.old_len >= c.q;
+    bool hit = use_index && !multi && have && j != (GENERAL ? c.skip : c.i) &&
+               hj.new_len > hj.old_len && hj.old_len >= c.q;
 #pragma unroll
     for (int a = 0; a < QC; ++a) hit = hit && (a >= c.q || hj.tail[a] == c.Q[a]);
     wave_push(s, n_match, hit, make_match(y, j, hj.old_len, hj.old_len, hj.new_len), lane);
+  }
+  if (GENERAL && multi && use_index) {
+    // every position this launch appends, a lane per (path, offset): its gram runs through
+    // the old tail and the step's input
+    block_sync<kWave>();                                // the lengths are in LDS
+    const int32_t pairs = y.N * y.n;
+    for (int32_t x0 = 0; x0 < pairs; x0 += kWave) {
+      const int32_t x = x0 + lane;
+      const int32_t j = x < pairs ? x % y.N : 0;        // (offset-major: the first offsets, which
+      int32_t old_j, new_j;                             // most paths have, fill the first rounds)
+      lens_of(s, y, j, old_j, new_j);
+      const int32_t e = old_j + x / y.N;
+      bool hit = x < pairs && j != c.skip && e < new_j && e >= c.q;
+      if (wave_ballot(hit) == 0) continue;              // no path has that many new tokens
+      // (idle lanes look at the row's own end, where every token of the gram exists)
+      hit = gram_equals_query(c, hit ? j : c.i, hit ? e : c.len_i, hit ? old_j : old_i) && hit;
+      wave_push(s, n_match, hit, make_match(y, j, e, old_j, new_j), lane);
+    }
   }
   if (ticket_used) insert_claim(ticket, gram, c.bucket_mask, lane);   // round trip 3 starts
   wi.n_fresh = n_match;
@@ -616,10 +638,16 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
 // the one that drafts: the row's token goes to the history and the meta row, its position to
 // the index.  Nothing the drafting waves of this launch read is written here: they take
 // positions from the old lengths on from the step's input, and ignore newer postings.
-template <int QC>
+// GENERAL: also compiled for steps of several tokens per path.
+template <int QC, bool GENERAL = false>
 __device__ __forceinline__ void wave_append(const Ctx& c, const IndexView& ix, int32_t p) {
   const int lane = c.tid;
   const Paths& y = c.y;
+  if (GENERAL && y.n > 1) {
+    const int32_t old_i = y.old_len(c.i);
+    append_row<kWave, true>(ix, y, p, c.i, old_i, y.new_len(c.i, old_i), lane);
+    return;
+  }
   if (y.n != 1) return;
   const int64_t row = (int64_t)p * ix.N + c.i;
   int32_t* gram = const_cast<int32_t*>(c.gram);

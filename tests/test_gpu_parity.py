@@ -137,6 +137,35 @@ def test_ragged_appends(oracle):
                 assert_step_equal(got, want[t], t, "ragged %s flags=%d %s" % (name, flags, how))
 
 
+def test_long_ragged_steps_around_the_fused_limit(oracle):
+    """Steps of up to 63, 64 and 65 tokens per path: the index matcher fuses up to 64 (a lane per
+    new position, many more new positions than old ones in the first steps) and appends longer
+    steps in a launch of their own; with counts from 0 to n, vocabulary 6, so that the appended
+    positions themselves match."""
+    rng = np.random.default_rng(6465)
+    P, N, T, V, k, L = 2, 5, 400, 6, 2, 8
+    motif = rng.integers(0, V, size=9)
+    tokens = np.zeros((P, N, T), dtype=np.int32)
+    for p in range(P):
+        for j in range(N):
+            seq = np.tile(np.roll(motif, int(rng.integers(0, 9))), T // 9 + 1)[:T]
+            tokens[p, j] = np.where(rng.random(T) < 0.08, rng.integers(0, V, size=T), seq)
+    probs = (rng.integers(1, 17, size=tokens.shape) / 16.0).astype(np.float32)
+    for n in (63, 64, 65):
+        steps = 8
+        counts = rng.integers(0, n + 1, size=(steps, P, N)).astype(np.int32)
+        for flags, mode in ((INDEX, 0), (INDEX | binding.INCLUDE_SELF, 1), (SCAN, 0)):
+            what = "n%d flags%d mode%d" % (n, flags, mode)
+            print(what, flush=True)
+            got = gpu_replay(tokens, probs, k, L, 0.5, mode, flags, steps=steps, counts=counts,
+                             n_per_step=n, how="step")
+            assert got["status"] in (0, binding.STATUS_CAPACITY), what
+            for t in range(steps):
+                want = oracle.draft_all(tokens, probs, got["lens"][t], k, L, 0.5, mode,
+                                        include_self=bool(flags & binding.INCLUDE_SELF))
+                assert_step_equal(got, want, t, what)
+
+
 def test_query_len_longer_and_shorter_than_history(oracle):
     """q = min(k, len_i): the first steps of a replay use 1- and 2-token queries; also
     draft() with every query_len up to the maximum on a full history."""
