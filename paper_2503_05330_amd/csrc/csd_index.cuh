@@ -72,25 +72,14 @@ __device__ __forceinline__ void gram_insert_from(int32_t* tbl, uint32_t mask, Gr
   }
 }
 
-// Inserts the posting of position e of path i (e >= kmax), by one whole wave
-// (used for bulk appends).
-__device__ __forceinline__ void gram_insert_position(int32_t* gram, uint32_t mask, int32_t kmax,
-                                                     const Paths& y, int32_t i, int32_t e,
-                                                     int32_t old_i, int lane) {
-  if (e < kmax) return;
-  uint32_t acc = kGramSeed;
-  for (int32_t g = 1; g <= kmax; ++g) acc = gram_hash_add(acc, y.token(i, e - g, old_i));
-  gram_insert_from(gram, mask, gram_hash_end(acc, kmax), 0u, y.pos(i, e), lane);
-}
-
-// Inserts the postings of the cnt <= 64 positions old_i .. old_i + cnt - 1 of path i by one
+// Inserts the postings of the cnt <= 64 positions first .. first + cnt - 1 of path i by one
 // wave, a lane per position: every lane hashes its gram, reads the fill count of its first
 // bucket and claims a slot there — three round trips for all of them together.  A lane whose
 // first buckets are full (rare) leaves its posting to the whole wave.
 __device__ __forceinline__ void gram_insert_lanes(int32_t* gram, uint32_t mask, int32_t kmax,
                                                   const Paths& y, int32_t i, int32_t old_i,
-                                                  int32_t cnt, int lane) {
-  const int32_t e = old_i + lane;
+                                                  int32_t first, int32_t cnt, int lane) {
+  const int32_t e = first + lane;
   const bool mine = lane < cnt && e >= kmax;
   uint32_t acc = kGramSeed;
   for (int32_t g = 1; g <= kmax; ++g)                  // (idle lanes read the path's first token)
@@ -318,13 +307,15 @@ __device__ __forceinline__ void append_row(const IndexView& ix, const Paths& y, 
   }
   if (WITH_INDEX && ix.gram) {
     int32_t* gram = ix.gram + (int64_t)p * ((int64_t)ix.bucket_mask + 1) * kBucketWords;
-    if (BLOCK == kWave && ix.eps == 0 && cnt <= kWave) {            // one wave: a lane per new position
-      gram_insert_lanes(gram, ix.bucket_mask, ix.kmax, y, i, old_i, cnt, tid);
-    } else {
-      for (int32_t t = tid / kWave; t < cnt; t += BLOCK / kWave) {   // one wave per new position
-        if (ix.eps > 0) gram_insert_variants(gram, ix.bucket_mask, ix.kmax, y, i, old_i + t, old_i, tid & 63);
-        else gram_insert_position(gram, ix.bucket_mask, ix.kmax, y, i, old_i + t, old_i, tid & 63);
+    if (ix.eps == 0) {                                  // a lane per new position, 64 per wave and round
+      for (int32_t t0 = (tid / kWave) * kWave; t0 < cnt; t0 += BLOCK) {
+        const int32_t left = cnt - t0;
+        gram_insert_lanes(gram, ix.bucket_mask, ix.kmax, y, i, old_i, old_i + t0,
+                          left < kWave ? left : kWave, tid & 63);
       }
+    } else {
+      for (int32_t t = tid / kWave; t < cnt; t += BLOCK / kWave)   // one wave per new position
+        gram_insert_variants(gram, ix.bucket_mask, ix.kmax, y, i, old_i + t, old_i, tid & 63);
     }
   }
   if (flags) atomicOr(ix.status, flags);
