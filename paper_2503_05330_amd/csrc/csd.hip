@@ -209,6 +209,11 @@ void launch_draft(const csd_index* h, const IndexView& v, const StepIn& in, cons
   } else if (a.pool_mode != CSD_POOL_DAG || v.options != 0 || in.n > 1) {   // tree and list pools, own history, back-off, steps of several tokens: the general kernels
     if (!h->indexed && v.eps > 0) step_scan_kernel<1, true, true><<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
     else if (!h->indexed) step_scan_kernel<1, true, false><<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
+    else if (v.kmax <= 4) {                      // the usual gram lengths: loops unrolled to 4
+      if (a.L <= 8) step_wave_kernel<8, true, LdsWave, false, 4><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
+      else if (a.L <= 16) step_wave_kernel<16, true, LdsWave, false, 4><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
+      else step_wave_kernel<32, true, LdsWave, false, 4><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
+    }
     else if (a.L <= 8) step_wave_kernel<8, true, LdsWave, false, CSD_MAX_QUERY_LEN><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
     else if (a.L <= 16) step_wave_kernel<16, true, LdsWave, false, CSD_MAX_QUERY_LEN><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
     else step_wave_kernel<32, true, LdsWave, false, CSD_MAX_QUERY_LEN><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
