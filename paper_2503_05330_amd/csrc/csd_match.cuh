@@ -343,6 +343,9 @@ __device__ __forceinline__ void match_plain(const LDS& s, const Ctx& c, Sink& si
 // from the step's input, and the appended positions are matched one lane per position).  With
 // exact matching the append and the insert are another wave's (wave_append).
 
+constexpr int kStageTokens = 1024;   // a step's tokens (N * n) that the general front end stages in LDS
+constexpr int kStagePaths = 64;      // .. and the paths whose old tails it stages
+
 struct Head {                   // a path's end before this step
   int32_t old_len, new_len;
   int32_t tail[kTailCap];       // tail[a] = a-th token from the old end (tail_len of them are kept)
@@ -548,6 +551,17 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
   const int32_t jl = lane < y.N ? lane : 0;
   int32_t st_j = y.n == 1 ? y.st[jl] : 0;               // (before the head: its lengths wait for it)
   Head hj = load_head<QC>(y, ix.tail_len, jl);
+  // a step of several tokens per path (general kernels): the step's tokens and the paths' old
+  // tails go to LDS (laid over the table, which nothing uses before the walk) when they fit, so
+  // that the query and the matches among the appended positions need no further round trip
+  const bool multi = GENERAL && y.n > 1;
+  const bool staged = multi && y.N * y.n <= kStageTokens && y.N <= kStagePaths;
+  int32_t* stage = reinterpret_cast<int32_t*>(s.table);   // [N][n] the step's tokens
+  int32_t* tails = stage + kStageTokens;                  // [N][QC] tokens before the old ends
+  static_assert(!GENERAL || (kStageTokens + kStagePaths * QC) * sizeof(int32_t) <= sizeof(s.table),
+                "the staged step fits the table");
+  if (GENERAL && staged)
+    for (int32_t x = lane; x < y.N * y.n; x += kWave) stage[x] = y.st[x];
   Head me;
   int32_t st_i;
   if (c.i < kWave) {
@@ -564,7 +578,6 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
   if (APPENDS && y.n == 1 && y.sp) sp_i = y.sp[c.i];
   const int32_t old_i = me.old_len, cnt_i = me.new_len - me.old_len;
   c.len_i = me.new_len;
-  const bool multi = GENERAL && y.n > 1;                // a step of several tokens per path
   c.q = k < c.len_i ? k : c.len_i;
 #pragma unroll
   for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) {
@@ -572,7 +585,14 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
     if (a < QC && a < c.q) v = a < cnt_i ? st_i : pick_n<QC>(me.tail, a - cnt_i);
     c.Q[a] = v;
   }
-  if (multi) load_query(c, k, old_i);                   // (one more round trip: from the step's input)
+  if (GENERAL && staged) {
+    block_sync<kWave>();                                // the staged tokens are in LDS
+#pragma unroll
+    for (int a = 0; a < QC; ++a)
+      if (a < c.q && a < cnt_i) c.Q[a] = stage[c.i * y.n + cnt_i - 1 - a];
+  } else if (multi) {
+    load_query(c, k, old_i);                            // (one more round trip: from the step's input)
+  }
   const bool use_index = c.q == ix.kmax;                // shorter queries: scan (short paths)
   // ---- round trip 2 is requested: fill counts for the insert, first 4 buckets of the query
   ticket_used = APPENDS && cnt_i == 1;
@@ -595,6 +615,10 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
       s.len_old[j] = hj.old_len;
       s.len_new[j] = hj.new_len;
     }
+    if (GENERAL && staged && have) {
+#pragma unroll
+      for (int a = 0; a < QC; ++a) tails[j * QC + a] = hj.tail[a];
+    }
     // a position appended by this very launch matches when the old tail before it is the query
     bool hit = use_index && !multi && have && j != (GENERAL ? c.skip : c.i) &&
                hj.new_len > hj.old_len && hj.old_len >= c.q;
@@ -615,8 +639,17 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
       const int32_t e = old_j + x / y.N;
       bool hit = x < pairs && j != c.skip && e < new_j && e >= c.q;
       if (wave_ballot(hit) == 0) continue;              // no path has that many new tokens
-      // (idle lanes look at the row's own end, where every token of the gram exists)
-      hit = gram_equals_query(c, hit ? j : c.i, hit ? e : c.len_i, hit ? old_j : old_i) && hit;
+      if (staged) {
+        const int32_t off = hit ? e - old_j : 0;        // new tokens before the position
+#pragma unroll
+        for (int a = 0; a < QC; ++a) {
+          const int32_t t = a < off ? stage[j * y.n + off - 1 - a] : tails[j * QC + (a - off)];
+          hit = hit && (a >= c.q || t == c.Q[a]);
+        }
+      } else {
+        // (idle lanes look at the row's own end, where every token of the gram exists)
+        hit = gram_equals_query(c, hit ? j : c.i, hit ? e : c.len_i, hit ? old_j : old_i) && hit;
+      }
       wave_push(s, n_match, hit, make_match(y, j, e, old_j, new_j), lane);
     }
   }
