@@ -215,9 +215,12 @@ int csd_replay(csd_index* index, int32_t n_steps, const int32_t* d_tokens, const
  * against the path's next draft_len future tokens.  Path lengths diverge as
  * paths accept different numbers of tokens.  A host loop inside the library:
  * per step one small kernel that gathers the step's input and csd_step with
- * draft_len + 1 tokens per path and counts.
+ * draft_len + 1 tokens per path and counts (with the index matcher, exact
+ * matching and twice the minimum of scratch memory: one launch per step, whose
+ * tail gathers the next step's input).
  *   d_scratch: device memory, 4-byte aligned, scratch_bytes >=
  *     P*N*(3*draft_len + 3)*4 (step tokens, probabilities, targets, counts);
+ *     with twice as much, steps alternate between the two halves;
  *   d_draft_tokens [n_steps][P][N][draft_len], d_draft_len, d_accept_len and
  *   d_path_len (lengths after the step's append) [n_steps][P][N].
  * Errors: CSD_ERR_INVALID_ARG, CSD_ERR_WORKSPACE (scratch too small or

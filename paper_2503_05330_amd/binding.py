@@ -236,17 +236,19 @@ class Index:
         out["accept"] = accept_out
         return out
 
-    def accept_loop(self, n_steps, future_tokens, future_probs, query_len, draft_len, out=None):
+    def accept_loop(self, n_steps, future_tokens, future_probs, query_len, draft_len, out=None,
+                    min_scratch=False):
         """n_steps of the propose / verify / accept loop with each path's own future
         (future_tokens / future_probs [P][N][max_len]) standing in for the model.  Returns
-        dict(tokens [S][P][N][L], length, accept, path_len [S][P][N])."""
+        dict(tokens [S][P][N][L], length, accept, path_len [S][P][N]).  min_scratch: hand over
+        the minimum of scratch memory instead of twice as much (same results, more launches)."""
         L, S = draft_len, n_steps
         if out is None:
             out = dict(tokens=torch.empty((S, self.P, self.N, L), dtype=torch.int32, device=self.device))
             for name in ("length", "accept", "path_len"):
                 out[name] = torch.empty((S, self.P, self.N), dtype=torch.int32, device=self.device)
         cells = self.rows * self.cfg.max_len
-        nbytes = self.rows * (3 * L + 3) * 4
+        nbytes = (1 if min_scratch else 2) * self.rows * (3 * L + 3) * 4   # twice the minimum: one launch per step
         scratch = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
         self._check(load().csd_accept_loop(self._h, S, _ptr(future_tokens, torch.int32, cells),
                                            _ptr(future_probs, torch.float32, cells), query_len, L,

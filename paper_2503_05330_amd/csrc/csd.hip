@@ -462,6 +462,43 @@ int csd_accept_loop(csd_index* h, int32_t n_steps, const int32_t* d_future_token
   int32_t* targets = reinterpret_cast<int32_t*>(step_prob + rows * n);
   int32_t* step_cnt = targets + rows * L;
   hipStream_t st = as_stream(stream);
+  if (h->indexed && h->view.eps == 0 && h->view.kmax <= 4 && n_steps > 0 &&
+      scratch_bytes >= 2 * rows * (2 * n + L + 1) * 4) {
+    // one launch per step: the fused step of up to L + 1 tokens per path, whose tail works out
+    // the next step's input into the other half of the scratch memory
+    int32_t* half[2] = {step_tok, step_tok + rows * (2 * n + L + 1)};
+    auto tok_of = [&](int x) { return half[x]; };
+    auto prob_of = [&](int x) { return reinterpret_cast<float*>(half[x] + rows * n); };
+    auto targets_of = [&](int x) { return half[x] + rows * 2 * n; };
+    auto cnt_of = [&](int x) { return half[x] + rows * (2 * n + L); };
+    advance_kernel<<<(uint32_t)((rows + 255) / 256), 256, 0, st>>>(
+        (int64_t)rows, h->cfg.max_len, (int32_t)n, draft_len, h->meta[h->cur], h->view.meta_stride,
+        nullptr, d_future_tokens, d_future_probs, tok_of(0), d_future_probs ? prob_of(0) : nullptr,
+        cnt_of(0), targets_of(0), d_path_len);
+    CSD_HIP(hipGetLastError());
+    const uint32_t grid = xcd_grid((int64_t)rows);
+    for (int32_t s = 0; s < n_steps; ++s) {
+      const int x = s & 1;
+      rc = note_append(h, true, (int32_t)n);
+      if (rc != CSD_OK) return rc;
+      IndexView v = h->view;
+      v.meta_old = h->meta[h->cur];
+      v.meta_new = h->meta[h->cur ^ 1];
+      const StepIn in{tok_of(x), d_future_probs ? prob_of(x) : nullptr, cnt_of(x), (int32_t)n};
+      DraftArgs a{query_len, draft_len, h->alpha_q, h->cfg.score_mode, h->cfg.pool_mode,
+                  d_draft_tokens + (size_t)s * rows * L, d_draft_len + (size_t)s * rows,
+                  nullptr, nullptr, targets_of(x), d_accept_len + (size_t)s * rows};
+      const LoopTail tail{d_future_tokens, d_future_probs, tok_of(x ^ 1),
+                          d_future_probs ? prob_of(x ^ 1) : nullptr, cnt_of(x ^ 1), targets_of(x ^ 1),
+                          d_path_len + (size_t)s * rows, (int32_t)n, h->cfg.max_len};
+      if (draft_len <= 8) step_loop_kernel<8, 4><<<grid, step_wave_threads(false), 0, st>>>(v, in, a, tail);
+      else if (draft_len <= 16) step_loop_kernel<16, 4><<<grid, step_wave_threads(false), 0, st>>>(v, in, a, tail);
+      else step_loop_kernel<32, 4><<<grid, step_wave_threads(false), 0, st>>>(v, in, a, tail);
+      CSD_HIP(hipGetLastError());
+      h->cur ^= 1;
+    }
+    return CSD_OK;
+  }
   for (int32_t s = 0; s < n_steps; ++s) {
     const int32_t* settled = s > 0 ? d_accept_len + (size_t)(s - 1) * rows : nullptr;
     if (h->indexed) {                   // two launches: step input + append, then the draft

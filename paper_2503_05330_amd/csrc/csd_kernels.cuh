@@ -53,11 +53,14 @@ __device__ __forceinline__ void write_outputs(const DraftArgs& a, int32_t row, c
 }
 
 // "Draft acceptance": the first lane whose draft token differs from its target.
-__device__ __forceinline__ void write_accept(const DraftArgs& a, int32_t row, const DraftOut& o,
-                                             int32_t target, int tid) {
+// Returns the accept length (the same in every lane).
+__device__ __forceinline__ int32_t write_accept(const DraftArgs& a, int32_t row, const DraftOut& o,
+                                                int32_t target, int tid) {
   bool same = tid < o.n && target == o.tok;
   u64 differs = wave_ballot(!same);
-  if (tid == 0) a.accept_len[row] = differs ? (int32_t)__ffsll((long long)differs) - 1 : kWave;
+  const int32_t accepted = differs ? (int32_t)__ffsll((long long)differs) - 1 : kWave;
+  if (tid == 0) a.accept_len[row] = accepted;
+  return accepted;
 }
 
 // Lengths of the first kLenCache paths into LDS (the scan reads them per tile).
@@ -269,11 +272,27 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
 // path of the first.  The two never meet at a barrier.
 constexpr int step_wave_threads(bool fuzzy) { return fuzzy ? kWave : 2 * kWave; }
 
-template <int LCAP, bool POOLS, class LDS, bool FUZZY, int QC>
-__global__ __launch_bounds__(step_wave_threads(FUZZY)) void step_wave_kernel(IndexView ix, StepIn in,
-                                                                             DraftArgs a) {
+// The accept-driven loop's stand-in model as the tail of a step (see advance_kernel): the row
+// that has just drafted and counted its accepted tokens works out what it appends at the NEXT
+// step — those tokens plus the one the model emits itself, from the path's own future — and
+// the targets of the next draft, into buffers that the next launch reads (not the ones this
+// launch reads: the caller alternates between two sets).
+struct NoTail {};
+struct LoopTail {
+  const int32_t* future_tok;    // [rows][max_len]
+  const float* future_prob;     // [rows][max_len] or null
+  int32_t* next_tok;            // [rows][n]
+  float* next_prob;             // [rows][n] or null
+  int32_t* next_cnt;            // [rows]
+  int32_t* next_targets;        // [rows][L]
+  int32_t* path_len;            // [rows] output: lengths after this step's append
+  int32_t n, max_len;
+};
+
+template <int LCAP, bool POOLS, class LDS, bool FUZZY, int QC, class TAIL>
+__device__ __forceinline__ void step_wave_body(const IndexView& ix, const StepIn& in,
+                                               const DraftArgs& a, const TAIL& tail) {
   constexpr bool SPLIT = step_wave_threads(FUZZY) > kWave;
-  fetch_kernel_arguments<sizeof(IndexView) + sizeof(StepIn) + sizeof(DraftArgs)>();
   __shared__ LDS s;
   int32_t row = xcd_row(ix.P * ix.N);
   if (row < 0) return;
@@ -362,7 +381,47 @@ __global__ __launch_bounds__(step_wave_threads(FUZZY)) void step_wave_kernel(Ind
     insert_finish(ticket, const_cast<int32_t*>(c.gram), c.bucket_mask,
                   c.y.pos(c.i, c.len_i - 1), c.tid);
   write_outputs<kWave>(a, row, o, c.tid);
-  if (a.targets) write_accept(a, row, o, target, c.tid);
+  int32_t accepted = 0;
+  if (a.targets) accepted = write_accept(a, row, o, target, c.tid);
+  if constexpr (std::is_same<TAIL, LoopTail>::value) {
+    const int32_t len = c.len_i;                        // after this step's append
+    int32_t grow = accepted + 1;
+    grow = grow > tail.n ? tail.n : grow;
+    const int32_t room = tail.max_len - len;
+    grow = grow < room ? grow : room;
+    const int64_t r = row;
+    const int32_t* ft = tail.future_tok + r * tail.max_len;
+    if (c.tid == 0) {
+      tail.next_cnt[r] = grow;
+      tail.path_len[r] = len;
+    }
+    for (int32_t t = c.tid; t < tail.n; t += kWave) {
+      const bool in_path = len + t < tail.max_len;
+      tail.next_tok[r * tail.n + t] = in_path ? ft[len + t] : 0;
+      if (tail.next_prob)
+        tail.next_prob[r * tail.n + t] = in_path ? tail.future_prob[r * tail.max_len + len + t] : 0.0f;
+    }
+    for (int32_t d = c.tid; d < L; d += kWave) {
+      const int32_t t = len + grow + d;
+      tail.next_targets[r * L + d] = t < tail.max_len ? ft[t] : -1;
+    }
+  }
+}
+
+template <int LCAP, bool POOLS, class LDS, bool FUZZY, int QC>
+__global__ __launch_bounds__(step_wave_threads(FUZZY)) void step_wave_kernel(IndexView ix, StepIn in,
+                                                                             DraftArgs a) {
+  fetch_kernel_arguments<sizeof(IndexView) + sizeof(StepIn) + sizeof(DraftArgs)>();
+  step_wave_body<LCAP, POOLS, LDS, FUZZY, QC>(ix, in, a, NoTail{});
+}
+
+// One step of the accept-driven loop in one launch: a step of up to L + 1 tokens per path
+// (general instantiation, exact matching), then the tail that prepares the next step.
+template <int LCAP, int QC>
+__global__ __launch_bounds__(step_wave_threads(false)) void step_loop_kernel(IndexView ix, StepIn in,
+                                                                             DraftArgs a,
+                                                                             LoopTail tail) {
+  step_wave_body<LCAP, true, LdsWave, false, QC>(ix, in, a, tail);
 }
 
 __global__ __launch_bounds__(256) void accept_kernel(int64_t rows, int32_t L,

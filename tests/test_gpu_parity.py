@@ -524,7 +524,8 @@ def test_pool_modes_small_and_degenerate_cases(oracle, pool_mode):
 
 
 # ---------------------------------------------------------------- the propose / verify / accept loop
-def _accept_loop_case(oracle, w, n_steps, flags, eps=0, pool_mode=0, use_probs=True, warm=None):
+def _accept_loop_case(oracle, w, n_steps, flags, eps=0, pool_mode=0, use_probs=True, warm=None,
+                      min_scratch=False):
     tokens, probs = synth.make_paths(w)
     pr = probs if use_probs else None
     dev = torch.device("cuda:0")
@@ -538,9 +539,10 @@ def _accept_loop_case(oracle, w, n_steps, flags, eps=0, pool_mode=0, use_probs=T
                   None if pr is None else torch.from_numpy(np.ascontiguousarray(pr[:, :, :n0])).to(dev),
                   torch.from_numpy(lens0).to(dev), n0)
     got = ix.accept_loop(n_steps, torch.from_numpy(tokens).to(dev),
-                         None if pr is None else torch.from_numpy(pr).to(dev), k, L)
+                         None if pr is None else torch.from_numpy(pr).to(dev), k, L,
+                         min_scratch=min_scratch)
     want = oracle.accept_loop(tokens, pr, lens0, k, L, n_steps, eps=eps, pool_mode=pool_mode)
-    what = "%s flags=%d eps=%d pool=%d" % (w.name, flags, eps, pool_mode)
+    what = "%s flags=%d eps=%d pool=%d min_scratch=%d" % (w.name, flags, eps, pool_mode, min_scratch)
     assert np.array_equal(got["path_len"].cpu().numpy(), want["path_len"]), what
     assert np.array_equal(got["length"].cpu().numpy(), want["draft_len"]), what
     assert np.array_equal(got["tokens"].cpu().numpy(), want["draft"]), what
@@ -556,6 +558,15 @@ def test_accept_loop_diverging_path_lengths(oracle):
         assert want["accept_len"].sum() > 0 and want["path_len"][-1].max() > want["path_len"][-1].min()
         _accept_loop_case(oracle, c1, 120, flags, use_probs=False,
                           warm=np.array([[40, 3, 0, 17]]))
+    # with the minimum of scratch memory the index matcher takes two launches per step
+    _accept_loop_case(oracle, c1, 200, INDEX, min_scratch=True)
+    _accept_loop_case(oracle, c1, 120, INDEX, use_probs=False, warm=np.array([[40, 3, 0, 17]]), min_scratch=True)
+    # longer drafts (the loop's kernels for up to 16 and up to 32 draft tokens), more paths than the
+    # staged step holds (N * (L + 1) > 1024), a query of 4
+    c3 = synth.WORKLOADS["C3"]
+    _accept_loop_case(oracle, synth.scaled(c3, max_len=300), 80, INDEX)
+    _accept_loop_case(oracle, synth.scaled(c2, max_len=400, draft_len=16), 100, INDEX)
+    _accept_loop_case(oracle, synth.scaled(c2, n_paths=64, max_len=200, draft_len=32), 60, INDEX)
     _accept_loop_case(oracle, c1, 200, SCAN, eps=1)
     _accept_loop_case(oracle, c1, 200, INDEX, pool_mode=binding.POOL_TREE)
     _accept_loop_case(oracle, c1, 200, SCAN, eps=1, pool_mode=binding.POOL_LIST)
