@@ -11,11 +11,13 @@
 // reductions.  The step is latency-bound (a chain of a few dependent memory
 // round trips per path, then the serial work of one wave), so the design
 // minimises round trips, barriers and instruction count:
-//   * one launch per decode step (append + draft + accept fused),
+//   * one launch per decode step (append + draft + accept fused), also for
+//     steps that append several tokens per path and for the accept-driven
+//     loop (whose next input the step's own tail works out),
 //   * per (problem, path) one wave64 that drafts and one that appends: no
 //     workgroup barriers on the hot path,
 //   * matches come from an incrementally updated n-gram hash index,
-//   * the DAG of a row with up to 64 matches lives in the lanes of the wave
+//   * the DAG of a row with up to 128 matches lives in the lanes of the wave
 //     (sums by lane exchanges, ballots and DPP reductions); LDS tables take
 //     the rows with more.
 //
