@@ -314,6 +314,17 @@ __device__ __forceinline__ void step_wave_body(const IndexView& ix, const StepIn
   int32_t M = FUZZY ? wave_front_end_fuzzy<LCAP>(s, c, ix, p, a.k, L, wi, tickets, ticket_used)
                     : wave_front_end<LCAP, QC, !SPLIT, POOLS>(s, c, ix, p, a.k, L, wi, ticket, ticket_used);
   block_sync<kWave>();
+  // the loop's tail needs the path's future from its new end on (lane x: x tokens further):
+  // requested here, so that the load travels during the walk
+  int32_t future_a = 0, future_b = 0;
+  float future_p = 0.0f;
+  if constexpr (std::is_same<TAIL, LoopTail>::value) {
+    const int64_t base = (int64_t)row * tail.max_len;
+    const int32_t xa = c.len_i + c.tid, xb = xa + kWave;
+    future_a = tail.future_tok[base + (xa < tail.max_len ? xa : 0)];
+    future_b = tail.future_tok[base + (xb < tail.max_len ? xb : 0)];
+    if (tail.future_prob) future_p = tail.future_prob[base + (xa < tail.max_len ? xa : 0)];
+  }
   if (POOLS && (ix.options & 2)) {
     // query back-off: no match, so the query loses its oldest token and the histories are
     // searched again (position by position: the index holds grams of max_query_len tokens only)
@@ -390,21 +401,23 @@ __device__ __forceinline__ void step_wave_body(const IndexView& ix, const StepIn
     const int32_t room = tail.max_len - len;
     grow = grow < room ? grow : room;
     const int64_t r = row;
-    const int32_t* ft = tail.future_tok + r * tail.max_len;
+    static_assert(CSD_MAX_DRAFT_LEN + 1 <= kWave && 2 * CSD_MAX_DRAFT_LEN < 2 * kWave,
+                  "a lane per step token; the targets lie within two waves' worth of the future");
     if (c.tid == 0) {
       tail.next_cnt[r] = grow;
       tail.path_len[r] = len;
     }
-    for (int32_t t = c.tid; t < tail.n; t += kWave) {
-      const bool in_path = len + t < tail.max_len;
-      tail.next_tok[r * tail.n + t] = in_path ? ft[len + t] : 0;
-      if (tail.next_prob)
-        tail.next_prob[r * tail.n + t] = in_path ? tail.future_prob[r * tail.max_len + len + t] : 0.0f;
+    if (c.tid < tail.n) {
+      const bool in_path = len + c.tid < tail.max_len;
+      tail.next_tok[r * tail.n + c.tid] = in_path ? future_a : 0;
+      if (tail.next_prob) tail.next_prob[r * tail.n + c.tid] = in_path ? future_p : 0.0f;
     }
-    for (int32_t d = c.tid; d < L; d += kWave) {
-      const int32_t t = len + grow + d;
-      tail.next_targets[r * L + d] = t < tail.max_len ? ft[t] : -1;
-    }
+    // target d of the next draft is the future token grow + d places beyond the new end
+    const int32_t x = grow + c.tid;
+    const int32_t from_a = __shfl(future_a, x & (kWave - 1));
+    const int32_t from_b = __shfl(future_b, x & (kWave - 1));
+    if (c.tid < L)
+      tail.next_targets[r * L + c.tid] = len + x < tail.max_len ? (x < kWave ? from_a : from_b) : -1;
   }
 }
 
