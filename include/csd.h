@@ -26,7 +26,11 @@
  *    in the caller's workspace, which must stay allocated, and untouched by
  *    the caller, until csd_destroy.
  *  - All functions return CSD_OK (0) or a negative csd_error.  On an error
- *    nothing has been enqueued.  A handle is not thread-safe.
+ *    of a single-step call (csd_append, csd_draft, csd_accept, csd_step)
+ *    nothing has been enqueued and the handle is as it was.  The multi-step
+ *    calls (csd_replay, csd_accept_loop) check all arguments before the first
+ *    launch; a CSD_ERR_HIP from a later launch leaves the earlier steps
+ *    enqueued.  A handle is not thread-safe.
  *  - Token ids must lie in [0, vocab).  Ids outside are a caller error: the
  *    append kernel raises CSD_STATUS_TOKEN_RANGE (see csd_status); drafts that
  *    involve such ids are memory-safe but unspecified.
@@ -55,7 +59,8 @@ typedef enum {
   CSD_ERR_CAPACITY = -2,      /* append would exceed max_len / dump buffer too small  */
   CSD_ERR_WORKSPACE = -3,     /* workspace too small or misaligned (needs 256 B)      */
   CSD_ERR_HIP = -4,           /* a HIP runtime call failed                            */
-  CSD_ERR_UNIMPLEMENTED = -5  /* reserved flag bits set                               */
+  CSD_ERR_UNIMPLEMENTED = -5  /* unknown flag bits, or a configuration this build
+                                 does not implement (max_edits > 1, ...)              */
 } csd_error;
 
 /* Limits of this build (csd_create rejects configurations beyond them). */

@@ -247,6 +247,15 @@ void launch_draft(const csd_index* h, const IndexView& v, const StepIn& in, cons
     step_wave_kernel<32, false, LdsWave, false, 8><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
 }
 
+// Host-side bounds on the paths' lengths as they were before a call: put back when the call's
+// launch fails, so that an error leaves the handle as it was.
+struct LengthBounds {
+  csd_index* h;
+  int64_t lo, hi;
+  explicit LengthBounds(csd_index* index);
+  int launched(const char* what);        // CSD_OK, or CSD_ERR_HIP with the bounds restored
+};
+
 // Host-side bookkeeping shared by csd_append and csd_step.
 int note_append(csd_index* h, bool has_counts, int32_t n) {
   if (!has_counts && h->len_lo + n > h->cfg.max_len) return CSD_ERR_CAPACITY;
@@ -254,6 +263,15 @@ int note_append(csd_index* h, bool has_counts, int32_t n) {
   h->len_hi += n;
   if (h->len_hi > h->cfg.max_len) h->len_hi = h->cfg.max_len;
   return CSD_OK;
+}
+
+LengthBounds::LengthBounds(csd_index* index) : h(index), lo(index->len_lo), hi(index->len_hi) {}
+int LengthBounds::launched(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess) return CSD_OK;
+  h->len_lo = lo;
+  h->len_hi = hi;
+  return hip_fail(e, what);
 }
 }  // namespace
 
@@ -346,13 +364,13 @@ int csd_append(csd_index* h, const int32_t* d_tokens, const float* d_probs,
                const int32_t* d_counts, int32_t n, void* stream) {
   if (!h || !d_tokens || n < 0) return CSD_ERR_INVALID_ARG;
   if (n == 0) return CSD_OK;
+  LengthBounds before(h);
   int rc = note_append(h, d_counts != nullptr, n);
   if (rc != CSD_OK) return rc;
   int64_t rows = (int64_t)h->view.P * h->view.N;
   append_kernel<<<(uint32_t)rows, 256, 0, as_stream(stream)>>>(
       view_in_place(h), StepIn{d_tokens, d_probs, d_counts, n});
-  CSD_HIP(hipGetLastError());
-  return CSD_OK;
+  return before.launched("csd_append");
 }
 
 int csd_draft(csd_index* h, int32_t query_len, int32_t draft_len, int32_t* d_draft_tokens,
@@ -389,6 +407,7 @@ int csd_step(csd_index* h, const int32_t* d_tokens, const float* d_probs, const 
   if ((d_targets == nullptr) != (d_accept_len == nullptr)) return CSD_ERR_INVALID_ARG;
   int rc = check_draft_args(h, query_len, draft_len);
   if (rc != CSD_OK) return rc;
+  LengthBounds before(h);
   rc = note_append(h, d_counts != nullptr, n);
   if (rc != CSD_OK) return rc;
   DraftArgs a{query_len, draft_len, h->alpha_q, h->cfg.score_mode, h->cfg.pool_mode,
@@ -401,16 +420,15 @@ int csd_step(csd_index* h, const int32_t* d_tokens, const float* d_probs, const 
     append_kernel<<<(uint32_t)rows, 256, 0, as_stream(stream)>>>(
         view_in_place(h), StepIn{d_tokens, d_probs, d_counts, n});
     launch_draft(h, view_in_place(h), StepIn{nullptr, nullptr, nullptr, 0}, a, as_stream(stream));
-    CSD_HIP(hipGetLastError());
-    return CSD_OK;
+    return before.launched("csd_step");
   }
   IndexView v = h->view;
   v.meta_old = h->meta[h->cur];
   v.meta_new = h->meta[h->cur ^ 1];
   launch_draft(h, v, StepIn{d_tokens, d_probs, d_counts, n}, a, as_stream(stream));
-  CSD_HIP(hipGetLastError());
-  h->cur ^= 1;
-  return CSD_OK;
+  rc = before.launched("csd_step");
+  if (rc == CSD_OK) h->cur ^= 1;
+  return rc;
 }
 
 int csd_replay(csd_index* h, int32_t n_steps, const int32_t* d_tokens, const float* d_probs,
@@ -481,6 +499,7 @@ int csd_accept_loop(csd_index* h, int32_t n_steps, const int32_t* d_future_token
     const uint32_t grid = xcd_grid((int64_t)rows);
     for (int32_t s = 0; s < n_steps; ++s) {
       const int x = s & 1;
+      LengthBounds before(h);
       rc = note_append(h, true, (int32_t)n);
       if (rc != CSD_OK) return rc;
       IndexView v = h->view;
@@ -496,7 +515,8 @@ int csd_accept_loop(csd_index* h, int32_t n_steps, const int32_t* d_future_token
       if (draft_len <= 8) step_loop_kernel<8, 4><<<grid, step_wave_threads(false), 0, st>>>(v, in, a, tail);
       else if (draft_len <= 16) step_loop_kernel<16, 4><<<grid, step_wave_threads(false), 0, st>>>(v, in, a, tail);
       else step_loop_kernel<32, 4><<<grid, step_wave_threads(false), 0, st>>>(v, in, a, tail);
-      CSD_HIP(hipGetLastError());
+      rc = before.launched("csd_accept_loop");
+      if (rc != CSD_OK) return rc;
       h->cur ^= 1;
     }
     return CSD_OK;
@@ -504,6 +524,7 @@ int csd_accept_loop(csd_index* h, int32_t n_steps, const int32_t* d_future_token
   for (int32_t s = 0; s < n_steps; ++s) {
     const int32_t* settled = s > 0 ? d_accept_len + (size_t)(s - 1) * rows : nullptr;
     if (h->indexed) {                   // two launches: step input + append, then the draft
+      LengthBounds before(h);
       rc = note_append(h, true, (int32_t)n);
       if (rc != CSD_OK) return rc;
       advance_append_kernel<<<(uint32_t)rows, 256, 0, st>>>(
@@ -513,7 +534,8 @@ int csd_accept_loop(csd_index* h, int32_t n_steps, const int32_t* d_future_token
                   d_draft_tokens + (size_t)s * rows * L, d_draft_len + (size_t)s * rows,
                   nullptr, nullptr, targets, d_accept_len + (size_t)s * rows};
       launch_draft(h, view_in_place(h), StepIn{nullptr, nullptr, nullptr, 0}, a, st);
-      CSD_HIP(hipGetLastError());
+      rc = before.launched("csd_accept_loop");
+      if (rc != CSD_OK) return rc;
       continue;
     }
     advance_kernel<<<(uint32_t)((rows + 255) / 256), 256, 0, st>>>(
@@ -654,7 +676,7 @@ const char* csd_strerror(int err) {
     case CSD_ERR_CAPACITY: return "capacity exceeded";
     case CSD_ERR_WORKSPACE: return "workspace too small or misaligned";
     case CSD_ERR_HIP: return g_hip_msg;
-    case CSD_ERR_UNIMPLEMENTED: return "reserved flag bits set";
+    case CSD_ERR_UNIMPLEMENTED: return "configuration not implemented in this build";
     default: return "unknown csd error";
   }
 }

@@ -70,6 +70,7 @@ def test_null_and_misaligned_arguments_are_rejected(lib):
                      (lib.csd_append, (None, None, None, None, 1, None)),
                      (lib.csd_draft, (None, 1, 1, None, None, None, None, None)),
                      (lib.csd_accept, (None, None, None, None, 1, None, None)),
+                     (lib.csd_accept_loop, (None, 1, None, None, 1, 1, None, 0, None, None, None, None, None)),
                      (lib.csd_status, (None, None, None)),
                      (lib.csd_dump_matches, (None, 1, None, None, 0, None)),
                      (lib.csd_dump_edges, (None, 1, 1, None, None, None, 0, None))):
@@ -83,7 +84,7 @@ def test_binding_has_no_cpu_fallback():
     pkg = os.path.join(ROOT, "paper_2503_05330_amd")
     for dirpath, _, files in os.walk(pkg):
         for f in files:
-            if f.endswith((".py", ".hip", ".h", ".cpp")):
+            if f.endswith((".py", ".hip", ".h", ".cpp", ".cuh", ".hpp", ".inc")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert not re.search(r"import\s+oracle|from\s+oracle|csd_oracle|oracle[/.]", text), \
                     f + " reaches for the oracle"
