@@ -59,8 +59,10 @@ typedef enum {
   CSD_ERR_CAPACITY = -2,      /* append would exceed max_len / dump buffer too small  */
   CSD_ERR_WORKSPACE = -3,     /* workspace too small or misaligned (needs 256 B)      */
   CSD_ERR_HIP = -4,           /* a HIP runtime call failed                            */
-  CSD_ERR_UNIMPLEMENTED = -5  /* unknown flag bits, or a configuration this build
+  CSD_ERR_UNIMPLEMENTED = -5, /* unknown flag bits, or a configuration this build
                                  does not implement (max_edits > 1, ...)              */
+  CSD_ERR_SCRATCH_LIMIT = -6  /* csd_accept_loop_noalloc: the input needs more scratch
+                                 memory than the library's fixed array holds          */
 } csd_error;
 
 /* Limits of this build (csd_create rejects configurations beyond them). */
@@ -234,6 +236,25 @@ int csd_accept_loop(csd_index* index, int32_t n_steps, const int32_t* d_future_t
                     const float* d_future_probs, int32_t query_len, int32_t draft_len,
                     void* d_scratch, size_t scratch_bytes, int32_t* d_draft_tokens,
                     int32_t* d_draft_len, int32_t* d_accept_len, int32_t* d_path_len, void* stream);
+
+/* csd_accept_loop for callers that cannot allocate device memory or hand over a scratch
+ * buffer: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments (without d_scratch / scratch_bytes), same results, same
+ * launches as csd_accept_loop with twice the minimum of scratch memory; the step
+ * buffers live in a fixed array of CSD_NOALLOC_SCRATCH_BYTES inside the library's device
+ * image (one copy per GPU, held until the process ends).  Calls no hipMalloc / hipFree
+ * nor anything else that allocates.
+ *   Limit: 2 * P*N*(3*draft_len + 3)*4 bytes <= CSD_NOALLOC_SCRATCH_BYTES, else
+ *   CSD_ERR_SCRATCH_LIMIT (nothing enqueued).
+ *   The device current at the call must be the one the index's workspace is on.
+ *   All calls on one GPU share the array: calls that overlap in time on one GPU (two
+ *   streams, two indexes) race; serialise them.  Nothing in the array has to start at
+ *   zero: every word is written by the launch before the one that reads it. */
+#define CSD_NOALLOC_SCRATCH_BYTES (1u << 20)
+int csd_accept_loop_noalloc(csd_index* index, int32_t n_steps, const int32_t* d_future_tokens,
+                            const float* d_future_probs, int32_t query_len, int32_t draft_len,
+                            int32_t* d_draft_tokens, int32_t* d_draft_len, int32_t* d_accept_len,
+                            int32_t* d_path_len, void* stream);
 
 /* Waits for `stream` and copies the sticky CSD_STATUS_* bits to *host_flags. */
 int csd_status(csd_index* index, uint32_t* host_flags, void* stream);

@@ -19,9 +19,11 @@ INCLUDE_SELF, QUERY_BACKOFF = 4, 8      # options OR-ed to a MATCH_* value
 POOL_DAG, POOL_TREE, POOL_LIST = 0, 1, 2
 STATUS_CAPACITY, STATUS_TOKEN_RANGE, STATUS_TABLE_FULL = 1, 2, 4
 OK, ERR_INVALID_ARG, ERR_CAPACITY, ERR_WORKSPACE, ERR_HIP, ERR_UNIMPLEMENTED = 0, -1, -2, -3, -4, -5
+ERR_SCRATCH_LIMIT = -6
+NOALLOC_SCRATCH_BYTES = 1 << 20
 
 EXPORTS = ["csd_workspace_bytes", "csd_create", "csd_destroy", "csd_reset", "csd_append",
-           "csd_draft", "csd_accept", "csd_step", "csd_replay", "csd_accept_loop", "csd_status",
+           "csd_draft", "csd_accept", "csd_step", "csd_replay", "csd_accept_loop", "csd_accept_loop_noalloc", "csd_status",
            "csd_dump_matches",
            "csd_dump_edges", "csd_debug_copy", "csd_strerror"]
 
@@ -65,6 +67,7 @@ def load() -> ctypes.CDLL:
         lib.csd_replay.argtypes = [_vp, i32, _vp, _vp, i32, i32, _vp, _vp, _vp, _vp, _vp, _vp, i32, _vp]
         lib.csd_accept_loop.argtypes = [_vp, i32, _vp, _vp, i32, i32, _vp, ctypes.c_size_t, _vp, _vp, _vp, _vp,
                                         _vp]
+        lib.csd_accept_loop_noalloc.argtypes = [_vp, i32, _vp, _vp, i32, i32, _vp, _vp, _vp, _vp, _vp]
         lib.csd_status.argtypes = [_vp, ctypes.POINTER(ctypes.c_uint32), _vp]
         lib.csd_dump_matches.argtypes = [_vp, i32, _vp, _vp, i64, _vp]
         lib.csd_dump_edges.argtypes = [_vp, i32, i32, _vp, _vp, _vp, i64, _vp]
@@ -259,6 +262,18 @@ class Index:
                                            _ptr(out["path_len"], torch.int32, S * self.rows), _stream()),
                     "csd_accept_loop")
         out["_scratch"] = scratch        # enqueued work still uses it
+        return out
+
+    def accept_loop_noalloc(self, n_steps, future_tokens, future_probs, query_len, draft_len, out):
+        """csd_accept_loop_noalloc: the same loop with the step buffers in the library's fixed
+        device array.  `out` (as returned by accept_loop) must be given: nothing is allocated."""
+        L, S = draft_len, n_steps
+        cells = self.rows * self.cfg.max_len
+        self._check(load().csd_accept_loop_noalloc(
+            self._h, S, _ptr(future_tokens, torch.int32, cells), _ptr(future_probs, torch.float32, cells),
+            query_len, L, _ptr(out["tokens"], torch.int32, S * self.rows * L),
+            _ptr(out["length"], torch.int32, S * self.rows), _ptr(out["accept"], torch.int32, S * self.rows),
+            _ptr(out["path_len"], torch.int32, S * self.rows), _stream()), "csd_accept_loop_noalloc")
         return out
 
     def status(self) -> int:

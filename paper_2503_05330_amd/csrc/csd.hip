@@ -30,6 +30,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "csd.h"
@@ -161,6 +162,12 @@ uint32_t to_alpha_q(float alpha) {
 }
 
 }  // namespace
+
+// Scratch memory of csd_accept_loop_noalloc: one copy per GPU the library runs on, held until
+// the process ends.  In host code the array's name is only a stand-in for the symbol: the
+// device address comes from hipGetSymbolAddress, once per device (scratch_on_this_device).
+constexpr size_t kStaticScratchBytes = CSD_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 struct csd_index {
   csd_config cfg;
@@ -464,10 +471,10 @@ int csd_replay(csd_index* h, int32_t n_steps, const int32_t* d_tokens, const flo
   return CSD_OK;
 }
 
-int csd_accept_loop(csd_index* h, int32_t n_steps, const int32_t* d_future_tokens,
-                    const float* d_future_probs, int32_t query_len, int32_t draft_len,
-                    void* d_scratch, size_t scratch_bytes, int32_t* d_draft_tokens,
-                    int32_t* d_draft_len, int32_t* d_accept_len, int32_t* d_path_len, void* stream) {
+static int accept_loop(csd_index* h, int32_t n_steps, const int32_t* d_future_tokens,
+                       const float* d_future_probs, int32_t query_len, int32_t draft_len,
+                       void* d_scratch, size_t scratch_bytes, int32_t* d_draft_tokens,
+                       int32_t* d_draft_len, int32_t* d_accept_len, int32_t* d_path_len, void* stream) {
   if (!h || n_steps < 0 || !d_future_tokens || !d_scratch || !d_draft_tokens || !d_draft_len ||
       !d_accept_len || !d_path_len)
     return CSD_ERR_INVALID_ARG;
@@ -549,6 +556,53 @@ int csd_accept_loop(csd_index* h, int32_t n_steps, const int32_t* d_future_token
     if (rc != CSD_OK) return rc;
   }
   return CSD_OK;
+}
+
+int csd_accept_loop(csd_index* h, int32_t n_steps, const int32_t* d_future_tokens,
+                    const float* d_future_probs, int32_t query_len, int32_t draft_len,
+                    void* d_scratch, size_t scratch_bytes, int32_t* d_draft_tokens,
+                    int32_t* d_draft_len, int32_t* d_accept_len, int32_t* d_path_len, void* stream) {
+  return accept_loop(h, n_steps, d_future_tokens, d_future_probs, query_len, draft_len, d_scratch,
+                     scratch_bytes, d_draft_tokens, d_draft_len, d_accept_len, d_path_len, stream);
+}
+
+// Device address of `scratch` on the current device, looked up once per device (each GPU
+// holds its own copy of the array at its own address).
+static int scratch_on_this_device(void** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex lock;
+  static void* known[kMaxDevices] = {};
+  int dev = -1;
+  CSD_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return CSD_ERR_INVALID_ARG;
+  std::lock_guard<std::mutex> guard(lock);
+  if (!known[dev]) {
+    void* ptr = nullptr;
+    CSD_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return CSD_ERR_HIP;
+    known[dev] = ptr;
+  }
+  *out = known[dev];
+  return CSD_OK;
+}
+
+int csd_accept_loop_noalloc(csd_index* h, int32_t n_steps, const int32_t* d_future_tokens,
+                            const float* d_future_probs, int32_t query_len, int32_t draft_len,
+                            int32_t* d_draft_tokens, int32_t* d_draft_len, int32_t* d_accept_len,
+                            int32_t* d_path_len, void* stream) {
+  if (!h) return CSD_ERR_INVALID_ARG;
+  int rc = check_draft_args(h, query_len, draft_len);
+  if (rc != CSD_OK) return rc;
+  // two sets of step buffers (one launch per step); every word of a set is written by the
+  // launch before the one that reads it, so nothing of an earlier call's contents is seen
+  const size_t rows = (size_t)h->view.P * h->view.N;
+  const size_t need = 2 * rows * (3 * (size_t)draft_len + 3) * 4;
+  if (need > kStaticScratchBytes) return CSD_ERR_SCRATCH_LIMIT;
+  void* ptr = nullptr;
+  rc = scratch_on_this_device(&ptr);
+  if (rc != CSD_OK) return rc;
+  return accept_loop(h, n_steps, d_future_tokens, d_future_probs, query_len, draft_len, ptr, need,
+                     d_draft_tokens, d_draft_len, d_accept_len, d_path_len, stream);
 }
 
 int csd_status(csd_index* h, uint32_t* host_flags, void* stream) {
@@ -677,6 +731,7 @@ const char* csd_strerror(int err) {
     case CSD_ERR_WORKSPACE: return "workspace too small or misaligned";
     case CSD_ERR_HIP: return g_hip_msg;
     case CSD_ERR_UNIMPLEMENTED: return "configuration not implemented in this build";
+    case CSD_ERR_SCRATCH_LIMIT: return "input exceeds the fixed scratch array of the non-allocating entry point";
     default: return "unknown csd error";
   }
 }

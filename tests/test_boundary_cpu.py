@@ -71,11 +71,12 @@ def test_null_and_misaligned_arguments_are_rejected(lib):
                      (lib.csd_draft, (None, 1, 1, None, None, None, None, None)),
                      (lib.csd_accept, (None, None, None, None, 1, None, None)),
                      (lib.csd_accept_loop, (None, 1, None, None, 1, 1, None, 0, None, None, None, None, None)),
+                     (lib.csd_accept_loop_noalloc, (None, 1, None, None, 1, 1, None, None, None, None, None)),
                      (lib.csd_status, (None, None, None)),
                      (lib.csd_dump_matches, (None, 1, None, None, 0, None)),
                      (lib.csd_dump_edges, (None, 1, 1, None, None, None, 0, None))):
         assert fn(*args) == b.ERR_INVALID_ARG
-    for code in (0, -1, -2, -3, -4, -5, -99):
+    for code in (0, -1, -2, -3, -4, -5, -6, -99):
         assert isinstance(b.strerror(code), str) and b.strerror(code)
 
 
