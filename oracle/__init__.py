@@ -15,7 +15,8 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "csd_oracle.cpp")
-_LIB = os.path.join(_HERE, "libcsd_oracle.so")
+_SANITIZE = os.environ.get("CSD_ORACLE_SANITIZE") == "1"
+_LIB = os.path.join(_HERE, "libcsd_oracle_san.so" if _SANITIZE else "libcsd_oracle.so")
 _lib = None
 
 _i32p = ctypes.POINTER(ctypes.c_int32)
@@ -23,10 +24,31 @@ _u64p = ctypes.POINTER(ctypes.c_uint64)
 _f32p = ctypes.POINTER(ctypes.c_float)
 
 
+def _extra_flags():
+    """CSD_ORACLE_SANITIZE=1 builds the oracle (into a library of its own) with the address and
+    undefined-behaviour sanitizers: host code only.  A Python process can load that library
+    only with libasan preloaded; tests/test_oracle_pins.py runs the pins that way."""
+    if _SANITIZE:
+        return ["-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+                "-fno-omit-frame-pointer"]
+    return []
+
+
+def host_threads() -> int:
+    """Threads the threaded oracle entry point uses by default: the cores this process may run
+    on, at most 16 (a GPU machine's CPU share)."""
+    try:
+        n = len(os.sched_getaffinity(0))
+    except AttributeError:
+        n = os.cpu_count() or 1
+    return max(1, min(n, 16))
+
+
 def build(force: bool = False) -> str:
     """Compile the oracle with g++ (plain -O2, no GPU toolchain)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(["g++", "-O2", "-std=c++14", "-shared", "-fPIC", "-o", _LIB, _SRC])
+        subprocess.check_call(["g++", "-O2", "-std=c++14", "-pthread", *_extra_flags(), "-shared", "-fPIC",
+                               "-o", _LIB, _SRC])
     return _LIB
 
 
@@ -60,6 +82,11 @@ def _load():
                                          ctypes.c_int32, ctypes.c_uint32, ctypes.c_int32, ctypes.c_int32,
                                          ctypes.c_int32, _i32p, _i32p, _f32p, _f32p,
                                          _i32p, _i32p]
+        lib.oracle_draft_many.restype = None
+        lib.oracle_draft_many.argtypes = [_i32p, _f32p, _i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                          ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                          ctypes.c_uint32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                          ctypes.c_int32, _i32p, _i32p, _f32p, _f32p, _i32p, _i32p]
         lib.oracle_accept_loop.restype = None
         lib.oracle_accept_loop.argtypes = [_i32p, _f32p, _i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                            ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_uint32,
@@ -176,6 +203,37 @@ def draft_all(tok, prob, length, k, L, alpha=1.0, score_mode=0, target=None, eps
     lib.oracle_draft_all(tp, pp, lp, P, N, max_len, k, eps, L, lib.oracle_alpha_q(float(alpha)),
                          score_mode, pool_mode, _extras(include_self, backoff), d.ctypes.data_as(_i32p),
                          dl.ctypes.data_as(_i32p), ts.ctypes.data_as(_f32p), ps.ctypes.data_as(_f32p), tgp, alp)
+    return dict(draft=d, draft_len=dl, token_scores=ts, path_scores=ps, accept_len=al)
+
+
+def draft_many(tok, prob, lengths, k, L, alpha=1.0, score_mode=0, targets=None, eps=0, pool_mode=0,
+               include_self=False, backoff=False, threads=None):
+    """draft_all for S independent history states of one path set, on `threads` host threads
+    (default: host_threads()).  tok [P][N][max_len], lengths [S][P][N], targets [S][P][N][L] or
+    None.  Returns the dict of draft_all with a leading S axis on every array."""
+    tok, tp = _i32(tok)
+    prob, pp = _f32(prob)
+    lengths, lp = _i32(lengths)
+    P, N, max_len = tok.shape
+    S = lengths.shape[0]
+    assert lengths.shape == (S, P, N)
+    d = np.empty((S, P, N, L), dtype=np.int32)
+    dl = np.empty((S, P, N), dtype=np.int32)
+    ts = np.empty((S, P, N, L), dtype=np.float32)
+    ps = np.empty((S, P, N), dtype=np.float32)
+    lib = _load()
+    if targets is not None:
+        targets, tgp = _i32(targets)
+        assert targets.shape == (S, P, N, L)
+        al = np.empty((S, P, N), dtype=np.int32)
+        alp = al.ctypes.data_as(_i32p)
+    else:
+        tgp, al, alp = None, None, None
+    n_threads = host_threads() if threads is None else int(threads)
+    lib.oracle_draft_many(tp, pp, lp, S, P, N, max_len, k, eps, L, lib.oracle_alpha_q(float(alpha)),
+                          score_mode, pool_mode, _extras(include_self, backoff), n_threads,
+                          d.ctypes.data_as(_i32p), dl.ctypes.data_as(_i32p), ts.ctypes.data_as(_f32p),
+                          ps.ctypes.data_as(_f32p), tgp, alp)
     return dict(draft=d, draft_len=dl, token_scores=ts, path_scores=ps, accept_len=al)
 
 

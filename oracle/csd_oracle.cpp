@@ -85,11 +85,19 @@
  *      token, until its match set is non-empty; the draft is built from the
  *      first non-empty set.  No length with a match: empty draft.
  *
- * Build: g++ -O2 -shared -fPIC -o libcsd_oracle.so csd_oracle.cpp
+ * Threads.  oracle_draft_many runs the drafts of many independent
+ * (history state, problem, path) rows on several host threads; each row is
+ * one call of oracle_draft, whose arithmetic is untouched (the rows share
+ * nothing but read-only inputs, so the result does not depend on the number
+ * of threads: a CPU test compares it with the serial loop bit for bit).
+ *
+ * Build: g++ -O2 -pthread -shared -fPIC -o libcsd_oracle.so csd_oracle.cpp
  */
+#include <atomic>
 #include <cmath>
 #include <cstdint>
 #include <map>
+#include <thread>
 #include <utility>
 #include <vector>
 
@@ -252,7 +260,9 @@ int64_t oracle_edges(const int32_t* tok, const float* prob, const int32_t* len, 
   Paths Y{tok, prob, len, N, max_len};
   int32_t q;
   std::vector<Candidate> pool = candidate_pool(Y, i, k, eps, (extras & 1) != 0, &q);
-  std::vector<EdgeTable> edges = build_dag(Y, pool, L, Y.token(i, Y.len[i] - 1));
+  /* R9: the root is the last query token; an empty path has no query, no pool and no edges */
+  int32_t root = Y.len[i] > 0 ? Y.token(i, Y.len[i] - 1) : 0;
+  std::vector<EdgeTable> edges = build_dag(Y, pool, L, root);
   int64_t n = 0;
   for (int32_t d = 1; d <= L; ++d) {
     for (const auto& kv : edges[d - 1]) {
@@ -422,6 +432,42 @@ void oracle_draft_all(const int32_t* tok, const float* prob, const int32_t* len,
         accept_len[r] = oracle_accept(draft + r * L, draft_len[r], target + r * L);
     }
   }
+}
+
+/* The same over S independent history states of one path set (the states of a
+ * replay: len [S][P][N] says how much of each path exists in state s), on
+ * n_threads host threads.  Rows (s, p, i) are handed out one at a time; each
+ * is one oracle_draft (+ oracle_accept) call, exactly as in oracle_draft_all.
+ * Outputs are [S][P][N][...]; target [S][P][N][L] and accept_len may be null.
+ * n_threads <= 1: a plain serial loop on the calling thread. */
+void oracle_draft_many(const int32_t* tok, const float* prob, const int32_t* len, int32_t S, int32_t P,
+                       int32_t N, int32_t max_len, int32_t k, int32_t eps, int32_t L, uint32_t alpha_q,
+                       int32_t score_mode, int32_t pool_mode, int32_t extras, int32_t n_threads,
+                       int32_t* draft, int32_t* draft_len, float* token_scores, float* path_scores,
+                       const int32_t* target, int32_t* accept_len) {
+  const int64_t rows = (int64_t)P * N, items = (int64_t)S * rows;
+  auto one_row = [&](int64_t x) {
+    const int64_t s = x / rows, r = x % rows;
+    const int32_t p = (int32_t)(r / N), i = (int32_t)(r % N);
+    const int32_t* tk = tok + (int64_t)p * N * max_len;
+    const float* pr = prob ? prob + (int64_t)p * N * max_len : nullptr;
+    const int32_t* ln = len + s * rows + (int64_t)p * N;
+    draft_len[x] = oracle_draft(tk, pr, ln, N, max_len, i, k, eps, L, alpha_q, score_mode, pool_mode,
+                                extras, draft + x * L, token_scores + x * L, path_scores + x);
+    if (target && accept_len) accept_len[x] = oracle_accept(draft + x * L, draft_len[x], target + x * L);
+  };
+  if (n_threads <= 1) {
+    for (int64_t x = 0; x < items; ++x) one_row(x);
+    return;
+  }
+  std::atomic<int64_t> next(0);
+  auto worker = [&]() {
+    for (int64_t x = next.fetch_add(1); x < items; x = next.fetch_add(1)) one_row(x);
+  };
+  std::vector<std::thread> pool;
+  for (int32_t t = 1; t < n_threads; ++t) pool.emplace_back(worker);
+  worker();
+  for (std::thread& t : pool) t.join();
 }
 
 /* The propose / verify / accept loop of speculative decoding (Background

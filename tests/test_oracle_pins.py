@@ -292,6 +292,33 @@ def test_draft_all_matches_single_calls(oracle):
             assert out["accept_len"][p, i] == oracle.accept(d, n, tg[p, i])
 
 
+def test_threaded_batch_equals_the_serial_loop_bit_for_bit(oracle):
+    """oracle.draft_many (rows handed to several host threads) against draft_all called state by
+    state on one thread: same bits for every output, whatever the number of threads, under
+    exact and one-edit matching and every pool."""
+    w = synth.scaled(synth.WORKLOADS["C4"], n_problems=3, n_paths=6, max_len=150)
+    tokens, probs = synth.make_paths(w)
+    rng = np.random.default_rng(11)
+    S, L = 9, w.draft_len
+    lens = rng.integers(0, 151, size=(S, 3, 6)).astype(np.int32)
+    lens[0] = 150
+    targets = np.stack([synth.make_noisy_targets(w, tokens, 40 + s, L) for s in range(S)])
+    for eps, pool, extras in ((0, 0, {}), (1, 0, {}), (0, 1, {}), (1, 2, {}),
+                              (0, 0, dict(include_self=True, backoff=True))):
+        serial = [oracle.draft_all(tokens, probs, lens[s], 3, L, 0.75, 1, targets[s], eps=eps,
+                                   pool_mode=pool, **extras) for s in range(S)]
+        for threads in (1, 2, 8, 37):
+            many = oracle.draft_many(tokens, probs, lens, 3, L, 0.75, 1, targets, eps=eps, pool_mode=pool,
+                                     threads=threads, **extras)
+            for key in ("draft", "draft_len", "token_scores", "path_scores", "accept_len"):
+                want = np.stack([x[key] for x in serial])
+                assert many[key].tobytes() == want.tobytes(), (key, eps, pool, threads)
+    assert int(np.stack([x["draft_len"] for x in serial]).max()) > 0
+    none = oracle.draft_many(tokens, None, lens[:2], 3, L, threads=4)
+    assert none["accept_len"] is None and none["draft"].shape == (2, 3, 6, L)
+    assert 1 <= oracle.host_threads() <= 16
+
+
 def test_generator_is_seeded_and_shaped():
     for name, w in synth.WORKLOADS.items():
         if name in ("C4", "C5"):
@@ -592,3 +619,25 @@ def test_options_reach_the_batched_entry_points(oracle):
     for s in range(6):
         step = oracle.draft_all(tokens, probs, run["path_len"][s], 3, 5, 1.0, 0, include_self=True, backoff=True)
         assert step["draft"].tolist() == run["draft"][s].tolist()
+
+
+def test_pins_pass_with_the_oracle_built_under_sanitizers():
+    """The whole pin suite once more in a child process whose oracle is compiled with
+    -fsanitize=address,undefined (host code only): an out-of-bounds read, a use after free or
+    signed overflow anywhere in the oracle aborts the child."""
+    import subprocess
+    import sys
+    if os.environ.get("CSD_ORACLE_SANITIZE") == "1":
+        pytest.skip("already inside the sanitized run")
+    libasan = subprocess.check_output(["g++", "-print-file-name=libasan.so"], text=True).strip()
+    if not os.path.isabs(libasan) or not os.path.exists(libasan):
+        pytest.skip("no libasan in this toolchain")
+    env = dict(os.environ, CSD_ORACLE_SANITIZE="1", ASAN_OPTIONS="detect_leaks=0",
+               UBSAN_OPTIONS="halt_on_error=1:print_stacktrace=1")
+    env["LD_PRELOAD"] = ":".join(x for x in (libasan, os.environ.get("LD_PRELOAD", "")) if x)
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    run = subprocess.run([sys.executable, "-m", "pytest", os.path.abspath(__file__), "-x", "-q", "-p",
+                          "no:cacheprovider"], cwd=root, env=env, capture_output=True, text=True, timeout=1500)
+    tail = (run.stdout + run.stderr)[-3000:]
+    assert run.returncode == 0, tail
+    assert " passed" in run.stdout and "ERROR: AddressSanitizer" not in tail and "runtime error" not in tail
