@@ -16,29 +16,43 @@ def oracle_step(oracle, tokens, probs, lens_t, k, L, alpha, mode, target=None):
     return oracle.draft_all(tokens, probs, lens_t, k, L, alpha, mode, target)
 
 
-def check_dumps(oracle, ix, tokens, probs, lens_t, k, L):
-    """Match sets and edge tables of every row at the index's current state."""
+def check_dumps(oracle, ix, tokens, probs, lens_t, k, L, eps=0, rows=None):
+    """Match sets and edge tables of every row (or of `rows`) at the index's current state.
+    The edge tables come from the LDS-table builder (build_dag), whatever form of the walk the
+    step kernel would choose for the row."""
     P, N, _ = tokens.shape
     je, moff = ix.dump_matches(k)
     duv, cs, eoff = ix.dump_edges(k, L)
-    for p in range(P):
-        for i in range(N):
-            r = p * N + i
-            want = oracle.matches(tokens[p], lens_t[p], i, k)
-            assert np.array_equal(je[moff[r]:moff[r + 1]], want), "matches row %d" % r
-            wduv, wcs = oracle.edges(tokens[p], None if probs is None else probs[p], lens_t[p], i, k, L)
-            assert np.array_equal(duv[eoff[r]:eoff[r + 1]], wduv), "edge keys row %d" % r
-            assert np.array_equal(cs[eoff[r]:eoff[r + 1]], wcs), "edge weights row %d" % r
+    for r in (range(P * N) if rows is None else rows):
+        p, i = divmod(r, N)
+        want = oracle.matches(tokens[p], lens_t[p], i, k, eps=eps)
+        assert np.array_equal(je[moff[r]:moff[r + 1]], want), "matches row %d" % r
+        wduv, wcs = oracle.edges(tokens[p], None if probs is None else probs[p], lens_t[p], i, k, L, eps=eps)
+        assert np.array_equal(duv[eoff[r]:eoff[r + 1]], wduv), "edge keys row %d" % r
+        assert np.array_equal(cs[eoff[r]:eoff[r + 1]], wcs), "edge weights row %d" % r
 
 
 SCAN, INDEX = binding.MATCH_SCAN, binding.MATCH_INDEX
 ALL_VARIANTS = ((INDEX, "replay"), (INDEX, "calls"), (SCAN, "step"), (SCAN, "replay_unfused"))
 
 
+def oracle_steps(oracle, tokens, probs, steps, k, L, alpha, mode, targets=None, **kw):
+    """The oracle's outputs after steps[x] + 1 tokens per path, for all x, in one threaded call:
+    {step: dict as draft_all returns it}."""
+    P, N, _ = tokens.shape
+    lens = np.empty((len(steps), P, N), dtype=np.int32)
+    lens[:] = (np.asarray(steps, dtype=np.int32) + 1)[:, None, None]
+    tg = None if targets is None else np.ascontiguousarray(targets[list(steps)])
+    many = oracle.draft_many(tokens, probs, lens, k, L, alpha, mode, tg, **kw)
+    return {t: {key: (None if val is None else val[x]) for key, val in many.items()}
+            for x, t in enumerate(steps)}
+
+
 def run_config(oracle, w, use_probs, alpha, mode, check_every=1, dump_at=(), accept=False,
-               variants=ALL_VARIANTS):
+               variants=ALL_VARIANTS, max_edits=0):
     """Replays the workload once per (matcher, call pattern) variant and compares every
-    checked step of every variant with the oracle (computed once per step)."""
+    checked step of every variant with the oracle (computed once, all steps in one threaded
+    call)."""
     tokens, probs = synth.make_paths(w)
     if not use_probs:
         probs = None
@@ -47,18 +61,16 @@ def run_config(oracle, w, use_probs, alpha, mode, check_every=1, dump_at=(), acc
     if accept:
         targets = np.stack([synth.make_noisy_targets(w, tokens, t + 1, w.draft_len) for t in range(T)])
     steps = sorted(set(list(range(0, T, check_every)) + [T - 1]))
-    want = {}
-    for t in steps:
-        lens_t = np.full(tokens.shape[:2], t + 1, dtype=np.int32)
-        want[t] = oracle_step(oracle, tokens, probs, lens_t, w.query_len, w.draft_len, alpha, mode,
-                              targets[t] if accept else None)
+    print("oracle", w.name, len(steps), "steps", flush=True)
+    want = oracle_steps(oracle, tokens, probs, steps, w.query_len, w.draft_len, alpha, mode, targets,
+                        eps=max_edits)
     assert sum(int((x["draft_len"] > 0).sum()) for x in want.values()) > 0
     got = None
     for flags, how in variants:
         print("replay", w.name, "P,N,T", tokens.shape, "probs", use_probs, "alpha", alpha, "mode", mode,
-              "flags", flags, "how", how, flush=True)
+              "flags", flags, "how", how, "max_edits", max_edits, flush=True)
         got = gpu_replay(tokens, probs, w.query_len, w.draft_len, alpha, mode, flags, targets=targets,
-                         how=how)
+                         how=how, max_edits=max_edits)
         assert got["status"] == 0
         for t in steps:
             assert_step_equal(got, want[t], t, "%s flags=%d %s" % (w.name, flags, how))
@@ -68,13 +80,15 @@ def run_config(oracle, w, use_probs, alpha, mode, check_every=1, dump_at=(), acc
             print("dumps", w.name, "flags", flags, "history", t, flush=True)
             dev = torch.device("cuda:0")
             ix = binding.Index(w.n_problems, w.n_paths, T, w.vocab, w.query_len, w.draft_len, alpha,
-                               mode, flags, device=dev)
+                               mode, flags, device=dev, max_edits=max_edits)
             ix.append(torch.from_numpy(np.ascontiguousarray(tokens[:, :, :t])).to(dev),
                       None if probs is None else torch.from_numpy(np.ascontiguousarray(probs[:, :, :t])).to(dev),
                       None, t)
             lens_t = np.full(tokens.shape[:2], t, dtype=np.int32)
-            check_dumps(oracle, ix, tokens, probs, lens_t, w.query_len, w.draft_len)
+            check_dumps(oracle, ix, tokens, probs, lens_t, w.query_len, w.draft_len, eps=max_edits)
             for q in range(1, w.query_len):      # shorter queries at full history: many more matches
+                if max_edits:
+                    break
                 je, moff = ix.dump_matches(q)
                 for p in range(min(w.n_problems, 2)):
                     for i in range(w.n_paths):
@@ -99,6 +113,26 @@ def test_c2_every_step(oracle):
     run_config(oracle, w, False, 1.0, 1, variants=((INDEX, "step"), (SCAN, "calls")))
 
 
+def test_c2_match_sets_and_edge_tables_along_the_replay(oracle):
+    """Match sets (Eq. 3) and edge tables (Eq. 5) of every row after every 64th step of the C2
+    replay, from the index as the replay itself leaves it (not from a freshly filled one), under
+    both matchers."""
+    w = synth.WORKLOADS["C2"]
+    tokens, probs = synth.make_paths(w)
+    T, k, L = w.max_len, w.query_len, w.draft_len
+    dev = torch.device("cuda:0")
+    d_tok = torch.from_numpy(np.ascontiguousarray(tokens.transpose(2, 0, 1))).to(dev)
+    d_pr = torch.from_numpy(np.ascontiguousarray(probs.transpose(2, 0, 1))).to(dev)
+    for flags in (INDEX, SCAN):
+        ix = binding.Index(1, w.n_paths, T, w.vocab, k, L, 1.0, 0, flags, device=dev)
+        for t0 in range(0, T, 64):
+            ix.replay(64, d_tok[t0:t0 + 64], d_pr[t0:t0 + 64], k, L)
+            print("dumps along the replay: flags", flags, "history", t0 + 64, flush=True)
+            lens_t = np.full((1, w.n_paths), t0 + 64, dtype=np.int32)
+            check_dumps(oracle, ix, tokens, probs, lens_t, k, L)
+        assert ix.status() == 0
+
+
 def test_c3_every_step(oracle):
     w = synth.WORKLOADS["C3"]
     run_config(oracle, w, True, 1.0, 0, check_every=1, dump_at=(2048,),
@@ -107,13 +141,13 @@ def test_c3_every_step(oracle):
 
 def test_c4_batched_problems(oracle):
     w = synth.WORKLOADS["C4"]
-    run_config(oracle, w, True, 1.0, 0, check_every=4, dump_at=(1024,),
+    run_config(oracle, w, True, 1.0, 0, check_every=1, dump_at=(1024,),
                variants=((INDEX, "replay"), (SCAN, "replay"), (INDEX, "replay_unfused")))
 
 
 def test_c5_sparse_matches_with_accept(oracle):
     w = synth.WORKLOADS["C5"]
-    got = run_config(oracle, w, True, 1.0, 0, check_every=16, dump_at=(4096,), accept=True,
+    got = run_config(oracle, w, True, 1.0, 0, check_every=1, dump_at=(4096,), accept=True,
                      variants=((INDEX, "replay"), (SCAN, "replay"), (INDEX, "calls")))
     assert got["accept_len"].max() > 0
 
@@ -417,6 +451,77 @@ def test_fuzzy_c3_longer_query_through_the_index(oracle):
     # query of 4 tokens: five gram variants per position, the fifth filed by the general insert
     _fuzzy_replay(oracle, synth.scaled(synth.WORKLOADS["C3"], max_len=512), 16, ((INDEX, "replay"),),
                   dump_at=(200,), edges=False)
+
+
+def _fuzzy_sampled(oracle, w, steps, variants, dump=None):
+    """One-edit replay of a whole workload compared with the (threaded) oracle at the sampled
+    steps; dump = (history length, rows): match sets of those rows at that length."""
+    tokens, probs = synth.make_paths(w)
+    T, k, L = w.max_len, w.query_len, w.draft_len
+    steps = sorted(set(t for t in steps if 0 <= t < T))
+    print("oracle, one edit:", w.name, tokens.shape, len(steps), "steps", flush=True)
+    want = oracle_steps(oracle, tokens, probs, steps, k, L, 1.0, 0, eps=1)
+    assert sum(int((x["draft_len"] > 0).sum()) for x in want.values()) > 0
+    dev = torch.device("cuda:0")
+    for flags, how in variants:
+        print("one-edit replay", w.name, "flags", flags, how, flush=True)
+        got = gpu_replay(tokens, probs, k, L, 1.0, 0, flags, how=how, max_edits=1)
+        assert got["status"] == 0
+        for t in steps:
+            assert_step_equal(got, want[t], t, "one edit %s flags=%d %s" % (w.name, flags, how))
+        if dump is not None:
+            t, rows = dump
+            ix = got["index"]
+            ix.reset()
+            ix.append(torch.from_numpy(np.ascontiguousarray(tokens[:, :, :t])).to(dev),
+                      torch.from_numpy(np.ascontiguousarray(probs[:, :, :t])).to(dev), None, t)
+            lens_t = np.full(tokens.shape[:2], t, dtype=np.int32)
+            je, moff = ix.dump_matches(k, cap=1 << 23)
+            for r in rows:
+                p_, i_ = divmod(r, w.n_paths)
+                assert np.array_equal(je[moff[r]:moff[r + 1]], oracle.matches(tokens[p_], lens_t[p_], i_, k, 1)), \
+                    "one edit %s flags=%d matches of row %d" % (w.name, flags, r)
+        del got
+        torch.cuda.empty_cache()
+
+
+def test_fuzzy_full_size_c3_c4_c5(oracle):
+    """One-edit matching (Eq. 4, the tolerance of the paper's experiments) at the full size of
+    C3 and C5 and on 8 problems of C4: sampled steps up to the full history, under the matcher
+    CSD_MATCH_AUTO picks (the sliced scan: at most 128 rows) and through the variant index."""
+    AUTO = binding.MATCH_AUTO
+    w = synth.WORKLOADS["C3"]
+    T = w.max_len
+    _fuzzy_sampled(oracle, w, list(range(0, 6)) + list(range(127, T, 128)) + [T - 2, T - 1],
+                   ((AUTO, "replay"), (INDEX, "replay")), dump=(700, range(0, w.n_paths, 5)))
+    w = synth.WORKLOADS["C5"]
+    T = w.max_len
+    _fuzzy_sampled(oracle, w, list(range(0, 6)) + list(range(511, T, 512)) + [T - 2, T - 1],
+                   ((AUTO, "replay"), (INDEX, "replay")), dump=(1500, range(0, w.n_paths, 9)))
+    w = synth.scaled(synth.WORKLOADS["C4"], n_problems=8)
+    T = w.max_len
+    _fuzzy_sampled(oracle, w, list(range(0, 5)) + list(range(127, T, 128)) + [T - 1],
+                   ((AUTO, "replay"), (INDEX, "replay")), dump=(400, range(0, 128, 11)))
+
+
+def test_fuzzy_auto_picks_the_variant_index_and_many_rows(oracle):
+    """One-edit matching where CSD_MATCH_AUTO takes the variant index (queries of 4 tokens, more
+    than 128 rows), and launches of 2048 rows under both of AUTO's choices."""
+    AUTO = binding.MATCH_AUTO
+
+    def ws(w, flags):
+        return binding.workspace_bytes(binding.Config(w.n_problems, w.n_paths, w.max_len, w.vocab, w.query_len,
+                                                      w.draft_len, 1.0, 0, flags, 1, 0))
+    w = synth.scaled(synth.WORKLOADS["C3"], n_problems=6, max_len=384, pool=96)       # 192 rows, k = 4
+    assert ws(w, AUTO) == ws(w, INDEX) != ws(w, SCAN)          # AUTO's workspace holds the variant index
+    _fuzzy_sampled(oracle, w, range(0, w.max_len, 8), ((AUTO, "replay"), (AUTO, "calls")),
+                   dump=(200, range(0, 192, 17)))
+    w = synth.scaled(synth.WORKLOADS["C3"], n_problems=128, n_paths=16, max_len=96, pool=24)   # 2048 rows, k = 4
+    assert ws(w, AUTO) == ws(w, INDEX) != ws(w, SCAN)
+    _fuzzy_sampled(oracle, w, range(0, w.max_len, 5), ((AUTO, "replay"),), dump=(96, range(0, 2048, 97)))
+    w = synth.scaled(synth.WORKLOADS["C4"], n_problems=128, max_len=96, pool=24)      # 2048 rows, k = 3: scan
+    assert ws(w, AUTO) == ws(w, SCAN) != ws(w, INDEX)
+    _fuzzy_sampled(oracle, w, range(0, w.max_len, 5), ((AUTO, "replay"),), dump=(96, range(0, 2048, 97)))
 
 
 def test_fuzzy_small_cases(oracle):
