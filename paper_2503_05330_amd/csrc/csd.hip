@@ -148,8 +148,8 @@ Layout make_layout(const csd_config* c) {
   if (!uses_index(c) && rows <= (size_t)kSlicedScanRows && !(c->flags & CSD_QUERY_BACKOFF) &&
       (c->max_edits > 0 || (int64_t)c->n_paths * c->max_len >= 32768)) {
     while (l.n_slices < 8 && rows * (size_t)l.n_slices * 2 <= 256) l.n_slices *= 2;
-    if (l.n_slices > 1)
-      at += align_up(rows * LdsScan::kMatch * sizeof(Match)) + 2 * align_up(rows * sizeof(int32_t));
+    if (l.n_slices > 1)         // per row the match list and a state word
+      at += align_up(rows * LdsScan::kMatch * sizeof(Match)) + align_up(rows * sizeof(u64));
   }
   l.total = at;
   return l;
@@ -215,10 +215,18 @@ void launch_draft(const csd_index* h, const IndexView& v, const StepIn& in, cons
     if (a.L <= 8) step_wave_kernel<8, true, LdsWaveFuzzy, true, CSD_MAX_QUERY_LEN><<<grid, kWave, 0, st>>>(v, in, a);
     else if (a.L <= 16) step_wave_kernel<16, true, LdsWaveFuzzy, true, CSD_MAX_QUERY_LEN><<<grid, kWave, 0, st>>>(v, in, a);
     else step_wave_kernel<32, true, LdsWaveFuzzy, true, CSD_MAX_QUERY_LEN><<<grid, kWave, 0, st>>>(v, in, a);
+  } else if (!h->indexed) {
+    // scan mode; the general kernels (POOLS) take the tree and list pools, own history,
+    // back-off and steps of several tokens
+    const bool general = a.pool_mode != CSD_POOL_DAG || v.options != 0 || in.n > 1;
+    const bool fuzzy = v.eps > 0, q4 = v.kmax <= 4;
+    auto* kernel = general ? (fuzzy ? (q4 ? step_scan_kernel<4, true, true> : step_scan_kernel<8, true, true>)
+                                    : (q4 ? step_scan_kernel<4, true, false> : step_scan_kernel<8, true, false>))
+                           : (fuzzy ? (q4 ? step_scan_kernel<4, false, true> : step_scan_kernel<8, false, true>)
+                                    : (q4 ? step_scan_kernel<4, false, false> : step_scan_kernel<8, false, false>));
+    kernel<<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
   } else if (a.pool_mode != CSD_POOL_DAG || v.options != 0 || in.n > 1) {   // tree and list pools, own history, back-off, steps of several tokens: the general kernels
-    if (!h->indexed && v.eps > 0) step_scan_kernel<1, true, true><<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
-    else if (!h->indexed) step_scan_kernel<1, true, false><<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
-    else if (v.kmax <= 4) {                      // the usual gram lengths: loops unrolled to 4
+    if (v.kmax <= 4) {                           // the usual gram lengths: loops unrolled to 4
       if (a.L <= 8) step_wave_kernel<8, true, LdsWave, false, 4><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
       else if (a.L <= 16) step_wave_kernel<16, true, LdsWave, false, 4><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
       else step_wave_kernel<32, true, LdsWave, false, 4><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
@@ -226,15 +234,7 @@ void launch_draft(const csd_index* h, const IndexView& v, const StepIn& in, cons
     else if (a.L <= 8) step_wave_kernel<8, true, LdsWave, false, CSD_MAX_QUERY_LEN><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
     else if (a.L <= 16) step_wave_kernel<16, true, LdsWave, false, CSD_MAX_QUERY_LEN><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
     else step_wave_kernel<32, true, LdsWave, false, CSD_MAX_QUERY_LEN><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
-  } else if (!h->indexed && a.L <= 8)
-    (v.eps > 0 ? step_scan_kernel<8, false, true> : step_scan_kernel<8, false, false>)
-        <<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
-  else if (!h->indexed && a.L <= 16)
-    (v.eps > 0 ? step_scan_kernel<16, false, true> : step_scan_kernel<16, false, false>)
-        <<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
-  else if (!h->indexed)     // longer drafts: the walk's register-resident fast path is left out
-    (v.eps > 0 ? step_scan_kernel<1, false, true> : step_scan_kernel<1, false, false>)
-        <<<scan_grid, kScanBlock, 0, st>>>(v, in, a, sl);
+  }
   else if (v.kmax <= 4) {                        // the usual gram lengths: loops unrolled to 4
     if (a.L <= 8 && rows >= kSmallLdsRows)       // more rows than fit the chip at once
       step_wave_kernel<8, false, LdsWaveSmall, false, 4><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
@@ -323,13 +323,11 @@ int csd_create(const csd_config* cfg, void* d_workspace, size_t workspace_bytes,
   h->view.gram = h->indexed ? reinterpret_cast<int32_t*>(base + l.gram) : nullptr;
   h->view.bucket_mask = h->indexed ? l.n_buckets - 1 : 0;
   h->gram_words = l.gram_words;
-  h->slices = ScanSlices{l.n_slices, nullptr, nullptr, nullptr};
+  h->slices = ScanSlices{l.n_slices, nullptr, nullptr};
   if (l.n_slices > 1) {
     h->slices.matches = reinterpret_cast<Match*>(base + l.slices);
-    h->slices.count = reinterpret_cast<int32_t*>(base + l.slices +
-                                                 align_up(rows * LdsScan::kMatch * sizeof(Match)));
-    h->slices.ticket = reinterpret_cast<uint32_t*>(
-        reinterpret_cast<char*>(h->slices.count) + align_up(rows * sizeof(int32_t)));
+    h->slices.state = reinterpret_cast<u64*>(base + l.slices +
+                                             align_up(rows * LdsScan::kMatch * sizeof(Match)));
   }
   h->view.P = cfg->n_problems;
   h->view.N = cfg->n_paths;
@@ -722,6 +720,15 @@ int csd_debug_copy(void* d_dst, const void* d_src, size_t bytes, void* stream) {
   CSD_HIP(hipGetLastError());
   return CSD_OK;
 }
+
+#ifdef CSD_STAMPS
+// Timing build only: copies the stamps of the last launches to the host (after a device
+// synchronisation by the caller).
+int csd_read_stamps(unsigned long long* host, size_t count) {
+  CSD_HIP(hipMemcpyFromSymbol(host, HIP_SYMBOL(csd::g_stamps), count * sizeof(unsigned long long)));
+  return CSD_OK;
+}
+#endif
 
 const char* csd_strerror(int err) {
   switch (err) {

@@ -31,6 +31,24 @@ constexpr int kBucketWords = 16;            // one 64-byte line: [count, 15 post
 constexpr int kBucketSlots = kBucketWords - 1;
 constexpr int kTailCap = CSD_MAX_QUERY_LEN + 1;   // most tokens a meta row keeps
 
+// ---------------------------------------------------------------- timing build
+// With -DCSD_STAMPS (never in the shipped library) the first thread of a workgroup writes
+// the constant-rate device clock (10 ns units) at marked places of the step kernels into a
+// device array that a test harness reads back: where a step's time goes, row by row.
+#ifdef CSD_STAMPS
+constexpr int kStampSlots = 32;
+__device__ unsigned long long g_stamps[(1 << 14) * kStampSlots];
+#define CSD_STAMP(unit, n, value)                                                         \
+  do {                                                                                    \
+    if (threadIdx.x == 0 && (unit) < (1 << 14))                                           \
+      csd::g_stamps[(unit) * csd::kStampSlots + (n)] = (value);                           \
+  } while (0)
+#define CSD_CLOCK() ((unsigned long long)wall_clock64())
+#else
+#define CSD_STAMP(unit, n, value) do { } while (0)
+#define CSD_CLOCK() 0ull
+#endif
+
 // ---------------------------------------------------------------- exact weights
 
 // DAG table key: layer d (6 bits) | predecessor u (29) | token v (29).
@@ -220,6 +238,14 @@ __device__ __forceinline__ int32_t pick(const int32_t (&arr)[SIZE], int32_t idx)
   return r;
 }
 
+// Forces a loaded value to be waited for here and not earlier: everything that
+// uses it depends on this statement.  Lets independent loads issued before it
+// share one memory round trip.
+template <class T>
+__device__ __forceinline__ void consume_here(T& v) {
+  asm volatile("" : "+v"(v));
+}
+
 // BLOCK == kWave: code run by one wave on its own (a wave's LDS accesses execute in order),
 // possibly beside other waves of the workgroup that do something else: no hardware barrier.
 template <int BLOCK>
@@ -253,13 +279,13 @@ struct Match;
 
 // A row's scan shared by several workgroups ("slices"), all on one XCD: every
 // slice adds the matches it finds to the row's list in memory; the slice that
-// finishes last (a ticket counter tells it; nobody waits) goes on with the
+// finishes last (the row's state word tells it; nobody waits) goes on with the
 // whole list.  n == 1: one workgroup per row, nothing of this is used.
 struct ScanSlices {
   int32_t n;                    // slices per row (power of two)
   Match* matches;               // [rows][LdsScan::kMatch]
-  int32_t* count;               // [rows] matches listed so far; the last slice zeroes it again
-  uint32_t* ticket;             // [rows] slices finished, over all launches
+  u64* state;                   // [rows] low half: matches listed so far in this launch (the last
+                                //   slice zeroes it again); high half: slices finished, over all launches
 };
 
 struct StepIn {                 // tokens a step appends; n == 0: none
@@ -303,14 +329,25 @@ struct Paths {
     int64_t off = hist ? (int64_t)cell(j, t) : (int64_t)j * n + (t - old_j);
     return base[off];
   }
-  __device__ __forceinline__ uint32_t prob(int32_t j, int32_t t, int32_t old_j) const {
+  // A probability as loaded, and what it takes to make the quantised value of it: the load
+  // can be issued long before the value is needed (prob_value waits for it, prob_load does not).
+  struct ProbWord {
+    uint32_t word;
+    bool hist, given;
+  };
+  __device__ __forceinline__ ProbWord prob_load(int32_t j, int32_t t, int32_t old_j) const {
     bool hist = t < old_j;
     bool given = !hist && sp != nullptr;
     const uint32_t* base = given ? reinterpret_cast<const uint32_t*>(sp) : pq;
     int64_t off = hist ? (int64_t)cell(j, t) : (given ? (int64_t)j * n + (t - old_j) : 0);
-    uint32_t word = base[off];
-    if (hist) return word;
-    return given ? quantize_prob(__uint_as_float(word)) : 65536u;
+    return ProbWord{base[off], hist, given};
+  }
+  static __device__ __forceinline__ uint32_t prob_value(ProbWord w) {
+    if (w.hist) return w.word;
+    return w.given ? quantize_prob(__uint_as_float(w.word)) : 65536u;
+  }
+  __device__ __forceinline__ uint32_t prob(int32_t j, int32_t t, int32_t old_j) const {
+    return prob_value(prob_load(j, t, old_j));
   }
   __device__ __forceinline__ int32_t pos(int32_t j, int32_t e) const { return (j << eshift) | e; }
   __device__ __forceinline__ int32_t pos_path(int32_t pos) const { return pos >> eshift; }
@@ -375,6 +412,9 @@ struct Ctx {                    // one (problem, query path)
   int32_t q;                    // effective query length min(k, len_i)
   int32_t Q[CSD_MAX_QUERY_LEN]; // Q[a] = a-th token from the end of path i
   int tid;
+#ifdef CSD_STAMPS
+  int32_t unit = 0;             // timing build: where this workgroup's stamps go
+#endif
 };
 
 struct DraftArgs {

@@ -9,6 +9,8 @@
 //           holds its edges (d,u,v) -> (count, probability sum) and its nodes
 //           (d,*,v) -> in-weight; every edge slot links to its target node, so
 //           the walk can fetch all ranks before its serial part starts;
+//   tier 1b a thread per match (up to a workgroup's worth), layer by layer: only the
+//           successors of the current node are tabulated (walk_wide);
 //   tier 2  bounded memory for any input: one layer at a time, and within a
 //           layer one class of tokens (by hash residue) at a time.
 #pragma once
@@ -476,16 +478,36 @@ __device__ __forceinline__ Cand scan_successors(const LDS& s, Region r, int d, i
   return best;
 }
 
-// Tier 1b, for M <= BLOCK matches whose L layers do not fit the table together
-// (a fuzzy query: many matches with unrelated continuations).  Thread m owns
-// match m.  The layers are built and walked one at a time in a single region —
-// a layer holds at most 2M keys, which a table of 4 * BLOCK slots takes at half
-// load — and the tokens of layer d + 1 are in flight while layer d is built
-// and searched.  Same result as tier 1: all sums are exact.
+// Tier 1b, for up to BLOCK matches with one thread per match and no per-layer table
+// of all instances: a layer only needs the weights of the successors of the current
+// node, and those are few.  Per layer, (A) the candidates — matches whose previous token
+// is the current node — enter their token in a hash set (a key carries the layer number,
+// so the set is never cleared: entries of earlier layers count as free slots); (B) every
+// match that reaches the layer looks its token up there and, if it is a successor, adds
+// its (1, p) to the successor's cell (score_mode 1: only the candidates do); (C) the
+// thread that entered a successor ranks it and puts it on a short list, which every wave
+// then reads for the heaviest (ties: lowest token).  Same sums as the tables of tier 1, in
+// exact integers: the same draft.  Set, cells and list lie over the (otherwise unused)
+// table.  Waves without a match leave before the layers start (a workgroup barrier waits
+// for the waves that are still running only), so a row with few matches pays for few waves.
+// Nothing after this function may synchronise the workgroup.
+// (Measured against two other forms with identical results: every instance of a layer added
+// to a set of all the layer's keys, with two barriers per layer instead of three, was 4 %
+// slower on the one-edit step; the ranks of all instances of all layers tabulated before the
+// walk, which then needs one argmax and one barrier per layer, 20 % slower: unrolled over the
+// layers its code is long, and code that runs once per launch is fetched cold.)
 template <int BLOCK, class LDS>
-__device__ __forceinline__ void walk_layers(LDS& s, const Ctx& c, int32_t M, int32_t L,
-                                            uint32_t alpha_q, int score_mode, DraftOut& o) {
-  static_assert(LDS::kTable >= 4 * BLOCK, "a layer of BLOCK matches must fit at half load");
+__device__ __forceinline__ void walk_wide(LDS& s, const Ctx& c, int32_t M, int32_t L,
+                                          uint32_t alpha_q, int score_mode, DraftOut& o) {
+  constexpr uint32_t kSet = 2 * BLOCK;                 // at most BLOCK distinct successors: half load
+  static_assert(2 * kSet * sizeof(u64) + 2 * BLOCK * sizeof(Cand) <= sizeof(s.table),
+                "set, cells and the two successor lists fit the table");
+  u64* keys = reinterpret_cast<u64*>(s.table);         // (layer << 32) | token, or kEmpty
+  u64* cell = keys + kSet;                             // (count, probability sum) of the key's token
+  Cand* list = reinterpret_cast<Cand*>(cell + kSet);   // [2][BLOCK] successors of a layer, ranked
+  int32_t* listed = s.chosen;                          // [2] how many (the tree pool's array is free here)
+  for (uint32_t h = c.tid; h < kSet; h += BLOCK) keys[h] = kEmpty;
+  if (c.tid < 2) listed[c.tid] = 0;
   int32_t rem = 0, j = 0, e = 0, old_j = 1;
   if (c.tid < M) {
     Match m = s.match[c.tid];
@@ -494,31 +516,97 @@ __device__ __forceinline__ void walk_layers(LDS& s, const Ctx& c, int32_t M, int
     e = c.y.pos_index(m.pos);
     old_j = e + (int32_t)m.rel_old;                   // exact wherever it decides (see layer_instance)
   }
-  uint32_t size = 64;
-  while (size < 4u * (uint32_t)M) size <<= 1;         // <= 4 * BLOCK <= LDS::kTable
-  const Region r{0u, size - 1u};
   int32_t cur = c.Q[0];
   uint32_t u = (uint32_t)c.Q[0];
-  // lanes whose candidate has ended read cell 0 of path 0: every lane loads, nothing branches
-  int32_t v_next = c.y.token(rem >= 1 ? j : 0, rem >= 1 ? e : 0, rem >= 1 ? old_j : 1);
-  uint32_t p_next = c.y.prob(rem >= 1 ? j : 0, rem >= 1 ? e : 0, rem >= 1 ? old_j : 1);
+  // a match's token and probability of layer x are requested two layers ahead of their use;
+  // lanes whose candidate has ended by then read its first cell again: every lane loads,
+  // nothing branches.  Nearly always everything a wave needs is history already: then it comes
+  // from fixed addresses.  (Requesting the whole continuation up front, all loads together,
+  // was slower: sixteen loads per thread before the first layer can start.)
+  const int32_t* tok_at = c.y.tok + c.y.cell(j, e);
+  const uint32_t* pq_at = c.y.pq + c.y.cell(j, e);
+  const bool plain = wave_ballot(c.tid < M && old_j - e < rem) == 0;   // uniform over the wave
+  auto request = [&](int32_t x, int32_t& tok, Paths::ProbWord& prob) {
+    const bool has = x <= rem;
+    if (plain) {
+      tok = tok_at[has ? x - 1 : 0];
+      prob = Paths::ProbWord{pq_at[has ? x - 1 : 0], true, false};
+    } else {
+      tok = c.y.token(has ? j : 0, has ? e + x - 1 : 0, has ? old_j : 1);
+      prob = c.y.prob_load(has ? j : 0, has ? e + x - 1 : 0, has ? old_j : 1);
+    }
+  };
+  int32_t tok_a, tok_b;
+  Paths::ProbWord prob_a, prob_b;
+  request(1, tok_a, prob_a);
+  request(2, tok_b, prob_b);
+  lds_barrier<BLOCK>();                               // the set is empty
+  if (c.tid >= ((M + kWave - 1) & ~(kWave - 1))) return;   // waves without a match
+  const int lane = c.tid & (kWave - 1);
   for (int32_t d = 1; d <= L; ++d) {
-    uint32_t v = (uint32_t)v_next;
-    u64 w = pack_cs(1u, p_next);
-    bool more = d < rem;
-    v_next = c.y.token(more ? j : 0, more ? e + d : 0, more ? old_j : 1);
-    p_next = c.y.prob(more ? j : 0, more ? e + d : 0, more ? old_j : 1);
-    lds_barrier<BLOCK>();                             // readers of the previous layer are done
-    table_clear<BLOCK>(s, size, c.tid);
-    lds_barrier<BLOCK>();
-    if (d <= rem) {
-      table_add(s, r, dag_key(d, kAnyTok, v), w);
-      if (u == (uint32_t)cur) table_add(s, r, dag_key(d, u, v), w);
+    consume_here(tok_a);
+    consume_here(prob_a.word);
+    const uint32_t v = (uint32_t)tok_a;
+    const u64 w = pack_cs(1u, Paths::prob_value(prob_a));
+    tok_a = tok_b;
+    prob_a = prob_b;
+    request(d + 2, tok_b, prob_b);
+    const bool alive = d <= rem;
+    const bool cand = alive && u == (uint32_t)cur;
+    const u64 mine = ((u64)(uint32_t)d << 32) | v;
+    const uint32_t h0 = (v * 0x9E3779B1u) >> 7 & (kSet - 1);
+    const int par = d & 1;
+    // (A) successors of the current node enter the set; the thread that enters one owns it
+    uint32_t slot = h0;
+    bool owner = false;
+    if (cand) {
+      u64 seen = keys[slot];
+      for (uint32_t probe = 0; probe < 2 * kSet; ++probe) {
+        if (seen == mine) break;
+        if ((uint32_t)(seen >> 32) != (uint32_t)d) {   // free: empty, or an earlier layer's
+          const u64 prev = atomicCAS(&keys[slot], seen, mine);
+          if (prev == seen) {
+            owner = true;
+            cell[slot] = 0ull;
+            break;
+          }
+          seen = prev;                                // somebody else took it: look again
+          continue;
+        }
+        slot = (slot + 1) & (kSet - 1);
+        seen = keys[slot];
+      }
     }
     lds_barrier<BLOCK>();
-    Cand best = scan_successors<BLOCK>(s, r, d, cur, alpha_q, score_mode, c.tid, cand_none());
-    best = block_argmax<BLOCK>(s, best, c.tid, d & 1);
-    if (best.v == INT_MAX) break;                     // leaf: no edge leaves cur
+    if (c.tid == 0) listed[par ^ 1] = 0;              // the next layer's list: its last readers are past the barrier
+    // (B) Eq. 5: the instances of this layer whose token is a successor
+    if (cand) {
+      atomicAdd(&cell[slot], w);
+    } else if (alive && score_mode == 0) {
+      uint32_t h = h0;
+      for (uint32_t probe = 0; probe < kSet; ++probe) {
+        const u64 seen = keys[h];
+        if (seen == mine) {
+          atomicAdd(&cell[h], w);
+          break;
+        }
+        if ((uint32_t)(seen >> 32) != (uint32_t)d) break;   // free slot: not a successor
+        h = (h + 1) & (kSet - 1);
+      }
+    }
+    lds_barrier<BLOCK>();
+    // (C) every successor once, ranked by its owner; the heaviest wins, ties to the lowest token
+    if (owner) list[par * BLOCK + atomicAdd(&listed[par], 1)] = Cand{weight_key(cell[slot], alpha_q), (int32_t)v};
+    lds_barrier<BLOCK>();
+    const int32_t n = listed[par];                     // <= BLOCK
+    if (n == 0) break;                                 // leaf: no edge leaves cur
+    Cand best = cand_none();
+    if (n <= 4) {                                      // every lane reads the few entries
+      for (int x = 0; x < n; ++x) best = cand_best(best, list[par * BLOCK + x]);
+    } else {
+      for (int x = lane; x < n; x += kWave) best = cand_best(best, list[par * BLOCK + x]);
+      best = wave_argmax(best);
+    }
     note_choice(o, best, d, c.tid);
     cur = best.v;
     u = v;

@@ -39,14 +39,6 @@ __device__ __forceinline__ int32_t* gram_bucket(int32_t* tbl, GramHash gh, uint3
   return tbl + (int64_t)((gh.h + r * gh.step) & mask) * kBucketWords;
 }
 
-// Forces a loaded value to be waited for here and not earlier: everything that
-// uses it depends on this statement.  Lets independent loads issued before it
-// share one memory round trip.
-template <class T>
-__device__ __forceinline__ void consume_here(T& v) {
-  asm volatile("" : "+v"(v));
-}
-
 // General insert, by one whole wave: reads the fill counts of 64 buckets of
 // the sequence per round trip, starting at bucket r0, and claims a slot in the
 // first one that is not full.  Bounded by the table size; the tables hold more

@@ -16,10 +16,7 @@ __global__ __launch_bounds__(256) void reset_kernel(IndexView ix, int64_t gram_w
   int64_t stride = (int64_t)gridDim.x * 256;
   int64_t rows = (int64_t)ix.P * ix.N;
   if (sl.n > 1)
-    for (int64_t r = t; r < rows; r += stride) {
-      sl.count[r] = 0;
-      sl.ticket[r] = 0u;
-    }
+    for (int64_t r = t; r < rows; r += stride) sl.state[r] = 0ull;
   for (int64_t r = t; r < rows * ix.meta_stride; r += stride) ix.meta_new[r] = 0;
   for (int64_t w = t; w < gram_words; w += stride) ix.gram[w] = (w & (kBucketWords - 1)) ? -1 : 0;
   if (t == 0) *ix.status = 0u;
@@ -106,7 +103,8 @@ __device__ __forceinline__ void fetch_windows(LDS& s, const Ctx& c, int32_t M, i
 // one that finishes last does the rest of the row's work.
 // FUZZY: matching tolerates one edit (compiled apart from the exact kernel: code a launch
 // does not run still costs it time).
-template <int LCAP, bool POOLS, bool FUZZY>
+// QC: compile-time bound (4 or 8) of the query length: the comparison loops are unrolled to it.
+template <int QC, bool POOLS, bool FUZZY>
 __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, StepIn in,
                                                                DraftArgs a, ScanSlices sl) {
   constexpr int BLOCK = kScanBlock;
@@ -123,8 +121,14 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
     if (row >= ix.P * ix.N) row = -1;
   }
   if (row < 0) return;
+  const int32_t unit = row * 8 + slice;                  // (timing build only)
+  CSD_STAMP(unit, 0, CSD_CLOCK());
+  CSD_STAMP(unit, 6, 0ull);
   int32_t p;
   Ctx c = make_ctx(ix, in, row, p);
+#ifdef CSD_STAMPS
+  c.unit = unit;
+#endif
   int32_t st_i = in.n == 1 ? c.y.st[c.i] : 0;           // (first: the head's lengths wait for its load)
   Head me = load_head(c.y, ix.tail_len, c.i);           // length and newest tokens in one read
   const int32_t old_i = me.old_len;
@@ -148,47 +152,58 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
                                         // which nothing in this launch reads, need not have landed
   DraftOut o;
   const int32_t L = a.L;
+  CSD_STAMP(unit, 1, CSD_CLOCK());
   if (c.q > 0) {
     ListSink<LdsScan> sink{&s};
-    match_scan<BLOCK, FUZZY>(s, c, sink, slice, sl.n);
+    match_scan<BLOCK, FUZZY, QC>(s, c, sink, slice, sl.n);
     block_sync<BLOCK>();
     int32_t M = s.n_match;
+    CSD_STAMP(unit, 2, CSD_CLOCK());
+    CSD_STAMP(unit, 8, (unsigned long long)M);
     if (POOLS && (ix.options & 2)) {
       // query back-off (never with slices): no match, so the query loses its oldest token and
       // the scan runs again; every thread sees the same M and q, so the barriers pair up
       while (M == 0 && c.q > 1) {
         block_sync<BLOCK>();            // everybody has read the count before anybody pushes again
         --c.q;
-        match_scan<BLOCK, FUZZY>(s, c, sink);
+        match_scan<BLOCK, FUZZY, QC>(s, c, sink);
         block_sync<BLOCK>();
         M = s.n_match;
       }
     }
     if (sl.n > 1) {
-      // hand this slice's matches to the row's list in memory
+      // hand this slice's matches to the row's list in memory.  One 64-bit word per row
+      // holds the matches listed so far (low half) and the slices finished, over all
+      // launches (high half): a slice reserves its part of the list with one atomic and
+      // signs off with a second one, whose result tells the last slice the row's total
       Match* listed = sl.matches + (int64_t)row * LdsScan::kMatch;
-      if (c.tid == 0) sh_base = atomicAdd(&sl.count[row], M);
+      if (c.tid == 0) sh_base = (int32_t)(uint32_t)atomicAdd(&sl.state[row], (u64)(uint32_t)M);
       block_sync<BLOCK>();
       for (int32_t m = c.tid; m < M && m < LdsScan::kMatch; m += BLOCK)
         if (sh_base + m < LdsScan::kMatch) listed[sh_base + m] = s.match[m];
       block_sync<BLOCK>();              // every wave's stores have left the CU
       if (c.tid == 0) {
         // one wave fences for the workgroup (a device-scope fence writes the L2 back: sixteen
-        // of them in a row cost more than the scan): list entries before ticket, ticket
-        // before the reads below
+        // of them in a row cost more than the scan): list entries before the sign-off, the
+        // sign-off before the reads below
         __threadfence();
-        uint32_t drawn = atomicAdd(&sl.ticket[row], 1u);
-        sh_last = (drawn & (uint32_t)(sl.n - 1)) == (uint32_t)(sl.n - 1);
-        sh_total = sh_last ? atomicExch(&sl.count[row], 0) : 0;   // the next launch starts at 0
+        const u64 seen = atomicAdd(&sl.state[row], 1ull << 32);
+        sh_last = ((uint32_t)(seen >> 32) & (uint32_t)(sl.n - 1)) == (uint32_t)(sl.n - 1);
+        sh_total = (int32_t)(uint32_t)seen;   // every slice has reserved before it signs off
+        // the next launch starts with an empty list (nobody else touches the word any more)
+        if (sh_last) sl.state[row] = ((seen >> 32) + 1ull) << 32;
         __threadfence();
       }
       block_sync<BLOCK>();
+      CSD_STAMP(unit, 3, CSD_CLOCK());
       if (!sh_last) return;             // the last slice goes on with all matches of the row
       M = sh_total;
       for (int32_t m = c.tid; m < M && m < LdsScan::kMatch; m += BLOCK) s.match[m] = listed[m];
       if (c.tid == 0) s.n_match = M;
       block_sync<BLOCK>();
     }
+    CSD_STAMP(unit, 4, CSD_CLOCK());
+    CSD_STAMP(unit, 9, (unsigned long long)M);
     if (POOLS && M > 0 && a.pool_mode != CSD_POOL_DAG) {
       auto each = [&](auto f) {
         if (M <= LdsScan::kMatch) {
@@ -196,7 +211,7 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
         } else {
           auto g = [&](Match found) { f(found, -1); };
           FnSink<decltype(g)> fs{g};
-          match_scan<BLOCK, FUZZY>(s, c, fs);
+          match_scan<BLOCK, FUZZY, QC>(s, c, fs);
         }
       };
       if (a.pool_mode == CSD_POOL_TREE && M <= kWave) {
@@ -210,8 +225,8 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
         walk_list<BLOCK>(s, c, WinInfo{M, 0}, L, a.alpha_q, o, each);
       }
     } else if (M > 0) {
-      // tier 1 when every layer's region is sure to hold its <= 2M keys; else layer by
-      // layer with one thread per match (M <= BLOCK); else streaming
+      // up to a wave's worth of matches: a lane per match; up to a workgroup's worth: a thread
+      // per match; else streaming
       bool done = false;
       if (M <= kWave) {
         // one lane of wave 0 per match, no tables: all threads fetch the continuations into
@@ -222,22 +237,9 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
         fetch_windows<BLOCK>(s, c, M, L, windows);
         if (c.tid < kWave) walk_matches(s, c, M, L, WinInfo{0, M}, windows, a.alpha_q, a.score_mode, o);
         done = true;
-      } else if (2u * (uint32_t)M <= tier1_geometry(M, L, LdsScan::kTable).region) {
-        Tier1 t1 = build_dag<BLOCK>(s, c, M, L, WinInfo{M, 0}, a.alpha_q);
-        done = s.overflow == 0;
-        // every thread helps to score large tables; one wave then walks them without
-        // workgroup barriers (and it is wave 0 that writes the outputs)
-        const bool small = walk_fits_registers<LCAP>(t1, L);
-        if (done && !small) {
-          score_edges<BLOCK>(s, t1.region * (uint32_t)L, a.alpha_q, a.score_mode, c.tid);
-          block_sync<BLOCK>();
-        }
-        if (done && c.tid < kWave) {
-          if (small) walk_dag<kWave, LCAP>(s, c, t1, L, a.alpha_q, a.score_mode, o);
-          else walk_scored<kWave>(s, c, t1, L, o);
-        }
       } else if (M <= BLOCK) {
-        walk_layers<BLOCK>(s, c, M, L, a.alpha_q, a.score_mode, o);
+        // one thread per match, layer by layer
+        walk_wide<BLOCK>(s, c, M, L, a.alpha_q, a.score_mode, o);
         done = true;
       }
       if (!done)
@@ -247,16 +249,18 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
           } else {
             auto g = [&](Match found) { f(found, -1); };
             FnSink<decltype(g)> fs{g};
-            match_scan<BLOCK, FUZZY>(s, c, fs);
+            match_scan<BLOCK, FUZZY, QC>(s, c, fs);
           }
         });
     }
   }
+  CSD_STAMP(unit, 5, CSD_CLOCK());
   write_outputs<BLOCK>(a, row, o, c.tid);
   if (a.targets && c.tid < kWave) {
     int32_t target = c.tid < L ? a.targets[(int64_t)row * L + c.tid] : 0;
     write_accept(a, row, o, target, c.tid);
   }
+  CSD_STAMP(unit, 6, CSD_CLOCK());
 }
 
 // Index mode.  Per (problem, path) one wave64 runs the front end (matches with

@@ -41,13 +41,15 @@ __device__ __forceinline__ void tokens_before(const Ctx& c, int32_t j, int32_t e
 }
 
 // Does the q-gram that ends just before index e >= q of path j equal the query?
+// QK: compile-time bound of the query length (the loops are unrolled to it).
+template <int QK = CSD_MAX_QUERY_LEN>
 __device__ __forceinline__ bool gram_equals_query(const Ctx& c, int32_t j, int32_t e,
                                                   int32_t old_j) {
-  int32_t t[CSD_MAX_QUERY_LEN];
+  int32_t t[QK];
   tokens_before(c, j, e, old_j, c.q, t);
   bool hit = true;
 #pragma unroll
-  for (int a = 0; a < CSD_MAX_QUERY_LEN; ++a) hit = hit && (a >= c.q || t[a] == c.Q[a]);
+  for (int a = 0; a < QK; ++a) hit = hit && (a >= c.q || t[a] == c.Q[a]);
   return hit;
 }
 
@@ -58,9 +60,9 @@ __device__ __forceinline__ bool gram_equals_query(const Ctx& c, int32_t j, int32
 // step further back (the text has an extra token) or one step closer (the text
 // lacks a token).
 // t[a] = the a-th token before e for a < min(q + 1, e), else 0.
-__device__ __forceinline__ bool near_query(const Ctx& c, int32_t e,
-                                           const int32_t (&t)[CSD_MAX_QUERY_LEN + 1]) {
-  constexpr int K = CSD_MAX_QUERY_LEN;
+// K: compile-time bound of the query length (the loops are unrolled to it).
+template <int K = CSD_MAX_QUERY_LEN>
+__device__ __forceinline__ bool near_query(const Ctx& c, int32_t e, const int32_t (&t)[K + 1]) {
   const int32_t q = c.q;
   // pre[p]: t[a] == Q[a] for all a < p.  same/back/fwd[p]: the agreement of the older part
   // a > p (same, fwd) or a >= p (back) at shift 0 / +1 / -1, scanned from the oldest token.
@@ -90,10 +92,11 @@ __device__ __forceinline__ bool near_query(const Ctx& c, int32_t e,
   return hit;
 }
 
+template <int QK = CSD_MAX_QUERY_LEN>
 __device__ __forceinline__ bool gram_near_query(const Ctx& c, int32_t j, int32_t e, int32_t old_j) {
-  int32_t t[CSD_MAX_QUERY_LEN + 1];
+  int32_t t[QK + 1];
   tokens_before(c, j, e, old_j, c.q + 1, t);
-  return near_query(c, e, t);
+  return near_query<QK>(c, e, t);
 }
 
 template <int QC>
@@ -203,14 +206,17 @@ __device__ __forceinline__ bool may_match(const Ctx& c, const int32_t (&t)[kFilt
 // pushed in no particular order; every wave runs its own trip counts (push() is
 // a wave-level operation).  A row's scan can be shared by n_slices workgroups:
 // this one, number `slice`, takes every n_slices-th share of the spans.
-template <int BLOCK, bool FUZZY, class LDS, class Sink>
+// QK: compile-time bound of the query length.
+template <int BLOCK, bool FUZZY, int QK = CSD_MAX_QUERY_LEN, class LDS, class Sink>
 __device__ __forceinline__ void match_scan(const LDS& s, const Ctx& c, Sink& sink, int32_t slice = 0,
                                            int32_t n_slices = 1) {
   const int32_t n_waves = (BLOCK / kWave) * n_slices;       // waves that share the row
   constexpr int kPerLane = 4;                              // consecutive positions of a lane
   constexpr int kSpan = kWave * kPerLane;                  // positions of a span
   constexpr int kSpans = 4;                                // spans in flight: 16 candidate bits
-  const int lane = c.tid & 63, wave = slice * (BLOCK / kWave) + (c.tid >> 6);
+  // (consecutive spans go to different slices: a row with fewer spans than waves still keeps
+  // all its workgroups busy)
+  const int lane = c.tid & 63, wave = (c.tid >> 6) * n_slices + slice;
   const int32_t first_e = FUZZY ? (c.q > 1 ? c.q - 1 : 0) : c.q;   // shortest substring that can match
   const int32_t spans_per_path = (c.y.max_len + kSpan - 1) / kSpan;
   const int32_t spans = c.y.N * spans_per_path;            // < 2^24
@@ -231,8 +237,13 @@ __device__ __forceinline__ void match_scan(const LDS& s, const Ctx& c, Sink& sin
 #pragma unroll
     for (int u = 0; u < kSpans; ++u) {
       int32_t g = g0 + u * n_waves, j, e0, old_j = 0, new_j = 0;
+      if (g >= spans) {                                    // uniform over the wave: no such span
+#pragma unroll
+        for (int x = 0; x < 2 * kFilterTokens; ++x) w[u][x] = 0;
+        continue;
+      }
       locate(g, j, e0);
-      bool on = g < spans && j != c.skip;                  // uniform over the wave
+      bool on = j != c.skip;                               // uniform over the wave
       if (on) lens_of(s, c.y, j, old_j, new_j);
       // the lane that starts a path has no three tokens before its positions: it reads the
       // path's first six instead, which serve its fourth position and pre-filter the others
@@ -257,6 +268,7 @@ __device__ __forceinline__ void match_scan(const LDS& s, const Ctx& c, Sink& sin
     }
 #pragma unroll
     for (int u = 0; u < kSpans; ++u) {
+      if (g0 + u * n_waves >= spans) continue;             // uniform over the wave
       const bool fs = (firsts >> u & 1u) != 0;
 #pragma unroll
       for (int r = 0; r < kPerLane; ++r) {
@@ -289,7 +301,7 @@ __device__ __forceinline__ void match_scan(const LDS& s, const Ctx& c, Sink& sin
       bool hit = have;
       if (have) lens_of(s, c.y, j, old_j, new_j);
       if (have && !(filter_decides && (filtered >> bit & 1u)))
-        hit = FUZZY ? gram_near_query(c, j, e, old_j) : gram_equals_query(c, j, e, old_j);
+        hit = FUZZY ? gram_near_query<QK>(c, j, e, old_j) : gram_equals_query<QK>(c, j, e, old_j);
       sink.push(c.y, hit, make_match(c.y, j, e, old_j, new_j));
     }
   }
