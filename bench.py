@@ -359,6 +359,27 @@ def main():
                               float(loop["accept"].cpu().numpy().reshape(T, -1)[growing].mean()),
                           "note": "csd_accept_loop over %d steps: draft -> accept against the path's own "
                                   "future -> append accepted + 1; synthetic stand-in for the model" % T}
+    # the same two host-free loops with the device-side loop (many steps per launch): reported
+    # beside the per-launch figures, never instead of them
+    r.ix.set_steps_per_launch(1 << 20)
+    dev_tail = r.time_tail(K, min(R, 10))
+    dev_loop_us = []
+    for _ in range(5):
+        r.ix.reset()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        ev0.record()
+        loop = r.ix.accept_loop(T, d_future_tok, d_future_pr, k, L, out=loop)
+        ev1.record()
+        torch.cuda.synchronize()
+        dev_loop_us.append(ev0.elapsed_time(ev1) / T * 1e3)
+    r.ix.set_steps_per_launch(1)
+    res["device_side_loop"] = {
+        "replay_us_per_step_at_full_history": percentile(dev_tail, 0.5),
+        "accept_loop_us_per_step": percentile(dev_loop_us, 0.5),
+        "note": "csd_set_steps_per_launch: csd_replay / csd_accept_loop as ONE launch for all their steps "
+                "(a workgroup per problem, a wave per path, a barrier between steps); same steps and "
+                "timing as `value` and accept_loop.us_per_step; not the per-call headline"}
     del loop, d_future_tok, d_future_pr
 
     # the other workloads, one-edit matching and two batch sizes: step time at full history

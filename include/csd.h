@@ -237,6 +237,18 @@ int csd_accept_loop(csd_index* index, int32_t n_steps, const int32_t* d_future_t
                     void* d_scratch, size_t scratch_bytes, int32_t* d_draft_tokens,
                     int32_t* d_draft_len, int32_t* d_accept_len, int32_t* d_path_len, void* stream);
 
+/* How many steps one launch of csd_replay (fused != 0) and csd_accept_loop runs.
+ * 1 (the default): a launch per step.  More: a device-side loop — one workgroup per
+ * problem, one wave per path, a workgroup barrier between steps — runs up to `steps`
+ * steps per launch where the configuration allows it: exact matching through the index,
+ * max_query_len <= 4, n_paths <= 16 (csd_accept_loop also needs twice the minimum of
+ * scratch memory); otherwise the calls work as with 1.  Results are identical.  Nothing
+ * happens on the host between two steps of these calls, so nothing is lost, and the
+ * per-step cost of a launch (dispatch, cold caches, argument fetch) is paid once per
+ * `steps` steps.  csd_step and the other per-step calls are not affected.
+ * CSD_ERR_INVALID_ARG if steps < 1. */
+int csd_set_steps_per_launch(csd_index* index, int32_t steps);
+
 /* csd_accept_loop for callers that cannot allocate device memory or hand over a scratch
  * buffer: code under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc.  Same arguments (without d_scratch / scratch_bytes), same results, same

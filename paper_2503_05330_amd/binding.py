@@ -23,7 +23,7 @@ ERR_SCRATCH_LIMIT = -6
 NOALLOC_SCRATCH_BYTES = 1 << 20
 
 EXPORTS = ["csd_workspace_bytes", "csd_create", "csd_destroy", "csd_reset", "csd_append",
-           "csd_draft", "csd_accept", "csd_step", "csd_replay", "csd_accept_loop", "csd_accept_loop_noalloc", "csd_status",
+           "csd_draft", "csd_accept", "csd_step", "csd_replay", "csd_accept_loop", "csd_accept_loop_noalloc", "csd_set_steps_per_launch", "csd_status",
            "csd_dump_matches",
            "csd_dump_edges", "csd_debug_copy", "csd_strerror"]
 
@@ -68,6 +68,7 @@ def load() -> ctypes.CDLL:
         lib.csd_accept_loop.argtypes = [_vp, i32, _vp, _vp, i32, i32, _vp, ctypes.c_size_t, _vp, _vp, _vp, _vp,
                                         _vp]
         lib.csd_accept_loop_noalloc.argtypes = [_vp, i32, _vp, _vp, i32, i32, _vp, _vp, _vp, _vp, _vp]
+        lib.csd_set_steps_per_launch.argtypes = [_vp, i32]
         lib.csd_status.argtypes = [_vp, ctypes.POINTER(ctypes.c_uint32), _vp]
         lib.csd_dump_matches.argtypes = [_vp, i32, _vp, _vp, i64, _vp]
         lib.csd_dump_edges.argtypes = [_vp, i32, i32, _vp, _vp, _vp, i64, _vp]
@@ -151,6 +152,10 @@ class Index:
     def _check(self, rc, what):
         if rc != OK:
             raise CsdError(rc, what)
+
+    def set_steps_per_launch(self, steps: int):
+        """Steps per launch of replay() and accept_loop() (1 = a launch per step)."""
+        self._check(load().csd_set_steps_per_launch(self._h, steps), "csd_set_steps_per_launch")
 
     def reset(self):
         self._check(load().csd_reset(self._h, _stream()), "csd_reset")

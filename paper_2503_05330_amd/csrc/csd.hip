@@ -179,6 +179,7 @@ struct csd_index {
   bool indexed;
   uint32_t alpha_q;
   int64_t len_lo, len_hi;       // host-side bounds on every path's length
+  int32_t steps_per_launch;     // csd_replay / csd_accept_loop: steps one launch runs (1: a launch per step)
 };
 
 namespace {
@@ -252,6 +253,28 @@ void launch_draft(const csd_index* h, const IndexView& v, const StepIn& in, cons
     step_wave_kernel<16, false, LdsWave, false, 8><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
   else
     step_wave_kernel<32, false, LdsWave, false, 8><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
+}
+
+// The device-side loops (many steps per launch) serve exact matching through the index with
+// grams of at most 4 tokens and at most 16 paths per problem (a wave per path, a workgroup
+// per problem).
+bool multi_step_ok(const csd_index* h) {
+  return h->indexed && h->view.eps == 0 && h->view.kmax <= 4 && h->view.N <= 16;
+}
+
+template <bool LOOP>
+void launch_multi(const csd_index* h, const MultiArgs& m, bool general, hipStream_t st) {
+  const uint32_t grid = (uint32_t)h->view.P, block = (uint32_t)h->view.N * kWave;
+  const int32_t L = m.a.L;
+  if (LOOP || general) {
+    if (L <= 8) step_multi_kernel<8, true, 4, LOOP><<<grid, block, 0, st>>>(h->view, m);
+    else if (L <= 16) step_multi_kernel<16, true, 4, LOOP><<<grid, block, 0, st>>>(h->view, m);
+    else step_multi_kernel<32, true, 4, LOOP><<<grid, block, 0, st>>>(h->view, m);
+  } else {
+    if (L <= 8) step_multi_kernel<8, false, 4, false><<<grid, block, 0, st>>>(h->view, m);
+    else if (L <= 16) step_multi_kernel<16, false, 4, false><<<grid, block, 0, st>>>(h->view, m);
+    else step_multi_kernel<32, false, 4, false><<<grid, block, 0, st>>>(h->view, m);
+  }
 }
 
 // Host-side bounds on the paths' lengths as they were before a call: put back when the call's
@@ -337,6 +360,7 @@ int csd_create(const csd_config* cfg, void* d_workspace, size_t workspace_bytes,
   h->view.eps = cfg->max_edits;
   h->view.options = (cfg->flags >> 2) & 3;
   h->alpha_q = to_alpha_q(cfg->alpha);
+  h->steps_per_launch = 1;
   rc = csd_reset(h, stream);
   if (rc != CSD_OK) {
     delete h;
@@ -448,6 +472,35 @@ int csd_replay(csd_index* h, int32_t n_steps, const int32_t* d_tokens, const flo
   if (h->len_lo + n_steps > h->cfg.max_len) return CSD_ERR_CAPACITY;
   size_t rows = (size_t)h->view.P * h->view.N;
   size_t L = (size_t)draft_len;
+  if (fused && h->steps_per_launch > 1 && multi_step_ok(h)) {
+    // the device-side loop: up to steps_per_launch steps per launch
+    const bool general = h->cfg.pool_mode != CSD_POOL_DAG || h->view.options != 0;
+    for (int32_t t = 0; t < n_steps;) {
+      const int32_t chunk = n_steps - t < h->steps_per_launch ? n_steps - t : h->steps_per_launch;
+      MultiArgs m{};
+      m.n_steps = chunk;
+      m.cur = h->cur;
+      m.meta[0] = h->meta[0];
+      m.meta[1] = h->meta[1];
+      m.tokens = d_tokens + t * rows;
+      m.probs = d_probs ? d_probs + t * rows : nullptr;
+      m.a = DraftArgs{query_len, draft_len, h->alpha_q, h->cfg.score_mode, h->cfg.pool_mode,
+                      d_draft_tokens + t * rows * L, d_draft_len + t * rows,
+                      d_token_scores ? d_token_scores + t * rows * L : nullptr,
+                      d_path_scores ? d_path_scores + t * rows : nullptr,
+                      d_targets ? d_targets + t * rows * L : nullptr,
+                      d_accept_len ? d_accept_len + t * rows : nullptr};
+      LengthBounds before(h);
+      h->len_lo += chunk;
+      h->len_hi = h->len_hi + chunk > h->cfg.max_len ? h->cfg.max_len : h->len_hi + chunk;
+      launch_multi<false>(h, m, general, as_stream(stream));
+      rc = before.launched("csd_replay");
+      if (rc != CSD_OK) return rc;
+      h->cur ^= chunk & 1;
+      t += chunk;
+    }
+    return CSD_OK;
+  }
   for (int32_t t = 0; t < n_steps; ++t) {
     const int32_t* tk = d_tokens + t * rows;
     const float* pr = d_probs ? d_probs + t * rows : nullptr;
@@ -501,6 +554,41 @@ static int accept_loop(csd_index* h, int32_t n_steps, const int32_t* d_future_to
         nullptr, d_future_tokens, d_future_probs, tok_of(0), d_future_probs ? prob_of(0) : nullptr,
         cnt_of(0), targets_of(0), d_path_len);
     CSD_HIP(hipGetLastError());
+    if (h->steps_per_launch > 1 && multi_step_ok(h)) {
+      // the device-side loop: up to steps_per_launch steps per launch (an even number, so
+      // that every launch starts with the first set of step buffers)
+      const int32_t most = h->steps_per_launch & ~1;
+      for (int32_t s = 0; s < n_steps;) {
+        const int32_t chunk = n_steps - s < most ? n_steps - s : most;
+        MultiArgs m{};
+        m.n_steps = chunk;
+        m.cur = h->cur;
+        m.meta[0] = h->meta[0];
+        m.meta[1] = h->meta[1];
+        for (int x = 0; x < 2; ++x) {
+          m.step_tok[x] = tok_of(x);
+          m.step_prob[x] = d_future_probs ? prob_of(x) : nullptr;
+          m.step_cnt[x] = cnt_of(x);
+          m.step_targets[x] = targets_of(x);
+        }
+        m.future_tok = d_future_tokens;
+        m.future_prob = d_future_probs;
+        m.path_len = d_path_len + (size_t)s * rows;
+        m.n = (int32_t)n;
+        m.a = DraftArgs{query_len, draft_len, h->alpha_q, h->cfg.score_mode, h->cfg.pool_mode,
+                        d_draft_tokens + (size_t)s * rows * L, d_draft_len + (size_t)s * rows,
+                        nullptr, nullptr, targets_of(0), d_accept_len + (size_t)s * rows};
+        LengthBounds before(h);
+        h->len_hi = h->len_hi + (int64_t)chunk * (int64_t)n > h->cfg.max_len
+                        ? h->cfg.max_len : h->len_hi + (int64_t)chunk * (int64_t)n;
+        launch_multi<true>(h, m, true, st);
+        rc = before.launched("csd_accept_loop");
+        if (rc != CSD_OK) return rc;
+        h->cur ^= chunk & 1;
+        s += chunk;
+      }
+      return CSD_OK;
+    }
     const uint32_t grid = xcd_grid((int64_t)rows);
     for (int32_t s = 0; s < n_steps; ++s) {
       const int x = s & 1;
@@ -601,6 +689,12 @@ int csd_accept_loop_noalloc(csd_index* h, int32_t n_steps, const int32_t* d_futu
   if (rc != CSD_OK) return rc;
   return accept_loop(h, n_steps, d_future_tokens, d_future_probs, query_len, draft_len, ptr, need,
                      d_draft_tokens, d_draft_len, d_accept_len, d_path_len, stream);
+}
+
+int csd_set_steps_per_launch(csd_index* h, int32_t steps) {
+  if (!h || steps < 1) return CSD_ERR_INVALID_ARG;
+  h->steps_per_launch = steps;
+  return CSD_OK;
 }
 
 int csd_status(csd_index* h, uint32_t* host_flags, void* stream) {

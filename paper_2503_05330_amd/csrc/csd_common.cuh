@@ -369,19 +369,21 @@ struct Slot {
 
 // On-chip state of one row.  TABLE = hash slots for DAG edges + nodes (power of
 // two), MATCH = matches kept (beyond: streaming tier), WIN = words for cached
-// continuations of matches, WAVES = waves of the workgroup.
-template <int TABLE, int MATCH, int WIN, int WAVES>
+// continuations of matches, WAVES = waves of the workgroup, LENS = paths whose lengths
+// are cached (more paths: their lengths are read from memory).
+template <int TABLE, int MATCH, int WIN, int WAVES, int LENS = kLenCache>
 struct LdsT {
   static constexpr int kTable = TABLE;
   static constexpr int kMatch = MATCH;
   static constexpr int kWin = WIN;
+  static constexpr int kLens = LENS;
   Slot table[TABLE];
   uint16_t link[TABLE > MATCH ? TABLE : MATCH];   // edge slot -> slot of its target node (tier 1);
                                 // the tree pool keeps one flag per listed match here
   Match match[MATCH];
   int32_t win[WIN];             // per cached match: L continuation tokens, then their L probabilities
-  int32_t len_old[kLenCache];
-  int32_t len_new[kLenCache];
+  int32_t len_old[LENS];
+  int32_t len_new[LENS];
   Cand red[2][WAVES];
   int32_t chosen[CSD_MAX_DRAFT_LEN];   // the draft so far (tree pool)
   int n_match;                  // total matches found (may exceed MATCH)
@@ -396,6 +398,10 @@ typedef LdsT<256, 256, 1024, 1> LdsWaveSmall;
 // One wave per row with one-edit matching through the index: such queries have
 // many more matches, so the list is longer (66 KB, two rows per CU).
 typedef LdsT<1024, 4096, 2048, 1> LdsWaveFuzzy;
+// One wave per row, all rows of a problem (at most 16) in one workgroup that runs many
+// steps per launch (the device-side loops): 10 KB per row, 160 KB per workgroup.  Rows with
+// more than 64 matches (at a draft length of 8) take the bounded-memory tiers.
+typedef LdsT<256, 128, 1024, 1, 16> LdsMulti;
 // One 1024-thread workgroup per row (scan mode, where a fuzzy query can have
 // thousands of matches): 108 KB, one row per CU.
 typedef LdsT<4096, 4096, 16, kScanBlock / kWave> LdsScan;

@@ -60,11 +60,11 @@ __device__ __forceinline__ int32_t write_accept(const DraftArgs& a, int32_t row,
   return accepted;
 }
 
-// Lengths of the first kLenCache paths into LDS (the scan reads them per tile).
+// Lengths of the first LDS::kLens paths into LDS (the scan reads them per tile).
 // The caller synchronises the workgroup before using them.
 template <int BLOCK, class LDS>
 __device__ __forceinline__ void cache_lens(LDS& s, const Paths& y, int tid) {
-  for (int32_t j = tid; j < y.N && j < kLenCache; j += BLOCK) {
+  for (int32_t j = tid; j < y.N && j < LDS::kLens; j += BLOCK) {
     int32_t old_j = y.old_len(j);
     s.len_old[j] = old_j;
     s.len_new[j] = y.new_len(j, old_j);
@@ -293,22 +293,15 @@ struct LoopTail {
   int32_t n, max_len;
 };
 
-template <int LCAP, bool POOLS, class LDS, bool FUZZY, int QC, class TAIL>
-__device__ __forceinline__ void step_wave_body(const IndexView& ix, const StepIn& in,
-                                               const DraftArgs& a, const TAIL& tail) {
-  constexpr bool SPLIT = step_wave_threads(FUZZY) > kWave;
-  __shared__ LDS s;
-  int32_t row = xcd_row(ix.P * ix.N);
-  if (row < 0) return;
+// One decode step of one row by one wave: front end, DAG, walk, outputs, accept, tail.
+// APPENDS: the wave also appends the row's tokens and files them in the index (false: another
+// wave of the workgroup does, see wave_append).  s: the row's on-chip state.
+template <int LCAP, bool POOLS, class LDS, bool FUZZY, int QC, bool APPENDS, class TAIL>
+__device__ __forceinline__ void row_step(LDS& s, const IndexView& ix, const StepIn& in,
+                                         const DraftArgs& a, const TAIL& tail, int32_t row, int lane) {
   int32_t p;
   Ctx c = make_ctx(ix, in, row, p);
-  if (SPLIT) {
-    c.tid = (int)(threadIdx.x & (kWave - 1));
-    if (__builtin_amdgcn_readfirstlane((int)threadIdx.x) >= kWave) {
-      wave_append<QC, POOLS>(c, ix, p);
-      return;
-    }
-  }
+  c.tid = lane;
   const int32_t L = a.L;
   int32_t target = (a.targets && c.tid < L) ? a.targets[(int64_t)row * L + c.tid] : 0;
   WinInfo wi;
@@ -316,8 +309,14 @@ __device__ __forceinline__ void step_wave_body(const IndexView& ix, const StepIn
   VariantTicket tickets;
   bool ticket_used;
   int32_t M = FUZZY ? wave_front_end_fuzzy<LCAP>(s, c, ix, p, a.k, L, wi, tickets, ticket_used)
-                    : wave_front_end<LCAP, QC, !SPLIT, POOLS>(s, c, ix, p, a.k, L, wi, ticket, ticket_used);
+                    : wave_front_end<LCAP, QC, APPENDS, POOLS>(s, c, ix, p, a.k, L, wi, ticket, ticket_used);
   block_sync<kWave>();
+  if (APPENDS && POOLS && !FUZZY && in.n > 1) {
+    // a step of several tokens appended by the drafting wave itself (nothing this step's
+    // drafts read is written here)
+    const int32_t old_i = c.y.old_len(c.i);
+    append_row<kWave, true>(ix, c.y, p, c.i, old_i, c.y.new_len(c.i, old_i), lane);
+  }
   // the loop's tail needs the path's future from its new end on (lane x: x tokens further):
   // requested here, so that the load travels during the walk
   int32_t future_a = 0, future_b = 0;
@@ -425,6 +424,25 @@ __device__ __forceinline__ void step_wave_body(const IndexView& ix, const StepIn
   }
 }
 
+// The row of this workgroup: its first wave drafts; with exact matching a second wave appends.
+template <int LCAP, bool POOLS, class LDS, bool FUZZY, int QC, class TAIL>
+__device__ __forceinline__ void step_wave_body(const IndexView& ix, const StepIn& in,
+                                               const DraftArgs& a, const TAIL& tail) {
+  constexpr bool SPLIT = step_wave_threads(FUZZY) > kWave;
+  __shared__ LDS s;
+  int32_t row = xcd_row(ix.P * ix.N);
+  if (row < 0) return;
+  const int lane = (int)(threadIdx.x & (kWave - 1));
+  if (SPLIT && __builtin_amdgcn_readfirstlane((int)threadIdx.x) >= kWave) {
+    int32_t p;
+    Ctx c = make_ctx(ix, in, row, p);
+    c.tid = lane;
+    wave_append<QC, POOLS>(c, ix, p);
+    return;
+  }
+  row_step<LCAP, POOLS, LDS, FUZZY, QC, !SPLIT>(s, ix, in, a, tail, row, lane);
+}
+
 template <int LCAP, bool POOLS, class LDS, bool FUZZY, int QC>
 __global__ __launch_bounds__(step_wave_threads(FUZZY)) void step_wave_kernel(IndexView ix, StepIn in,
                                                                              DraftArgs a) {
@@ -439,6 +457,71 @@ __global__ __launch_bounds__(step_wave_threads(false)) void step_loop_kernel(Ind
                                                                              DraftArgs a,
                                                                              LoopTail tail) {
   step_wave_body<LCAP, true, LdsWave, false, QC>(ix, in, a, tail);
+}
+
+// Many steps per launch (the device-side form of the host loops csd_replay and
+// csd_accept_loop, where nothing happens on the host between two steps): one workgroup per
+// problem, one wave per path (at most 16), exact matching through the index.  A step's rows
+// only read what earlier steps wrote, so one workgroup barrier between steps orders
+// everything; no launch, no cold cache and no argument fetch per step.
+struct MultiArgs {
+  int32_t n_steps, cur;         // cur: which meta buffer holds the paths' ends on entry
+  int32_t* meta[2];
+  // replay: step t appends tokens[t] (one token per path) and drafts into slice t
+  const int32_t* tokens;        // [n_steps][P][N], or null (the accept-driven loop)
+  const float* probs;           // [n_steps][P][N] or null
+  const int32_t* targets;       // [n_steps][P][N][L] or null
+  float* token_scores;          // [n_steps][P][N][L] or null
+  float* path_scores;           // [n_steps][P][N] or null
+  // accept-driven loop: the two sets of step buffers (see LoopTail); step t reads set t & 1
+  int32_t* step_tok[2];
+  float* step_prob[2];
+  int32_t* step_cnt[2];
+  int32_t* step_targets[2];
+  const int32_t* future_tok;
+  const float* future_prob;
+  int32_t* path_len;            // [n_steps][P][N]
+  int32_t n;                    // tokens per path and step the loop offers (L + 1)
+  // both
+  DraftArgs a;                  // outputs of step 0; step t writes slice t
+};
+
+template <int LCAP, bool POOLS, int QC, bool LOOP>
+__global__ __launch_bounds__(16 * kWave) void step_multi_kernel(IndexView ix, MultiArgs m) {
+  __shared__ LdsMulti rows_lds[16];
+  const int wave = (int)(threadIdx.x >> 6), lane = (int)(threadIdx.x & (kWave - 1));
+  const int32_t row = (int32_t)blockIdx.x * ix.N + wave;    // the block has N waves
+  const int64_t rows = (int64_t)ix.P * ix.N;
+  const int64_t L = m.a.L;
+  for (int32_t t = 0; t < m.n_steps; ++t) {
+    IndexView v = ix;
+    v.meta_old = m.meta[(m.cur + t) & 1];
+    v.meta_new = m.meta[(m.cur + t + 1) & 1];
+    DraftArgs a = m.a;
+    a.draft_tokens += t * rows * L;
+    a.draft_len += t * rows;
+    if (a.accept_len) a.accept_len += t * rows;
+    if constexpr (LOOP) {
+      const int x = t & 1;
+      const StepIn in{m.step_tok[x], m.step_prob[x], m.step_cnt[x], m.n};
+      a.targets = m.step_targets[x];
+      const LoopTail tail{m.future_tok, m.future_prob, m.step_tok[x ^ 1], m.step_prob[x ^ 1],
+                          m.step_cnt[x ^ 1], m.step_targets[x ^ 1], m.path_len + t * rows, m.n, ix.max_len};
+      row_step<LCAP, true, LdsMulti, false, QC, true>(rows_lds[wave], v, in, a, tail, row, lane);
+    } else {
+      const StepIn in{m.tokens + t * rows, m.probs ? m.probs + t * rows : nullptr, nullptr, 1};
+      if (a.targets) a.targets += t * rows * L;
+      if (a.token_scores) a.token_scores += t * rows * L;
+      if (a.path_scores) a.path_scores += t * rows;
+      row_step<LCAP, POOLS, LdsMulti, false, QC, true>(rows_lds[wave], v, in, a, NoTail{}, row, lane);
+    }
+    // what this step wrote (histories, path ends, index, the loop's next input) before what
+    // the next step reads: the waves of a workgroup share their CU's vector cache, which is
+    // dropped here all the same (index buckets are also written by atomics, which work in
+    // the L2)
+    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+  }
 }
 
 __global__ __launch_bounds__(256) void accept_kernel(int64_t rows, int32_t L,

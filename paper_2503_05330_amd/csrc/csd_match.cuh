@@ -148,11 +148,11 @@ struct FnSink {
 
 // ---------------------------------------------------------------- general matchers
 
-// Lengths of path j: from the LDS cache for the first kLenCache paths.
+// Lengths of path j: from the LDS cache for the first LDS::kLens paths.
 template <class LDS>
 __device__ __forceinline__ void lens_of(const LDS& s, const Paths& y, int32_t j, int32_t& old_j,
                                         int32_t& new_j) {
-  if (j < kLenCache) {
+  if (j < LDS::kLens) {
     old_j = s.len_old[j];
     new_j = s.len_new[j];
   } else {
@@ -190,7 +190,7 @@ __device__ __forceinline__ bool may_match(const Ctx& c, const int32_t (&t)[kFilt
 // Eq. 3 (FUZZY = false) or Eq. 4 with one edit (FUZZY = true) by exhaustive
 // comparison: every position e of every other path j with q - eps <= e <=
 // len_j - 1 is tested.  s.len_old / s.len_new hold the lengths of the first
-// kLenCache paths.
+// LDS::kLens paths.
 //
 // A row's positions all pass through one CU, and what bounds the scan there is
 // instruction issue, so the common case is kept lean.  The paths are cut into
@@ -355,8 +355,6 @@ __device__ __forceinline__ void match_plain(const LDS& s, const Ctx& c, Sink& si
 // from the step's input, and the appended positions are matched one lane per position).  With
 // exact matching the append and the insert are another wave's (wave_append).
 
-constexpr int kStageTokens = 1024;   // a step's tokens (N * n) that the general front end stages in LDS
-constexpr int kStagePaths = 64;      // .. and the paths whose old tails it stages
 
 struct Head {                   // a path's end before this step
   int32_t old_len, new_len;
@@ -567,11 +565,10 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
   // tails go to LDS (laid over the table, which nothing uses before the walk) when they fit, so
   // that the query and the matches among the appended positions need no further round trip
   const bool multi = GENERAL && y.n > 1;
-  const bool staged = multi && y.N * y.n <= kStageTokens && y.N <= kStagePaths;
+  constexpr int kStageWords = (int)(sizeof(s.table) / (sizeof(int32_t)));
+  const bool staged = multi && y.N * (y.n + QC) <= kStageWords;
   int32_t* stage = reinterpret_cast<int32_t*>(s.table);   // [N][n] the step's tokens
-  int32_t* tails = stage + kStageTokens;                  // [N][QC] tokens before the old ends
-  static_assert(!GENERAL || (kStageTokens + kStagePaths * QC) * sizeof(int32_t) <= sizeof(s.table),
-                "the staged step fits the table");
+  int32_t* tails = stage + y.N * y.n;                     // [N][QC] tokens before the old ends
   if (GENERAL && staged)
     for (int32_t x = lane; x < y.N * y.n; x += kWave) stage[x] = y.st[x];
   Head me;
@@ -607,7 +604,7 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
   }
   const bool use_index = c.q == ix.kmax;                // shorter queries: scan (short paths)
   // ---- round trip 2 is requested: fill counts for the insert, first 4 buckets of the query
-  ticket_used = APPENDS && cnt_i == 1;
+  ticket_used = APPENDS && y.n == 1 && cnt_i == 1;   // (longer steps are appended by append_row)
   if (ticket_used) ticket = insert_begin<QC>(gram, c.bucket_mask, ix.kmax, me.tail, old_i, lane);
   GramHash gh{0u, 1u};
   int32_t word = -1;
@@ -623,7 +620,7 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
     int32_t j = j0 + lane;
     bool have = j < y.N;
     if (j0 > 0) hj = load_head<QC>(y, ix.tail_len, have ? j : 0);
-    if (have && j < kLenCache) {
+    if (have && j < LDS::kLens) {
       s.len_old[j] = hj.old_len;
       s.len_new[j] = hj.new_len;
     }
@@ -941,7 +938,7 @@ __device__ __forceinline__ int32_t wave_front_end_fuzzy(LDS& s, Ctx& c, const In
       for (int a = 0; a < K; ++a)
         first_tokens[a] = y.tok[y.cell(have ? j : 0, a < ix.kmax - 1 ? ix.kmax - 2 - a : 0)];
     }
-    if (have && j < kLenCache) {
+    if (have && j < LDS::kLens) {
       s.len_old[j] = hj.old_len;
       s.len_new[j] = hj.new_len;
     }

@@ -7,18 +7,21 @@ from paper_2503_05330_amd import binding
 
 
 def gpu_replay(tokens, probs, k, L, alpha=1.0, score_mode=0, flags=0, steps=None, targets=None,
-               counts=None, n_per_step=1, how="calls", max_edits=0, pool_mode=0):
+               counts=None, n_per_step=1, how="calls", max_edits=0, pool_mode=0, steps_per_launch=1):
     """Appends n_per_step tokens per path per step (or counts[t] of them) and drafts after
     every step.  Returns host arrays indexed by step, plus the final status bits.
     how: "calls"  = csd_append + csd_draft (+ csd_accept) per step,
          "step"   = one fused csd_step per step,
          "replay" / "replay_unfused" = one csd_replay call for all steps (n_per_step == 1,
-                    no counts)."""
+                    no counts).
+    steps_per_launch > 1: csd_replay runs its device-side loop where the configuration allows."""
     P, N, T = tokens.shape
     steps = steps if steps is not None else T // n_per_step
     dev = torch.device("cuda:0")
     ix = binding.Index(P, N, T, int(tokens.max()) + 1 if tokens.size else 1, k, L, alpha,
                        score_mode, flags, device=dev, max_edits=max_edits, pool_mode=pool_mode)
+    if steps_per_launch > 1:
+        ix.set_steps_per_launch(steps_per_launch)
     out_tok = torch.empty((steps, P, N, L), dtype=torch.int32, device=dev)
     out_len = torch.empty((steps, P, N), dtype=torch.int32, device=dev)
     out_ts = torch.empty((steps, P, N, L), dtype=torch.float32, device=dev)

@@ -630,12 +630,14 @@ def test_pool_modes_small_and_degenerate_cases(oracle, pool_mode):
 
 # ---------------------------------------------------------------- the propose / verify / accept loop
 def _accept_loop_case(oracle, w, n_steps, flags, eps=0, pool_mode=0, use_probs=True, warm=None,
-                      min_scratch=False):
+                      min_scratch=False, steps_per_launch=1):
     tokens, probs = synth.make_paths(w)
     pr = probs if use_probs else None
     dev = torch.device("cuda:0")
     P, N, T, k, L = w.n_problems, w.n_paths, w.max_len, w.query_len, w.draft_len
     ix = binding.Index(P, N, T, w.vocab, k, L, 1.0, 0, flags, device=dev, max_edits=eps, pool_mode=pool_mode)
+    if steps_per_launch > 1:
+        ix.set_steps_per_launch(steps_per_launch)
     lens0 = np.zeros((P, N), np.int32)
     if warm is not None:                          # start from ragged, partly filled paths
         lens0 = warm.astype(np.int32)
@@ -647,7 +649,9 @@ def _accept_loop_case(oracle, w, n_steps, flags, eps=0, pool_mode=0, use_probs=T
                          None if pr is None else torch.from_numpy(pr).to(dev), k, L,
                          min_scratch=min_scratch)
     want = oracle.accept_loop(tokens, pr, lens0, k, L, n_steps, eps=eps, pool_mode=pool_mode)
-    what = "%s flags=%d eps=%d pool=%d min_scratch=%d" % (w.name, flags, eps, pool_mode, min_scratch)
+    what = "%s flags=%d eps=%d pool=%d min_scratch=%d steps_per_launch=%d" % (
+        w.name, flags, eps, pool_mode, min_scratch, steps_per_launch)
+    print("accept loop", what, flush=True)
     assert np.array_equal(got["path_len"].cpu().numpy(), want["path_len"]), what
     assert np.array_equal(got["length"].cpu().numpy(), want["draft_len"]), what
     assert np.array_equal(got["tokens"].cpu().numpy(), want["draft"]), what
@@ -678,6 +682,53 @@ def test_accept_loop_diverging_path_lengths(oracle):
     want = _accept_loop_case(oracle, c2, 700, INDEX)          # runs every path to its full length
     assert (want["final_len"] == c2.max_len).all()
     _accept_loop_case(oracle, synth.scaled(c4, n_problems=6), 60, INDEX)
+
+
+def test_device_side_loops_many_steps_per_launch(oracle):
+    """csd_set_steps_per_launch: csd_replay and csd_accept_loop with a device-side loop (one
+    workgroup per problem, a wave per path, a barrier between steps) against the oracle at
+    every step: whole replays in one launch and in chunks, 64 problems at once, the general
+    kernels (tree and list pools, own history), longer drafts, a query of 4, no probabilities;
+    and configurations the loop does not serve (32 paths; one-edit matching), which must fall
+    back to a launch per step with the same results."""
+    c1, c2, c3, c4 = (synth.WORKLOADS[n] for n in ("C1", "C2", "C3", "C4"))
+
+    def replay_case(w, spl, use_probs=True, mode=0, pool_mode=0, flags=INDEX, eps=0, accept=True, **extras):
+        tokens, probs = synth.make_paths(w)
+        if not use_probs:
+            probs = None
+        T = w.max_len
+        targets = np.stack([synth.make_noisy_targets(w, tokens, t + 1, w.draft_len) for t in range(T)]) if accept else None
+        what = "device loop %s steps_per_launch=%d probs=%s mode=%d pool=%d flags=%d eps=%d" % (
+            w.name, spl, use_probs, mode, pool_mode, flags, eps)
+        print(what, flush=True)
+        want = oracle_steps(oracle, tokens, probs, list(range(T)), w.query_len, w.draft_len, 0.75, mode, targets,
+                            eps=eps, pool_mode=pool_mode, **extras)
+        got = gpu_replay(tokens, probs, w.query_len, w.draft_len, 0.75, mode, flags, targets=targets, how="replay",
+                         max_edits=eps, pool_mode=pool_mode, steps_per_launch=spl)
+        assert got["status"] == 0
+        for t in range(T):
+            assert_step_equal(got, want[t], t, what)
+
+    replay_case(c1, 1000)
+    replay_case(c1, 7, use_probs=False, mode=1, accept=False)
+    replay_case(c2, 1024)
+    replay_case(c2, 100, mode=1)
+    replay_case(c4, 256)
+    replay_case(synth.scaled(c3, n_paths=16, max_len=600), 64)                      # query of 4, drafts of 10
+    replay_case(synth.scaled(c2, max_len=300, draft_len=32), 300)
+    replay_case(c1, 64, pool_mode=binding.POOL_TREE)
+    replay_case(c1, 64, pool_mode=binding.POOL_LIST)
+    replay_case(c1, 64, flags=INDEX | binding.INCLUDE_SELF, include_self=True)
+    replay_case(synth.scaled(c3, max_len=200), 64)                                  # 32 paths: a launch per step
+    replay_case(c1, 64, flags=binding.MATCH_AUTO, eps=1)                            # one edit: a launch per step
+    for w, steps, spl in ((c1, 200, 50), (c2, 700, 700), (c2, 300, 64), (synth.scaled(c4, n_problems=6), 120, 30),
+                          (synth.scaled(c2, max_len=400, draft_len=16), 100, 100),
+                          (synth.scaled(c2, max_len=300, draft_len=32), 60, 8)):
+        want = _accept_loop_case(oracle, w, steps, INDEX, steps_per_launch=spl)
+        assert want["accept_len"].sum() > 0
+    _accept_loop_case(oracle, c1, 120, INDEX, use_probs=False, warm=np.array([[40, 3, 0, 17]]), steps_per_launch=33)
+    _accept_loop_case(oracle, c1, 200, INDEX, pool_mode=binding.POOL_TREE, steps_per_launch=64)
 
 
 def test_large_batch_uses_the_small_on_chip_layout(oracle):
