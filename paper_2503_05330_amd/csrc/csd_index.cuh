@@ -103,10 +103,13 @@ __device__ __forceinline__ void gram_insert_lanes(int32_t* gram, uint32_t mask, 
 // Split-phase insert of ONE new position by one wave, so that its two memory
 // round trips overlap the lookup's: lanes 0..3 look at the first four buckets of
 // the gram's sequence (sixteen were no faster and fetched twelve more lines per row).
+// (With thousands of rows per launch the step is bound by what all rows together issue and
+// fetch, not by one row's latency: there only the first bucket is looked at up front, LANES = 1.)
 constexpr int kInsertLanes = 4;     // buckets of the chain whose fill counts are read up front
 struct InsertTicket {
   GramHash gh;
-  int32_t fill;                 // fill count of bucket `lane` of the sequence (lanes < kInsertLanes)
+  int32_t fill;                 // fill count of bucket `lane` of the sequence (lanes < LANES)
+  int32_t lanes;                // LANES: buckets looked at up front
   int32_t first;                // first open bucket among those looked at, or -1
   int32_t claimed;              // lane 0: slot the atomic returned, or kBucketSlots
   bool live;                    // the position has kmax tokens before it
@@ -114,11 +117,13 @@ struct InsertTicket {
 
 // Phase 1: hash of the gram that ends just before the new position (tail[a] =
 // a-th token before it) and the fill-count loads (not waited for here).
-template <int QC>
+template <int QC, int LANES = kInsertLanes>
 __device__ __forceinline__ InsertTicket insert_begin(int32_t* gram, uint32_t mask, int32_t kmax,
                                                      const int32_t (&tail)[kTailCap],
                                                      int32_t n_before, int lane) {
+  static_assert(LANES >= 1 && (LANES & (LANES - 1)) == 0, "a power of two of buckets");
   InsertTicket t;
+  t.lanes = LANES;
   uint32_t acc = kGramSeed;
 #pragma unroll
   for (int a = 1; a <= QC; ++a)
@@ -127,7 +132,7 @@ __device__ __forceinline__ InsertTicket insert_begin(int32_t* gram, uint32_t mas
   t.live = kmax <= n_before;
   t.first = -1;
   t.claimed = kBucketSlots;
-  uint32_t r = (uint32_t)(lane & (kInsertLanes - 1));   // every lane loads: no branch, no early wait
+  uint32_t r = (uint32_t)(lane & (LANES - 1));          // every lane loads: no branch, no early wait
   t.fill = gram_bucket(gram, t.gh, r <= mask ? r : 0u, mask)[0];
   return t;
 }
@@ -136,7 +141,7 @@ __device__ __forceinline__ InsertTicket insert_begin(int32_t* gram, uint32_t mas
 __device__ __forceinline__ void insert_claim(InsertTicket& t, int32_t* gram, uint32_t mask,
                                              int lane) {
   consume_here(t.fill);
-  bool open = t.live && lane < kInsertLanes && (uint32_t)lane <= mask && t.fill < kBucketSlots;
+  bool open = t.live && lane < t.lanes && (uint32_t)lane <= mask && t.fill < kBucketSlots;
   u64 m = wave_ballot(open);
   t.first = m ? (int32_t)__ffsll((long long)m) - 1 : -1;
   if (t.live && lane == 0 && t.first >= 0)
@@ -153,7 +158,7 @@ __device__ __forceinline__ void insert_finish(const InsertTicket& t, int32_t* gr
     if (lane == 0) gram_bucket(gram, t.gh, (uint32_t)t.first, mask)[1 + claimed] = pos;
     return;
   }
-  gram_insert_from(gram, mask, t.gh, t.first < 0 ? (uint32_t)kInsertLanes : (uint32_t)t.first, pos,
+  gram_insert_from(gram, mask, t.gh, t.first < 0 ? (uint32_t)t.lanes : (uint32_t)t.first, pos,
                    lane);
 }
 

@@ -437,7 +437,7 @@ __device__ __forceinline__ void step_wave_body(const IndexView& ix, const StepIn
     int32_t p;
     Ctx c = make_ctx(ix, in, row, p);
     c.tid = lane;
-    wave_append<QC, POOLS>(c, ix, p);
+    wave_append<QC, POOLS, std::is_same<LDS, LdsWaveSmall>::value ? 1 : kInsertLanes>(c, ix, p);
     return;
   }
   row_step<LCAP, POOLS, LDS, FUZZY, QC, !SPLIT>(s, ix, in, a, tail, row, lane);

@@ -440,7 +440,9 @@ __device__ __forceinline__ void append_own_single(const IndexView& ix, const Pat
 // of 4 buckets, already requested.  Adds its hits behind the matches already
 // listed; match number x of the list gets window x (if x < win_cap).
 // GENERAL: also compiled for the options (own history searched): kept out of the usual kernels.
-template <int LCAP, int QC, bool GENERAL = false, class LDS>
+// FIRST: buckets of the first batch (4, or 1 where fetched lines count for more than a row's
+// latency: `word` is then requested by the first 16 lanes only); later batches have 4.
+template <int LCAP, int QC, bool GENERAL = false, int FIRST = 4, class LDS>
 __device__ __forceinline__ void lookup_with_windows(LDS& s, const Ctx& c, int32_t L,
                                                     int32_t win_cap, int32_t& n_match,
                                                     GramHash gh, int32_t word) {
@@ -453,15 +455,17 @@ __device__ __forceinline__ void lookup_with_windows(LDS& s, const Ctx& c, int32_
   int32_t query_oldest_first[QC];     // [x] = Q[q - 1 - x]
 #pragma unroll
   for (int x = 0; x < QC; ++x) query_oldest_first[x] = pick_n<QC>(c.Q, c.q - 1 - x);
-  for (uint32_t r0 = 0; r0 < n_buckets; r0 += 4) {
+  uint32_t width = FIRST;             // buckets of this batch
+  for (uint32_t r0 = 0; r0 < n_buckets; r0 += width, width = 4) {
     consume_here(word);
-    if (r0 + grp >= n_buckets) word = -1;
+    const bool in_batch = (uint32_t)grp < width;
+    if (!in_batch || r0 + grp >= n_buckets) word = -1;
     int32_t count = __shfl(word, lane & ~15);
     bool full = count >= kBucketSlots;
-    bool seq_ends = wave_ballot(!full || r0 + grp >= n_buckets) != 0;
+    bool seq_ends = wave_ballot(in_batch && (!full || r0 + grp >= n_buckets)) != 0;
     int32_t next_word = -1;           // next batch: in flight while this one is processed
     if (!seq_ends) {
-      uint32_t r = r0 + 4 + grp;
+      uint32_t r = r0 + width + grp;
       next_word = gram_bucket(tbl, gh, r < n_buckets ? r : 0u, c.bucket_mask)[sub];
     }
     bool cand = sub >= 1 && word >= 0 && (sub - 1) < (full ? kBucketSlots : count);
@@ -603,15 +607,19 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
     load_query(c, k, old_i);                            // (one more round trip: from the step's input)
   }
   const bool use_index = c.q == ix.kmax;                // shorter queries: scan (short paths)
-  // ---- round trip 2 is requested: fill counts for the insert, first 4 buckets of the query
+  // ---- round trip 2 is requested: fill counts for the insert, first buckets of the query
+  // (four of each; one with the layout of launches of thousands of rows, whose time is set by
+  // what all rows together fetch and issue, not by a row's latency)
+  constexpr int kFirst = std::is_same<LDS, LdsWaveSmall>::value ? 1 : 4;
   ticket_used = APPENDS && y.n == 1 && cnt_i == 1;   // (longer steps are appended by append_row)
-  if (ticket_used) ticket = insert_begin<QC>(gram, c.bucket_mask, ix.kmax, me.tail, old_i, lane);
+  if (ticket_used) ticket = insert_begin<QC, kFirst>(gram, c.bucket_mask, ix.kmax, me.tail, old_i, lane);
   GramHash gh{0u, 1u};
   int32_t word = -1;
   if (use_index) {
     gh = query_hash<QC>(c);
     uint32_t r = (uint32_t)(lane >> 4);
-    word = gram_bucket(gram, gh, r <= c.bucket_mask ? r : 0u, c.bucket_mask)[lane & 15];
+    if (kFirst == 4 || r == 0)
+      word = gram_bucket(gram, gh, r <= c.bucket_mask ? r : 0u, c.bucket_mask)[lane & 15];
   }
   // ---- while it travels: own append, lengths into LDS, matches among the new positions
   if (APPENDS && y.n == 1) append_own_single<QC>(ix, y, row, c.i, me, st_i, sp_i, lane);
@@ -666,7 +674,7 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
   wi.n_fresh = n_match;
   wi.win_cap = use_index ? LDS::kWin / (2 * L) : 0;
   if (use_index) {
-    lookup_with_windows<LCAP, QC, GENERAL>(s, c, L, wi.win_cap, n_match, gh, word);
+    lookup_with_windows<LCAP, QC, GENERAL, kFirst>(s, c, L, wi.win_cap, n_match, gh, word);
   } else if (c.q > 0) {
     WaveListSink<LDS> sink{&s, &n_match, lane};
     match_plain<false>(s, c, sink);                     // covers old and new positions alike
@@ -681,7 +689,8 @@ __device__ __forceinline__ int32_t wave_front_end(LDS& s, Ctx& c, const IndexVie
 // the index.  Nothing the drafting waves of this launch read is written here: they take
 // positions from the old lengths on from the step's input, and ignore newer postings.
 // GENERAL: also compiled for steps of several tokens per path.
-template <int QC, bool GENERAL = false>
+// LANES: buckets of the insert's chain whose fill counts are read up front.
+template <int QC, bool GENERAL = false, int LANES = kInsertLanes>
 __device__ __forceinline__ void wave_append(const Ctx& c, const IndexView& ix, int32_t p) {
   const int lane = c.tid;
   const Paths& y = c.y;
@@ -698,7 +707,7 @@ __device__ __forceinline__ void wave_append(const Ctx& c, const IndexView& ix, i
   const float sp_i = y.sp ? y.sp[c.i] : 1.0f;
   const bool ticket_used = me.new_len - me.old_len == 1;
   InsertTicket ticket;
-  if (ticket_used) ticket = insert_begin<QC>(gram, c.bucket_mask, ix.kmax, me.tail, me.old_len, lane);
+  if (ticket_used) ticket = insert_begin<QC, LANES>(gram, c.bucket_mask, ix.kmax, me.tail, me.old_len, lane);
   append_own_single<QC>(ix, y, row, c.i, me, st_i, sp_i, lane);
   if (ticket_used) {
     insert_claim(ticket, gram, c.bucket_mask, lane);
