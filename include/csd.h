@@ -96,7 +96,18 @@ typedef enum {
 /* Sticky device-side status bits, read with csd_status. */
 #define CSD_STATUS_CAPACITY 1u     /* an append was clipped at max_len               */
 #define CSD_STATUS_TOKEN_RANGE 2u  /* a token id outside [0, vocab) was appended     */
-#define CSD_STATUS_TABLE_FULL 4u   /* a draft was cut short: DAG tables exhausted    */
+#define CSD_STATUS_TABLE_FULL 4u   /* a draft was cut short: DAG tables exhausted.
+                                      Cannot happen with vocab <= 2^24, whatever the
+                                      input.  The bounded-memory tier splits a layer's
+                                      tokens into up to 2^20 classes by bits 12..31 of
+                                      id * 0x9E3779B1 mod 2^32; at most 65 ids below 2^24
+                                      (2045 below 2^29) share a class, and the smallest
+                                      on-chip table holds 256 keys (two per id).  Beyond
+                                      2^24 it takes a layer whose continuation tokens
+                                      include more than 128 distinct ids of ONE class
+                                      (512 with fewer than 2048 rows per launch): only a
+                                      constructed input does that.  The draft then ends
+                                      before that layer; everything else stays exact.   */
 
 typedef struct {
   int32_t n_problems;     /* P > 0                                                    */

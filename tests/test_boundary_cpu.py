@@ -89,3 +89,27 @@ def test_binding_has_no_cpu_fallback():
                 text = open(os.path.join(dirpath, f)).read()
                 assert not re.search(r"import\s+oracle|from\s+oracle|csd_oracle|oracle[/.]", text), \
                     f + " reaches for the oracle"
+
+
+def test_bound_behind_the_table_full_status_bit():
+    """csd.h promises that CSD_STATUS_TABLE_FULL cannot occur with vocab <= 2^24: token ids are
+    split into 2^20 classes by bits 12..31 of id * 0x9E3779B1 mod 2^32, so two ids of one class
+    differ by delta / 0x9E3779B1 (mod 2^32) for some |delta| < 4096.  Counting the deltas whose
+    quotient is smaller than the vocabulary bounds a class's population; two keys per id must
+    fit the smallest table (256 slots)."""
+    src = open(os.path.join(ROOT, "paper_2503_05330_amd", "csrc", "csd_dag.cuh")).read()
+    assert "0x9E3779B1u) >> 12 & (n_class - 1)" in src          # the class function the header describes
+    common = open(os.path.join(ROOT, "paper_2503_05330_amd", "csrc", "csd_common.cuh")).read()
+    assert "kMaxClassBits = 20" in common and "LdsT<256, 256, 1024, 1> LdsWaveSmall" in common
+    inv = pow(0x9E3779B1, -1, 1 << 32)
+
+    def most_ids_in_a_class(vocab):
+        n = 1
+        for delta in range(-4095, 4096):
+            d = (delta * inv) % (1 << 32)
+            d -= (1 << 32) if d >= (1 << 31) else 0
+            n += 1 if delta != 0 and abs(d) < vocab else 0
+        return n
+    assert most_ids_in_a_class(1 << 24) == 65 and 2 * 65 <= 256
+    assert most_ids_in_a_class((1 << 29) - 1) == 2045
+    assert most_ids_in_a_class(152064) == 1                   # the largest vocabulary of the workloads

@@ -334,6 +334,52 @@ def test_status_bits_and_reset(oracle):
     assert out["tokens"].cpu().numpy()[0, 0].tolist() == [8, 9, 7]
 
 
+def test_table_full_status_needs_a_constructed_input(oracle):
+    """CSD_STATUS_TABLE_FULL, the one documented inexact path: a layer whose continuation tokens
+    include more distinct ids of ONE hash class (bits 12..31 of id * 0x9E3779B1) than the
+    bounded-memory tier's table holds.  Ids below 2^24 cannot do that; 300 ids below 2^29 built
+    to share a class do, in a launch of 2048 rows (whose on-chip table has 256 slots): the draft
+    of that row ends early and the status bit is raised.  The scan kernel walks the same row one
+    thread per match, without tables, and agrees with the oracle."""
+    inv = pow(0x9E3779B1, -1, 1 << 32)
+    base = 12345
+    ids = []
+    for delta in range(-4095, 4096):
+        v = (base + delta * inv) % (1 << 32)
+        if v < (1 << 29) - 1 and ((v * 0x9E3779B1) % (1 << 32)) >> 12 == ((base * 0x9E3779B1) % (1 << 32)) >> 12:
+            ids.append(v)
+    ids = sorted(set(ids))[:300]
+    assert len(ids) == 300
+    a = 7
+    T = 2 * len(ids)
+    P = 1024                                       # 2048 rows: the one-wave kernel's small layout
+    dev = torch.device("cuda:0")
+    for vocab, successors in (((1 << 29) - 1, np.array(ids)), (1 << 24, np.arange(100, 400) * 9973 % (1 << 24))):
+        tok = np.zeros((P, 2, T), dtype=np.int32)
+        tok[:, 0, :3] = [3, 4, a]
+        tok[:, 1, 0::2] = 5
+        tok[:, 1, 1::2] = 6
+        tok[0, 1, 0::2] = a                        # problem 0: `a` followed by 300 different tokens
+        tok[0, 1, 1::2] = successors
+        cnt = np.tile(np.array([[3, T]], dtype=np.int32), (P, 1))
+        want = oracle.draft_all(tok[:1], None, cnt[:1], 1, 4)
+        assert want["draft_len"][0, 0] == 4        # 300 successors of weight 1: the lowest id, then `a`, ..
+        for flags in (SCAN, INDEX):
+            ix = binding.Index(P, 2, T, vocab, 1, 4, 1.0, 0, flags, device=dev)
+            ix.append(torch.from_numpy(tok).to(dev), None, torch.from_numpy(cnt).to(dev), T)
+            out = ix.draft(1, 4)
+            status = ix.status()
+            got_len, got_tok = out["length"].cpu().numpy(), out["tokens"].cpu().numpy()
+            assert (got_len[1:] == 0).all()        # the other problems: `a` occurs nowhere else
+            if flags == INDEX and vocab > (1 << 24):
+                assert status == binding.STATUS_TABLE_FULL and got_len[0, 0] == 0
+            else:
+                assert status == 0 and got_len[0, 0] == 4
+                assert got_tok[0, 0].tolist() == want["draft"][0, 0].tolist()
+            del ix, out
+        torch.cuda.empty_cache()
+
+
 def test_determinism_two_runs_identical(oracle):
     w = synth.WORKLOADS["C2"]
     tokens, probs = synth.make_paths(w)
