@@ -302,6 +302,9 @@ def main():
                              "launch and memory latency, not by bandwidth"},
     }
     if args.headline_only:
+        if args.batch_sweep:
+            res["batch"] = batch_points(binding, torch, dev, r.w, r.tokens, r.probs, matches_per_step / P, r.flags,
+                                        args.max_edits, (1, 4, 16, 64, 256, 1024, 4096))
         print(json.dumps(res))
         return
 
