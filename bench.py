@@ -97,7 +97,7 @@ class Replay:
         self.accs = mk((T, P, N), torch.int32)
         rows = P * N
         by_scan = matcher == "scan" or (matcher == "auto" and backoff) or (
-            max_edits > 0 and matcher == "auto" and not (self.k >= 4 and rows > 128))
+            max_edits > 0 and matcher == "auto" and not (self.k >= 4 and (rows > 128 or N * T >= 1 << 18)))
         self.kernel = "step_scan_kernel" if by_scan else "step_wave_kernel"
         self.variant = (w.name + ("_one_edit" if max_edits else "") + ("" if pool == "dag" else "_" + pool)
                         + ("_self" if include_self else "") + ("_backoff" if backoff else ""))
@@ -406,6 +406,7 @@ def main():
             per[name] = tail_of(name)
         res["per_workload"] = per
         res["one_edit"] = {"C2": tail_of("C2", max_edits=1), "C3": tail_of("C3", max_edits=1),
+                           "C5": tail_of("C5", max_edits=1),
                            "note": "Eq. 4 with one edit, the tolerance of the paper's experiments, under the "
                                    "matcher CSD_MATCH_AUTO picks"}
         problems = (1, 4, 16, 64, 256, 1024, 4096) if args.batch_sweep else (64, 4096)

@@ -130,8 +130,9 @@ typedef struct {
                              files every position under the max_query_len + 1 variants
                              of its gram (the gram itself and the gram without one of its
                              tokens): CSD_MATCH_AUTO takes the index from max_query_len 4
-                             on if there are more than 128 rows (problem, path), else the
-                             scan; CSD_MATCH_INDEX takes it from max_query_len 2 on
+                             on if there are more than 128 rows (problem, path) or a
+                             problem has 2^18 positions (n_paths * max_len) or more, else
+                             the scan; CSD_MATCH_INDEX takes it from max_query_len 2 on
                              (1: CSD_ERR_UNIMPLEMENTED).                                 */
   int32_t pool_mode;      /* how the candidate pool is organised before the greedy
                              extraction: CSD_POOL_DAG (the method: equal tokens of a layer

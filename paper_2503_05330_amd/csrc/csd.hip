@@ -75,18 +75,24 @@ constexpr int64_t kSlicedScanRows = 128;
 // One-edit matching can go through the index when the query has at least two tokens (with
 // one token every position is within one edit: a scan's job).  The index files positions
 // under grams of max_query_len - 1 tokens then; for three-token queries those are pairs,
-// the chains of frequent pairs get long, and the scan is the faster matcher; with few rows
-// the sliced scan is as fast as the index for longer queries too.  CSD_MATCH_AUTO therefore
-// takes the index from four query tokens on when there are too many rows to slice the scan.
+// the chains of frequent pairs get long, and the scan is the faster matcher; with few rows and
+// short histories the sliced scan beats the index for longer queries too (measured with one
+// edit and four-token queries: 32 x 2048 positions per problem 20.7 us by scan, 29.5 through
+// the index; 64 x 4096 positions 52.3 against 43.1: the scan's cost grows with the positions,
+// the index's with the matches).  CSD_MATCH_AUTO therefore takes the index from four query
+// tokens on when there are too many rows to slice the scan or a problem has 2^18 positions
+// or more.
 // With query back-off a query without matches is searched again in shorter forms, which the
 // index (grams of max_query_len tokens only) cannot serve: CSD_MATCH_AUTO takes the scan then.
+constexpr int64_t kIndexedFuzzyPositions = 1 << 18;
 int matcher_of(const csd_config* c) { return c->flags & 3; }
 bool uses_index(const csd_config* c) {
   if (matcher_of(c) == CSD_MATCH_SCAN) return false;
   if (matcher_of(c) == CSD_MATCH_AUTO && (c->flags & CSD_QUERY_BACKOFF)) return false;
   if (c->max_edits == 0) return true;
   if (matcher_of(c) == CSD_MATCH_INDEX) return c->max_query_len >= 2;
-  return c->max_query_len >= 4 && (int64_t)c->n_problems * c->n_paths > kSlicedScanRows;
+  return c->max_query_len >= 4 && ((int64_t)c->n_problems * c->n_paths > kSlicedScanRows ||
+                                   (int64_t)c->n_paths * c->max_len >= kIndexedFuzzyPositions);
 }
 int32_t tail_len_of(const csd_config* c) {
   return c->max_query_len + ((uses_index(c) && c->max_edits > 0) ? 1 : 0);
