@@ -68,6 +68,7 @@ typedef enum {
 /* Limits of this build (csd_create rejects configurations beyond them). */
 #define CSD_MAX_QUERY_LEN 8
 #define CSD_MAX_DRAFT_LEN 32
+#define CSD_MAX_EDITS 3             /* largest edit tolerance of the suffix match (Eq. 4) */
 #define CSD_MAX_VOCAB ((1 << 29) - 1)
 #define CSD_MAX_POSITIONS (1 << 24) /* n_paths * max_len per problem */
 #define CSD_MAX_STEP_TOKENS 32767   /* csd_step: tokens per path per call */
@@ -121,11 +122,14 @@ typedef struct {
                              sum_u w(u,v) (the rule after Eq. 5); 1: by w(cur,v)      */
   int32_t flags;          /* one CSD_MATCH_* value, optionally | CSD_INCLUDE_SELF and/or
                              | CSD_QUERY_BACKOFF; all other bits must be 0            */
-  int32_t max_edits;      /* Eq. 4's edit-distance tolerance of the suffix match: 0 = exact
-                             (Eq. 3), 1 = one substitution, insertion or deletion (the
-                             paper's experiments use 1).  With 1 a position e of another
-                             path matches when some substring ending just before e is
-                             within one edit of the query, each e counting once.  Such
+  int32_t max_edits;      /* Eq. 4's edit-distance tolerance eps of the suffix match, in
+                             [0, CSD_MAX_EDITS]: 0 = exact (Eq. 3), 1 = one substitution,
+                             insertion or deletion (the paper's experiments use 1), 2 and
+                             3 likewise (Levenshtein distance; always matched by scan:
+                             CSD_ERR_UNIMPLEMENTED with CSD_MATCH_INDEX).  A position e of
+                             another path matches when some substring ending just before
+                             e is within eps edits of the query, each e counting once (a
+                             query of at most eps tokens matches everywhere).  One-edit
                              matches are found by scan, or through the index, which then
                              files every position under the max_query_len + 1 variants
                              of its gram (the gram itself and the gram without one of its

@@ -90,6 +90,7 @@ bool uses_index(const csd_config* c) {
   if (matcher_of(c) == CSD_MATCH_SCAN) return false;
   if (matcher_of(c) == CSD_MATCH_AUTO && (c->flags & CSD_QUERY_BACKOFF)) return false;
   if (c->max_edits == 0) return true;
+  if (c->max_edits > 1) return false;                  // more than one edit: by scan only
   if (matcher_of(c) == CSD_MATCH_INDEX) return c->max_query_len >= 2;
   return c->max_query_len >= 4 && ((int64_t)c->n_problems * c->n_paths > kSlicedScanRows ||
                                    (int64_t)c->n_paths * c->max_len >= kIndexedFuzzyPositions);
@@ -112,7 +113,8 @@ int validate(const csd_config* c) {
     return CSD_ERR_UNIMPLEMENTED;
   if (c->max_edits < 0) return CSD_ERR_INVALID_ARG;
   if (c->pool_mode < CSD_POOL_DAG || c->pool_mode > CSD_POOL_LIST) return CSD_ERR_INVALID_ARG;
-  if (c->max_edits > 1) return CSD_ERR_UNIMPLEMENTED;
+  if (c->max_edits > CSD_MAX_EDITS) return CSD_ERR_UNIMPLEMENTED;
+  if (c->max_edits > 1 && matcher_of(c) == CSD_MATCH_INDEX) return CSD_ERR_UNIMPLEMENTED;
   if (c->max_edits == 1 && matcher_of(c) == CSD_MATCH_INDEX && c->max_query_len < 2) return CSD_ERR_UNIMPLEMENTED;
   return CSD_OK;
 }

@@ -99,6 +99,49 @@ __device__ __forceinline__ bool gram_near_query(const Ctx& c, int32_t j, int32_t
   return near_query<QK>(c, e, t);
 }
 
+// Eq. 4 with any tolerance up to CSD_MAX_EDITS: is SOME substring of path j that ends just
+// before index e within eps edits of the query?  With both strings read backwards from e
+// (Q[a] = a-th query token from its end, t[b] = b-th token before e) the substrings that end
+// at e are the prefixes of t, so one dynamic programme answers for all their lengths at once:
+// D[i][b] = Levenshtein distance between the first i tokens of Q and the first b of t; the
+// position matches when D[q][b] <= eps for some b <= min(e, q + eps).  Column by column
+// over b, the column kept in registers.
+// t[b] = the b-th token before e for b < min(q + eps, e), else anything.
+template <int K = CSD_MAX_QUERY_LEN>
+__device__ __forceinline__ bool within_edits(const Ctx& c, int32_t e,
+                                             const int32_t (&t)[K + CSD_MAX_EDITS]) {
+  const int32_t q = c.q;
+  int32_t D[K + 1];
+#pragma unroll
+  for (int i = 0; i <= K; ++i) D[i] = i;                 // against the empty substring
+  int32_t best = q;
+  const int32_t longest = q + c.eps < e ? q + c.eps : e;   // substrings of up to this many tokens
+#pragma unroll
+  for (int b = 1; b <= K + CSD_MAX_EDITS; ++b) {
+    int32_t diag = D[0];
+    D[0] = b;
+#pragma unroll
+    for (int i = 1; i <= K; ++i) {
+      const int32_t up = D[i];
+      int32_t v = diag + ((i <= q && c.Q[i - 1] == t[b - 1]) ? 0 : 1);   // substitute / keep
+      v = v < up + 1 ? v : up + 1;                                       // the text has one token more
+      v = v < D[i - 1] + 1 ? v : D[i - 1] + 1;                           // the query has one token more
+      D[i] = v;
+      diag = up;
+    }
+    const int32_t here = pick(D, q);
+    best = (b <= longest && here < best) ? here : best;
+  }
+  return best <= c.eps;
+}
+
+template <int QK = CSD_MAX_QUERY_LEN>
+__device__ __forceinline__ bool gram_within_edits(const Ctx& c, int32_t j, int32_t e, int32_t old_j) {
+  int32_t t[QK + CSD_MAX_EDITS];
+  tokens_before(c, j, e, old_j, c.q + c.eps, t);
+  return within_edits<QK>(c, e, t);
+}
+
 template <int QC>
 __device__ __forceinline__ GramHash query_hash(const Ctx& c) {
   uint32_t acc = kGramSeed;
@@ -180,7 +223,7 @@ __device__ __forceinline__ bool may_match(const Ctx& c, const int32_t (&t)[kFilt
     for (int a = 0; a < kFilterTokens; ++a) ok = ok && (a >= c.q || t[a] == c.Q[a]);
     return ok;
   }
-  if (c.q < 2) return true;
+  if (c.q < 2 || c.eps > 1) return true;                   // (more than one edit: no filter)
   if (c.q < 3) return t[0] == c.Q[0] || t[0] == c.Q[1] || t[1] == c.Q[0] || t[1] == c.Q[1];
   bool c0 = t[0] == c.Q[0], c1 = t[1] == c.Q[1], c2 = t[2] == c.Q[2];
   bool a01 = t[0] == c.Q[1], a12 = t[1] == c.Q[2], b10 = t[1] == c.Q[0], b21 = t[2] == c.Q[1];
@@ -217,7 +260,7 @@ __device__ __forceinline__ void match_scan(const LDS& s, const Ctx& c, Sink& sin
   // (consecutive spans go to different slices: a row with fewer spans than waves still keeps
   // all its workgroups busy)
   const int lane = c.tid & 63, wave = (c.tid >> 6) * n_slices + slice;
-  const int32_t first_e = FUZZY ? (c.q > 1 ? c.q - 1 : 0) : c.q;   // shortest substring that can match
+  const int32_t first_e = c.q > c.eps ? c.q - c.eps : 0;          // shortest substring that can match
   const int32_t spans_per_path = (c.y.max_len + kSpan - 1) / kSpan;
   const int32_t spans = c.y.N * spans_per_path;            // < 2^24
   const float inv_spp = 1.0f / (float)spans_per_path;
@@ -285,7 +328,7 @@ __device__ __forceinline__ void match_scan(const LDS& s, const Ctx& c, Sink& sin
           bool pass = r == 0;
           if (r >= 1) {
             pass = t0 == c.Q[0];
-            if (FUZZY) pass = pass || c.q < 2 || t0 == c.Q[1] || (r >= 2 && (t1 == c.Q[0] || t1 == c.Q[1]));
+            if (FUZZY) pass = pass || c.q < 2 || c.eps > 1 || t0 == c.Q[1] || (r >= 2 && (t1 == c.Q[0] || t1 == c.Q[1]));
           }
           todo |= ((early & bit) && pass) ? bit : 0u;
         }
@@ -301,7 +344,9 @@ __device__ __forceinline__ void match_scan(const LDS& s, const Ctx& c, Sink& sin
       bool hit = have;
       if (have) lens_of(s, c.y, j, old_j, new_j);
       if (have && !(filter_decides && (filtered >> bit & 1u)))
-        hit = FUZZY ? gram_near_query<QK>(c, j, e, old_j) : gram_equals_query<QK>(c, j, e, old_j);
+        hit = !FUZZY ? gram_equals_query<QK>(c, j, e, old_j)
+                     : (c.eps > 1 ? gram_within_edits<QK>(c, j, e, old_j)     // uniform over the launch
+                                  : gram_near_query<QK>(c, j, e, old_j));
       sink.push(c.y, hit, make_match(c.y, j, e, old_j, new_j));
     }
   }
@@ -324,7 +369,7 @@ __device__ __forceinline__ void match_scan_any(const LDS& s, const Ctx& c, Sink&
 template <bool FUZZY, class LDS, class Sink>
 __device__ __forceinline__ void match_plain(const LDS& s, const Ctx& c, Sink& sink) {
   const int lane = c.tid & 63;
-  const int32_t first_e = FUZZY ? (c.q > 1 ? c.q - 1 : 0) : c.q;   // shortest substring that can match
+  const int32_t first_e = c.q > c.eps ? c.q - c.eps : 0;          // shortest substring that can match
   for (int32_t j = 0; j < c.y.N; ++j) {
     if (j == c.skip) continue;
     int32_t old_j, new_j;
@@ -332,7 +377,9 @@ __device__ __forceinline__ void match_plain(const LDS& s, const Ctx& c, Sink& si
     for (int32_t e0 = first_e; e0 < new_j; e0 += kWave) {  // trip counts are uniform over the wave
       int32_t e = e0 + lane;
       bool hit = false;
-      if (e < new_j) hit = FUZZY ? gram_near_query(c, j, e, old_j) : gram_equals_query(c, j, e, old_j);
+      if (e < new_j)
+        hit = !FUZZY ? gram_equals_query(c, j, e, old_j)
+                     : (c.eps > 1 ? gram_within_edits(c, j, e, old_j) : gram_near_query(c, j, e, old_j));
       sink.push(c.y, hit, make_match(c.y, j, e, old_j, new_j));
     }
   }

@@ -43,12 +43,14 @@ def test_workspace_size_and_validation(lib):
     for unknown in (16, 3, 3 | b.INCLUDE_SELF, -1):        # an unknown option bit; no such matcher
         cfg = b.Config(**{**good, "flags": unknown})
         assert lib.csd_workspace_bytes(ctypes.byref(cfg), ctypes.byref(out)) == b.ERR_UNIMPLEMENTED, unknown
-    for bad, code in ((dict(max_edits=-1), b.ERR_INVALID_ARG), (dict(max_edits=2), b.ERR_UNIMPLEMENTED),
+    for bad, code in ((dict(max_edits=-1), b.ERR_INVALID_ARG), (dict(max_edits=4), b.ERR_UNIMPLEMENTED),
+                      (dict(max_edits=2, flags=b.MATCH_INDEX), b.ERR_UNIMPLEMENTED),
                       (dict(max_edits=1, flags=b.MATCH_INDEX, max_query_len=1), b.ERR_UNIMPLEMENTED),
                       (dict(pool_mode=-1), b.ERR_INVALID_ARG), (dict(pool_mode=3), b.ERR_INVALID_ARG)):
         cfg = b.Config(**{**good, **bad})
         assert lib.csd_workspace_bytes(ctypes.byref(cfg), ctypes.byref(out)) == code, bad
-    for fine in (dict(max_edits=1), dict(max_edits=1, flags=b.MATCH_INDEX), dict(pool_mode=b.POOL_TREE),
+    for fine in (dict(max_edits=1), dict(max_edits=2), dict(max_edits=3, flags=b.MATCH_SCAN),
+                 dict(max_edits=1, flags=b.MATCH_INDEX), dict(pool_mode=b.POOL_TREE),
                  dict(pool_mode=b.POOL_LIST, max_edits=1), dict(flags=b.INCLUDE_SELF),
                  dict(flags=b.MATCH_INDEX | b.QUERY_BACKOFF), dict(flags=b.MATCH_SCAN | b.INCLUDE_SELF | b.QUERY_BACKOFF)):
         cfg = b.Config(**{**good, **fine})

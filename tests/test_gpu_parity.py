@@ -570,6 +570,76 @@ def test_fuzzy_auto_picks_the_variant_index_and_many_rows(oracle):
     _fuzzy_sampled(oracle, w, range(0, w.max_len, 5), ((AUTO, "replay"),), dump=(96, range(0, 2048, 97)))
 
 
+def test_two_and_three_edits(oracle):
+    """Eq. 4 with tolerances above one edit (always by scan): C1 at every step with match sets,
+    C2 at sampled steps up to the full history, and random small configurations in which
+    geometry, query and draft lengths, scoring, pool, options and call pattern vary together
+    (queries no longer than the tolerance match every position)."""
+    AUTO = binding.MATCH_AUTO
+    dev = torch.device("cuda:0")
+    for eps, how in ((2, "replay"), (3, "calls")):
+        w = synth.WORKLOADS["C1"]
+        tokens, probs = synth.make_paths(w)
+        T, k, L = w.max_len, w.query_len, w.draft_len
+        want = oracle_steps(oracle, tokens, probs, list(range(T)), k, L, 0.5, 0, eps=eps)
+        for flags in (AUTO, SCAN):
+            print("edits", eps, "C1 flags", flags, how, flush=True)
+            got = gpu_replay(tokens, probs, k, L, 0.5, 0, flags, how=how, max_edits=eps)
+            assert got["status"] == 0
+            for t in range(T):
+                assert_step_equal(got, want[t], t, "C1 %d edits flags=%d" % (eps, flags))
+        ix = got["index"]
+        lens_t = np.full((1, w.n_paths), T, dtype=np.int32)
+        for q in range(1, k + 1):
+            je, moff = ix.dump_matches(q, cap=1 << 22)
+            for i in range(w.n_paths):
+                assert np.array_equal(je[moff[i]:moff[i + 1]], oracle.matches(tokens[0], lens_t[0], i, q, eps)), (eps, q, i)
+    w = synth.WORKLOADS["C2"]
+    tokens, probs = synth.make_paths(w)
+    steps = [0, 1, 2, 3, 5, 200, 500, 800, 1022, 1023]
+    want = oracle_steps(oracle, tokens, probs, steps, w.query_len, w.draft_len, 1.0, 0, eps=2)
+    print("edits 2 C2", flush=True)
+    got = gpu_replay(tokens, probs, w.query_len, w.draft_len, 1.0, 0, AUTO, how="replay", max_edits=2)
+    assert got["status"] == 0
+    for t in steps:
+        assert_step_equal(got, want[t], t, "C2 two edits")
+    del got
+    rng = np.random.default_rng(2503)
+    for case in range(90):
+        P, N = int(rng.integers(1, 3)), int(rng.integers(1, 7))
+        T = int(rng.integers(4, 70))
+        V = int(rng.choice([3, 5, 40]))
+        k, L = int(rng.integers(1, 9)), int(rng.integers(1, 17))
+        eps, pool_mode, mode = int(rng.integers(2, 4)), int(rng.integers(0, 3)), int(rng.integers(0, 2))
+        flags = int(rng.choice([AUTO, SCAN]))
+        include_self, backoff = bool(case % 3 == 1), bool(case % 4 == 2)
+        flags |= (binding.INCLUDE_SELF if include_self else 0) | (binding.QUERY_BACKOFF if backoff else 0)
+        n_per_step = int(rng.choice([1, 1, 3]))
+        how = str(rng.choice(["calls", "step"]))
+        segs = [rng.integers(0, V, size=int(rng.integers(2, 9))) for _ in range(4)]
+        tokens = np.zeros((P, N, T), dtype=np.int32)
+        for p in range(P):
+            for j in range(N):
+                seq = np.concatenate([segs[int(x)] for x in rng.integers(0, 4, size=T)])[:T]
+                tokens[p, j] = np.where(rng.random(T) < 0.15, rng.integers(0, V, size=T), seq)
+        probs = (rng.integers(1, 17, size=tokens.shape) / 16.0).astype(np.float32)
+        steps_n = T // n_per_step
+        counts = rng.integers(0, n_per_step + 1, size=(steps_n, P, N)).astype(np.int32) if n_per_step > 1 else None
+        what = "edits case %d: P%d N%d T%d V%d k%d L%d eps%d pool%d mode%d flags%d n%d %s" % (
+            case, P, N, T, V, k, L, eps, pool_mode, mode, flags, n_per_step, how)
+        print(what, flush=True)
+        got = gpu_replay(tokens, probs, k, L, 0.75, mode, flags, steps=steps_n, counts=counts,
+                         n_per_step=n_per_step, how=how, max_edits=eps, pool_mode=pool_mode)
+        assert got["status"] in (0, binding.STATUS_CAPACITY), what
+        for t in range(steps_n):
+            want_t = oracle.draft_all(tokens, probs, got["lens"][t], k, L, 0.75, mode, eps=eps, pool_mode=pool_mode,
+                                      include_self=include_self, backoff=backoff)
+            assert_step_equal(got, want_t, t, what)
+    cfg = binding.Config(1, 4, 64, 100, 3, 5, 1.0, 0, INDEX, 2, 0)
+    with pytest.raises(binding.CsdError):
+        binding.workspace_bytes(cfg)                       # more than one edit through the index: not built
+
+
 def test_fuzzy_small_cases(oracle):
     """Hand cases and tiny random inputs, including queries of one token (every position of
     every other path is within one edit of it) and matches at index 0."""
