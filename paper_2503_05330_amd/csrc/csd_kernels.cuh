@@ -302,6 +302,13 @@ __device__ __forceinline__ void row_step(LDS& s, const IndexView& ix, const Step
   int32_t p;
   Ctx c = make_ctx(ix, in, row, p);
   c.tid = lane;
+#ifdef CSD_STAMPS
+  c.unit = row;
+  if (lane == 0 && row < (1 << 14)) {
+    g_stamps[row * kStampSlots + 0] = CSD_CLOCK();
+    g_stamps[row * kStampSlots + 6] = 0ull;
+  }
+#endif
   const int32_t L = a.L;
   int32_t target = (a.targets && c.tid < L) ? a.targets[(int64_t)row * L + c.tid] : 0;
   WinInfo wi;
@@ -311,6 +318,12 @@ __device__ __forceinline__ void row_step(LDS& s, const IndexView& ix, const Step
   int32_t M = FUZZY ? wave_front_end_fuzzy<LCAP>(s, c, ix, p, a.k, L, wi, tickets, ticket_used)
                     : wave_front_end<LCAP, QC, APPENDS, POOLS>(s, c, ix, p, a.k, L, wi, ticket, ticket_used);
   block_sync<kWave>();
+#ifdef CSD_STAMPS
+  if (lane == 0 && row < (1 << 14)) {
+    g_stamps[row * kStampSlots + 1] = CSD_CLOCK();
+    g_stamps[row * kStampSlots + 9] = (unsigned long long)M;
+  }
+#endif
   if (APPENDS && POOLS && !FUZZY && in.n > 1) {
     // a step of several tokens appended by the drafting wave itself (nothing this step's
     // drafts read is written here)
@@ -387,6 +400,9 @@ __device__ __forceinline__ void row_step(LDS& s, const IndexView& ix, const Step
         }
       });
   }
+#ifdef CSD_STAMPS
+  if (lane == 0 && row < (1 << 14)) g_stamps[row * kStampSlots + 5] = CSD_CLOCK();
+#endif
   // the posting stores wait on atomics issued long ago: do them before the output stores
   if (ticket_used && FUZZY)
     variants_finish(tickets, const_cast<int32_t*>(c.gram), c.bucket_mask, c.y.pos(c.i, c.len_i - 1),
@@ -397,6 +413,9 @@ __device__ __forceinline__ void row_step(LDS& s, const IndexView& ix, const Step
   write_outputs<kWave>(a, row, o, c.tid);
   int32_t accepted = 0;
   if (a.targets) accepted = write_accept(a, row, o, target, c.tid);
+#ifdef CSD_STAMPS
+  if (lane == 0 && row < (1 << 14)) g_stamps[row * kStampSlots + 6] = CSD_CLOCK();
+#endif
   if constexpr (std::is_same<TAIL, LoopTail>::value) {
     const int32_t len = c.len_i;                        // after this step's append
     int32_t grow = accepted + 1;
