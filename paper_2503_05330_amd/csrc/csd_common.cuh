@@ -219,6 +219,22 @@ __device__ __forceinline__ uint32_t wave_sum(uint32_t x) {
   return (uint32_t)__builtin_amdgcn_readlane((int)x, 63);
 }
 
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_max(uint32_t x) {   // lanes the pattern does not reach see 0
+  uint32_t y = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, ROW_MASK, 0xF, false);
+  return x > y ? x : y;
+}
+// Maximum over the 64 lanes of a wave (the lane moves of wave_sum); every lane gets it.
+__device__ __forceinline__ uint32_t wave_max(uint32_t x) {
+  x = dpp_max<0x111, 0xF>(x);
+  x = dpp_max<0x112, 0xF>(x);
+  x = dpp_max<0x114, 0xF>(x);
+  x = dpp_max<0x118, 0xF>(x);
+  x = dpp_max<0x142, 0xA>(x);
+  x = dpp_max<0x143, 0xC>(x);
+  return (uint32_t)__builtin_amdgcn_readlane((int)x, 63);
+}
+
 // arr[idx] for idx < N without indexing registers by a variable (0 when idx is out of range)
 template <int N, int SIZE>
 __device__ __forceinline__ int32_t pick_n(const int32_t (&arr)[SIZE], int32_t idx) {
@@ -404,7 +420,7 @@ typedef LdsT<1024, 4096, 2048, 1> LdsWaveFuzzy;
 typedef LdsT<256, 128, 1024, 1, 16> LdsMulti;
 // One 1024-thread workgroup per row (scan mode, where a fuzzy query can have
 // thousands of matches): 108 KB, one row per CU.
-typedef LdsT<4096, 4096, 16, kScanBlock / kWave> LdsScan;
+typedef LdsT<4096, 4096, 6144, kScanBlock / kWave> LdsScan;
 
 struct Ctx {                    // one (problem, query path)
   Paths y;

@@ -478,8 +478,9 @@ __device__ __forceinline__ Cand scan_successors(const LDS& s, Region r, int d, i
   return best;
 }
 
-// Tier 1b, for up to BLOCK matches with one thread per match and no per-layer table
-// of all instances: a layer only needs the weights of the successors of the current
+// Tier 1b, for up to BLOCK matches where walk_tab (below) does not apply: edge scoring,
+// token ids of 2^21 or more, more than its instances, or too many distinct continuations.
+// One thread per match and no per-layer table of all instances: a layer only needs the weights of the successors of the current
 // node, and those are few.  Per layer, (A) the candidates — matches whose previous token
 // is the current node — enter their token in a hash set (a key carries the layer number,
 // so the set is never cleared: entries of earlier layers count as free slots); (B) every
@@ -611,6 +612,194 @@ __device__ __forceinline__ void walk_wide(LDS& s, const Ctx& c, int32_t M, int32
     cur = best.v;
     u = v;
   }
+}
+
+// Tier 1c, the usual form for 65 .. BLOCK matches: Eq. 5's node weights do not depend on the
+// walk (a node's in-weight counts EVERY match that carries its token in that layer), so they
+// are tabulated first, for all layers at once and by all waves, and the greedy walk after
+// that is short.
+//   Fill: BLOCK / M threads share a match, each taking every (BLOCK / M)-th layer; an
+//   instance (match, layer d, token v) finds or enters the 32-bit key (d, v) in a hash set,
+//   adds its (1, p) to the key's cell and notes the slot.  No barrier between layers.
+//   Walk, one thread per match: per layer the candidates (matches whose previous token is
+//   the current node; all of them in layer 1) rank their node, and the heaviest (ties: lowest
+//   token) is found with a wave maximum and one 64-bit LDS atomic maximum per wave: weight
+//   (+ 1, so that 0 means "no successor") above the inverted token.  One barrier per layer;
+//   the next layer's slot, key, cell and rank are fetched and computed before it, behind the
+//   atomic.
+// Needs score_mode 0 (edge weights depend on the walk: walk_wide), tokens below 2^21 (the
+// weight of at most 1024 instances takes 43 bits) and at most kTabInstances instances.  The
+// set has two to four times as many slots as there are instances, but at most kTabSlots; an
+// instance that finds no place within kTabProbes gives up, and the function then returns
+// false with nothing decided (thousands of distinct continuations: the caller takes walk_wide).  Same sums as the other tiers, in exact
+// integers: the same draft.  Cells lie over the table, the layers' maxima over the links,
+// keys and slots behind the first BLOCK entries of the match list (which stay).
+// After a return of true nothing may synchronise the workgroup.
+constexpr int kTabSlots = 8192;
+constexpr int kTabInstances = 8192;
+constexpr int kTabProbes = 128;
+constexpr int kTabTokenBits = 21;
+
+template <int BLOCK>
+__device__ __forceinline__ bool walk_tab_fits(int32_t M, int32_t L, int32_t vocab, int score_mode) {
+  return score_mode == 0 && M <= BLOCK && M * L <= kTabInstances && vocab <= (1 << kTabTokenBits);
+}
+
+template <int BLOCK, class LDS>
+__device__ __forceinline__ bool walk_tab(LDS& s, const Ctx& c, int32_t M, int32_t L, uint32_t alpha_q,
+                                         DraftOut& o) {
+  static_assert(LDS::kMatch >= BLOCK && sizeof(s.table) >= kTabSlots * sizeof(u64) &&
+                sizeof(s.link) >= CSD_MAX_DRAFT_LEN * sizeof(u64),
+                "cells over the table, the layers' maxima over the links");
+  static_assert((LDS::kMatch - BLOCK) * sizeof(Match) + sizeof(s.win) >=
+                kTabSlots * sizeof(uint32_t) + kTabInstances * sizeof(uint16_t),
+                "keys and slots behind the listed matches");
+  static_assert(offsetof(LDS, win) == offsetof(LDS, match) + sizeof(s.match), "no gap before the windows");
+  constexpr uint32_t kNoKey = ~0u;
+  constexpr uint32_t kTokBits = (1u << kTabTokenBits) - 1u;
+  u64* cell = reinterpret_cast<u64*>(s.table);         // [n_slots] (count, probability sum)
+  u64* best = reinterpret_cast<u64*>(s.link);          // [L] the layer's heaviest successor, packed
+  uint32_t* keys = reinterpret_cast<uint32_t*>(&s.match[BLOCK]);   // [n_slots] (d - 1) << 24 | token
+  uint16_t* slot_of = reinterpret_cast<uint16_t*>(keys + kTabSlots);   // [L][M]
+  // two to four times as many slots as instances (a power of two, at most kTabSlots): what is
+  // not used is not cleared
+  int slot_bits = 32 - __clz(4 * M * L - 1);
+  slot_bits = slot_bits < 10 ? 10 : (slot_bits > 13 ? 13 : slot_bits);
+  const uint32_t n_slots = 1u << slot_bits;
+  {                                                    // empty set, zero cells
+    uint2* cells2 = reinterpret_cast<uint2*>(cell);
+    uint2* keys2 = reinterpret_cast<uint2*>(keys);
+    for (uint32_t x = c.tid; x < n_slots; x += BLOCK) cells2[x] = uint2{0u, 0u};
+    for (uint32_t x = c.tid; x < n_slots / 2; x += BLOCK) keys2[x] = uint2{kNoKey, kNoKey};
+    if (c.tid < CSD_MAX_DRAFT_LEN) best[c.tid] = 0ull;
+    if (c.tid == 0) s.overflow = 0;
+  }
+  // the threads of a match: r-th of R, layers r + 1, r + 1 + R, ...
+  const int32_t R = BLOCK / M;
+  int32_t r = (int32_t)((float)c.tid * (1.0f / (float)M));   // tid / M, fixed up
+  r += (r + 1) * M <= c.tid;
+  r -= r * M > c.tid;
+  const int32_t t = c.tid - r * M;
+  const bool works = r < R;
+  const Match m = s.match[works ? t : 0];
+  const int32_t rem = (int32_t)m.rem_new < L ? (int32_t)m.rem_new : L;
+  const int32_t j = c.y.pos_path(m.pos), e = c.y.pos_index(m.pos);
+  const int32_t old_j = e + (int32_t)m.rel_old;       // exact wherever it decides (see layer_instance)
+  const int32_t* tok_at = c.y.tok + c.y.cell(j, e);
+  const uint32_t* pq_at = c.y.pq + c.y.cell(j, e);
+  // One instance: the key (d, v) is found or entered, its cell takes the instance's (1, p).
+  // Called by all lanes of a wave together; the probes are a loop of the wave (until no lane
+  // is left looking), which costs fewer instructions than a loop of each lane.
+  auto instance = [&](bool active, int32_t d, uint32_t v, uint32_t p) {
+    const uint32_t mine = ((uint32_t)(d - 1) << 24) | v;
+    uint32_t h = (mine * 0x9E3779B1u) >> (32 - slot_bits);   // the product's high bits: a slot
+    bool looking = active;
+    for (int probe = 0; probe < kTabProbes && wave_ballot(looking) != 0; ++probe) {   // uniform
+      uint32_t seen = keys[h];
+      if (looking && seen == kNoKey) seen = atomicCAS(&keys[h], kNoKey, mine);
+      const bool placed = seen == mine || seen == kNoKey;   // there already, or entered just now
+      h = (looking && !placed) ? (h + 1) & (n_slots - 1) : h;
+      looking = looking && !placed;
+    }
+    if (active && !looking) {
+      atomicAdd(&cell[h], pack_cs(1u, p));
+      slot_of[(d - 1) * M + t] = (uint16_t)h;
+    } else if (active) {
+      s.overflow = 1;
+    }
+  };
+  // A thread's tokens and probabilities are requested two turns ahead, as in walk_wide.  When
+  // everything the wave needs is history already (nearly always) they come from fixed addresses
+  // and the probability is the quantised one.
+  if (wave_ballot(works && old_j - e < rem) == 0) {    // uniform over the wave
+    auto request = [&](int32_t x, uint32_t& tok, uint32_t& p) {
+      const int32_t at = (works && x <= rem) ? x - 1 : 0;
+      tok = (uint32_t)tok_at[at];
+      p = pq_at[at];
+    };
+    uint32_t tok_a, tok_b, p_a, p_b;
+    request(r + 1, tok_a, p_a);
+    request(r + 1 + R, tok_b, p_b);
+    lds_barrier<BLOCK>();
+    CSD_STAMP(c.unit, 10, CSD_CLOCK());
+    for (int32_t d = r + 1; d <= L; d += R) {
+      consume_here(tok_a);
+      consume_here(p_a);
+      const uint32_t v = tok_a & 0xFFFFFFu, pv = p_a;
+      tok_a = tok_b;
+      p_a = p_b;
+      request(d + 2 * R, tok_b, p_b);
+      instance(works && d <= rem, d, v, pv);
+    }
+  } else {
+    auto request = [&](int32_t x, int32_t& tok, Paths::ProbWord& prob) {
+      const bool has = works && x <= rem;
+      tok = c.y.token(has ? j : 0, has ? e + x - 1 : 0, has ? old_j : 1);
+      prob = c.y.prob_load(has ? j : 0, has ? e + x - 1 : 0, has ? old_j : 1);
+    };
+    int32_t tok_a, tok_b;
+    Paths::ProbWord prob_a, prob_b;
+    request(r + 1, tok_a, prob_a);
+    request(r + 1 + R, tok_b, prob_b);
+    lds_barrier<BLOCK>();
+    CSD_STAMP(c.unit, 10, CSD_CLOCK());
+    for (int32_t d = r + 1; d <= L; d += R) {
+      consume_here(tok_a);
+      consume_here(prob_a.word);
+      const uint32_t v = (uint32_t)tok_a & 0xFFFFFFu, pv = Paths::prob_value(prob_a);
+      tok_a = tok_b;
+      prob_a = prob_b;
+      request(d + 2 * R, tok_b, prob_b);
+      instance(works && d <= rem, d, v, pv);
+    }
+  }
+  lds_barrier<BLOCK>();                                // Eq. 5's sums are complete
+  CSD_STAMP(c.unit, 11, CSD_CLOCK());
+  if (s.overflow) return false;                        // uniform over the workgroup
+  if (c.tid >= ((M + kWave - 1) & ~(kWave - 1))) return true;   // waves without a match of their own
+  const int lane = c.tid & (kWave - 1);
+  const bool mine_too = c.tid < M;                     // here r = 0, t = tid
+  // A layer's node of this thread's match is no part of the choice: its slot is read two
+  // layers ahead, key and cell one layer ahead, its rank (as the maximum takes it) is computed
+  // behind the atomic of the layer before.
+  auto slot_at = [&](int32_t d) { return (mine_too && d <= rem) ? (uint32_t)slot_of[(d - 1) * M + c.tid] : 0u; };
+  auto rank = [&](uint32_t key, u64 sums, uint32_t& v, uint32_t& hi, uint32_t& lo) {
+    v = key & 0xFFFFFFu;
+    const u64 packed = ((weight_key(sums, alpha_q) + 1ull) << kTabTokenBits) | (u64)(kTokBits - (v & kTokBits));
+    hi = (uint32_t)(packed >> 32);
+    lo = (uint32_t)packed;
+  };
+  int32_t cur = c.Q[0];
+  uint32_t u = (uint32_t)c.Q[0], v, hi, lo;
+  const uint32_t slot_1 = slot_at(1), slot_2 = slot_at(2);
+  uint32_t slot_n = slot_at(3);
+  rank(keys[slot_1], cell[slot_1], v, hi, lo);
+  uint32_t key_n = keys[slot_2];
+  u64 sums_n = cell[slot_2];
+  for (int32_t d = 1; d <= L; ++d) {
+    const bool cand = mine_too && d <= rem && u == (uint32_t)cur;
+    const uint32_t top_hi = wave_max(cand ? hi : 0u);
+    const uint32_t top_lo = wave_max((cand && hi == top_hi) ? lo : 0u);
+    if (lane == 0 && (top_hi | top_lo) != 0u) atomicMax(&best[d - 1], ((u64)top_hi << 32) | top_lo);
+    uint32_t v_next, hi_next, lo_next;
+    rank(key_n, sums_n, v_next, hi_next, lo_next);     // layer d + 1
+    consume_here(hi_next);                             // (computed here, behind the atomic: not after the barrier)
+    consume_here(lo_next);
+    lds_barrier<BLOCK>();
+    const u64 top = best[d - 1];
+    key_n = keys[slot_n];                              // layer d + 2
+    sums_n = cell[slot_n];
+    slot_n = slot_at(d + 3);
+    if (top == 0ull) break;                            // leaf: no edge leaves cur
+    const Cand chosen{(top >> kTabTokenBits) - 1ull, (int32_t)(kTokBits - ((uint32_t)top & kTokBits))};
+    note_choice(o, chosen, d, c.tid);
+    cur = chosen.v;
+    u = v;
+    v = v_next;
+    hi = hi_next;
+    lo = lo_next;
+  }
+  return true;
 }
 
 // ---------------------------------------------------------------- tier 2: streaming

@@ -238,8 +238,10 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
         if (c.tid < kWave) walk_matches(s, c, M, L, WinInfo{0, M}, windows, a.alpha_q, a.score_mode, o);
         done = true;
       } else if (M <= BLOCK) {
-        // one thread per match, layer by layer
-        walk_wide<BLOCK>(s, c, M, L, a.alpha_q, a.score_mode, o);
+        // one thread per match: node weights tabulated first, or layer by layer
+        // (the second where the first does not apply or finds too many distinct continuations)
+        if (!walk_tab_fits<BLOCK>(M, L, ix.vocab, a.score_mode) || !walk_tab<BLOCK>(s, c, M, L, a.alpha_q, o))
+          walk_wide<BLOCK>(s, c, M, L, a.alpha_q, a.score_mode, o);
         done = true;
       }
       if (!done)

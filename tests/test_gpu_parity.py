@@ -287,6 +287,30 @@ def test_many_distinct_edges_overflow_the_lds_table(oracle):
             _one_shot(oracle, paths, probs, 1, 6, 0.5, mode)
 
 
+def test_hundreds_of_matches_node_weights_tabulated_first(oracle):
+    """Rows of 65 .. 1024 matches in scan mode take the walk that tabulates Eq. 5's node weights
+    of all layers first: with few distinct continuations (every instance of a layer on a handful
+    of keys), with thousands of distinct ones, with so many that the key set gives up and the
+    row is walked layer by layer after all (1000 matches x 8 layers of random tokens), with
+    token ids too large for the packed rank, with long drafts, and under edge scoring (which
+    never tabulates).  The query token recurs at the head of every block."""
+    rng = np.random.default_rng(77)
+    for reps, n_paths, lo, hi, L in ((150, 5, 10, 4000, 8), (250, 5, 10, 4000, 8), (150, 5, 10, 3_000_000, 8),
+                                     (60, 5, 10, 14, 32), (200, 5, 10, 13, 8), (17, 5, 10, 200, 8)):
+        paths, probs = [], []
+        for j in range(n_paths):
+            body = rng.integers(lo, hi, size=(reps, L + 1))
+            body[:, 0] = 7
+            paths.append(body.reshape(-1).tolist())
+            probs.append((rng.integers(0, 9, size=reps * (L + 1)) / 8.0).tolist())
+        paths[0] = paths[0][:-L]                            # path 0 ends with the query token 7
+        probs[0] = probs[0][:-L]
+        for mode, alpha in ((0, 0.5), (1, 0.5), (0, 1.0), (0, 0.0)):
+            print("reps", reps, "tokens below", hi, "L", L, "mode", mode, "alpha", alpha, flush=True)
+            for fused in (False, True):
+                _one_shot(oracle, paths, probs, 1, L, alpha, mode, SCAN, fused)
+
+
 def test_empty_and_tiny_paths(oracle):
     _one_shot(oracle, [[1, 2, 3], [], [3], [2, 3, 9, 2, 3]], None, 2, 4)
     _one_shot(oracle, [[4], [4, 4], [9]], [[0.5], [0.25, 1.0], [1.0]], 3, 3)
