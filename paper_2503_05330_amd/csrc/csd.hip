@@ -246,7 +246,7 @@ void launch_draft(const csd_index* h, const IndexView& v, const StepIn& in, cons
   }
   else if (v.kmax <= 4) {                        // the usual gram lengths: loops unrolled to 4
     if (a.L <= 8 && rows >= kSmallLdsRows)       // more rows than fit the chip at once
-      step_wave_kernel<8, false, LdsWaveSmall, false, 4><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
+      step_wave_many_kernel<4><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
     else if (a.L <= 8)
       step_wave_kernel<8, false, LdsWave, false, 4><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
     else if (a.L <= 16)
@@ -254,7 +254,7 @@ void launch_draft(const csd_index* h, const IndexView& v, const StepIn& in, cons
     else
       step_wave_kernel<32, false, LdsWave, false, 4><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
   } else if (a.L <= 8 && rows >= kSmallLdsRows)
-    step_wave_kernel<8, false, LdsWaveSmall, false, 8><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
+    step_wave_many_kernel<8><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
   else if (a.L <= 8)
     step_wave_kernel<8, false, LdsWave, false, 8><<<grid, step_wave_threads(false), 0, st>>>(v, in, a);
   else if (a.L <= 16)

@@ -408,9 +408,10 @@ struct LdsT {
 // One wave per row (index mode): 38 KB, four rows share a CU's LDS.
 typedef LdsT<1024, 1024, 2048, 1> LdsWave;
 // The same for large batches, where the number of rows resident on a CU bounds
-// the throughput: 13 KB, twelve rows per CU.  Rows with more than 256 matches or
-// more than 32 distinct keys in a layer take the streaming tier.
-typedef LdsT<256, 256, 1024, 1> LdsWaveSmall;
+// the throughput: 9 KB, sixteen rows per CU (with the kernel built for eight waves
+// per SIMD).  Rows with more than 256 matches or more than 32 distinct keys in a
+// layer take the streaming tier.
+typedef LdsT<256, 256, 512, 1, 64> LdsWaveSmall;
 // One wave per row with one-edit matching through the index: such queries have
 // many more matches, so the list is longer (66 KB, two rows per CU).
 typedef LdsT<1024, 4096, 2048, 1> LdsWaveFuzzy;

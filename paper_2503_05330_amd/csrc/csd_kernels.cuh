@@ -471,6 +471,16 @@ __global__ __launch_bounds__(step_wave_threads(FUZZY)) void step_wave_kernel(Ind
   step_wave_body<LCAP, POOLS, LDS, FUZZY, QC>(ix, in, a, NoTail{});
 }
 
+// The same for launches of thousands of rows (exact matching, drafts of up to 8 tokens), where
+// the number of rows resident on a CU bounds the throughput: compiled for eight waves per SIMD
+// (at most 64 registers per lane), with the small on-chip layout: sixteen rows per CU.
+template <int QC>
+__global__ __launch_bounds__(step_wave_threads(false)) __attribute__((amdgpu_waves_per_eu(8, 8)))
+void step_wave_many_kernel(IndexView ix, StepIn in, DraftArgs a) {
+  fetch_kernel_arguments<sizeof(IndexView) + sizeof(StepIn) + sizeof(DraftArgs)>();
+  step_wave_body<8, false, LdsWaveSmall, false, QC>(ix, in, a, NoTail{});
+}
+
 // One step of the accept-driven loop in one launch: a step of up to L + 1 tokens per path
 // (general instantiation, exact matching), then the tail that prepares the next step.
 template <int LCAP, int QC>
