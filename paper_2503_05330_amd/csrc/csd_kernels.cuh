@@ -487,6 +487,7 @@ template <int LCAP, int QC>
 __global__ __launch_bounds__(step_wave_threads(false)) void step_loop_kernel(IndexView ix, StepIn in,
                                                                              DraftArgs a,
                                                                              LoopTail tail) {
+  fetch_kernel_arguments<sizeof(IndexView) + sizeof(StepIn) + sizeof(DraftArgs) + sizeof(LoopTail)>();
   step_wave_body<LCAP, true, LdsWave, false, QC>(ix, in, a, tail);
 }
 

@@ -102,7 +102,7 @@ def test_bound_behind_the_table_full_status_bit():
     src = open(os.path.join(ROOT, "paper_2503_05330_amd", "csrc", "csd_dag.cuh")).read()
     assert "0x9E3779B1u) >> 12 & (n_class - 1)" in src          # the class function the header describes
     common = open(os.path.join(ROOT, "paper_2503_05330_amd", "csrc", "csd_common.cuh")).read()
-    assert "kMaxClassBits = 20" in common and "LdsT<256, 256, 1024, 1> LdsWaveSmall" in common
+    assert "kMaxClassBits = 20" in common and "LdsT<256, 256, 512, 1, 64> LdsWaveSmall" in common
     inv = pow(0x9E3779B1, -1, 1 << 32)
 
     def most_ids_in_a_class(vocab):
