@@ -317,7 +317,7 @@ __device__ __forceinline__ void row_step(LDS& s, const IndexView& ix, const Step
   InsertTicket ticket;
   VariantTicket tickets;
   bool ticket_used;
-  int32_t M = FUZZY ? wave_front_end_fuzzy<LCAP>(s, c, ix, p, a.k, L, wi, tickets, ticket_used)
+  int32_t M = FUZZY ? wave_front_end_fuzzy<LCAP, QC>(s, c, ix, p, a.k, L, wi, tickets, ticket_used)
                     : wave_front_end<LCAP, QC, APPENDS, POOLS>(s, c, ix, p, a.k, L, wi, ticket, ticket_used);
   block_sync<kWave>();
 #ifdef CSD_STAMPS

@@ -778,9 +778,9 @@ __device__ __forceinline__ void wave_append(const Ctx& c, const IndexView& ix, i
 //                                  Q[x] == G[x+1] for b <= x < a.
 // With P / S the first / last index where Q and G differ, the b that asks
 // least of a given a is max(a, S) in the first case, min(a - 1, P) in the second.
-__device__ __forceinline__ bool variant_counts(const Ctx& c, const int32_t (&G)[CSD_MAX_QUERY_LEN + 1],
-                                               int32_t u, int32_t v) {
-  constexpr int K = CSD_MAX_QUERY_LEN;
+// K: compile-time bound of the query length (the loops are unrolled to it).
+template <int K = CSD_MAX_QUERY_LEN>
+__device__ __forceinline__ bool variant_counts(const Ctx& c, const int32_t (&G)[K + 1], int32_t u, int32_t v) {
   const int32_t q = c.q;
   int32_t P = q, S = -1;                                 // first / last mismatch
   int32_t up[K + 1], down[K + 1];      // failures of Q[x+1]==G[x] / Q[x]==G[x+1] among x < index
@@ -821,11 +821,10 @@ __device__ __forceinline__ bool variant_counts(const Ctx& c, const int32_t (&G)[
 // position counts once, whichever variants led to it (my_u: the variant whose
 // chain this bucket belongs to).  Returns whether the group's bucket was full
 // (its chain goes on).
-template <int LCAP, class LDS>
+template <int LCAP, int K, class LDS>
 __device__ __forceinline__ bool consume_variant_bucket(LDS& s, const Ctx& c, int32_t L,
                                                        int32_t win_cap, int32_t& n_match,
                                                        int32_t my_u, int32_t word) {
-  constexpr int K = CSD_MAX_QUERY_LEN;
   const int lane = c.tid;
   const Paths& y = c.y;
   const int sub = lane & 15;          // word of the bucket this lane reads
@@ -871,7 +870,7 @@ __device__ __forceinline__ bool consume_variant_bucket(LDS& s, const Ctx& c, int
     for (int a = 0; a <= K; ++a) tv[a] = (a <= c.q && a < e) ? tv[a] : 0;
   }
   // each position once: for the first variant it shares with the query
-  bool hit = cand && near_query(c, e, tv) && variant_counts(c, tv, my_u, filed_as);
+  bool hit = cand && near_query<K>(c, e, tv) && variant_counts<K>(c, tv, my_u, filed_as);
   if (wave_ballot(hit && rem > n_hist) != 0) {              // rare: runs into this step's new tokens
 #pragma unroll
     for (int d = 0; d < LCAP; ++d)
@@ -900,7 +899,7 @@ __device__ __forceinline__ bool consume_variant_bucket(LDS& s, const Ctx& c, int
 // with the next batch in flight (reading past the end of a chain is harmless:
 // buckets behind the first one that is not full are empty).  `word` is the
 // lane's word of bucket 0 of its group's first variant, already requested.
-template <int LCAP, class LDS>
+template <int LCAP, int K, class LDS>
 __device__ __forceinline__ void lookup_variants_with_windows(LDS& s, const Ctx& c, int32_t L,
                                                              int32_t win_cap, int32_t& n_match,
                                                              int32_t word) {
@@ -912,10 +911,12 @@ __device__ __forceinline__ void lookup_variants_with_windows(LDS& s, const Ctx& 
   for (int32_t pass = 0; pass * 4 <= c.q; ++pass) {
     const int32_t u = pass * 4 + grp;
     const bool active = u <= c.q && variant_is_new(c.Q, u);
-    if (pass > 0) word = gram_bucket(tbl, variant_hash(c.Q, c.q, u), 0u, c.bucket_mask)[sub];
     consume_here(word);
     if (!active) word = -1;           // idle groups see an empty bucket
-    bool full = consume_variant_bucket<LCAP>(s, c, L, win_cap, n_match, u, word);
+    // the next four variants' buckets travel while these are looked through
+    const int32_t u_next = u + 4 <= c.q ? u + 4 : 0;
+    const int32_t word_next = gram_bucket(tbl, variant_hash(c.Q, c.q, u_next), 0u, c.bucket_mask)[sub];
+    bool full = consume_variant_bucket<LCAP, K>(s, c, L, win_cap, n_match, u, word);
     const u64 goes_on = wave_ballot(active && full && sub == 0);       // bit 16 g: group g's chain
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
@@ -928,12 +929,13 @@ __device__ __forceinline__ void lookup_variants_with_windows(LDS& s, const Ctx& 
         if (r0 + grp >= n_buckets) tail = -1;
         uint32_t rn = r0 + 4 + grp;                                 // next batch: in flight meanwhile
         int32_t next_tail = gram_bucket(tbl, gh, rn < n_buckets ? rn : 0u, c.bucket_mask)[sub];
-        bool tail_full = consume_variant_bucket<LCAP>(s, c, L, win_cap, n_match,
-                                                      pass * 4 + g, tail);
+        bool tail_full = consume_variant_bucket<LCAP, K>(s, c, L, win_cap, n_match,
+                                                         pass * 4 + g, tail);
         if (wave_ballot(!tail_full) != 0) break;                       // the chain ends in this batch
         tail = next_tail;
       }
     }
+    word = word_next;
   }
 }
 
@@ -944,11 +946,11 @@ __device__ __forceinline__ void lookup_variants_with_windows(LDS& s, const Ctx& 
 // keep kmax + 1 tokens for that) and position kmax - 1 of each other path (the
 // only one with fewer than kmax tokens before it that can match a kmax-token
 // query).  Returns the number of matches.
-template <int LCAP, class LDS>
+// K: compile-time bound (4 or 8) of the index's gram length: the predicates are unrolled to it.
+template <int LCAP, int K = CSD_MAX_QUERY_LEN, class LDS>
 __device__ __forceinline__ int32_t wave_front_end_fuzzy(LDS& s, Ctx& c, const IndexView& ix,
                                                         int32_t p, int32_t k, int32_t L, WinInfo& wi,
                                                         VariantTicket& ticket, bool& ticket_used) {
-  constexpr int K = CSD_MAX_QUERY_LEN;
   const int lane = c.tid;
   const Paths& y = c.y;
   const int64_t row = (int64_t)p * ix.N + c.i;
@@ -1003,12 +1005,12 @@ __device__ __forceinline__ int32_t wave_front_end_fuzzy(LDS& s, Ctx& c, const In
     // the position appended by this very launch: the tokens before it are the old tail
 #pragma unroll
     for (int a = 0; a <= K; ++a) t[a] = (a <= c.q && a < hj.old_len) ? hj.tail[a] : 0;
-    bool hit = other && hj.new_len > hj.old_len && near_query(c, hj.old_len, t);
+    bool hit = other && hj.new_len > hj.old_len && near_query<K>(c, hj.old_len, t);
     wave_push(s, n_match, hit, make_match(y, j, hj.old_len, hj.old_len, hj.new_len), lane);
     // position kmax - 1, if it is history: no posting exists for it
 #pragma unroll
     for (int a = 0; a <= K; ++a) t[a] = (a < K && a < ix.kmax - 1) ? first_tokens[a < K ? a : 0] : 0;
-    hit = other && ix.kmax - 1 < hj.old_len && near_query(c, ix.kmax - 1, t);
+    hit = other && ix.kmax - 1 < hj.old_len && near_query<K>(c, ix.kmax - 1, t);
     wave_push(s, n_match, hit, make_match(y, j, ix.kmax - 1, hj.old_len, hj.new_len), lane);
   }
   if (ticket_used) {
@@ -1018,7 +1020,7 @@ __device__ __forceinline__ int32_t wave_front_end_fuzzy(LDS& s, Ctx& c, const In
   wi.n_fresh = n_match;
   wi.win_cap = use_index ? LDS::kWin / (2 * L) : 0;
   if (use_index) {
-    lookup_variants_with_windows<LCAP>(s, c, L, wi.win_cap, n_match, word);
+    lookup_variants_with_windows<LCAP, K>(s, c, L, wi.win_cap, n_match, word);
   } else if (c.q > 0) {
     WaveListSink<LDS> sink{&s, &n_match, lane};
     match_plain<true>(s, c, sink);                      // covers old and new positions alike
