@@ -222,13 +222,13 @@ void launch_draft(const csd_index* h, const IndexView& v, const StepIn& in, cons
   const uint32_t scan_grid = sl.n > 1 ? (uint32_t)((rows + 7) / 8 * sl.n * 8) : grid;
   if (h->indexed && v.eps > 0) {                         // one edit through the variant index
     if (v.kmax <= 4) {                           // the usual gram lengths: predicates unrolled to 4
-      if (a.L <= 8) step_wave_kernel<8, true, LdsWaveFuzzy, true, 4><<<grid, kWave, 0, st>>>(v, in, a);
-      else if (a.L <= 16) step_wave_kernel<16, true, LdsWaveFuzzy, true, 4><<<grid, kWave, 0, st>>>(v, in, a);
-      else step_wave_kernel<32, true, LdsWaveFuzzy, true, 4><<<grid, kWave, 0, st>>>(v, in, a);
+      if (a.L <= 8) step_wave_kernel<8, true, LdsWaveFuzzy, true, 4><<<grid, step_wave_threads(true), 0, st>>>(v, in, a);
+      else if (a.L <= 16) step_wave_kernel<16, true, LdsWaveFuzzy, true, 4><<<grid, step_wave_threads(true), 0, st>>>(v, in, a);
+      else step_wave_kernel<32, true, LdsWaveFuzzy, true, 4><<<grid, step_wave_threads(true), 0, st>>>(v, in, a);
     }
-    else if (a.L <= 8) step_wave_kernel<8, true, LdsWaveFuzzy, true, CSD_MAX_QUERY_LEN><<<grid, kWave, 0, st>>>(v, in, a);
-    else if (a.L <= 16) step_wave_kernel<16, true, LdsWaveFuzzy, true, CSD_MAX_QUERY_LEN><<<grid, kWave, 0, st>>>(v, in, a);
-    else step_wave_kernel<32, true, LdsWaveFuzzy, true, CSD_MAX_QUERY_LEN><<<grid, kWave, 0, st>>>(v, in, a);
+    else if (a.L <= 8) step_wave_kernel<8, true, LdsWaveFuzzy, true, CSD_MAX_QUERY_LEN><<<grid, step_wave_threads(true), 0, st>>>(v, in, a);
+    else if (a.L <= 16) step_wave_kernel<16, true, LdsWaveFuzzy, true, CSD_MAX_QUERY_LEN><<<grid, step_wave_threads(true), 0, st>>>(v, in, a);
+    else step_wave_kernel<32, true, LdsWaveFuzzy, true, CSD_MAX_QUERY_LEN><<<grid, step_wave_threads(true), 0, st>>>(v, in, a);
   } else if (!h->indexed) {
     // scan mode; the general kernels (POOLS) take the tree and list pools, own history,
     // back-off and steps of several tokens

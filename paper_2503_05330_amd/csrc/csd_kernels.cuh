@@ -273,10 +273,10 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
 // FUZZY: the index files every position under its gram's variants and matching tolerates
 // one edit (Eq. 4).
 // QC: compile-time bound (4 or 8) of the index's gram length.
-// Exact matching runs two waves per row (on two SIMDs of the CU): the second does the row's
-// append and index insert, which the draft does not depend on, so that they leave the critical
-// path of the first.  The two never meet at a barrier.
-constexpr int step_wave_threads(bool fuzzy) { return fuzzy ? kWave : 2 * kWave; }
+// Two waves per row (on two SIMDs of the CU): the second does the row's append and index
+// insert, which the draft does not depend on, so that they leave the critical path of the
+// first.  The two never meet at a barrier.
+constexpr int step_wave_threads(bool) { return 2 * kWave; }
 
 // The accept-driven loop's stand-in model as the tail of a step (see advance_kernel): the row
 // that has just drafted and counted its accepted tokens works out what it appends at the NEXT
@@ -317,7 +317,7 @@ __device__ __forceinline__ void row_step(LDS& s, const IndexView& ix, const Step
   InsertTicket ticket;
   VariantTicket tickets;
   bool ticket_used;
-  int32_t M = FUZZY ? wave_front_end_fuzzy<LCAP, QC>(s, c, ix, p, a.k, L, wi, tickets, ticket_used)
+  int32_t M = FUZZY ? wave_front_end_fuzzy<LCAP, QC, APPENDS>(s, c, ix, p, a.k, L, wi, tickets, ticket_used)
                     : wave_front_end<LCAP, QC, APPENDS, POOLS>(s, c, ix, p, a.k, L, wi, ticket, ticket_used);
   block_sync<kWave>();
 #ifdef CSD_STAMPS
@@ -384,6 +384,9 @@ __device__ __forceinline__ void row_step(LDS& s, const IndexView& ix, const Step
     walk_matches(s, c, M, L, wi, s.win, a.alpha_q, a.score_mode, o);             // one lane per match
   } else if (M > 0 && M <= 2 * kWave && M <= LDS::kWin / (2 * L)) {
     walk_matches<false, 2>(s, c, M, L, wi, s.win, a.alpha_q, a.score_mode, o);   // two matches per lane
+  } else if (M > 0 && walk_tab_wave_fits<LDS>(M, L, ix.vocab, a.score_mode) &&
+             walk_tab_wave(s, c, wi, M, L, a.alpha_q, o)) {
+    // node weights of all layers tabulated first, then the walk
   } else if (M > 0) {
     bool streaming = M > LDS::kMatch;
     if (!streaming) {
@@ -445,7 +448,7 @@ __device__ __forceinline__ void row_step(LDS& s, const IndexView& ix, const Step
   }
 }
 
-// The row of this workgroup: its first wave drafts; with exact matching a second wave appends.
+// The row of this workgroup: its first wave drafts, a second wave appends.
 template <int LCAP, bool POOLS, class LDS, bool FUZZY, int QC, class TAIL>
 __device__ __forceinline__ void step_wave_body(const IndexView& ix, const StepIn& in,
                                                const DraftArgs& a, const TAIL& tail) {
@@ -458,7 +461,8 @@ __device__ __forceinline__ void step_wave_body(const IndexView& ix, const StepIn
     int32_t p;
     Ctx c = make_ctx(ix, in, row, p);
     c.tid = lane;
-    wave_append<QC, POOLS, std::is_same<LDS, LdsWaveSmall>::value ? 1 : kInsertLanes>(c, ix, p);
+    if (FUZZY) wave_append_fuzzy(c, ix, p);
+    else wave_append<QC, POOLS, std::is_same<LDS, LdsWaveSmall>::value ? 1 : kInsertLanes>(c, ix, p);
     return;
   }
   row_step<LCAP, POOLS, LDS, FUZZY, QC, !SPLIT>(s, ix, in, a, tail, row, lane);

@@ -939,6 +939,28 @@ __device__ __forceinline__ void lookup_variants_with_windows(LDS& s, const Ctx& 
   }
 }
 
+// The writing half of a one-token step when the index files every position under its gram's
+// variants: as wave_append, by a wave of its own beside the one that drafts.
+__device__ __forceinline__ void wave_append_fuzzy(const Ctx& c, const IndexView& ix, int32_t p) {
+  const int lane = c.tid;
+  const Paths& y = c.y;
+  if (y.n != 1) return;
+  const int64_t row = (int64_t)p * ix.N + c.i;
+  int32_t* gram = const_cast<int32_t*>(c.gram);
+  Head me = load_head(y, ix.tail_len, c.i);
+  const int32_t st_i = y.st[c.i];
+  const float sp_i = y.sp ? y.sp[c.i] : 1.0f;
+  const bool ticket_used = me.new_len - me.old_len == 1;
+  VariantTicket ticket;
+  if (ticket_used) ticket = variants_begin(gram, c.bucket_mask, ix.kmax, me.tail, me.old_len, lane);
+  append_own_single(ix, y, row, c.i, me, st_i, sp_i, lane);
+  if (ticket_used) {
+    variants_claim(ticket, gram, c.bucket_mask, lane);
+    variants_beyond_four(ticket, gram, c.bucket_mask, ix.kmax, me.tail, y.pos(c.i, me.old_len), lane);
+    variants_finish(ticket, gram, c.bucket_mask, y.pos(c.i, me.new_len - 1), lane);
+  }
+}
+
 // The front end of a row handled by one wave when matching tolerates one edit
 // and the index files every position under its gram's variants.  Same three
 // round trips as wave_front_end.  Matched directly, without the index: the
@@ -947,7 +969,9 @@ __device__ __forceinline__ void lookup_variants_with_windows(LDS& s, const Ctx& 
 // only one with fewer than kmax tokens before it that can match a kmax-token
 // query).  Returns the number of matches.
 // K: compile-time bound (4 or 8) of the index's gram length: the predicates are unrolled to it.
-template <int LCAP, int K = CSD_MAX_QUERY_LEN, class LDS>
+// APPENDS: this wave also appends the row's token and files it (false: another wave does, see
+// wave_append_fuzzy).
+template <int LCAP, int K = CSD_MAX_QUERY_LEN, bool APPENDS = true, class LDS>
 __device__ __forceinline__ int32_t wave_front_end_fuzzy(LDS& s, Ctx& c, const IndexView& ix,
                                                         int32_t p, int32_t k, int32_t L, WinInfo& wi,
                                                         VariantTicket& ticket, bool& ticket_used) {
@@ -979,13 +1003,13 @@ __device__ __forceinline__ int32_t wave_front_end_fuzzy(LDS& s, Ctx& c, const In
   }
   const bool use_index = c.q == ix.kmax;                // shorter queries: scan (short paths)
   // ---- round trip 2 is requested: fill counts for the insert, bucket 0 of the first 4 variants
-  ticket_used = cnt_i == 1;
+  ticket_used = APPENDS && cnt_i == 1;
   if (ticket_used) ticket = variants_begin(gram, c.bucket_mask, ix.kmax, me.tail, old_i, lane);
   int32_t word = -1;
   if (use_index)
     word = gram_bucket(gram, variant_hash(c.Q, c.q, lane >> 4), 0u, c.bucket_mask)[lane & 15];
   // ---- while it travels: own append, lengths into LDS, matches that need no index
-  if (y.n == 1) append_own_single(ix, y, row, c.i, me, st_i, sp_i, lane);
+  if (APPENDS && y.n == 1) append_own_single(ix, y, row, c.i, me, st_i, sp_i, lane);
   int32_t n_match = 0;
   for (int32_t j0 = 0; j0 < y.N; j0 += kWave) {
     int32_t j = j0 + lane;

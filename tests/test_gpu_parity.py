@@ -311,6 +311,30 @@ def test_hundreds_of_matches_node_weights_tabulated_first(oracle):
                 _one_shot(oracle, paths, probs, 1, L, alpha, mode, SCAN, fused)
 
 
+def test_one_edit_through_the_index_rows_of_many_distinct_continuations(oracle):
+    """One-edit matching through the variant index with rows of 60 .. 200 matches whose
+    continuations mostly differ: more than the lane-per-match walks of the one-wave kernel
+    take, so the node weights are tabulated first (or, where that does not apply or the key set
+    fills up, the per-layer tables are built).  The two query tokens recur at the head of every
+    block; some blocks carry a substituted first token (a one-edit match)."""
+    rng = np.random.default_rng(78)
+    for reps, hi, L in ((16, 4000, 8), (30, 4000, 8), (30, 4000, 16), (50, 14, 8), (30, 3_000_000, 8), (56, 4000, 8)):
+        paths, probs = [], []
+        for j in range(5):
+            body = rng.integers(10, hi, size=(reps, L + 2))
+            body[:, 0] = np.where(rng.random(reps) < 0.25, 8, 7)
+            body[:, 1] = 9
+            paths.append(body.reshape(-1).tolist())
+            probs.append((rng.integers(0, 9, size=reps * (L + 2)) / 8.0).tolist())
+        paths[0] = paths[0][:-L]                            # path 0 ends with the query tokens 7 9
+        probs[0] = probs[0][:-L]
+        paths[0][-2] = 7
+        for mode, alpha in ((0, 0.5), (1, 0.5), (0, 1.0)):
+            print("reps", reps, "tokens below", hi, "L", L, "mode", mode, "alpha", alpha, flush=True)
+            for fused in (False, True):
+                _one_shot(oracle, paths, probs, 2, L, alpha, mode, INDEX, fused, eps=1)
+
+
 def test_empty_and_tiny_paths(oracle):
     _one_shot(oracle, [[1, 2, 3], [], [3], [2, 3, 9, 2, 3]], None, 2, 4)
     _one_shot(oracle, [[4], [4, 4], [9]], [[0.5], [0.25, 1.0], [1.0]], 3, 3)
