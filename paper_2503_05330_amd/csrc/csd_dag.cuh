@@ -807,13 +807,16 @@ __device__ __forceinline__ bool walk_tab(LDS& s, const Ctx& c, int32_t M, int32_
 // instances when a row has more matches than the lane-per-match walks take: with one-edit
 // matching such a row's continuations mostly differ, and the walks that settle one distinct
 // token per round, like the tables with an edge and a node entry per instance, cost it 100 us
-// and more.  Fill: the M * L instances are dealt to the lanes layer by layer; an instance's
-// token and probability come from its match's LDS window or, for matches without one, from
-// memory (both requested for the next instance before this one is entered; every lane issues
-// both loads, from a harmless address where it has no use for one).  Walk: a lane looks at its
-// matches (lane, lane + 64, ..) layer by layer; the previous layer's token of a match is read
-// back through its slot.  Set and cells lie over table and links, the slots in the upper half
-// of the match list.  Returns false, with nothing decided, when an instance finds no place.
+// and more.  The layers are done in runs that keep the key set at most three quarters full
+// (a run's first layer is entered once more by the next run, whose first walked layer reads
+// its matches' previous tokens there).  Fill: a run's instances are dealt to the lanes layer
+// by layer; an instance's token and probability come from its match's LDS window or, for
+// matches without one, from memory (both requested for the next instance before this one is
+// entered; every lane issues both loads, from a harmless address where it has no use for one).
+// Walk: a lane looks at its matches (lane, lane + 64, ..) layer by layer; the previous
+// layer's token of a match is read back through its slot.  Set and cells lie over table and
+// links, the slots in the upper half of the match list.  Returns false, with nothing
+// decided, when an instance of the first run finds no place (later runs cannot fail: see below).
 template <class LDS>
 constexpr uint32_t tab_wave_slots() {
   uint32_t n = 1;
@@ -822,10 +825,9 @@ constexpr uint32_t tab_wave_slots() {
   return n;
 }
 template <class LDS>
-__device__ __forceinline__ bool walk_tab_wave_fits(int32_t M, int32_t L, int32_t vocab, int score_mode) {
+__device__ __forceinline__ bool walk_tab_wave_fits(int32_t M, int32_t vocab, int score_mode) {
   return score_mode == 0 && vocab <= (1 << kTabTokenBits) && M <= LDS::kMatch / 2 &&
-         (uint32_t)(M * L) <= tab_wave_slots<LDS>() &&
-         (size_t)(M * L) * sizeof(uint16_t) <= (size_t)(LDS::kMatch / 2) * sizeof(Match);
+         (uint32_t)(2 * M) <= tab_wave_slots<LDS>() / 4 * 3;     // runs of at least one new layer
 }
 
 template <class LDS>
@@ -834,18 +836,13 @@ __device__ __forceinline__ bool walk_tab_wave(LDS& s, const Ctx& c, WinInfo wi, 
   constexpr uint32_t kSlots = tab_wave_slots<LDS>();
   static_assert(offsetof(LDS, link) == offsetof(LDS, table) + sizeof(s.table), "the links follow the table");
   static_assert(LDS::kWin >= 2 * CSD_MAX_DRAFT_LEN, "window 0 exists for any draft length");
+  static_assert((LDS::kMatch / 2) * sizeof(Match) >= kSlots * sizeof(uint16_t), "a slot per instance of a run");
   constexpr uint32_t kNoKey = ~0u;
   constexpr uint32_t kTokBits = (1u << kTabTokenBits) - 1u;
   u64* cell = reinterpret_cast<u64*>(s.table);                        // [kSlots]
   uint32_t* keys = reinterpret_cast<uint32_t*>(cell + kSlots);         // [kSlots] (d - 1) << 24 | token
-  uint16_t* slot_of = reinterpret_cast<uint16_t*>(&s.match[LDS::kMatch / 2]);   // [L][M]
+  uint16_t* slot_of = reinterpret_cast<uint16_t*>(&s.match[LDS::kMatch / 2]);   // [layers of the run][M]
   const int lane = c.tid;
-  for (uint32_t x = lane; x < kSlots; x += kWave) {
-    cell[x] = 0ull;
-    keys[x] = kNoKey;
-  }
-  lds_barrier<kWave>();
-  // ---- fill: instance x = (d - 1) * M + mi, lane by lane
   struct Instance {
     int32_t mi, d;
     bool alive, cached;
@@ -853,11 +850,11 @@ __device__ __forceinline__ bool walk_tab_wave(LDS& s, const Ctx& c, WinInfo wi, 
     uint32_t p_window;
     Paths::ProbWord p_memory;
   };
-  auto request = [&](int32_t mi, int32_t d) {
+  auto request = [&](int32_t mi, int32_t d, int32_t d_last) {
     Instance x;
     x.mi = mi;
     x.d = d;
-    const bool there = d <= L;
+    const bool there = d <= d_last;
     const Match m = s.match[there ? mi : 0];
     x.alive = there && d <= (int32_t)m.rem_new;
     x.cached = wi.cached(mi);
@@ -871,68 +868,97 @@ __device__ __forceinline__ bool walk_tab_wave(LDS& s, const Ctx& c, WinInfo wi, 
     x.p_window = (uint32_t)win[L + (x.alive ? d - 1 : 0)];
     return x;
   };
-  auto advance = [&](int32_t& mi, int32_t& d) {       // the lane's next instance
-    mi += kWave;
-    while (mi >= M && d <= L) {
+  const int32_t per_run = (int32_t)(kSlots / 4 * 3) / M - 1;   // new layers per run, >= 1
+  int32_t cur = c.Q[0];
+  for (int32_t d0 = 1; d0 <= L; d0 += per_run) {
+    const int32_t d_first = d0 > 1 ? d0 - 1 : 1;      // entered: d_first .. d_last; walked: d0 .. d_last
+    const int32_t d_last = d0 + per_run - 1 < L ? d0 + per_run - 1 : L;
+    for (uint32_t x = lane; x < kSlots; x += kWave) {
+      cell[x] = 0ull;
+      keys[x] = kNoKey;
+    }
+    lds_barrier<kWave>();
+    // ---- fill: the run's instances (layer, match), lane by lane
+    int32_t mi = lane, d = d_first;
+    while (mi >= M && d <= d_last) {
       mi -= M;
       ++d;
     }
-  };
-  int32_t mi = lane, d = 1;
-  while (mi >= M && d <= L) {
-    mi -= M;
-    ++d;
-  }
-  bool failed = false;
-  Instance now = request(mi, d);
-  while (wave_ballot(now.d <= L) != 0) {                // uniform over the wave
-    advance(mi, d);
-    const Instance next = request(mi, d);
-    const uint32_t v = (uint32_t)(now.cached ? now.tok_window : now.tok_memory) & 0xFFFFFFu;
-    const uint32_t p = now.cached ? now.p_window : Paths::prob_value(now.p_memory);
-    const uint32_t mine = ((uint32_t)(now.d - 1) << 24) | v;
-    uint32_t h = (mine * 0x9E3779B1u) >> (32 - __builtin_ctz(kSlots));   // the product's high bits: a slot
-    const uint32_t stride = (mine * 0x85EBCA6Bu) >> 15 | 1u;   // odd: the probes reach every slot
-    bool looking = now.alive;
-    for (int probe = 0; probe < kTabProbes && wave_ballot(looking) != 0; ++probe) {   // uniform
-      uint32_t seen = keys[h];
-      if (looking && seen == kNoKey) seen = atomicCAS(&keys[h], kNoKey, mine);
-      const bool placed = seen == mine || seen == kNoKey;   // there already, or entered just now
-      h = (looking && !placed) ? (h + stride) & (kSlots - 1) : h;
-      looking = looking && !placed;
+    bool failed = false;
+    auto advance = [&]() {                               // the lane's next instance
+      mi += kWave;
+      while (mi >= M && d <= d_last) {
+        mi -= M;
+        ++d;
+      }
+    };
+    // requested one instance ahead (three ahead was no faster: the wave is bound by the
+    // instructions it issues, not by these loads)
+    constexpr int kAhead = 1;
+    Instance queue[kAhead];
+#pragma unroll
+    for (int x = 0; x < kAhead; ++x) {
+      queue[x] = request(mi, d, d_last);
+      advance();
     }
-    if (now.alive && !looking) {
-      atomicAdd(&cell[h], pack_cs(1u, p));
-      slot_of[(now.d - 1) * M + now.mi] = (uint16_t)h;
+    while (wave_ballot(queue[0].d <= d_last) != 0) {     // uniform over the wave
+      const Instance now = queue[0];
+#pragma unroll
+      for (int x = 0; x + 1 < kAhead; ++x) queue[x] = queue[x + 1];
+      queue[kAhead - 1] = request(mi, d, d_last);
+      advance();
+      const uint32_t v = (uint32_t)(now.cached ? now.tok_window : now.tok_memory) & 0xFFFFFFu;
+      const uint32_t p = now.cached ? now.p_window : Paths::prob_value(now.p_memory);
+      const uint32_t mine = ((uint32_t)(now.d - 1) << 24) | v;
+      uint32_t h = (mine * 0x9E3779B1u) >> (32 - __builtin_ctz(kSlots));   // the product's high bits: a slot
+      const uint32_t stride = (mine * 0x85EBCA6Bu) >> 15 | 1u;   // odd: the probes reach every slot
+      bool looking = now.alive;
+      // (at most three quarters of the slots are taken: with an odd stride a free one is
+      // reached within kSlots probes; the bound below is only ever met by a first run that
+      // the caller may still hand to the tables)
+      const int most = d0 == 1 ? kTabProbes : (int)kSlots;
+      for (int probe = 0; probe < most && wave_ballot(looking) != 0; ++probe) {   // uniform
+        uint32_t seen = keys[h];
+        if (looking && seen == kNoKey) seen = atomicCAS(&keys[h], kNoKey, mine);
+        const bool placed = seen == mine || seen == kNoKey;   // there already, or entered just now
+        h = (looking && !placed) ? (h + stride) & (kSlots - 1) : h;
+        looking = looking && !placed;
+      }
+      if (now.alive && !looking) {
+        atomicAdd(&cell[h], pack_cs(1u, p));
+        slot_of[(now.d - d_first) * M + now.mi] = (uint16_t)h;
+      }
+      failed = failed || looking;
     }
-    failed = failed || looking;
-    now = next;
-  }
-  lds_barrier<kWave>();
-  if (wave_ballot(failed) != 0) return false;           // uniform over the wave
-  // ---- walk
-  int32_t cur = c.Q[0];
-  for (int32_t dd = 1; dd <= L; ++dd) {
-    uint32_t best_hi = 0, best_lo = 0;
-    for (int32_t m0 = lane; m0 < M; m0 += kWave) {
-      const Match m = s.match[m0];
-      if (dd > (int32_t)m.rem_new) continue;
-      if (dd > 1 && (keys[slot_of[(dd - 2) * M + m0]] & 0xFFFFFFu) != (uint32_t)cur) continue;
-      const uint32_t slot = slot_of[(dd - 1) * M + m0];
-      const uint32_t v = keys[slot] & 0xFFFFFFu;
-      const u64 packed = ((weight_key(cell[slot], alpha_q) + 1ull) << kTabTokenBits) | (u64)(kTokBits - (v & kTokBits));
-      const uint32_t hi = (uint32_t)(packed >> 32), lo = (uint32_t)packed;
-      const bool more = hi > best_hi || (hi == best_hi && lo > best_lo);
-      best_hi = more ? hi : best_hi;
-      best_lo = more ? lo : best_lo;
+    lds_barrier<kWave>();
+    if (wave_ballot(failed) != 0) return false;         // uniform over the wave; first run only
+    // ---- walk
+    bool ended = false;
+    for (int32_t dd = d0; dd <= d_last; ++dd) {
+      uint32_t best_hi = 0, best_lo = 0;
+      for (int32_t m0 = lane; m0 < M; m0 += kWave) {
+        const Match m = s.match[m0];
+        if (dd > (int32_t)m.rem_new) continue;
+        if (dd > 1 && (keys[slot_of[(dd - 1 - d_first) * M + m0]] & 0xFFFFFFu) != (uint32_t)cur) continue;
+        const uint32_t slot = slot_of[(dd - d_first) * M + m0];
+        const uint32_t v = keys[slot] & 0xFFFFFFu;
+        const u64 packed = ((weight_key(cell[slot], alpha_q) + 1ull) << kTabTokenBits) | (u64)(kTokBits - (v & kTokBits));
+        const uint32_t hi = (uint32_t)(packed >> 32), lo = (uint32_t)packed;
+        const bool more = hi > best_hi || (hi == best_hi && lo > best_lo);
+        best_hi = more ? hi : best_hi;
+        best_lo = more ? lo : best_lo;
+      }
+      const uint32_t top_hi = wave_max(best_hi);
+      const uint32_t top_lo = wave_max(best_hi == top_hi ? best_lo : 0u);
+      ended = (top_hi | top_lo) == 0u;
+      if (ended) break;                                 // leaf: no edge leaves cur
+      const u64 top = ((u64)top_hi << 32) | top_lo;
+      const Cand chosen{(top >> kTabTokenBits) - 1ull, (int32_t)(kTokBits - ((uint32_t)top & kTokBits))};
+      note_choice(o, chosen, dd, lane);
+      cur = chosen.v;
     }
-    const uint32_t top_hi = wave_max(best_hi);
-    const uint32_t top_lo = wave_max(best_hi == top_hi ? best_lo : 0u);
-    if ((top_hi | top_lo) == 0u) break;                 // leaf: no edge leaves cur
-    const u64 top = ((u64)top_hi << 32) | top_lo;
-    const Cand chosen{(top >> kTabTokenBits) - 1ull, (int32_t)(kTokBits - ((uint32_t)top & kTokBits))};
-    note_choice(o, chosen, dd, lane);
-    cur = chosen.v;
+    if (ended) break;
+    lds_barrier<kWave>();                               // the walk's reads are done before the next clearing
   }
   return true;
 }

@@ -384,7 +384,7 @@ __device__ __forceinline__ void row_step(LDS& s, const IndexView& ix, const Step
     walk_matches(s, c, M, L, wi, s.win, a.alpha_q, a.score_mode, o);             // one lane per match
   } else if (M > 0 && M <= 2 * kWave && M <= LDS::kWin / (2 * L)) {
     walk_matches<false, 2>(s, c, M, L, wi, s.win, a.alpha_q, a.score_mode, o);   // two matches per lane
-  } else if (M > 0 && walk_tab_wave_fits<LDS>(M, L, ix.vocab, a.score_mode) &&
+  } else if (M > 0 && walk_tab_wave_fits<LDS>(M, ix.vocab, a.score_mode) &&
              walk_tab_wave(s, c, wi, M, L, a.alpha_q, o)) {
     // node weights of all layers tabulated first, then the walk
   } else if (M > 0) {
