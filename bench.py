@@ -194,6 +194,42 @@ def batch_points(binding, torch, dev, w, tokens, probs, matches_per_problem_step
     return points
 
 
+def batch_points_full_history(binding, torch, dev, w, tokens, probs, matches_per_problem_step, flags, max_edits,
+                              problems, K=128):
+    """The same batches at FULL history: P copies of the workload's first problem, T - K steps
+    replayed untimed, then the last K steps timed (best of two)."""
+    N, T, k, L = w.n_paths, w.max_len, w.query_len, w.draft_len
+    points = []
+    for P in problems:
+        tok = np.ascontiguousarray(np.broadcast_to(tokens[0].T[:, None, :], (T, P, N)))
+        pr = np.ascontiguousarray(np.broadcast_to(probs[0].T[:, None, :], (T, P, N)))
+        d_tok, d_pr = torch.from_numpy(tok).to(dev), torch.from_numpy(pr).to(dev)
+        ix = binding.Index(P, N, T, w.vocab, k, L, 1.0, 0, flags, device=dev, max_edits=max_edits)
+        outs = dict(tokens=torch.empty((K, P, N, L), dtype=torch.int32, device=dev),
+                    length=torch.empty((K, P, N), dtype=torch.int32, device=dev),
+                    token_scores=torch.empty((K, P, N, L), dtype=torch.float32, device=dev),
+                    path_scores=torch.empty((K, P, N), dtype=torch.float32, device=dev))
+        best = None
+        for _ in range(2):
+            ix.reset()
+            ix.replay(T - K, d_tok[:T - K], d_pr[:T - K], k, L)
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            ev0.record()
+            ix.replay(K, d_tok[T - K:], d_pr[T - K:], k, L, out=outs)
+            ev1.record()
+            torch.cuda.synchronize()
+            us = ev0.elapsed_time(ev1) / K * 1e3
+            best = us if best is None else min(best, us)
+        b = algorithmic_bytes(N * P, k, L, k, matches_per_problem_step * P) - 4 * L * N * P
+        points.append({"problems": P, "rows": P * N, "timed_steps": K, "history": "%d..%d" % (T - K + 1, T),
+                       "us_per_step": best, "problem_steps_per_s": P / best * 1e6,
+                       "algorithmic_GBps": b / best / 1e3})
+        del ix, outs, d_tok, d_pr
+        torch.cuda.empty_cache()
+    return points
+
+
 def cpu_baseline(oracle, r, K, budget_s, threads):
     """The oracle on the last K steps of the replay (the timed region's steps), repeated until
     about budget_s seconds have passed: steps per second on `threads` host threads."""
@@ -412,6 +448,9 @@ def main():
         problems = (1, 4, 16, 64, 256, 1024, 4096) if args.batch_sweep else (64, 4096)
         res["batch"] = batch_points(binding, torch, dev, r.w, r.tokens, r.probs, matches_per_step / P, r.flags,
                                     args.max_edits, problems)
+        res["batch_at_full_history"] = batch_points_full_history(
+            binding, torch, dev, r.w, r.tokens, r.probs, matches_per_step / P, r.flags, args.max_edits,
+            (64, 1024, 4096) if args.batch_sweep else (1024, 4096))
     elif args.batch_sweep:
         res["batch"] = batch_points(binding, torch, dev, r.w, r.tokens, r.probs, matches_per_step / P, r.flags,
                                     args.max_edits, (1, 4, 16, 64, 256, 1024, 4096))

@@ -826,6 +826,7 @@ constexpr uint32_t tab_wave_slots() {
 }
 template <class LDS>
 __device__ __forceinline__ bool walk_tab_wave_fits(int32_t M, int32_t vocab, int score_mode) {
+  if (tab_wave_slots<LDS>() < 1024) return false;      // (the small layouts: not worth its code there)
   return score_mode == 0 && vocab <= (1 << kTabTokenBits) && M <= LDS::kMatch / 2 &&
          (uint32_t)(2 * M) <= tab_wave_slots<LDS>() / 4 * 3;     // runs of at least one new layer
 }
