@@ -266,14 +266,16 @@ __device__ __forceinline__ void walk_instances(LDS& s, const Ctx& c, int32_t M, 
 // reduction, and from the two follows its weight (Eq. 5) exactly as the tables
 // of tier 1 would hold it.  Matches without a window (found among the newest
 // positions) write theirs first.
-// `windows`: M windows of 2 L words (s.win, or any other LDS the caller has free).
+// `windows`: M windows of 2 L words (s.win, or any other LDS the caller has free); with
+// `split` given, only the first `split` of them, the others lie at `windows_beyond`.
 // TREE: the prefix-tree pool instead of the DAG: a layer's successors are the lanes whose
 // whole continuation so far is the draft so far, and only they count for a successor's weight.
 // R: matches per lane (lane l holds matches l, l + 64, ..): up to 64 R matches.
 template <bool TREE = false, int R = 1, class LDS>
 __device__ __forceinline__ void walk_matches(LDS& s, const Ctx& c, int32_t M, int32_t L, WinInfo wi,
                                              int32_t* windows, uint32_t alpha_q, int score_mode,
-                                             DraftOut& o) {
+                                             DraftOut& o, int32_t* windows_beyond = nullptr,
+                                             int32_t split = INT_MAX) {
   const int lane = c.tid;
   int32_t rem[R];                                     // layers this lane's matches reach
   const int32_t* win[R];
@@ -282,7 +284,8 @@ __device__ __forceinline__ void walk_matches(LDS& s, const Ctx& c, int32_t M, in
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     const int32_t mi = lane + r * kWave;
-    int32_t* mine = windows + (mi < M ? mi : 0) * 2 * L;
+    const int32_t wx = mi < M ? mi : 0;
+    int32_t* mine = wx < split ? windows + wx * 2 * L : windows_beyond + (wx - split) * 2 * L;
     rem[r] = 0;
     if (mi < M) {
       Match m = s.match[mi];

@@ -380,8 +380,12 @@ __device__ __forceinline__ void row_step(LDS& s, const IndexView& ix, const Step
       case 2: walk_instances<4>(s, c, M, L, wi, a.alpha_q, a.score_mode, o); break;
       default: walk_instances<8>(s, c, M, L, wi, a.alpha_q, a.score_mode, o); break;
     }
-  } else if (M > 0 && M <= kWave && M <= LDS::kWin / (2 * L)) {
-    walk_matches(s, c, M, L, wi, s.win, a.alpha_q, a.score_mode, o);             // one lane per match
+  } else if (M > 0 && M <= kWave &&
+             (M - LDS::kWin / (2 * L)) * 2 * L * (int32_t)sizeof(int32_t) <= (int32_t)sizeof(s.table)) {
+    // one lane per match; with more matches than the layout has windows, the others' windows
+    // are laid over the table, which this walk does not use
+    walk_matches(s, c, M, L, wi, s.win, a.alpha_q, a.score_mode, o, reinterpret_cast<int32_t*>(s.table),
+                 LDS::kWin / (2 * L));
   } else if (M > 0 && M <= 2 * kWave && M <= LDS::kWin / (2 * L)) {
     walk_matches<false, 2>(s, c, M, L, wi, s.win, a.alpha_q, a.score_mode, o);   // two matches per lane
   } else if (M > 0 && walk_tab_wave_fits<LDS>(M, ix.vocab, a.score_mode) &&
