@@ -420,7 +420,8 @@ typedef LdsT<1024, 4096, 2048, 1> LdsWaveFuzzy;
 // more than 64 matches (at a draft length of 8) take the bounded-memory tiers.
 typedef LdsT<256, 128, 1024, 1, 16> LdsMulti;
 // One 1024-thread workgroup per row (scan mode, where a fuzzy query can have
-// thousands of matches): 108 KB, one row per CU.
+// thousands of matches): 128 KB, one row per CU (the windows are not used as such: the walk
+// that tabulates node weights first keeps its keys and slots there).
 typedef LdsT<4096, 4096, 6144, kScanBlock / kWave> LdsScan;
 
 struct Ctx {                    // one (problem, query path)

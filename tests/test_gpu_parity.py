@@ -335,6 +335,38 @@ def test_one_edit_through_the_index_rows_of_many_distinct_continuations(oracle):
                 _one_shot(oracle, paths, probs, 2, L, alpha, mode, INDEX, fused, eps=1)
 
 
+def test_random_rows_of_hundreds_of_matches(oracle):
+    """Differential test of the walks that serve 65 .. 1024 matches per row (and the hand-overs
+    to the tiers on both sides): random paths over a few symbols, so that a short query recurs
+    hundreds of times with continuations that agree in part; geometry, query and draft length,
+    alpha, scoring, tolerance and matcher vary together."""
+    rng = np.random.default_rng(4711)
+    seen = []
+    for case in range(36):
+        N = int(rng.integers(2, 9))
+        T = int(rng.integers(120, 700))
+        V = int(rng.choice([2, 3, 4, 6, 12]))
+        k = int(rng.integers(1, 4))
+        L = int(rng.choice([1, 3, 8, 10, 16, 32]))
+        alpha = float(rng.choice([0.0, 0.3, 1.0]))
+        mode = int(rng.integers(0, 2))
+        eps = int(rng.integers(0, 2))
+        flags = SCAN if (eps and k < 2) or rng.random() < 0.6 else INDEX
+        fused = bool(rng.integers(0, 2))
+        base = rng.integers(0, V, size=T)
+        paths, probs = [], []
+        for j in range(N):
+            n = int(rng.integers(T // 2, T + 1))
+            noise = rng.random(n) < rng.choice([0.0, 0.05, 0.3])
+            paths.append(np.where(noise, rng.integers(0, V, size=n), base[:n]).tolist())
+            probs.append((rng.integers(0, 17, size=n) / 16.0).tolist())
+        print("case", case, "N", N, "T", T, "V", V, "k", k, "L", L, "alpha", alpha, "mode", mode, "eps", eps,
+              "flags", flags, "fused", fused, flush=True)
+        ix, tok, pr, cnt, want = _one_shot(oracle, paths, probs, k, L, alpha, mode, flags, fused, eps=eps)
+        seen.append(int(max(len(oracle.matches(tok[0], cnt[0], i, k, eps)) for i in range(N))))
+    assert sum(65 <= m <= 1024 for m in seen) >= 12 and any(m > 1024 for m in seen), sorted(seen)
+
+
 def test_empty_and_tiny_paths(oracle):
     _one_shot(oracle, [[1, 2, 3], [], [3], [2, 3, 9, 2, 3]], None, 2, 4)
     _one_shot(oracle, [[4], [4, 4], [9]], [[0.5], [0.25, 1.0], [1.0]], 3, 3)
