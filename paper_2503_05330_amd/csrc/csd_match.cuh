@@ -860,12 +860,13 @@ __device__ __forceinline__ bool consume_variant_bucket(LDS& s, const Ctx& c, int
     rem = rem < L ? rem : L;
     n_hist = old_j - e;               // >= 1: continuation tokens that are already history
     n_hist = n_hist < rem ? n_hist : rem;
+    // the whole window with a few wide loads, whatever part of it is valid: what lies beyond
+    // n_hist is replaced below or never looked at (the arrays are padded for it)
 #pragma unroll
-    for (int d = 0; d < LCAP; ++d)
-      if (d < n_hist) {
-        wv[d] = hrow[d];
-        wp[d] = prow[d];
-      }
+    for (int d = 0; d < LCAP; ++d) {
+      wv[d] = hrow[d];
+      wp[d] = prow[d];
+    }
 #pragma unroll
     for (int a = 0; a <= K; ++a) tv[a] = (a <= c.q && a < e) ? tv[a] : 0;
   }
@@ -883,12 +884,20 @@ __device__ __forceinline__ bool consume_variant_bucket(LDS& s, const Ctx& c, int
   int32_t w = slot;                   // a match's window has the match's number
   if (slot >= 0 && w < win_cap) {
     int32_t* win = s.win + w * 2 * L;
+    if (L == LCAP) {                  // the whole window at once; entries beyond rem are never read
 #pragma unroll
-    for (int d = 0; d < LCAP; ++d)
-      if (d < rem) {
+      for (int d = 0; d < LCAP; ++d) {
         win[d] = wv[d];
-        win[L + d] = (int32_t)wp[d];
+        win[LCAP + d] = (int32_t)wp[d];
       }
+    } else {
+#pragma unroll
+      for (int d = 0; d < LCAP; ++d)
+        if (d < rem) {
+          win[d] = wv[d];
+          win[L + d] = (int32_t)wp[d];
+        }
+    }
   }
   return full;
 }
