@@ -97,7 +97,7 @@ class Replay:
         self.accs = mk((T, P, N), torch.int32)
         rows = P * N
         by_scan = matcher == "scan" or (matcher == "auto" and backoff) or (
-            max_edits > 0 and matcher == "auto" and not (self.k >= 4 and (rows > 128 or N * T >= 1 << 18)))
+            max_edits > 0 and matcher == "auto" and not (self.k >= 4 and (rows > 128 or N * T >= 1 << 14)))
         self.kernel = "step_scan_kernel" if by_scan else "step_wave_kernel"
         self.variant = (w.name + ("_one_edit" if max_edits else "") + ("" if pool == "dag" else "_" + pool)
                         + ("_self" if include_self else "") + ("_backoff" if backoff else ""))

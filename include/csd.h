@@ -135,7 +135,7 @@ typedef struct {
                              of its gram (the gram itself and the gram without one of its
                              tokens): CSD_MATCH_AUTO takes the index from max_query_len 4
                              on if there are more than 128 rows (problem, path) or a
-                             problem has 2^18 positions (n_paths * max_len) or more, else
+                             problem has 2^14 positions (n_paths * max_len) or more, else
                              the scan; CSD_MATCH_INDEX takes it from max_query_len 2 on
                              (1: CSD_ERR_UNIMPLEMENTED).                                 */
   int32_t pool_mode;      /* how the candidate pool is organised before the greedy

@@ -75,16 +75,17 @@ constexpr int64_t kSlicedScanRows = 128;
 // One-edit matching can go through the index when the query has at least two tokens (with
 // one token every position is within one edit: a scan's job).  The index files positions
 // under grams of max_query_len - 1 tokens then; for three-token queries those are pairs,
-// the chains of frequent pairs get long, and the scan is the faster matcher; with few rows and
-// short histories the sliced scan beats the index for longer queries too (measured with one
-// edit and four-token queries: 32 x 2048 positions per problem 20.7 us by scan, 29.5 through
-// the index; 64 x 4096 positions 52.3 against 43.1: the scan's cost grows with the positions,
-// the index's with the matches).  CSD_MATCH_AUTO therefore takes the index from four query
-// tokens on when there are too many rows to slice the scan or a problem has 2^18 positions
-// or more.
+// the chains of frequent pairs get long, and the scan is the faster matcher.  With four-token
+// queries the index is the faster one except for small problems (measured with one edit, us
+// per step at full history, scan / index: 8 x 1024 positions per problem 12.0 / 11.5,
+// 16 x 1024 14.2 / 12.6, 32 x 2048 21.6 / 19.4, 64 x 2048 35.3 / 29.4, 64 x 4096 52.9 / 24.5;
+// only 32 x 4096, few long paths, went to the scan, 26.1 / 27.2): the scan's cost grows with
+// the positions, the index's with the matches.  CSD_MATCH_AUTO therefore takes the index from
+// four query tokens on when there are too many rows to slice the scan or a problem has 2^14
+// positions or more.
 // With query back-off a query without matches is searched again in shorter forms, which the
 // index (grams of max_query_len tokens only) cannot serve: CSD_MATCH_AUTO takes the scan then.
-constexpr int64_t kIndexedFuzzyPositions = 1 << 18;
+constexpr int64_t kIndexedFuzzyPositions = 1 << 14;
 int matcher_of(const csd_config* c) { return c->flags & 3; }
 bool uses_index(const csd_config* c) {
   if (matcher_of(c) == CSD_MATCH_SCAN) return false;

@@ -821,16 +821,24 @@ __device__ __forceinline__ bool variant_counts(const Ctx& c, const int32_t (&G)[
 // position counts once, whichever variants led to it (my_u: the variant whose
 // chain this bucket belongs to).  Returns whether the group's bucket was full
 // (its chain goes on).
+// Which lanes of a batch hold a posting (word 0 of a bucket is its fill count, held by the
+// first lane of each group of 16; -1 everywhere for an idle group), and is the group's bucket
+// full (its chain goes on)?
+__device__ __forceinline__ bool bucket_has_posting(int32_t word, int lane, bool& full) {
+  const int sub = lane & 15;          // word of the bucket this lane reads
+  const int32_t count = __shfl(word, lane & ~15);
+  full = count >= kBucketSlots;
+  return sub >= 1 && word >= 0 && (sub - 1) < (full ? kBucketSlots : count);
+}
+
+// The postings of a batch, one per lane (`cand`: this lane has one; `my_u`: the query variant
+// whose chain it was found in).
 template <int LCAP, int K, class LDS>
-__device__ __forceinline__ bool consume_variant_bucket(LDS& s, const Ctx& c, int32_t L,
-                                                       int32_t win_cap, int32_t& n_match,
-                                                       int32_t my_u, int32_t word) {
+__device__ __forceinline__ void consume_variant_postings(LDS& s, const Ctx& c, int32_t L,
+                                                         int32_t win_cap, int32_t& n_match,
+                                                         int32_t my_u, int32_t word, bool cand) {
   const int lane = c.tid;
   const Paths& y = c.y;
-  const int sub = lane & 15;          // word of the bucket this lane reads
-  int32_t count = __shfl(word, lane & ~15);
-  bool full = count >= kBucketSlots;
-  bool cand = sub >= 1 && word >= 0 && (sub - 1) < (full ? kBucketSlots : count);
   const int32_t filed_as = word >> kVariantShift;       // variant of its gram the posting stands for
   const int32_t pos = word & ((1 << kVariantShift) - 1);
   int32_t j = y.pos_path(pos), e = y.pos_index(pos), old_j = 0, new_j = 0;
@@ -899,52 +907,113 @@ __device__ __forceinline__ bool consume_variant_bucket(LDS& s, const Ctx& c, int
         }
     }
   }
+}
+
+// One batch by position: this lane's word of its group's bucket.  Returns whether the
+// group's bucket was full.
+template <int LCAP, int K, class LDS>
+__device__ __forceinline__ bool consume_variant_bucket(LDS& s, const Ctx& c, int32_t L,
+                                                       int32_t win_cap, int32_t& n_match,
+                                                       int32_t my_u, int32_t word) {
+  bool full;
+  const bool cand = bucket_has_posting(word, c.tid, full);
+  consume_variant_postings<LCAP, K>(s, c, L, win_cap, n_match, my_u, word, cand);
   return full;
 }
 
-// Eq. 4 (one edit) through the index.  Bucket 0 of the chains of four of the
-// query's variants is read at a time, one variant per group of 16 lanes; a
-// chain that goes on is then walked by the whole wave, four buckets per batch
-// with the next batch in flight (reading past the end of a chain is harmless:
-// buckets behind the first one that is not full are empty).  `word` is the
-// lane's word of bucket 0 of its group's first variant, already requested.
+// Eq. 4 (one edit) through the index.  Bucket 0 of the chains of the query's variants is
+// read in batches of four, one variant per group of 16 lanes; a chain that goes on is then
+// walked by the whole wave, four buckets per batch with the next batch in flight (reading
+// past the end of a chain is harmless: buckets behind the first one that is not full are
+// empty).  `word` / `word_beyond`: the lane's word of bucket 0 of its group's variant in the
+// first batch (variants 0 .. 3) / the second (4 .. 7), both already requested.
 template <int LCAP, int K, class LDS>
 __device__ __forceinline__ void lookup_variants_with_windows(LDS& s, const Ctx& c, int32_t L,
                                                              int32_t win_cap, int32_t& n_match,
-                                                             int32_t word) {
+                                                             int32_t word, int32_t word_beyond) {
   const int lane = c.tid;
   int32_t* tbl = const_cast<int32_t*>(c.gram);
   const int sub = lane & 15;
   const int grp = lane >> 4;
   const uint32_t n_buckets = c.bucket_mask + 1;
-  for (int32_t pass = 0; pass * 4 <= c.q; ++pass) {
-    const int32_t u = pass * 4 + grp;
-    const bool active = u <= c.q && variant_is_new(c.Q, u);
-    consume_here(word);
-    if (!active) word = -1;           // idle groups see an empty bucket
-    // the next four variants' buckets travel while these are looked through
-    const int32_t u_next = u + 4 <= c.q ? u + 4 : 0;
-    const int32_t word_next = gram_bucket(tbl, variant_hash(c.Q, c.q, u_next), 0u, c.bucket_mask)[sub];
-    bool full = consume_variant_bucket<LCAP, K>(s, c, L, win_cap, n_match, u, word);
-    const u64 goes_on = wave_ballot(active && full && sub == 0);       // bit 16 g: group g's chain
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      if ((goes_on >> (16 * g) & 1ull) == 0) continue;              // uniform over the wave
-      const GramHash gh = variant_hash(c.Q, c.q, pass * 4 + g);     // the same in every lane
-      uint32_t r0 = 1;
-      int32_t tail = gram_bucket(tbl, gh, r0 + grp < n_buckets ? r0 + grp : 0u, c.bucket_mask)[sub];
-      for (; r0 < n_buckets; r0 += 4) {
-        consume_here(tail);
-        if (r0 + grp >= n_buckets) tail = -1;
-        uint32_t rn = r0 + 4 + grp;                                 // next batch: in flight meanwhile
-        int32_t next_tail = gram_bucket(tbl, gh, rn < n_buckets ? rn : 0u, c.bucket_mask)[sub];
-        bool tail_full = consume_variant_bucket<LCAP, K>(s, c, L, win_cap, n_match,
-                                                         pass * 4 + g, tail);
-        if (wave_ballot(!tail_full) != 0) break;                       // the chain ends in this batch
-        tail = next_tail;
-      }
+  // variants 0 .. 3 and 4 .. 7: both batches of first buckets were requested together.  Buckets
+  // are a third full on average, so the postings of the second batch nearly always find a
+  // lane of their own among those that hold none of the first, and both are looked through at
+  // once (through a small LDS array: the x-th posting of the second batch goes to the x-th
+  // such lane).  Queries of 8 tokens have a ninth variant: a batch of its own.
+  const int32_t u_a = grp, u_b = 4 + grp, u_c = 8 + grp;
+  const bool active_a = u_a <= c.q && variant_is_new(c.Q, u_a);
+  const bool active_b = u_b <= c.q && variant_is_new(c.Q, u_b);
+  const bool active_c = K >= 8 && u_c <= c.q && variant_is_new(c.Q, 8);
+  consume_here(word);
+  consume_here(word_beyond);
+  if (!active_a) word = -1;           // idle groups see an empty bucket
+  if (!active_b) word_beyond = -1;
+  int32_t word_ninth = -1;
+  if (K >= 8 && c.q >= 8)             // (travels while the others are looked through)
+    word_ninth = gram_bucket(tbl, variant_hash(c.Q, c.q, 8), 0u, c.bucket_mask)[sub];
+  bool full_a, full_b, full_c = false;
+  const bool has_a = bucket_has_posting(word, lane, full_a);
+  const bool has_b = bucket_has_posting(word_beyond, lane, full_b);
+  const u64 mask_a = wave_ballot(has_a), mask_b = wave_ballot(has_b);
+  const u64 below = (1ull << lane) - 1ull;
+  const bool together = mask_b != 0 && __popcll(mask_b) <= kWave - __popcll(mask_a);   // uniform over the wave
+  int32_t posting = word, my_u = u_a;
+  bool cand = has_a;
+  if (together) {
+    int32_t* moved = reinterpret_cast<int32_t*>(s.link);              // (the links are not in use yet)
+    static_assert(sizeof(s.link) >= 2 * kWave * sizeof(int32_t), "room for a batch of postings");
+    if (has_b) {
+      const int x = (int)__popcll(mask_b & below);
+      moved[2 * x] = word_beyond;
+      moved[2 * x + 1] = u_b;
     }
-    word = word_next;
+    lds_barrier<kWave>();
+    const int x = (int)__popcll(~mask_a & below);                     // this lane's number among the free ones
+    const bool takes = !has_a && x < (int)__popcll(mask_b);
+    posting = takes ? moved[2 * x] : word;
+    my_u = takes ? moved[2 * x + 1] : u_a;
+    cand = has_a || takes;
+  }
+  // the batches of first buckets: both at once, or one after the other; then the ninth variant's
+#pragma unroll 1
+  for (int batch = 0; batch < 3; ++batch) {
+    if (batch == 1) {
+      if (together || mask_b == 0) continue;             // uniform over the wave
+      posting = word_beyond;
+      my_u = u_b;
+      cand = has_b;
+    } else if (batch == 2) {
+      if (!(K >= 8 && c.q >= 8)) break;
+      consume_here(word_ninth);
+      if (!active_c) word_ninth = -1;
+      posting = word_ninth;
+      my_u = u_c;
+      cand = bucket_has_posting(word_ninth, lane, full_c);
+    }
+    consume_variant_postings<LCAP, K>(s, c, L, win_cap, n_match, my_u, posting, cand);
+  }
+  // a chain that goes on beyond its first bucket: walked by the whole wave, four buckets per
+  // batch with the next batch in flight
+  const u64 on_a = wave_ballot(active_a && full_a && sub == 0);       // bit 16 g: group g's chain
+  const u64 on_b = wave_ballot(active_b && full_b && sub == 0);
+  const u64 on_c = wave_ballot(active_c && full_c && sub == 0);
+#pragma unroll 1
+  for (int chain = 0; chain < 12; ++chain) {
+    const u64 goes_on = chain < 4 ? on_a : chain < 8 ? on_b : on_c;
+    if ((goes_on >> (16 * (chain & 3)) & 1ull) == 0) continue;        // uniform over the wave
+    const GramHash gh = variant_hash(c.Q, c.q, chain);                // the same in every lane
+    uint32_t r0 = 1;
+    int32_t tail = gram_bucket(tbl, gh, r0 + grp < n_buckets ? r0 + grp : 0u, c.bucket_mask)[sub];
+    for (; r0 < n_buckets; r0 += 4) {
+      consume_here(tail);
+      if (r0 + grp >= n_buckets) tail = -1;
+      uint32_t rn = r0 + 4 + grp;                                     // next batch: in flight meanwhile
+      int32_t next_tail = gram_bucket(tbl, gh, rn < n_buckets ? rn : 0u, c.bucket_mask)[sub];
+      bool tail_full = consume_variant_bucket<LCAP, K>(s, c, L, win_cap, n_match, chain, tail);
+      if (wave_ballot(!tail_full) != 0) break;                         // the chain ends in this batch
+      tail = next_tail;
+    }
   }
 }
 
@@ -1014,9 +1083,12 @@ __device__ __forceinline__ int32_t wave_front_end_fuzzy(LDS& s, Ctx& c, const In
   // ---- round trip 2 is requested: fill counts for the insert, bucket 0 of the first 4 variants
   ticket_used = APPENDS && cnt_i == 1;
   if (ticket_used) ticket = variants_begin(gram, c.bucket_mask, ix.kmax, me.tail, old_i, lane);
-  int32_t word = -1;
-  if (use_index)
+  int32_t word = -1, word_beyond = -1;
+  if (use_index) {
     word = gram_bucket(gram, variant_hash(c.Q, c.q, lane >> 4), 0u, c.bucket_mask)[lane & 15];
+    const int32_t u_b = 4 + (lane >> 4);                // variants 4 .. 7 (queries of 4 tokens and more)
+    word_beyond = gram_bucket(gram, variant_hash(c.Q, c.q, u_b <= c.q ? u_b : 0), 0u, c.bucket_mask)[lane & 15];
+  }
   // ---- while it travels: own append, lengths into LDS, matches that need no index
   if (APPENDS && y.n == 1) append_own_single(ix, y, row, c.i, me, st_i, sp_i, lane);
   int32_t n_match = 0;
@@ -1053,7 +1125,7 @@ __device__ __forceinline__ int32_t wave_front_end_fuzzy(LDS& s, Ctx& c, const In
   wi.n_fresh = n_match;
   wi.win_cap = use_index ? LDS::kWin / (2 * L) : 0;
   if (use_index) {
-    lookup_variants_with_windows<LCAP, K>(s, c, L, wi.win_cap, n_match, word);
+    lookup_variants_with_windows<LCAP, K>(s, c, L, wi.win_cap, n_match, word, word_beyond);
   } else if (c.q > 0) {
     WaveListSink<LDS> sink{&s, &n_match, lane};
     match_plain<true>(s, c, sink);                      // covers old and new positions alike

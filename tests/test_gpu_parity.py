@@ -614,12 +614,13 @@ def _fuzzy_sampled(oracle, w, steps, variants, dump=None):
 def test_fuzzy_full_size_c3_c4_c5(oracle):
     """One-edit matching (Eq. 4, the tolerance of the paper's experiments) at the full size of
     C3 and C5 and on 8 problems of C4: sampled steps up to the full history, under the matcher
-    CSD_MATCH_AUTO picks (the sliced scan: at most 128 rows) and through the variant index."""
+    CSD_MATCH_AUTO picks (the variant index for C3 and C5, the sliced scan for C4's three-token
+    queries) and under the other one (C3: the sliced scan; C4: the index)."""
     AUTO = binding.MATCH_AUTO
     w = synth.WORKLOADS["C3"]
     T = w.max_len
     _fuzzy_sampled(oracle, w, list(range(0, 6)) + list(range(127, T, 128)) + [T - 2, T - 1],
-                   ((AUTO, "replay"), (INDEX, "replay")), dump=(700, range(0, w.n_paths, 5)))
+                   ((AUTO, "replay"), (SCAN, "replay")), dump=(700, range(0, w.n_paths, 5)))
     w = synth.WORKLOADS["C5"]
     T = w.max_len
     _fuzzy_sampled(oracle, w, list(range(0, 6)) + list(range(511, T, 512)) + [T - 2, T - 1],
