@@ -615,7 +615,7 @@ def test_fuzzy_full_size_c3_c4_c5(oracle):
     """One-edit matching (Eq. 4, the tolerance of the paper's experiments) at the full size of
     C3 and C5 and on 8 problems of C4: sampled steps up to the full history, under the matcher
     CSD_MATCH_AUTO picks (the variant index for C3 and C5, the sliced scan for C4's three-token
-    queries) and under the other one (C3: the sliced scan; C4: the index)."""
+    queries) and under the other one (C3, C5: the sliced scan; C4: the index)."""
     AUTO = binding.MATCH_AUTO
     w = synth.WORKLOADS["C3"]
     T = w.max_len
@@ -624,7 +624,7 @@ def test_fuzzy_full_size_c3_c4_c5(oracle):
     w = synth.WORKLOADS["C5"]
     T = w.max_len
     _fuzzy_sampled(oracle, w, list(range(0, 6)) + list(range(511, T, 512)) + [T - 2, T - 1],
-                   ((AUTO, "replay"), (INDEX, "replay")), dump=(1500, range(0, w.n_paths, 9)))
+                   ((AUTO, "replay"), (SCAN, "replay")), dump=(1500, range(0, w.n_paths, 9)))
     w = synth.scaled(synth.WORKLOADS["C4"], n_problems=8)
     T = w.max_len
     _fuzzy_sampled(oracle, w, list(range(0, 5)) + list(range(127, T, 128)) + [T - 1],
