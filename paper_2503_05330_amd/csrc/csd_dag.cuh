@@ -648,9 +648,26 @@ __device__ __forceinline__ bool walk_tab_fits(int32_t M, int32_t L, int32_t voca
   return score_mode == 0 && M <= BLOCK && M * L <= kTabInstances && vocab <= (1 << kTabTokenBits);
 }
 
+// Empties walk_tab's key set and zeroes its cells and the layers' maxima, all kTabSlots of
+// them, with threads `first` .. BLOCK - 1 (the scan kernel has this done by the waves that
+// idle while one of them hands the row's matches over; the first BLOCK entries of the match
+// list are not touched).
+template <int BLOCK, class LDS>
+__device__ __forceinline__ void walk_tab_clear(LDS& s, int tid, int first) {
+  uint2* cells2 = reinterpret_cast<uint2*>(s.table);
+  uint2* keys2 = reinterpret_cast<uint2*>(&s.match[BLOCK]);
+  u64* best = reinterpret_cast<u64*>(s.link);
+  if (tid < first) return;
+  for (uint32_t x = tid - first; x < kTabSlots; x += BLOCK - first) cells2[x] = uint2{0u, 0u};
+  for (uint32_t x = tid - first; x < kTabSlots / 2; x += BLOCK - first) keys2[x] = uint2{~0u, ~0u};
+  if (tid - first < CSD_MAX_DRAFT_LEN) best[tid - first] = 0ull;
+  if (tid == first) s.overflow = 0;
+}
+
+// cleared: walk_tab_clear has been called (and a barrier passed) since the table was last used.
 template <int BLOCK, class LDS>
 __device__ __forceinline__ bool walk_tab(LDS& s, const Ctx& c, int32_t M, int32_t L, uint32_t alpha_q,
-                                         DraftOut& o) {
+                                         DraftOut& o, bool cleared = false) {
   static_assert(LDS::kMatch >= BLOCK && sizeof(s.table) >= kTabSlots * sizeof(u64) &&
                 sizeof(s.link) >= CSD_MAX_DRAFT_LEN * sizeof(u64),
                 "cells over the table, the layers' maxima over the links");
@@ -668,8 +685,9 @@ __device__ __forceinline__ bool walk_tab(LDS& s, const Ctx& c, int32_t M, int32_
   // not used is not cleared
   int slot_bits = 32 - __clz(4 * M * L - 1);
   slot_bits = slot_bits < 10 ? 10 : (slot_bits > 13 ? 13 : slot_bits);
+  if (cleared) slot_bits = 13;                         // (uniform) all of them are empty: use them
   const uint32_t n_slots = 1u << slot_bits;
-  {                                                    // empty set, zero cells
+  if (!cleared) {                                      // empty set, zero cells
     uint2* cells2 = reinterpret_cast<uint2*>(cell);
     uint2* keys2 = reinterpret_cast<uint2*>(keys);
     for (uint32_t x = c.tid; x < n_slots; x += BLOCK) cells2[x] = uint2{0u, 0u};

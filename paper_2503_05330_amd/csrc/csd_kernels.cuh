@@ -182,6 +182,9 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
       for (int32_t m = c.tid; m < M && m < LdsScan::kMatch; m += BLOCK)
         if (sh_base + m < LdsScan::kMatch) listed[sh_base + m] = s.match[m];
       block_sync<BLOCK>();              // every wave's stores have left the CU
+      // (while wave 0 signs off, the others prepare the tables of the walk that rows of
+      // 65 .. 1024 matches take: wasted on all slices but the last, which would wait here anyway)
+      if (!POOLS || a.pool_mode == CSD_POOL_DAG) walk_tab_clear<BLOCK>(s, c.tid, kWave);
       if (c.tid == 0) {
         // one wave fences for the workgroup (a device-scope fence writes the L2 back: sixteen
         // of them in a row cost more than the scan): list entries before the sign-off, the
@@ -240,7 +243,8 @@ __global__ __launch_bounds__(kScanBlock) void step_scan_kernel(IndexView ix, Ste
       } else if (M <= BLOCK) {
         // one thread per match: node weights tabulated first, or layer by layer
         // (the second where the first does not apply or finds too many distinct continuations)
-        if (!walk_tab_fits<BLOCK>(M, L, ix.vocab, a.score_mode) || !walk_tab<BLOCK>(s, c, M, L, a.alpha_q, o))
+        if (!walk_tab_fits<BLOCK>(M, L, ix.vocab, a.score_mode) ||
+            !walk_tab<BLOCK>(s, c, M, L, a.alpha_q, o, sl.n > 1))
           walk_wide<BLOCK>(s, c, M, L, a.alpha_q, a.score_mode, o);
         done = true;
       }
